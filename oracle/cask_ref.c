@@ -1,0 +1,521 @@
+/*
+ * CASK compression-event ORACLE (test infrastructure; see cask_ref.h).
+ *
+ * Plain C, double precision, one loop nest per definition.  OpenMP is used only
+ * across independent (sequence, layer, KV head) units.
+ */
+#define _GNU_SOURCE
+#include "cask_ref.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------ element access */
+
+double cask_ref_bf16_to_double(uint16_t h) {
+  uint32_t bits = ((uint32_t)h) << 16;
+  float f;
+  memcpy(&f, &bits, 4);
+  return (double)f;
+}
+
+/* Nearest bf16 (8 significant bits, exponent range of float), ties to even.  The value
+ * is rounded directly from double on the bf16 grid, so there is no double rounding. */
+uint16_t cask_ref_bf16_from_double(double x) {
+  if (isnan(x)) return 0x7FC0;
+  if (isinf(x)) return x > 0 ? 0x7F80 : 0xFF80;
+  if (x == 0.0) return signbit(x) ? 0x8000 : 0x0000;
+  int e;
+  (void)frexp(x, &e);             /* |x| = m * 2^e, m in [0.5, 1) */
+  int q = e - 8;                  /* spacing of bf16 numbers near x is 2^(e-8) */
+  if (q < -133) q = -133;         /* subnormal spacing */
+  double r = ldexp(nearbyint(ldexp(x, -q)), q); /* nearbyint: round-half-even (default mode) */
+  if (fabs(r) >= ldexp(1.0, 128)) return r > 0 ? 0x7F80 : 0xFF80;
+  float f = (float)r;             /* exact: r is on the bf16 grid */
+  uint32_t bits;
+  memcpy(&bits, &f, 4);
+  return (uint16_t)(bits >> 16);
+}
+
+static size_t elem_size(int dtype) { return dtype == CASK_REF_BF16 ? 2 : 4; }
+
+static double load_elem(const void* base, int dtype, int64_t idx) {
+  if (dtype == CASK_REF_BF16) return cask_ref_bf16_to_double(((const uint16_t*)base)[idx]);
+  return (double)((const float*)base)[idx];
+}
+
+static void store_elem(void* base, int dtype, int64_t idx, double x) {
+  if (dtype == CASK_REF_BF16)
+    ((uint16_t*)base)[idx] = cask_ref_bf16_from_double(x);
+  else
+    ((float*)base)[idx] = (float)x;
+}
+
+/* ------------------------------------------------------------------ parameter checks */
+
+static int resolved_recent(const cask_ref_params* p) { return p->recent < 0 ? p->window : p->recent; }
+
+static int check_shape(const cask_ref_params* p) {
+  if (!p) return -1;
+  if (p->dtype != CASK_REF_F32 && p->dtype != CASK_REF_BF16) return -1;
+  if (p->head_dim < 1 || p->q_per_kv < 1 || p->window < 1) return -1;
+  return 0;
+}
+
+static int check_params(const cask_ref_params* p) {
+  if (check_shape(p)) return -1;
+  if (p->budget < resolved_recent(p) + 1) return -1;
+  return 0;
+}
+
+static int check_unit(const cask_ref_params* p, int64_t N, int64_t P) {
+  if (N < p->window || P < 0 || P > N || N > 0x7fffffff) return -1;
+  return 0;
+}
+
+/* ------------------------------------------------------------------ budget split
+ *
+ * Two-stage compression (Section 2.2): stage 1 evicts in the prefix only to leave room for
+ * the decode stage; stage 2 keeps a protected core and consolidates scratch into the slots
+ * that remain (Section 2.3: scratch is consolidated only within the remaining budget).  The
+ * paper gives no split rule; the reading taken here:
+ *   - the last R_eff = min(R, D) decode tokens ("recent reasoning pivots", Section 2.1) are
+ *     always kept and are counted outside the core;
+ *   - N <= B: nothing to do (identity);
+ *   - the prefix keeps B_p tokens (default max(B/4, ceil(P/64))), more if the decode trace
+ *     cannot use the space, never more than B - R_eff;
+ *   - the decode trace outside the recent tail gets slots = B - R_eff - P_keep;
+ *     slots = 0 with decode tokens waiting is the prefix_budget_exhausted regime (Section 5.2);
+ *   - of the slots, C (default 4/5) go to the protected core and M = slots - C to
+ *     representatives.
+ */
+void cask_ref_plan(const cask_ref_params* p, int32_t P, int32_t N, cask_ref_plan_t* out) {
+  int32_t R = resolved_recent(p);
+  int32_t B = p->budget;
+  int32_t D = N - P;
+  int32_t r_eff = R < D ? R : D;
+  int32_t dnr = D - r_eff;
+  memset(out, 0, sizeof(*out));
+  out->r_eff = r_eff;
+  if (N <= B) {
+    out->p_keep = P;
+    out->slots = dnr;
+    out->core = dnr;
+    out->seeds = 0;
+    out->status = CASK_REF_ST_IDENTITY;
+    return;
+  }
+  int32_t bp;
+  if (p->prefix_budget >= 0) {
+    bp = p->prefix_budget;
+  } else {
+    int32_t quarter = B / 4;
+    int32_t floor64 = (P + 63) / 64;
+    bp = quarter > floor64 ? quarter : floor64;
+  }
+  int32_t room = B - r_eff;          /* what prefix and non-recent decode share */
+  int32_t unused = room - dnr;       /* space the decode trace cannot fill */
+  int32_t want = bp > unused ? bp : unused;
+  int32_t p_keep = P;
+  if (room < p_keep) p_keep = room;
+  if (want < p_keep) p_keep = want;
+  out->p_keep = p_keep;
+  out->slots = room - p_keep;
+  if (dnr <= out->slots) {
+    out->core = dnr;
+    out->seeds = 0;
+    out->status = CASK_REF_ST_MERGE_INACTIVE;
+  } else if (out->slots == 0) {
+    out->core = 0;
+    out->seeds = 0;
+    out->status = CASK_REF_ST_PREFIX_BUDGET_EXHAUSTED;
+  } else {
+    int32_t c;
+    if (p->core >= 0)
+      c = p->core < out->slots ? p->core : out->slots;
+    else
+      c = (int32_t)((4LL * out->slots) / 5);
+    out->core = c;
+    out->seeds = out->slots - c;
+    out->status = out->seeds == 0 ? CASK_REF_ST_MERGE_INACTIVE : CASK_REF_ST_ACTIVE;
+  }
+}
+
+/* ------------------------------------------------------------------ scoring
+ *
+ * The paper inherits an eviction-style scalar importance (Section 1) and leaves the deployed
+ * form open; a_i is "local score mass" (Section 2.4).  Reading taken: window row (w, g) sits
+ * at cache slot t_w = N - W + w; its attention over the keys it can see is
+ * softmax_j(scale * <q_{w,g}, k_j>), j <= t_w (all j when causal = 0); the score of key j is
+ * the mean of that probability over all W*G rows.  Rounded once to float.
+ */
+static void score_unit(const cask_ref_params* p, int64_t N, const void* K, int64_t k_row0,
+                       const void* Q, int64_t q_row0, float* s_out) {
+  const int d = p->head_dim, W = p->window, G = p->q_per_kv;
+  const double scale = p->softmax_scale > 0.0f ? (double)p->softmax_scale : 1.0 / sqrt((double)d);
+  double* kd = (double*)malloc(sizeof(double) * (size_t)N * d);
+  double* logit = (double*)malloc(sizeof(double) * (size_t)N);
+  double* acc = (double*)calloc((size_t)N, sizeof(double));
+  double* q = (double*)malloc(sizeof(double) * d);
+  for (int64_t j = 0; j < N; ++j)
+    for (int c = 0; c < d; ++c) kd[j * d + c] = load_elem(K, p->dtype, (k_row0 + j) * d + c);
+  for (int w = 0; w < W; ++w) {
+    int64_t t = N - W + w;
+    int64_t last = p->causal ? t : N - 1;
+    for (int g = 0; g < G; ++g) {
+      int64_t qrow = q_row0 + (int64_t)w * G + g;
+      for (int c = 0; c < d; ++c) q[c] = load_elem(Q, p->dtype, qrow * d + c);
+      double mx = -INFINITY;
+      for (int64_t j = 0; j <= last; ++j) {
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c) dot += q[c] * kd[j * d + c];
+        logit[j] = scale * dot;
+        if (logit[j] > mx) mx = logit[j];
+      }
+      double z = 0.0;
+      for (int64_t j = 0; j <= last; ++j) z += exp(logit[j] - mx);
+      for (int64_t j = 0; j <= last; ++j) acc[j] += exp(logit[j] - mx) / z;
+    }
+  }
+  for (int64_t j = 0; j < N; ++j) s_out[j] = (float)(acc[j] / ((double)W * (double)G));
+  free(kd);
+  free(logit);
+  free(acc);
+  free(q);
+}
+
+int cask_ref_score(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                   const void* K, const void* Q, float* scores, int n_threads) {
+  if (check_shape(p) || n_units < 0) return -1;
+  for (int32_t u = 0; u < n_units; ++u)
+    if (check_unit(p, row_off[u + 1] - row_off[u], 0)) return -1;
+#ifdef _OPENMP
+  if (n_threads > 0) omp_set_num_threads(n_threads);
+#endif
+  (void)n_threads;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t u = 0; u < n_units; ++u) {
+    int64_t N = row_off[u + 1] - row_off[u];
+    score_unit(p, N, K, row_off[u], Q, (int64_t)u * p->window * p->q_per_kv, scores + row_off[u]);
+  }
+  return 0;
+}
+
+/* ------------------------------------------------------------------ ordering
+ *
+ * "Retain the top tokens" (Section 1).  Total order: higher float score first, equal scores
+ * in ascending cache index.  top-k = the first k of the range under this order.
+ */
+typedef struct {
+  float s;
+  int32_t i;
+} ranked_t;
+
+static int ranked_cmp(const void* a, const void* b) {
+  const ranked_t* x = (const ranked_t*)a;
+  const ranked_t* y = (const ranked_t*)b;
+  if (x->s > y->s) return -1;
+  if (x->s < y->s) return 1;
+  if (x->i < y->i) return -1;
+  if (x->i > y->i) return 1;
+  return 0;
+}
+
+/* order[0..n) := unit-local rows lo..hi-1 sorted by the total order */
+static ranked_t* rank_range(const float* s, int32_t lo, int32_t hi) {
+  int32_t n = hi - lo;
+  ranked_t* r = (ranked_t*)malloc(sizeof(ranked_t) * (size_t)(n > 0 ? n : 1));
+  for (int32_t t = 0; t < n; ++t) {
+    r[t].s = s[lo + t];
+    r[t].i = lo + t;
+  }
+  qsort(r, (size_t)n, sizeof(ranked_t), ranked_cmp);
+  return r;
+}
+
+/* Stage 1 (Section 2.2): eviction in the prefix; survivors are the top P_keep. */
+static void prefix_evict_unit(const cask_ref_plan_t* pl, int32_t P, const float* s, uint8_t* role) {
+  ranked_t* r = rank_range(s, 0, P);
+  for (int32_t t = 0; t < P; ++t)
+    role[r[t].i] = t < pl->p_keep ? CASK_REF_PREFIX_KEEP : CASK_REF_PREFIX_DROP;
+  free(r);
+}
+
+/* Stage 2 decomposition (Section 2.1): the protected core is decided first (top C of the
+ * decode trace outside the recent tail), then the next M become the seeds of the
+ * representatives, and the rest is mergeable scratch offered to them (donors). */
+static void partition_unit(const cask_ref_plan_t* pl, int32_t P, int32_t N, const float* s,
+                           uint8_t* role) {
+  int32_t hi = N - pl->r_eff;
+  for (int32_t j = hi; j < N; ++j) role[j] = CASK_REF_RECENT;
+  if (pl->status & CASK_REF_ST_PREFIX_BUDGET_EXHAUSTED) {
+    for (int32_t j = P; j < hi; ++j) role[j] = CASK_REF_DECODE_EVICT;
+    return;
+  }
+  ranked_t* r = rank_range(s, P, hi);
+  for (int32_t t = 0; t < hi - P; ++t) {
+    uint8_t x;
+    if (t < pl->core)
+      x = CASK_REF_CORE;
+    else if (t < pl->core + pl->seeds)
+      x = CASK_REF_SEED;
+    else
+      x = CASK_REF_DONOR;
+    role[r[t].i] = x;
+  }
+  free(r);
+}
+
+int cask_ref_prefix_evict(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                          const int32_t* prefix_len, const float* scores, uint8_t* role,
+                          int32_t* status) {
+  if (check_params(p) || n_units < 0) return -1;
+  for (int32_t u = 0; u < n_units; ++u)
+    if (check_unit(p, row_off[u + 1] - row_off[u], prefix_len[u])) return -1;
+  for (int32_t u = 0; u < n_units; ++u) {
+    int32_t N = (int32_t)(row_off[u + 1] - row_off[u]);
+    cask_ref_plan_t pl;
+    cask_ref_plan(p, prefix_len[u], N, &pl);
+    prefix_evict_unit(&pl, prefix_len[u], scores + row_off[u], role + row_off[u]);
+    if (status) status[u] = pl.status;
+  }
+  return 0;
+}
+
+int cask_ref_partition(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                       const int32_t* prefix_len, const float* scores, uint8_t* role,
+                       int32_t* status) {
+  if (check_params(p) || n_units < 0) return -1;
+  for (int32_t u = 0; u < n_units; ++u)
+    if (check_unit(p, row_off[u + 1] - row_off[u], prefix_len[u])) return -1;
+  for (int32_t u = 0; u < n_units; ++u) {
+    int32_t N = (int32_t)(row_off[u + 1] - row_off[u]);
+    cask_ref_plan_t pl;
+    cask_ref_plan(p, prefix_len[u], N, &pl);
+    partition_unit(&pl, prefix_len[u], N, scores + row_off[u], role + row_off[u]);
+    if (status) status[u] = pl.status;
+  }
+  return 0;
+}
+
+/* ------------------------------------------------------------------ consolidation
+ *
+ * A scratch token need not be kept "as long as a sufficiently similar representative
+ * remains" (Section 1); similarity is raw cosine between cached keys (Section 2.5 names raw
+ * cosine as the plain geometry).  Reading taken: each donor looks at every seed, picks the
+ * seed of largest cosine (ties: lowest cache index), and folds into it when that cosine is
+ * >= tau; otherwise it is evicted.  Core tokens neither give nor receive merges (Section 2.1).
+ */
+static void consolidate_unit(const cask_ref_params* p, int32_t N, const void* K, int64_t row0,
+                             const uint8_t* role, int32_t* assign, double* best_sim,
+                             double* second_sim) {
+  const int d = p->head_dim;
+  const double tau = (double)p->sim_threshold;
+  int32_t n_seed = 0;
+  for (int32_t j = 0; j < N; ++j) n_seed += role[j] == CASK_REF_SEED;
+  int32_t* seed_row = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_seed > 0 ? n_seed : 1));
+  double* seed_k = (double*)malloc(sizeof(double) * (size_t)(n_seed > 0 ? n_seed : 1) * d);
+  double* seed_norm = (double*)malloc(sizeof(double) * (size_t)(n_seed > 0 ? n_seed : 1));
+  double* ki = (double*)malloc(sizeof(double) * d);
+  int32_t t = 0;
+  for (int32_t j = 0; j < N; ++j) {
+    if (role[j] != CASK_REF_SEED) continue;
+    double nn = 0.0;
+    for (int c = 0; c < d; ++c) {
+      double x = load_elem(K, p->dtype, (row0 + j) * d + c);
+      seed_k[(size_t)t * d + c] = x;
+      nn += x * x;
+    }
+    seed_norm[t] = sqrt(nn);
+    seed_row[t] = j;
+    ++t;
+  }
+  for (int32_t i = 0; i < N; ++i) {
+    if (best_sim) best_sim[i] = NAN;
+    if (second_sim) second_sim[i] = NAN;
+    switch (role[i]) {
+      case CASK_REF_PREFIX_KEEP:
+      case CASK_REF_CORE:
+      case CASK_REF_SEED:
+      case CASK_REF_RECENT:
+        assign[i] = i;
+        continue;
+      case CASK_REF_DONOR:
+        break;
+      default:
+        assign[i] = -1;
+        continue;
+    }
+    double nn = 0.0;
+    for (int c = 0; c < d; ++c) {
+      ki[c] = load_elem(K, p->dtype, (row0 + i) * d + c);
+      nn += ki[c] * ki[c];
+    }
+    double ni = sqrt(nn);
+    double best = -INFINITY, second = -INFINITY;
+    int32_t best_r = -1;
+    for (int32_t r = 0; r < n_seed; ++r) { /* ascending cache index */
+      double dot = 0.0;
+      for (int c = 0; c < d; ++c) dot += ki[c] * seed_k[(size_t)r * d + c];
+      double sim = (ni == 0.0 || seed_norm[r] == 0.0) ? 0.0 : dot / (ni * seed_norm[r]);
+      if (sim > best) {
+        second = best;
+        best = sim;
+        best_r = r;
+      } else if (sim > second) {
+        second = sim;
+      }
+    }
+    if (best_sim) best_sim[i] = best;
+    if (second_sim) second_sim[i] = second;
+    assign[i] = (best_r >= 0 && best >= tau) ? seed_row[best_r] : -1;
+  }
+  free(seed_row);
+  free(seed_k);
+  free(seed_norm);
+  free(ki);
+}
+
+int cask_ref_consolidate(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                         const int32_t* prefix_len, const void* K, const float* scores,
+                         const uint8_t* role, int32_t* assign, double* best_sim,
+                         double* second_sim) {
+  (void)scores;
+  if (check_params(p) || n_units < 0) return -1;
+  for (int32_t u = 0; u < n_units; ++u)
+    if (check_unit(p, row_off[u + 1] - row_off[u], prefix_len[u])) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t u = 0; u < n_units; ++u) {
+    int32_t N = (int32_t)(row_off[u + 1] - row_off[u]);
+    consolidate_unit(p, N, K, row_off[u], role + row_off[u], assign + row_off[u],
+                     best_sim ? best_sim + row_off[u] : NULL,
+                     second_sim ? second_sim + row_off[u] : NULL);
+  }
+  return 0;
+}
+
+/* ------------------------------------------------------------------ fold + compaction
+ *
+ * m-folding (Section 2.4): for a group G (a seed and the donors assigned to it)
+ *   m = sum a_i,  k~ = sum a_i k_i / m,  v~ = sum a_i v_i / m,
+ * with a_i the token's score (its local score mass).  If every a_i is zero the weights
+ * become uniform.  A group of one is the token itself, copied without arithmetic.  The
+ * output keeps ascending source order (a representative sits at its seed's index); kept
+ * tokens pass through bit-identically (C subset of R, |R| <= B; Section 2.3).
+ */
+static void emit_unit(const cask_ref_params* p, int32_t N, const void* K, const void* V,
+                      int64_t row0, const float* s, const uint8_t* role, const int32_t* assign_src,
+                      void* K_out, void* V_out, int64_t out_row0, int32_t* out_len,
+                      int32_t* out_src, float* out_mass, int32_t* slot_of, int32_t* n_merged) {
+  const int d = p->head_dim;
+  const size_t es = elem_size(p->dtype);
+  double* ksum = (double*)malloc(sizeof(double) * d);
+  double* vsum = (double*)malloc(sizeof(double) * d);
+  int32_t* slot = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+  int32_t t = 0, merged = 0;
+  for (int32_t j = 0; j < N; ++j) {
+    slot[j] = -1;
+    uint8_t x = role[j];
+    if (x != CASK_REF_PREFIX_KEEP && x != CASK_REF_CORE && x != CASK_REF_RECENT &&
+        x != CASK_REF_SEED)
+      continue;
+    int32_t members = 1;
+    if (x == CASK_REF_SEED)
+      for (int32_t i = 0; i < N; ++i)
+        if (role[i] == CASK_REF_DONOR && assign_src[i] == j) ++members;
+    char* ko = (char*)K_out + (size_t)(out_row0 + t) * d * es;
+    char* vo = (char*)V_out + (size_t)(out_row0 + t) * d * es;
+    double mass;
+    if (members == 1) {
+      memcpy(ko, (const char*)K + (size_t)(row0 + j) * d * es, d * es);
+      memcpy(vo, (const char*)V + (size_t)(row0 + j) * d * es, d * es);
+      mass = (double)s[j];
+    } else {
+      double m = (double)s[j];
+      for (int32_t i = 0; i < N; ++i)
+        if (role[i] == CASK_REF_DONOR && assign_src[i] == j) m += (double)s[i];
+      int uniform = (m == 0.0);
+      double denom = uniform ? (double)members : m;
+      for (int c = 0; c < d; ++c) ksum[c] = vsum[c] = 0.0;
+      for (int32_t i = 0; i < N; ++i) {
+        if (!(i == j || (role[i] == CASK_REF_DONOR && assign_src[i] == j))) continue;
+        double a = uniform ? 1.0 : (double)s[i];
+        for (int c = 0; c < d; ++c) {
+          ksum[c] += a * load_elem(K, p->dtype, (row0 + i) * d + c);
+          vsum[c] += a * load_elem(V, p->dtype, (row0 + i) * d + c);
+        }
+      }
+      for (int c = 0; c < d; ++c) {
+        store_elem(K_out, p->dtype, (out_row0 + t) * d + c, ksum[c] / denom);
+        store_elem(V_out, p->dtype, (out_row0 + t) * d + c, vsum[c] / denom);
+      }
+      mass = m;
+      merged += members - 1;
+    }
+    out_src[t] = j;
+    if (out_mass) out_mass[t] = (float)mass;
+    slot[j] = t;
+    ++t;
+  }
+  *out_len = t;
+  *n_merged = merged;
+  if (slot_of) {
+    for (int32_t i = 0; i < N; ++i) {
+      if (role[i] == CASK_REF_DONOR)
+        slot_of[i] = assign_src[i] >= 0 ? slot[assign_src[i]] : -1;
+      else
+        slot_of[i] = slot[i];
+    }
+  }
+  free(ksum);
+  free(vsum);
+  free(slot);
+}
+
+int cask_ref_compress(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                      const int32_t* prefix_len, const void* K, const void* V, const void* Q,
+                      int scores_given, float* scores, void* K_out, void* V_out,
+                      int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
+                      uint8_t* role_out, int32_t* status, int n_threads) {
+  if (check_params(p) || n_units < 0 || !scores) return -1;
+  for (int32_t u = 0; u < n_units; ++u)
+    if (check_unit(p, row_off[u + 1] - row_off[u], prefix_len[u])) return -1;
+#ifdef _OPENMP
+  if (n_threads > 0) omp_set_num_threads(n_threads);
+#endif
+  (void)n_threads;
+  const int32_t B = p->budget;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t u = 0; u < n_units; ++u) {
+    const int64_t row0 = row_off[u];
+    const int32_t N = (int32_t)(row_off[u + 1] - row0);
+    const int32_t P = prefix_len[u];
+    float* s = scores + row0;
+    cask_ref_plan_t pl;
+    cask_ref_plan(p, P, N, &pl);
+    if (!scores_given)
+      score_unit(p, N, K, row0, Q, (int64_t)u * p->window * p->q_per_kv, s);
+    uint8_t* role = (uint8_t*)malloc((size_t)N);
+    int32_t* asrc = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    prefix_evict_unit(&pl, P, s, role);
+    partition_unit(&pl, P, N, s, role);
+    consolidate_unit(p, N, K, row0, role, asrc, NULL, NULL);
+    int32_t merged = 0;
+    emit_unit(p, N, K, V, row0, s, role, asrc, K_out, V_out, (int64_t)u * B, &out_len[u],
+              out_src + (int64_t)u * B, out_mass ? out_mass + (int64_t)u * B : NULL,
+              assign ? assign + row0 : NULL, &merged);
+    int32_t st = pl.status;
+    if (merged == 0 && !(st & (CASK_REF_ST_IDENTITY | CASK_REF_ST_PREFIX_BUDGET_EXHAUSTED)))
+      st |= CASK_REF_ST_MERGE_INACTIVE;
+    if (status) status[u] = st;
+    if (role_out) memcpy(role_out + row0, role, (size_t)N);
+    free(role);
+    free(asrc);
+  }
+  return 0;
+}

@@ -1,0 +1,124 @@
+/*
+ * CASK compression-event ORACLE -- test infrastructure, not product code.
+ *
+ * A plain, slow, single-pass-per-definition CPU implementation of the decode-time
+ * KV compression event of CASK (core-aware selective KV compression): score the
+ * cached tokens from a window of recent queries, evict in the prefix (two-stage
+ * compression, Section 2.2), split the decode trace into protected core and
+ * mergeable scratch (Section 2.1), fold near-duplicate scratch into weighted
+ * representatives (Section 2.4, the m-folding equations), and compact to the
+ * budget (|R| <= B and C subset of R, Section 2.3).
+ *
+ * Everything is computed in double precision on the exact input values; the score
+ * vector is rounded once to float and that float vector decides every ordering.
+ * Nothing here is blocked, fused or reordered beyond what the rules state.  It
+ * shares no code with the HIP library; only tests, the smoke check and the
+ * benchmark's cpu_baseline leg may call it.
+ *
+ * Where the paper leaves a rule open (deployed score form, similarity threshold,
+ * budget split, tie-break) the reading taken is stated at the function that
+ * implements it.  The constants of those readings (tau = 0.9, the quarter share
+ * and 1/64 floor of the prefix budget, the 4/5 core share, softmax-mean scoring)
+ * have no external anchor: "parity unpinned" for those constants -- they are
+ * parameters with defaults, pinned only by self-consistency tests.
+ *
+ * All pointers are HOST pointers owned by the caller.
+ */
+#ifndef CASK_REF_H
+#define CASK_REF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { CASK_REF_F32 = 0, CASK_REF_BF16 = 1 };
+
+/* per-unit regime bits (Section 5.2 names prefix_budget_exhausted and merge_inactive) */
+enum {
+  CASK_REF_ST_ACTIVE = 0,
+  CASK_REF_ST_IDENTITY = 1,
+  CASK_REF_ST_PREFIX_BUDGET_EXHAUSTED = 2,
+  CASK_REF_ST_MERGE_INACTIVE = 4
+};
+
+/* token roles */
+enum {
+  CASK_REF_PREFIX_DROP = 0,
+  CASK_REF_PREFIX_KEEP = 1,
+  CASK_REF_CORE = 2,
+  CASK_REF_SEED = 3,
+  CASK_REF_DONOR = 4,
+  CASK_REF_RECENT = 5,
+  CASK_REF_DECODE_EVICT = 6 /* decode token dropped without a merge attempt (exhausted regime) */
+};
+
+typedef struct {
+  int32_t dtype;         /* element type of K, V, Q and of K_out, V_out */
+  int32_t head_dim;      /* d */
+  int32_t q_per_kv;      /* G query heads per KV head */
+  int32_t window;        /* W query positions = the last W cache slots */
+  int32_t recent;        /* R always-kept tail; < 0 means W */
+  int32_t budget;        /* B */
+  int32_t core;          /* C; < 0 means floor(4*slots/5) */
+  int32_t prefix_budget; /* B_p; < 0 means max(floor(B/4), ceil(P/64)) */
+  float sim_threshold;   /* tau */
+  float softmax_scale;   /* <= 0 means 1/sqrt(d) */
+  int32_t causal;        /* 1: query at slot t sees keys j <= t */
+} cask_ref_params;
+
+typedef struct {
+  int32_t r_eff;  /* min(R, D) */
+  int32_t p_keep; /* prefix tokens kept */
+  int32_t slots;  /* decode slots outside the recent tail */
+  int32_t core;   /* C */
+  int32_t seeds;  /* M */
+  int32_t status; /* regime bits known from sizes alone */
+} cask_ref_plan_t;
+
+/* Budget split for one unit with prefix length P and cache length N. */
+void cask_ref_plan(const cask_ref_params* p, int32_t P, int32_t N, cask_ref_plan_t* out);
+
+/* Round a double to the nearest bf16 (ties to even); returns the 16-bit pattern. */
+uint16_t cask_ref_bf16_from_double(double x);
+double cask_ref_bf16_to_double(uint16_t h);
+
+/* scores[row_off[u] + j] = mean over the W*G window rows of softmax_j(scale <q,k_j>). */
+int cask_ref_score(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                   const void* K, const void* Q, float* scores, int n_threads);
+
+/* role[0,P_u) := PREFIX_KEEP for the top P_keep by (score desc, index asc), else PREFIX_DROP. */
+int cask_ref_prefix_evict(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                          const int32_t* prefix_len, const float* scores, uint8_t* role,
+                          int32_t* status);
+
+/* role[P_u,N_u) := CORE / SEED / DONOR / RECENT (or DECODE_EVICT when exhausted). */
+int cask_ref_partition(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                       const int32_t* prefix_len, const float* scores, uint8_t* role,
+                       int32_t* status);
+
+/* assign[row] = unit-local row of the seed a donor folds into, own row if kept, -1 if evicted.
+ * best_sim / second_sim (either may be NULL): per row, the largest and second largest cosine
+ * over the seeds for donors (NaN elsewhere); used by tests to excuse near-ties. */
+int cask_ref_consolidate(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                         const int32_t* prefix_len, const void* K, const float* scores,
+                         const uint8_t* role, int32_t* assign, double* best_sim,
+                         double* second_sim);
+
+/* The whole event.  scores_given != 0: `scores` is an input; else it is written.
+ * K_out, V_out: [n_units, B, d] in the cache dtype, rows >= out_len[u] untouched.
+ * out_src: [n_units, B] unit-local source row (the seed's row for a representative).
+ * out_mass: [n_units, B] (may be NULL) mass m of each output row.
+ * assign: [total_rows] (may be NULL) output slot of every input row, -1 if evicted.
+ * role: [total_rows] (may be NULL) final roles. */
+int cask_ref_compress(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                      const int32_t* prefix_len, const void* K, const void* V, const void* Q,
+                      int scores_given, float* scores, void* K_out, void* V_out,
+                      int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
+                      uint8_t* role, int32_t* status, int n_threads);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,614 @@
+"""Pins for the CPU oracle: closed forms, library routines, brute force and invariants.
+
+Each test anchors one rule of the oracle to something other than the oracle itself, so that
+a dropped term, a wrong sign or index, or a transposed operand fails at least one of them.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+from scipy.special import softmax as scipy_softmax
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ helpers
+
+def f32_params(ref, **kw):
+    base = dict(dtype=ref.F32, head_dim=16, q_per_kv=1, window=4, recent=-1, budget=32, core=-1,
+                prefix_budget=-1, sim_threshold=0.9, softmax_scale=0.0, causal=1)
+    base.update(kw)
+    return ref.Params(**base)
+
+
+def rand_unit(rng, N, d, W, G, n_units=1):
+    K = rng.standard_normal((n_units * N, d)).astype(np.float32)
+    V = rng.standard_normal((n_units * N, d)).astype(np.float32)
+    Q = rng.standard_normal((n_units, W, G, d)).astype(np.float32)
+    row_off = np.arange(n_units + 1, dtype=np.int64) * N
+    return K, V, Q, row_off
+
+
+def to_bf16_bits(x):
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16) \
+        .view(torch.int16).numpy().view(np.uint16)
+
+
+def from_bf16_bits(b):
+    return torch.from_numpy(b.view(np.int16).copy()).view(torch.bfloat16).to(torch.float64).numpy()
+
+
+# ------------------------------------------------------------------ bf16 rounding
+
+def test_bf16_rounding_matches_library(oracle):
+    rng = np.random.default_rng(1)
+    xs = np.concatenate([
+        rng.standard_normal(2000).astype(np.float32) * 10.0,
+        rng.standard_normal(200).astype(np.float32) * 1e-39,   # bf16 subnormals
+        np.array([0.0, -0.0, 1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -7,
+                  3.3895e38, -3.3895e38, 65504.0, 2.0 ** -133, 2.0 ** -134, 1.5 * 2.0 ** -133],
+                 dtype=np.float32)])
+    want = to_bf16_bits(xs)   # torch rounds float -> bfloat16 to nearest even
+    got = np.array([oracle.bf16_from_double(float(x)) for x in xs], dtype=np.uint16)
+    np.testing.assert_array_equal(got, want)
+    # ties that exist only in double: halfway between two bf16 neighbours plus/minus a hair
+    lo, hi = 1.0, 1.0 + 2.0 ** -7
+    mid = 0.5 * (lo + hi)
+    assert oracle.bf16_from_double(mid) == to_bf16_bits([lo])[0]              # tie -> even
+    assert oracle.bf16_from_double(mid + 2.0 ** -40) == to_bf16_bits([hi])[0]
+    assert oracle.bf16_from_double(mid - 2.0 ** -40) == to_bf16_bits([lo])[0]
+    # round trip
+    for h in [0x3F80, 0x4049, 0xC2F7, 0x0001, 0x8001, 0x7F7F]:
+        assert oracle.bf16_from_double(oracle.bf16_to_double(h)) == h
+
+
+# ------------------------------------------------------------------ R1 score
+
+def test_score_sums_to_one(oracle):
+    rng = np.random.default_rng(2)
+    for causal in (0, 1):
+        for (N, d, W, G) in [(37, 16, 5, 3), (64, 64, 32, 1), (9, 8, 9, 2)]:
+            K, _, Q, ro = rand_unit(rng, N, d, W, G, n_units=3)
+            p = f32_params(oracle, head_dim=d, window=W, q_per_kv=G, causal=causal)
+            s = oracle.score(p, ro, K, Q)
+            np.testing.assert_allclose(s.reshape(3, N).sum(1), 1.0, rtol=0, atol=2e-6)
+            assert (s >= 0).all()
+
+
+def test_score_single_row_is_library_softmax(oracle):
+    rng = np.random.default_rng(3)
+    N, d = 50, 24
+    K, _, Q, ro = rand_unit(rng, N, d, 1, 1)
+    for scale in (0.0, 0.37):
+        p = f32_params(oracle, head_dim=d, window=1, q_per_kv=1, softmax_scale=scale)
+        s = oracle.score(p, ro, K, Q)
+        c = scale if scale > 0 else 1.0 / np.sqrt(d)
+        want = scipy_softmax(np.float32(c).astype(np.float64) * (K.astype(np.float64) @ Q[0, 0, 0].astype(np.float64)))
+        np.testing.assert_allclose(s, want.astype(np.float32), rtol=2e-7, atol=0)
+
+
+def test_score_rows_decompose_into_library_softmax(oracle):
+    """Row (w, g) sits at slot N-W+w and sees keys up to its own slot; the score is the mean
+    of the rows' probabilities.  Each row is recomputed with scipy on the truncated key set."""
+    rng = np.random.default_rng(4)
+    N, d, W, G = 23, 12, 6, 3
+    K, _, Q, ro = rand_unit(rng, N, d, W, G, n_units=2)
+    for causal in (1, 0):
+        p = f32_params(oracle, head_dim=d, window=W, q_per_kv=G, causal=causal)
+        s = oracle.score(p, ro, K, Q).reshape(2, N)
+        for u in range(2):
+            Ku = K[u * N:(u + 1) * N].astype(np.float64)
+            acc = np.zeros(N)
+            for w in range(W):
+                last = N - W + w if causal else N - 1
+                for g in range(G):
+                    logits = (Ku[: last + 1] @ Q[u, w, g].astype(np.float64)) / np.sqrt(d)
+                    acc[: last + 1] += scipy_softmax(logits)
+            np.testing.assert_allclose(s[u], (acc / (W * G)).astype(np.float32), rtol=3e-7, atol=1e-12)
+
+
+def test_score_identical_keys_closed_form(oracle):
+    """All keys equal => every visible key gets 1/(t_w+1): s_j = (1/W) sum_w [j<=t_w]/(t_w+1)."""
+    N, d, W, G = 20, 8, 5, 2
+    rng = np.random.default_rng(5)
+    K = np.tile(rng.standard_normal((1, d)).astype(np.float32), (N, 1))
+    Q = rng.standard_normal((1, W, G, d)).astype(np.float32)
+    p = f32_params(oracle, head_dim=d, window=W, q_per_kv=G)
+    s = oracle.score(p, np.array([0, N]), K, Q)
+    want = np.zeros(N)
+    for w in range(W):
+        t = N - W + w
+        want[: t + 1] += 1.0 / (t + 1)
+    want /= W
+    np.testing.assert_allclose(s, want.astype(np.float32), rtol=3e-7)
+
+
+def test_score_log_integer_logits_closed_form(oracle):
+    """Logits ln(1), ln(2), ..., ln(N) => probabilities j / (N(N+1)/2)."""
+    N, d = 12, 4
+    scale = 0.5
+    K = np.zeros((N, d), dtype=np.float32)
+    K[:, 1] = np.log(np.arange(1, N + 1)) / scale / 2.0
+    Q = np.zeros((1, 1, 1, d), dtype=np.float32)
+    Q[0, 0, 0, 1] = 2.0
+    Q[0, 0, 0, 0] = 5.0   # orthogonal to every key: must not matter
+    p = f32_params(oracle, head_dim=d, window=1, q_per_kv=1, softmax_scale=scale)
+    s = oracle.score(p, np.array([0, N]), K, Q)
+    want = np.arange(1, N + 1) / (N * (N + 1) / 2)
+    np.testing.assert_allclose(s, want, rtol=2e-6)
+
+
+def test_score_bf16_inputs_are_read_exactly(oracle):
+    rng = np.random.default_rng(6)
+    N, d, W, G = 40, 16, 4, 2
+    K, _, Q, ro = rand_unit(rng, N, d, W, G)
+    Kb, Qb = to_bf16_bits(K), to_bf16_bits(Q)
+    pb = f32_params(oracle, dtype=oracle.BF16, head_dim=d, window=W, q_per_kv=G)
+    pf = f32_params(oracle, head_dim=d, window=W, q_per_kv=G)
+    s_b = oracle.score(pb, ro, Kb, Qb)
+    s_f = oracle.score(pf, ro, from_bf16_bits(Kb).astype(np.float32).reshape(N, d),
+                       from_bf16_bits(Qb).astype(np.float32).reshape(1, W, G, d))
+    np.testing.assert_array_equal(s_b, s_f)
+
+
+# ------------------------------------------------------------------ R2 order, R5 prefix
+
+def test_topk_maximises_score_sum_bruteforce(oracle):
+    rng = np.random.default_rng(7)
+    for trial in range(6):
+        P = 10
+        N = P + 8
+        s = rng.random(N).astype(np.float32)
+        if trial % 2:
+            s[:P] = np.round(s[:P] * 4) / 4     # many ties
+        for bp in (1, 3, 5):
+            # budget chosen so that P_keep = bp: decode (8 tokens, recent 4) never fills the room
+            p = f32_params(oracle, window=4, recent=4, budget=16, prefix_budget=bp)
+            pl = oracle.plan(p, P, N)
+            k = pl["p_keep"]
+            role, _ = oracle.prefix_evict(p, np.array([0, N]), np.array([P]), s)
+            keep = np.flatnonzero(role[:P] == oracle.PREFIX_KEEP)
+            assert len(keep) == k
+            best = max(float(np.sum(s[list(c)].astype(np.float64)))
+                       for c in itertools.combinations(range(P), k))
+            assert float(np.sum(s[keep].astype(np.float64))) == pytest.approx(best, rel=0, abs=1e-12)
+            # among equal scores the lower index is preferred: the kept set is the
+            # lexicographically smallest maximiser
+            order = np.lexsort((np.arange(P), -s[:P].astype(np.float64)))
+            np.testing.assert_array_equal(np.sort(order[:k]), keep)
+
+
+def test_constant_scores_keep_lowest_indices(oracle):
+    P, D = 40, 30
+    N = P + D
+    s = np.full(N, 0.125, dtype=np.float32)
+    p = f32_params(oracle, window=4, recent=6, budget=30, prefix_budget=10, core=8)
+    pl = oracle.plan(p, P, N)
+    assert (pl["p_keep"], pl["slots"], pl["core"], pl["seeds"]) == (10, 14, 8, 6)
+    role, _ = oracle.prefix_evict(p, np.array([0, N]), np.array([P]), s)
+    role, _ = oracle.partition(p, np.array([0, N]), np.array([P]), s, role)
+    assert (role[:10] == oracle.PREFIX_KEEP).all() and (role[10:P] == oracle.PREFIX_DROP).all()
+    assert (role[P:P + 8] == oracle.CORE).all()
+    assert (role[P + 8:P + 14] == oracle.SEED).all()
+    assert (role[P + 14:N - 6] == oracle.DONOR).all()
+    assert (role[N - 6:] == oracle.RECENT).all()
+
+
+def test_prefix_and_partition_match_library_sort(oracle):
+    rng = np.random.default_rng(8)
+    P, D = 300, 500
+    N = P + D
+    s = (rng.random(2 * N) ** 4).astype(np.float32)
+    s[rng.integers(0, 2 * N, 200)] = s[0]       # planted ties
+    ro = np.array([0, N, 2 * N])
+    p = f32_params(oracle, window=16, recent=20, budget=200)
+    pl = oracle.plan(p, P, N)
+    role, st = oracle.prefix_evict(p, ro, np.array([P, P]), s)
+    role, st = oracle.partition(p, ro, np.array([P, P]), s, role)
+    for u in range(2):
+        su = s[u * N:(u + 1) * N].astype(np.float64)
+        ru = role[u * N:(u + 1) * N]
+        order = np.lexsort((np.arange(P), -su[:P]))
+        want = np.full(P, oracle.PREFIX_DROP)
+        want[order[: pl["p_keep"]]] = oracle.PREFIX_KEEP
+        np.testing.assert_array_equal(ru[:P], want)
+        hi = N - pl["r_eff"]
+        order = P + np.lexsort((np.arange(hi - P), -su[P:hi]))
+        want = np.full(N - P, oracle.DONOR)
+        want[order[: pl["core"]] - P] = oracle.CORE
+        want[order[pl["core"]: pl["core"] + pl["seeds"]] - P] = oracle.SEED
+        want[hi - P:] = oracle.RECENT
+        np.testing.assert_array_equal(ru[P:], want)
+
+
+# ------------------------------------------------------------------ R4 plan
+
+def test_plan_golden_table(oracle):
+    rows = 0
+    with open(os.path.join(GOLDEN, "plan_table.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            lhs, rhs = line.split("|")
+            P, D, B, R, core = (int(x) for x in lhs.split())
+            r_eff, p_keep, slots, c, m, status = (int(x) for x in rhs.split())
+            p = f32_params(oracle, window=min(128, P + D), recent=R, budget=B, core=core)
+            got = oracle.plan(p, P, P + D)
+            assert got == dict(r_eff=r_eff, p_keep=p_keep, slots=slots, core=c, seeds=m,
+                               status=status), (line, got)
+            rows += 1
+    assert rows >= 10
+
+
+def test_plan_fills_budget_exactly(oracle):
+    """|R| <= B (Section 2.3) holds with equality whenever N > B: kept prefix + decode slots
+    actually usable + recent tail == min(N, B)."""
+    rng = np.random.default_rng(9)
+    for _ in range(3000):
+        R = int(rng.integers(0, 40))
+        B = int(rng.integers(R + 1, 300))
+        P = int(rng.integers(0, 2000))
+        D = int(rng.integers(0, 2000))
+        N = P + D
+        if N < 1:
+            continue
+        p = f32_params(oracle, window=1, recent=R, budget=B,
+                       core=int(rng.integers(-1, 50)), prefix_budget=int(rng.integers(-1, 200)))
+        pl = oracle.plan(p, P, N)
+        dnr = D - pl["r_eff"]
+        used = pl["p_keep"] + min(dnr, pl["slots"]) + pl["r_eff"]
+        assert used == min(N, B)
+        assert 0 <= pl["p_keep"] <= P and pl["core"] + pl["seeds"] == min(pl["slots"], max(dnr, 0)) \
+            or pl["status"] & (oracle.ST_IDENTITY | oracle.ST_MERGE_INACTIVE)
+        assert pl["core"] >= 0 and pl["seeds"] >= 0 and pl["core"] + pl["seeds"] <= max(pl["slots"], 0)
+        if pl["status"] & oracle.ST_PREFIX_BUDGET_EXHAUSTED:
+            assert pl["slots"] == 0 and dnr > 0 and pl["p_keep"] == B - pl["r_eff"]
+
+
+# ------------------------------------------------------------------ R6 consolidate
+
+def make_case(rng, oracle, P=20, D=120, d=16, W=8, G=2, B=64, tau=0.9, clusters=6, **kw):
+    N = P + D
+    K, V, Q, ro = rand_unit(rng, N, d, W, G)
+    # near-duplicate groups in the decode span
+    pos = P + rng.permutation(D - W)[: clusters * 5].reshape(clusters, 5)
+    for c in range(clusters):
+        base_k, base_v = K[pos[c, 0]].copy(), V[pos[c, 0]].copy()
+        for t in pos[c, 1:]:
+            K[t] = base_k + 0.03 * rng.standard_normal(d).astype(np.float32)
+            V[t] = base_v + 0.03 * rng.standard_normal(d).astype(np.float32)
+    p = f32_params(oracle, head_dim=d, window=W, q_per_kv=G, budget=B, sim_threshold=tau, **kw)
+    return p, K, V, Q, ro, np.array([P], dtype=np.int32), pos
+
+
+def test_consolidate_matches_numpy_cosine_argmax(oracle):
+    rng = np.random.default_rng(10)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle)
+    N = K.shape[0]
+    s = (rng.random(N) ** 3).astype(np.float32)
+    role, _ = oracle.prefix_evict(p, ro, pl, s)
+    role, _ = oracle.partition(p, ro, pl, s, role)
+    assign, best, second = oracle.consolidate(p, ro, pl, K, s, role, want_sims=True)
+    Kn = K.astype(np.float64)
+    Kn = Kn / np.linalg.norm(Kn, axis=1, keepdims=True)
+    seeds = np.flatnonzero(role == oracle.SEED)
+    donors = np.flatnonzero(role == oracle.DONOR)
+    assert len(seeds) > 0 and len(donors) > 0
+    cos = Kn[donors] @ Kn[seeds].T
+    arg = cos.argmax(1)          # numpy argmax returns the first (lowest index) maximum
+    mx = cos.max(1)
+    want = np.where(mx >= np.float32(0.9).astype(np.float64), seeds[arg], -1)
+    np.testing.assert_array_equal(assign[donors], want)
+    np.testing.assert_allclose(best[donors], mx, rtol=1e-12)
+    kept = np.isin(role, [oracle.PREFIX_KEEP, oracle.CORE, oracle.SEED, oracle.RECENT])
+    np.testing.assert_array_equal(assign[kept], np.flatnonzero(kept))
+    assert (assign[role == oracle.PREFIX_DROP] == -1).all()
+    assert (assign[donors] >= 0).sum() > 0
+
+
+def test_tau_above_one_is_pure_topk_eviction(oracle):
+    rng = np.random.default_rng(11)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, tau=1.5)
+    out = oracle.compress(p, ro, pl, K, V, Q)
+    N, P = K.shape[0], int(pl[0])
+    plan = oracle.plan(p, P, N)
+    s = out["scores"].astype(np.float64)
+    hi = N - plan["r_eff"]
+    keep_p = np.sort(np.lexsort((np.arange(P), -s[:P]))[: plan["p_keep"]])
+    keep_d = np.sort(P + np.lexsort((np.arange(hi - P), -s[P:hi]))[: plan["slots"]])
+    want_src = np.concatenate([keep_p, keep_d, np.arange(hi, N)])
+    L = int(out["out_len"][0])
+    np.testing.assert_array_equal(out["out_src"][0, :L], want_src)
+    np.testing.assert_array_equal(out["K_out"][0, :L], K[want_src])      # bit-identical rows
+    np.testing.assert_array_equal(out["V_out"][0, :L], V[want_src])
+    assert out["status"][0] & oracle.ST_MERGE_INACTIVE
+
+
+def test_tau_minus_one_conserves_decode_mass(oracle):
+    rng = np.random.default_rng(12)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, tau=-1.0)
+    out = oracle.compress(p, ro, pl, K, V, Q)
+    N, P = K.shape[0], int(pl[0])
+    plan = oracle.plan(p, P, N)
+    s = out["scores"].astype(np.float64)
+    role = out["role"]
+    assert (out["assign"][role == oracle.DONOR] >= 0).all()        # every donor merges
+    L = int(out["out_len"][0])
+    src = out["out_src"][0, :L]
+    dec = src >= P
+    assert float(out["out_mass"][0, :L][dec].astype(np.float64).sum()) == \
+        pytest.approx(float(s[P:].sum()), rel=1e-6)
+    # kept prefix rows carry their own score
+    np.testing.assert_array_equal(out["out_mass"][0, :L][~dec], out["scores"][src[~dec]])
+    assert plan["status"] == 0 and out["status"][0] == 0
+
+
+def test_planted_clusters_fold_onto_their_seed(oracle):
+    """Injected scores make exactly one member of each planted cluster a seed: all its mates
+    must land on it and unrelated tokens must be evicted."""
+    rng = np.random.default_rng(13)
+    clusters = 6
+    p, K, V, Q, ro, pl, pos = make_case(rng, oracle, clusters=clusters, B=8 + 10 + 6 + 20,
+                                        core=10, prefix_budget=20)
+    N, P = K.shape[0], int(pl[0])
+    plan = oracle.plan(p, P, N)
+    assert (plan["core"], plan["seeds"]) == (10, 6)
+    s = (0.001 * rng.random(N)).astype(np.float32)
+    free = np.setdiff1d(np.arange(P, N - 8), pos.ravel())
+    s[free[:10]] = 0.9 + 0.01 * np.arange(10, dtype=np.float32)      # the core
+    s[pos[:, 0]] = 0.5 + 0.01 * np.arange(clusters, dtype=np.float32)  # one seed per cluster
+    out = oracle.compress(p, ro, pl, K, V, Q, scores=s)
+    role, assign = out["role"], out["assign"]
+    np.testing.assert_array_equal(np.sort(np.flatnonzero(role == oracle.SEED)), np.sort(pos[:, 0]))
+    for c in range(clusters):
+        seed_slot = assign[pos[c, 0]]
+        assert seed_slot >= 0
+        assert (assign[pos[c, 1:]] == seed_slot).all()
+    others = np.setdiff1d(np.flatnonzero(role == oracle.DONOR), pos.ravel())
+    assert (assign[others] == -1).all()
+    assert out["status"][0] == 0
+
+
+# ------------------------------------------------------------------ R7 fold
+
+def test_fold_golden_example(oracle):
+    a, ks, vs, want = [], [], [], None
+    with open(os.path.join(GOLDEN, "fold_example.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = [np.array(x.split(), dtype=np.float64) for x in line.split("|")]
+            if len(a) < 3:
+                a.append(parts[0][0]); ks.append(parts[1]); vs.append(parts[2])
+            else:
+                want = parts
+    d = 4
+    for dtype in (oracle.F32, oracle.BF16):
+        # cache: 1 prefix token, 3 group tokens (seed first), 2 fillers, 1 recent
+        K = np.zeros((7, d), dtype=np.float32)
+        V = np.zeros((7, d), dtype=np.float32)
+        K[0] = [1, 0, 0, 0]
+        K[1:4], V[1:4] = np.array(ks), np.array(vs)
+        # make the three group keys parallel enough: tau = -1 merges everything anyway
+        K[4] = [0, 0, 9, 1]; K[5] = [7, 7, 7, 7]; K[6] = [1, 1, 1, 1]
+        s = np.array([0.5, a[0], a[1], a[2], 0.9, 0.8, 0.1], dtype=np.float32)
+        # B = 1 recent + 1 prefix + 2 core + 1 seed = 5 ; donors = rows 1 and 3 (0.25 each)
+        p = oracle.Params(dtype=dtype, head_dim=d, q_per_kv=1, window=1, recent=1, budget=5,
+                          core=2, prefix_budget=1, sim_threshold=-1.0)
+        Kx, Vx = (K, V) if dtype == oracle.F32 else (to_bf16_bits(K).reshape(7, d), to_bf16_bits(V).reshape(7, d))
+        out = oracle.compress(p, np.array([0, 7]), np.array([1]), Kx, Vx, None, scores=s)
+        assert out["out_len"][0] == 5
+        np.testing.assert_array_equal(out["role"], [1, 4, 3, 4, 2, 2, 5])
+        np.testing.assert_array_equal(out["out_src"][0, :5], [0, 2, 4, 5, 6])
+        np.testing.assert_array_equal(out["assign"], [0, 1, 1, 1, 2, 3, 4])
+        ko, vo = out["K_out"][0, 1], out["V_out"][0, 1]
+        if dtype == oracle.BF16:
+            ko, vo = from_bf16_bits(ko), from_bf16_bits(vo)
+        np.testing.assert_array_equal(ko, want[1])
+        np.testing.assert_array_equal(vo, want[2])
+        assert out["out_mass"][0, 1] == want[0][0]
+
+
+def check_representatives(oracle, p, K, V, out, rtol):
+    """Every output row is either an input row, bit for bit, or the score-weighted mean of its
+    members (recomputed here from the assignment alone)."""
+    s = out["scores"].astype(np.float64)
+    L = int(out["out_len"][0])
+    n_folded = 0
+    for t in range(L):
+        members = np.flatnonzero(out["assign"] == t)
+        src = out["out_src"][0, t]
+        assert src in members
+        if len(members) == 1:
+            np.testing.assert_array_equal(out["K_out"][0, t], K[src])
+            np.testing.assert_array_equal(out["V_out"][0, t], V[src])
+            assert out["out_mass"][0, t] == out["scores"][src]
+            continue
+        n_folded += 1
+        a = s[members]
+        m = a.sum()
+        kk = (a[:, None] * K[members].astype(np.float64)).sum(0) / m
+        vv = (a[:, None] * V[members].astype(np.float64)).sum(0) / m
+        np.testing.assert_allclose(out["K_out"][0, t], kk, rtol=0, atol=rtol * np.abs(kk).max())
+        np.testing.assert_allclose(out["V_out"][0, t], vv, rtol=0, atol=rtol * np.abs(vv).max())
+        assert out["out_mass"][0, t] == pytest.approx(m, rel=1e-6)
+    return n_folded
+
+
+def test_representative_is_score_weighted_mean(oracle):
+    rng = np.random.default_rng(14)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, tau=0.5)
+    out = oracle.compress(p, ro, pl, K, V, Q)
+    assert check_representatives(oracle, p, K, V, out, 1e-6) > 0
+    L = int(out["out_len"][0])
+    assert L <= p.budget
+    assert (np.diff(out["out_src"][0, :L]) > 0).all()
+
+
+def test_first_order_mass_identity(oracle):
+    """sum_i a_i <q, k_i> = m <q, k~> for any probe q (the linear part of the perturbation
+    decomposition, Section 2.6)."""
+    rng = np.random.default_rng(15)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, tau=0.0)
+    out = oracle.compress(p, ro, pl, K, V, Q)
+    s = out["scores"].astype(np.float64)
+    L = int(out["out_len"][0])
+    q = rng.standard_normal(K.shape[1])
+    checked = 0
+    for t in range(L):
+        members = np.flatnonzero(out["assign"] == t)
+        if len(members) < 2:
+            continue
+        lhs = float((s[members] * (K[members].astype(np.float64) @ q)).sum())
+        rhs = float(out["out_mass"][0, t]) * float(out["K_out"][0, t].astype(np.float64) @ q)
+        assert lhs == pytest.approx(rhs, rel=2e-5, abs=1e-7)
+        checked += 1
+    assert checked > 0
+
+
+def test_scaling_scores_by_power_of_two_changes_nothing(oracle):
+    rng = np.random.default_rng(16)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, tau=0.3)
+    s = (rng.random(K.shape[0]) ** 2).astype(np.float32)
+    a = oracle.compress(p, ro, pl, K, V, Q, scores=s)
+    b = oracle.compress(p, ro, pl, K, V, Q, scores=s * np.float32(2.0 ** -7))
+    for key in ("K_out", "V_out", "out_src", "out_len", "assign", "role"):
+        np.testing.assert_array_equal(a[key], b[key])
+    np.testing.assert_array_equal(a["out_mass"] * np.float32(2.0 ** -7), b["out_mass"])
+
+
+def test_zero_mass_group_uses_uniform_weights(oracle):
+    d = 4
+    K = np.array([[1, 0, 0, 0], [2, 0, 0, 0], [4, 0, 0, 0], [0, 1, 0, 0], [0, 0, 1, 0]], dtype=np.float32)
+    V = np.arange(20, dtype=np.float32).reshape(5, d)
+    s = np.array([0, 0, 0, 0.5, 0.25], dtype=np.float32)
+    # P = 0, recent 1, budget 3: slots 2 -> core 1 (row 3), seed 1 (row 0: zero score, lowest
+    # index among the ties), donors rows 1, 2 (parallel to row 0 => cosine 1)
+    p = oracle.Params(dtype=oracle.F32, head_dim=d, q_per_kv=1, window=1, recent=1, budget=3,
+                      core=1, prefix_budget=0, sim_threshold=0.99)
+    out = oracle.compress(p, np.array([0, 5]), np.array([0]), K, V, None, scores=s)
+    np.testing.assert_array_equal(out["role"], [3, 4, 4, 2, 5])
+    np.testing.assert_array_equal(out["assign"], [0, 0, 0, 1, 2])
+    np.testing.assert_allclose(out["K_out"][0, 0], K[:3].mean(0))
+    np.testing.assert_allclose(out["V_out"][0, 0], V[:3].mean(0))
+    assert out["out_mass"][0, 0] == 0.0
+
+
+# ------------------------------------------------------------------ R8 / R9 and regimes
+
+def test_core_and_recent_pass_through_bit_identically(oracle):
+    rng = np.random.default_rng(17)
+    for dtype in (oracle.F32, oracle.BF16):
+        p, K, V, Q, ro, pl, _ = make_case(rng, oracle, tau=0.2)
+        if dtype == oracle.BF16:
+            shp = K.shape
+            K, V, Q = to_bf16_bits(K).reshape(shp), to_bf16_bits(V).reshape(shp), to_bf16_bits(Q).reshape(Q.shape)
+            p.dtype = oracle.BF16
+        out = oracle.compress(p, ro, pl, K, V, Q)
+        role = out["role"]
+        for r in np.flatnonzero(np.isin(role, [oracle.CORE, oracle.RECENT, oracle.PREFIX_KEEP])):
+            t = out["assign"][r]
+            assert t >= 0 and out["out_src"][0, t] == r
+            np.testing.assert_array_equal(out["K_out"][0, t], K[r])
+            np.testing.assert_array_equal(out["V_out"][0, t], V[r])
+        assert out["out_len"][0] == p.budget
+
+
+def test_budget_not_smaller_than_cache_is_identity(oracle):
+    rng = np.random.default_rng(18)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, B=140)
+    N = K.shape[0]
+    assert N == 140
+    out = oracle.compress(p, ro, pl, K, V, Q)
+    assert out["out_len"][0] == N and out["status"][0] == oracle.ST_IDENTITY
+    np.testing.assert_array_equal(out["K_out"][0, :N], K)
+    np.testing.assert_array_equal(out["V_out"][0, :N], V)
+    np.testing.assert_array_equal(out["out_src"][0, :N], np.arange(N))
+    np.testing.assert_array_equal(out["assign"], np.arange(N))
+
+
+def test_second_compress_at_same_budget_is_identity(oracle):
+    rng = np.random.default_rng(19)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, tau=0.3)
+    a = oracle.compress(p, ro, pl, K, V, Q)
+    L = int(a["out_len"][0])
+    P2 = int((a["out_src"][0, :L] < pl[0]).sum())
+    K2, V2 = a["K_out"][0, :L].copy(), a["V_out"][0, :L].copy()
+    b = oracle.compress(p, np.array([0, L]), np.array([P2]), K2, V2, Q)
+    assert b["status"][0] == oracle.ST_IDENTITY and b["out_len"][0] == L
+    np.testing.assert_array_equal(b["K_out"][0, :L], K2)
+
+
+def test_exhausted_prefix_turns_consolidation_off(oracle):
+    rng = np.random.default_rng(20)
+    P, D, d, W, G, B = 400, 60, 16, 8, 1, 40
+    N = P + D
+    K, V, Q, ro = rand_unit(rng, N, d, W, G)
+    K[P + 10] = K[P + 11]       # an exact duplicate pair that would merge if the path were open
+    p = f32_params(oracle, head_dim=d, window=W, q_per_kv=G, budget=B, prefix_budget=100)
+    plan = oracle.plan(p, P, N)
+    assert plan["status"] == oracle.ST_PREFIX_BUDGET_EXHAUSTED and plan["p_keep"] == B - W
+    out = oracle.compress(p, ro, np.array([P]), K, V, Q)
+    role = out["role"]
+    assert out["status"][0] == oracle.ST_PREFIX_BUDGET_EXHAUSTED
+    assert not np.isin(role, [oracle.SEED, oracle.DONOR, oracle.CORE]).any()
+    assert (role[P:N - W] == oracle.DECODE_EVICT).all() and (out["assign"][P:N - W] == -1).all()
+    assert out["out_len"][0] == B
+    src = out["out_src"][0]
+    np.testing.assert_array_equal(out["K_out"][0], K[src])          # no row is new
+    np.testing.assert_array_equal(out["V_out"][0], V[src])
+    np.testing.assert_array_equal(src[B - W:], np.arange(N - W, N))
+    s = out["scores"].astype(np.float64)
+    np.testing.assert_array_equal(src[:B - W], np.sort(np.lexsort((np.arange(P), -s[:P]))[:B - W]))
+
+
+def test_representative_set_mass_not_below_core_mass(oracle):
+    """rho_core <= rho_rep (Section 2.6) when the method's own score stands in for the
+    oracle-relevant mass: R contains C, and folding keeps the donors' mass."""
+    rng = np.random.default_rng(21)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, tau=0.3)
+    out = oracle.compress(p, ro, pl, K, V, Q)
+    s = out["scores"].astype(np.float64)
+    L = int(out["out_len"][0])
+    top = np.sort(s)[::-1][:p.budget].sum()
+    core_mass = s[np.isin(out["role"], [oracle.CORE, oracle.RECENT, oracle.PREFIX_KEEP])].sum()
+    rep_mass = out["out_mass"][0, :L].astype(np.float64).sum()
+    assert 0.0 <= core_mass / top <= rep_mass / top + 1e-9
+    assert rep_mass <= s.sum() * (1 + 1e-6)
+
+
+def test_invalid_arguments_are_rejected(oracle):
+    rng = np.random.default_rng(22)
+    K, V, Q, ro = rand_unit(rng, 10, 16, 4, 1)
+    with pytest.raises(ValueError):    # budget must exceed the recent tail
+        oracle.compress(f32_params(oracle, budget=4, recent=4), ro, np.array([2]), K, V, Q)
+    with pytest.raises(ValueError):    # cache shorter than the window
+        oracle.compress(f32_params(oracle, window=4), np.array([0, 3]), np.array([0]), K[:3], V[:3], Q)
+    with pytest.raises(ValueError):    # prefix longer than the cache
+        oracle.compress(f32_params(oracle), ro, np.array([11]), K, V, Q)
+
+
+def test_multi_unit_ragged_batch_equals_unit_by_unit(oracle):
+    rng = np.random.default_rng(23)
+    d, W, G, B = 16, 6, 2, 40
+    lens = [70, 41, 120, 39]
+    Ps = [10, 0, 60, 5]
+    K = rng.standard_normal((sum(lens), d)).astype(np.float32)
+    V = rng.standard_normal((sum(lens), d)).astype(np.float32)
+    Q = rng.standard_normal((4, W, G, d)).astype(np.float32)
+    ro = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    p = f32_params(oracle, head_dim=d, window=W, q_per_kv=G, budget=B, sim_threshold=0.1)
+    out = oracle.compress(p, ro, np.array(Ps), K, V, Q)
+    for u in range(4):
+        sl = slice(ro[u], ro[u + 1])
+        one = oracle.compress(p, np.array([0, lens[u]]), np.array([Ps[u]]), K[sl], V[sl], Q[u:u + 1])
+        L = one["out_len"][0]
+        assert out["out_len"][u] == L
+        np.testing.assert_array_equal(out["K_out"][u, :L], one["K_out"][0, :L])
+        np.testing.assert_array_equal(out["assign"][sl], one["assign"])
+        np.testing.assert_array_equal(out["scores"][sl], one["scores"])
+        assert out["status"][u] == one["status"][0]
