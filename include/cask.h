@@ -1,0 +1,161 @@
+/*
+ * cask.h -- C ABI of the MI355X (gfx950) CASK compression-event library.
+ *
+ * One compression event, for every unit u = (sequence, layer, KV head) of a batch:
+ *   score      the cached tokens with the attention mass that a window of recent queries
+ *              puts on them (the scalar importance the method inherits, Section 1; used as
+ *              the local score mass a_i of Section 2.4);
+ *   evict      in the prefix, to leave room for the decode stage (stage 1, Section 2.2);
+ *   partition  the decode trace into protected core and mergeable scratch (Section 2.1);
+ *   consolidate near-duplicate scratch onto representatives by key cosine similarity
+ *              (Section 2.5 names raw cosine as the plain merge geometry);
+ *   fold       each group into a weighted representative (Section 2.4:
+ *              m = sum a_i, k~ = sum a_i k_i / m, v~ = sum a_i v_i / m);
+ *   compact    to the budget with the core included (|R| <= B, C subset of R, Section 2.3),
+ *              flagging the prefix_budget_exhausted / merge_inactive regimes (Section 5.2).
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller, unless marked HOST.
+ *     The library allocates nothing, never synchronises, and only enqueues work on
+ *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Inputs are never modified.  Outputs of one call must not alias its inputs.
+ *   - Argument errors are found on the host before any launch and returned as a
+ *     negative code; nothing is enqueued then.  Per-unit regime outcomes are status bits
+ *     in device memory, not errors.
+ *   - Row layout: K, V are [total_rows, d] row-major in the cache dtype; unit u owns rows
+ *     [row_off[u], row_off[u+1]).  row_off and prefix_len live on the device AND are
+ *     mirrored on the host (the host copy sizes the launches).
+ *   - Calls that share a workspace on different streams race; one workspace per stream.
+ */
+#ifndef CASK_H
+#define CASK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { CASK_F32 = 0, CASK_BF16 = 1 } cask_dtype;
+
+/* return codes */
+enum {
+  CASK_OK = 0,
+  CASK_EINVAL = -1,  /* bad parameter, shape or NULL pointer */
+  CASK_ENOMEM = -2,  /* workspace smaller than cask_workspace_bytes() */
+  CASK_EDEVICE = -3  /* a HIP call failed (launch error) */
+};
+
+/* per-unit status bits (device memory) */
+enum {
+  CASK_ST_ACTIVE = 0,
+  CASK_ST_IDENTITY = 1,                /* N <= B: output equals input */
+  CASK_ST_PREFIX_BUDGET_EXHAUSTED = 2, /* the prefix left no decode slot (Section 5.2) */
+  CASK_ST_MERGE_INACTIVE = 4           /* no donor was folded into any representative */
+};
+
+/* token roles */
+enum {
+  CASK_ROLE_PREFIX_DROP = 0,
+  CASK_ROLE_PREFIX_KEEP = 1,
+  CASK_ROLE_CORE = 2,
+  CASK_ROLE_SEED = 3,   /* kept scratch token that representatives are built around */
+  CASK_ROLE_DONOR = 4,  /* scratch token offered to the seeds */
+  CASK_ROLE_RECENT = 5,
+  CASK_ROLE_DECODE_EVICT = 6 /* decode token dropped unseen: exhausted regime only */
+};
+
+typedef struct {
+  int32_t dtype;         /* cask_dtype of K, V, Q and of K_out, V_out */
+  int32_t head_dim;      /* d: 64 or 128 */
+  int32_t q_per_kv;      /* G query heads per KV head */
+  int32_t window;        /* W query positions = the last W cache slots of the unit */
+  int32_t recent;        /* R: tail always kept verbatim; < 0 => W */
+  int32_t budget;        /* B >= R + 1 */
+  int32_t core;          /* C; < 0 => floor(4 * slots / 5) */
+  int32_t prefix_budget; /* B_p; < 0 => max(floor(B / 4), ceil(P / 64)) */
+  float sim_threshold;   /* tau: a donor folds into its best seed iff cosine >= tau */
+  float softmax_scale;   /* <= 0 => 1 / sqrt(d) */
+  int32_t causal;        /* 1: the query at slot t sees keys j <= t; 0: all keys */
+  int32_t scores_given;  /* cask_compress only: 1 => `scores` is an input, scoring skipped */
+} cask_params;
+
+typedef struct {
+  int32_t n_units;
+  const int64_t* row_off;      /* DEVICE [n_units + 1] */
+  const int32_t* prefix_len;   /* DEVICE [n_units], 0 <= P_u <= N_u */
+  const int64_t* row_off_host; /* HOST mirror of row_off */
+  const int32_t* prefix_len_host; /* HOST mirror of prefix_len */
+  const void* K;               /* DEVICE [total_rows, d], keys as cached (post-RoPE) */
+  const void* V;               /* DEVICE [total_rows, d] */
+  const void* Q;               /* DEVICE [n_units, W, G, d]; row (w, g) sits at slot N_u - W + w */
+} cask_batch;
+
+/* Budget split of one unit (two-stage compression, Section 2.2; pure host arithmetic). */
+typedef struct {
+  int32_t r_eff;  /* min(R, D) */
+  int32_t p_keep; /* prefix tokens kept by stage 1 */
+  int32_t slots;  /* decode slots outside the recent tail: B - r_eff - p_keep */
+  int32_t core;   /* C */
+  int32_t seeds;  /* M = slots - C representatives */
+  int32_t status; /* regime bits that follow from the sizes alone */
+} cask_plan_t;
+
+/* HOST: the split for prefix length P and cache length N.  Returns CASK_EINVAL on bad sizes. */
+int cask_plan(const cask_params* params, int32_t P, int32_t N, cask_plan_t* out);
+
+/* HOST: bytes of device workspace every entry point below needs for such a batch. */
+size_t cask_workspace_bytes(const cask_params* params, int32_t n_units, int64_t total_rows,
+                            int32_t max_unit_len);
+
+/* Scores (importance; the a_i of Section 2.4): scores[row_off[u] + j] = mean over the W*G
+ * window rows of softmax_j(scale * <q, k_j>) with the causal mask of `params`.
+ * Reads K, Q.  Writes scores [total_rows] float. */
+int cask_score(const cask_params* params, const cask_batch* batch, float* scores, void* ws,
+               size_t ws_bytes, void* hip_stream);
+
+/* Stage 1 (Section 2.2): role[row_off[u] + j], j < P_u, := PREFIX_KEEP for the top P_keep
+ * by (score descending, index ascending), else PREFIX_DROP.  status[u] := plan bits.
+ * Rows >= P_u of `role` are left untouched. */
+int cask_prefix_evict(const cask_params* params, const cask_batch* batch, const float* scores,
+                      uint8_t* role, int32_t* status, void* ws, size_t ws_bytes,
+                      void* hip_stream);
+
+/* Stage 2 decomposition (Section 2.1): writes role for rows [P_u, N_u): top C => CORE, next
+ * M => SEED, rest => DONOR, last r_eff => RECENT (DECODE_EVICT when exhausted).
+ * status[u] := plan bits.  Rows < P_u are left untouched. */
+int cask_partition(const cask_params* params, const cask_batch* batch, const float* scores,
+                   uint8_t* role, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Selective consolidation (Sections 2.1, 2.5): for every DONOR the seed of largest key
+ * cosine (ties: lowest cache index); assign[row] = unit-local row of that seed when the
+ * cosine is >= tau, -1 otherwise; kept rows get their own unit-local row; dropped rows -1.
+ * Reads K, role.  `scores` is accepted for symmetry and not read. */
+int cask_consolidate(const cask_params* params, const cask_batch* batch, const float* scores,
+                     const uint8_t* role, int32_t* assign, void* ws, size_t ws_bytes,
+                     void* hip_stream);
+
+/* The whole event (Sections 2.1-2.4).
+ *   K_out, V_out [n_units, B, d]  rows [0, out_len[u]) in ascending source order; a
+ *                                 representative sits at its seed's position; kept tokens
+ *                                 are bit-identical copies; rows >= out_len[u] untouched
+ *   out_len  [n_units]            = min(N_u, B)
+ *   out_src  [n_units, B]         unit-local source row of each output row
+ *   out_mass [n_units, B] or NULL mass m of each output row (own score if not merged)
+ *   assign   [total_rows] or NULL output slot each input row went to, -1 if evicted
+ *   scores   [total_rows] or NULL input when params->scores_given, else optional output
+ *   status   [n_units]            regime bits (plan bits, plus MERGE_INACTIVE when no donor
+ *                                 passed tau)
+ */
+int cask_compress(const cask_params* params, const cask_batch* batch, void* K_out, void* V_out,
+                  int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
+                  float* scores, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* HOST: short name of a return code. */
+const char* cask_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CASK_H */

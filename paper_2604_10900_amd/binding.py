@@ -1,0 +1,252 @@
+"""Thin ctypes binding of libcask.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (torch is used for device
+memory and streams, nothing else), passes their raw pointers and the current HIP stream to
+the C ABI declared in include/cask.h, and returns the output tensors.  No step of the
+compression event is computed here, and there is no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcask.so")
+
+F32, BF16 = 0, 1
+OK, EINVAL, ENOMEM, EDEVICE = 0, -1, -2, -3
+ST_ACTIVE, ST_IDENTITY, ST_PREFIX_BUDGET_EXHAUSTED, ST_MERGE_INACTIVE = 0, 1, 2, 4
+(ROLE_PREFIX_DROP, ROLE_PREFIX_KEEP, ROLE_CORE, ROLE_SEED, ROLE_DONOR, ROLE_RECENT,
+ ROLE_DECODE_EVICT) = range(7)
+
+EXPORTS = ["cask_plan", "cask_workspace_bytes", "cask_score", "cask_prefix_evict",
+           "cask_partition", "cask_consolidate", "cask_compress", "cask_strerror"]
+
+
+class CaskError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        self.code = code
+        super().__init__(f"{fn} failed: {code} ({_strerror(code)})")
+
+
+class _Params(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("head_dim", C.c_int32), ("q_per_kv", C.c_int32),
+                ("window", C.c_int32), ("recent", C.c_int32), ("budget", C.c_int32),
+                ("core", C.c_int32), ("prefix_budget", C.c_int32),
+                ("sim_threshold", C.c_float), ("softmax_scale", C.c_float),
+                ("causal", C.c_int32), ("scores_given", C.c_int32)]
+
+
+class _Batch(C.Structure):
+    _fields_ = [("n_units", C.c_int32), ("row_off", C.c_void_p), ("prefix_len", C.c_void_p),
+                ("row_off_host", C.c_void_p), ("prefix_len_host", C.c_void_p),
+                ("K", C.c_void_p), ("V", C.c_void_p), ("Q", C.c_void_p)]
+
+
+class _Plan(C.Structure):
+    _fields_ = [("r_eff", C.c_int32), ("p_keep", C.c_int32), ("slots", C.c_int32),
+                ("core", C.c_int32), ("seeds", C.c_int32), ("status", C.c_int32)]
+
+
+@dataclass
+class Params:
+    dtype: int = BF16
+    head_dim: int = 128
+    q_per_kv: int = 1
+    window: int = 128
+    recent: int = -1
+    budget: int = 384
+    core: int = -1
+    prefix_budget: int = -1
+    sim_threshold: float = 0.9
+    softmax_scale: float = 0.0
+    causal: int = 1
+
+    def c(self, scores_given: int = 0) -> _Params:
+        return _Params(self.dtype, self.head_dim, self.q_per_kv, self.window, self.recent,
+                       self.budget, self.core, self.prefix_budget, self.sim_threshold,
+                       self.softmax_scale, self.causal, scores_given)
+
+
+_lib = None
+
+
+def load():
+    """Load libcask.so (built in-tree by paper_2604_10900_amd.build.build_lib)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with "
+                              "`python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = C.CDLL(LIB_PATH)
+        lib.cask_workspace_bytes.restype = C.c_size_t
+        lib.cask_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32]
+        lib.cask_strerror.restype = C.c_char_p
+        lib.cask_strerror.argtypes = [C.c_int]
+        lib.cask_plan.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+        vp = C.c_void_p
+        lib.cask_score.argtypes = [vp, vp, vp, vp, C.c_size_t, vp]
+        lib.cask_prefix_evict.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        lib.cask_partition.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        lib.cask_consolidate.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        lib.cask_compress.argtypes = [vp] * 11 + [C.c_size_t, vp]
+        for name in ("cask_plan", "cask_score", "cask_prefix_evict", "cask_partition",
+                     "cask_consolidate", "cask_compress"):
+            getattr(lib, name).restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def _strerror(code: int) -> str:
+    try:
+        return load().cask_strerror(code).decode()
+    except Exception:  # pragma: no cover
+        return "?"
+
+
+def plan(p: Params, P: int, N: int) -> dict:
+    """Host-side budget split of one unit (cask_plan)."""
+    out = _Plan()
+    cp = p.c()
+    rc = load().cask_plan(C.byref(cp), P, N, C.byref(out))
+    if rc:
+        raise CaskError("cask_plan", rc)
+    return {k: getattr(out, k) for k, _ in _Plan._fields_}
+
+
+def _dptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensor expected"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Batch:
+    """Device pointers of one batch plus the host mirrors of its offsets."""
+
+    def __init__(self, p: Params, row_off, prefix_len, K, V=None, Q=None):
+        self.params = p
+        host_ro = row_off.cpu() if isinstance(row_off, torch.Tensor) else torch.as_tensor(np.asarray(row_off))
+        host_pl = prefix_len.cpu() if isinstance(prefix_len, torch.Tensor) else torch.as_tensor(np.asarray(prefix_len))
+        self.row_off_host = host_ro.to(torch.int64).contiguous()
+        self.prefix_len_host = host_pl.to(torch.int32).contiguous()
+        dev = K.device
+        self.row_off = (row_off if isinstance(row_off, torch.Tensor) and row_off.is_cuda and row_off.dtype == torch.int64
+                        else self.row_off_host.to(dev)).contiguous()
+        self.prefix_len = (prefix_len if isinstance(prefix_len, torch.Tensor) and prefix_len.is_cuda and prefix_len.dtype == torch.int32
+                           else self.prefix_len_host.to(dev)).contiguous()
+        self.n_units = int(self.row_off_host.numel() - 1)
+        self.total_rows = int(self.row_off_host[-1]) if self.n_units > 0 else 0
+        lens = self.row_off_host[1:] - self.row_off_host[:-1]
+        self.max_unit_len = int(lens.max()) if self.n_units > 0 else 0
+        want = torch.float32 if p.dtype == F32 else torch.bfloat16
+        for t in (K, V, Q):
+            if t is not None:
+                assert t.dtype == want, (t.dtype, want)
+        self.K, self.V, self.Q = K, V, Q
+        self.device = dev
+        self._ws = None
+
+    def c(self) -> _Batch:
+        return _Batch(self.n_units, self.row_off.data_ptr(), self.prefix_len.data_ptr(),
+                      self.row_off_host.data_ptr(), self.prefix_len_host.data_ptr(),
+                      self.K.data_ptr(), self.V.data_ptr() if self.V is not None else None,
+                      self.Q.data_ptr() if self.Q is not None else None)
+
+    def workspace(self) -> torch.Tensor:
+        if self._ws is None:
+            n = workspace_bytes(self.params, self.n_units, self.total_rows, self.max_unit_len)
+            self._ws = torch.empty(max(n, 256), dtype=torch.uint8, device=self.device)
+        return self._ws
+
+
+def workspace_bytes(p: Params, n_units: int, total_rows: int, max_unit_len: int) -> int:
+    cp = p.c()
+    return int(load().cask_workspace_bytes(C.byref(cp), n_units, total_rows, max_unit_len))
+
+
+def score(b: Batch, scores: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if scores is None:
+        scores = torch.empty(b.total_rows, dtype=torch.float32, device=b.device)
+    cp, cb, ws = b.params.c(), b.c(), b.workspace()
+    rc = load().cask_score(C.byref(cp), C.byref(cb), _dptr(scores), _dptr(ws), ws.numel(), _stream())
+    if rc:
+        raise CaskError("cask_score", rc)
+    return scores
+
+
+def prefix_evict(b: Batch, scores: torch.Tensor, role: Optional[torch.Tensor] = None):
+    if role is None:
+        role = torch.full((b.total_rows,), 255, dtype=torch.uint8, device=b.device)
+    status = torch.zeros(b.n_units, dtype=torch.int32, device=b.device)
+    cp, cb, ws = b.params.c(), b.c(), b.workspace()
+    rc = load().cask_prefix_evict(C.byref(cp), C.byref(cb), _dptr(scores), _dptr(role),
+                                  _dptr(status), _dptr(ws), ws.numel(), _stream())
+    if rc:
+        raise CaskError("cask_prefix_evict", rc)
+    return role, status
+
+
+def partition(b: Batch, scores: torch.Tensor, role: Optional[torch.Tensor] = None):
+    if role is None:
+        role = torch.full((b.total_rows,), 255, dtype=torch.uint8, device=b.device)
+    status = torch.zeros(b.n_units, dtype=torch.int32, device=b.device)
+    cp, cb, ws = b.params.c(), b.c(), b.workspace()
+    rc = load().cask_partition(C.byref(cp), C.byref(cb), _dptr(scores), _dptr(role),
+                               _dptr(status), _dptr(ws), ws.numel(), _stream())
+    if rc:
+        raise CaskError("cask_partition", rc)
+    return role, status
+
+
+def consolidate(b: Batch, scores: torch.Tensor, role: torch.Tensor) -> torch.Tensor:
+    assign = torch.full((b.total_rows,), -2, dtype=torch.int32, device=b.device)
+    cp, cb, ws = b.params.c(), b.c(), b.workspace()
+    rc = load().cask_consolidate(C.byref(cp), C.byref(cb), _dptr(scores), _dptr(role),
+                                 _dptr(assign), _dptr(ws), ws.numel(), _stream())
+    if rc:
+        raise CaskError("cask_consolidate", rc)
+    return assign
+
+
+class Outputs:
+    """Pre-allocated output tensors of cask_compress for one batch shape."""
+
+    def __init__(self, b: Batch, want_mass: bool = True, want_assign: bool = True,
+                 want_scores: bool = True):
+        p, dev = b.params, b.device
+        dt = torch.float32 if p.dtype == F32 else torch.bfloat16
+        self.K_out = torch.zeros(b.n_units, p.budget, p.head_dim, dtype=dt, device=dev)
+        self.V_out = torch.zeros(b.n_units, p.budget, p.head_dim, dtype=dt, device=dev)
+        self.out_len = torch.zeros(b.n_units, dtype=torch.int32, device=dev)
+        self.out_src = torch.full((b.n_units, p.budget), -1, dtype=torch.int32, device=dev)
+        self.out_mass = torch.zeros(b.n_units, p.budget, dtype=torch.float32, device=dev) if want_mass else None
+        self.assign = torch.full((b.total_rows,), -2, dtype=torch.int32, device=dev) if want_assign else None
+        self.scores = torch.zeros(b.total_rows, dtype=torch.float32, device=dev) if want_scores else None
+        self.status = torch.zeros(b.n_units, dtype=torch.int32, device=dev)
+
+
+def compress(b: Batch, out: Optional[Outputs] = None, scores: Optional[torch.Tensor] = None) -> Outputs:
+    """One compression event.  `scores` given => used as input and scoring is skipped."""
+    if out is None:
+        out = Outputs(b)
+    given = scores is not None
+    if given:
+        out.scores = scores
+    cp, cb, ws = b.params.c(1 if given else 0), b.c(), b.workspace()
+    rc = load().cask_compress(C.byref(cp), C.byref(cb), _dptr(out.K_out), _dptr(out.V_out),
+                              _dptr(out.out_len), _dptr(out.out_src), _dptr(out.out_mass),
+                              _dptr(out.assign), _dptr(out.scores), _dptr(out.status), _dptr(ws),
+                              ws.numel(), _stream())
+    if rc:
+        raise CaskError("cask_compress", rc)
+    return out

@@ -1,0 +1,269 @@
+// C-ABI layer: argument checks on the host, workspace carving, and the launch sequence of
+// one compression event (two-stage compression, Section 2.2 of the paper):
+//   score -> select (stage-1 prefix eviction + stage-2 core/seed/donor split) -> index roles
+//   -> similarity -> gather merged donors -> emit (copy kept rows, fold representatives).
+// Nothing here allocates or synchronises; everything is enqueued on the caller's stream.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "cask_common.h"
+
+namespace cask {
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, int max_unit_len) {
+  Workspace w;
+  std::memset(&w, 0, sizeof(w));
+  int split_len = 2048;
+  if (const char* e = std::getenv("CASK_SPLIT_LEN")) {
+    const int v = std::atoi(e);
+    if (v >= 128) split_len = v / 128 * 128;
+  }
+  int n_splits = (max_unit_len + split_len - 1) / split_len;
+  if (n_splits < 1) n_splits = 1;
+  if (n_splits > 32) {
+    n_splits = 32;
+    split_len = (int)align_up((size_t)(max_unit_len + n_splits - 1) / n_splits, 128);
+    n_splits = (max_unit_len + split_len - 1) / split_len;
+  }
+  w.n_splits = n_splits;
+  w.split_len = split_len;
+  w.mq_pad = (int)align_up((size_t)kp.Mq, 64);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off = align_up(off + bytes, 256);
+    return at;
+  };
+  const size_t rows = (size_t)total_rows, units = (size_t)n_units;
+  w.rowstat = take(units * n_splits * w.mq_pad * sizeof(float2));
+  w.scores = take(rows * sizeof(float));
+  w.role = take(rows);
+  w.slot_of = take(rows * sizeof(int32_t));
+  w.assign_ord = take(rows * sizeof(int32_t));
+  w.merged_row = take(rows * sizeof(int32_t));
+  w.merged_ord = take(rows * sizeof(int32_t));
+  w.seed_rows = take(units * kp.B * sizeof(int32_t));
+  w.ord_of_slot = take(units * kp.B * sizeof(int32_t));
+  w.n_merged = take(units * sizeof(int32_t));
+  w.n_seeds = take(units * sizeof(int32_t));
+  w.total = off;
+  return w;
+}
+
+static int resolve_params(const cask_params* p, KParams* kp, bool need_budget) {
+  if (!p) return CASK_EINVAL;
+  if (p->dtype != CASK_F32 && p->dtype != CASK_BF16) return CASK_EINVAL;
+  if (p->head_dim != 64 && p->head_dim != 128) return CASK_EINVAL;
+  if (p->q_per_kv < 1 || p->window < 1) return CASK_EINVAL;
+  if ((int64_t)p->q_per_kv * p->window > (1 << 20)) return CASK_EINVAL;
+  const int R = p->recent < 0 ? p->window : p->recent;
+  if (need_budget && (p->budget < R + 1 || p->budget > (1 << 24))) return CASK_EINVAL;
+  if (!(p->sim_threshold == p->sim_threshold)) return CASK_EINVAL;  // NaN
+  kp->dtype = p->dtype;
+  kp->d = p->head_dim;
+  kp->G = p->q_per_kv;
+  kp->W = p->window;
+  kp->R = R;
+  kp->B = p->budget > 0 ? p->budget : 1;
+  kp->core = p->core;
+  kp->prefix_budget = p->prefix_budget;
+  kp->tau = p->sim_threshold;
+  const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
+  kp->scale_log2 = (float)(scale * 1.4426950408889634);
+  kp->causal = p->causal ? 1 : 0;
+  kp->Mq = p->q_per_kv * p->window;
+  return CASK_OK;
+}
+
+static int resolve_batch(const KParams& kp, const cask_batch* b, Batch* out, bool need_q, bool need_v) {
+  if (!b || b->n_units < 0) return CASK_EINVAL;
+  out->n_units = b->n_units;
+  out->max_unit_len = 0;
+  out->total_rows = 0;
+  if (b->n_units == 0) return CASK_OK;
+  if (!b->row_off || !b->prefix_len || !b->row_off_host || !b->prefix_len_host || !b->K) return CASK_EINVAL;
+  if (need_q && !b->Q) return CASK_EINVAL;
+  if (need_v && !b->V) return CASK_EINVAL;
+  if (b->row_off_host[0] != 0) return CASK_EINVAL;
+  for (int u = 0; u < b->n_units; ++u) {
+    const int64_t n = b->row_off_host[u + 1] - b->row_off_host[u];
+    if (n < kp.W || n > 0x7fffffffLL) return CASK_EINVAL;
+    const int32_t P = b->prefix_len_host[u];
+    if (P < 0 || P > n) return CASK_EINVAL;
+    if ((int)n > out->max_unit_len) out->max_unit_len = (int)n;
+  }
+  out->total_rows = b->row_off_host[b->n_units];
+  out->row_off = b->row_off;
+  out->prefix_len = b->prefix_len;
+  out->K = b->K;
+  out->V = b->V;
+  out->Q = b->Q;
+  return CASK_OK;
+}
+
+static int dev_rc(hipError_t e) { return e == hipSuccess ? CASK_OK : CASK_EDEVICE; }
+
+}  // namespace cask
+
+using namespace cask;
+
+extern "C" {
+
+const char* cask_strerror(int code) {
+  switch (code) {
+    case CASK_OK: return "ok";
+    case CASK_EINVAL: return "invalid argument";
+    case CASK_ENOMEM: return "workspace too small";
+    case CASK_EDEVICE: return "HIP error";
+    default: return "unknown";
+  }
+}
+
+int cask_plan(const cask_params* params, int32_t P, int32_t N, cask_plan_t* out) {
+  KParams kp;
+  if (!out || resolve_params(params, &kp, true) != CASK_OK) return CASK_EINVAL;
+  if (N < 0 || P < 0 || P > N) return CASK_EINVAL;
+  const UnitPlan pl = make_plan(kp, P, N);
+  out->r_eff = pl.r_eff;
+  out->p_keep = pl.p_keep;
+  out->slots = pl.slots;
+  out->core = pl.core;
+  out->seeds = pl.seeds;
+  out->status = pl.status;
+  return CASK_OK;
+}
+
+size_t cask_workspace_bytes(const cask_params* params, int32_t n_units, int64_t total_rows,
+                            int32_t max_unit_len) {
+  KParams kp;
+  if (resolve_params(params, &kp, false) != CASK_OK || n_units < 0 || total_rows < 0 || max_unit_len < 0)
+    return 0;
+  return layout_workspace(kp, n_units, total_rows, max_unit_len).total + 256;
+}
+
+int cask_score(const cask_params* params, const cask_batch* batch, float* scores, void* ws,
+               size_t ws_bytes, void* hip_stream) {
+  KParams kp;
+  Batch b;
+  int rc = resolve_params(params, &kp, false);
+  if (rc) return rc;
+  rc = resolve_batch(kp, batch, &b, true, false);
+  if (rc) return rc;
+  if (b.n_units == 0) return CASK_OK;
+  if (!scores || !ws) return CASK_EINVAL;
+  const Workspace wl = layout_workspace(kp, b.n_units, b.total_rows, b.max_unit_len);
+  if (ws_bytes < wl.total) return CASK_ENOMEM;
+  return dev_rc(launch_score(kp, b, wl, static_cast<char*>(ws), scores, static_cast<hipStream_t>(hip_stream)));
+}
+
+int cask_prefix_evict(const cask_params* params, const cask_batch* batch, const float* scores,
+                      uint8_t* role, int32_t* status, void* ws, size_t ws_bytes,
+                      void* hip_stream) {
+  (void)ws;
+  (void)ws_bytes;
+  KParams kp;
+  Batch b;
+  int rc = resolve_params(params, &kp, true);
+  if (rc) return rc;
+  rc = resolve_batch(kp, batch, &b, false, false);
+  if (rc) return rc;
+  if (b.n_units == 0) return CASK_OK;
+  if (!scores || !role) return CASK_EINVAL;
+  return dev_rc(launch_select(kp, b, scores, role, status, true, false, static_cast<hipStream_t>(hip_stream)));
+}
+
+int cask_partition(const cask_params* params, const cask_batch* batch, const float* scores,
+                   uint8_t* role, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream) {
+  (void)ws;
+  (void)ws_bytes;
+  KParams kp;
+  Batch b;
+  int rc = resolve_params(params, &kp, true);
+  if (rc) return rc;
+  rc = resolve_batch(kp, batch, &b, false, false);
+  if (rc) return rc;
+  if (b.n_units == 0) return CASK_OK;
+  if (!scores || !role) return CASK_EINVAL;
+  return dev_rc(launch_select(kp, b, scores, role, status, false, true, static_cast<hipStream_t>(hip_stream)));
+}
+
+int cask_consolidate(const cask_params* params, const cask_batch* batch, const float* scores,
+                     const uint8_t* role, int32_t* assign, void* ws, size_t ws_bytes,
+                     void* hip_stream) {
+  (void)scores;
+  KParams kp;
+  Batch b;
+  int rc = resolve_params(params, &kp, true);
+  if (rc) return rc;
+  rc = resolve_batch(kp, batch, &b, false, false);
+  if (rc) return rc;
+  if (b.n_units == 0) return CASK_OK;
+  if (!role || !assign || !ws) return CASK_EINVAL;
+  const Workspace wl = layout_workspace(kp, b.n_units, b.total_rows, b.max_unit_len);
+  if (ws_bytes < wl.total) return CASK_ENOMEM;
+  char* w = static_cast<char*>(ws);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int32_t* seed_rows = reinterpret_cast<int32_t*>(w + wl.seed_rows);
+  int32_t* n_seeds = reinterpret_cast<int32_t*>(w + wl.n_seeds);
+  int32_t* assign_ord = reinterpret_cast<int32_t*>(w + wl.assign_ord);
+  hipError_t e = launch_index_roles(kp, b, role, nullptr, nullptr, nullptr, seed_rows, nullptr, n_seeds, st);
+  if (e != hipSuccess) return CASK_EDEVICE;
+  e = launch_similarity(kp, b, role, seed_rows, n_seeds, assign_ord, st);
+  if (e != hipSuccess) return CASK_EDEVICE;
+  e = launch_gather_merged(kp, b, role, assign_ord, nullptr, seed_rows,
+                           reinterpret_cast<int32_t*>(w + wl.merged_row),
+                           reinterpret_cast<int32_t*>(w + wl.merged_ord), nullptr, assign, 2,
+                           nullptr, st);
+  return dev_rc(e);
+}
+
+int cask_compress(const cask_params* params, const cask_batch* batch, void* K_out, void* V_out,
+                  int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
+                  float* scores, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream) {
+  KParams kp;
+  Batch b;
+  int rc = resolve_params(params, &kp, true);
+  if (rc) return rc;
+  const bool given = params->scores_given != 0;
+  rc = resolve_batch(kp, batch, &b, !given, true);
+  if (rc) return rc;
+  if (b.n_units == 0) return CASK_OK;
+  if (!K_out || !V_out || !out_len || !out_src || !status || !ws) return CASK_EINVAL;
+  if (given && !scores) return CASK_EINVAL;
+  const Workspace wl = layout_workspace(kp, b.n_units, b.total_rows, b.max_unit_len);
+  if (ws_bytes < wl.total) return CASK_ENOMEM;
+  char* w = static_cast<char*>(ws);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  float* s = scores ? scores : reinterpret_cast<float*>(w + wl.scores);
+  uint8_t* role = reinterpret_cast<uint8_t*>(w + wl.role);
+  int32_t* slot_of = reinterpret_cast<int32_t*>(w + wl.slot_of);
+  int32_t* assign_ord = reinterpret_cast<int32_t*>(w + wl.assign_ord);
+  int32_t* merged_row = reinterpret_cast<int32_t*>(w + wl.merged_row);
+  int32_t* merged_ord = reinterpret_cast<int32_t*>(w + wl.merged_ord);
+  int32_t* seed_rows = reinterpret_cast<int32_t*>(w + wl.seed_rows);
+  int32_t* ord_of_slot = reinterpret_cast<int32_t*>(w + wl.ord_of_slot);
+  int32_t* n_merged = reinterpret_cast<int32_t*>(w + wl.n_merged);
+  int32_t* n_seeds = reinterpret_cast<int32_t*>(w + wl.n_seeds);
+  hipError_t e;
+  if (!given) {
+    e = launch_score(kp, b, wl, w, s, st);
+    if (e != hipSuccess) return CASK_EDEVICE;
+  }
+  e = launch_select(kp, b, s, role, status, true, true, st);
+  if (e != hipSuccess) return CASK_EDEVICE;
+  e = launch_index_roles(kp, b, role, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds, st);
+  if (e != hipSuccess) return CASK_EDEVICE;
+  e = launch_similarity(kp, b, role, seed_rows, n_seeds, assign_ord, st);
+  if (e != hipSuccess) return CASK_EDEVICE;
+  e = launch_gather_merged(kp, b, role, assign_ord, slot_of, seed_rows, merged_row, merged_ord,
+                           n_merged, assign, assign ? 1 : 0, status, st);
+  if (e != hipSuccess) return CASK_EDEVICE;
+  e = launch_emit(kp, b, s, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out,
+                  V_out, out_mass, st);
+  return dev_rc(e);
+}
+
+}  // extern "C"

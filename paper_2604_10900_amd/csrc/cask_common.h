@@ -1,0 +1,187 @@
+// Shared declarations of the gfx950 CASK kernels: kernel-side parameter block, the budget
+// split (two-stage compression, Section 2.2 of the paper), workspace layout and the
+// launchers each translation unit exports to the C-ABI layer.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cask.h"
+
+namespace cask {
+
+constexpr int kWave = 64;
+
+// Kernel-side copy of cask_params with defaults resolved.
+struct KParams {
+  int dtype;
+  int d;
+  int G;
+  int W;
+  int R;             // resolved recent
+  int B;
+  int core;          // < 0 => default share
+  int prefix_budget; // < 0 => default
+  float tau;
+  float scale_log2;  // softmax scale * log2(e): logits are handled in base-2 units
+  int causal;
+  int Mq;            // W * G window rows
+};
+
+struct UnitPlan {
+  int r_eff, p_keep, slots, core, seeds, status;
+};
+
+// Budget split of one unit.  Stage 1 evicts in the prefix only to leave room for the decode
+// stage; the decode trace outside the always-kept recent tail gets the remaining slots, split
+// into a protected core and representative seeds (Sections 2.1-2.3); a unit whose prefix
+// leaves no slot is flagged prefix_budget_exhausted (Section 5.2).
+__host__ __device__ inline UnitPlan make_plan(int R, int B, int core_param, int prefix_budget,
+                                              int P, int N) {
+  UnitPlan pl;
+  const int D = N - P;
+  const int r_eff = R < D ? R : D;
+  const int dnr = D - r_eff;
+  pl.r_eff = r_eff;
+  if (N <= B) {
+    pl.p_keep = P;
+    pl.slots = dnr;
+    pl.core = dnr;
+    pl.seeds = 0;
+    pl.status = CASK_ST_IDENTITY;
+    return pl;
+  }
+  int bp = prefix_budget;
+  if (bp < 0) {
+    const int quarter = B / 4, floor64 = (P + 63) / 64;
+    bp = quarter > floor64 ? quarter : floor64;
+  }
+  const int room = B - r_eff;
+  const int unused = room - dnr;
+  const int want = bp > unused ? bp : unused;
+  int p_keep = P;
+  if (room < p_keep) p_keep = room;
+  if (want < p_keep) p_keep = want;
+  pl.p_keep = p_keep;
+  pl.slots = room - p_keep;
+  if (dnr <= pl.slots) {
+    pl.core = dnr;
+    pl.seeds = 0;
+    pl.status = CASK_ST_MERGE_INACTIVE;
+  } else if (pl.slots == 0) {
+    pl.core = 0;
+    pl.seeds = 0;
+    pl.status = CASK_ST_PREFIX_BUDGET_EXHAUSTED;
+  } else {
+    int c = core_param >= 0 ? (core_param < pl.slots ? core_param : pl.slots)
+                            : (int)((4LL * pl.slots) / 5);
+    pl.core = c;
+    pl.seeds = pl.slots - c;
+    pl.status = pl.seeds == 0 ? CASK_ST_MERGE_INACTIVE : CASK_ST_ACTIVE;
+  }
+  return pl;
+}
+
+__host__ __device__ inline UnitPlan make_plan(const KParams& kp, int P, int N) {
+  return make_plan(kp.R, kp.B, kp.core, kp.prefix_budget, P, N);
+}
+
+// ---------------------------------------------------------------- element helpers
+
+__device__ inline float bf16_bits_to_float(uint16_t h) {
+  return __uint_as_float(((uint32_t)h) << 16);
+}
+
+// round-to-nearest-even float -> bf16 bit pattern
+__device__ inline uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);  // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+  __device__ static float load(const float* p) { return *p; }
+  __device__ static void store(float* p, float x) { *p = x; }
+};
+template <>
+struct Elem<uint16_t> {
+  __device__ static float load(const uint16_t* p) { return bf16_bits_to_float(*p); }
+  __device__ static void store(uint16_t* p, float x) { *p = float_to_bf16_bits(x); }
+};
+
+// Order-preserving 32-bit key of a float score: larger score <=> larger key; -0 == +0.
+__device__ inline uint32_t score_key(float s) {
+  uint32_t u = __float_as_uint(s);
+  if ((u << 1) == 0u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// ---------------------------------------------------------------- workspace layout
+
+struct Workspace {
+  // all offsets in bytes from the workspace base, 256-byte aligned
+  size_t rowstat;    // float2 [n_units][n_splits][mq_pad]: per-split running (max, sum) per window row
+  size_t scores;     // float  [total_rows] (used when the caller passes no score buffer)
+  size_t role;       // uint8  [total_rows]
+  size_t slot_of;    // int32  [total_rows] output slot of kept rows, -1 otherwise
+  size_t assign_ord; // int32  [total_rows] seed ordinal a donor folds into, -1 otherwise
+  size_t merged_row; // int32  [total_rows] per unit: rows of merged donors, ascending
+  size_t merged_ord; // int32  [total_rows] their seed ordinals
+  size_t seed_rows;  // int32  [n_units][B] unit-local rows of the seeds, ascending
+  size_t ord_of_slot;// int32  [n_units][B] seed ordinal of an output slot, -1 if not a seed
+  size_t n_merged;   // int32  [n_units]
+  size_t n_seeds;    // int32  [n_units]
+  size_t total;
+  int n_splits;
+  int split_len;     // keys per split (multiple of the key tile)
+  int mq_pad;
+};
+
+Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, int max_unit_len);
+
+// ---------------------------------------------------------------- launchers
+
+struct Batch {
+  int n_units;
+  const int64_t* row_off;
+  const int32_t* prefix_len;
+  const void* K;
+  const void* V;
+  const void* Q;
+  int max_unit_len;
+  int64_t total_rows;
+};
+
+hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, char* ws,
+                        float* scores, hipStream_t st);
+hipError_t launch_select(const KParams& kp, const Batch& b, const float* scores, uint8_t* role,
+                         int32_t* status, bool do_prefix, bool do_decode, hipStream_t st);
+hipError_t launch_index_roles(const KParams& kp, const Batch& b, const uint8_t* role,
+                              int32_t* slot_of, int32_t* out_src, int32_t* out_len,
+                              int32_t* seed_rows, int32_t* ord_of_slot, int32_t* n_seeds,
+                              hipStream_t st);
+hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* role,
+                             const int32_t* seed_rows, const int32_t* n_seeds,
+                             int32_t* assign_ord, hipStream_t st);
+hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t* role,
+                                const int32_t* assign_ord, const int32_t* slot_of,
+                                const int32_t* seed_rows, int32_t* merged_row, int32_t* merged_ord,
+                                int32_t* n_merged, int32_t* assign_out, int assign_mode,
+                                int32_t* status, hipStream_t st);
+hipError_t launch_emit(const KParams& kp, const Batch& b, const float* scores,
+                       const int32_t* out_src, const int32_t* out_len, const int32_t* ord_of_slot,
+                       const int32_t* merged_row, const int32_t* merged_ord,
+                       const int32_t* n_merged, void* K_out, void* V_out, float* out_mass,
+                       hipStream_t st);
+
+}  // namespace cask

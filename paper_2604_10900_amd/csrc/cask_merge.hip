@@ -1,0 +1,447 @@
+// Selective consolidation of the mergeable scratch (Sections 2.1, 2.4, 2.5 of the paper):
+//   similarity   every donor against every seed of its unit by key cosine; best seed kept
+//                when the cosine reaches tau (bf16 d=128: MFMA contraction seeds x donors^T,
+//                each lane owns one donor and scans its seeds in ascending order);
+//   gather       ordered list of the donors that merge (ascending row), per unit;
+//   emit         one wavefront per output row: kept tokens are copied bit for bit, a seed
+//                with donors becomes the weighted fold m = sum a_i, k~ = sum a_i k_i / m,
+//                v~ = sum a_i v_i / m with a_i the token's score, accumulated in fp32 in
+//                ascending row order (fixed order: reruns are bitwise identical).
+#include "cask_common.h"
+
+namespace cask {
+
+namespace {
+
+constexpr float kNegInf = -__builtin_inff();
+
+__device__ inline bool better(float sim, int ord, float best, int best_ord) {
+  return sim > best || (sim == best && ord < best_ord);
+}
+
+// ------------------------------------------------------------------ similarity, MFMA path
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+constexpr int kD = 128;
+constexpr int kPitch = 272;
+constexpr int kSeedStage = 64;   // seeds per LDS stage
+constexpr int kDonorTile = 256;  // donor rows per workgroup (4 waves x 64)
+
+__device__ inline float sumsq_bf16x8(const uint4& v) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float lo = __uint_as_float(w[i] << 16);
+    const float hi = __uint_as_float(w[i] & 0xFFFF0000u);
+    s = __builtin_fmaf(lo, lo, s);
+    s = __builtin_fmaf(hi, hi, s);
+  }
+  return s;
+}
+
+__global__ __launch_bounds__(256) void similarity_mfma_kernel(
+    KParams kp, int n_units, int tiles_per_unit, const int64_t* __restrict__ row_off,
+    const int32_t* __restrict__ prefix_len, const uint16_t* __restrict__ K,
+    const uint8_t* __restrict__ role, const int32_t* __restrict__ seed_rows,
+    const int32_t* __restrict__ n_seeds, int32_t* __restrict__ assign_ord) {
+  __shared__ __attribute__((aligned(16))) unsigned char stage[kSeedStage * kPitch];
+  __shared__ float seed_inv[kSeedStage];
+  const int bid = blockIdx.x;
+  const int xcd = bid & 7, kk = bid >> 3;
+  const int u = (kk / tiles_per_unit) * 8 + xcd;
+  const int tile = kk % tiles_per_unit;
+  if (u >= n_units) return;
+  const int64_t row0 = row_off[u];
+  const int N = (int)(row_off[u + 1] - row0);
+  const int P = prefix_len[u];
+  const UnitPlan pl = make_plan(kp, P, N);
+  const int hi = N - pl.r_eff;
+  const int base = P + tile * kDonorTile;
+  if (base >= hi) return;
+  const int M = n_seeds[u];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int c32 = lane & 31, h = lane >> 5;
+  const uint16_t* Ku = K + (size_t)row0 * kD;
+  const uint8_t* ro = role + row0;
+  const int32_t* srow = seed_rows + (size_t)u * kp.B;
+
+  // resident donors: lane (c32, h) holds row c32 of each 32-row tile, k-chunk h
+  bf16x8 bres[2][8];
+  int drow[2];
+  float dinv[2];
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct) {
+    const int r = base + wv * 64 + ct * 32 + c32;
+    drow[ct] = r;
+    const bool ok = r < hi;
+    const uint4* src = reinterpret_cast<const uint4*>(Ku + (size_t)(ok ? r : P) * kD) + h;
+    float ss = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      uint4 v = ok ? src[ks * 2] : make_uint4(0, 0, 0, 0);
+      ss += sumsq_bf16x8(v);
+      bres[ct][ks] = *reinterpret_cast<bf16x8*>(&v);
+    }
+    ss += __shfl_xor(ss, 32, 64);
+    dinv[ct] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+  }
+  float best[2] = {kNegInf, kNegInf};
+  int best_ord[2] = {-1, -1};
+
+  for (int s0 = 0; s0 < M; s0 += kSeedStage) {
+    __syncthreads();  // previous stage fully consumed
+    // load up to 64 seed rows: 16 threads per row, 4 rows per pass per wave
+#pragma unroll
+    for (int i = 0; i < kSeedStage * 16 / 256; ++i) {
+      const int q = tid + 256 * i;
+      const int sr = q >> 4;
+      const int ord = s0 + sr;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (ord < M) v = reinterpret_cast<const uint4*>(Ku + (size_t)srow[ord] * kD)[q & 15];
+      *reinterpret_cast<uint4*>(stage + sr * kPitch + (q & 15) * 16) = v;
+      float ss = sumsq_bf16x8(v);
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+      if ((q & 15) == 0) seed_inv[sr] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      if (s0 + rt * 32 >= M) continue;
+      bf16x8 a[8];
+      const unsigned char* ap = stage + (rt * 32 + c32) * kPitch + h * 16;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 32);
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) {
+        f32x16 acc = {0};
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct][ks], acc, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {  // ascending seed ordinal within the lane
+          const int sr = rt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+          const int ord = s0 + sr;
+          const float sim = (acc[r] * seed_inv[sr]) * dinv[ct];
+          if (ord < M && sim > best[ct]) {
+            best[ct] = sim;
+            best_ord[ct] = ord;
+          }
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct) {
+    const float ob = __shfl_xor(best[ct], 32, 64);
+    const int oo = __shfl_xor(best_ord[ct], 32, 64);
+    if (oo >= 0 && (best_ord[ct] < 0 || better(ob, oo, best[ct], best_ord[ct]))) {
+      best[ct] = ob;
+      best_ord[ct] = oo;
+    }
+    if (h == 0 && drow[ct] < hi) {
+      const bool donor = ro[drow[ct]] == CASK_ROLE_DONOR;
+      assign_ord[row0 + drow[ct]] = (donor && best_ord[ct] >= 0 && best[ct] >= kp.tau) ? best_ord[ct] : -1;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ similarity, plain path
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void similarity_fma_kernel(
+    KParams kp, int n_units, int tiles_per_unit, const int64_t* __restrict__ row_off,
+    const int32_t* __restrict__ prefix_len, const T* __restrict__ K,
+    const uint8_t* __restrict__ role, const int32_t* __restrict__ seed_rows,
+    const int32_t* __restrict__ n_seeds, int32_t* __restrict__ assign_ord) {
+  constexpr int SEEDS = 32;
+  __shared__ float sk[SEEDS][D + 1];
+  __shared__ float sinv[SEEDS];
+  const int bid = blockIdx.x;
+  const int u = bid / tiles_per_unit, tile = bid % tiles_per_unit;
+  if (u >= n_units) return;
+  const int64_t row0 = row_off[u];
+  const int N = (int)(row_off[u + 1] - row0);
+  const int P = prefix_len[u];
+  const UnitPlan pl = make_plan(kp, P, N);
+  const int hi = N - pl.r_eff;
+  const int base = P + tile * 256;
+  if (base >= hi) return;
+  const int M = n_seeds[u];
+  const int tid = threadIdx.x;
+  const int i = base + tid;
+  const bool ok = i < hi;
+  const T* Ku = K + (size_t)row0 * D;
+  const int32_t* srow = seed_rows + (size_t)u * kp.B;
+  float k[D];
+  float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < D; ++c) {
+    k[c] = Elem<T>::load(Ku + (size_t)(ok ? i : P) * D + c);
+    ss = __builtin_fmaf(k[c], k[c], ss);
+  }
+  const float dinv = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+  float best = kNegInf;
+  int best_ord = -1;
+  for (int s0 = 0; s0 < M; s0 += SEEDS) {
+    __syncthreads();
+    for (int q = tid; q < SEEDS * D; q += 256) {
+      const int sr = q / D, c = q % D;
+      sk[sr][c] = (s0 + sr < M) ? Elem<T>::load(Ku + (size_t)srow[s0 + sr] * D + c) : 0.f;
+    }
+    __syncthreads();
+    if (tid < SEEDS) {
+      float t = 0.f;
+      for (int c = 0; c < D; ++c) t = __builtin_fmaf(sk[tid][c], sk[tid][c], t);
+      sinv[tid] = t > 0.f ? 1.0f / sqrtf(t) : 0.f;
+    }
+    __syncthreads();
+    const int lim = min(SEEDS, M - s0);
+    for (int sr = 0; sr < lim; ++sr) {
+      float dot = 0.f;
+#pragma unroll
+      for (int c = 0; c < D; ++c) dot = __builtin_fmaf(k[c], sk[sr][c], dot);
+      const float sim = (dot * sinv[sr]) * dinv;
+      if (sim > best) {
+        best = sim;
+        best_ord = s0 + sr;
+      }
+    }
+  }
+  if (ok) {
+    const bool donor = role[row0 + i] == CASK_ROLE_DONOR;
+    assign_ord[row0 + i] = (donor && best_ord >= 0 && best >= kp.tau) ? best_ord : -1;
+  }
+}
+
+// ------------------------------------------------------------------ gather merged donors
+
+constexpr int kGatherThreads = 1024;
+
+// assign_mode: 0 none, 1 output slot (whole event), 2 unit-local source row (consolidate API)
+__global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
+    KParams kp, const int64_t* __restrict__ row_off, const int32_t* __restrict__ prefix_len,
+    const uint8_t* __restrict__ role, const int32_t* __restrict__ assign_ord,
+    const int32_t* __restrict__ slot_of, const int32_t* __restrict__ seed_rows,
+    int32_t* __restrict__ merged_row, int32_t* __restrict__ merged_ord,
+    int32_t* __restrict__ n_merged, int32_t* __restrict__ assign_out, int assign_mode,
+    int32_t* __restrict__ status) {
+  __shared__ int wsum[kGatherThreads / 64];
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int64_t row0 = row_off[u];
+  const int N = (int)(row_off[u + 1] - row0);
+  const int P = prefix_len[u];
+  const UnitPlan pl = make_plan(kp, P, N);
+  const int hi = N - pl.r_eff;
+  const int32_t* srow = seed_rows + (size_t)u * kp.B;
+  // rows outside the donor range: kept rows map to themselves, the rest is dropped
+  if (assign_mode != 0) {
+    for (int i = tid; i < N; i += kGatherThreads) {
+      if (i >= P && i < hi) continue;
+      const int r = role[row0 + i];
+      const bool kept = r == CASK_ROLE_PREFIX_KEEP || r == CASK_ROLE_RECENT || r == CASK_ROLE_CORE ||
+                        r == CASK_ROLE_SEED;
+      assign_out[row0 + i] = !kept ? -1 : (assign_mode == 1 ? slot_of[row0 + i] : i);
+    }
+  }
+  int count = 0;
+  for (int base = P; base < hi; base += kGatherThreads) {
+    const int i = base + tid;
+    const bool in = i < hi;
+    const int r = in ? role[row0 + i] : CASK_ROLE_PREFIX_DROP;
+    const int ord = (in && r == CASK_ROLE_DONOR) ? assign_ord[row0 + i] : -1;
+    const int flag = ord >= 0 ? 1 : 0;
+    // ordered block scan of the flags
+    const unsigned long long bal = __ballot(flag);
+    const int in_wave = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wsum[wv] = __popcll(bal);
+    __syncthreads();
+    int before = 0, tot = 0;
+    for (int w = 0; w < kGatherThreads / 64; ++w) {
+      const int x = wsum[w];
+      if (w < wv) before += x;
+      tot += x;
+    }
+    __syncthreads();
+    if (flag) {
+      const int pos = count + before + in_wave;
+      merged_row[row0 + pos] = i;
+      merged_ord[row0 + pos] = ord;
+    }
+    if (in && assign_mode != 0) {
+      int v;
+      if (r == CASK_ROLE_DONOR) {
+        v = ord < 0 ? -1 : (assign_mode == 1 ? slot_of[row0 + srow[ord]] : srow[ord]);
+      } else {
+        const bool kept = r == CASK_ROLE_CORE || r == CASK_ROLE_SEED;
+        v = !kept ? -1 : (assign_mode == 1 ? slot_of[row0 + i] : i);
+      }
+      assign_out[row0 + i] = v;
+    }
+    count += tot;
+  }
+  if (tid == 0) {
+    if (n_merged) n_merged[u] = count;
+    if (status && count == 0 && !(pl.status & (CASK_ST_IDENTITY | CASK_ST_PREFIX_BUDGET_EXHAUSTED)))
+      status[u] = pl.status | CASK_ST_MERGE_INACTIVE;
+  }
+}
+
+// ------------------------------------------------------------------ emit (copy + fold)
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void emit_kernel(
+    KParams kp, int n_units, const int64_t* __restrict__ row_off, const T* __restrict__ K,
+    const T* __restrict__ V, const float* __restrict__ scores, const int32_t* __restrict__ out_src,
+    const int32_t* __restrict__ out_len, const int32_t* __restrict__ ord_of_slot,
+    const int32_t* __restrict__ merged_row, const int32_t* __restrict__ merged_ord,
+    const int32_t* __restrict__ n_merged, T* __restrict__ K_out, T* __restrict__ V_out,
+    float* __restrict__ out_mass) {
+  constexpr int EPL = D / 64;  // elements per lane
+  const int lane = threadIdx.x & 63;
+  const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int B = kp.B;
+  const int u = (int)(wave / B), t = (int)(wave % B);
+  if (u >= n_units || t >= out_len[u]) return;
+  const int64_t row0 = row_off[u];
+  const int src = out_src[(size_t)u * B + t];
+  const int ord = ord_of_slot[(size_t)u * B + t];
+  const T* kr = K + (size_t)(row0 + src) * D + lane * EPL;
+  const T* vr = V + (size_t)(row0 + src) * D + lane * EPL;
+  T* ko = K_out + ((size_t)u * B + t) * D + lane * EPL;
+  T* vo = V_out + ((size_t)u * B + t) * D + lane * EPL;
+  T kraw[EPL], vraw[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    kraw[e] = kr[e];
+    vraw[e] = vr[e];
+  }
+  const float a0 = scores[row0 + src];
+  int members = 1;
+  float mass = a0;
+  float ka[EPL], va[EPL], ku[EPL], vu[EPL];  // weighted and unweighted sums
+  if (ord >= 0) {
+    const int nm = n_merged[u];
+    const int32_t* mr = merged_row + row0;
+    const int32_t* mo = merged_ord + row0;
+    for (int b0 = 0; b0 < nm; b0 += 64) {
+      const int idx = b0 + lane;
+      const int my_ord = idx < nm ? mo[idx] : -1;
+      const int my_row = idx < nm ? mr[idx] : 0;
+      unsigned long long hit = __ballot(my_ord == ord);
+      while (hit) {
+        const int l = __ffsll((long long)hit) - 1;
+        hit &= hit - 1;
+        const int drow = __shfl(my_row, l, 64);
+        if (members == 1) {
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            const float kf = Elem<T>::load(&kraw[e]), vf = Elem<T>::load(&vraw[e]);
+            ka[e] = a0 * kf; va[e] = a0 * vf; ku[e] = kf; vu[e] = vf;
+          }
+        }
+        const float a = scores[row0 + drow];
+        const T* dk = K + (size_t)(row0 + drow) * D + lane * EPL;
+        const T* dv = V + (size_t)(row0 + drow) * D + lane * EPL;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const float kf = Elem<T>::load(dk + e), vf = Elem<T>::load(dv + e);
+          ka[e] = __builtin_fmaf(a, kf, ka[e]);
+          va[e] = __builtin_fmaf(a, vf, va[e]);
+          ku[e] += kf;
+          vu[e] += vf;
+        }
+        mass += a;
+        ++members;
+      }
+    }
+  }
+  if (members == 1) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      ko[e] = kraw[e];
+      vo[e] = vraw[e];
+    }
+  } else {
+    const bool uniform = mass == 0.f;
+    const float denom = uniform ? (float)members : mass;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      Elem<T>::store(ko + e, (uniform ? ku[e] : ka[e]) / denom);
+      Elem<T>::store(vo + e, (uniform ? vu[e] : va[e]) / denom);
+    }
+  }
+  if (out_mass && lane == 0) out_mass[(size_t)u * B + t] = mass;
+}
+
+template <typename T, int D>
+hipError_t launch_emit_t(const KParams& kp, const Batch& b, const float* scores,
+                         const int32_t* out_src, const int32_t* out_len,
+                         const int32_t* ord_of_slot, const int32_t* merged_row,
+                         const int32_t* merged_ord, const int32_t* n_merged, void* K_out,
+                         void* V_out, float* out_mass, hipStream_t st) {
+  const long long waves = (long long)b.n_units * kp.B;
+  const long long blocks = (waves + 3) / 4;
+  emit_kernel<T, D><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(
+      kp, b.n_units, b.row_off, static_cast<const T*>(b.K), static_cast<const T*>(b.V), scores,
+      out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, static_cast<T*>(K_out),
+      static_cast<T*>(V_out), out_mass);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t launch_similarity_fma(const KParams& kp, const Batch& b, const uint8_t* role,
+                                 const int32_t* seed_rows, const int32_t* n_seeds,
+                                 int32_t* assign_ord, hipStream_t st) {
+  const int tiles = (b.max_unit_len + 255) / 256;
+  similarity_fma_kernel<T, D><<<dim3(b.n_units * tiles), dim3(256), 0, st>>>(
+      kp, b.n_units, tiles, b.row_off, b.prefix_len, static_cast<const T*>(b.K), role, seed_rows,
+      n_seeds, assign_ord);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* role,
+                             const int32_t* seed_rows, const int32_t* n_seeds,
+                             int32_t* assign_ord, hipStream_t st) {
+  if (kp.dtype == CASK_BF16 && kp.d == 128) {
+    const int tiles = (b.max_unit_len + kDonorTile - 1) / kDonorTile;
+    const int units8 = (b.n_units + 7) / 8 * 8;
+    similarity_mfma_kernel<<<dim3(units8 * tiles), dim3(256), 0, st>>>(
+        kp, b.n_units, tiles, b.row_off, b.prefix_len, static_cast<const uint16_t*>(b.K), role,
+        seed_rows, n_seeds, assign_ord);
+    return hipGetLastError();
+  }
+  if (kp.dtype == CASK_F32)
+    return kp.d == 64 ? launch_similarity_fma<float, 64>(kp, b, role, seed_rows, n_seeds, assign_ord, st)
+                      : launch_similarity_fma<float, 128>(kp, b, role, seed_rows, n_seeds, assign_ord, st);
+  return launch_similarity_fma<uint16_t, 64>(kp, b, role, seed_rows, n_seeds, assign_ord, st);
+}
+
+hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t* role,
+                                const int32_t* assign_ord, const int32_t* slot_of,
+                                const int32_t* seed_rows, int32_t* merged_row, int32_t* merged_ord,
+                                int32_t* n_merged, int32_t* assign_out, int assign_mode,
+                                int32_t* status, hipStream_t st) {
+  gather_merged_kernel<<<dim3(b.n_units), dim3(kGatherThreads), 0, st>>>(
+      kp, b.row_off, b.prefix_len, role, assign_ord, slot_of, seed_rows, merged_row, merged_ord,
+      n_merged, assign_out, assign_mode, status);
+  return hipGetLastError();
+}
+
+hipError_t launch_emit(const KParams& kp, const Batch& b, const float* scores,
+                       const int32_t* out_src, const int32_t* out_len, const int32_t* ord_of_slot,
+                       const int32_t* merged_row, const int32_t* merged_ord,
+                       const int32_t* n_merged, void* K_out, void* V_out, float* out_mass,
+                       hipStream_t st) {
+  if (kp.dtype == CASK_F32)
+    return kp.d == 64 ? launch_emit_t<float, 64>(kp, b, scores, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out, V_out, out_mass, st)
+                      : launch_emit_t<float, 128>(kp, b, scores, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out, V_out, out_mass, st);
+  return kp.d == 64 ? launch_emit_t<uint16_t, 64>(kp, b, scores, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out, V_out, out_mass, st)
+                    : launch_emit_t<uint16_t, 128>(kp, b, scores, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out, V_out, out_mass, st);
+}
+
+}  // namespace cask

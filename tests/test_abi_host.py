@@ -1,0 +1,112 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol that include/cask.h
+declares, and its host-side logic (budget split, workspace sizing, argument validation)
+behaves as documented.  No compute call is made here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def cask():
+    import paper_2604_10900_amd as cask
+    if not os.path.exists(cask.binding.LIB_PATH):
+        from paper_2604_10900_amd.build import build_lib
+        build_lib()
+    cask.load()
+    return cask
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "cask.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cask_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(cask):
+    names = declared_functions()
+    assert {"cask_score", "cask_partition", "cask_consolidate", "cask_prefix_evict",
+            "cask_compress", "cask_plan", "cask_workspace_bytes"} <= set(names)
+    lib = cask.load()
+    for n in names:
+        assert getattr(lib, n) is not None, n
+    assert sorted(cask.binding.EXPORTS) == names
+
+
+def test_plan_matches_golden_table(cask):
+    rows = 0
+    with open(os.path.join(GOLDEN, "plan_table.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            lhs, rhs = line.split("|")
+            P, D, B, R, core = (int(x) for x in lhs.split())
+            r_eff, p_keep, slots, c, m, status = (int(x) for x in rhs.split())
+            p = cask.Params(window=min(128, P + D), recent=R, budget=B, core=core)
+            assert cask.plan(p, P, P + D) == dict(r_eff=r_eff, p_keep=p_keep, slots=slots, core=c,
+                                                  seeds=m, status=status), line
+            rows += 1
+    assert rows >= 10
+
+
+def test_plan_agrees_with_oracle_on_random_sizes(cask, oracle):
+    rng = np.random.default_rng(0)
+    for _ in range(4000):
+        R = int(rng.integers(0, 200))
+        B = int(rng.integers(R + 1, 3000))
+        P = int(rng.integers(0, 70000))
+        D = int(rng.integers(0, 40000))
+        if P + D == 0:
+            continue
+        kw = dict(window=1, recent=R, budget=B, core=int(rng.integers(-1, 400)),
+                  prefix_budget=int(rng.integers(-1, 1500)))
+        got = cask.plan(cask.Params(**kw), P, P + D)
+        want = oracle.plan(oracle.Params(**kw), P, P + D)
+        assert got == want, (kw, P, D)
+        assert got["p_keep"] + min(D - got["r_eff"], got["slots"]) + got["r_eff"] == min(P + D, B)
+
+
+def test_plan_rejects_bad_sizes(cask):
+    with pytest.raises(cask.CaskError):
+        cask.plan(cask.Params(budget=100, recent=100), 10, 1000)
+    with pytest.raises(cask.CaskError):
+        cask.plan(cask.Params(), 11, 10)
+    with pytest.raises(cask.CaskError):
+        cask.plan(cask.Params(head_dim=100), 1, 10)
+
+
+def test_workspace_size_is_sane(cask):
+    p = cask.Params(q_per_kv=7, budget=384)
+    small = cask.workspace_bytes(p, 4, 4 * 8448, 8448)
+    big = cask.workspace_bytes(p, 112, 112 * 8448, 8448)
+    assert 0 < small < big
+    assert big < 64 * 112 * 8448            # a few dozen bytes per cached row
+    assert cask.workspace_bytes(cask.Params(dtype=7), 1, 10, 10) == 0
+
+
+def test_host_validation_needs_no_gpu(cask):
+    """Bad arguments are refused before any HIP call; an empty batch is a no-op."""
+    lib = cask.load()
+    b = cask.binding._Batch(0, None, None, None, None, None, None, None)
+    ok = cask.Params().c()
+    assert lib.cask_compress(C.byref(ok), C.byref(b), None, None, None, None, None, None, None,
+                             None, None, 0, None) == cask.binding.OK
+    bad = cask.Params(window=0).c()
+    assert lib.cask_score(C.byref(bad), C.byref(b), None, None, 0, None) == cask.binding.EINVAL
+    assert lib.cask_score(None, C.byref(b), None, None, 0, None) == cask.binding.EINVAL
+    assert lib.cask_compress(C.byref(ok), None, None, None, None, None, None, None, None, None,
+                             None, 0, None) == cask.binding.EINVAL
+    # one unit shorter than the window: refused on the host mirrors alone
+    ro = np.array([0, 10], dtype=np.int64)
+    pl = np.array([0], dtype=np.int32)
+    fake = C.c_void_p(256)   # never dereferenced: validation fails first
+    b1 = cask.binding._Batch(1, fake, fake, ro.ctypes.data, pl.ctypes.data, fake, fake, fake)
+    assert lib.cask_compress(C.byref(ok), C.byref(b1), fake, fake, fake, fake, None, None, None,
+                             fake, fake, 1 << 30, None) == cask.binding.EINVAL
+    assert cask.load().cask_strerror(cask.binding.ENOMEM).decode() == "workspace too small"

@@ -1,0 +1,363 @@
+"""GPU parity tests: every entry point of the HIP library against the CPU oracle, through the
+C ABI, on seeded synthetic caches (several tiles, ragged tails, every regime)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2604_10900_amd as cask  # noqa: E402
+from oracle import ref  # noqa: E402
+from synth import caches  # noqa: E402
+from tests import parity  # noqa: E402
+
+W = caches.WORKLOADS
+
+
+def _note(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ whole-path parity
+
+def test_cfg1_tiny_fp32():
+    _note("cfg1 fp32 d=64 N=1088")
+    c = caches.make(W["cfg1"])
+    st = parity.full_check(c, parity.params_of(W["cfg1"]))
+    _note(st)
+
+
+def test_cfg1_all_donors_merge_fp32():
+    c = caches.make(W["cfg1"], seed=7)
+    st = parity.full_check(c, parity.params_of(W["cfg1"], sim_threshold=-1.0), expect_folds=True)
+    assert st["folded_rows"] >= 30
+    _note(st)
+
+
+def test_fp32_d128_gqa_ragged():
+    w = caches.scaled(W["cfg1"], head_dim=128, q_per_kv=3, n_layers=2, n_kv_heads=2, decode=700,
+                      decode_hi=1900, n_seqs=3, window=20, recent=16, budget=150, core=-1,
+                      fixed_clusters=None, cluster_lo=4, cluster_hi=9)
+    c = caches.make(w)
+    st = parity.full_check(c, parity.params_of(w, sim_threshold=0.8), expect_folds=True)
+    _note(st)
+
+
+def test_bf16_d64_plain_path():
+    w = caches.scaled(W["cfg2"], head_dim=64, n_layers=1, n_kv_heads=3, q_per_kv=2, decode=900,
+                      prefix=100, window=48, budget=160)
+    c = caches.make(w)
+    st = parity.full_check(c, parity.params_of(w, sim_threshold=0.85))
+    _note(st)
+
+
+def _ragged_bf16(lens, prefixes, G=7, Wn=128, seed=3):
+    """Hand-built ragged batch: one generator group per unit."""
+    parts = []
+    for i, (n, pfx) in enumerate(zip(lens, prefixes)):
+        w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=1, q_per_kv=G, window=Wn, prefix=pfx,
+                          decode=n - pfx, wid=100 + i)
+        parts.append(caches.make(w, seed=seed))
+    K = torch.cat([p["K"] for p in parts])
+    V = torch.cat([p["V"] for p in parts])
+    Q = torch.cat([p["Q"] for p in parts])
+    row_off = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int64)
+    return dict(K=K, V=V, Q=Q, row_off=row_off, prefix_len=torch.tensor(prefixes, dtype=torch.int32))
+
+
+def test_bf16_mfma_ragged_units_all_regimes():
+    """N == W, N just above W, identity (N <= B), merge-inactive, active, several key tiles with
+    ragged tails, and prefix lengths from 0 to almost N."""
+    lens = [128, 129, 200, 257, 300, 1000, 2177, 5000, 2304, 640]
+    pref = [0, 1, 0, 100, 290, 0, 50, 300, 2048, 512]
+    c = _ragged_bf16(lens, pref)
+    p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=7, window=128, budget=256,
+                    sim_threshold=0.9)
+    st = parity.full_check(c, p)
+    _note(st)
+
+
+def test_bf16_mfma_odd_window_noncausal_and_custom_scale():
+    lens = [100, 333, 1500, 3001]
+    pref = [0, 33, 200, 0]
+    c = _ragged_bf16(lens, pref, G=4, Wn=100, seed=5)
+    for causal, scale in ((0, 0.0), (1, 0.05)):
+        p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=4, window=100, recent=37, budget=190,
+                        core=60, prefix_budget=25, sim_threshold=0.7, causal=causal,
+                        softmax_scale=scale)
+        st = parity.full_check(c, p)
+        _note((causal, scale, st))
+
+
+def test_bf16_single_query_head_small_window():
+    c = _ragged_bf16([64, 700, 4100], [0, 10, 100], G=1, Wn=8, seed=9)
+    p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=1, window=8, budget=96)
+    _note(parity.full_check(c, p))
+
+
+def test_cfg2_two_layers_full_length():
+    w = caches.scaled(W["cfg2"], n_layers=2)
+    c = caches.make(w)
+    st = parity.full_check(c, parity.params_of(w))
+    _note(st)
+
+
+def test_cfg2_heavy_merging():
+    w = caches.scaled(W["cfg2"], n_layers=1, decode=3000)
+    c = caches.make(w, seed=11)
+    for tau in (-1.0, 0.3):
+        st = parity.full_check(c, parity.params_of(w, sim_threshold=tau), expect_folds=True)
+        _note((tau, st))
+
+
+def test_prompt_heavy_two_stage_and_exhausted():
+    w = caches.scaled(W["cfg4"], n_layers=1, n_kv_heads=2, prefix=4096, decode=1024, budget=1024)
+    c = caches.make(w)
+    p = parity.params_of(w)
+    pl = cask.plan(p, 4096, 5120)
+    assert pl["status"] == 0 and pl["p_keep"] == 256 and pl["seeds"] > 64
+    _note(parity.full_check(c, p))
+    # same cache, budget so small that the prefix floor eats it: consolidation must not run
+    w2 = caches.scaled(w, prefix=16384, decode=512, budget=300)
+    c2 = caches.make(w2)
+    p2 = parity.params_of(w2)
+    assert cask.plan(p2, 16384, 16896)["status"] == cask.binding.ST_PREFIX_BUDGET_EXHAUSTED
+    st = parity.full_check(c2, p2)
+    b = parity.to_device(c2, p2)
+    out = cask.compress(b)
+    torch.cuda.synchronize()
+    assert (out.status.cpu().numpy() == cask.binding.ST_PREFIX_BUDGET_EXHAUSTED).all()
+    assert (out.out_len.cpu().numpy() == 300).all()
+    a = out.assign.cpu().numpy().reshape(2, -1)
+    assert (a[:, 16384:16896 - 128] == -1).all()
+    _note(st)
+
+
+def test_ragged_batch_llama_shape():
+    w = caches.scaled(W["cfg5"], n_seqs=5, n_layers=1, n_kv_heads=2, decode=300, decode_hi=3000)
+    c = caches.make(w)
+    _note(parity.full_check(c, parity.params_of(w)))
+
+
+# ------------------------------------------------------------------ selection under ties
+
+@pytest.mark.parametrize("quant", [0, 3, 50])
+def test_selection_with_tied_scores(quant):
+    """quant == 0: all scores equal; else scores rounded to `quant` levels so that every
+    rank boundary falls inside a run of equal values."""
+    rng = np.random.default_rng(quant)
+    lens = [1500, 2600, 4097]
+    pref = [300, 1200, 100]
+    row_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(row_off[-1])
+    s = np.full(total, 0.25, dtype=np.float32) if quant == 0 else \
+        (np.floor(rng.random(total) * quant) / quant).astype(np.float32)
+    p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=1, window=64, budget=400)
+    rp = parity.ref_params(p)
+    role_w, _ = ref.prefix_evict(rp, row_off, np.array(pref), s)
+    role_w, st_w = ref.partition(rp, row_off, np.array(pref), s, role_w)
+    dev = torch.device("cuda:0")
+    K = torch.zeros(total, 128, dtype=torch.bfloat16, device=dev)
+    b = cask.Batch(p, torch.from_numpy(row_off), torch.tensor(pref, dtype=torch.int32), K, K, None)
+    sd = torch.from_numpy(s).to(dev)
+    role, st = cask.prefix_evict(b, sd)
+    role, st = cask.partition(b, sd, role)
+    torch.cuda.synchronize()
+    assert np.array_equal(role.cpu().numpy(), role_w)
+    assert np.array_equal(st.cpu().numpy(), st_w)
+
+
+def test_selection_handles_zero_and_tiny_scores():
+    rng = np.random.default_rng(5)
+    N, P = 3000, 500
+    s = (rng.random(N) ** 8 * 1e-30).astype(np.float32)
+    s[rng.integers(0, N, 400)] = 0.0
+    s[rng.integers(0, N, 50)] = -0.0
+    p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=1, window=32, budget=300)
+    rp = parity.ref_params(p)
+    row_off = np.array([0, N], dtype=np.int64)
+    role_w, _ = ref.prefix_evict(rp, row_off, np.array([P]), s)
+    role_w, _ = ref.partition(rp, row_off, np.array([P]), s, role_w)
+    dev = torch.device("cuda:0")
+    K = torch.zeros(N, 128, dtype=torch.bfloat16, device=dev)
+    b = cask.Batch(p, torch.from_numpy(row_off), torch.tensor([P], dtype=torch.int32), K, K, None)
+    sd = torch.from_numpy(s).to(dev)
+    role, _ = cask.prefix_evict(b, sd)
+    role, _ = cask.partition(b, sd, role)
+    torch.cuda.synchronize()
+    assert np.array_equal(role.cpu().numpy(), role_w)
+
+
+# ------------------------------------------------------------------ folds
+
+def test_zero_mass_group_and_exact_fold():
+    """Scores injected: one group whose members all score zero (uniform weights) and one whose
+    donors carry zero weight next to a seed with weight 1/4 (the fold is the seed, exactly)."""
+    d, N, P = 128, 600, 0
+    rng = np.random.default_rng(2)
+    K = rng.integers(-4, 5, (N, d)).astype(np.float32)
+    V = rng.integers(-4, 5, (N, d)).astype(np.float32)
+    K[1], K[2] = 2 * K[0], 4 * K[0]            # parallel to row 0: cosine 1
+    K[201], K[202] = K[200], K[200]
+    V[201], V[202] = V[200], V[200]
+    s = np.zeros(N, dtype=np.float32)
+    core = 10 + rng.permutation(N - 64 - 10)[:30]
+    core = core[~np.isin(core, [200, 201, 202])]
+    s[core] = 0.5
+    s[200] = 0.25     # its two duplicates score zero, like everything outside the core
+    p = cask.Params(dtype=cask.BF16, head_dim=d, q_per_kv=1, window=64, budget=64 + len(core) + 2,
+                    core=len(core), prefix_budget=0, sim_threshold=0.999)
+    rp = parity.ref_params(p)
+    tb = lambda x: torch.from_numpy(x).to(torch.bfloat16)
+    c = dict(K=tb(K), V=tb(V), Q=torch.zeros(1, 64, 1, d, dtype=torch.bfloat16),
+             row_off=torch.tensor([0, N], dtype=torch.int64), prefix_len=torch.tensor([P], dtype=torch.int32))
+    row_off, prefix_len, Kb, Vb, Qb = parity.host_arrays(c)
+    want = ref.compress(rp, row_off, prefix_len, Kb, Vb, Qb, scores=s)
+    # seeds: row 200 (0.25) and row 0 (first of the zero-score tie)
+    assert want["role"][0] == ref.SEED and want["role"][200] == ref.SEED
+    assert want["assign"][1] == want["assign"][0] == want["assign"][2]
+    assert want["assign"][201] == want["assign"][200] == want["assign"][202]
+    b = parity.to_device(c, p)
+    out = cask.compress(b, scores=torch.from_numpy(s).cuda())
+    torch.cuda.synchronize()
+    got = parity.gpu_outputs(out, p)
+    assert np.array_equal(got["out_src"], want["out_src"])
+    assert np.array_equal(got["assign"], want["assign"])
+    assert np.array_equal(got["status"], want["status"])
+    assert parity.check_values(p, got, want, Kb.reshape(N, d), Vb.reshape(N, d), row_off) == 2
+    t200, t0 = want["assign"][200], want["assign"][0]
+    np.testing.assert_array_equal(parity.rows_as_float(got["K_out"][0, t200], cask.BF16), K[200])
+    np.testing.assert_array_equal(parity.rows_as_float(got["V_out"][0, t200], cask.BF16), V[200])
+    assert got["out_mass"][0, t200] == 0.25 and got["out_mass"][0, t0] == 0.0
+    np.testing.assert_allclose(parity.rows_as_float(got["K_out"][0, t0], cask.BF16), K[0] * 7 / 3, rtol=1e-2)
+
+
+# ------------------------------------------------------------------ determinism, errors, edges
+
+def test_two_runs_are_bitwise_identical():
+    w = caches.scaled(W["cfg2"], n_layers=1, decode=2500)
+    c = caches.make(w, seed=21)
+    p = parity.params_of(w, sim_threshold=0.2)
+    b = parity.to_device(c, p)
+    a = parity.gpu_outputs(cask.compress(b), p)
+    torch.cuda.synchronize()
+    for _ in range(2):
+        o = parity.gpu_outputs(cask.compress(b), p)
+        for k in a:
+            assert np.array_equal(a[k], o[k]), k
+
+
+def test_argument_errors_and_empty_batch():
+    dev = torch.device("cuda:0")
+    p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=2, window=16, budget=64)
+    K = torch.zeros(100, 128, dtype=torch.bfloat16, device=dev)
+    Q = torch.zeros(1, 16, 2, 128, dtype=torch.bfloat16, device=dev)
+    ok = cask.Batch(p, torch.tensor([0, 100]), torch.tensor([10], dtype=torch.int32), K, K, Q)
+    cask.compress(ok)
+    torch.cuda.synchronize()
+
+    def expect(code, fn):
+        with pytest.raises(cask.CaskError) as e:
+            fn()
+        assert e.value.code == code
+
+    short = cask.Batch(p, torch.tensor([0, 10]), torch.tensor([0], dtype=torch.int32), K, K, Q)
+    expect(cask.binding.EINVAL, lambda: cask.compress(short))            # N < W
+    badp = cask.Batch(p, torch.tensor([0, 100]), torch.tensor([101], dtype=torch.int32), K, K, Q)
+    expect(cask.binding.EINVAL, lambda: cask.score(badp))                 # P > N
+    for bad in (dataclasses.replace(p, budget=16), dataclasses.replace(p, head_dim=96),
+                dataclasses.replace(p, dtype=5), dataclasses.replace(p, window=0)):
+        bb = cask.Batch(dataclasses.replace(p), torch.tensor([0, 100]), torch.tensor([10], dtype=torch.int32), K, K, Q)
+        bb.params = bad
+        bb._ws = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+        expect(cask.binding.EINVAL, lambda: cask.compress(bb))
+    small = cask.Batch(p, torch.tensor([0, 100]), torch.tensor([10], dtype=torch.int32), K, K, Q)
+    small._ws = torch.empty(256, dtype=torch.uint8, device=dev)
+    expect(cask.binding.ENOMEM, lambda: cask.compress(small))
+    expect(cask.binding.ENOMEM, lambda: cask.score(small))
+    empty = cask.Batch(p, torch.tensor([0]), torch.zeros(0, dtype=torch.int32), K, K, Q)
+    out = cask.compress(empty)
+    torch.cuda.synchronize()
+    assert out.out_len.numel() == 0
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+
+def _full_size(name, sample_units, seed=caches.BASE_SEED):
+    """Whole workload on the GPU in the benchmark's launch configuration; the oracle runs on a
+    sample of units (each regenerated bit-identically on the host is not needed: the sampled
+    rows are copied back)."""
+    w = W[name]
+    dev = torch.device("cuda:0")
+    c = caches.make(w, seed=seed, device=dev)
+    p = parity.params_of(w)
+    b = cask.Batch(p, c["row_off"], c["prefix_len"], c["K"], c["V"], c["Q"])
+    out = cask.compress(b)
+    torch.cuda.synchronize()
+    got = parity.gpu_outputs(out, p)
+    ro = b.row_off_host.numpy()
+    n_units = b.n_units
+    # properties that hold at any size
+    sums = np.add.reduceat(got["scores"].astype(np.float64), ro[:-1])
+    np.testing.assert_allclose(sums, 1.0, atol=2e-5)
+    for u in range(n_units):
+        N = int(ro[u + 1] - ro[u])
+        pl = cask.plan(p, int(b.prefix_len_host[u]), N)
+        L = int(got["out_len"][u])
+        assert L == min(N, p.budget)
+        src = got["out_src"][u, :L]
+        assert (np.diff(src) > 0).all() and src[0] >= 0 and src[-1] == N - 1
+        assert (got["status"][u] & ~cask.binding.ST_MERGE_INACTIVE) == (pl["status"] & ~cask.binding.ST_MERGE_INACTIVE)
+        assert (src < int(b.prefix_len_host[u])).sum() == pl["p_keep"]
+    # sampled units against the oracle, as a sub-batch with the same bits
+    for u in sample_units:
+        sl = slice(int(ro[u]), int(ro[u + 1]))
+        sub = dict(K=c["K"][sl].cpu(), V=c["V"][sl].cpu(), Q=c["Q"][u:u + 1].cpu(),
+                   row_off=torch.tensor([0, sl.stop - sl.start], dtype=torch.int64),
+                   prefix_len=b.prefix_len_host[u:u + 1].clone())
+        rp = parity.ref_params(p)
+        row_off, prefix_len, K, V, Q = parity.host_arrays(sub)
+        want = ref.compress(rp, row_off, prefix_len, K, V, Q)
+        parity.check_scores(got["scores"][sl], want["scores"], row_off)
+        L = int(want["out_len"][0])
+        full_src = got["out_src"][u, :L]
+        if not np.array_equal(full_src, want["out_src"][0, :L]):
+            s = want["scores"].astype(np.float64)
+            for j in np.setxor1d(full_src, want["out_src"][0, :L]):
+                gap = np.min(np.abs(np.delete(s, j) - s[j]))
+                assert gap <= 1e-4 * s[j], f"{name} unit {u}: keep-set differs at row {j} without a near-tie"
+        _note(f"{name} unit {u}: {parity.full_check(sub, p)}")
+
+
+def test_cfg2_full_size_sampled_units():
+    _full_size("cfg2", [0, 37, 111])
+
+
+def test_cfg3_full_size_sampled_units():
+    _full_size("cfg3", [5])
+
+
+def test_cfg4_full_size_sampled_units():
+    _full_size("cfg4", [1, 60])
+
+
+def test_cfg4v_full_size_exhausted():
+    w = W["cfg4v"]
+    dev = torch.device("cuda:0")
+    c = caches.make(w, device=dev, layers=range(4))
+    p = parity.params_of(w)
+    b = cask.Batch(p, c["row_off"], c["prefix_len"], c["K"], c["V"], c["Q"])
+    out = cask.compress(b)
+    torch.cuda.synchronize()
+    got = parity.gpu_outputs(out, p)
+    assert (got["status"] == cask.binding.ST_PREFIX_BUDGET_EXHAUSTED).all()
+    assert (got["out_len"] == 1024).all()
+    ro = b.row_off_host.numpy()
+    u = 3
+    sl = slice(int(ro[u]), int(ro[u + 1]))
+    sub = dict(K=c["K"][sl].cpu(), V=c["V"][sl].cpu(), Q=c["Q"][u:u + 1].cpu(),
+               row_off=torch.tensor([0, sl.stop - sl.start], dtype=torch.int64),
+               prefix_len=b.prefix_len_host[u:u + 1].clone())
+    _note(parity.full_check(sub, p))
