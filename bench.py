@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the CASK compression event on one MI355X.
+
+A step is one whole compression event (score -> prefix eviction -> core/scratch partition ->
+consolidation -> fold -> compaction) over every (layer, KV head) unit of a synthetic cache
+that is already resident in HBM.  The default workload is the Qwen2.5-7B-shaped cache at
+budget 384 (28 layers x 4 KV heads, 256 prefix + 8192 decode tokens, 128-query window).
+
+Prints ONE JSON line: whole-event throughput in KV tokens/s (one KV token = one
+(token, layer, KV head) K/V row pair), the roofline position of the dominant kernel measured
+with HIP events recorded between the kernels inside the timed region, and the CPU oracle
+timed on a bounded sample of the same units.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "KV tokens compressed/s per layer x head at budget 384; % HBM/MFMA roofline"
+PEAK_MFMA_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs, scaled by a copy kernel of known size (see profiles/); None where not measured.
+MEASURED_TRAFFIC = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", help="cfg2 (default) | cfg3 | cfg4 | cfg4v | cfg5")
+    ap.add_argument("--layers", type=int, default=0, help="use only the first L layers (0 = all)")
+    ap.add_argument("--seqs", type=int, default=0, help="cfg5: use only the first S sequences")
+    ap.add_argument("--copies", type=int, default=0,
+                    help="input copies alternated between steps (0 = 2 when they fit in 2 GB)")
+    ap.add_argument("--cpu-units", type=int, default=16, help="units the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-stage-events", action="store_true",
+                    help="do not record per-kernel HIP events inside the timed region")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; the compression event shards over units "
+              "with no exchange, so N > 1 is not run here (use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2604_10900_amd as cask
+    from paper_2604_10900_amd import binding
+    from synth import caches
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    cask.load()
+    dev = torch.device("cuda:0")
+    w = caches.WORKLOADS[args.workload]
+    layers = range(args.layers) if args.layers > 0 else None
+    seqs = range(args.seqs) if args.seqs > 0 else None
+    n_layers = args.layers if args.layers > 0 else w.n_layers
+    p = cask.Params(dtype=cask.F32 if w.dtype == "f32" else cask.BF16, head_dim=w.head_dim,
+                    q_per_kv=w.q_per_kv, window=w.window, recent=w.recent, budget=w.budget,
+                    core=w.core)
+
+    # ---- inputs, resident in HBM; alternate copies so the 256 MB last-level cache cannot
+    # stand in for HBM between steps
+    first = caches.make(w, seed=caches.BASE_SEED, device=dev, layers=layers, seqs=seqs)
+    in_bytes = first["K"].numel() * first["K"].element_size() * 2
+    copies = args.copies if args.copies > 0 else (2 if in_bytes <= (2 << 30) else 1)
+    batches = []
+    for i in range(copies):
+        c = first if i == 0 else caches.make(w, seed=caches.BASE_SEED + i, device=dev, layers=layers, seqs=seqs)
+        b = cask.Batch(p, c["row_off"], c["prefix_len"], c["K"], c["V"], c["Q"])
+        batches.append((c, b))
+    b0 = batches[0][1]
+    outs = cask.Outputs(b0)
+    ws = b0.workspace()
+    for _, b in batches[1:]:
+        b._ws = ws
+    kv_tokens = b0.total_rows
+    n_units = b0.n_units
+
+    def step(i):
+        cask.compress(batches[i % copies][1], outs)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    use_events = not args.no_stage_events
+    if use_events:
+        binding.timing_enable(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    stage_ms = None
+    if use_events:
+        stage_ms, n_rec = binding.timing_read()
+        binding.timing_enable(0)
+        assert n_rec == args.steps
+    status = outs.status.cpu().numpy()
+    out_len = outs.out_len.cpu().numpy()
+    lens = (b0.row_off_host[1:] - b0.row_off_host[:-1]).numpy()
+    saved = 1.0 - float(out_len.sum()) / float(lens.sum())
+
+    # ---- roofline of the dominant kernel: one scoring sweep is one Q.K^T pass of
+    # 2 * (W*G) * N * d flops per unit on the matrix cores
+    Mq = p.q_per_kv * p.window
+    flops_pass = 2.0 * Mq * float(kv_tokens) * p.head_dim
+    roof = None
+    if stage_ms is not None:
+        dom = max(("score_rows", "score_cols"), key=lambda k: stage_ms[k])
+        t_dom = stage_ms[dom] * 1e-3
+        achieved = flops_pass / t_dom / 1e12
+        roof = {"bound": "mfma", "kernel": "score_mfma_kernel<%d> (%s)" % (0 if dom == "score_rows" else 1, dom),
+                "achieved": round(achieved, 2), "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),
+                "traffic": MEASURED_TRAFFIC.get(args.workload),
+                "kernel_ms": round(stage_ms[dom], 4),
+                "flops_per_launch": flops_pass,
+                "both_sweeps_frac": round(2 * flops_pass / ((stage_ms["score_rows"] + stage_ms["score_cols"]) * 1e-3)
+                                          / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4)}
+
+    # ---- CPU oracle on a bounded sample of the same units (rank 0, N = 1 only)
+    cpu = None
+    if args.cpu_units > 0:
+        from oracle import ref
+        rng = np.random.default_rng(0)
+        take = min(args.cpu_units, n_units)
+        pick = np.sort(rng.choice(n_units, size=take, replace=False))
+        c0 = batches[0][0]
+        ro = b0.row_off_host.numpy()
+        Ks, Vs, Qs, sub_lens = [], [], [], []
+        for u in pick:
+            sl = slice(int(ro[u]), int(ro[u + 1]))
+            Ks.append(c0["K"][sl].cpu())
+            Vs.append(c0["V"][sl].cpu())
+            Qs.append(c0["Q"][u:u + 1].cpu())
+            sub_lens.append(sl.stop - sl.start)
+        Kh, Vh, Qh = (caches.host_bits(torch.cat(x)) for x in (Ks, Vs, Qs))
+        sub_ro = np.concatenate([[0], np.cumsum(sub_lens)]).astype(np.int64)
+        sub_pl = b0.prefix_len_host.numpy()[pick]
+        rp = ref.Params(dtype=p.dtype, head_dim=p.head_dim, q_per_kv=p.q_per_kv, window=p.window,
+                        recent=p.recent, budget=p.budget, core=p.core)
+        threads = min(int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), os.cpu_count() or 1, take)
+        tc0 = time.perf_counter()
+        want = ref.compress(rp, sub_ro, sub_pl, Kh, Vh, Qh, n_threads=threads)
+        tc1 = time.perf_counter()
+        cpu = {"value": round(float(sum(sub_lens)) / (tc1 - tc0), 1), "unit": "KV tokens/s",
+               "cores": threads, "kind": "oracle",
+               "sample": "%d of %d units of %s (%d KV tokens), %.1f s" % (take, n_units, args.workload,
+                                                                          sum(sub_lens), tc1 - tc0)}
+        # the sampled units double as a live parity check of this very run
+        # outs holds the last step's result: recompute on copy 0 for the comparison
+        cask.compress(b0, outs)
+        torch.cuda.synchronize()
+        got_src = outs.out_src.cpu().numpy()[pick]
+        got_scores = outs.scores.cpu().numpy()
+        worst = 0.0
+        for k, u in enumerate(pick):
+            sl = slice(int(ro[u]), int(ro[u + 1]))
+            ssl = slice(int(sub_ro[k]), int(sub_ro[k + 1]))
+            worst = max(worst, float(np.abs(got_scores[sl] - want["scores"][ssl]).max() / want["scores"][ssl].max()))
+        cpu["parity"] = {"score_rel_err_max": worst,
+                         "keep_set_equal_units": int(sum(np.array_equal(got_src[k], want["out_src"][k]) for k in range(take)))}
+
+    value = kv_tokens / (ms_per_step * 1e-3)
+    line = {
+        "metric": METRIC, "value": round(value, 1), "unit": "KV tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": "%s: %d layers x %d KV heads x %d seqs, G=%d, d=%d, prefix %d, decode %s, window %d, budget %d"
+                   % (args.workload, n_layers, w.n_kv_heads, (args.seqs or w.n_seqs), w.q_per_kv, w.head_dim, w.prefix,
+                      (str(w.decode) if w.decode_hi is None else "%d..%d" % (w.decode, w.decode_hi)), w.window, w.budget),
+                   "units": n_units, "kv_tokens_per_event": kv_tokens,
+                   "seq_tokens_per_s": round(value / (n_layers * w.n_kv_heads), 1),
+                   "input_copies": copies, "saved_ratio": round(saved, 4),
+                   "status_counts": {str(k): int(v) for k, v in zip(*np.unique(status, return_counts=True))},
+                   "stage_ms": ({k: round(v, 4) for k, v in stage_ms.items()} if stage_ms else None)},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -152,6 +152,19 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
                   int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
                   float* scores, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* Measurement aid (not part of the method): per-stage timing of cask_compress with HIP
+ * events recorded on the caller's stream between its kernels.  Stage order: 0 score sweep A
+ * (row statistics), 1 score sweep B (column mass), 2 select, 3 index roles, 4 similarity,
+ * 5 gather merged donors, 6 emit.
+ * cask_timing_enable(n > 0) creates events for the next n compress calls (n <= 4096) and
+ * switches recording on; n <= 0 switches it off and destroys them.  Calls beyond n are not
+ * recorded.  cask_timing_read waits for the recorded calls, writes the summed milliseconds
+ * per stage into stage_ms[CASK_N_STAGES] and the number of recorded calls into *n_calls,
+ * and rearms.  Not thread-safe; one stream at a time. */
+#define CASK_N_STAGES 7
+int cask_timing_enable(int max_calls);
+int cask_timing_read(float* stage_ms, int* n_calls);
+
 /* HOST: short name of a return code. */
 const char* cask_strerror(int code);
 

@@ -25,7 +25,9 @@ ST_ACTIVE, ST_IDENTITY, ST_PREFIX_BUDGET_EXHAUSTED, ST_MERGE_INACTIVE = 0, 1, 2,
  ROLE_DECODE_EVICT) = range(7)
 
 EXPORTS = ["cask_plan", "cask_workspace_bytes", "cask_score", "cask_prefix_evict",
-           "cask_partition", "cask_consolidate", "cask_compress", "cask_strerror"]
+           "cask_partition", "cask_consolidate", "cask_compress", "cask_strerror",
+           "cask_timing_enable", "cask_timing_read"]
+STAGES = ["score_rows", "score_cols", "select", "index_roles", "similarity", "gather", "emit"]
 
 
 class CaskError(RuntimeError):
@@ -95,8 +97,10 @@ def load():
         lib.cask_partition.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         lib.cask_consolidate.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         lib.cask_compress.argtypes = [vp] * 11 + [C.c_size_t, vp]
+        lib.cask_timing_enable.argtypes = [C.c_int]
+        lib.cask_timing_read.argtypes = [vp, vp]
         for name in ("cask_plan", "cask_score", "cask_prefix_evict", "cask_partition",
-                     "cask_consolidate", "cask_compress"):
+                     "cask_consolidate", "cask_compress", "cask_timing_enable", "cask_timing_read"):
             getattr(lib, name).restype = C.c_int
         _lib = lib
     return _lib
@@ -107,6 +111,23 @@ def _strerror(code: int) -> str:
         return load().cask_strerror(code).decode()
     except Exception:  # pragma: no cover
         return "?"
+
+
+def timing_enable(max_calls: int) -> None:
+    rc = load().cask_timing_enable(C.c_int(max_calls))
+    if rc:
+        raise CaskError("cask_timing_enable", rc)
+
+
+def timing_read() -> tuple:
+    """(mean milliseconds per stage as a dict, number of recorded compress calls)."""
+    ms = (C.c_float * len(STAGES))()
+    n = C.c_int(0)
+    rc = load().cask_timing_read(ms, C.byref(n))
+    if rc:
+        raise CaskError("cask_timing_read", rc)
+    k = max(n.value, 1)
+    return {s: ms[i] / k for i, s in enumerate(STAGES)}, n.value
 
 
 def plan(p: Params, P: int, N: int) -> dict:

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <vector>
 
 #include "cask_common.h"
 
@@ -105,6 +106,32 @@ static int resolve_batch(const KParams& kp, const cask_batch* b, Batch* out, boo
 }
 
 static int dev_rc(hipError_t e) { return e == hipSuccess ? CASK_OK : CASK_EDEVICE; }
+
+// Optional per-stage timing of cask_compress: HIP events recorded on the caller's stream
+// between the kernels of an event.  Off by default; the events are created when it is
+// switched on, never inside a compression call.
+struct StageTiming {
+  bool on = false;
+  int max_calls = 0;
+  int n_calls = 0;
+  std::vector<hipEvent_t> ev;  // (CASK_N_STAGES + 1) per call
+};
+static StageTiming g_timing;
+
+struct StageRecorder {
+  hipEvent_t* ev = nullptr;
+  hipStream_t st;
+  int next = 0;
+  explicit StageRecorder(hipStream_t s) : st(s) {
+    if (g_timing.on && g_timing.n_calls < g_timing.max_calls) {
+      ev = g_timing.ev.data() + (size_t)g_timing.n_calls * (CASK_N_STAGES + 1);
+      ++g_timing.n_calls;
+    }
+  }
+  hipEvent_t peek() const { return ev ? ev[next] : nullptr; }  // handed to a launcher to record
+  void skip() { if (ev) ++next; }
+  void mark() { if (ev) (void)hipEventRecord(ev[next++], st); }
+};
 
 }  // namespace cask
 
@@ -248,22 +275,66 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
   int32_t* n_merged = reinterpret_cast<int32_t*>(w + wl.n_merged);
   int32_t* n_seeds = reinterpret_cast<int32_t*>(w + wl.n_seeds);
   hipError_t e;
+  StageRecorder rec(st);
+  rec.mark();  // start
   if (!given) {
-    e = launch_score(kp, b, wl, w, s, st);
+    e = launch_score(kp, b, wl, w, s, st, rec.peek());  // records the end of sweep A itself
     if (e != hipSuccess) return CASK_EDEVICE;
+    rec.skip();
+  } else {
+    rec.mark();
   }
+  rec.mark();  // end of sweep B
   e = launch_select(kp, b, s, role, status, true, true, st);
   if (e != hipSuccess) return CASK_EDEVICE;
+  rec.mark();
   e = launch_index_roles(kp, b, role, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds, st);
   if (e != hipSuccess) return CASK_EDEVICE;
+  rec.mark();
   e = launch_similarity(kp, b, role, seed_rows, n_seeds, assign_ord, st);
   if (e != hipSuccess) return CASK_EDEVICE;
+  rec.mark();
   e = launch_gather_merged(kp, b, role, assign_ord, slot_of, seed_rows, merged_row, merged_ord,
                            n_merged, assign, assign ? 1 : 0, status, st);
   if (e != hipSuccess) return CASK_EDEVICE;
+  rec.mark();
   e = launch_emit(kp, b, s, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out,
                   V_out, out_mass, st);
+  rec.mark();
   return dev_rc(e);
+}
+
+int cask_timing_enable(int max_calls) {
+  for (hipEvent_t e : g_timing.ev) (void)hipEventDestroy(e);
+  g_timing.ev.clear();
+  g_timing.on = false;
+  g_timing.n_calls = 0;
+  g_timing.max_calls = 0;
+  if (max_calls <= 0) return CASK_OK;
+  if (max_calls > 4096) return CASK_EINVAL;
+  g_timing.ev.resize((size_t)max_calls * (CASK_N_STAGES + 1));
+  for (auto& e : g_timing.ev)
+    if (hipEventCreate(&e) != hipSuccess) return CASK_EDEVICE;
+  g_timing.max_calls = max_calls;
+  g_timing.on = true;
+  return CASK_OK;
+}
+
+int cask_timing_read(float* stage_ms, int* n_calls) {
+  if (!stage_ms || !n_calls) return CASK_EINVAL;
+  for (int i = 0; i < CASK_N_STAGES; ++i) stage_ms[i] = 0.f;
+  *n_calls = g_timing.n_calls;
+  for (int c = 0; c < g_timing.n_calls; ++c) {
+    hipEvent_t* ev = g_timing.ev.data() + (size_t)c * (CASK_N_STAGES + 1);
+    if (hipEventSynchronize(ev[CASK_N_STAGES]) != hipSuccess) return CASK_EDEVICE;
+    for (int i = 0; i < CASK_N_STAGES; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) return CASK_EDEVICE;
+      stage_ms[i] += ms;
+    }
+  }
+  g_timing.n_calls = 0;
+  return CASK_OK;
 }
 
 }  // extern "C"

@@ -162,8 +162,9 @@ struct Batch {
   int64_t total_rows;
 };
 
+// `between`, when not null, is recorded on the stream between the two scoring sweeps.
 hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, char* ws,
-                        float* scores, hipStream_t st);
+                        float* scores, hipStream_t st, hipEvent_t between = nullptr);
 hipError_t launch_select(const KParams& kp, const Batch& b, const float* scores, uint8_t* role,
                          int32_t* status, bool do_prefix, bool do_decode, hipStream_t st);
 hipError_t launch_index_roles(const KParams& kp, const Batch& b, const uint8_t* role,

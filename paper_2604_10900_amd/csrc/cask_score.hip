@@ -34,14 +34,15 @@ __device__ inline void ml_combine(float& m, float& l, float m2, float l2) {
 }
 
 // -L_row (base-2) of every window row from the per-split partials; -inf for padding rows.
-__device__ inline void fill_neg_lse(const float2* __restrict__ part, int n_splits, int mq_pad,
-                                    int Mq, float* negL, int tid, int nthreads) {
-  for (int r = tid; r < mq_pad; r += nthreads) {
+// Fills negL[0, n_fill); rows >= Mq get -inf.  `pitch` is the row pitch of the partials.
+__device__ inline void fill_neg_lse(const float2* __restrict__ part, int n_splits, int n_fill,
+                                    int Mq, float* negL, int tid, int nthreads, int pitch) {
+  for (int r = tid; r < n_fill; r += nthreads) {
     float v = kNegInf;
     if (r < Mq) {
       float m = kNegInf, l = 0.f;
       for (int s = 0; s < n_splits; ++s) {
-        const float2 p = part[(size_t)s * mq_pad + r];
+        const float2 p = part[(size_t)s * pitch + r];
         ml_combine(m, l, p.x, p.y);
       }
       v = -(m + log2f(l));
@@ -81,19 +82,60 @@ struct Geo<1> {  // sweep B: resident = keys (K), stream = window rows (Q)
   static constexpr int RES_ROWS = 256, STAGE_ROWS = 64;   // 4 resident wave groups
 };
 
+// Raw buffer descriptor over [p, p + bytes): loads past the end return zero, so ragged stream
+// tiles need no per-lane bounds test.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  // stride 0 (raw byte addressing), `bytes` records, 32-bit data format
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+// Pad value of -L for window rows past W*G: large, finite (inf would turn 0 * inf into NaN
+// inside the matrix core), and far enough down that exp2 flushes to zero.
+constexpr float kPadNegL = -1.0e30f;
+
+// Three bf16 whose sum is x to fp32 precision (8 + 8 + 8 significant bits).
+__device__ inline void split3_bf16(float x, uint16_t& hi, uint16_t& mid, uint16_t& lo) {
+  hi = float_to_bf16_bits(x);
+  const float r1 = x - bf16_bits_to_float(hi);
+  mid = float_to_bf16_bits(r1);
+  const float r2 = r1 - bf16_bits_to_float(mid);
+  lo = float_to_bf16_bits(r2);
+}
+
+// One workgroup = 4 waves.  Each wave keeps 64 resident rows (two 32-column MFMA tiles) in
+// registers and walks the staged stream rows 32 at a time.  Per stage a wave runs four tiles
+//   (rt0,ct0) (rt0,ct1) (rt1,ct0) (rt1,ct1)
+// software-pipelined: the MFMA chain of a tile is issued interleaved, two logits per MFMA,
+// with the exp2 epilogue of the tile before it, so the matrix cores and the vector ALU of a
+// wave run at the same time; the epilogue of the last tile of a stage rides on the first chain
+// of the next stage.
+//
+// Epilogue cost is the bound (fma/mul + exp2 + add per logit on the vector ALU against
+// 256 matrix flops), so it is kept to exactly those three instructions:
+//   sweep A  the running maximum is lazy: exp2 is taken against a per-lane reference that
+//            is only raised when a tile's sum threatens fp32 range (checked once per tile),
+//            which is exact because (reference, sum) pairs combine exactly;
+//   sweep B  -L_row is carried into the accumulator by a ninth k-step: the staged window row
+//            is extended by three bf16 that add up to -L_row / c and meet ones in the
+//            resident operand, so the epilogue is mul, exp2, add with no per-row operand.
+// Stages that touch masked keys (causal tail, ragged end) or initialise the reference take
+// a plain, unpipelined path with explicit masks.
 template <int MODE>
-__global__ __launch_bounds__(256) void score_mfma_kernel(
+__global__ __launch_bounds__(256, 2) void score_mfma_kernel(
     KParams kp, int n_units, int tiles_per_unit, int n_splits, int split_len, int mq_pad,
     const int64_t* __restrict__ row_off, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ Q, float2* __restrict__ rowstat, float* __restrict__ scores) {
   using G_ = Geo<MODE>;
   constexpr int STAGE_ROWS = G_::STAGE_ROWS;
   constexpr int CHUNKS = STAGE_ROWS * 16 / 256;  // 16-byte chunks per thread per stage
+  constexpr int NK = (MODE == 0) ? 8 : 9;        // k-steps per tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* stage0 = smem;
   unsigned char* stage1 = smem + STAGE_ROWS * kPitch;
-  float* negL = reinterpret_cast<float*>(smem + 2 * STAGE_ROWS * kPitch);  // MODE 1 only
-  float* xchg = negL;                                                     // MODE 0 only
+  // MODE 1: per window row, -L_row / c as three bf16 packed in 8 bytes; MODE 0: exchange area
+  uint2* bias_tab = reinterpret_cast<uint2*>(smem + 2 * STAGE_ROWS * kPitch);
+  float* xchg = reinterpret_cast<float*>(bias_tab);
 
   int unit, tile;
   if (!map_block(n_units, tiles_per_unit, unit, tile)) return;
@@ -137,11 +179,27 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
     s_begin = 0;
     s_end = Mq;
     if (kp.causal && res_base > N - W) s_begin = (((res_base - (N - W)) * Gq) / STAGE_ROWS) * STAGE_ROWS;
-    fill_neg_lse(part, n_splits, mq_pad, Mq, negL, tid, 256);
+    const float inv_c = 1.0f / c;
+    // one stage of slack: the prefetch of the stage after the last one reads it
+    for (int r = tid; r < mq_pad + STAGE_ROWS; r += 256) {
+      float nl = kPadNegL;
+      if (r < Mq) {
+        float m = kNegInf, l = 0.f;
+        for (int sp = 0; sp < n_splits; ++sp) {
+          const float2 pr = part[(size_t)sp * mq_pad + r];
+          ml_combine(m, l, pr.x, pr.y);
+        }
+        nl = -(m + log2f(l));
+      }
+      uint16_t b0, b1, b2;
+      split3_bf16(nl * inv_c, b0, b1, b2);
+      bias_tab[r] = make_uint2((uint32_t)b0 | ((uint32_t)b1 << 16), (uint32_t)b2);
+    }
+    __syncthreads();  // the first stash reads the table
   }
 
   // ---- resident fragments: lane (c32, h) holds row c32 of each 32-row tile, k-chunk h
-  bf16x8 bres[2][8];
+  bf16x8 bres[2][NK];
   int res_row[2];
 #pragma unroll
   for (int ct = 0; ct < 2; ++ct) {
@@ -154,10 +212,14 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
       uint4 v = ok ? src[ks * 2] : make_uint4(0, 0, 0, 0);
       bres[ct][ks] = *reinterpret_cast<bf16x8*>(&v);
     }
+    if (NK == 9) {  // ones that pick up the three bias terms; the upper k-half contributes nothing
+      uint4 v = (h == 0) ? make_uint4(0x3F803F80u, 0x00003F80u, 0, 0) : make_uint4(0, 0, 0, 0);
+      bres[ct][NK - 1] = *reinterpret_cast<bf16x8*>(&v);
+    }
   }
 
   // per-lane reduction state
-  float m_run[2] = {kNegInf, kNegInf}, l_run[2] = {0.f, 0.f};  // sweep A
+  float m_ref[2] = {kNegInf, kNegInf}, l_run[2] = {0.f, 0.f};  // sweep A
   float colsum[2] = {0.f, 0.f};                                  // sweep B
   int vis_limit[2];  // sweep A: last key the lane's window row sees; sweep B: the lane's key
 #pragma unroll
@@ -166,117 +228,193 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
   const int tail_start = kp.causal ? N - W : N;  // keys > tail_start are hidden from some row
 
   const int n_stages = (s_end - s_begin + STAGE_ROWS - 1) / STAGE_ROWS;
-  uint4 pre[CHUNKS];
+  // stream rows come through a buffer descriptor that ends at row s_end
+  const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(str_ptr, (uint32_t)max(s_end, 0) * (uint32_t)(kD * 2));
+  const int voff = tid * 16;  // thread t: row t / 16 of a 16-row group, 16-byte chunk t % 16
+  u32x4 pre[CHUNKS];
   auto fetch = [&](int stage) {
-    const int base = s_begin + stage * STAGE_ROWS;
+    const int sbase = (s_begin + stage * STAGE_ROWS) * (kD * 2);
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i)
+      pre[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, sbase + i * 16 * kD * 2, 0);
+  };
+  auto stash = [&](unsigned char* buf, int stage) {
 #pragma unroll
     for (int i = 0; i < CHUNKS; ++i) {
       const int q = tid + 256 * i;
-      const int r = base + (q >> 4);
-      pre[i] = (r < s_end) ? reinterpret_cast<const uint4*>(str_ptr + (size_t)r * kD)[q & 15]
-                           : make_uint4(0, 0, 0, 0);
+      *reinterpret_cast<u32x4*>(buf + (q >> 4) * kPitch + (q & 15) * 16) = pre[i];
+      if (MODE == 1 && (q & 15) == 0) {
+        // the row's pad chunk carries its bias terms into the ninth k-step
+        const uint2 bt = bias_tab[s_begin + stage * STAGE_ROWS + (q >> 4)];
+        *reinterpret_cast<uint4*>(buf + (q >> 4) * kPitch + 256) = make_uint4(bt.x, bt.y, 0, 0);
+      }
     }
   };
-  auto stash = [&](unsigned char* buf) {
+  auto load_a = [&](bf16x8(&a)[NK], const unsigned char* buf, int rt) {
+    const unsigned char* rowp = buf + (sgrp * 64 + rt * 32 + c32) * kPitch;
 #pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) {
-      const int q = tid + 256 * i;
-      *reinterpret_cast<uint4*>(buf + (q >> 4) * kPitch + (q & 15) * 16) = pre[i];
+    for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(rowp + h * 16 + ks * 32);
+    if (NK == 9) a[NK - 1] = *reinterpret_cast<const bf16x8*>(rowp + 256);
+  };
+
+  // ---- epilogues
+  float tsum = 0.f;  // sweep A: sum of the tile in flight
+  auto piece = [&](const f32x16& acc, int ct, int i) {  // two logits of the fast epilogue
+    if (MODE == 0) {
+      const float nm = -m_ref[ct];
+      tsum += fast_exp2(__builtin_fmaf(acc[2 * i], c, nm));
+      tsum += fast_exp2(__builtin_fmaf(acc[2 * i + 1], c, nm));
+    } else {
+      colsum[ct] += fast_exp2(acc[2 * i] * c);
+      colsum[ct] += fast_exp2(acc[2 * i + 1] * c);
     }
+  };
+  // exact online-softmax update of (m_ref, l_run) with the 16 logits of `acc` (masked = -inf)
+  auto exact_update = [&](const f32x16& acc, int ct) {
+    float xm = acc[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) xm = fmaxf(xm, acc[r]);
+    const float m_new = fmaxf(m_ref[ct], xm * c);
+    const float nm = (m_new == kNegInf) ? 0.f : -m_new;
+    float sum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += fast_exp2(__builtin_fmaf(acc[r], c, nm));
+    l_run[ct] = l_run[ct] * fast_exp2(m_ref[ct] + nm) + sum;
+    m_ref[ct] = m_new;
+  };
+  auto finish_fast = [&](const f32x16& acc, int ct) {  // sweep A: bank the tile sum, guard the range
+    if (MODE == 0) {
+      const bool bad = !(tsum < 0x1p100f);
+      if (__builtin_amdgcn_ballot_w64(bad) != 0ull) {
+        if (bad) exact_update(acc, ct); else l_run[ct] += tsum;
+      } else {
+        l_run[ct] += tsum;
+      }
+      tsum = 0.f;
+    }
+  };
+  auto slow_tile = [&](f32x16& acc, int ct, int trow0) {
+    if (MODE == 0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = trow0 + (r >> 2) * 8 + h * 4 + (r & 3);
+        if (!(key < s_end && key <= vis_limit[ct])) acc[r] = kNegInf;
+      }
+      exact_update(acc, ct);
+    } else {
+      float sum = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = trow0 + (r >> 2) * 8 + h * 4 + (r & 3);
+        const int tw = N - W + row / Gq;
+        const float y = (kp.causal && vis_limit[ct] > tw) ? kNegInf : acc[r] * c;
+        sum += fast_exp2(y);
+      }
+      colsum[ct] += sum;
+    }
+  };
+  auto chain = [&](f32x16& acc, const bf16x8(&a)[NK], int ct) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], bres[ct][0], f32x16{0}, 0, 0, 0);
+#pragma unroll
+    for (int ks = 1; ks < NK; ++ks)
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct][ks], acc, 0, 0, 0);
+  };
+  // chain of the new tile interleaved with the fast epilogue of the old one
+  auto fused = [&](f32x16& acc_new, const bf16x8(&a)[NK], int ct_new, const f32x16& acc_old, int ct_old) {
+#pragma unroll
+    for (int ks = 0; ks < NK; ++ks) {
+      if (ks < 8) piece(acc_old, ct_old, ks);
+      acc_new = (ks == 0)
+                    ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], bres[ct_new][0], f32x16{0}, 0, 0, 0)
+                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct_new][ks], acc_new, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    finish_fast(acc_old, ct_old);
+  };
+  auto drain = [&](const f32x16& acc_old, int ct_old) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) piece(acc_old, ct_old, i);
+    finish_fast(acc_old, ct_old);
   };
 
   if (n_stages > 0) {
     fetch(0);
-    stash(stage0);
+    stash(stage0, 0);
   }
   __syncthreads();
 
+  // sweep B masks only in the key blocks that reach into the window; sweep A per stage
+  const bool blk_slow = (MODE == 1) && kp.causal && (res_base + G_::RES_ROWS - 1 > tail_start);
+  f32x16 acc0, acc1;
+  bf16x8 a0[NK], a1[NK];
+  bool carry = false;  // the last tile of the previous stage (acc1, ct 1) still owes its epilogue
   for (int it = 0; it < n_stages; ++it) {
     unsigned char* cur = (it & 1) ? stage1 : stage0;
     unsigned char* nxt = (it & 1) ? stage0 : stage1;
-    if (it + 1 < n_stages) fetch(it + 1);
-    const int stage_row0 = s_begin + it * STAGE_ROWS + sgrp * 64;
+    const int stage_base = s_begin + it * STAGE_ROWS;
+    const int wrow0 = stage_base + sgrp * 64;  // first stream row of this wave in the stage
+    bool slow;
+    if (MODE == 0)
+      slow = (it == 0) || (stage_base + STAGE_ROWS - 1 > tail_start) || (stage_base + STAGE_ROWS > s_end);
+    else
+      slow = blk_slow;
+    fetch(it + 1);  // past the last stage the descriptor returns zeros
+    if (slow) {
+      if (carry) {
+        drain(acc1, 1);
+        carry = false;
+      }
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-      const int trow0 = stage_row0 + rt * 32;  // stream index of this tile's row 0
-      if (trow0 >= s_end) continue;
-      bf16x8 a[8];
-      const unsigned char* ap = cur + (sgrp * 64 + rt * 32 + c32) * kPitch + h * 16;
+      for (int rt = 0; rt < 2; ++rt) {
+        const int trow0 = wrow0 + rt * 32;
+        if (trow0 >= s_end) continue;
+        load_a(a0, cur, rt);
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 32);
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        f32x16 acc = {0};
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct][ks], acc, 0, 0, 0);
-        if (MODE == 0) {
-          // stream rows are keys; the lane's column is one window row
-          const bool slow = (trow0 + 31 > tail_start) || (trow0 + 32 > s_end);
-          if (slow) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int key = trow0 + (r >> 2) * 8 + h * 4 + (r & 3);
-              if (!(key < s_end && key <= vis_limit[ct])) acc[r] = kNegInf;
-            }
-          }
-          float xm = acc[0];
-#pragma unroll
-          for (int r = 1; r < 16; ++r) xm = fmaxf(xm, acc[r]);
-          const float m_new = fmaxf(m_run[ct], xm * c);
-          const float nm = (m_new == kNegInf) ? 0.f : -m_new;
-          float sum = 0.f;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sum += fast_exp2(__builtin_fmaf(acc[r], c, nm));
-          l_run[ct] = l_run[ct] * fast_exp2(m_run[ct] + nm) + sum;
-          m_run[ct] = m_new;
-        } else {
-          // stream rows are window rows; the lane's column is one key
-          const bool slow = kp.causal && (res_base + G_::RES_ROWS - 1 > tail_start);
-          float sum = 0.f;
-#pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) {
-            const int rowb = trow0 + g4 * 8 + h * 4;
-            const float4 nl = *reinterpret_cast<const float4*>(negL + rowb);
-            const float nls[4] = {nl.x, nl.y, nl.z, nl.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              float y = __builtin_fmaf(acc[g4 * 4 + e], c, nls[e]);
-              if (slow) {
-                const int tw = N - W + (rowb + e) / Gq;
-                if (vis_limit[ct] > tw) y = kNegInf;
-              }
-              sum += fast_exp2(y);
-            }
-          }
-          colsum[ct] += sum;
+        for (int ct = 0; ct < 2; ++ct) {
+          chain(acc0, a0, ct);
+          slow_tile(acc0, ct, trow0);
         }
       }
+      if (MODE == 0) {
+        // a lane that saw nothing yet takes 0 as its reference: (0, 0) is the empty sum
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+          if (m_ref[ct] == kNegInf) m_ref[ct] = 0.f;
+      }
+    } else {
+      load_a(a0, cur, 0);
+      if (carry) fused(acc0, a0, 0, acc1, 1); else chain(acc0, a0, 0);
+      load_a(a1, cur, 1);
+      fused(acc1, a0, 1, acc0, 0);
+      fused(acc0, a1, 0, acc1, 1);
+      fused(acc1, a1, 1, acc0, 0);
+      carry = true;
     }
-    if (it + 1 < n_stages) stash(nxt);
+    stash(nxt, it + 1);
     __syncthreads();
   }
+  if (carry) drain(acc1, 1);
 
   // ---- finish
   if (MODE == 0) {
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct) {
-      const float m2 = __shfl_xor(m_run[ct], 32, 64);
+      const float m2 = __shfl_xor(m_ref[ct], 32, 64);
       const float l2 = __shfl_xor(l_run[ct], 32, 64);
-      ml_combine(m_run[ct], l_run[ct], m2, l2);
+      ml_combine(m_ref[ct], l_run[ct], m2, l2);
     }
     float2* x2 = reinterpret_cast<float2*>(xchg);
     if (sgrp == 1 && h == 0) {
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) x2[rgrp * 64 + ct * 32 + c32] = make_float2(m_run[ct], l_run[ct]);
+      for (int ct = 0; ct < 2; ++ct) x2[rgrp * 64 + ct * 32 + c32] = make_float2(m_ref[ct], l_run[ct]);
     }
     __syncthreads();
     if (sgrp == 0 && h == 0) {
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct) {
         const float2 o = x2[rgrp * 64 + ct * 32 + c32];
-        ml_combine(m_run[ct], l_run[ct], o.x, o.y);
-        if (res_row[ct] < Mq) part[(size_t)split * mq_pad + res_row[ct]] = make_float2(m_run[ct], l_run[ct]);
+        ml_combine(m_ref[ct], l_run[ct], o.x, o.y);
+        if (res_row[ct] < Mq) part[(size_t)split * mq_pad + res_row[ct]] = make_float2(m_ref[ct], l_run[ct]);
       }
     }
   } else {
@@ -354,7 +492,7 @@ __global__ __launch_bounds__(256) void score_cols_fma_kernel(
   const int N = (int)(row_off[unit + 1] - row0);
   if (tile * 256 >= N) return;
   const int Mq = kp.Mq;
-  fill_neg_lse(rowstat + (size_t)unit * n_splits * mq_pad, n_splits, mq_pad, Mq, negL, tid, 256);
+  fill_neg_lse(rowstat + (size_t)unit * n_splits * mq_pad, n_splits, mq_pad, Mq, negL, tid, 256, mq_pad);
   __syncthreads();
   const int j = tile * 256 + tid;
   const bool ok = j < N;
@@ -377,7 +515,7 @@ __global__ __launch_bounds__(256) void score_cols_fma_kernel(
 
 template <typename T, int D>
 hipError_t launch_fma(const KParams& kp, const Batch& b, const Workspace& wl, char* ws,
-                      float* scores, hipStream_t st) {
+                      float* scores, hipStream_t st, hipEvent_t between) {
   float2* rowstat = reinterpret_cast<float2*>(ws + wl.rowstat);
   const int units8 = (b.n_units + 7) / 8 * 8;
   const int qblocks = (kp.Mq + 63) / 64;
@@ -385,6 +523,7 @@ hipError_t launch_fma(const KParams& kp, const Batch& b, const Workspace& wl, ch
   score_rows_fma_kernel<T, D><<<dim3(units8 * tilesA), dim3(256), 0, st>>>(
       kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off,
       static_cast<const T*>(b.K), static_cast<const T*>(b.Q), rowstat);
+  if (between) (void)hipEventRecord(between, st);
   const int tilesB = (b.max_unit_len + 255) / 256;
   score_cols_fma_kernel<T, D><<<dim3(units8 * tilesB), dim3(256), wl.mq_pad * sizeof(float), st>>>(
       kp, b.n_units, tilesB, wl.n_splits, wl.mq_pad, b.row_off, static_cast<const T*>(b.K),
@@ -399,13 +538,13 @@ bool score_uses_mfma(const KParams& kp) {
 }
 
 hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, char* ws,
-                        float* scores, hipStream_t st) {
+                        float* scores, hipStream_t st, hipEvent_t between) {
   if (!score_uses_mfma(kp)) {
     if (kp.dtype == CASK_F32)
-      return kp.d == 64 ? launch_fma<float, 64>(kp, b, wl, ws, scores, st)
-                        : launch_fma<float, 128>(kp, b, wl, ws, scores, st);
-    return kp.d == 64 ? launch_fma<uint16_t, 64>(kp, b, wl, ws, scores, st)
-                      : launch_fma<uint16_t, 128>(kp, b, wl, ws, scores, st);
+      return kp.d == 64 ? launch_fma<float, 64>(kp, b, wl, ws, scores, st, between)
+                        : launch_fma<float, 128>(kp, b, wl, ws, scores, st, between);
+    return kp.d == 64 ? launch_fma<uint16_t, 64>(kp, b, wl, ws, scores, st, between)
+                      : launch_fma<uint16_t, 128>(kp, b, wl, ws, scores, st, between);
   }
   float2* rowstat = reinterpret_cast<float2*>(ws + wl.rowstat);
   const int units8 = (b.n_units + 7) / 8 * 8;
@@ -413,7 +552,7 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   const uint16_t* Q = static_cast<const uint16_t*>(b.Q);
   static bool attr_set = false;
   const size_t ldsA = 2 * Geo<0>::STAGE_ROWS * kPitch + 128 * sizeof(float2);
-  const size_t ldsB = 2 * Geo<1>::STAGE_ROWS * kPitch + (size_t)wl.mq_pad * sizeof(float);
+  const size_t ldsB = 2 * Geo<1>::STAGE_ROWS * kPitch + (size_t)(wl.mq_pad + Geo<1>::STAGE_ROWS) * sizeof(uint2);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<0>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
@@ -428,6 +567,7 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   score_mfma_kernel<0><<<dim3(units8 * tilesA), dim3(256), ldsA, st>>>(
       kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off, K, Q, rowstat,
       scores);
+  if (between) (void)hipEventRecord(between, st);
   const int tilesB = (b.max_unit_len + Geo<1>::RES_ROWS - 1) / Geo<1>::RES_ROWS;
   score_mfma_kernel<1><<<dim3(units8 * tilesB), dim3(256), ldsB, st>>>(
       kp, b.n_units, tilesB, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off, K, Q, rowstat,

@@ -141,6 +141,34 @@ def test_ragged_batch_llama_shape():
     _note(parity.full_check(c, parity.params_of(w)))
 
 
+def test_score_with_steep_logit_ramps():
+    """Logits that climb (or fall) by hundreds of octaves along the cache: the running
+    reference of the row statistics has to be raised many times without losing mass."""
+    d, Wn, G = 128, 16, 3
+    rng = np.random.default_rng(4)
+    N = 6000
+    q = rng.standard_normal(d).astype(np.float32)
+    q /= np.linalg.norm(q)
+    for direction in (+1, -1):
+        ramp = np.linspace(0.0, 1.0, N, dtype=np.float32)
+        if direction < 0:
+            ramp = ramp[::-1].copy()
+        # logit_j = scale * |Q| * ramp_j * gain  ->  up to ~500 in base-2 units
+        K = (ramp[:, None] * q[None, :] * 60.0 + 0.05 * rng.standard_normal((N, d))).astype(np.float32)
+        Qm = (q[None, :] * 66.0 + 0.1 * rng.standard_normal((Wn * G, d))).astype(np.float32)
+        c = dict(K=torch.from_numpy(K).to(torch.bfloat16), V=torch.from_numpy(K).to(torch.bfloat16),
+                 Q=torch.from_numpy(Qm).to(torch.bfloat16).reshape(1, Wn, G, d),
+                 row_off=torch.tensor([0, N], dtype=torch.int64), prefix_len=torch.tensor([0], dtype=torch.int32))
+        p = cask.Params(dtype=cask.BF16, head_dim=d, q_per_kv=G, window=Wn, budget=64)
+        row_off, prefix_len, Kb, Vb, Qb = parity.host_arrays(c)
+        want = ref.score(parity.ref_params(p), row_off, Kb, Qb)
+        got = cask.score(parity.to_device(c, p))
+        torch.cuda.synchronize()
+        assert np.isfinite(got.cpu().numpy()).all()
+        err = parity.check_scores(got.cpu().numpy(), want, row_off)
+        _note((direction, "max score", float(want.max()), "rel err", err))
+
+
 # ------------------------------------------------------------------ selection under ties
 
 @pytest.mark.parametrize("quant", [0, 3, 50])
