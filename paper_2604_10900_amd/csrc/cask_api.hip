@@ -17,7 +17,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, int max_unit_len) {
   Workspace w;
   std::memset(&w, 0, sizeof(w));
-  int split_len = 2048;
+  int split_len = 1024;
   if (const char* e = std::getenv("CASK_SPLIT_LEN")) {
     const int v = std::atoi(e);
     if (v >= 128) split_len = v / 128 * 128;
@@ -40,6 +40,7 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
   };
   const size_t rows = (size_t)total_rows, units = (size_t)n_units;
   w.rowstat = take(units * n_splits * w.mq_pad * sizeof(float2));
+  w.bias = take(units * w.mq_pad * sizeof(uint4));
   w.scores = take(rows * sizeof(float));
   w.role = take(rows);
   w.slot_of = take(rows * sizeof(int32_t));

@@ -67,28 +67,19 @@ __device__ inline bool map_block(int n_units, int tiles_per_unit, int& unit, int
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;
-constexpr int kPitch = 272;  // LDS row pitch in bytes: 256 + 16 keeps b128 reads conflict-free
-
-template <int MODE>
-struct Geo;
-template <>
-struct Geo<0> {  // sweep A: resident = window rows (Q), stream = keys (K)
-  static constexpr int RES_ROWS = 128, STAGE_ROWS = 128;  // 2 resident x 2 stream wave groups
-};
-template <>
-struct Geo<1> {  // sweep B: resident = keys (K), stream = window rows (Q)
-  static constexpr int RES_ROWS = 256, STAGE_ROWS = 64;   // 4 resident wave groups
-};
-
-// Raw buffer descriptor over [p, p + bytes): loads past the end return zero, so ragged stream
-// tiles need no per-lane bounds test.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
-  // stride 0 (raw byte addressing), `bytes` records, 32-bit data format
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
-}
+constexpr int kRowBytes = kD * 2;
+constexpr int kWaves = 8;                    // waves per workgroup, 2 per SIMD
+constexpr int kThreads = kWaves * 64;
+constexpr int kResRows = kWaves * 64;        // resident rows per workgroup (64 per wave)
+constexpr int kStageRows = 64;               // stream rows per ring slot
+constexpr int kGroupPitch = 1024 + 64;       // LDS pitch of a 4-row group (see stage layout)
+constexpr int kDataBytes = (kStageRows / 4) * kGroupPitch;
+constexpr int kStageBytes = kDataBytes + kStageRows * 16;  // + one 16-byte bias entry per row (sweep B)
+constexpr int kDepth = 6;                    // ring slots: loads run kDepth - 1 stages ahead
+constexpr int kLoadsPerThread = kStageRows * 16 / kThreads;  // 16-byte pieces per thread per stage
 
 // Pad value of -L for window rows past W*G: large, finite (inf would turn 0 * inf into NaN
 // inside the matrix core), and far enough down that exp2 flushes to zero.
@@ -103,53 +94,79 @@ __device__ inline void split3_bf16(float x, uint16_t& hi, uint16_t& mid, uint16_
   lo = float_to_bf16_bits(r2);
 }
 
-// One workgroup = 4 waves.  Each wave keeps 64 resident rows (two 32-column MFMA tiles) in
-// registers and walks the staged stream rows 32 at a time.  Per stage a wave runs four tiles
-//   (rt0,ct0) (rt0,ct1) (rt1,ct0) (rt1,ct1)
-// software-pipelined: the MFMA chain of a tile is issued interleaved, two logits per MFMA,
-// with the exp2 epilogue of the tile before it, so the matrix cores and the vector ALU of a
-// wave run at the same time; the epilogue of the last tile of a stage rides on the first chain
-// of the next stage.
+// Per window row of a unit: -L_row / c as three bf16 (8 bytes), L_row the base-2 log-sum-exp
+// combined over the key splits of sweep A.  Sweep B feeds it to the matrix cores as a ninth
+// k-step, so its epilogue needs no per-row operand.
+__global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_splits, int mq_pad,
+                                                         const float2* __restrict__ rowstat,
+                                                         uint4* __restrict__ bias) {
+  const int unit = blockIdx.x;
+  const float inv_c = 1.0f / kp.scale_log2;
+  const float2* part = rowstat + (size_t)unit * n_splits * mq_pad;
+  for (int r = threadIdx.x; r < mq_pad; r += 256) {
+    float nl = kPadNegL;
+    if (r < kp.Mq) {
+      float m = kNegInf, l = 0.f;
+      for (int sp = 0; sp < n_splits; ++sp) {
+        const float2 pr = part[(size_t)sp * mq_pad + r];
+        ml_combine(m, l, pr.x, pr.y);
+      }
+      nl = -(m + log2f(l));
+    }
+    uint16_t b0, b1, b2;
+    split3_bf16(nl * inv_c, b0, b1, b2);
+    bias[(size_t)unit * mq_pad + r] = make_uint4((uint32_t)b0 | ((uint32_t)b1 << 16), (uint32_t)b2, 0, 0);
+  }
+}
+
+// Both scoring sweeps.  MODE 0 = sweep A (resident: window rows, stream: keys),
+// MODE 1 = sweep B (resident: keys, stream: window rows).
 //
-// Epilogue cost is the bound (fma/mul + exp2 + add per logit on the vector ALU against
-// 256 matrix flops), so it is kept to exactly those three instructions:
-//   sweep A  the running maximum is lazy: exp2 is taken against a per-lane reference that
-//            is only raised when a tile's sum threatens fp32 range (checked once per tile),
-//            which is exact because (reference, sum) pairs combine exactly;
-//   sweep B  -L_row is carried into the accumulator by a ninth k-step: the staged window row
-//            is extended by three bf16 that add up to -L_row / c and meet ones in the
-//            resident operand, so the epilogue is mul, exp2, add with no per-row operand.
-// Stages that touch masked keys (causal tail, ragged end) or initialise the reference take
-// a plain, unpipelined path with explicit masks.
+// Workgroup: 8 waves; wave w keeps resident rows [64 w, 64 w + 64) of the workgroup's 512 as
+// MFMA B-operands in registers.  Stream rows arrive 64 at a time in a ring of LDS slots,
+// written by direct global->LDS loads (no register staging, no LDS stores) that run
+// kDepth - 1 stages ahead of the stage being consumed; one barrier per stage both publishes a
+// slot and frees the one consumed before it.
+//
+// Stage layout in LDS: each load instruction of a wave lands 1 KB = four 256-byte rows; lane s
+// fetches 16-byte piece s / 4 of row s % 4, so the group holds piece-major data
+// (piece g of row r at g * 64 + r * 16).  A wave reading A-operands (lane = row) then touches
+// 16 consecutive bytes per row and groups 1088 bytes apart: conflict-free, and the eight
+// k-steps are plain immediate offsets (128 bytes apart).
+//
+// Per stage a wave runs four 32x32 tiles (rt0,ct0) (rt0,ct1) (rt1,ct0) (rt1,ct1),
+// software-pipelined: the MFMA chain of a tile is issued interleaved, two logits per MFMA, with
+// the exp2 epilogue of the tile before it, so the matrix cores and the vector ALU of a wave
+// run at the same time; the epilogue of a stage's last tile rides on the next stage's first
+// chain.  The epilogue is exactly three vector instructions per logit:
+//   sweep A  fma, exp2, add: the running maximum is lazy -- exp2 is taken against a per-lane
+//            reference that is only raised when a tile's sum threatens fp32 range (one test
+//            per tile); exact, because (reference, sum) pairs combine exactly;
+//   sweep B  mul, exp2, add: -L_row is already in the accumulator (ninth k-step: the bias
+//            terms meet ones in the resident operand).
+// Stages that touch masked keys (causal tail, ragged end) or initialise the reference take a
+// plain, unpipelined path with explicit masks.
 template <int MODE>
-__global__ __launch_bounds__(256, 2) void score_mfma_kernel(
+__global__ __launch_bounds__(kThreads, 1) void score_mfma_kernel(
     KParams kp, int n_units, int tiles_per_unit, int n_splits, int split_len, int mq_pad,
     const int64_t* __restrict__ row_off, const uint16_t* __restrict__ K,
-    const uint16_t* __restrict__ Q, float2* __restrict__ rowstat, float* __restrict__ scores) {
-  using G_ = Geo<MODE>;
-  constexpr int STAGE_ROWS = G_::STAGE_ROWS;
-  constexpr int CHUNKS = STAGE_ROWS * 16 / 256;  // 16-byte chunks per thread per stage
-  constexpr int NK = (MODE == 0) ? 8 : 9;        // k-steps per tile
+    const uint16_t* __restrict__ Q, float2* __restrict__ rowstat,
+    const uint4* __restrict__ bias, float* __restrict__ scores) {
+  constexpr int NK = (MODE == 0) ? 8 : 9;  // k-steps per tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  unsigned char* stage0 = smem;
-  unsigned char* stage1 = smem + STAGE_ROWS * kPitch;
-  // MODE 1: per window row, -L_row / c as three bf16 packed in 8 bytes; MODE 0: exchange area
-  uint2* bias_tab = reinterpret_cast<uint2*>(smem + 2 * STAGE_ROWS * kPitch);
-  float* xchg = reinterpret_cast<float*>(bias_tab);
+  unsigned char* ring = smem;
 
   int unit, tile;
   if (!map_block(n_units, tiles_per_unit, unit, tile)) return;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c32 = lane & 31, h = lane >> 5;
-  const int rgrp = (MODE == 0) ? (wv & 1) : wv;
-  const int sgrp = (MODE == 0) ? (wv >> 1) : 0;
   const int64_t row0 = row_off[unit];
   const int N = (int)(row_off[unit + 1] - row0);
   const int Mq = kp.Mq, W = kp.W, Gq = kp.G;
   const float c = kp.scale_log2;
   const uint16_t* Ku = K + (size_t)row0 * kD;
   const uint16_t* Qu = Q + (size_t)unit * Mq * kD;
-  float2* part = rowstat + (size_t)unit * n_splits * mq_pad;
 
   // ---- what this workgroup covers
   const uint16_t* res_ptr;
@@ -159,7 +176,7 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(
   if (MODE == 0) {
     const int qb = tile / n_splits;
     split = tile % n_splits;
-    res_base = qb * G_::RES_ROWS;
+    res_base = qb * kResRows;
     if (res_base >= Mq) return;
     res_ptr = Qu;
     res_limit = Mq;
@@ -167,49 +184,34 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(
     s_begin = split * split_len;
     s_end = min(N, s_begin + split_len);
     if (kp.causal) {
-      const int last_row = min(Mq, res_base + G_::RES_ROWS) - 1;
+      const int last_row = min(Mq, res_base + kResRows) - 1;
       s_end = min(s_end, N - W + last_row / Gq + 1);
     }
   } else {
-    res_base = tile * G_::RES_ROWS;
+    res_base = tile * kResRows;
     if (res_base >= N) return;
     res_ptr = Ku;
     res_limit = N;
     str_ptr = Qu;
     s_begin = 0;
     s_end = Mq;
-    if (kp.causal && res_base > N - W) s_begin = (((res_base - (N - W)) * Gq) / STAGE_ROWS) * STAGE_ROWS;
-    const float inv_c = 1.0f / c;
-    // one stage of slack: the prefetch of the stage after the last one reads it
-    for (int r = tid; r < mq_pad + STAGE_ROWS; r += 256) {
-      float nl = kPadNegL;
-      if (r < Mq) {
-        float m = kNegInf, l = 0.f;
-        for (int sp = 0; sp < n_splits; ++sp) {
-          const float2 pr = part[(size_t)sp * mq_pad + r];
-          ml_combine(m, l, pr.x, pr.y);
-        }
-        nl = -(m + log2f(l));
-      }
-      uint16_t b0, b1, b2;
-      split3_bf16(nl * inv_c, b0, b1, b2);
-      bias_tab[r] = make_uint2((uint32_t)b0 | ((uint32_t)b1 << 16), (uint32_t)b2);
-    }
-    __syncthreads();  // the first stash reads the table
+    if (kp.causal && res_base > N - W) s_begin = (((res_base - (N - W)) * Gq) / kStageRows) * kStageRows;
   }
+  const int n_stages = (s_end - s_begin + kStageRows - 1) / kStageRows;
 
   // ---- resident fragments: lane (c32, h) holds row c32 of each 32-row tile, k-chunk h
   bf16x8 bres[2][NK];
   int res_row[2];
 #pragma unroll
   for (int ct = 0; ct < 2; ++ct) {
-    const int r = res_base + rgrp * 64 + ct * 32 + c32;
+    const int r = res_base + wv * 64 + ct * 32 + c32;
     res_row[ct] = r;
     const bool ok = r < res_limit;
-    const uint4* src = reinterpret_cast<const uint4*>(res_ptr + (size_t)(ok ? r : 0) * kD) + h;
+    const uint4* src = reinterpret_cast<const uint4*>(res_ptr + (size_t)(ok ? r : res_base) * kD) + h;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      uint4 v = ok ? src[ks * 2] : make_uint4(0, 0, 0, 0);
+      uint4 v = src[ks * 2];
+      if (!ok) v = make_uint4(0, 0, 0, 0);
       bres[ct][ks] = *reinterpret_cast<bf16x8*>(&v);
     }
     if (NK == 9) {  // ones that pick up the three bias terms; the upper k-half contributes nothing
@@ -217,6 +219,50 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(
       bres[ct][NK - 1] = *reinterpret_cast<bf16x8*>(&v);
     }
   }
+  // a wave whose resident rows are all past the end only helps with loads and barriers
+  const bool wave_live = res_base + wv * 64 < res_limit;
+
+  // ---- ring loads: thread t, piece j covers LDS slot t + 512 j of the stage:
+  //      row = 4 * (slot / 64) + slot % 4, 16-byte piece = (slot % 64) / 4
+  const __amdgpu_buffer_rsrc_t rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(str_ptr), 0,
+                                        max(s_end, 0) * kRowBytes, 0x00020000);
+  int ld_voff[kLoadsPerThread];
+#pragma unroll
+  for (int j = 0; j < kLoadsPerThread; ++j) {
+    const int grp = wv + kWaves * j;  // 4-row group of the stage this wave's load j fills
+    ld_voff[j] = (grp * 4 + (lane & 3)) * kRowBytes + (lane >> 2) * 16;
+  }
+  // sweep B: the bias entries of a stage's 64 rows are one more 1 KB load, taken in turn by
+  // the waves (stage % 8), so every wave has at most one extra load in flight
+  const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint4*>(bias + (size_t)unit * mq_pad), 0, mq_pad * 16, 0x00020000);
+  auto issue_stage = [&](int stage) {  // rows past s_end read as zero through the descriptor
+    unsigned char* slot = ring + (stage % kDepth) * kStageBytes;
+    const int soff = (s_begin + stage * kStageRows) * kRowBytes;
+    if (MODE == 1 && (stage & (kWaves - 1)) == wv)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          brsrc, (__attribute__((address_space(3))) void*)(slot + kDataBytes), 16, lane * 16,
+          (s_begin + stage * kStageRows) * 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < kLoadsPerThread; ++j) {
+      const int grp = wv + kWaves * j;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          rsrc, (__attribute__((address_space(3))) void*)(slot + grp * kGroupPitch),
+          16, ld_voff[j], soff, 0, 0);
+    }
+  };
+
+  // A-operand rows of this lane inside a stage: row rt * 32 + c32 -> group, row-in-group
+  const int a_off = (c32 >> 2) * kGroupPitch + (c32 & 3) * 16 + h * 64;
+  auto load_a = [&](bf16x8(&a)[NK], const unsigned char* slot, int rt) {
+    const unsigned char* p = slot + rt * 8 * kGroupPitch + a_off;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(p + ks * 128);
+    if (NK == 9) {
+      a[NK - 1] = *reinterpret_cast<const bf16x8*>(slot + kDataBytes + (rt * 32 + c32) * 16);
+    }
+  };
 
   // per-lane reduction state
   float m_ref[2] = {kNegInf, kNegInf}, l_run[2] = {0.f, 0.f};  // sweep A
@@ -226,36 +272,10 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(
   for (int ct = 0; ct < 2; ++ct)
     vis_limit[ct] = (MODE == 0) ? (kp.causal ? N - W + res_row[ct] / Gq : N - 1) : res_row[ct];
   const int tail_start = kp.causal ? N - W : N;  // keys > tail_start are hidden from some row
-
-  const int n_stages = (s_end - s_begin + STAGE_ROWS - 1) / STAGE_ROWS;
-  // stream rows come through a buffer descriptor that ends at row s_end
-  const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(str_ptr, (uint32_t)max(s_end, 0) * (uint32_t)(kD * 2));
-  const int voff = tid * 16;  // thread t: row t / 16 of a 16-row group, 16-byte chunk t % 16
-  u32x4 pre[CHUNKS];
-  auto fetch = [&](int stage) {
-    const int sbase = (s_begin + stage * STAGE_ROWS) * (kD * 2);
+  int first_row[2];  // sweep B: first window row that sees the lane's key
 #pragma unroll
-    for (int i = 0; i < CHUNKS; ++i)
-      pre[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, sbase + i * 16 * kD * 2, 0);
-  };
-  auto stash = [&](unsigned char* buf, int stage) {
-#pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) {
-      const int q = tid + 256 * i;
-      *reinterpret_cast<u32x4*>(buf + (q >> 4) * kPitch + (q & 15) * 16) = pre[i];
-      if (MODE == 1 && (q & 15) == 0) {
-        // the row's pad chunk carries its bias terms into the ninth k-step
-        const uint2 bt = bias_tab[s_begin + stage * STAGE_ROWS + (q >> 4)];
-        *reinterpret_cast<uint4*>(buf + (q >> 4) * kPitch + 256) = make_uint4(bt.x, bt.y, 0, 0);
-      }
-    }
-  };
-  auto load_a = [&](bf16x8(&a)[NK], const unsigned char* buf, int rt) {
-    const unsigned char* rowp = buf + (sgrp * 64 + rt * 32 + c32) * kPitch;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(rowp + h * 16 + ks * 32);
-    if (NK == 9) a[NK - 1] = *reinterpret_cast<const bf16x8*>(rowp + 256);
-  };
+  for (int ct = 0; ct < 2; ++ct)
+    first_row[ct] = (MODE == 1 && kp.causal) ? max(0, (res_row[ct] - (N - W)) * Gq) : 0;
 
   // ---- epilogues
   float tsum = 0.f;  // sweep A: sum of the tile in flight
@@ -264,9 +284,13 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(
       const float nm = -m_ref[ct];
       tsum += fast_exp2(__builtin_fmaf(acc[2 * i], c, nm));
       tsum += fast_exp2(__builtin_fmaf(acc[2 * i + 1], c, nm));
+      // pin the partial sum here: without it the optimiser is free to sink these pieces out
+      // of the MFMA chain they are meant to overlap with
+      asm volatile("" : "+v"(tsum));
     } else {
       colsum[ct] += fast_exp2(acc[2 * i] * c);
       colsum[ct] += fast_exp2(acc[2 * i + 1] * c);
+      asm volatile("" : "+v"(colsum[ct]));
     }
   };
   // exact online-softmax update of (m_ref, l_run) with the 16 logits of `acc` (masked = -inf)
@@ -302,12 +326,13 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(
       }
       exact_update(acc, ct);
     } else {
+      // window row r sits at slot N - W + r / G, so key j is visible to it iff
+      // r >= (j - (N - W)) * G: one comparison against a per-lane constant
       float sum = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = trow0 + (r >> 2) * 8 + h * 4 + (r & 3);
-        const int tw = N - W + row / Gq;
-        const float y = (kp.causal && vis_limit[ct] > tw) ? kNegInf : acc[r] * c;
+        const float y = (row < first_row[ct]) ? kNegInf : acc[r] * c;
         sum += fast_exp2(y);
       }
       colsum[ct] += sum;
@@ -337,85 +362,106 @@ __global__ __launch_bounds__(256, 2) void score_mfma_kernel(
     finish_fast(acc_old, ct_old);
   };
 
+  // ---- main loop over ring stages
   if (n_stages > 0) {
-    fetch(0);
-    stash(stage0, 0);
+#pragma unroll
+    for (int s = 0; s < kDepth - 1; ++s) issue_stage(s);
   }
-  __syncthreads();
-
-  // sweep B masks only in the key blocks that reach into the window; sweep A per stage
-  const bool blk_slow = (MODE == 1) && kp.causal && (res_base + G_::RES_ROWS - 1 > tail_start);
+  // Once per stage: this thread's pieces of stages `it` and `it + 1` have landed when at most
+  // (kDepth - 3) later stages of its loads are still in flight; the barrier extends that to
+  // every thread's pieces and tells everyone that the slot consumed in the previous iteration
+  // is free, so the next load can go there.  Being one stage ahead lets a wave fetch the next
+  // stage's first operands from LDS while it is still busy with this one.  The barrier is
+  // bare: a fence here would drain the whole ring.
+  auto stage_sync = [&](int it) {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (((kDepth - 3) * kLoadsPerThread) & 0xF) |
+                               ((((kDepth - 3) * kLoadsPerThread) >> 4) << 14));
+    __builtin_amdgcn_s_barrier();
+    issue_stage(it + kDepth - 1);
+  };
+  auto slot_of = [&](int it) -> const unsigned char* { return ring + (it % kDepth) * kStageBytes; };
   f32x16 acc0, acc1;
   bf16x8 a0[NK], a1[NK];
-  bool carry = false;  // the last tile of the previous stage (acc1, ct 1) still owes its epilogue
-  for (int it = 0; it < n_stages; ++it) {
-    unsigned char* cur = (it & 1) ? stage1 : stage0;
-    unsigned char* nxt = (it & 1) ? stage0 : stage1;
-    const int stage_base = s_begin + it * STAGE_ROWS;
-    const int wrow0 = stage_base + sgrp * 64;  // first stream row of this wave in the stage
-    bool slow;
-    if (MODE == 0)
-      slow = (it == 0) || (stage_base + STAGE_ROWS - 1 > tail_start) || (stage_base + STAGE_ROWS > s_end);
-    else
-      slow = blk_slow;
-    fetch(it + 1);  // past the last stage the descriptor returns zeros
-    if (slow) {
-      if (carry) {
-        drain(acc1, 1);
-        carry = false;
-      }
+  auto slow_stage = [&](int it) {
+    const unsigned char* cur = slot_of(it);
+    const int stage_base = s_begin + it * kStageRows;
 #pragma unroll
-      for (int rt = 0; rt < 2; ++rt) {
-        const int trow0 = wrow0 + rt * 32;
-        if (trow0 >= s_end) continue;
-        load_a(a0, cur, rt);
+    for (int rt = 0; rt < 2; ++rt) {
+      const int trow0 = stage_base + rt * 32;
+      if (trow0 >= s_end) continue;
+      load_a(a0, cur, rt);
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
-          chain(acc0, a0, ct);
-          slow_tile(acc0, ct, trow0);
-        }
+      for (int ct = 0; ct < 2; ++ct) {
+        chain(acc0, a0, ct);
+        slow_tile(acc0, ct, trow0);
       }
-      if (MODE == 0) {
-        // a lane that saw nothing yet takes 0 as its reference: (0, 0) is the empty sum
+    }
+    if (MODE == 0) {
+      // a lane that saw nothing yet takes 0 as its reference: (0, 0) is the empty sum
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-          if (m_ref[ct] == kNegInf) m_ref[ct] = 0.f;
-      }
-    } else {
-      load_a(a0, cur, 0);
-      if (carry) fused(acc0, a0, 0, acc1, 1); else chain(acc0, a0, 0);
+      for (int ct = 0; ct < 2; ++ct)
+        if (m_ref[ct] == kNegInf) m_ref[ct] = 0.f;
+    }
+  };
+
+  // stages [f0, f1) run the pipelined path; the ones before and after take the masked path.
+  // Sweep A: stage 0 initialises the reference, the causal tail and the ragged end are masked.
+  // Sweep B: a wave is masked throughout iff its keys reach into the window.
+  int f0, f1;
+  if (MODE == 0) {
+    f0 = 1;
+    const int clean_rows = min(tail_start + 1, s_end) - s_begin;  // keys every row sees
+    f1 = clean_rows > 0 ? clean_rows / kStageRows : 0;
+  } else {
+    const bool wave_slow = kp.causal && (res_base + wv * 64 + 63 > tail_start);
+    f0 = 0;
+    f1 = wave_slow ? 0 : n_stages;
+  }
+  f0 = min(f0, n_stages);
+  f1 = max(min(f1, n_stages), f0);
+  if (!wave_live) f0 = f1 = n_stages;  // only loads and barriers: the first loop below
+
+  int it = 0;
+  for (; it < f0 && it < n_stages; ++it) {
+    stage_sync(it);
+    if (wave_live) slow_stage(it);
+  }
+  if (f1 > f0) {
+    stage_sync(f0);
+    load_a(a0, slot_of(f0), 0);
+    chain(acc0, a0, 0);
+    for (it = f0;; ++it) {
+      const unsigned char* cur = slot_of(it);
       load_a(a1, cur, 1);
       fused(acc1, a0, 1, acc0, 0);
+      load_a(a0, slot_of(it + 1), 0);  // a0 is free: operands of the coming stage
       fused(acc0, a1, 0, acc1, 1);
       fused(acc1, a1, 1, acc0, 0);
-      carry = true;
+      if (it + 1 >= f1) break;
+      stage_sync(it + 1);
+      fused(acc0, a0, 0, acc1, 1);
     }
-    stash(nxt, it + 1);
-    __syncthreads();
+    drain(acc1, 1);
+    it = f1;
   }
-  if (carry) drain(acc1, 1);
+  for (; it < n_stages; ++it) {
+    stage_sync(it);
+    if (wave_live) slow_stage(it);
+  }
+  // loads issued past the last stage may still be landing in LDS: let them finish before the
+  // workgroup's LDS can be handed to another one
+  __builtin_amdgcn_s_waitcnt(0x0F70);
 
   // ---- finish
   if (MODE == 0) {
+    float2* part = rowstat + (size_t)unit * n_splits * mq_pad;
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct) {
       const float m2 = __shfl_xor(m_ref[ct], 32, 64);
       const float l2 = __shfl_xor(l_run[ct], 32, 64);
       ml_combine(m_ref[ct], l_run[ct], m2, l2);
-    }
-    float2* x2 = reinterpret_cast<float2*>(xchg);
-    if (sgrp == 1 && h == 0) {
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct) x2[rgrp * 64 + ct * 32 + c32] = make_float2(m_ref[ct], l_run[ct]);
-    }
-    __syncthreads();
-    if (sgrp == 0 && h == 0) {
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        const float2 o = x2[rgrp * 64 + ct * 32 + c32];
-        ml_combine(m_ref[ct], l_run[ct], o.x, o.y);
-        if (res_row[ct] < Mq) part[(size_t)split * mq_pad + res_row[ct]] = make_float2(m_ref[ct], l_run[ct]);
-      }
+      if (h == 0 && res_row[ct] < Mq)
+        part[(size_t)split * mq_pad + res_row[ct]] = make_float2(m_ref[ct], l_run[ct]);
     }
   } else {
     const float inv = 1.0f / (float)Mq;
@@ -534,7 +580,7 @@ hipError_t launch_fma(const KParams& kp, const Batch& b, const Workspace& wl, ch
 }  // namespace
 
 bool score_uses_mfma(const KParams& kp) {
-  return kp.dtype == CASK_BF16 && kp.d == 128 && kp.Mq <= 8192;
+  return kp.dtype == CASK_BF16 && kp.d == 128;
 }
 
 hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, char* ws,
@@ -547,30 +593,32 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
                       : launch_fma<uint16_t, 128>(kp, b, wl, ws, scores, st, between);
   }
   float2* rowstat = reinterpret_cast<float2*>(ws + wl.rowstat);
+  uint4* bias = reinterpret_cast<uint4*>(ws + wl.bias);
   const int units8 = (b.n_units + 7) / 8 * 8;
   const uint16_t* K = static_cast<const uint16_t*>(b.K);
   const uint16_t* Q = static_cast<const uint16_t*>(b.Q);
   static bool attr_set = false;
-  const size_t ldsA = 2 * Geo<0>::STAGE_ROWS * kPitch + 128 * sizeof(float2);
-  const size_t ldsB = 2 * Geo<1>::STAGE_ROWS * kPitch + (size_t)(wl.mq_pad + Geo<1>::STAGE_ROWS) * sizeof(uint2);
+  const size_t ldsA = (size_t)kDepth * kStageBytes;
+  const size_t ldsB = ldsA;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<0>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<1>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int qblocks = (kp.Mq + Geo<0>::RES_ROWS - 1) / Geo<0>::RES_ROWS;
+  const int qblocks = (kp.Mq + kResRows - 1) / kResRows;
   const int tilesA = qblocks * wl.n_splits;
-  score_mfma_kernel<0><<<dim3(units8 * tilesA), dim3(256), ldsA, st>>>(
-      kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off, K, Q, rowstat,
+  score_mfma_kernel<0><<<dim3(units8 * tilesA), dim3(kThreads), ldsA, st>>>(
+      kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off, K, Q, rowstat, bias,
       scores);
+  score_bias_kernel<<<dim3(b.n_units), dim3(256), 0, st>>>(kp, wl.n_splits, wl.mq_pad, rowstat, bias);
   if (between) (void)hipEventRecord(between, st);
-  const int tilesB = (b.max_unit_len + Geo<1>::RES_ROWS - 1) / Geo<1>::RES_ROWS;
-  score_mfma_kernel<1><<<dim3(units8 * tilesB), dim3(256), ldsB, st>>>(
-      kp, b.n_units, tilesB, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off, K, Q, rowstat,
+  const int tilesB = (b.max_unit_len + kResRows - 1) / kResRows;
+  score_mfma_kernel<1><<<dim3(units8 * tilesB), dim3(kThreads), ldsB, st>>>(
+      kp, b.n_units, tilesB, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off, K, Q, rowstat, bias,
       scores);
   return hipGetLastError();
 }
