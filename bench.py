@@ -27,9 +27,13 @@ METRIC = "KV tokens compressed/s per layer x head at budget 384; % HBM/MFMA roof
 PEAK_MFMA_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs, scaled by a copy kernel of known size (see profiles/); None where not measured.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch of the two scoring sweeps from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this file, each counter scaled by what it reads for a conversion kernel of known
+# traffic (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0; profiles/cfg2_hbm_traffic.md).  None where
+# not measured.
+MEASURED_TRAFFIC = {
+    "cfg2": {"score_rows": (130947.5 * 2.0 + 1568.0) * 1024, "score_cols": (134943.2 * 2.0 + 3696.0) * 1024},
+}
 
 
 def parse():
@@ -43,6 +47,10 @@ def parse():
     ap.add_argument("--copies", type=int, default=0,
                     help="input copies alternated between steps (0 = 2 when they fit in 2 GB)")
     ap.add_argument("--cpu-units", type=int, default=16, help="units the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--pmc-copy-mib", type=int, default=0,
+                    help="also run one fp32 -> bf16 conversion of a buffer of this many MiB (a kernel of "
+                         "known traffic, N MiB read and N/2 MiB written, for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="do not record per-kernel HIP events inside the timed region")
     return ap.parse_args()
@@ -98,6 +106,12 @@ def main():
     def step(i):
         cask.compress(batches[i % copies][1], outs)
 
+    if args.pmc_copy_mib > 0:
+        src = torch.rand((args.pmc_copy_mib << 20) // 4, dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        dst = src.to(torch.bfloat16)
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -133,7 +147,8 @@ def main():
         roof = {"bound": "mfma", "kernel": "score_mfma_kernel<%d> (%s)" % (0 if dom == "score_rows" else 1, dom),
                 "achieved": round(achieved, 2), "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC.get(args.workload),
+                "traffic": (MEASURED_TRAFFIC.get(args.workload, {}).get(dom)
+                            if args.layers == 0 and args.seqs == 0 else None),
                 "kernel_ms": round(stage_ms[dom], 4),
                 "flops_per_launch": flops_pass,
                 "both_sweeps_frac": round(2 * flops_pass / ((stage_ms["score_rows"] + stage_ms["score_cols"]) * 1e-3)

@@ -17,18 +17,28 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, int max_unit_len) {
   Workspace w;
   std::memset(&w, 0, sizeof(w));
-  int split_len = 1024;
-  if (const char* e = std::getenv("CASK_SPLIT_LEN")) {
-    const int v = std::atoi(e);
-    if (v >= 128) split_len = v / 128 * 128;
+  // Key splits of the row-statistics sweep.  Long splits amortise the unpipelined first stage
+  // of every split; short ones are only worth it when there are too few (unit, row block)
+  // pairs to occupy the 256 compute units.
+  const int row_blocks = (kp.Mq + 511) / 512;
+  int n_splits = (max_unit_len + 4607) / 4608;
+  const int64_t pairs = (int64_t)n_units * row_blocks;
+  if (pairs > 0 && pairs < 256) {
+    const int want = (int)((256 + pairs - 1) / pairs);
+    const int cap = max_unit_len / 512;
+    const int more = want < cap ? want : cap;
+    if (more > n_splits) n_splits = more;
   }
-  int n_splits = (max_unit_len + split_len - 1) / split_len;
   if (n_splits < 1) n_splits = 1;
-  if (n_splits > 32) {
-    n_splits = 32;
-    split_len = (int)align_up((size_t)(max_unit_len + n_splits - 1) / n_splits, 128);
-    n_splits = (max_unit_len + split_len - 1) / split_len;
+  if (n_splits > 64) n_splits = 64;
+  if (const char* e = std::getenv("CASK_SPLITS")) {
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= 64) n_splits = v;
   }
+  int split_len = (int)align_up((size_t)(max_unit_len + n_splits - 1) / n_splits, 64);
+  if (split_len < 64) split_len = 64;
+  n_splits = (max_unit_len + split_len - 1) / split_len;
+  if (n_splits < 1) n_splits = 1;
   w.n_splits = n_splits;
   w.split_len = split_len;
   w.mq_pad = (int)align_up((size_t)kp.Mq, 64);
