@@ -20,12 +20,12 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
   // Key splits of the row-statistics sweep.  Long splits amortise the unpipelined first stage
   // of every split; short ones are only worth it when there are too few (unit, row block)
   // pairs to occupy the 256 compute units.
-  const int row_blocks = (kp.Mq + 511) / 512;
+  const int row_blocks = (kp.Mq + 255) / 256;
   int n_splits = (max_unit_len + 4607) / 4608;
   const int64_t pairs = (int64_t)n_units * row_blocks;
   if (pairs > 0 && pairs < 256) {
     const int want = (int)((256 + pairs - 1) / pairs);
-    const int cap = max_unit_len / 512;
+    const int cap = max_unit_len / 256;
     const int more = want < cap ? want : cap;
     if (more > n_splits) n_splits = more;
   }

@@ -71,14 +71,14 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;
 constexpr int kRowBytes = kD * 2;
-constexpr int kWaves = 8;                    // waves per workgroup, 2 per SIMD
+constexpr int kWaves = 4;                    // waves per workgroup, 1 per SIMD; two workgroups share a CU
 constexpr int kThreads = kWaves * 64;
 constexpr int kResRows = kWaves * 64;        // resident rows per workgroup (64 per wave)
 constexpr int kStageRows = 64;               // stream rows per ring slot
 constexpr int kGroupPitch = 1024 + 64;       // LDS pitch of a 4-row group (see stage layout)
 constexpr int kDataBytes = (kStageRows / 4) * kGroupPitch;
 constexpr int kStageBytes = kDataBytes + kStageRows * 16;  // + one 16-byte bias entry per row (sweep B)
-constexpr int kDepth = 6;                    // ring slots: loads run kDepth - 1 stages ahead
+constexpr int kDepth = 4;                    // ring slots: loads run kDepth - 1 stages ahead
 constexpr int kLoadsPerThread = kStageRows * 16 / kThreads;  // 16-byte pieces per thread per stage
 
 // Pad value of -L for window rows past W*G: large, finite (inf would turn 0 * inf into NaN
@@ -122,8 +122,10 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
 // Both scoring sweeps.  MODE 0 = sweep A (resident: window rows, stream: keys),
 // MODE 1 = sweep B (resident: keys, stream: window rows).
 //
-// Workgroup: 8 waves; wave w keeps resident rows [64 w, 64 w + 64) of the workgroup's 512 as
-// MFMA B-operands in registers.  Stream rows arrive 64 at a time in a ring of LDS slots,
+// Workgroup: 4 waves, one per SIMD, and two workgroups per compute unit, so a SIMD always has a
+// second wave from an independent workgroup to run while the first sits in its prologue or at
+// a barrier.  Wave w keeps resident rows [64 w, 64 w + 64) of the workgroup's 256 as MFMA
+// B-operands in registers.  Stream rows arrive 64 at a time in a ring of LDS slots,
 // written by direct global->LDS loads (no register staging, no LDS stores) that run
 // kDepth - 1 stages ahead of the stage being consumed; one barrier per stage both publishes a
 // slot and frees the one consumed before it.
@@ -147,7 +149,7 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
 // Stages that touch masked keys (causal tail, ragged end) or initialise the reference take a
 // plain, unpipelined path with explicit masks.
 template <int MODE>
-__global__ __launch_bounds__(kThreads, 1) void score_mfma_kernel(
+__global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     KParams kp, int n_units, int tiles_per_unit, int n_splits, int split_len, int mq_pad,
     const int64_t* __restrict__ row_off, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ Q, float2* __restrict__ rowstat,
@@ -199,30 +201,7 @@ __global__ __launch_bounds__(kThreads, 1) void score_mfma_kernel(
   }
   const int n_stages = (s_end - s_begin + kStageRows - 1) / kStageRows;
 
-  // ---- resident fragments: lane (c32, h) holds row c32 of each 32-row tile, k-chunk h
-  bf16x8 bres[2][NK];
-  int res_row[2];
-#pragma unroll
-  for (int ct = 0; ct < 2; ++ct) {
-    const int r = res_base + wv * 64 + ct * 32 + c32;
-    res_row[ct] = r;
-    const bool ok = r < res_limit;
-    const uint4* src = reinterpret_cast<const uint4*>(res_ptr + (size_t)(ok ? r : res_base) * kD) + h;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      uint4 v = src[ks * 2];
-      if (!ok) v = make_uint4(0, 0, 0, 0);
-      bres[ct][ks] = *reinterpret_cast<bf16x8*>(&v);
-    }
-    if (NK == 9) {  // ones that pick up the three bias terms; the upper k-half contributes nothing
-      uint4 v = (h == 0) ? make_uint4(0x3F803F80u, 0x00003F80u, 0, 0) : make_uint4(0, 0, 0, 0);
-      bres[ct][NK - 1] = *reinterpret_cast<bf16x8*>(&v);
-    }
-  }
-  // a wave whose resident rows are all past the end only helps with loads and barriers
-  const bool wave_live = res_base + wv * 64 < res_limit;
-
-  // ---- ring loads: thread t, piece j covers LDS slot t + 512 j of the stage:
+  // ---- ring loads: thread t, piece j covers 16-byte LDS slot t + kThreads * j of the stage:
   //      row = 4 * (slot / 64) + slot % 4, 16-byte piece = (slot % 64) / 4
   const __amdgpu_buffer_rsrc_t rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(str_ptr), 0,
@@ -234,7 +213,7 @@ __global__ __launch_bounds__(kThreads, 1) void score_mfma_kernel(
     ld_voff[j] = (grp * 4 + (lane & 3)) * kRowBytes + (lane >> 2) * 16;
   }
   // sweep B: the bias entries of a stage's 64 rows are one more 1 KB load, taken in turn by
-  // the waves (stage % 8), so every wave has at most one extra load in flight
+  // the waves (stage % kWaves), so every wave has at most one extra load in flight
   const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint4*>(bias + (size_t)unit * mq_pad), 0, mq_pad * 16, 0x00020000);
   auto issue_stage = [&](int stage) {  // rows past s_end read as zero through the descriptor
@@ -252,6 +231,35 @@ __global__ __launch_bounds__(kThreads, 1) void score_mfma_kernel(
           16, ld_voff[j], soff, 0, 0);
     }
   };
+
+  if (n_stages > 0) {
+#pragma unroll
+    for (int s = 0; s < kDepth - 1; ++s) issue_stage(s);
+  }
+
+  // ---- resident fragments: lane (c32, h) holds row c32 of each 32-row tile, k-chunk h.
+  // Loaded through a bounds-checked descriptor (rows past the end read as zero), after the
+  // ring's first loads are on their way so that the two latencies overlap.
+  const __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(res_ptr), 0, res_limit * kRowBytes, 0x00020000);
+  bf16x8 bres[2][NK];
+  int res_row[2];
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct) {
+    const int r = res_base + wv * 64 + ct * 32 + c32;
+    res_row[ct] = r;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(res_rsrc, r * kRowBytes + h * 16, ks * 32, 0);
+      bres[ct][ks] = __builtin_bit_cast(bf16x8, v);
+    }
+    if (NK == 9) {  // ones that pick up the three bias terms; the upper k-half contributes nothing
+      uint4 v = (h == 0) ? make_uint4(0x3F803F80u, 0x00003F80u, 0, 0) : make_uint4(0, 0, 0, 0);
+      bres[ct][NK - 1] = *reinterpret_cast<bf16x8*>(&v);
+    }
+  }
+  // a wave whose resident rows are all past the end only helps with loads and barriers
+  const bool wave_live = res_base + wv * 64 < res_limit;
 
   // A-operand rows of this lane inside a stage: row rt * 32 + c32 -> group, row-in-group
   const int a_off = (c32 >> 2) * kGroupPitch + (c32 & 3) * 16 + h * 64;
@@ -363,10 +371,13 @@ __global__ __launch_bounds__(kThreads, 1) void score_mfma_kernel(
   };
 
   // ---- main loop over ring stages
-  if (n_stages > 0) {
+  // Take the wait for the resident operands here, before the first barrier issues more loads:
+  // left to the compiler it lands inside the loop prologue as a wait for every load in flight,
+  // the ring's newest stage included.
 #pragma unroll
-    for (int s = 0; s < kDepth - 1; ++s) issue_stage(s);
-  }
+  for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(bres[ct][ks]));
   // Once per stage: this thread's pieces of stages `it` and `it + 1` have landed when at most
   // (kDepth - 3) later stages of its loads are still in flight; the barrier extends that to
   // every thread's pieces and tells everyone that the slot consumed in the previous iteration
@@ -405,11 +416,11 @@ __global__ __launch_bounds__(kThreads, 1) void score_mfma_kernel(
   };
 
   // stages [f0, f1) run the pipelined path; the ones before and after take the masked path.
-  // Sweep A: stage 0 initialises the reference, the causal tail and the ragged end are masked.
+  // Sweep A: the causal tail and the ragged end are masked.
   // Sweep B: a wave is masked throughout iff its keys reach into the window.
   int f0, f1;
   if (MODE == 0) {
-    f0 = 1;
+    f0 = 0;
     const int clean_rows = min(tail_start + 1, s_end) - s_begin;  // keys every row sees
     f1 = clean_rows > 0 ? clean_rows / kStageRows : 0;
   } else {
@@ -429,7 +440,17 @@ __global__ __launch_bounds__(kThreads, 1) void score_mfma_kernel(
   if (f1 > f0) {
     stage_sync(f0);
     load_a(a0, slot_of(f0), 0);
-    chain(acc0, a0, 0);
+    if (MODE == 0 && f0 == 0) {
+      // Nothing seen yet: the first logit of the lane's own row is a safe reference.  Too low
+      // is caught by the range guard of the fast epilogue; too high only means every other
+      // term is negligible next to this one, which is itself part of the sum.
+      chain(acc1, a0, 1);
+      m_ref[1] = acc1[0] * c;
+      chain(acc0, a0, 0);
+      m_ref[0] = acc0[0] * c;
+    } else {
+      chain(acc0, a0, 0);
+    }
     for (it = f0;; ++it) {
       const unsigned char* cur = slot_of(it);
       load_a(a1, cur, 1);
