@@ -67,20 +67,51 @@ __global__ __launch_bounds__(256) void similarity_mfma_kernel(
   const uint8_t* ro = role + row0;
   const int32_t* srow = seed_rows + (size_t)u * kp.B;
 
+  // Every load the workgroup needs is put in flight before anything waits: the row indices of
+  // the first seed stage, then the donor rows, then (as soon as the indices are back) the seed
+  // rows; later seed stages are fetched one stage ahead.  Each workgroup then pays about two
+  // memory round trips instead of one per dependent step.
+  constexpr int kSeedLoads = kSeedStage * 16 / 256;  // 16-byte pieces per thread per seed stage
+  int sidx[kSeedLoads];
+  uint4 sreg[kSeedLoads];
+  auto fetch_idx = [&](int s0) {
+#pragma unroll
+    for (int i = 0; i < kSeedLoads; ++i) {
+      const int ord = s0 + ((tid + 256 * i) >> 4);
+      sidx[i] = ord < M ? srow[ord] : -1;
+    }
+  };
+  auto fetch_rows = [&]() {
+#pragma unroll
+    for (int i = 0; i < kSeedLoads; ++i) {
+      sreg[i] = make_uint4(0, 0, 0, 0);
+      if (sidx[i] >= 0) sreg[i] = reinterpret_cast<const uint4*>(Ku + (size_t)sidx[i] * kD)[tid & 15];
+    }
+  };
+  fetch_idx(0);
+
   // resident donors: lane (c32, h) holds row c32 of each 32-row tile, k-chunk h
-  bf16x8 bres[2][8];
+  uint4 draw[2][8];
   int drow[2];
-  float dinv[2];
 #pragma unroll
   for (int ct = 0; ct < 2; ++ct) {
     const int r = base + wv * 64 + ct * 32 + c32;
     drow[ct] = r;
     const bool ok = r < hi;
     const uint4* src = reinterpret_cast<const uint4*>(Ku + (size_t)(ok ? r : P) * kD) + h;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) draw[ct][ks] = src[ks * 2];
+  }
+  fetch_rows();
+  bf16x8 bres[2][8];
+  float dinv[2];
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct) {
+    const bool ok = drow[ct] < hi;
     float ss = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      uint4 v = ok ? src[ks * 2] : make_uint4(0, 0, 0, 0);
+      uint4 v = ok ? draw[ct][ks] : make_uint4(0, 0, 0, 0);
       ss += sumsq_bf16x8(v);
       bres[ct][ks] = *reinterpret_cast<bf16x8*>(&v);
     }
@@ -92,19 +123,21 @@ __global__ __launch_bounds__(256) void similarity_mfma_kernel(
 
   for (int s0 = 0; s0 < M; s0 += kSeedStage) {
     __syncthreads();  // previous stage fully consumed
-    // load up to 64 seed rows: 16 threads per row, 4 rows per pass per wave
+    // store the fetched stage (up to 64 seed rows: 16 threads per row) and its inverse norms
 #pragma unroll
-    for (int i = 0; i < kSeedStage * 16 / 256; ++i) {
+    for (int i = 0; i < kSeedLoads; ++i) {
       const int q = tid + 256 * i;
       const int sr = q >> 4;
-      const int ord = s0 + sr;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (ord < M) v = reinterpret_cast<const uint4*>(Ku + (size_t)srow[ord] * kD)[q & 15];
+      const uint4 v = sreg[i];
       *reinterpret_cast<uint4*>(stage + sr * kPitch + (q & 15) * 16) = v;
       float ss = sumsq_bf16x8(v);
 #pragma unroll
       for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
       if ((q & 15) == 0) seed_inv[sr] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+    }
+    if (s0 + kSeedStage < M) {  // next stage on its way while this one is contracted
+      fetch_idx(s0 + kSeedStage);
+      fetch_rows();
     }
     __syncthreads();
 #pragma unroll

@@ -190,7 +190,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       s_end = min(s_end, N - W + last_row / Gq + 1);
     }
   } else {
-    res_base = tile * kResRows;
+    // a unit's last tile first: its waves run the masked path and take longest
+    res_base = (tiles_per_unit - 1 - tile) * kResRows;
     if (res_base >= N) return;
     res_ptr = Ku;
     res_limit = N;
@@ -415,27 +416,32 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
   };
 
-  // stages [f0, f1) run the pipelined path; the ones before and after take the masked path.
+  // Stages [f0, f1) run the pipelined path, [sk, f0) and [f1, n_stages) the masked path, and
+  // the wave sits out stages [0, sk).
   // Sweep A: the causal tail and the ragged end are masked.
-  // Sweep B: a wave is masked throughout iff its keys reach into the window.
-  int f0, f1;
+  // Sweep B: window rows come in slot order, so a wave whose keys lie in the window sees
+  // nothing in the first stages (every row is older than its oldest key), is partly masked
+  // until the rows pass its youngest key, and is clean from there on.
+  int sk = 0, f0 = 0, f1;
   if (MODE == 0) {
-    f0 = 0;
     const int clean_rows = min(tail_start + 1, s_end) - s_begin;  // keys every row sees
     f1 = clean_rows > 0 ? clean_rows / kStageRows : 0;
   } else {
-    const bool wave_slow = kp.causal && (res_base + wv * 64 + 63 > tail_start);
-    f0 = 0;
-    f1 = wave_slow ? 0 : n_stages;
+    if (kp.causal) {
+      const int k0 = res_base + wv * 64 - (N - W);  // the wave's oldest key, relative to the window
+      const int fr_min = max(0, k0 * Gq), fr_max = max(0, (k0 + 63) * Gq);
+      sk = max(0, min(n_stages, (fr_min - s_begin) / kStageRows));
+      f0 = max(sk, min(n_stages, (fr_max - s_begin + kStageRows - 1) / kStageRows));
+    }
+    f1 = n_stages;
   }
-  f0 = min(f0, n_stages);
   f1 = max(min(f1, n_stages), f0);
-  if (!wave_live) f0 = f1 = n_stages;  // only loads and barriers: the first loop below
+  if (!wave_live) sk = f0 = f1 = n_stages;  // only loads and barriers: the first loop below
 
   int it = 0;
-  for (; it < f0 && it < n_stages; ++it) {
+  for (; it < f0; ++it) {
     stage_sync(it);
-    if (wave_live) slow_stage(it);
+    if (it >= sk) slow_stage(it);
   }
   if (f1 > f0) {
     stage_sync(f0);
@@ -467,7 +473,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   }
   for (; it < n_stages; ++it) {
     stage_sync(it);
-    if (wave_live) slow_stage(it);
+    slow_stage(it);
   }
   // loads issued past the last stage may still be landing in LDS: let them finish before the
   // workgroup's LDS can be handed to another one
