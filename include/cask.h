@@ -83,7 +83,7 @@ typedef struct {
 
 typedef struct {
   int32_t n_units;
-  const int64_t* row_off;      /* DEVICE [n_units + 1] */
+  const int64_t* row_off;      /* DEVICE [n_units + 1]; W <= N_u = row_off[u+1] - row_off[u] <= 2^23 - 1 */
   const int32_t* prefix_len;   /* DEVICE [n_units], 0 <= P_u <= N_u */
   const int64_t* row_off_host; /* HOST mirror of row_off */
   const int32_t* prefix_len_host; /* HOST mirror of prefix_len */

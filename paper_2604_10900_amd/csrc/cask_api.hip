@@ -94,6 +94,7 @@ static int resolve_batch(const KParams& kp, const cask_batch* b, Batch* out, boo
   if (!b || b->n_units < 0) return CASK_EINVAL;
   out->n_units = b->n_units;
   out->max_unit_len = 0;
+  out->max_decode_len = 0;
   out->total_rows = 0;
   if (b->n_units == 0) return CASK_OK;
   if (!b->row_off || !b->prefix_len || !b->row_off_host || !b->prefix_len_host || !b->K) return CASK_EINVAL;
@@ -102,10 +103,12 @@ static int resolve_batch(const KParams& kp, const cask_batch* b, Batch* out, boo
   if (b->row_off_host[0] != 0) return CASK_EINVAL;
   for (int u = 0; u < b->n_units; ++u) {
     const int64_t n = b->row_off_host[u + 1] - b->row_off_host[u];
-    if (n < kp.W || n > 0x7fffffffLL) return CASK_EINVAL;
+    // a unit's keys are addressed with 32-bit byte offsets: at most 2^23 - 1 rows
+    if (n < kp.W || n > 0x7fffffLL) return CASK_EINVAL;
     const int32_t P = b->prefix_len_host[u];
     if (P < 0 || P > n) return CASK_EINVAL;
     if ((int)n > out->max_unit_len) out->max_unit_len = (int)n;
+    if ((int)n - P > out->max_decode_len) out->max_decode_len = (int)n - P;
   }
   out->total_rows = b->row_off_host[b->n_units];
   out->row_off = b->row_off;

@@ -160,6 +160,7 @@ struct Batch {
   const void* V;
   const void* Q;
   int max_unit_len;
+  int max_decode_len;  // longest decode trace N - P of the batch
   int64_t total_rows;
 };
 

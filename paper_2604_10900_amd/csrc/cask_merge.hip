@@ -25,8 +25,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kD = 128;
 constexpr int kPitch = 272;
-constexpr int kSeedStage = 64;   // seeds per LDS stage
-constexpr int kDonorTile = 256;  // donor rows per workgroup (4 waves x 64)
+constexpr int kSeedStage = 64;    // seeds per MFMA pass (two 32-row tiles)
+constexpr int kSeedBlock = 256;   // seeds held in LDS at a time
+constexpr int kDonorTile = 256;   // donor rows per tile (4 waves x 64)
 
 __device__ inline float sumsq_bf16x8(const uint4& v) {
   const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -41,25 +42,32 @@ __device__ inline float sumsq_bf16x8(const uint4& v) {
   return s;
 }
 
-__global__ __launch_bounds__(256) void similarity_mfma_kernel(
-    KParams kp, int n_units, int tiles_per_unit, const int64_t* __restrict__ row_off,
-    const int32_t* __restrict__ prefix_len, const uint16_t* __restrict__ K,
-    const uint8_t* __restrict__ role, const int32_t* __restrict__ seed_rows,
-    const int32_t* __restrict__ n_seeds, int32_t* __restrict__ assign_ord) {
-  __shared__ __attribute__((aligned(16))) unsigned char stage[kSeedStage * kPitch];
-  __shared__ float seed_inv[kSeedStage];
+// Workgroup = `tiles_per_wg` consecutive donor tiles of one unit.  The unit's seeds (up to
+// kSeedBlock of them; more are taken block by block) sit in LDS with their inverse norms; the
+// donors of a tile are MFMA B-operands in registers (lane = donor), and the loads of the next
+// tile are issued before the current one is contracted, so the kernel streams K at memory
+// speed instead of paying a round trip per tile.
+__global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
+    KParams kp, int n_units, int chunks_per_unit, int tiles_per_wg,
+    const int64_t* __restrict__ row_off, const int32_t* __restrict__ prefix_len,
+    const uint16_t* __restrict__ K, const uint8_t* __restrict__ role,
+    const int32_t* __restrict__ seed_rows, const int32_t* __restrict__ n_seeds,
+    int32_t* __restrict__ assign_ord) {
+  __shared__ __attribute__((aligned(16))) unsigned char stage[kSeedBlock * kPitch];
+  __shared__ float seed_inv[kSeedBlock];
   const int bid = blockIdx.x;
   const int xcd = bid & 7, kk = bid >> 3;
-  const int u = (kk / tiles_per_unit) * 8 + xcd;
-  const int tile = kk % tiles_per_unit;
+  const int u = (kk / chunks_per_unit) * 8 + xcd;
+  const int chunk = kk % chunks_per_unit;
   if (u >= n_units) return;
   const int64_t row0 = row_off[u];
   const int N = (int)(row_off[u + 1] - row0);
   const int P = prefix_len[u];
   const UnitPlan pl = make_plan(kp, P, N);
   const int hi = N - pl.r_eff;
-  const int base = P + tile * kDonorTile;
-  if (base >= hi) return;
+  const int first = P + chunk * tiles_per_wg * kDonorTile;
+  if (first >= hi) return;
+  const int n_tiles = min(tiles_per_wg, (hi - first + kDonorTile - 1) / kDonorTile);
   const int M = n_seeds[u];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int c32 = lane & 31, h = lane >> 5;
@@ -67,116 +75,116 @@ __global__ __launch_bounds__(256) void similarity_mfma_kernel(
   const uint8_t* ro = role + row0;
   const int32_t* srow = seed_rows + (size_t)u * kp.B;
 
-  // Every load the workgroup needs is put in flight before anything waits: the row indices of
-  // the first seed stage, then the donor rows, then (as soon as the indices are back) the seed
-  // rows; later seed stages are fetched one stage ahead.  Each workgroup then pays about two
-  // memory round trips instead of one per dependent step.
-  constexpr int kSeedLoads = kSeedStage * 16 / 256;  // 16-byte pieces per thread per seed stage
-  int sidx[kSeedLoads];
-  uint4 sreg[kSeedLoads];
-  auto fetch_idx = [&](int s0) {
-#pragma unroll
-    for (int i = 0; i < kSeedLoads; ++i) {
-      const int ord = s0 + ((tid + 256 * i) >> 4);
-      sidx[i] = ord < M ? srow[ord] : -1;
-    }
-  };
-  auto fetch_rows = [&]() {
-#pragma unroll
-    for (int i = 0; i < kSeedLoads; ++i) {
-      sreg[i] = make_uint4(0, 0, 0, 0);
-      if (sidx[i] >= 0) sreg[i] = reinterpret_cast<const uint4*>(Ku + (size_t)sidx[i] * kD)[tid & 15];
-    }
-  };
-  fetch_idx(0);
-
-  // resident donors: lane (c32, h) holds row c32 of each 32-row tile, k-chunk h
+  // donors of a tile: lane (c32, h) holds row c32 of each 32-row half, k-chunk h
   uint4 draw[2][8];
-  int drow[2];
+  auto fetch_donors = [&](int t) {
 #pragma unroll
-  for (int ct = 0; ct < 2; ++ct) {
-    const int r = base + wv * 64 + ct * 32 + c32;
-    drow[ct] = r;
-    const bool ok = r < hi;
-    const uint4* src = reinterpret_cast<const uint4*>(Ku + (size_t)(ok ? r : P) * kD) + h;
+    for (int ct = 0; ct < 2; ++ct) {
+      const int r = first + t * kDonorTile + wv * 64 + ct * 32 + c32;
+      const uint4* src = reinterpret_cast<const uint4*>(Ku + (size_t)(r < hi ? r : P) * kD) + h;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) draw[ct][ks] = src[ks * 2];
-  }
-  fetch_rows();
-  bf16x8 bres[2][8];
-  float dinv[2];
-#pragma unroll
-  for (int ct = 0; ct < 2; ++ct) {
-    const bool ok = drow[ct] < hi;
-    float ss = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      uint4 v = ok ? draw[ct][ks] : make_uint4(0, 0, 0, 0);
-      ss += sumsq_bf16x8(v);
-      bres[ct][ks] = *reinterpret_cast<bf16x8*>(&v);
+      for (int ks = 0; ks < 8; ++ks) draw[ct][ks] = src[ks * 2];
     }
-    ss += __shfl_xor(ss, 32, 64);
-    dinv[ct] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
-  }
-  float best[2] = {kNegInf, kNegInf};
-  int best_ord[2] = {-1, -1};
+  };
+  // seeds [sb, sb + kSeedBlock) -> LDS, 64 at a time (16 threads per row), with inverse norms;
+  // rows past M are zero
+  auto stage_seeds = [&](int sb) {
+    for (int s0 = 0; s0 < kSeedBlock && sb + s0 < M; s0 += kSeedStage) {
+      constexpr int kLoads = kSeedStage * 16 / 256;
+      int idx[kLoads];
+      uint4 v[kLoads];
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        const int ord = sb + s0 + ((tid + 256 * i) >> 4);
+        idx[i] = ord < M ? srow[ord] : -1;
+      }
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        v[i] = make_uint4(0, 0, 0, 0);
+        if (idx[i] >= 0) v[i] = reinterpret_cast<const uint4*>(Ku + (size_t)idx[i] * kD)[tid & 15];
+      }
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        const int sr = s0 + ((tid + 256 * i) >> 4);
+        *reinterpret_cast<uint4*>(stage + sr * kPitch + (tid & 15) * 16) = v[i];
+        float ss = sumsq_bf16x8(v[i]);
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        if ((tid & 15) == 0) seed_inv[sr] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+      }
+    }
+  };
 
-  for (int s0 = 0; s0 < M; s0 += kSeedStage) {
-    __syncthreads();  // previous stage fully consumed
-    // store the fetched stage (up to 64 seed rows: 16 threads per row) and its inverse norms
-#pragma unroll
-    for (int i = 0; i < kSeedLoads; ++i) {
-      const int q = tid + 256 * i;
-      const int sr = q >> 4;
-      const uint4 v = sreg[i];
-      *reinterpret_cast<uint4*>(stage + sr * kPitch + (q & 15) * 16) = v;
-      float ss = sumsq_bf16x8(v);
-#pragma unroll
-      for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-      if ((q & 15) == 0) seed_inv[sr] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
-    }
-    if (s0 + kSeedStage < M) {  // next stage on its way while this one is contracted
-      fetch_idx(s0 + kSeedStage);
-      fetch_rows();
-    }
+  fetch_donors(0);
+  const bool one_block = M <= kSeedBlock;
+  if (one_block) {
+    stage_seeds(0);
     __syncthreads();
+  }
+  for (int t = 0; t < n_tiles; ++t) {
+    bf16x8 bres[2][8];
+    int drow[2];
+    float dinv[2];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-      if (s0 + rt * 32 >= M) continue;
-      bf16x8 a[8];
-      const unsigned char* ap = stage + (rt * 32 + c32) * kPitch + h * 16;
+    for (int ct = 0; ct < 2; ++ct) {
+      drow[ct] = first + t * kDonorTile + wv * 64 + ct * 32 + c32;
+      const bool ok = drow[ct] < hi;
+      float ss = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 32);
+      for (int ks = 0; ks < 8; ++ks) {
+        uint4 v = ok ? draw[ct][ks] : make_uint4(0, 0, 0, 0);
+        ss += sumsq_bf16x8(v);
+        bres[ct][ks] = *reinterpret_cast<bf16x8*>(&v);
+      }
+      ss += __shfl_xor(ss, 32, 64);
+      dinv[ct] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+    }
+    if (t + 1 < n_tiles) fetch_donors(t + 1);  // in flight while this tile is contracted
+
+    float best[2] = {kNegInf, kNegInf};
+    int best_ord[2] = {-1, -1};
+    for (int sb = 0; sb < M; sb += kSeedBlock) {
+      if (!one_block) {
+        __syncthreads();  // previous block fully consumed
+        stage_seeds(sb);
+        __syncthreads();
+      }
+      const int m_blk = min(kSeedBlock, M - sb);
+      for (int s0 = 0; s0 < m_blk; s0 += 32) {
+        bf16x8 a[8];
+        const unsigned char* ap = stage + (s0 + c32) * kPitch + h * 16;
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        f32x16 acc = {0};
+        for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 32);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct][ks], acc, 0, 0, 0);
+        for (int ct = 0; ct < 2; ++ct) {
+          f32x16 acc = {0};
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {  // ascending seed ordinal within the lane
-          const int sr = rt * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-          const int ord = s0 + sr;
-          const float sim = (acc[r] * seed_inv[sr]) * dinv[ct];
-          if (ord < M && sim > best[ct]) {
-            best[ct] = sim;
-            best_ord[ct] = ord;
+          for (int ks = 0; ks < 8; ++ks)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct][ks], acc, 0, 0, 0);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {  // ascending seed ordinal within the lane
+            const int sr = s0 + (r >> 2) * 8 + h * 4 + (r & 3);
+            const float sim = (acc[r] * seed_inv[sr]) * dinv[ct];
+            if (sr < m_blk && sim > best[ct]) {
+              best[ct] = sim;
+              best_ord[ct] = sb + sr;
+            }
           }
         }
       }
     }
-  }
 #pragma unroll
-  for (int ct = 0; ct < 2; ++ct) {
-    const float ob = __shfl_xor(best[ct], 32, 64);
-    const int oo = __shfl_xor(best_ord[ct], 32, 64);
-    if (oo >= 0 && (best_ord[ct] < 0 || better(ob, oo, best[ct], best_ord[ct]))) {
-      best[ct] = ob;
-      best_ord[ct] = oo;
-    }
-    if (h == 0 && drow[ct] < hi) {
-      const bool donor = ro[drow[ct]] == CASK_ROLE_DONOR;
-      assign_ord[row0 + drow[ct]] = (donor && best_ord[ct] >= 0 && best[ct] >= kp.tau) ? best_ord[ct] : -1;
+    for (int ct = 0; ct < 2; ++ct) {
+      const float ob = __shfl_xor(best[ct], 32, 64);
+      const int oo = __shfl_xor(best_ord[ct], 32, 64);
+      if (oo >= 0 && (best_ord[ct] < 0 || better(ob, oo, best[ct], best_ord[ct]))) {
+        best[ct] = ob;
+        best_ord[ct] = oo;
+      }
+      if (h == 0 && drow[ct] < hi) {
+        const bool donor = ro[drow[ct]] == CASK_ROLE_DONOR;
+        assign_ord[row0 + drow[ct]] = (donor && best_ord[ct] >= 0 && best[ct] >= kp.tau) ? best_ord[ct] : -1;
+      }
     }
   }
 }
@@ -428,7 +436,8 @@ template <typename T, int D>
 hipError_t launch_similarity_fma(const KParams& kp, const Batch& b, const uint8_t* role,
                                  const int32_t* seed_rows, const int32_t* n_seeds,
                                  int32_t* assign_ord, hipStream_t st) {
-  const int tiles = (b.max_unit_len + 255) / 256;
+  const int tiles = (b.max_decode_len + 255) / 256;
+  if (tiles == 0) return hipSuccess;
   similarity_fma_kernel<T, D><<<dim3(b.n_units * tiles), dim3(256), 0, st>>>(
       kp, b.n_units, tiles, b.row_off, b.prefix_len, static_cast<const T*>(b.K), role, seed_rows,
       n_seeds, assign_ord);
@@ -441,11 +450,19 @@ hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* r
                              const int32_t* seed_rows, const int32_t* n_seeds,
                              int32_t* assign_ord, hipStream_t st) {
   if (kp.dtype == CASK_BF16 && kp.d == 128) {
-    const int tiles = (b.max_unit_len + kDonorTile - 1) / kDonorTile;
+    // a few workgroups per unit, about two per compute unit in all, each walking its share of
+    // the unit's donor tiles
+    const int tiles = (b.max_decode_len + kDonorTile - 1) / kDonorTile;
+    if (tiles == 0) return hipSuccess;
+    int chunks = b.n_units > 0 ? 512 / b.n_units : 1;
+    if (chunks < 1) chunks = 1;
+    if (chunks > tiles) chunks = tiles;
+    const int tiles_per_wg = (tiles + chunks - 1) / chunks;
+    chunks = (tiles + tiles_per_wg - 1) / tiles_per_wg;
     const int units8 = (b.n_units + 7) / 8 * 8;
-    similarity_mfma_kernel<<<dim3(units8 * tiles), dim3(256), 0, st>>>(
-        kp, b.n_units, tiles, b.row_off, b.prefix_len, static_cast<const uint16_t*>(b.K), role,
-        seed_rows, n_seeds, assign_ord);
+    similarity_mfma_kernel<<<dim3(units8 * chunks), dim3(256), 0, st>>>(
+        kp, b.n_units, chunks, tiles_per_wg, b.row_off, b.prefix_len,
+        static_cast<const uint16_t*>(b.K), role, seed_rows, n_seeds, assign_ord);
     return hipGetLastError();
   }
   if (kp.dtype == CASK_F32)
