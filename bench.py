@@ -52,7 +52,9 @@ def parse():
                          "known traffic, N MiB read and N/2 MiB written, for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--no-stage-events", action="store_true",
-                    help="do not record per-kernel HIP events inside the timed region")
+                    help="record no HIP events inside the timed region (no roofline object then)")
+    ap.add_argument("--breakdown-steps", type=int, default=10,
+                    help="extra untimed steps with an event after every kernel for config.stage_ms (0 = skip)")
     return ap.parse_args()
 
 
@@ -115,9 +117,11 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    # timed region: K whole events; the library brackets the two scoring sweeps (the dominant
+    # kernels) with three HIP events per step on the stream they run on
     use_events = not args.no_stage_events
     if use_events:
-        binding.timing_enable(args.steps)
+        binding.timing_enable(args.steps, 2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -125,11 +129,21 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    stage_ms = None
+    sweep_ms = None
     if use_events:
-        stage_ms, n_rec = binding.timing_read()
+        sweep_ms, n_rec = binding.timing_read()
         binding.timing_enable(0)
         assert n_rec == args.steps
+    # per-kernel breakdown: a separate, untimed pass with an event after every kernel (the
+    # events cost about 2 us each, so they stay out of the timed region)
+    stage_ms = None
+    if args.breakdown_steps > 0:
+        binding.timing_enable(args.breakdown_steps)
+        for i in range(args.breakdown_steps):
+            step(i)
+        torch.cuda.synchronize()
+        stage_ms, _ = binding.timing_read()
+        binding.timing_enable(0)
     status = outs.status.cpu().numpy()
     out_len = outs.out_len.cpu().numpy()
     lens = (b0.row_off_host[1:] - b0.row_off_host[:-1]).numpy()
@@ -140,18 +154,18 @@ def main():
     Mq = p.q_per_kv * p.window
     flops_pass = 2.0 * Mq * float(kv_tokens) * p.head_dim
     roof = None
-    if stage_ms is not None:
-        dom = max(("score_rows", "score_cols"), key=lambda k: stage_ms[k])
-        t_dom = stage_ms[dom] * 1e-3
+    if sweep_ms is not None:
+        dom = max(("score_rows", "score_cols"), key=lambda k: sweep_ms[k])
+        t_dom = sweep_ms[dom] * 1e-3
         achieved = flops_pass / t_dom / 1e12
         roof = {"bound": "mfma", "kernel": "score_mfma_kernel<%d> (%s)" % (0 if dom == "score_rows" else 1, dom),
                 "achieved": round(achieved, 2), "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),
                 "traffic": (MEASURED_TRAFFIC.get(args.workload, {}).get(dom)
                             if args.layers == 0 and args.seqs == 0 else None),
-                "kernel_ms": round(stage_ms[dom], 4),
+                "kernel_ms": round(sweep_ms[dom], 4),
                 "flops_per_launch": flops_pass,
-                "both_sweeps_frac": round(2 * flops_pass / ((stage_ms["score_rows"] + stage_ms["score_cols"]) * 1e-3)
+                "both_sweeps_frac": round(2 * flops_pass / ((sweep_ms["score_rows"] + sweep_ms["score_cols"]) * 1e-3)
                                           / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4)}
 
     # ---- CPU oracle on a bounded sample of the same units (rank 0, N = 1 only)

@@ -19,6 +19,7 @@
  *     The library allocates nothing, never synchronises, and only enqueues work on
  *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
  *   - Inputs are never modified.  Outputs of one call must not alias its inputs.
+ *   - K, V, Q, K_out, V_out and the workspace must be 16-byte aligned (CASK_EINVAL otherwise).
  *   - Argument errors are found on the host before any launch and returned as a
  *     negative code; nothing is enqueued then.  Per-unit regime outcomes are status bits
  *     in device memory, not errors.
@@ -154,15 +155,19 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
 
 /* Measurement aid (not part of the method): per-stage timing of cask_compress with HIP
  * events recorded on the caller's stream between its kernels.  Stage order: 0 score sweep A
- * (row statistics), 1 score sweep B (column mass), 2 select, 3 index roles, 4 similarity,
- * 5 gather merged donors, 6 emit.
+ * (row statistics), 1 score sweep B (column mass), 2 select (with the ordered walk over the
+ * roles, which cask_compress runs in the same kernel), 3 index roles (zero in cask_compress),
+ * 4 similarity, 5 gather merged donors, 6 emit.
  * cask_timing_enable(n > 0) creates events for the next n compress calls (n <= 4096) and
  * switches recording on; n <= 0 switches it off and destroys them.  Calls beyond n are not
  * recorded.  cask_timing_read waits for the recorded calls, writes the summed milliseconds
  * per stage into stage_ms[CASK_N_STAGES] and the number of recorded calls into *n_calls,
- * and rearms.  Not thread-safe; one stream at a time. */
+ * and rearms.  cask_timing_enable_stages(n, k) records only the first k stages (k = 2: the two
+ * scoring sweeps, three events per call instead of eight); the other entries read as 0.
+ * Not thread-safe; one stream at a time. */
 #define CASK_N_STAGES 7
 int cask_timing_enable(int max_calls);
+int cask_timing_enable_stages(int max_calls, int n_stages);
 int cask_timing_read(float* stage_ms, int* n_calls);
 
 /* HOST: short name of a return code. */

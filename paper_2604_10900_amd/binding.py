@@ -26,7 +26,7 @@ ST_ACTIVE, ST_IDENTITY, ST_PREFIX_BUDGET_EXHAUSTED, ST_MERGE_INACTIVE = 0, 1, 2,
 
 EXPORTS = ["cask_plan", "cask_workspace_bytes", "cask_score", "cask_prefix_evict",
            "cask_partition", "cask_consolidate", "cask_compress", "cask_strerror",
-           "cask_timing_enable", "cask_timing_read"]
+           "cask_timing_enable", "cask_timing_enable_stages", "cask_timing_read"]
 STAGES = ["score_rows", "score_cols", "select", "index_roles", "similarity", "gather", "emit"]
 
 
@@ -98,6 +98,7 @@ def load():
         lib.cask_consolidate.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         lib.cask_compress.argtypes = [vp] * 11 + [C.c_size_t, vp]
         lib.cask_timing_enable.argtypes = [C.c_int]
+        lib.cask_timing_enable_stages.argtypes = [C.c_int, C.c_int]
         lib.cask_timing_read.argtypes = [vp, vp]
         for name in ("cask_plan", "cask_score", "cask_prefix_evict", "cask_partition",
                      "cask_consolidate", "cask_compress", "cask_timing_enable", "cask_timing_read"):
@@ -113,10 +114,11 @@ def _strerror(code: int) -> str:
         return "?"
 
 
-def timing_enable(max_calls: int) -> None:
-    rc = load().cask_timing_enable(C.c_int(max_calls))
+def timing_enable(max_calls: int, n_stages: int = len(STAGES)) -> None:
+    """Record the first n_stages stages of the next max_calls compress calls (0 = off)."""
+    rc = load().cask_timing_enable_stages(C.c_int(max_calls), C.c_int(n_stages))
     if rc:
-        raise CaskError("cask_timing_enable", rc)
+        raise CaskError("cask_timing_enable_stages", rc)
 
 
 def timing_read() -> tuple:

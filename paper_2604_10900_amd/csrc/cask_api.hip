@@ -100,6 +100,8 @@ static int resolve_batch(const KParams& kp, const cask_batch* b, Batch* out, boo
   if (!b->row_off || !b->prefix_len || !b->row_off_host || !b->prefix_len_host || !b->K) return CASK_EINVAL;
   if (need_q && !b->Q) return CASK_EINVAL;
   if (need_v && !b->V) return CASK_EINVAL;
+  auto misaligned = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; };
+  if (misaligned(b->K) || misaligned(b->V) || misaligned(b->Q)) return CASK_EINVAL;
   if (b->row_off_host[0] != 0) return CASK_EINVAL;
   for (int u = 0; u < b->n_units; ++u) {
     const int64_t n = b->row_off_host[u + 1] - b->row_off_host[u];
@@ -128,6 +130,7 @@ struct StageTiming {
   bool on = false;
   int max_calls = 0;
   int n_calls = 0;
+  int stages = CASK_N_STAGES;  // stages recorded per call (the first `stages` of them)
   std::vector<hipEvent_t> ev;  // (CASK_N_STAGES + 1) per call
 };
 static StageTiming g_timing;
@@ -142,9 +145,13 @@ struct StageRecorder {
       ++g_timing.n_calls;
     }
   }
-  hipEvent_t peek() const { return ev ? ev[next] : nullptr; }  // handed to a launcher to record
+  hipEvent_t peek() const { return (ev && next <= g_timing.stages) ? ev[next] : nullptr; }  // handed to a launcher to record
   void skip() { if (ev) ++next; }
-  void mark() { if (ev) (void)hipEventRecord(ev[next++], st); }
+  void mark() {
+    if (!ev) return;
+    if (next <= g_timing.stages) (void)hipEventRecord(ev[next], st);
+    ++next;
+  }
 };
 
 }  // namespace cask
@@ -195,6 +202,7 @@ int cask_score(const cask_params* params, const cask_batch* batch, float* scores
   if (rc) return rc;
   if (b.n_units == 0) return CASK_OK;
   if (!scores || !ws) return CASK_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(ws) & 15u) != 0) return CASK_EINVAL;
   const Workspace wl = layout_workspace(kp, b.n_units, b.total_rows, b.max_unit_len);
   if (ws_bytes < wl.total) return CASK_ENOMEM;
   return dev_rc(launch_score(kp, b, wl, static_cast<char*>(ws), scores, static_cast<hipStream_t>(hip_stream)));
@@ -243,6 +251,7 @@ int cask_consolidate(const cask_params* params, const cask_batch* batch, const f
   if (rc) return rc;
   if (b.n_units == 0) return CASK_OK;
   if (!role || !assign || !ws) return CASK_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(ws) & 15u) != 0) return CASK_EINVAL;
   const Workspace wl = layout_workspace(kp, b.n_units, b.total_rows, b.max_unit_len);
   if (ws_bytes < wl.total) return CASK_ENOMEM;
   char* w = static_cast<char*>(ws);
@@ -273,6 +282,8 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
   if (rc) return rc;
   if (b.n_units == 0) return CASK_OK;
   if (!K_out || !V_out || !out_len || !out_src || !status || !ws) return CASK_EINVAL;
+  if (((reinterpret_cast<uintptr_t>(K_out) | reinterpret_cast<uintptr_t>(V_out) | reinterpret_cast<uintptr_t>(ws)) & 15u) != 0)
+    return CASK_EINVAL;
   if (given && !scores) return CASK_EINVAL;
   const Workspace wl = layout_workspace(kp, b.n_units, b.total_rows, b.max_unit_len);
   if (ws_bytes < wl.total) return CASK_ENOMEM;
@@ -299,12 +310,11 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
     rec.mark();
   }
   rec.mark();  // end of sweep B
-  e = launch_select(kp, b, s, role, status, true, true, st);
+  e = launch_select_index(kp, b, s, role, status, slot_of, out_src, out_len, seed_rows, ord_of_slot,
+                          n_seeds, st);
   if (e != hipSuccess) return CASK_EDEVICE;
   rec.mark();
-  e = launch_index_roles(kp, b, role, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds, st);
-  if (e != hipSuccess) return CASK_EDEVICE;
-  rec.mark();
+  rec.mark();  // the ordered walk runs inside the select kernel here: its own stage reads as zero
   e = launch_similarity(kp, b, role, seed_rows, n_seeds, assign_ord, st);
   if (e != hipSuccess) return CASK_EDEVICE;
   rec.mark();
@@ -318,14 +328,17 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
   return dev_rc(e);
 }
 
-int cask_timing_enable(int max_calls) {
+int cask_timing_enable(int max_calls) { return cask_timing_enable_stages(max_calls, CASK_N_STAGES); }
+
+int cask_timing_enable_stages(int max_calls, int n_stages) {
   for (hipEvent_t e : g_timing.ev) (void)hipEventDestroy(e);
   g_timing.ev.clear();
   g_timing.on = false;
   g_timing.n_calls = 0;
   g_timing.max_calls = 0;
   if (max_calls <= 0) return CASK_OK;
-  if (max_calls > 4096) return CASK_EINVAL;
+  if (max_calls > 4096 || n_stages < 1 || n_stages > CASK_N_STAGES) return CASK_EINVAL;
+  g_timing.stages = n_stages;
   g_timing.ev.resize((size_t)max_calls * (CASK_N_STAGES + 1));
   for (auto& e : g_timing.ev)
     if (hipEventCreate(&e) != hipSuccess) return CASK_EDEVICE;
@@ -340,8 +353,8 @@ int cask_timing_read(float* stage_ms, int* n_calls) {
   *n_calls = g_timing.n_calls;
   for (int c = 0; c < g_timing.n_calls; ++c) {
     hipEvent_t* ev = g_timing.ev.data() + (size_t)c * (CASK_N_STAGES + 1);
-    if (hipEventSynchronize(ev[CASK_N_STAGES]) != hipSuccess) return CASK_EDEVICE;
-    for (int i = 0; i < CASK_N_STAGES; ++i) {
+    if (hipEventSynchronize(ev[g_timing.stages]) != hipSuccess) return CASK_EDEVICE;
+    for (int i = 0; i < g_timing.stages; ++i) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) return CASK_EDEVICE;
       stage_ms[i] += ms;

@@ -169,6 +169,11 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
                         float* scores, hipStream_t st, hipEvent_t between = nullptr);
 hipError_t launch_select(const KParams& kp, const Batch& b, const float* scores, uint8_t* role,
                          int32_t* status, bool do_prefix, bool do_decode, hipStream_t st);
+// both stages of the selection and the ordered walk in one launch (whole-event path)
+hipError_t launch_select_index(const KParams& kp, const Batch& b, const float* scores,
+                               uint8_t* role, int32_t* status, int32_t* slot_of, int32_t* out_src,
+                               int32_t* out_len, int32_t* seed_rows, int32_t* ord_of_slot,
+                               int32_t* n_seeds, hipStream_t st);
 hipError_t launch_index_roles(const KParams& kp, const Batch& b, const uint8_t* role,
                               int32_t* slot_of, int32_t* out_src, int32_t* out_len,
                               int32_t* seed_rows, int32_t* ord_of_slot, int32_t* n_seeds,

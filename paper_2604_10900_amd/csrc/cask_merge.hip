@@ -260,6 +260,7 @@ __global__ __launch_bounds__(256) void similarity_fma_kernel(
 // ------------------------------------------------------------------ gather merged donors
 
 constexpr int kGatherThreads = 1024;
+constexpr int kGatherPer = 16;  // 64-row groups per wave and chunk
 
 // assign_mode: 0 none, 1 output slot (whole event), 2 unit-local source row (consolidate API)
 __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
@@ -287,17 +288,29 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
       assign_out[row0 + i] = !kept ? -1 : (assign_mode == 1 ? slot_of[row0 + i] : i);
     }
   }
+  // A wave owns kGatherPer * 64 consecutive rows, touched 64 consecutive rows at a time
+  // (coalesced); positions inside the wave come from ballots with a running carry, and one
+  // exchange of the wave totals per chunk orders the waves.
+  const unsigned long long below = (1ull << lane) - 1ull;
   int count = 0;
-  for (int base = P; base < hi; base += kGatherThreads) {
-    const int i = base + tid;
-    const bool in = i < hi;
-    const int r = in ? role[row0 + i] : CASK_ROLE_PREFIX_DROP;
-    const int ord = (in && r == CASK_ROLE_DONOR) ? assign_ord[row0 + i] : -1;
-    const int flag = ord >= 0 ? 1 : 0;
-    // ordered block scan of the flags
-    const unsigned long long bal = __ballot(flag);
-    const int in_wave = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) wsum[wv] = __popcll(bal);
+  for (int cb = P; cb < hi; cb += kGatherThreads * kGatherPer) {
+    const int i0 = cb + wv * (64 * kGatherPer) + lane;
+    int r[kGatherPer], ord[kGatherPer], pos[kGatherPer];
+#pragma unroll
+    for (int e = 0; e < kGatherPer; ++e) {
+      const bool in = i0 + e * 64 < hi;
+      r[e] = in ? (int)role[row0 + i0 + e * 64] : (int)CASK_ROLE_PREFIX_DROP;
+      ord[e] = in ? assign_ord[row0 + i0 + e * 64] : -1;
+    }
+    int run = 0;
+#pragma unroll
+    for (int e = 0; e < kGatherPer; ++e) {
+      if (r[e] != CASK_ROLE_DONOR) ord[e] = -1;
+      const unsigned long long b = __ballot(ord[e] >= 0);
+      pos[e] = run + __popcll(b & below);
+      run += __popcll(b);
+    }
+    if (lane == 0) wsum[wv] = run;
     __syncthreads();
     int before = 0, tot = 0;
     for (int w = 0; w < kGatherThreads / 64; ++w) {
@@ -306,20 +319,26 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
       tot += x;
     }
     __syncthreads();
-    if (flag) {
-      const int pos = count + before + in_wave;
-      merged_row[row0 + pos] = i;
-      merged_ord[row0 + pos] = ord;
-    }
-    if (in && assign_mode != 0) {
-      int v;
-      if (r == CASK_ROLE_DONOR) {
-        v = ord < 0 ? -1 : (assign_mode == 1 ? slot_of[row0 + srow[ord]] : srow[ord]);
-      } else {
-        const bool kept = r == CASK_ROLE_CORE || r == CASK_ROLE_SEED;
-        v = !kept ? -1 : (assign_mode == 1 ? slot_of[row0 + i] : i);
+#pragma unroll
+    for (int e = 0; e < kGatherPer; ++e) {
+      const int i = i0 + e * 64;
+      if (i < hi) {
+        if (ord[e] >= 0) {
+          const int at = count + before + pos[e];
+          merged_row[row0 + at] = i;
+          merged_ord[row0 + at] = ord[e];
+        }
+        if (assign_mode != 0) {
+          int v;
+          if (r[e] == CASK_ROLE_DONOR) {
+            v = ord[e] < 0 ? -1 : (assign_mode == 1 ? slot_of[row0 + srow[ord[e]]] : srow[ord[e]]);
+          } else {
+            const bool kept = r[e] == CASK_ROLE_CORE || r[e] == CASK_ROLE_SEED;
+            v = !kept ? -1 : (assign_mode == 1 ? slot_of[row0 + i] : i);
+          }
+          assign_out[row0 + i] = v;
+        }
       }
-      assign_out[row0 + i] = v;
     }
     count += tot;
   }
@@ -332,6 +351,11 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
 
 // ------------------------------------------------------------------ emit (copy + fold)
 
+// Sixteen lanes per output row (D / 16 elements each), so a wave moves four rows per load
+// instruction; it owns 16 consecutive slots of one unit and puts the loads of four rows of K
+// and V in flight before it touches any of them.  A seed slot then folds its donors: the
+// group walks the unit's merged list (ascending rows) and accumulates the matching ones in
+// fp32 in that order.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void emit_kernel(
     KParams kp, int n_units, const int64_t* __restrict__ row_off, const T* __restrict__ K,
@@ -340,81 +364,112 @@ __global__ __launch_bounds__(256) void emit_kernel(
     const int32_t* __restrict__ merged_row, const int32_t* __restrict__ merged_ord,
     const int32_t* __restrict__ n_merged, T* __restrict__ K_out, T* __restrict__ V_out,
     float* __restrict__ out_mass) {
-  constexpr int EPL = D / 64;  // elements per lane
-  const int lane = threadIdx.x & 63;
+  constexpr int EPL = D / 16;                    // elements per lane
+  constexpr int WORDS = EPL * sizeof(T) / 4;     // 32-bit words per lane
+  constexpr int kSlotsPerWave = 16;
+  struct alignas(WORDS * 4 > 16 ? 16 : WORDS * 4) Raw { uint32_t w[WORDS]; };
+  const int lane = threadIdx.x & 63, grp = lane >> 4, gl = lane & 15;
   const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int B = kp.B;
-  const int u = (int)(wave / B), t = (int)(wave % B);
-  if (u >= n_units || t >= out_len[u]) return;
+  const int waves_per_unit = (B + kSlotsPerWave - 1) / kSlotsPerWave;
+  const int u = (int)(wave / waves_per_unit);
+  const int t_base = (int)(wave % waves_per_unit) * kSlotsPerWave;
+  if (u >= n_units) return;
+  const int len = out_len[u];
+  if (t_base >= len) return;
   const int64_t row0 = row_off[u];
-  const int src = out_src[(size_t)u * B + t];
-  const int ord = ord_of_slot[(size_t)u * B + t];
-  const T* kr = K + (size_t)(row0 + src) * D + lane * EPL;
-  const T* vr = V + (size_t)(row0 + src) * D + lane * EPL;
-  T* ko = K_out + ((size_t)u * B + t) * D + lane * EPL;
-  T* vo = V_out + ((size_t)u * B + t) * D + lane * EPL;
-  T kraw[EPL], vraw[EPL];
+  const int nm = n_merged[u];
+  const int32_t* mr = merged_row + row0;
+  const int32_t* mo = merged_ord + row0;
+
+  int slot[4], src[4], ord[4];
+  float a0[4];
+  Raw kraw[4], vraw[4];
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) {
-    kraw[e] = kr[e];
-    vraw[e] = vr[e];
+  for (int j = 0; j < 4; ++j) {
+    slot[j] = t_base + j * 4 + grp;
+    const bool ok = slot[j] < len;
+    src[j] = ok ? out_src[(size_t)u * B + slot[j]] : -1;
+    ord[j] = ok ? ord_of_slot[(size_t)u * B + slot[j]] : -1;
   }
-  const float a0 = scores[row0 + src];
-  int members = 1;
-  float mass = a0;
-  float ka[EPL], va[EPL], ku[EPL], vu[EPL];  // weighted and unweighted sums
-  if (ord >= 0) {
-    const int nm = n_merged[u];
-    const int32_t* mr = merged_row + row0;
-    const int32_t* mo = merged_ord + row0;
-    for (int b0 = 0; b0 < nm; b0 += 64) {
-      const int idx = b0 + lane;
-      const int my_ord = idx < nm ? mo[idx] : -1;
-      const int my_row = idx < nm ? mr[idx] : 0;
-      unsigned long long hit = __ballot(my_ord == ord);
-      while (hit) {
-        const int l = __ffsll((long long)hit) - 1;
-        hit &= hit - 1;
-        const int drow = __shfl(my_row, l, 64);
-        if (members == 1) {
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) {
-            const float kf = Elem<T>::load(&kraw[e]), vf = Elem<T>::load(&vraw[e]);
-            ka[e] = a0 * kf; va[e] = a0 * vf; ku[e] = kf; vu[e] = vf;
+  for (int j = 0; j < 4; ++j) {
+    if (src[j] >= 0) {
+      kraw[j] = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + src[j]) * D + gl * EPL);
+      vraw[j] = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + src[j]) * D + gl * EPL);
+      a0[j] = scores[row0 + src[j]];
+    } else {
+      a0[j] = 0.f;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    int members = 1;
+    float mass = a0[j];
+    float ka[EPL], va[EPL], ku[EPL], vu[EPL];  // weighted and unweighted sums
+    const T* kself = reinterpret_cast<const T*>(&kraw[j]);
+    const T* vself = reinterpret_cast<const T*>(&vraw[j]);
+    if (nm > 0 && __any(ord[j] >= 0)) {
+      for (int b0 = 0; b0 < nm; b0 += 16) {
+        const int idx = b0 + gl;
+        const int my_ord = idx < nm ? mo[idx] : -1;
+        const int my_row = idx < nm ? mr[idx] : 0;
+        const unsigned long long bal = __ballot(ord[j] >= 0 && my_ord == ord[j]);
+        unsigned hit = (unsigned)(bal >> (grp * 16)) & 0xFFFFu;
+        while (__any(hit != 0u)) {  // every group steps through its own matches, together
+          const bool have = hit != 0u;
+          const int l = have ? __ffs((int)hit) - 1 : 0;
+          hit &= hit - 1u;
+          const int drow = __shfl(my_row, grp * 16 + l, 64);
+          if (have) {
+            if (members == 1) {
+#pragma unroll
+              for (int e = 0; e < EPL; ++e) {
+                const float kf = Elem<T>::load(kself + e), vf = Elem<T>::load(vself + e);
+                ka[e] = a0[j] * kf; va[e] = a0[j] * vf; ku[e] = kf; vu[e] = vf;
+              }
+            }
+            const float a = scores[row0 + drow];
+            const Raw dk = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + drow) * D + gl * EPL);
+            const Raw dv = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + drow) * D + gl * EPL);
+            const T* dkp = reinterpret_cast<const T*>(&dk);
+            const T* dvp = reinterpret_cast<const T*>(&dv);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+              const float kf = Elem<T>::load(dkp + e), vf = Elem<T>::load(dvp + e);
+              ka[e] = __builtin_fmaf(a, kf, ka[e]);
+              va[e] = __builtin_fmaf(a, vf, va[e]);
+              ku[e] += kf;
+              vu[e] += vf;
+            }
+            mass += a;
+            ++members;
           }
         }
-        const float a = scores[row0 + drow];
-        const T* dk = K + (size_t)(row0 + drow) * D + lane * EPL;
-        const T* dv = V + (size_t)(row0 + drow) * D + lane * EPL;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-          const float kf = Elem<T>::load(dk + e), vf = Elem<T>::load(dv + e);
-          ka[e] = __builtin_fmaf(a, kf, ka[e]);
-          va[e] = __builtin_fmaf(a, vf, va[e]);
-          ku[e] += kf;
-          vu[e] += vf;
-        }
-        mass += a;
-        ++members;
       }
     }
-  }
-  if (members == 1) {
+    if (src[j] < 0) continue;
+    T* ko = K_out + ((size_t)u * B + slot[j]) * D + gl * EPL;
+    T* vo = V_out + ((size_t)u * B + slot[j]) * D + gl * EPL;
+    if (members == 1) {
+      *reinterpret_cast<Raw*>(ko) = kraw[j];
+      *reinterpret_cast<Raw*>(vo) = vraw[j];
+    } else {
+      const bool uniform = mass == 0.f;
+      const float denom = uniform ? (float)members : mass;
+      Raw ok_, ov_;
+      T* okp = reinterpret_cast<T*>(&ok_);
+      T* ovp = reinterpret_cast<T*>(&ov_);
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      ko[e] = kraw[e];
-      vo[e] = vraw[e];
+      for (int e = 0; e < EPL; ++e) {
+        Elem<T>::store(okp + e, (uniform ? ku[e] : ka[e]) / denom);
+        Elem<T>::store(ovp + e, (uniform ? vu[e] : va[e]) / denom);
+      }
+      *reinterpret_cast<Raw*>(ko) = ok_;
+      *reinterpret_cast<Raw*>(vo) = ov_;
     }
-  } else {
-    const bool uniform = mass == 0.f;
-    const float denom = uniform ? (float)members : mass;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      Elem<T>::store(ko + e, (uniform ? ku[e] : ka[e]) / denom);
-      Elem<T>::store(vo + e, (uniform ? vu[e] : va[e]) / denom);
-    }
+    if (out_mass && gl == 0) out_mass[(size_t)u * B + slot[j]] = mass;
   }
-  if (out_mass && lane == 0) out_mass[(size_t)u * B + t] = mass;
 }
 
 template <typename T, int D>
@@ -423,8 +478,9 @@ hipError_t launch_emit_t(const KParams& kp, const Batch& b, const float* scores,
                          const int32_t* ord_of_slot, const int32_t* merged_row,
                          const int32_t* merged_ord, const int32_t* n_merged, void* K_out,
                          void* V_out, float* out_mass, hipStream_t st) {
-  const long long waves = (long long)b.n_units * kp.B;
+  const long long waves = (long long)b.n_units * ((kp.B + 15) / 16);
   const long long blocks = (waves + 3) / 4;
+  if (blocks == 0) return hipSuccess;
   emit_kernel<T, D><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(
       kp, b.n_units, b.row_off, static_cast<const T*>(b.K), static_cast<const T*>(b.V), scores,
       out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, static_cast<T*>(K_out),

@@ -3,7 +3,8 @@
 //
 // "Top k" is exact and order-defined: higher float score first, equal scores by ascending
 // cache index.  One workgroup per unit runs an LDS radix select (4 passes of 8 bits over an
-// order-preserving key image of the scores) to find the k-th key, then marks the elements;
+// order-preserving key image of the scores; the three ranks a unit needs -- prefix keep, core,
+// core + seeds -- are found in the same passes) to find the k-th keys, then marks the elements;
 // when the k-th value is shared by more elements than there are places left, an ordered block
 // scan hands the places to the lowest indices -- no atomics decide membership.
 //
@@ -25,64 +26,119 @@ struct Kth {
   int total_eq;   // how many elements equal to `key` exist in the range
 };
 
-// Block-wide radix select over s[lo, hi): the key of rank k (1 <= k <= hi - lo).
-// All threads of the block must call it; `hist` is 256 ints of LDS, `bcast` 4 ints.
-__device__ Kth radix_select(const float* __restrict__ s, int lo, int hi, int k, int* hist,
-                            int* bcast) {
-  const int tid = threadIdx.x;
-  uint32_t prefix = 0, mask = 0;
-  int remaining = k;
-  int eq_total = 0;
+// Up to three rank queries answered together by one block-wide radix select (4 passes of 8
+// bits): query q asks for the key of rank k[q] (1 <= k <= hi - lo) among s[lo[q], hi[q]).
+// Every pass walks the rows of the active ranges once and feeds one LDS histogram per query;
+// wave q then finds the digit of query q.  Inactive queries (k <= 0) are skipped.
+// Scores of one unit crowd into a few digits (the top byte holds sign and exponent), and LDS
+// atomics on one address serialise; so every histogram exists in kHistCopies copies, a lane
+// adds to copy lane % kHistCopies, and the copies are summed before the digit search.
+// All threads of the block must call it; `hist` is 3 x 256 x kHistCopies ints of LDS, `bcast`
+// 3 x 4 ints.
+constexpr int kHistCopies = 16;
+struct Query3 {
+  int lo[3], hi[3], k[3];
+};
+
+constexpr int kSelPer = 16;                       // keys a thread holds at a time
+constexpr int kSelChunk = kSelThreads * kSelPer;  // rows per chunk
+
+// keys of rows base + e * kSelThreads + tid, e < kSelPer (0 past `end`): all loads of the
+// chunk are in flight together
+__device__ inline void load_keys(const float* __restrict__ s, int base, int end, uint32_t (&key)[kSelPer]) {
+  float v[kSelPer];
+#pragma unroll
+  for (int e = 0; e < kSelPer; ++e) {
+    const int i = base + e * kSelThreads + (int)threadIdx.x;
+    v[e] = i < end ? s[i] : 0.f;
+  }
+#pragma unroll
+  for (int e = 0; e < kSelPer; ++e) key[e] = score_key(v[e]);
+}
+
+// `key` holds the chunk starting at lo_all on return when the ranges fit one chunk
+// (hi_all - lo_all <= kSelChunk), so the caller can mark the rows without reading them again.
+__device__ void radix_select3(const float* __restrict__ s, const Query3& q, int lo_all, int hi_all,
+                              Kth (&out)[3], uint32_t (&key)[kSelPer], int* hist, int* bcast) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  uint32_t prefix[3] = {0, 0, 0};
+  uint32_t mask = 0;
+  int remaining[3] = {q.k[0], q.k[1], q.k[2]};
+  int eq_total[3] = {0, 0, 0};
+  const bool single = hi_all - lo_all <= kSelChunk;
+  if (single) load_keys(s, lo_all, hi_all, key);
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
-    if (tid < 256) hist[tid] = 0;
+    for (int b = tid; b < 768 * kHistCopies; b += kSelThreads) hist[b] = 0;
     __syncthreads();
-    for (int i = lo + tid; i < hi; i += kSelThreads) {
-      const uint32_t key = score_key(s[i]);
-      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+    for (int base = lo_all; base < hi_all; base += kSelChunk) {
+      if (!single) load_keys(s, base, hi_all, key);
+#pragma unroll
+      for (int e = 0; e < kSelPer; ++e) {
+        const int i = base + e * kSelThreads + tid;
+        const uint32_t digit = (key[e] >> shift) & 255u;
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+          if (q.k[j] > 0 && i >= q.lo[j] && i < q.hi[j] && (key[e] & mask) == prefix[j])
+            atomicAdd(&hist[(j * 256 + digit) * kHistCopies + (tid & (kHistCopies - 1))], 1);
+      }
     }
     __syncthreads();
-    // wave 0: lane l owns digits 255-4l .. 252-4l (descending); find the digit where the
-    // running count from the top reaches `remaining`
-    if (tid < 64) {
+    if (tid < 768) {  // fold the copies into copy 0
+      int sum = 0;
+#pragma unroll
+      for (int cpy = 0; cpy < kHistCopies; ++cpy) sum += hist[tid * kHistCopies + ((cpy + tid) & (kHistCopies - 1))];
+      hist[tid * kHistCopies] = sum;
+    }
+    __syncthreads();
+    // wave j: lane l owns digits 255-4l .. 252-4l (descending) of query j; find the digit where
+    // the running count from the top reaches `remaining`
+    if (wv < 3 && q.k[wv] > 0) {
+      const int rem = wv == 0 ? remaining[0] : (wv == 1 ? remaining[1] : remaining[2]);
+      const int* hq = hist + wv * 256 * kHistCopies;
       int h4[4];
       int local = 0;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        h4[e] = hist[255 - (tid * 4 + e)];
+        h4[e] = hq[(255 - (lane * 4 + e)) * kHistCopies];
         local += h4[e];
       }
       int incl = local;
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) {
         const int v = __shfl_up(incl, o, 64);
-        if (tid >= o) incl += v;
+        if (lane >= o) incl += v;
       }
       int before = incl - local;  // elements in digits above this lane's four
-      if (before < remaining && remaining <= incl) {
+      if (before < rem && rem <= incl) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          if (before < remaining && remaining <= before + h4[e]) {
-            bcast[0] = 255 - (tid * 4 + e);
-            bcast[1] = remaining - before;
-            bcast[2] = h4[e];
+          if (before < rem && rem <= before + h4[e]) {
+            bcast[wv * 4 + 0] = 255 - (lane * 4 + e);
+            bcast[wv * 4 + 1] = rem - before;
+            bcast[wv * 4 + 2] = h4[e];
           }
           before += h4[e];
         }
       }
     }
     __syncthreads();
-    prefix |= ((uint32_t)bcast[0]) << shift;
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+      if (q.k[j] > 0) {
+        prefix[j] |= ((uint32_t)bcast[j * 4 + 0]) << shift;
+        remaining[j] = bcast[j * 4 + 1];
+        eq_total[j] = bcast[j * 4 + 2];
+      }
     mask |= 0xFFu << shift;
-    remaining = bcast[1];
-    eq_total = bcast[2];
     __syncthreads();
   }
-  Kth r;
-  r.key = prefix;
-  r.take_eq = remaining;
-  r.total_eq = eq_total;
-  return r;
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    out[j].key = prefix[j];
+    out[j].take_eq = remaining[j];
+    out[j].total_eq = eq_total[j];
+  }
 }
 
 // Exclusive block scan of a small per-thread count (two 16-bit fields packed in one int).
@@ -108,12 +164,86 @@ __device__ inline int block_excl_scan(int v, int* wsum, int* total) {
   return base + incl - v;
 }
 
+// Ordered walk over the roles of a unit: output slot of every kept row, ordinal of every seed.
+// A wave owns kIdxPer * 64 consecutive rows, read and written 64 consecutive rows at a time
+// (coalesced); positions inside the wave come from ballots with a running carry, and one
+// exchange of the wave totals per chunk of kSelThreads * kIdxPer rows orders the waves.
+constexpr int kIdxPer = 16;
+
+__device__ void index_walk(const KParams& kp, int u, int64_t row0, int N, const uint8_t* __restrict__ ro,
+                           int32_t* __restrict__ slot_of, int32_t* __restrict__ out_src,
+                           int32_t* __restrict__ out_len, int32_t* __restrict__ seed_rows,
+                           int32_t* __restrict__ ord_of_slot, int32_t* __restrict__ n_seeds,
+                           int* wsum) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int B = kp.B;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  int kept_before = 0, seeds_before = 0;
+  for (int cb = 0; cb < N; cb += kSelThreads * kIdxPer) {
+    const int i0 = cb + wv * (64 * kIdxPer) + lane;
+    uint8_t r[kIdxPer];
+#pragma unroll
+    for (int e = 0; e < kIdxPer; ++e) r[e] = (i0 + e * 64 < N) ? ro[i0 + e * 64] : (uint8_t)CASK_ROLE_PREFIX_DROP;
+    int kpos[kIdxPer], spos[kIdxPer];  // kept rows / seeds before this row inside the wave
+    int run_k = 0, run_s = 0;
+#pragma unroll
+    for (int e = 0; e < kIdxPer; ++e) {
+      const bool is_seed = r[e] == CASK_ROLE_SEED;
+      const bool kept = r[e] == CASK_ROLE_PREFIX_KEEP || r[e] == CASK_ROLE_CORE ||
+                        r[e] == CASK_ROLE_RECENT || is_seed;
+      const unsigned long long bk = __ballot(kept), bs = __ballot(is_seed);
+      kpos[e] = run_k + __popcll(bk & below);
+      spos[e] = run_s + __popcll(bs & below);
+      run_k += __popcll(bk);
+      run_s += __popcll(bs);
+    }
+    if (lane == 0) wsum[wv] = run_k | (run_s << 16);
+    __syncthreads();
+    int base = 0, tot = 0;
+    for (int w = 0; w < kSelWaves; ++w) {
+      const int x = wsum[w];
+      if (w < wv) base += x;
+      tot += x;
+    }
+    __syncthreads();
+    const int k0 = kept_before + (base & 0xFFFF), s0 = seeds_before + (base >> 16);
+#pragma unroll
+    for (int e = 0; e < kIdxPer; ++e) {
+      const int i = i0 + e * 64;
+      if (i < N) {
+        const bool is_seed = r[e] == CASK_ROLE_SEED;
+        const bool kept = r[e] == CASK_ROLE_PREFIX_KEEP || r[e] == CASK_ROLE_CORE ||
+                          r[e] == CASK_ROLE_RECENT || is_seed;
+        const int slot = k0 + kpos[e], ord = s0 + spos[e];
+        // a caller-supplied role array could keep more rows than the budget: never write
+        // past the unit's B output slots
+        const bool fits = kept && slot < B;
+        if (slot_of) slot_of[row0 + i] = fits ? slot : -1;
+        if (fits) {
+          if (out_src) out_src[(size_t)u * B + slot] = i;
+          if (ord_of_slot) ord_of_slot[(size_t)u * B + slot] = is_seed ? ord : -1;
+        }
+        if (is_seed && ord < B) seed_rows[(size_t)u * B + ord] = i;
+      }
+    }
+    kept_before += tot & 0xFFFF;
+    seeds_before += tot >> 16;
+  }
+  if (tid == 0) {
+    if (out_len) out_len[u] = kept_before < B ? kept_before : B;
+    n_seeds[u] = seeds_before < B ? seeds_before : B;
+  }
+}
+
+
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     KParams kp, const int64_t* __restrict__ row_off, const int32_t* __restrict__ prefix_len,
     const float* __restrict__ scores, uint8_t* __restrict__ role, int32_t* __restrict__ status,
-    int do_prefix, int do_decode) {
-  __shared__ int hist[256];
-  __shared__ int bcast[4];
+    int do_prefix, int do_decode, int do_index, int32_t* __restrict__ slot_of,
+    int32_t* __restrict__ out_src, int32_t* __restrict__ out_len, int32_t* __restrict__ seed_rows,
+    int32_t* __restrict__ ord_of_slot, int32_t* __restrict__ n_seeds) {
+  __shared__ int hist[3 * 256 * kHistCopies];
+  __shared__ int bcast[3 * 4];
   __shared__ int wsum[kSelWaves];
   const int u = blockIdx.x, tid = threadIdx.x;
   const int64_t row0 = row_off[u];
@@ -124,16 +254,52 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   uint8_t* ro = role + row0;
   if (tid == 0 && status) status[u] = pl.status;
 
+  // which ranks have to be found: prefix rank p_keep, decode ranks C (core) and C + M (core
+  // and seeds).  A rank of 0 selects nothing, a rank >= the range everything.
+  const int hi = N - pl.r_eff;
+  const int n = hi - P;
+  const int C = pl.core, CM = pl.core + pl.seeds;
+  const bool pre_sel = do_prefix && P > 0 && pl.p_keep > 0 && pl.p_keep < P;
+  const bool dec_sel = do_decode && n > 0 && !(pl.status & CASK_ST_PREFIX_BUDGET_EXHAUSTED) && C < n;
+  const bool all_seed = CM >= n;
+  Query3 q;
+  q.lo[0] = 0; q.hi[0] = P; q.k[0] = pre_sel ? pl.p_keep : 0;
+  q.lo[1] = P; q.hi[1] = hi; q.k[1] = (dec_sel && C > 0) ? C : 0;
+  q.lo[2] = P; q.hi[2] = hi; q.k[2] = (dec_sel && !all_seed && CM > C) ? CM : 0;
+  Kth kth[3];
+  uint32_t key[kSelPer];
+  bool have_keys = false;  // `key` holds rows lo_all + e * kSelThreads + tid
+  int lo_all = N, hi_all = 0;
+#pragma unroll
+  for (int j = 0; j < 3; ++j)
+    if (q.k[j] > 0) {
+      lo_all = min(lo_all, q.lo[j]);
+      hi_all = max(hi_all, q.hi[j]);
+    }
+  if (hi_all > lo_all) {
+    radix_select3(s, q, lo_all, hi_all, kth, key, hist, bcast);
+    have_keys = hi_all - lo_all <= kSelChunk;
+  }
+  const bool keys_cover_prefix = have_keys && lo_all == 0 && hi_all >= P;
+  const bool keys_cover_decode = have_keys && lo_all <= P && hi_all >= hi;
   if (do_prefix && P > 0) {
     if (pl.p_keep >= P) {
       for (int i = tid; i < P; i += kSelThreads) ro[i] = CASK_ROLE_PREFIX_KEEP;
     } else if (pl.p_keep == 0) {
       for (int i = tid; i < P; i += kSelThreads) ro[i] = CASK_ROLE_PREFIX_DROP;
     } else {
-      const Kth kt = radix_select(s, 0, P, pl.p_keep, hist, bcast);
+      const Kth kt = kth[0];
       if (kt.take_eq == kt.total_eq) {
-        for (int i = tid; i < P; i += kSelThreads)
-          ro[i] = score_key(s[i]) >= kt.key ? CASK_ROLE_PREFIX_KEEP : CASK_ROLE_PREFIX_DROP;
+        if (keys_cover_prefix) {
+#pragma unroll
+          for (int e = 0; e < kSelPer; ++e) {
+            const int i = lo_all + e * kSelThreads + tid;
+            if (i < P) ro[i] = key[e] >= kt.key ? CASK_ROLE_PREFIX_KEEP : CASK_ROLE_PREFIX_DROP;
+          }
+        } else {
+          for (int i = tid; i < P; i += kSelThreads)
+            ro[i] = score_key(s[i]) >= kt.key ? CASK_ROLE_PREFIX_KEEP : CASK_ROLE_PREFIX_DROP;
+        }
       } else {
         int seen = 0;  // elements equal to the k-th key at lower indices
         for (int base = 0; base < P; base += kSelThreads) {
@@ -152,41 +318,44 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     }
   }
 
-  if (do_decode) {
-    const int hi = N - pl.r_eff;
+  auto decode_roles = [&]() {
     for (int i = hi + tid; i < N; i += kSelThreads) ro[i] = CASK_ROLE_RECENT;
-    const int n = hi - P;
     if (n <= 0) return;
     if (pl.status & CASK_ST_PREFIX_BUDGET_EXHAUSTED) {
       for (int i = P + tid; i < hi; i += kSelThreads) ro[i] = CASK_ROLE_DECODE_EVICT;
       return;
     }
-    const int C = pl.core, CM = pl.core + pl.seeds;
     if (C >= n) {
       for (int i = P + tid; i < hi; i += kSelThreads) ro[i] = CASK_ROLE_CORE;
       return;
     }
-    // thresholds of rank C (core) and rank C+M (core and seeds); a rank of 0 selects nothing
+    // thresholds of rank C (core) and rank C+M (core and seeds)
     Kth kc, km;
     kc.key = 0xFFFFFFFFu; kc.take_eq = 0; kc.total_eq = 0;
-    km = kc;
-    if (C > 0) kc = radix_select(s, P, hi, C, hist, bcast);
-    if (CM >= n) {
+    if (C > 0) kc = kth[1];
+    if (all_seed) {
       km.key = 0u; km.take_eq = 0; km.total_eq = 0;  // everything not core is a seed
     } else if (CM > C) {
-      km = radix_select(s, P, hi, CM, hist, bcast);
+      km = kth[2];
     } else {
       km = kc;
     }
-    const bool all_seed = CM >= n;
     const bool ties = (C > 0 && kc.take_eq != kc.total_eq) ||
                       (!all_seed && CM > 0 && km.take_eq != km.total_eq);
     if (!ties) {
-      for (int i = P + tid; i < hi; i += kSelThreads) {
-        const uint32_t key = score_key(s[i]);
-        const bool in_c = C > 0 && key >= kc.key;
-        const bool in_cm = all_seed || (CM > 0 && key >= km.key);
+      auto mark = [&](int i, uint32_t k) {
+        const bool in_c = C > 0 && k >= kc.key;
+        const bool in_cm = all_seed || (CM > 0 && k >= km.key);
         ro[i] = in_c ? CASK_ROLE_CORE : (in_cm ? CASK_ROLE_SEED : CASK_ROLE_DONOR);
+      };
+      if (keys_cover_decode) {
+#pragma unroll
+        for (int e = 0; e < kSelPer; ++e) {
+          const int i = lo_all + e * kSelThreads + tid;
+          if (i >= P && i < hi) mark(i, key[e]);
+        }
+      } else {
+        for (int i = P + tid; i < hi; i += kSelThreads) mark(i, score_key(s[i]));
       }
     } else {
       int seen_c = 0, seen_m = 0;
@@ -207,50 +376,26 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         seen_m += tot >> 16;
       }
     }
+  };
+  if (do_decode) decode_roles();
+  if (do_index) {
+    // the roles this workgroup just wrote are read back in index order: the barrier makes
+    // them visible to all of its threads
+    __syncthreads();
+    index_walk(kp, u, row0, N, ro, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds, wsum);
   }
 }
 
-// Ordered walk over the roles of a unit: output slot of every kept row, ordinal of every seed.
 __global__ __launch_bounds__(kSelThreads) void index_roles_kernel(
     KParams kp, const int64_t* __restrict__ row_off, const uint8_t* __restrict__ role,
     int32_t* __restrict__ slot_of, int32_t* __restrict__ out_src, int32_t* __restrict__ out_len,
     int32_t* __restrict__ seed_rows, int32_t* __restrict__ ord_of_slot,
     int32_t* __restrict__ n_seeds) {
   __shared__ int wsum[kSelWaves];
-  const int u = blockIdx.x, tid = threadIdx.x;
+  const int u = blockIdx.x;
   const int64_t row0 = row_off[u];
   const int N = (int)(row_off[u + 1] - row0);
-  const uint8_t* ro = role + row0;
-  const int B = kp.B;
-  int kept_before = 0, seeds_before = 0;
-  for (int base = 0; base < N; base += kSelThreads) {
-    const int i = base + tid;
-    const int r = i < N ? ro[i] : CASK_ROLE_PREFIX_DROP;
-    const int is_seed = (r == CASK_ROLE_SEED) ? 1 : 0;
-    const int kept = (r == CASK_ROLE_PREFIX_KEEP || r == CASK_ROLE_CORE || r == CASK_ROLE_RECENT ||
-                      is_seed) ? 1 : 0;
-    int tot;
-    const int ex = block_excl_scan(kept | (is_seed << 16), wsum, &tot);
-    if (i < N) {
-      const int slot = kept_before + (ex & 0xFFFF);
-      const int ord = seeds_before + (ex >> 16);
-      // a caller-supplied role array could keep more rows than the budget: never write
-      // past the unit's B output slots
-      const bool fits = kept && slot < B;
-      if (slot_of) slot_of[row0 + i] = fits ? slot : -1;
-      if (fits) {
-        if (out_src) out_src[(size_t)u * B + slot] = i;
-        if (ord_of_slot) ord_of_slot[(size_t)u * B + slot] = is_seed ? ord : -1;
-      }
-      if (is_seed && ord < B) seed_rows[(size_t)u * B + ord] = i;
-    }
-    kept_before += tot & 0xFFFF;
-    seeds_before += tot >> 16;
-  }
-  if (tid == 0) {
-    if (out_len) out_len[u] = kept_before < B ? kept_before : B;
-    n_seeds[u] = seeds_before < B ? seeds_before : B;
-  }
+  index_walk(kp, u, row0, N, role + row0, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds, wsum);
 }
 
 }  // namespace
@@ -258,7 +403,18 @@ __global__ __launch_bounds__(kSelThreads) void index_roles_kernel(
 hipError_t launch_select(const KParams& kp, const Batch& b, const float* scores, uint8_t* role,
                          int32_t* status, bool do_prefix, bool do_decode, hipStream_t st) {
   select_kernel<<<dim3(b.n_units), dim3(kSelThreads), 0, st>>>(
-      kp, b.row_off, b.prefix_len, scores, role, status, do_prefix ? 1 : 0, do_decode ? 1 : 0);
+      kp, b.row_off, b.prefix_len, scores, role, status, do_prefix ? 1 : 0, do_decode ? 1 : 0, 0,
+      nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_index(const KParams& kp, const Batch& b, const float* scores,
+                               uint8_t* role, int32_t* status, int32_t* slot_of, int32_t* out_src,
+                               int32_t* out_len, int32_t* seed_rows, int32_t* ord_of_slot,
+                               int32_t* n_seeds, hipStream_t st) {
+  select_kernel<<<dim3(b.n_units), dim3(kSelThreads), 0, st>>>(
+      kp, b.row_off, b.prefix_len, scores, role, status, 1, 1, 1, slot_of, out_src, out_len,
+      seed_rows, ord_of_slot, n_seeds);
   return hipGetLastError();
 }
 
