@@ -53,7 +53,7 @@ def parse():
                          "FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="record no HIP events inside the timed region (no roofline object then)")
-    ap.add_argument("--breakdown-steps", type=int, default=10,
+    ap.add_argument("--breakdown-steps", type=int, default=20,
                     help="extra untimed steps with an event after every kernel for config.stage_ms (0 = skip)")
     return ap.parse_args()
 
@@ -134,16 +134,24 @@ def main():
         sweep_ms, n_rec = binding.timing_read()
         binding.timing_enable(0)
         assert n_rec == args.steps
-    # per-kernel breakdown: a separate, untimed pass with an event after every kernel (the
-    # events cost about 2 us each, so they stay out of the timed region)
+    # per-kernel breakdown and per-event spread: a separate, untimed pass with an event after
+    # every kernel (the events cost about 2 us each, so they stay out of the timed region)
     stage_ms = None
+    spread = None
     if args.breakdown_steps > 0:
         binding.timing_enable(args.breakdown_steps)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.breakdown_steps + 1)]
+        marks[0].record()
         for i in range(args.breakdown_steps):
             step(i)
+            marks[i + 1].record()
         torch.cuda.synchronize()
         stage_ms, _ = binding.timing_read()
         binding.timing_enable(0)
+        per = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(args.breakdown_steps)])
+        spread = {"median": round(float(np.median(per)), 4), "p10": round(float(np.percentile(per, 10)), 4),
+                  "p90": round(float(np.percentile(per, 90)), 4), "steps": args.breakdown_steps,
+                  "note": "separate pass with an event after every kernel"}
     status = outs.status.cpu().numpy()
     out_len = outs.out_len.cpu().numpy()
     lens = (b0.row_off_host[1:] - b0.row_off_host[:-1]).numpy()
@@ -224,7 +232,8 @@ def main():
                    "seq_tokens_per_s": round(value / (n_layers * w.n_kv_heads), 1),
                    "input_copies": copies, "saved_ratio": round(saved, 4),
                    "status_counts": {str(k): int(v) for k, v in zip(*np.unique(status, return_counts=True))},
-                   "stage_ms": ({k: round(v, 4) for k, v in stage_ms.items()} if stage_ms else None)},
+                   "stage_ms": ({k: round(v, 4) for k, v in stage_ms.items()} if stage_ms else None),
+                   "event_ms_spread": spread},
         "roofline": roof,
         "cpu_baseline": cpu,
     }

@@ -23,38 +23,52 @@ __device__ inline bool better(float sim, int ord, float best, int best_ord) {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kD = 128;
-constexpr int kPitch = 272;
-constexpr int kSeedStage = 64;    // seeds per MFMA pass (two 32-row tiles)
-constexpr int kSeedBlock = 256;   // seeds held in LDS at a time
-constexpr int kDonorTile = 256;   // donor rows per tile (4 waves x 64)
+constexpr int kRowBytes = kD * 2;
+constexpr int kGroupPitch = 1024 + 64;  // LDS pitch of a 4-row group, piece-major (see below)
+constexpr int kSeedBlock = 128;         // seeds held in LDS at a time
+constexpr int kDonorTile = 128;         // donor rows per tile: 4 waves x 32
+constexpr int kPrefetch = 2;            // donor tiles in flight ahead of the one being contracted
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 __device__ inline float sumsq_bf16x8(const uint4& v) {
   const uint32_t w[4] = {v.x, v.y, v.z, v.w};
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const float lo = __uint_as_float(w[i] << 16);
-    const float hi = __uint_as_float(w[i] & 0xFFFF0000u);
-    s = __builtin_fmaf(lo, lo, s);
-    s = __builtin_fmaf(hi, hi, s);
+    const bf16x2 x = __builtin_bit_cast(bf16x2, w[i]);
+    s = __builtin_amdgcn_fdot2_f32_bf16(x, x, s, false);
   }
   return s;
 }
 
-// Workgroup = `tiles_per_wg` consecutive donor tiles of one unit.  The unit's seeds (up to
-// kSeedBlock of them; more are taken block by block) sit in LDS with their inverse norms; the
-// donors of a tile are MFMA B-operands in registers (lane = donor), and the loads of the next
-// tile are issued before the current one is contracted, so the kernel streams K at memory
-// speed instead of paying a round trip per tile.
+// Workgroup = `tiles_per_wg` consecutive donor tiles of one unit; wave w owns rows
+// [32 w, 32 w + 32) of every tile.
+//
+// Memory side: a wave reads its 32 rows with 8 fully coalesced loads (4 whole 256-byte rows
+// per instruction: lane l takes 16-byte piece l % 16 of row l / 16), kPrefetch tiles ahead, so
+// K streams at memory speed.  The registers then hold rows across lanes, not MFMA operands;
+// the wave turns them round through a private LDS region: piece g of row r of a 4-row group
+// goes to g * 64 + r * 16 (a 1 KB store per instruction, conflict-free), and lane (c32, h)
+// reads back row c32's pieces h, h + 2, ... as the B operand of the eight k-steps
+// (conflict-free as well, 1088-byte group pitch).  No barrier: the region is the wave's own.
+//
+// Compute side: the unit's seeds (kSeedBlock at a time, same layout, with inverse norms) are
+// the A operand, so a lane owns one donor and sees its seeds in ascending order:
+// cos = (dot * |seed|^-1) * |donor|^-1 in fp32, first maximum wins.
+// ONE_BLOCK: every unit has at most kSeedBlock seeds, so they are staged once per workgroup and
+// the tile loop contains nothing but the donor stream (the host knows the bound).
+template <bool ONE_BLOCK>
 __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
     KParams kp, int n_units, int chunks_per_unit, int tiles_per_wg,
     const int64_t* __restrict__ row_off, const int32_t* __restrict__ prefix_len,
     const uint16_t* __restrict__ K, const uint8_t* __restrict__ role,
     const int32_t* __restrict__ seed_rows, const int32_t* __restrict__ n_seeds,
     int32_t* __restrict__ assign_ord) {
-  __shared__ __attribute__((aligned(16))) unsigned char stage[kSeedBlock * kPitch];
-  __shared__ float seed_inv[kSeedBlock];
+  __shared__ __attribute__((aligned(16))) unsigned char seeds[(kSeedBlock / 4) * kGroupPitch];
+  __shared__ __attribute__((aligned(16))) unsigned char turn[4][8 * kGroupPitch];
+  __shared__ __attribute__((aligned(16))) float seed_inv[kSeedBlock];
   const int bid = blockIdx.x;
   const int xcd = bid & 7, kk = bid >> 3;
   const int u = (kk / chunks_per_unit) * 8 + xcd;
@@ -69,44 +83,53 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
   if (first >= hi) return;
   const int n_tiles = min(tiles_per_wg, (hi - first + kDonorTile - 1) / kDonorTile);
   const int M = n_seeds[u];
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: feeds scalar load offsets
   const int c32 = lane & 31, h = lane >> 5;
   const uint16_t* Ku = K + (size_t)row0 * kD;
   const uint8_t* ro = role + row0;
   const int32_t* srow = seed_rows + (size_t)u * kp.B;
+  // rows past the donor range read as zero through the descriptor's bounds check
+  const __amdgpu_buffer_rsrc_t krsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(Ku), 0, hi * kRowBytes, 0x00020000);
 
-  // donors of a tile: lane (c32, h) holds row c32 of each 32-row half, k-chunk h
-  uint4 draw[2][8];
-  auto fetch_donors = [&](int t) {
+  // ---- donor stream: the wave's 32 rows of tile t, 4 rows per load
+  // (the role of the lane's donor row rides along, so that nothing at the end of a tile has
+  // to wait on memory behind the loads already issued for the tiles after it)
+  uint4 dreg[kPrefetch][8];
+  int rreg[kPrefetch];
+  auto fetch_donors = [&](int t, uint4 (&d)[8], int& rl) {
+    // Always issued, also for tiles past the end (their rows read as zero and are never
+    // stored): with an unconditional load count the waits for a tile can leave the loads of
+    // the tiles after it in flight.
+    const int r0 = first + t * kDonorTile + wv * 32;
+    rl = (int)ro[min(r0 + c32, N - 1)];
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
-      const int r = first + t * kDonorTile + wv * 64 + ct * 32 + c32;
-      const uint4* src = reinterpret_cast<const uint4*>(Ku + (size_t)(r < hi ? r : P) * kD) + h;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) draw[ct][ks] = src[ks * 2];
+    for (int j = 0; j < 8; ++j) {
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(
+          krsrc, lane * 16, (int)((unsigned)(r0 + 4 * j) * (unsigned)kRowBytes), 0);
+      d[j] = make_uint4(v[0], v[1], v[2], v[3]);
     }
   };
-  // seeds [sb, sb + kSeedBlock) -> LDS, 64 at a time (16 threads per row), with inverse norms;
-  // rows past M are zero
+  // ---- seeds [sb, sb + kSeedBlock) -> LDS (16 threads per row, 16 rows per pass) + inverse norms
   auto stage_seeds = [&](int sb) {
-    for (int s0 = 0; s0 < kSeedBlock && sb + s0 < M; s0 += kSeedStage) {
-      constexpr int kLoads = kSeedStage * 16 / 256;
-      int idx[kLoads];
-      uint4 v[kLoads];
+    for (int s0 = 0; s0 < kSeedBlock && sb + s0 < M; s0 += 64) {
+      int idx[4];
+      uint4 v[4];
 #pragma unroll
-      for (int i = 0; i < kLoads; ++i) {
-        const int ord = sb + s0 + ((tid + 256 * i) >> 4);
+      for (int i = 0; i < 4; ++i) {
+        const int ord = sb + s0 + i * 16 + (tid >> 4);
         idx[i] = ord < M ? srow[ord] : -1;
       }
 #pragma unroll
-      for (int i = 0; i < kLoads; ++i) {
+      for (int i = 0; i < 4; ++i) {
         v[i] = make_uint4(0, 0, 0, 0);
         if (idx[i] >= 0) v[i] = reinterpret_cast<const uint4*>(Ku + (size_t)idx[i] * kD)[tid & 15];
       }
 #pragma unroll
-      for (int i = 0; i < kLoads; ++i) {
-        const int sr = s0 + ((tid + 256 * i) >> 4);
-        *reinterpret_cast<uint4*>(stage + sr * kPitch + (tid & 15) * 16) = v[i];
+      for (int i = 0; i < 4; ++i) {
+        const int sr = s0 + i * 16 + (tid >> 4);
+        *reinterpret_cast<uint4*>(seeds + (sr >> 2) * kGroupPitch + (tid & 15) * 64 + (sr & 3) * 16) = v[i];
         float ss = sumsq_bf16x8(v[i]);
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
@@ -115,34 +138,37 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
     }
   };
 
-  fetch_donors(0);
-  const bool one_block = M <= kSeedBlock;
+#pragma unroll
+  for (int t = 0; t < kPrefetch; ++t) fetch_donors(t, dreg[t], rreg[t]);
+  constexpr bool one_block = ONE_BLOCK;
   if (one_block) {
     stage_seeds(0);
     __syncthreads();
   }
-  for (int t = 0; t < n_tiles; ++t) {
-    bf16x8 bres[2][8];
-    int drow[2];
-    float dinv[2];
-#pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
-      drow[ct] = first + t * kDonorTile + wv * 64 + ct * 32 + c32;
-      const bool ok = drow[ct] < hi;
-      float ss = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        uint4 v = ok ? draw[ct][ks] : make_uint4(0, 0, 0, 0);
-        ss += sumsq_bf16x8(v);
-        bres[ct][ks] = *reinterpret_cast<bf16x8*>(&v);
-      }
-      ss += __shfl_xor(ss, 32, 64);
-      dinv[ct] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
-    }
-    if (t + 1 < n_tiles) fetch_donors(t + 1);  // in flight while this tile is contracted
+  unsigned char* my_turn = turn[wv];
+  const int op_off = (c32 >> 2) * kGroupPitch + (c32 & 3) * 16 + h * 64;  // operand rows of this lane
 
-    float best[2] = {kNegInf, kNegInf};
-    int best_ord[2] = {-1, -1};
+  auto tile_body = [&](int t, uint4 (&d)[8], int& rl) {
+    // registers -> private LDS region -> B operand of this lane's donor
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      *reinterpret_cast<uint4*>(my_turn + j * kGroupPitch + (lane & 15) * 64 + (lane >> 4) * 16) = d[j];
+    const bool donor = rl == CASK_ROLE_DONOR;
+    fetch_donors(t + kPrefetch, d, rl);  // refill the registers just freed
+    bf16x8 bres[8];
+    float ss = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const uint4 v = *reinterpret_cast<const uint4*>(my_turn + op_off + ks * 128);
+      ss += sumsq_bf16x8(v);
+      bres[ks] = __builtin_bit_cast(bf16x8, v);
+    }
+    ss += __shfl_xor(ss, 32, 64);
+    const float dinv = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+    const int drow = first + t * kDonorTile + wv * 32 + c32;
+
+    float best = kNegInf;
+    int best_ord = -1;
     for (int sb = 0; sb < M; sb += kSeedBlock) {
       if (!one_block) {
         __syncthreads();  // previous block fully consumed
@@ -152,40 +178,41 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
       const int m_blk = min(kSeedBlock, M - sb);
       for (int s0 = 0; s0 < m_blk; s0 += 32) {
         bf16x8 a[8];
-        const unsigned char* ap = stage + (s0 + c32) * kPitch + h * 16;
+        const unsigned char* ap = seeds + (s0 >> 2) * kGroupPitch + op_off;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 32);
+        for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 128);
+        f32x16 acc = {0};
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
-          f32x16 acc = {0};
+        for (int ks = 0; ks < 8; ++ks)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ks], acc, 0, 0, 0);
 #pragma unroll
-          for (int ks = 0; ks < 8; ++ks)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct][ks], acc, 0, 0, 0);
+        for (int g = 0; g < 4; ++g) {  // ascending seed ordinal within the lane
+          const float4 si = *reinterpret_cast<const float4*>(&seed_inv[s0 + g * 8 + h * 4]);
+          const float sv[4] = {si.x, si.y, si.z, si.w};
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {  // ascending seed ordinal within the lane
-            const int sr = s0 + (r >> 2) * 8 + h * 4 + (r & 3);
-            const float sim = (acc[r] * seed_inv[sr]) * dinv[ct];
-            if (sr < m_blk && sim > best[ct]) {
-              best[ct] = sim;
-              best_ord[ct] = sb + sr;
+          for (int q = 0; q < 4; ++q) {
+            const int sr = s0 + g * 8 + h * 4 + q;
+            const float sim = (acc[g * 4 + q] * sv[q]) * dinv;
+            if (sr < m_blk && sim > best) {
+              best = sim;
+              best_ord = sb + sr;
             }
           }
         }
       }
     }
-#pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
-      const float ob = __shfl_xor(best[ct], 32, 64);
-      const int oo = __shfl_xor(best_ord[ct], 32, 64);
-      if (oo >= 0 && (best_ord[ct] < 0 || better(ob, oo, best[ct], best_ord[ct]))) {
-        best[ct] = ob;
-        best_ord[ct] = oo;
-      }
-      if (h == 0 && drow[ct] < hi) {
-        const bool donor = ro[drow[ct]] == CASK_ROLE_DONOR;
-        assign_ord[row0 + drow[ct]] = (donor && best_ord[ct] >= 0 && best[ct] >= kp.tau) ? best_ord[ct] : -1;
-      }
+    const float ob = __shfl_xor(best, 32, 64);
+    const int oo = __shfl_xor(best_ord, 32, 64);
+    if (oo >= 0 && (best_ord < 0 || better(ob, oo, best, best_ord))) {
+      best = ob;
+      best_ord = oo;
     }
+    if (h == 0 && drow < hi)
+      assign_ord[row0 + drow] = (donor && best_ord >= 0 && best >= kp.tau) ? best_ord : -1;
+  };
+  for (int t = 0; t < n_tiles; t += kPrefetch) {
+#pragma unroll
+    for (int b = 0; b < kPrefetch; ++b) tile_body(t + b, dreg[b], rreg[b]);
   }
 }
 
@@ -516,9 +543,17 @@ hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* r
     const int tiles_per_wg = (tiles + chunks - 1) / chunks;
     chunks = (tiles + tiles_per_wg - 1) / tiles_per_wg;
     const int units8 = (b.n_units + 7) / 8 * 8;
-    similarity_mfma_kernel<<<dim3(units8 * chunks), dim3(256), 0, st>>>(
-        kp, b.n_units, chunks, tiles_per_wg, b.row_off, b.prefix_len,
-        static_cast<const uint16_t*>(b.K), role, seed_rows, n_seeds, assign_ord);
+    // seeds of a unit = slots - core with slots <= B: at most B - core for an explicit core
+    // size, at most ceil(B / 5) for the default four-fifths core share
+    const int seed_bound = kp.core >= 0 ? (kp.B - kp.core > 0 ? kp.B - kp.core : 0) : (kp.B + 4) / 5;
+    if (seed_bound <= kSeedBlock)
+      similarity_mfma_kernel<true><<<dim3(units8 * chunks), dim3(256), 0, st>>>(
+          kp, b.n_units, chunks, tiles_per_wg, b.row_off, b.prefix_len,
+          static_cast<const uint16_t*>(b.K), role, seed_rows, n_seeds, assign_ord);
+    else
+      similarity_mfma_kernel<false><<<dim3(units8 * chunks), dim3(256), 0, st>>>(
+          kp, b.n_units, chunks, tiles_per_wg, b.row_off, b.prefix_len,
+          static_cast<const uint16_t*>(b.K), role, seed_rows, n_seeds, assign_ord);
     return hipGetLastError();
   }
   if (kp.dtype == CASK_F32)
