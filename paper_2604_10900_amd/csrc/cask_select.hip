@@ -32,10 +32,10 @@ struct Kth {
 // wave q then finds the digit of query q.  Inactive queries (k <= 0) are skipped.
 // Scores of one unit crowd into a few digits (the top byte holds sign and exponent), and LDS
 // atomics on one address serialise; so every histogram exists in kHistCopies copies, a lane
-// adds to copy lane % kHistCopies, and the copies are summed before the digit search.
-// All threads of the block must call it; `hist` is 3 x 256 x kHistCopies ints of LDS, `bcast`
+// adds to copy lane % kHistCopies, and the copies are summed in the digit search.
+// All threads of the block must call it; `hist` is 2 x 3 x 256 x kHistCopies ints of LDS, `bcast`
 // 3 x 4 ints.
-constexpr int kHistCopies = 16;
+constexpr int kHistCopies = 8;
 struct Query3 {
   int lo[3], hi[3], k[3];
 };
@@ -66,42 +66,80 @@ __device__ void radix_select3(const float* __restrict__ s, const Query3& q, int 
   int remaining[3] = {q.k[0], q.k[1], q.k[2]};
   int eq_total[3] = {0, 0, 0};
   const bool single = hi_all - lo_all <= kSelChunk;
-  if (single) load_keys(s, lo_all, hi_all, key);
+  // single chunk: bit j of live[e] says that row e of this thread still competes in query j
+  // (inside its range, all digits so far equal to the chosen ones), so later passes skip most
+  // rows with one test
+  uint32_t live[kSelPer];
+  if (single) {
+    load_keys(s, lo_all, hi_all, key);
+#pragma unroll
+    for (int e = 0; e < kSelPer; ++e) {
+      const int i = lo_all + e * kSelThreads + tid;
+      live[e] = 0;
+#pragma unroll
+      for (int j = 0; j < 3; ++j)
+        if (q.k[j] > 0 && i >= q.lo[j] && i < q.hi[j]) live[e] |= 1u << j;
+    }
+  }
+  // queries 1 and 2 over one range have the same first histogram: count it once
+  const bool same12 = q.k[1] > 0 && q.k[2] > 0 && q.lo[1] == q.lo[2] && q.hi[1] == q.hi[2];
+  // Two barriers per pass: rows are counted into one histogram buffer while the other one is
+  // cleared for the next pass; then wave j sums the copies of query j's digits and finds the
+  // digit; the threads pick the result up after the second barrier.
+  constexpr int kHistInts = 768 * kHistCopies;
+  for (int b = tid; b < kHistInts; b += kSelThreads) hist[b] = 0;
+  __syncthreads();
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
-    for (int b = tid; b < 768 * kHistCopies; b += kSelThreads) hist[b] = 0;
-    __syncthreads();
-    for (int base = lo_all; base < hi_all; base += kSelChunk) {
-      if (!single) load_keys(s, base, hi_all, key);
+    int* cur = hist + (pass & 1) * kHistInts;
+    int* nxt = hist + ((pass & 1) ^ 1) * kHistInts;
+    for (int b = tid; b < kHistInts; b += kSelThreads) nxt[b] = 0;
+    const bool share = same12 && pass == 0;
+    if (single) {
 #pragma unroll
       for (int e = 0; e < kSelPer; ++e) {
-        const int i = base + e * kSelThreads + tid;
-        const uint32_t digit = (key[e] >> shift) & 255u;
+        uint32_t lv = live[e];
+        if (share) lv &= ~4u;
+        if (lv != 0u) {
+          const uint32_t digit = (key[e] >> shift) & 255u;
 #pragma unroll
-        for (int j = 0; j < 3; ++j)
-          if (q.k[j] > 0 && i >= q.lo[j] && i < q.hi[j] && (key[e] & mask) == prefix[j])
-            atomicAdd(&hist[(j * 256 + digit) * kHistCopies + (tid & (kHistCopies - 1))], 1);
+          for (int j = 0; j < 3; ++j)
+            if (lv & (1u << j))
+              atomicAdd(&cur[(j * 256 + digit) * kHistCopies + (tid & (kHistCopies - 1))], 1);
+        }
+      }
+    } else {
+      for (int base = lo_all; base < hi_all; base += kSelChunk) {
+        load_keys(s, base, hi_all, key);
+#pragma unroll
+        for (int e = 0; e < kSelPer; ++e) {
+          const int i = base + e * kSelThreads + tid;
+          const uint32_t digit = (key[e] >> shift) & 255u;
+#pragma unroll
+          for (int j = 0; j < 3; ++j)
+            if (q.k[j] > 0 && !(share && j == 2) && i >= q.lo[j] && i < q.hi[j] &&
+                (key[e] & mask) == prefix[j])
+              atomicAdd(&cur[(j * 256 + digit) * kHistCopies + (tid & (kHistCopies - 1))], 1);
+        }
       }
     }
     __syncthreads();
-    if (tid < 768) {  // fold the copies into copy 0
-      int sum = 0;
-#pragma unroll
-      for (int cpy = 0; cpy < kHistCopies; ++cpy) sum += hist[tid * kHistCopies + ((cpy + tid) & (kHistCopies - 1))];
-      hist[tid * kHistCopies] = sum;
-    }
-    __syncthreads();
-    // wave j: lane l owns digits 255-4l .. 252-4l (descending) of query j; find the digit where
-    // the running count from the top reaches `remaining`
+    // wave j: lane l owns digits 255-4l .. 252-4l (descending) of query j (query 2 reads query
+    // 1's counts while they are shared); find the digit where the running count from the top
+    // reaches `remaining`
     if (wv < 3 && q.k[wv] > 0) {
       const int rem = wv == 0 ? remaining[0] : (wv == 1 ? remaining[1] : remaining[2]);
-      const int* hq = hist + wv * 256 * kHistCopies;
+      const int* hq = cur + ((share && wv == 2) ? 1 : wv) * 256 * kHistCopies;
       int h4[4];
       int local = 0;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        h4[e] = hq[(255 - (lane * 4 + e)) * kHistCopies];
-        local += h4[e];
+        const int* bin = hq + (255 - (lane * 4 + e)) * kHistCopies;
+        int sum = 0;
+#pragma unroll
+        for (int cpy = 0; cpy < kHistCopies; ++cpy) sum += bin[(cpy + lane) & (kHistCopies - 1)];
+        h4[e] = sum;
+        local += sum;
       }
       int incl = local;
 #pragma unroll
@@ -131,8 +169,18 @@ __device__ void radix_select3(const float* __restrict__ s, const Query3& q, int 
         eq_total[j] = bcast[j * 4 + 2];
       }
     mask |= 0xFFu << shift;
-    __syncthreads();
+    if (single) {
+#pragma unroll
+      for (int e = 0; e < kSelPer; ++e) {
+        if (live[e] != 0u) {
+#pragma unroll
+          for (int j = 0; j < 3; ++j)
+            if ((live[e] & (1u << j)) && (key[e] & mask) != prefix[j]) live[e] &= ~(1u << j);
+        }
+      }
+    }
   }
+  __syncthreads();  // the caller may reuse `bcast` and `hist`
 #pragma unroll
   for (int j = 0; j < 3; ++j) {
     out[j].key = prefix[j];
@@ -242,7 +290,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     int do_prefix, int do_decode, int do_index, int32_t* __restrict__ slot_of,
     int32_t* __restrict__ out_src, int32_t* __restrict__ out_len, int32_t* __restrict__ seed_rows,
     int32_t* __restrict__ ord_of_slot, int32_t* __restrict__ n_seeds) {
-  __shared__ int hist[3 * 256 * kHistCopies];
+  __shared__ int hist[2 * 3 * 256 * kHistCopies];
   __shared__ int bcast[3 * 4];
   __shared__ int wsum[kSelWaves];
   const int u = blockIdx.x, tid = threadIdx.x;
