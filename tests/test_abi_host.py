@@ -110,3 +110,42 @@ def test_host_validation_needs_no_gpu(cask):
     assert lib.cask_compress(C.byref(ok), C.byref(b1), fake, fake, fake, fake, None, None, None,
                              fake, fake, 1 << 30, None) == cask.binding.EINVAL
     assert cask.load().cask_strerror(cask.binding.ENOMEM).decode() == "workspace too small"
+
+
+def test_host_validation_alignment_and_unit_size(cask):
+    """Misaligned data pointers and units beyond the 32-bit byte-offset limit are refused on the
+    host; nothing is dereferenced."""
+    lib = cask.load()
+    ok = cask.Params().c()
+    ro = np.array([0, 1000], dtype=np.int64)
+    pl = np.array([100], dtype=np.int32)
+    fake = C.c_void_p(4096)
+    odd = C.c_void_p(4096 + 2)
+    good = cask.binding._Batch(1, fake, fake, ro.ctypes.data, pl.ctypes.data, fake, fake, fake)
+    # a well-formed call with a workspace that is too small gets past validation: ENOMEM
+    assert lib.cask_compress(C.byref(ok), C.byref(good), fake, fake, fake, fake, None, None, None,
+                             fake, fake, 16, None) == cask.binding.ENOMEM
+    for k in range(3):
+        ptrs = [fake, fake, fake]
+        ptrs[k] = odd
+        b = cask.binding._Batch(1, fake, fake, ro.ctypes.data, pl.ctypes.data, *ptrs)
+        assert lib.cask_compress(C.byref(ok), C.byref(b), fake, fake, fake, fake, None, None, None,
+                                 fake, fake, 16, None) == cask.binding.EINVAL
+    assert lib.cask_compress(C.byref(ok), C.byref(good), odd, fake, fake, fake, None, None, None,
+                             fake, fake, 16, None) == cask.binding.EINVAL
+    assert lib.cask_compress(C.byref(ok), C.byref(good), fake, fake, fake, fake, None, None, None,
+                             fake, odd, 1 << 40, None) == cask.binding.EINVAL
+    big = np.array([0, 1 << 23], dtype=np.int64)
+    b = cask.binding._Batch(1, fake, fake, big.ctypes.data, pl.ctypes.data, fake, fake, fake)
+    assert lib.cask_score(C.byref(ok), C.byref(b), fake, fake, 1 << 40, None) == cask.binding.EINVAL
+
+
+def test_timing_calls_validate_without_gpu(cask):
+    lib = cask.load()
+    assert lib.cask_timing_enable_stages(4, 0) == cask.binding.EINVAL
+    assert lib.cask_timing_enable_stages(5000, 2) == cask.binding.EINVAL
+    assert lib.cask_timing_enable(0) == cask.binding.OK
+    ms = (C.c_float * 7)()
+    n = C.c_int(-1)
+    assert lib.cask_timing_read(ms, C.byref(n)) == cask.binding.OK and n.value == 0
+    assert lib.cask_timing_read(None, C.byref(n)) == cask.binding.EINVAL

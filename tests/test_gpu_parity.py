@@ -135,6 +135,43 @@ def test_prompt_heavy_two_stage_and_exhausted():
     _note(st)
 
 
+def test_many_seeds_take_several_lds_blocks():
+    """A small explicit core leaves hundreds of seeds per unit: the similarity kernel then walks
+    the seeds block by block for every donor tile."""
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=2, prefix=64, decode=2500, budget=900)
+    c = caches.make(w, seed=5)
+    p = parity.params_of(w, core=100, sim_threshold=0.3)
+    pl = cask.plan(p, 64, 2564)
+    assert pl["seeds"] > 384
+    st = parity.full_check(c, p, expect_folds=True)
+    _note(st)
+
+
+def test_stage_timing_api():
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=2, decode=1200)
+    c = caches.make(w)
+    p = parity.params_of(w)
+    b = parity.to_device(c, p)
+    out = cask.compress(b)
+    torch.cuda.synchronize()
+    ref_src = out.out_src.clone()
+    cask.binding.timing_enable(3)
+    for _ in range(4):          # the fourth call is beyond the armed count: not recorded
+        cask.compress(b, out)
+    ms, n = cask.binding.timing_read()
+    assert n == 3 and set(ms) == set(cask.binding.STAGES)
+    assert all(v >= 0 for v in ms.values()) and ms["score_rows"] > 0 and ms["emit"] > 0
+    cask.binding.timing_enable(2, 2)   # only the two scoring sweeps
+    cask.compress(b, out)
+    cask.compress(b, out)
+    ms2, n2 = cask.binding.timing_read()
+    assert n2 == 2 and ms2["score_rows"] > 0 and ms2["score_cols"] > 0
+    assert all(ms2[k] == 0 for k in cask.binding.STAGES[2:])
+    cask.binding.timing_enable(0)
+    torch.cuda.synchronize()
+    assert torch.equal(out.out_src, ref_src)   # recording changes nothing
+
+
 def test_ragged_batch_llama_shape():
     w = caches.scaled(W["cfg5"], n_seqs=5, n_layers=1, n_kv_heads=2, decode=300, decode_hi=3000)
     c = caches.make(w)
@@ -291,6 +328,9 @@ def test_argument_errors_and_empty_batch():
             fn()
         assert e.value.code == code
 
+    Kodd = torch.zeros(100 * 128 + 8, dtype=torch.bfloat16, device=dev)[1:1 + 100 * 128].view(100, 128)
+    mis = cask.Batch(p, torch.tensor([0, 100]), torch.tensor([10], dtype=torch.int32), Kodd, K, Q)
+    expect(cask.binding.EINVAL, lambda: cask.compress(mis))              # K not 16-byte aligned
     short = cask.Batch(p, torch.tensor([0, 10]), torch.tensor([0], dtype=torch.int32), K, K, Q)
     expect(cask.binding.EINVAL, lambda: cask.compress(short))            # N < W
     badp = cask.Batch(p, torch.tensor([0, 100]), torch.tensor([101], dtype=torch.int32), K, K, Q)
