@@ -89,9 +89,11 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
   const uint16_t* Ku = K + (size_t)row0 * kD;
   const uint8_t* ro = role + row0;
   const int32_t* srow = seed_rows + (size_t)u * kp.B;
-  // rows past the donor range read as zero through the descriptor's bounds check
+  // rows past this workgroup's share of the donor range read as zero through the descriptor's
+  // bounds check, without touching memory
+  const int last = min(hi, first + n_tiles * kDonorTile);
   const __amdgpu_buffer_rsrc_t krsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(Ku), 0, hi * kRowBytes, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(Ku), 0, last * kRowBytes, 0x00020000);
 
   // ---- donor stream: the wave's 32 rows of tile t, 4 rows per load
   // (the role of the lane's donor row rides along, so that nothing at the end of a tile has
@@ -207,7 +209,7 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
       best = ob;
       best_ord = oo;
     }
-    if (h == 0 && drow < hi)
+    if (h == 0 && drow < last)  // rows past the workgroup's share belong to another one
       assign_ord[row0 + drow] = (donor && best_ord >= 0 && best >= kp.tau) ? best_ord : -1;
   };
   for (int t = 0; t < n_tiles; t += kPrefetch) {

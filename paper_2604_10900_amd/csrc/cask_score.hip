@@ -68,6 +68,7 @@ __device__ inline bool map_block(int n_units, int tiles_per_unit, int& unit, int
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;
 constexpr int kRowBytes = kD * 2;
@@ -77,31 +78,19 @@ constexpr int kResRows = kWaves * 64;        // resident rows per workgroup (64 
 constexpr int kStageRows = 64;               // stream rows per ring slot
 constexpr int kGroupPitch = 1024 + 64;       // LDS pitch of a 4-row group (see stage layout)
 constexpr int kDataBytes = (kStageRows / 4) * kGroupPitch;
-constexpr int kStageBytes = kDataBytes + kStageRows * 16;  // + one 16-byte bias entry per row (sweep B)
+constexpr int kStageBytes = kDataBytes + kStageRows * 4;   // + one float per row: -L_row (sweep B)
 constexpr int kDepth = 4;                    // ring slots: loads run kDepth - 1 stages ahead
 constexpr int kLoadsPerThread = kStageRows * 16 / kThreads;  // 16-byte pieces per thread per stage
 
-// Pad value of -L for window rows past W*G: large, finite (inf would turn 0 * inf into NaN
-// inside the matrix core), and far enough down that exp2 flushes to zero.
+// Pad value of -L for window rows past W*G: far enough down that exp2 flushes to zero.
 constexpr float kPadNegL = -1.0e30f;
 
-// Three bf16 whose sum is x to fp32 precision (8 + 8 + 8 significant bits).
-__device__ inline void split3_bf16(float x, uint16_t& hi, uint16_t& mid, uint16_t& lo) {
-  hi = float_to_bf16_bits(x);
-  const float r1 = x - bf16_bits_to_float(hi);
-  mid = float_to_bf16_bits(r1);
-  const float r2 = r1 - bf16_bits_to_float(mid);
-  lo = float_to_bf16_bits(r2);
-}
-
-// Per window row of a unit: -L_row / c as three bf16 (8 bytes), L_row the base-2 log-sum-exp
-// combined over the key splits of sweep A.  Sweep B feeds it to the matrix cores as a ninth
-// k-step, so its epilogue needs no per-row operand.
+// Per window row of a unit: -L_row, L_row the base-2 log-sum-exp combined over the key splits
+// of sweep A.  Sweep B adds it to every logit of the row inside the exponent's fma.
 __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_splits, int mq_pad,
                                                          const float2* __restrict__ rowstat,
-                                                         uint4* __restrict__ bias) {
+                                                         float* __restrict__ bias) {
   const int unit = blockIdx.x;
-  const float inv_c = 1.0f / kp.scale_log2;
   const float2* part = rowstat + (size_t)unit * n_splits * mq_pad;
   for (int r = threadIdx.x; r < mq_pad; r += 256) {
     float nl = kPadNegL;
@@ -113,9 +102,7 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
       }
       nl = -(m + log2f(l));
     }
-    uint16_t b0, b1, b2;
-    split3_bf16(nl * inv_c, b0, b1, b2);
-    bias[(size_t)unit * mq_pad + r] = make_uint4((uint32_t)b0 | ((uint32_t)b1 << 16), (uint32_t)b2, 0, 0);
+    bias[(size_t)unit * mq_pad + r] = nl;
   }
 }
 
@@ -144,8 +131,8 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
 //   sweep A  fma, exp2, add: the running maximum is lazy -- exp2 is taken against a per-lane
 //            reference that is only raised when a tile's sum threatens fp32 range (one test
 //            per tile); exact, because (reference, sum) pairs combine exactly;
-//   sweep B  mul, exp2, add: -L_row is already in the accumulator (ninth k-step: the bias
-//            terms meet ones in the resident operand).
+//   sweep B  fma, exp2, add: the fma adds -L_row, read from LDS next to the stage's rows (a lane's
+//            16 rows of a tile are four float4 reads).
 // Stages that touch masked keys (causal tail, ragged end) or initialise the reference take a
 // plain, unpipelined path with explicit masks.
 template <int MODE>
@@ -153,8 +140,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     KParams kp, int n_units, int tiles_per_unit, int n_splits, int split_len, int mq_pad,
     const int64_t* __restrict__ row_off, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ Q, float2* __restrict__ rowstat,
-    const uint4* __restrict__ bias, float* __restrict__ scores) {
-  constexpr int NK = (MODE == 0) ? 8 : 9;  // k-steps per tile
+    const float* __restrict__ bias, float* __restrict__ scores) {
+  constexpr int NK = 8;  // k-steps per tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* ring = smem;
 
@@ -213,17 +200,17 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     const int grp = wv + kWaves * j;  // 4-row group of the stage this wave's load j fills
     ld_voff[j] = (grp * 4 + (lane & 3)) * kRowBytes + (lane >> 2) * 16;
   }
-  // sweep B: the bias entries of a stage's 64 rows are one more 1 KB load, taken in turn by
-  // the waves (stage % kWaves), so every wave has at most one extra load in flight
+  // sweep B: the -L_row of a stage's 64 rows is one more 256-byte load, taken in turn by the
+  // waves (stage % kWaves), so every wave has at most one extra load in flight
   const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint4*>(bias + (size_t)unit * mq_pad), 0, mq_pad * 16, 0x00020000);
+      const_cast<float*>(bias + (size_t)unit * mq_pad), 0, mq_pad * 4, 0x00020000);
   auto issue_stage = [&](int stage) {  // rows past s_end read as zero through the descriptor
     unsigned char* slot = ring + (stage % kDepth) * kStageBytes;
     const int soff = (s_begin + stage * kStageRows) * kRowBytes;
     if (MODE == 1 && (stage & (kWaves - 1)) == wv)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
-          brsrc, (__attribute__((address_space(3))) void*)(slot + kDataBytes), 16, lane * 16,
-          (s_begin + stage * kStageRows) * 16, 0, 0);
+          brsrc, (__attribute__((address_space(3))) void*)(slot + kDataBytes), 4, lane * 4,
+          (s_begin + stage * kStageRows) * 4, 0, 0);
 #pragma unroll
     for (int j = 0; j < kLoadsPerThread; ++j) {
       const int grp = wv + kWaves * j;
@@ -254,10 +241,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(res_rsrc, r * kRowBytes + h * 16, ks * 32, 0);
       bres[ct][ks] = __builtin_bit_cast(bf16x8, v);
     }
-    if (NK == 9) {  // ones that pick up the three bias terms; the upper k-half contributes nothing
-      uint4 v = (h == 0) ? make_uint4(0x3F803F80u, 0x00003F80u, 0, 0) : make_uint4(0, 0, 0, 0);
-      bres[ct][NK - 1] = *reinterpret_cast<bf16x8*>(&v);
-    }
   }
   // a wave whose resident rows are all past the end only helps with loads and barriers
   const bool wave_live = res_base + wv * 64 < res_limit;
@@ -268,8 +251,18 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     const unsigned char* p = slot + rt * 8 * kGroupPitch + a_off;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(p + ks * 128);
-    if (NK == 9) {
-      a[NK - 1] = *reinterpret_cast<const bf16x8*>(slot + kDataBytes + (rt * 32 + c32) * 16);
+  };
+  // sweep B: -L of the lane's 16 rows of tile row rt (accumulator order)
+  auto load_nl = [&](float (&nl)[16], const unsigned char* slot, int rt) {
+    if (MODE == 1) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        // read with the operands' vector type: a differently typed LDS read is taken to alias
+        // the ring's loads still in flight and would wait for all of them
+        const bf16x8 raw = *reinterpret_cast<const bf16x8*>(slot + kDataBytes + (rt * 32 + g * 8 + h * 4) * 4);
+        const f32x4 v = __builtin_bit_cast(f32x4, raw);
+        nl[g * 4 + 0] = v[0]; nl[g * 4 + 1] = v[1]; nl[g * 4 + 2] = v[2]; nl[g * 4 + 3] = v[3];
+      }
     }
   };
 
@@ -288,7 +281,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
 
   // ---- epilogues
   float tsum = 0.f;  // sweep A: sum of the tile in flight
-  auto piece = [&](const f32x16& acc, int ct, int i) {  // two logits of the fast epilogue
+  auto piece = [&](const f32x16& acc, const float (&nl)[16], int ct, int i) {  // two logits of the fast epilogue
     if (MODE == 0) {
       const float nm = -m_ref[ct];
       tsum += fast_exp2(__builtin_fmaf(acc[2 * i], c, nm));
@@ -297,8 +290,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       // of the MFMA chain they are meant to overlap with
       asm volatile("" : "+v"(tsum));
     } else {
-      colsum[ct] += fast_exp2(acc[2 * i] * c);
-      colsum[ct] += fast_exp2(acc[2 * i + 1] * c);
+      colsum[ct] += fast_exp2(__builtin_fmaf(acc[2 * i], c, nl[2 * i]));
+      colsum[ct] += fast_exp2(__builtin_fmaf(acc[2 * i + 1], c, nl[2 * i + 1]));
       asm volatile("" : "+v"(colsum[ct]));
     }
   };
@@ -326,7 +319,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       tsum = 0.f;
     }
   };
-  auto slow_tile = [&](f32x16& acc, int ct, int trow0) {
+  auto slow_tile = [&](f32x16& acc, const float (&nl)[16], int ct, int trow0) {
     if (MODE == 0) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -341,7 +334,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = trow0 + (r >> 2) * 8 + h * 4 + (r & 3);
-        const float y = (row < first_row[ct]) ? kNegInf : acc[r] * c;
+        const float y = (row < first_row[ct]) ? kNegInf : __builtin_fmaf(acc[r], c, nl[r]);
         sum += fast_exp2(y);
       }
       colsum[ct] += sum;
@@ -354,10 +347,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct][ks], acc, 0, 0, 0);
   };
   // chain of the new tile interleaved with the fast epilogue of the old one
-  auto fused = [&](f32x16& acc_new, const bf16x8(&a)[NK], int ct_new, const f32x16& acc_old, int ct_old) {
+  auto fused = [&](f32x16& acc_new, const bf16x8(&a)[NK], int ct_new, const f32x16& acc_old,
+                   const float (&nl_old)[16], int ct_old) {
 #pragma unroll
     for (int ks = 0; ks < NK; ++ks) {
-      if (ks < 8) piece(acc_old, ct_old, ks);
+      piece(acc_old, nl_old, ct_old, ks);
       acc_new = (ks == 0)
                     ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], bres[ct_new][0], f32x16{0}, 0, 0, 0)
                     : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct_new][ks], acc_new, 0, 0, 0);
@@ -365,9 +359,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
     finish_fast(acc_old, ct_old);
   };
-  auto drain = [&](const f32x16& acc_old, int ct_old) {
+  auto drain = [&](const f32x16& acc_old, const float (&nl_old)[16], int ct_old) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) piece(acc_old, ct_old, i);
+    for (int i = 0; i < 8; ++i) piece(acc_old, nl_old, ct_old, i);
     finish_fast(acc_old, ct_old);
   };
 
@@ -394,6 +388,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   auto slot_of = [&](int it) -> const unsigned char* { return ring + (it % kDepth) * kStageBytes; };
   f32x16 acc0, acc1;
   bf16x8 a0[NK], a1[NK];
+  float nl0[16], nl1[16];  // sweep B: -L of the rows of tile rows 0 and 1 of the stage in flight
   auto slow_stage = [&](int it) {
     const unsigned char* cur = slot_of(it);
     const int stage_base = s_begin + it * kStageRows;
@@ -402,10 +397,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       const int trow0 = stage_base + rt * 32;
       if (trow0 >= s_end) continue;
       load_a(a0, cur, rt);
+      load_nl(nl0, cur, rt);
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct) {
         chain(acc0, a0, ct);
-        slow_tile(acc0, ct, trow0);
+        slow_tile(acc0, nl0, ct, trow0);
       }
     }
     if (MODE == 0) {
@@ -446,6 +442,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   if (f1 > f0) {
     stage_sync(f0);
     load_a(a0, slot_of(f0), 0);
+    load_nl(nl0, slot_of(f0), 0);
     if (MODE == 0 && f0 == 0) {
       // Nothing seen yet: the first logit of the lane's own row is a safe reference.  Too low
       // is caught by the range guard of the fast epilogue; too high only means every other
@@ -460,15 +457,17 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     for (it = f0;; ++it) {
       const unsigned char* cur = slot_of(it);
       load_a(a1, cur, 1);
-      fused(acc1, a0, 1, acc0, 0);
+      load_nl(nl1, cur, 1);
+      fused(acc1, a0, 1, acc0, nl0, 0);
       load_a(a0, slot_of(it + 1), 0);  // a0 is free: operands of the coming stage
-      fused(acc0, a1, 0, acc1, 1);
-      fused(acc1, a1, 1, acc0, 0);
+      fused(acc0, a1, 0, acc1, nl0, 1);
+      load_nl(nl0, slot_of(it + 1), 0);  // the last tile of tile row 0 is through its epilogue
+      fused(acc1, a1, 1, acc0, nl1, 0);
       if (it + 1 >= f1) break;
       stage_sync(it + 1);
-      fused(acc0, a0, 0, acc1, 1);
+      fused(acc0, a0, 0, acc1, nl1, 1);
     }
-    drain(acc1, 1);
+    drain(acc1, nl1, 1);
     it = f1;
   }
   for (; it < n_stages; ++it) {
@@ -620,7 +619,7 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
                       : launch_fma<uint16_t, 128>(kp, b, wl, ws, scores, st, between);
   }
   float2* rowstat = reinterpret_cast<float2*>(ws + wl.rowstat);
-  uint4* bias = reinterpret_cast<uint4*>(ws + wl.bias);
+  float* bias = reinterpret_cast<float*>(ws + wl.bias);
   const int units8 = (b.n_units + 7) / 8 * 8;
   const uint16_t* K = static_cast<const uint16_t*>(b.K);
   const uint16_t* Q = static_cast<const uint16_t*>(b.Q);
