@@ -32,21 +32,22 @@ PEAK_HBM_GBS = 8000.0
 # traffic (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0; profiles/cfg2_hbm_traffic.md).  None where
 # not measured.
 MEASURED_TRAFFIC = {
-    "cfg2": {"score_rows": (130947.5 * 2.0 + 1568.0) * 1024, "score_cols": (134943.2 * 2.0 + 3696.0) * 1024},
+    "cfg2": {"score_rows": (131173.9 * 2.0 + 1568.0) * 1024, "score_cols": (131103.7 * 2.0 + 3696.0) * 1024},
 }
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20,
+                    help="untimed events first; the clocks settle within about 20")
     ap.add_argument("--workload", default="cfg2", help="cfg2 (default) | cfg3 | cfg4 | cfg4v | cfg5")
     ap.add_argument("--layers", type=int, default=0, help="use only the first L layers (0 = all)")
     ap.add_argument("--seqs", type=int, default=0, help="cfg5: use only the first S sequences")
     ap.add_argument("--copies", type=int, default=0,
                     help="input copies alternated between steps (0 = 2 when they fit in 2 GB)")
-    ap.add_argument("--cpu-units", type=int, default=16, help="units the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-units", type=int, default=48, help="units the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--pmc-copy-mib", type=int, default=0,
                     help="also run one fp32 -> bf16 conversion of a buffer of this many MiB (a kernel of "
                          "known traffic, N MiB read and N/2 MiB written, for scaling rocprofv3 "

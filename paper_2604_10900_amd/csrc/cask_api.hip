@@ -50,7 +50,7 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
   };
   const size_t rows = (size_t)total_rows, units = (size_t)n_units;
   w.rowstat = take(units * n_splits * w.mq_pad * sizeof(float2));
-  w.bias = take(units * w.mq_pad * sizeof(uint4));
+  w.bias = take(units * w.mq_pad * sizeof(float));
   w.scores = take(rows * sizeof(float));
   w.role = take(rows);
   w.slot_of = take(rows * sizeof(int32_t));

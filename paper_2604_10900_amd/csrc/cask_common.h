@@ -131,7 +131,7 @@ __device__ inline float wave_sum(float v) {
 struct Workspace {
   // all offsets in bytes from the workspace base, 256-byte aligned
   size_t rowstat;    // float2 [n_units][n_splits][mq_pad]: per-split running (max, sum) per window row
-  size_t bias;       // uint4  [n_units][mq_pad]: -L_row / c of every window row as three bf16 (+ zero fill)
+  size_t bias;       // float  [n_units][mq_pad]: -L_row of every window row (base-2 log-sum-exp over all keys)
   size_t scores;     // float  [total_rows] (used when the caller passes no score buffer)
   size_t role;       // uint8  [total_rows]
   size_t slot_of;    // int32  [total_rows] output slot of kept rows, -1 otherwise

@@ -3,7 +3,7 @@
 //                when the cosine reaches tau (bf16 d=128: MFMA contraction seeds x donors^T,
 //                each lane owns one donor and scans its seeds in ascending order);
 //   gather       ordered list of the donors that merge (ascending row), per unit;
-//   emit         one wavefront per output row: kept tokens are copied bit for bit, a seed
+//   emit         sixteen lanes per output row: kept tokens are copied bit for bit, a seed
 //                with donors becomes the weighted fold m = sum a_i, k~ = sum a_i k_i / m,
 //                v~ = sum a_i v_i / m with a_i the token's score, accumulated in fp32 in
 //                ascending row order (fixed order: reruns are bitwise identical).

@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
 //            per tile); exact, because (reference, sum) pairs combine exactly;
 //   sweep B  fma, exp2, add: the fma adds -L_row, read from LDS next to the stage's rows (a lane's
 //            16 rows of a tile are four float4 reads).
-// Stages that touch masked keys (causal tail, ragged end) or initialise the reference take a
+// Stages that touch masked entries (causal tail, ragged end, keys inside the window) take a
 // plain, unpipelined path with explicit masks.
 template <int MODE>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
