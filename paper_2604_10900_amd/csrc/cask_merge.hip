@@ -84,6 +84,11 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
   const int n_tiles = min(tiles_per_wg, (hi - first + kDonorTile - 1) / kDonorTile);
   const int M = n_seeds[u];
   const int tid = threadIdx.x, lane = tid & 63;
+  if (M == 0) {  // no seed to fold into: nothing to read
+    const int end = min(hi, first + n_tiles * kDonorTile);
+    for (int i = first + tid; i < end; i += 256) assign_ord[row0 + i] = -1;
+    return;
+  }
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: feeds scalar load offsets
   const int c32 = lane & 31, h = lane >> 5;
   const uint16_t* Ku = K + (size_t)row0 * kD;
@@ -539,7 +544,10 @@ hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* r
     // the unit's donor tiles
     const int tiles = (b.max_decode_len + kDonorTile - 1) / kDonorTile;
     if (tiles == 0) return hipSuccess;
+    // (with more units than workgroup slots, units of different length would leave the longest
+    // ones running alone at the end: cut them into pieces of about 32 tiles instead)
     int chunks = b.n_units > 0 ? 512 / b.n_units : 1;
+    if (chunks < 1) chunks = (tiles + 31) / 32;
     if (chunks < 1) chunks = 1;
     if (chunks > tiles) chunks = tiles;
     const int tiles_per_wg = (tiles + chunks - 1) / chunks;
