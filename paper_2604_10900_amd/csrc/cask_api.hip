@@ -17,20 +17,26 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, int max_unit_len) {
   Workspace w;
   std::memset(&w, 0, sizeof(w));
-  // Key splits of the row-statistics sweep.  Long splits amortise the unpipelined first stage
-  // of every split; short ones are only worth it when there are too few (unit, row block)
-  // pairs to occupy the 256 compute units.
+  // Key splits of the row-statistics sweep: more splits mean more, shorter workgroups (better
+  // balance over the 512 workgroup slots, two per compute unit) but a fixed cost per workgroup.
+  // Measured on this kernel, a launch takes about (rounds of 512 workgroups, rounded up to a
+  // half) x (stages per workgroup + 4); take the split count that minimises it.
   const int row_blocks = (kp.Mq + 255) / 256;
-  int n_splits = (max_unit_len + 4607) / 4608;
   const int64_t pairs = (int64_t)n_units * row_blocks;
-  if (pairs > 0 && pairs < 256) {
-    const int want = (int)((256 + pairs - 1) / pairs);
-    const int cap = max_unit_len / 256;
-    const int more = want < cap ? want : cap;
-    if (more > n_splits) n_splits = more;
+  int n_splits = 1;
+  double best_cost = 0.0;
+  for (int sp = 1; sp <= 64; ++sp) {
+    const int len = (int)align_up((size_t)(max_unit_len + sp - 1) / sp, 64);
+    if (sp > 1 && len < 1024) break;
+    const int eff = len > 0 ? (max_unit_len + len - 1) / len : 1;
+    const int64_t wgs = pairs * eff;
+    const double rounds = 0.5 * (double)((wgs + 255) / 256);
+    const double cost = rounds * (len / 64 + 4);
+    if (sp == 1 || cost < best_cost) {
+      best_cost = cost;
+      n_splits = sp;
+    }
   }
-  if (n_splits < 1) n_splits = 1;
-  if (n_splits > 64) n_splits = 64;
   if (const char* e = std::getenv("CASK_SPLITS")) {
     const int v = std::atoi(e);
     if (v >= 1 && v <= 64) n_splits = v;
