@@ -175,7 +175,10 @@ def main():
                 "kernel_ms": round(sweep_ms[dom], 4),
                 "flops_per_launch": flops_pass,
                 "both_sweeps_frac": round(2 * flops_pass / ((sweep_ms["score_rows"] + sweep_ms["score_cols"]) * 1e-3)
-                                          / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4)}
+                                          / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4),
+                # whole event against its own bound: one algorithmic Q.K^T pass at MFMA peak
+                "event_frac_of_one_pass_at_peak": round(flops_pass / (ms_per_step * 1e-3) / 1e12
+                                                        / PEAK_MFMA_BF16_TFLOPS, 4)}
 
     # ---- CPU oracle on a bounded sample of the same units (rank 0, N = 1 only)
     cpu = None

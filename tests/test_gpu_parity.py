@@ -314,6 +314,49 @@ def test_two_runs_are_bitwise_identical():
             assert np.array_equal(a[k], o[k]), k
 
 
+def test_compress_replays_from_a_hip_graph():
+    """The whole event is plain kernel launches on the caller's stream (no allocation, no
+    synchronisation, no memset): it can be captured once and replayed; every replay must equal
+    the eager result, with eager work in between."""
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=3, decode=2100)
+    c = caches.make(w, seed=9)
+    p = parity.params_of(w, sim_threshold=0.5)
+    b = parity.to_device(c, p)
+    eager = cask.compress(b)
+    torch.cuda.synchronize()
+    want = {k: getattr(eager, k).clone() for k in ("K_out", "V_out", "out_src", "out_len", "out_mass", "assign", "status", "scores")}
+    out = cask.Outputs(b)
+    b.workspace()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        cask.compress(b, out)          # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cask.compress(b, out)
+    for rep in range(3):
+        for t in (out.K_out, out.V_out, out.out_mass, out.scores):
+            t.zero_()
+        out.out_src.fill_(-7)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        L = want["out_len"]
+        assert torch.equal(out.out_len, L) and torch.equal(out.status, want["status"])
+        assert torch.equal(out.assign, want["assign"]) and torch.equal(out.scores, want["scores"])
+        for u in range(b.n_units):
+            n = int(L[u])
+            assert torch.equal(out.out_src[u, :n], want["out_src"][u, :n])
+            assert torch.equal(out.K_out[u, :n], want["K_out"][u, :n])
+            assert torch.equal(out.V_out[u, :n], want["V_out"][u, :n])
+            assert torch.equal(out.out_mass[u, :n], want["out_mass"][u, :n])
+        cask.score(b)                  # eager work between the replays
+        torch.cuda.synchronize()
+    _note("graph replays equal the eager event")
+
+
 def test_argument_errors_and_empty_batch():
     dev = torch.device("cuda:0")
     p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=2, window=16, budget=64)
