@@ -519,3 +519,41 @@ int cask_ref_compress(const cask_ref_params* p, int32_t n_units, const int64_t* 
   }
   return 0;
 }
+
+/* Representative-set mass diagnostics (Section 2.6):
+ *   rho_core = sum_{k in C} s_k / sum_{k in TopK} s_k,
+ *   rho_rep  = sum_{k in R} s_k / sum_{k in TopK} s_k.
+ * Readings (the paper names an oracle scorer and a k without fixing either):
+ *   s     the event's own score vector -- no other scorer exists at this boundary;
+ *   TopK  the min(B, N) best rows of the unit in the order (score descending, index
+ *         ascending): what plain top-k eviction to the same budget would keep;
+ *   C     the rows protection keeps verbatim: prefix survivors, decode core, recent tail;
+ *   R     the output rows; a representative counts with the mass of its whole group, so the
+ *         sum over R is the sum of out_mass (rho_rep can exceed 1 when folding recovers mass
+ *         from outside TopK).
+ * A unit whose TopK mass is zero reports 1 for both: there is nothing to lose. */
+int cask_ref_mass_diagnostics(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                              const float* scores, const uint8_t* role, const float* out_mass,
+                              const int32_t* out_len, float* rho) {
+  if (!p || !row_off || !scores || !role || !out_mass || !out_len || !rho || n_units < 0) return -1;
+  if (check_shape(p) != 0) return -1;
+  for (int32_t u = 0; u < n_units; ++u) {
+    const int64_t row0 = row_off[u];
+    const int32_t N = (int32_t)(row_off[u + 1] - row0);
+    const float* s = scores + row0;
+    ranked_t* r = rank_range(s, 0, N);
+    const int32_t k = N < p->budget ? N : p->budget;
+    double top = 0.0, core = 0.0, rep = 0.0;
+    for (int32_t t = 0; t < k; ++t) top += (double)r[t].s;
+    free(r);
+    for (int32_t i = 0; i < N; ++i) {
+      const uint8_t ro = role[row0 + i];
+      if (ro == CASK_REF_PREFIX_KEEP || ro == CASK_REF_CORE || ro == CASK_REF_RECENT) core += (double)s[i];
+    }
+    for (int32_t t = 0; t < out_len[u]; ++t) rep += (double)out_mass[(int64_t)u * p->budget + t];
+    rho[2 * u + 0] = top > 0.0 ? (float)(core / top) : 1.0f;
+    rho[2 * u + 1] = top > 0.0 ? (float)(rep / top) : 1.0f;
+  }
+  return 0;
+}
+

@@ -118,6 +118,13 @@ int cask_ref_compress(const cask_ref_params* p, int32_t n_units, const int64_t* 
                       int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
                       uint8_t* role, int32_t* status, int n_threads);
 
+/* Representative-set mass diagnostics of Section 2.6 (see the definition in the source for the
+ * readings of TopK, C and R).  role, out_mass, out_len as produced by cask_ref_compress.
+ * rho: [n_units][2] = {rho_core, rho_rep}. */
+int cask_ref_mass_diagnostics(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                              const float* scores, const uint8_t* role, const float* out_mass,
+                              const int32_t* out_len, float* rho);
+
 #ifdef __cplusplus
 }
 #endif

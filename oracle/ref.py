@@ -216,3 +216,22 @@ def compress(p: Params, row_off, prefix_len, K, V, Q, scores=None, n_threads: in
         raise ValueError(f"cask_ref_compress: {rc}")
     return dict(K_out=K_out, V_out=V_out, out_len=out_len, out_src=out_src, out_mass=out_mass,
                 assign=assign, role=role, status=status, scores=scores)
+
+
+def mass_diagnostics(p: Params, row_off, scores, role, out_mass, out_len) -> np.ndarray:
+    """(rho_core, rho_rep) per unit, Section 2.6; inputs as returned by compress()."""
+    row_off = np.ascontiguousarray(row_off, dtype=np.int64)
+    n_units = len(row_off) - 1
+    scores = np.ascontiguousarray(scores, dtype=np.float32)
+    role = np.ascontiguousarray(role, dtype=np.uint8)
+    out_mass = np.ascontiguousarray(out_mass, dtype=np.float32)
+    out_len = np.ascontiguousarray(out_len, dtype=np.int32)
+    assert out_mass.shape == (n_units, p.budget) and scores.size == int(row_off[-1]) == role.size
+    rho = np.zeros((n_units, 2), dtype=np.float32)
+    cp = p.c()
+    rc = lib().cask_ref_mass_diagnostics(C.byref(cp), C.c_int32(n_units), _ptr(row_off), _ptr(scores),
+                                         _ptr(role), _ptr(out_mass), _ptr(out_len), _ptr(rho))
+    if rc:
+        raise ValueError(f"cask_ref_mass_diagnostics: {rc}")
+    return rho
+

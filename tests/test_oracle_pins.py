@@ -612,3 +612,69 @@ def test_multi_unit_ragged_batch_equals_unit_by_unit(oracle):
         np.testing.assert_array_equal(out["assign"][sl], one["assign"])
         np.testing.assert_array_equal(out["scores"][sl], one["scores"])
         assert out["status"][u] == one["status"][0]
+
+
+# ------------------------------------------------------------------ mass diagnostics (Section 2.6)
+
+def test_mass_diagnostics_match_a_library_sort(oracle):
+    """rho_core and rho_rep against numpy: TopK mass from numpy's own sort, the core and
+    representative masses summed directly, over several regimes and budgets."""
+    rng = np.random.default_rng(31)
+    for tau, B, P, D in ((0.9, 64, 20, 120), (0.3, 48, 0, 200), (-1.0, 40, 60, 90), (2.0, 64, 300, 40)):
+        p, K, V, Q, ro, pl, _ = make_case(rng, oracle, P=P, D=D, B=B, tau=tau)
+        out = oracle.compress(p, ro, pl, K, V, Q)
+        rho = oracle.mass_diagnostics(p, ro, out["scores"], out["role"], out["out_mass"], out["out_len"])
+        s = out["scores"].astype(np.float64)
+        top = np.sort(s, kind="stable")[::-1][:min(B, s.size)].sum()
+        prot = np.isin(out["role"], [oracle.PREFIX_KEEP, oracle.CORE, oracle.RECENT])
+        L = int(out["out_len"][0])
+        want = np.array([s[prot].sum() / top, out["out_mass"][0, :L].astype(np.float64).sum() / top])
+        np.testing.assert_allclose(rho[0], want, rtol=2e-7)
+        assert 0.0 <= rho[0, 0] <= rho[0, 1] * (1 + 1e-6)          # C is part of R
+        assert rho[0, 1] <= s.sum() / top * (1 + 1e-6)             # R holds no more than everything
+
+
+def test_mass_diagnostics_closed_forms(oracle):
+    rng = np.random.default_rng(32)
+    # identity regime (N <= B): everything is protected and kept, both ratios are exactly 1
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, P=10, D=40, B=64)
+    out = oracle.compress(p, ro, pl, K, V, Q)
+    rho = oracle.mass_diagnostics(p, ro, out["scores"], out["role"], out["out_mass"], out["out_len"])
+    np.testing.assert_array_equal(rho, np.ones((1, 2), dtype=np.float32))
+    # constant scores and no merging: the ratios count rows -- |C| / B and out_len / B = 1
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, P=30, D=150, B=64, tau=2.0)
+    N = K.shape[0]
+    s = np.full(N, 0.25, dtype=np.float32)
+    out = oracle.compress(p, ro, pl, K, V, Q, scores=s)
+    rho = oracle.mass_diagnostics(p, ro, s, out["role"], out["out_mass"], out["out_len"])
+    n_prot = int(np.isin(out["role"], [oracle.PREFIX_KEEP, oracle.CORE, oracle.RECENT]).sum())
+    plan = oracle.plan(p, 30, N)
+    assert n_prot == plan["p_keep"] + plan["core"] + plan["r_eff"]
+    np.testing.assert_allclose(rho[0], [n_prot / 64.0, 1.0], rtol=1e-7)
+    # scaling every score by a power of two changes nothing
+    s2 = (rng.random(N) ** 2).astype(np.float32)
+    a = oracle.compress(p, ro, pl, K, V, Q, scores=s2)
+    b = oracle.compress(p, ro, pl, K, V, Q, scores=s2 * np.float32(64.0))
+    ra = oracle.mass_diagnostics(p, ro, s2, a["role"], a["out_mass"], a["out_len"])
+    rb = oracle.mass_diagnostics(p, ro, s2 * np.float32(64.0), b["role"], b["out_mass"], b["out_len"])
+    np.testing.assert_array_equal(ra, rb)
+    # all scores zero: nothing to lose
+    z = np.zeros(N, dtype=np.float32)
+    o = oracle.compress(p, ro, pl, K, V, Q, scores=z)
+    np.testing.assert_array_equal(oracle.mass_diagnostics(p, ro, z, o["role"], o["out_mass"], o["out_len"]),
+                                  np.ones((1, 2), dtype=np.float32))
+
+
+def test_mass_diagnostics_pure_eviction_of_the_best_rows(oracle):
+    """No prefix, no recent tail, tau above 1: the event is plain top-B eviction, so the kept set
+    IS TopK and rho_rep = 1; the core is the best C of them: rho_core = mass(top C) / mass(top B)."""
+    rng = np.random.default_rng(33)
+    d, W, G, B, N = 16, 4, 1, 40, 300
+    K, V, Q, ro = rand_unit(rng, N, d, W, G)
+    p = f32_params(oracle, head_dim=d, window=W, q_per_kv=G, budget=B, recent=0, sim_threshold=2.0)
+    s = rng.permutation(N).astype(np.float32) + 1.0      # distinct
+    out = oracle.compress(p, ro, np.array([0]), K, V, Q, scores=s)
+    rho = oracle.mass_diagnostics(p, ro, s, out["role"], out["out_mass"], out["out_len"])
+    best = np.sort(s.astype(np.float64))[::-1]
+    C = oracle.plan(p, 0, N)["core"]
+    np.testing.assert_allclose(rho[0], [best[:C].sum() / best[:B].sum(), 1.0], rtol=2e-7)
