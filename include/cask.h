@@ -153,6 +153,21 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
                   int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
                   float* scores, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* Representative-set mass diagnostics (Section 2.6), optional, after cask_compress:
+ *   rho[2u]     = rho_core = mass(C) / mass(TopK)
+ *   rho[2u + 1] = rho_rep  = mass(R) / mass(TopK)
+ * for every unit, where mass is the sum of `scores`; TopK = the min(B, N_u) best rows in the
+ * order (score descending, index ascending), i.e. what plain top-k eviction to the same budget
+ * would keep; C = the rows protection keeps verbatim (PREFIX_KEEP, CORE, RECENT); mass(R) = the
+ * sum of out_mass over the unit's out_len output rows (a representative counts with its whole
+ * group, so rho_rep may exceed 1).  A unit whose TopK mass is zero reports 1 and 1.
+ * Reads scores [total_rows], role [total_rows] (as written by cask_prefix_evict and
+ * cask_partition for the same scores), out_mass [n_units, B], out_len [n_units]; writes
+ * rho [n_units, 2] float.  Needs no workspace. */
+int cask_mass_diagnostics(const cask_params* params, const cask_batch* batch, const float* scores,
+                          const uint8_t* role, const float* out_mass, const int32_t* out_len,
+                          float* rho, void* hip_stream);
+
 /* Measurement aid (not part of the method): per-stage timing of cask_compress with HIP
  * events recorded on the caller's stream between its kernels.  Stage order: 0 score sweep A
  * (row statistics), 1 score sweep B (column mass), 2 select (with the ordered walk over the

@@ -25,7 +25,7 @@ ST_ACTIVE, ST_IDENTITY, ST_PREFIX_BUDGET_EXHAUSTED, ST_MERGE_INACTIVE = 0, 1, 2,
  ROLE_DECODE_EVICT) = range(7)
 
 EXPORTS = ["cask_plan", "cask_workspace_bytes", "cask_score", "cask_prefix_evict",
-           "cask_partition", "cask_consolidate", "cask_compress", "cask_strerror",
+           "cask_partition", "cask_consolidate", "cask_compress", "cask_mass_diagnostics", "cask_strerror",
            "cask_timing_enable", "cask_timing_enable_stages", "cask_timing_read"]
 STAGES = ["score_rows", "score_cols", "select", "index_roles", "similarity", "gather", "emit"]
 
@@ -101,7 +101,8 @@ def load():
         lib.cask_timing_enable_stages.argtypes = [C.c_int, C.c_int]
         lib.cask_timing_read.argtypes = [vp, vp]
         for name in ("cask_plan", "cask_score", "cask_prefix_evict", "cask_partition",
-                     "cask_consolidate", "cask_compress", "cask_timing_enable", "cask_timing_read"):
+                     "cask_consolidate", "cask_compress", "cask_mass_diagnostics", "cask_timing_enable",
+                     "cask_timing_read"):
             getattr(lib, name).restype = C.c_int
         _lib = lib
     return _lib
@@ -239,6 +240,18 @@ def consolidate(b: Batch, scores: torch.Tensor, role: torch.Tensor) -> torch.Ten
     if rc:
         raise CaskError("cask_consolidate", rc)
     return assign
+
+
+def mass_diagnostics(b: Batch, scores: torch.Tensor, role: torch.Tensor, out_mass: torch.Tensor,
+                     out_len: torch.Tensor) -> torch.Tensor:
+    """[n_units, 2] float: (rho_core, rho_rep) of every unit (cask_mass_diagnostics)."""
+    rho = torch.zeros(b.n_units, 2, dtype=torch.float32, device=b.device)
+    cp, cb = b.params.c(), b.c()
+    rc = load().cask_mass_diagnostics(C.byref(cp), C.byref(cb), _dptr(scores), _dptr(role),
+                                      _dptr(out_mass), _dptr(out_len), _dptr(rho), _stream())
+    if rc:
+        raise CaskError("cask_mass_diagnostics", rc)
+    return rho
 
 
 class Outputs:

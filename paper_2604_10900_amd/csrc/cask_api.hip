@@ -276,6 +276,21 @@ int cask_consolidate(const cask_params* params, const cask_batch* batch, const f
   return dev_rc(e);
 }
 
+int cask_mass_diagnostics(const cask_params* params, const cask_batch* batch, const float* scores,
+                          const uint8_t* role, const float* out_mass, const int32_t* out_len,
+                          float* rho, void* hip_stream) {
+  KParams kp;
+  Batch b;
+  int rc = resolve_params(params, &kp, true);
+  if (rc) return rc;
+  rc = resolve_batch(kp, batch, &b, false, false);
+  if (rc) return rc;
+  if (b.n_units == 0) return CASK_OK;
+  if (!scores || !role || !out_mass || !out_len || !rho) return CASK_EINVAL;
+  return dev_rc(launch_mass_diag(kp, b, scores, role, out_mass, out_len, rho,
+                                 static_cast<hipStream_t>(hip_stream)));
+}
+
 int cask_compress(const cask_params* params, const cask_batch* batch, void* K_out, void* V_out,
                   int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
                   float* scores, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream) {

@@ -178,6 +178,9 @@ hipError_t launch_index_roles(const KParams& kp, const Batch& b, const uint8_t* 
                               int32_t* slot_of, int32_t* out_src, int32_t* out_len,
                               int32_t* seed_rows, int32_t* ord_of_slot, int32_t* n_seeds,
                               hipStream_t st);
+hipError_t launch_mass_diag(const KParams& kp, const Batch& b, const float* scores,
+                            const uint8_t* role, const float* out_mass, const int32_t* out_len,
+                            float* rho, hipStream_t st);
 hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* role,
                              const int32_t* seed_rows, const int32_t* n_seeds,
                              int32_t* assign_ord, hipStream_t st);

@@ -446,6 +446,71 @@ __global__ __launch_bounds__(kSelThreads) void index_roles_kernel(
   index_walk(kp, u, row0, N, role + row0, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds, wsum);
 }
 
+// Representative-set mass diagnostics (Section 2.6): per unit
+//   rho_core = mass(C) / mass(TopK),  rho_rep = mass(R) / mass(TopK)
+// with TopK the min(B, N) best rows by (score descending, index ascending), C the rows that
+// protection keeps verbatim (prefix survivors, decode core, recent tail) and mass(R) the sum of
+// the output rows' masses.  TopK's mass comes from one radix select (the rank-B key) and a sum
+// over the keys above it plus the ties that belong; sums are carried in double.
+__device__ inline double block_sum(double v, double* red) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();  // `red` may still be read from the previous call
+  if (lane == 0) red[wv] = v;
+  __syncthreads();
+  double t = 0.0;
+  for (int w = 0; w < kSelWaves; ++w) t += red[w];
+  return t;
+}
+
+__global__ __launch_bounds__(kSelThreads) void mass_diag_kernel(
+    KParams kp, const int64_t* __restrict__ row_off, const float* __restrict__ scores,
+    const uint8_t* __restrict__ role, const float* __restrict__ out_mass,
+    const int32_t* __restrict__ out_len, float* __restrict__ rho) {
+  __shared__ int hist[2 * 3 * 256 * kHistCopies];
+  __shared__ int bcast[3 * 4];
+  __shared__ double red[kSelWaves];
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int64_t row0 = row_off[u];
+  const int N = (int)(row_off[u + 1] - row0);
+  const float* s = scores + row0;
+  const uint8_t* ro = role + row0;
+  const int B = kp.B;
+  double top = 0.0, core = 0.0, rep = 0.0;
+  Kth kt;
+  kt.key = 0u; kt.take_eq = 0; kt.total_eq = 0;
+  if (N > B) {  // the key of rank B; with N <= B every row is in TopK
+    Query3 q;
+    q.lo[0] = 0; q.hi[0] = N; q.k[0] = B;
+    q.lo[1] = q.hi[1] = q.k[1] = 0;
+    q.lo[2] = q.hi[2] = q.k[2] = 0;
+    Kth kth[3];
+    uint32_t key[kSelPer];
+    radix_select3(s, q, 0, N, kth, key, hist, bcast);
+    kt = kth[0];
+  }
+  for (int i = tid; i < N; i += kSelThreads) {
+    const float v = s[i];
+    if (N <= B || score_key(v) > kt.key) top += (double)v;
+    const int r = ro[i];
+    if (r == CASK_ROLE_PREFIX_KEEP || r == CASK_ROLE_CORE || r == CASK_ROLE_RECENT) core += (double)v;
+  }
+  const int L = out_len[u];
+  for (int t = tid; t < L; t += kSelThreads) rep += (double)out_mass[(size_t)u * B + t];
+  top = block_sum(top, red);
+  core = block_sum(core, red);
+  rep = block_sum(rep, red);
+  if (tid == 0) {
+    if (N > B) {  // the ties at the rank-B key that belong to TopK
+      const uint32_t bits = (kt.key & 0x80000000u) ? (kt.key & 0x7FFFFFFFu) : ~kt.key;
+      top += (double)kt.take_eq * (double)__uint_as_float(bits);
+    }
+    rho[2 * u + 0] = top > 0.0 ? (float)(core / top) : 1.0f;
+    rho[2 * u + 1] = top > 0.0 ? (float)(rep / top) : 1.0f;
+  }
+}
+
 }  // namespace
 
 hipError_t launch_select(const KParams& kp, const Batch& b, const float* scores, uint8_t* role,
@@ -472,6 +537,14 @@ hipError_t launch_index_roles(const KParams& kp, const Batch& b, const uint8_t* 
                               hipStream_t st) {
   index_roles_kernel<<<dim3(b.n_units), dim3(kSelThreads), 0, st>>>(
       kp, b.row_off, role, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds);
+  return hipGetLastError();
+}
+
+hipError_t launch_mass_diag(const KParams& kp, const Batch& b, const float* scores,
+                            const uint8_t* role, const float* out_mass, const int32_t* out_len,
+                            float* rho, hipStream_t st) {
+  mass_diag_kernel<<<dim3(b.n_units), dim3(kSelThreads), 0, st>>>(kp, b.row_off, scores, role,
+                                                                    out_mass, out_len, rho);
   return hipGetLastError();
 }
 

@@ -185,6 +185,14 @@ def full_check(c: dict, p: cask.Params, expect_folds: bool = False, n_threads: i
     if expect_folds:
         assert stats["folded_rows"] > 0
 
+    # ---- mass diagnostics (Section 2.6) on the same injected scores and roles
+    rho = cask.binding.mass_diagnostics(b, s_inj, role, out.out_mass, out.out_len)
+    torch.cuda.synchronize()
+    if n_bad == 0:
+        want_rho = ref.mass_diagnostics(rp, row_off, want["scores"], want["role"], want["out_mass"], want["out_len"])
+        np.testing.assert_allclose(rho.cpu().numpy(), want_rho, rtol=2e-6, atol=0)
+        stats["rho_rep_min"] = float(want_rho[:, 1].min())
+
     # ---- end to end with the library's own scores
     out_e = cask.compress(b)
     torch.cuda.synchronize()

@@ -149,3 +149,17 @@ def test_timing_calls_validate_without_gpu(cask):
     n = C.c_int(-1)
     assert lib.cask_timing_read(ms, C.byref(n)) == cask.binding.OK and n.value == 0
     assert lib.cask_timing_read(None, C.byref(n)) == cask.binding.EINVAL
+
+
+def test_mass_diagnostics_validates_on_the_host(cask):
+    lib = cask.load()
+    ok = cask.Params().c()
+    ro = np.array([0, 1000], dtype=np.int64)
+    pl = np.array([100], dtype=np.int32)
+    fake = C.c_void_p(4096)
+    good = cask.binding._Batch(1, fake, fake, ro.ctypes.data, pl.ctypes.data, fake, fake, fake)
+    assert lib.cask_mass_diagnostics(C.byref(ok), C.byref(good), fake, fake, fake, fake, None, None) == cask.binding.EINVAL
+    assert lib.cask_mass_diagnostics(C.byref(ok), C.byref(good), None, fake, fake, fake, fake, None) == cask.binding.EINVAL
+    empty = cask.binding._Batch(0, None, None, None, None, None, None, None)
+    assert lib.cask_mass_diagnostics(C.byref(ok), C.byref(empty), None, None, None, None, None, None) == cask.binding.OK
+
