@@ -267,7 +267,7 @@ int cask_consolidate(const cask_params* params, const cask_batch* batch, const f
   int32_t* assign_ord = reinterpret_cast<int32_t*>(w + wl.assign_ord);
   hipError_t e = launch_index_roles(kp, b, role, nullptr, nullptr, nullptr, seed_rows, nullptr, n_seeds, st);
   if (e != hipSuccess) return CASK_EDEVICE;
-  e = launch_similarity(kp, b, role, seed_rows, n_seeds, assign_ord, st);
+  e = launch_similarity(kp, b, role, seed_rows, n_seeds, assign_ord, false, st);
   if (e != hipSuccess) return CASK_EDEVICE;
   e = launch_gather_merged(kp, b, role, assign_ord, nullptr, seed_rows,
                            reinterpret_cast<int32_t*>(w + wl.merged_row),
@@ -336,7 +336,7 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
   if (e != hipSuccess) return CASK_EDEVICE;
   rec.mark();
   rec.mark();  // the ordered walk runs inside the select kernel here: its own stage reads as zero
-  e = launch_similarity(kp, b, role, seed_rows, n_seeds, assign_ord, st);
+  e = launch_similarity(kp, b, role, seed_rows, n_seeds, assign_ord, true, st);
   if (e != hipSuccess) return CASK_EDEVICE;
   rec.mark();
   e = launch_gather_merged(kp, b, role, assign_ord, slot_of, seed_rows, merged_row, merged_ord,

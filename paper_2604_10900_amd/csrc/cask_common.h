@@ -181,9 +181,11 @@ hipError_t launch_index_roles(const KParams& kp, const Batch& b, const uint8_t* 
 hipError_t launch_mass_diag(const KParams& kp, const Batch& b, const float* scores,
                             const uint8_t* role, const float* out_mass, const int32_t* out_len,
                             float* rho, hipStream_t st);
+// roles_follow_plan: the roles were written by launch_select for these parameters, so the
+// seeds per unit are bounded by the plan (lets the kernel keep all of them in LDS)
 hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* role,
                              const int32_t* seed_rows, const int32_t* n_seeds,
-                             int32_t* assign_ord, hipStream_t st);
+                             int32_t* assign_ord, bool roles_follow_plan, hipStream_t st);
 hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t* role,
                                 const int32_t* assign_ord, const int32_t* slot_of,
                                 const int32_t* seed_rows, int32_t* merged_row, int32_t* merged_ord,

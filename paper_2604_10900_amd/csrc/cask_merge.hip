@@ -538,7 +538,7 @@ hipError_t launch_similarity_fma(const KParams& kp, const Batch& b, const uint8_
 
 hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* role,
                              const int32_t* seed_rows, const int32_t* n_seeds,
-                             int32_t* assign_ord, hipStream_t st) {
+                             int32_t* assign_ord, bool roles_follow_plan, hipStream_t st) {
   if (kp.dtype == CASK_BF16 && kp.d == 128) {
     // a few workgroups per unit, about two per compute unit in all, each walking its share of
     // the unit's donor tiles
@@ -556,7 +556,8 @@ hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* r
     // seeds of a unit = slots - core with slots <= B: at most B - core for an explicit core
     // size, at most ceil(B / 5) for the default four-fifths core share
     const int seed_bound = kp.core >= 0 ? (kp.B - kp.core > 0 ? kp.B - kp.core : 0) : (kp.B + 4) / 5;
-    if (seed_bound <= kSeedBlock)
+    // (a caller-supplied role array may name any number of seeds: general kernel then)
+    if (roles_follow_plan && seed_bound <= kSeedBlock)
       similarity_mfma_kernel<true><<<dim3(units8 * chunks), dim3(256), 0, st>>>(
           kp, b.n_units, chunks, tiles_per_wg, b.row_off, b.prefix_len,
           static_cast<const uint16_t*>(b.K), role, seed_rows, n_seeds, assign_ord);

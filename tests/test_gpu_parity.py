@@ -147,6 +147,33 @@ def test_many_seeds_take_several_lds_blocks():
     _note(st)
 
 
+def test_consolidate_with_caller_roles_naming_many_seeds():
+    """cask_consolidate takes any role array: here far more seeds than the plan would ever
+    produce, so the seeds of a unit do not fit one LDS block."""
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=2, prefix=50, decode=1800, budget=384)
+    c = caches.make(w, seed=17)
+    p = parity.params_of(w, sim_threshold=0.2)
+    rp = parity.ref_params(p)
+    row_off, prefix_len, K, V, Q = parity.host_arrays(c)
+    rng = np.random.default_rng(3)
+    total = int(row_off[-1])
+    role = np.full(total, ref.DONOR, dtype=np.uint8)
+    for u in range(2):
+        lo, hi = int(row_off[u]), int(row_off[u + 1])
+        role[lo:lo + 50] = ref.PREFIX_KEEP
+        role[hi - 128:hi] = ref.RECENT
+        seeds = lo + 50 + rng.choice(hi - 128 - lo - 50, size=300, replace=False)
+        role[seeds] = ref.SEED
+    s = rng.random(total).astype(np.float32)
+    want, best, second = ref.consolidate(rp, row_off, prefix_len, K, s, role, want_sims=True)
+    b = parity.to_device(c, p)
+    got = cask.consolidate(b, torch.from_numpy(s).to(b.device), torch.from_numpy(role).to(b.device))
+    torch.cuda.synchronize()
+    n = parity.check_assign_excused(got.cpu().numpy(), want, best, second, float(np.float32(0.2)), "caller roles")
+    assert (want >= 0).sum() > 1000
+    _note(("excused", n))
+
+
 def test_stage_timing_api():
     w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=2, decode=1200)
     c = caches.make(w)
