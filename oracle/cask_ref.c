@@ -403,15 +403,19 @@ int cask_ref_consolidate(const cask_ref_params* p, int32_t n_units, const int64_
  *
  * m-folding (Section 2.4): for a group G (a seed and the donors assigned to it)
  *   m = sum a_i,  k~ = sum a_i k_i / m,  v~ = sum a_i v_i / m,
- * with a_i the token's score (its local score mass).  If every a_i is zero the weights
- * become uniform.  A group of one is the token itself, copied without arithmetic.  The
+ * with a_i the token's score (its local score mass).  A cache row may itself stand for
+ * several original tokens (a representative of an earlier event): `count` says how many, 1
+ * when no counts are given, and folding adds the counts.  If every a_i is zero the weights
+ * become the counts (the uniform mean over the original tokens).  A group of one is the
+ * token itself, copied without arithmetic.  The
  * output keeps ascending source order (a representative sits at its seed's index); kept
  * tokens pass through bit-identically (C subset of R, |R| <= B; Section 2.3).
  */
 static void emit_unit(const cask_ref_params* p, int32_t N, const void* K, const void* V,
                       int64_t row0, const float* s, const uint8_t* role, const int32_t* assign_src,
                       void* K_out, void* V_out, int64_t out_row0, int32_t* out_len,
-                      int32_t* out_src, float* out_mass, int32_t* slot_of, int32_t* n_merged) {
+                      int32_t* out_src, float* out_mass, int32_t* slot_of, int32_t* n_merged,
+                      const int32_t* count, int32_t* out_count) {
   const int d = p->head_dim;
   const size_t es = elem_size(p->dtype);
   double* ksum = (double*)malloc(sizeof(double) * d);
@@ -431,6 +435,7 @@ static void emit_unit(const cask_ref_params* p, int32_t N, const void* K, const 
     char* ko = (char*)K_out + (size_t)(out_row0 + t) * d * es;
     char* vo = (char*)V_out + (size_t)(out_row0 + t) * d * es;
     double mass;
+    int64_t cnt = count ? count[j] : 1;
     if (members == 1) {
       memcpy(ko, (const char*)K + (size_t)(row0 + j) * d * es, d * es);
       memcpy(vo, (const char*)V + (size_t)(row0 + j) * d * es, d * es);
@@ -438,13 +443,16 @@ static void emit_unit(const cask_ref_params* p, int32_t N, const void* K, const 
     } else {
       double m = (double)s[j];
       for (int32_t i = 0; i < N; ++i)
-        if (role[i] == CASK_REF_DONOR && assign_src[i] == j) m += (double)s[i];
+        if (role[i] == CASK_REF_DONOR && assign_src[i] == j) {
+          m += (double)s[i];
+          cnt += count ? count[i] : 1;
+        }
       int uniform = (m == 0.0);
-      double denom = uniform ? (double)members : m;
+      double denom = uniform ? (double)cnt : m;
       for (int c = 0; c < d; ++c) ksum[c] = vsum[c] = 0.0;
       for (int32_t i = 0; i < N; ++i) {
         if (!(i == j || (role[i] == CASK_REF_DONOR && assign_src[i] == j))) continue;
-        double a = uniform ? 1.0 : (double)s[i];
+        double a = uniform ? (double)(count ? count[i] : 1) : (double)s[i];
         for (int c = 0; c < d; ++c) {
           ksum[c] += a * load_elem(K, p->dtype, (row0 + i) * d + c);
           vsum[c] += a * load_elem(V, p->dtype, (row0 + i) * d + c);
@@ -459,6 +467,7 @@ static void emit_unit(const cask_ref_params* p, int32_t N, const void* K, const 
     }
     out_src[t] = j;
     if (out_mass) out_mass[t] = (float)mass;
+    if (out_count) out_count[t] = (int32_t)cnt;
     slot[j] = t;
     ++t;
   }
@@ -477,12 +486,16 @@ static void emit_unit(const cask_ref_params* p, int32_t N, const void* K, const 
   free(slot);
 }
 
-int cask_ref_compress(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
-                      const int32_t* prefix_len, const void* K, const void* V, const void* Q,
-                      int scores_given, float* scores, void* K_out, void* V_out,
-                      int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
-                      uint8_t* role_out, int32_t* status, int n_threads) {
-  if (check_params(p) || n_units < 0 || !scores) return -1;
+int cask_ref_compress_step(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                           const int32_t* prefix_len, const void* K, const void* V, const void* Q,
+                           int scores_given, float* scores, const int32_t* in_count, void* K_out,
+                           void* V_out, int32_t out_stride_rows, int32_t* out_len,
+                           int32_t* out_src, float* out_mass, int32_t* out_count,
+                           int32_t* assign, uint8_t* role_out, int32_t* status, int n_threads) {
+  if (check_params(p) || n_units < 0 || !scores || out_stride_rows < p->budget) return -1;
+  if (in_count)
+    for (int64_t i = 0; i < row_off[n_units]; ++i)
+      if (in_count[i] < 1) return -1;
   for (int32_t u = 0; u < n_units; ++u)
     if (check_unit(p, row_off[u + 1] - row_off[u], prefix_len[u])) return -1;
 #ifdef _OPENMP
@@ -506,9 +519,10 @@ int cask_ref_compress(const cask_ref_params* p, int32_t n_units, const int64_t* 
     partition_unit(&pl, P, N, s, role);
     consolidate_unit(p, N, K, row0, role, asrc, NULL, NULL);
     int32_t merged = 0;
-    emit_unit(p, N, K, V, row0, s, role, asrc, K_out, V_out, (int64_t)u * B, &out_len[u],
-              out_src + (int64_t)u * B, out_mass ? out_mass + (int64_t)u * B : NULL,
-              assign ? assign + row0 : NULL, &merged);
+    emit_unit(p, N, K, V, row0, s, role, asrc, K_out, V_out, (int64_t)u * out_stride_rows,
+              &out_len[u], out_src + (int64_t)u * B, out_mass ? out_mass + (int64_t)u * B : NULL,
+              assign ? assign + row0 : NULL, &merged, in_count ? in_count + row0 : NULL,
+              out_count ? out_count + (int64_t)u * B : NULL);
     int32_t st = pl.status;
     if (merged == 0 && !(st & (CASK_REF_ST_IDENTITY | CASK_REF_ST_PREFIX_BUDGET_EXHAUSTED)))
       st |= CASK_REF_ST_MERGE_INACTIVE;
@@ -518,6 +532,16 @@ int cask_ref_compress(const cask_ref_params* p, int32_t n_units, const int64_t* 
     free(asrc);
   }
   return 0;
+}
+
+int cask_ref_compress(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                      const int32_t* prefix_len, const void* K, const void* V, const void* Q,
+                      int scores_given, float* scores, void* K_out, void* V_out,
+                      int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
+                      uint8_t* role_out, int32_t* status, int n_threads) {
+  return cask_ref_compress_step(p, n_units, row_off, prefix_len, K, V, Q, scores_given, scores, NULL,
+                                K_out, V_out, p ? p->budget : 0, out_len, out_src, out_mass, NULL,
+                                assign, role_out, status, n_threads);
 }
 
 /* Representative-set mass diagnostics (Section 2.6):

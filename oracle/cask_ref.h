@@ -118,6 +118,26 @@ int cask_ref_compress(const cask_ref_params* p, int32_t n_units, const int64_t* 
                       int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
                       uint8_t* role, int32_t* status, int n_threads);
 
+/* One event of a decode loop (the paper's runs compress a trace several times, Tables 3 and
+ * the bridge table count the events; it states no trigger or carry rule, so these are readings):
+ *   - a unit is compressed when it holds B + delta rows (delta = the number of tokens decoded
+ *     between events; the caller decides when to call);
+ *   - every cache row stands for in_count[row] >= 1 original tokens (NULL: all 1); a fold adds
+ *     the counts of its members into out_count, and a group whose score mass is zero is
+ *     averaged with the counts as weights.  Scores are always fresh: the mass a representative
+ *     receives from the current window already is the mass of what it stands for;
+ *   - the output of unit u starts at row u * out_stride_rows of K_out / V_out
+ *     (out_stride_rows >= B), so that a caller can keep appending decoded tokens behind it;
+ *     out_src, out_mass, out_count stay [n_units, B];
+ *   - the prefix of the next event is the surviving prefix: p_keep of this event's plan.
+ * With in_count == NULL and out_stride_rows == B this is cask_ref_compress. */
+int cask_ref_compress_step(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                           const int32_t* prefix_len, const void* K, const void* V, const void* Q,
+                           int scores_given, float* scores, const int32_t* in_count, void* K_out,
+                           void* V_out, int32_t out_stride_rows, int32_t* out_len,
+                           int32_t* out_src, float* out_mass, int32_t* out_count,
+                           int32_t* assign, uint8_t* role_out, int32_t* status, int n_threads);
+
 /* Representative-set mass diagnostics of Section 2.6 (see the definition in the source for the
  * readings of TopK, C and R).  role, out_mass, out_len as produced by cask_ref_compress.
  * rho: [n_units][2] = {rho_core, rho_rep}. */

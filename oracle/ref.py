@@ -218,6 +218,46 @@ def compress(p: Params, row_off, prefix_len, K, V, Q, scores=None, n_threads: in
                 assign=assign, role=role, status=status, scores=scores)
 
 
+def compress_step(p: Params, row_off, prefix_len, K, V, Q, in_count=None, out_stride_rows: int = 0,
+                  scores=None, n_threads: int = 0) -> dict:
+    """One event of a decode loop: compress() with per-row token counts carried in and out and
+    an output row stride (rows [u * stride, u * stride + out_len[u]) of K_out / V_out)."""
+    row_off, prefix_len, n_units = _units(row_off, prefix_len)
+    _check_data(p, K, V, Q)
+    total = int(row_off[-1])
+    d, B = p.head_dim, p.budget
+    stride = out_stride_rows if out_stride_rows > 0 else B
+    given = scores is not None
+    if given:
+        scores = np.ascontiguousarray(scores, dtype=np.float32).copy()
+        assert scores.size == total
+    else:
+        scores = np.zeros(total, dtype=np.float32)
+    if in_count is not None:
+        in_count = np.ascontiguousarray(in_count, dtype=np.int32)
+        assert in_count.size == total
+    K_out = np.zeros((n_units, stride, d), dtype=_np_elem(p.dtype))
+    V_out = np.zeros((n_units, stride, d), dtype=_np_elem(p.dtype))
+    out_len = np.zeros(n_units, dtype=np.int32)
+    out_src = np.full((n_units, B), -1, dtype=np.int32)
+    out_mass = np.zeros((n_units, B), dtype=np.float32)
+    out_count = np.zeros((n_units, B), dtype=np.int32)
+    assign = np.full(total, -2, dtype=np.int32)
+    role = np.full(total, 255, dtype=np.uint8)
+    status = np.zeros(n_units, dtype=np.int32)
+    cp = p.c()
+    rc = lib().cask_ref_compress_step(C.byref(cp), C.c_int32(n_units), _ptr(row_off), _ptr(prefix_len),
+                                      _ptr(K), _ptr(V), _ptr(Q), C.c_int(1 if given else 0),
+                                      _ptr(scores), _ptr(in_count) if in_count is not None else None,
+                                      _ptr(K_out), _ptr(V_out), C.c_int32(stride), _ptr(out_len),
+                                      _ptr(out_src), _ptr(out_mass), _ptr(out_count), _ptr(assign),
+                                      _ptr(role), _ptr(status), C.c_int(n_threads))
+    if rc:
+        raise ValueError(f"cask_ref_compress_step: {rc}")
+    return dict(K_out=K_out, V_out=V_out, out_len=out_len, out_src=out_src, out_mass=out_mass,
+                out_count=out_count, assign=assign, role=role, status=status, scores=scores)
+
+
 def mass_diagnostics(p: Params, row_off, scores, role, out_mass, out_len) -> np.ndarray:
     """(rho_core, rho_rep) per unit, Section 2.6; inputs as returned by compress()."""
     row_off = np.ascontiguousarray(row_off, dtype=np.int64)

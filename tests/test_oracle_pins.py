@@ -678,3 +678,71 @@ def test_mass_diagnostics_pure_eviction_of_the_best_rows(oracle):
     best = np.sort(s.astype(np.float64))[::-1]
     C = oracle.plan(p, 0, N)["core"]
     np.testing.assert_allclose(rho[0], [best[:C].sum() / best[:B].sum(), 1.0], rtol=2e-7)
+
+
+# ------------------------------------------------------------------ decode-loop step (counts, stride)
+
+def test_step_with_unit_counts_is_the_plain_event(oracle):
+    rng = np.random.default_rng(41)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, tau=0.3)
+    a = oracle.compress(p, ro, pl, K, V, Q)
+    N = K.shape[0]
+    b = oracle.compress_step(p, ro, pl, K, V, Q, in_count=np.ones(N, dtype=np.int32), out_stride_rows=p.budget + 17)
+    L = int(a["out_len"][0])
+    for k in ("out_len", "out_src", "out_mass", "assign", "role", "status", "scores"):
+        np.testing.assert_array_equal(a[k], b[k])
+    np.testing.assert_array_equal(a["K_out"][0, :L], b["K_out"][0, :L])
+    np.testing.assert_array_equal(a["V_out"][0, :L], b["V_out"][0, :L])
+    assert b["K_out"].shape[1] == p.budget + 17 and not b["K_out"][0, p.budget:].any()
+    # counts of an output row = members of its group
+    members = np.bincount(a["assign"][a["assign"] >= 0], minlength=L)
+    np.testing.assert_array_equal(b["out_count"][0, :L], members[:L])
+
+
+def test_step_conserves_token_counts_and_places_units_by_stride(oracle):
+    rng = np.random.default_rng(42)
+    d, W, G, B = 16, 6, 2, 40
+    lens, Ps = [90, 120, 41], [10, 30, 0]
+    K = rng.standard_normal((sum(lens), d)).astype(np.float32)
+    K[20:60] = K[20] + 0.01 * rng.standard_normal((40, d)).astype(np.float32)     # mergeable rows
+    K[100:180] = K[100] + 0.01 * rng.standard_normal((80, d)).astype(np.float32)
+    V = rng.standard_normal((sum(lens), d)).astype(np.float32)
+    Q = rng.standard_normal((3, W, G, d)).astype(np.float32)
+    ro = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    cnt = rng.integers(1, 9, sum(lens)).astype(np.int32)
+    p = f32_params(oracle, head_dim=d, window=W, q_per_kv=G, budget=B, sim_threshold=0.5)
+    out = oracle.compress_step(p, ro, np.array(Ps), K, V, Q, in_count=cnt, out_stride_rows=B + W)
+    assert (out["assign"] >= 0).sum() > sum(out["out_len"])          # something was folded
+    for u in range(3):
+        sl = slice(ro[u], ro[u + 1])
+        L = int(out["out_len"][u])
+        kept = out["assign"][sl] >= 0
+        assert out["out_count"][u, :L].sum() == cnt[sl][kept].sum()
+        want = np.bincount(out["assign"][sl][kept], weights=cnt[sl][kept], minlength=L)
+        np.testing.assert_array_equal(out["out_count"][u, :L], want[:L].astype(np.int32))
+        one = oracle.compress_step(p, np.array([0, lens[u]]), np.array([Ps[u]]), K[sl], V[sl], Q[u:u + 1],
+                                   in_count=cnt[sl])
+        np.testing.assert_array_equal(out["K_out"][u, :L], one["K_out"][0, :L])   # stride only moves rows
+        assert not out["K_out"][u, L:].any()
+    with pytest.raises(ValueError):
+        oracle.compress_step(p, ro, np.array(Ps), K, V, Q, in_count=np.zeros(sum(lens), dtype=np.int32))
+    with pytest.raises(ValueError):
+        oracle.compress_step(p, ro, np.array(Ps), K, V, Q, out_stride_rows=B - 1)
+
+
+def test_step_zero_mass_group_is_the_count_weighted_mean(oracle):
+    """Same hand-built unit as the uniform-weights pin, now with counts 1, 3, 4 on the three
+    parallel rows: k~ = (1 k0 + 3 k1 + 4 k2) / 8 exactly."""
+    d = 4
+    K = np.array([[1, 0, 0, 0], [2, 0, 0, 0], [4, 0, 0, 0], [0, 1, 0, 0], [0, 0, 1, 0]], dtype=np.float32)
+    V = np.arange(20, dtype=np.float32).reshape(5, d)
+    s = np.array([0, 0, 0, 0.5, 0.25], dtype=np.float32)
+    cnt = np.array([1, 3, 4, 2, 5], dtype=np.int32)
+    p = oracle.Params(dtype=oracle.F32, head_dim=d, q_per_kv=1, window=1, recent=1, budget=3,
+                      core=1, prefix_budget=0, sim_threshold=0.99)
+    out = oracle.compress_step(p, np.array([0, 5]), np.array([0]), K, V, None, in_count=cnt, scores=s)
+    np.testing.assert_array_equal(out["assign"], [0, 0, 0, 1, 2])
+    np.testing.assert_array_equal(out["K_out"][0, 0], (1 * K[0] + 3 * K[1] + 4 * K[2]) / 8)
+    np.testing.assert_array_equal(out["V_out"][0, 0], (1 * V[0] + 3 * V[1] + 4 * V[2]) / 8)
+    np.testing.assert_array_equal(out["out_count"][0], [8, 2, 5])
+    assert out["out_mass"][0, 0] == 0.0
