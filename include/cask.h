@@ -153,6 +153,28 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
                   int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
                   float* scores, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* One event of a decode loop: cask_compress with per-row token counts carried in and out and
+ * an output row stride.  The paper's runs compress a trace several times (its result tables
+ * count the events) without stating a trigger or carry rule; the readings taken:
+ *   - the caller fires the event when a unit holds B + delta rows (delta tokens decoded since
+ *     the last event); the next event's prefix length is this event's p_keep (cask_plan);
+ *   - in_count [total_rows] or NULL: original tokens each cache row stands for (>= 1; NULL = 1
+ *     each).  out_count [n_units, B] or NULL: sum over each output row's group.  A group whose
+ *     score mass is zero is averaged with the counts as weights; otherwise the fold weights are
+ *     the fresh scores, exactly as in cask_compress;
+ *   - K_out, V_out are [n_units, out_stride_rows, d] with out_stride_rows >= B: unit u's output
+ *     starts at row u * out_stride_rows, so decoded tokens can be appended behind it and the
+ *     buffer handed back as the next event's K, V (units of equal length then lie back to
+ *     back).  out_src, out_mass, out_count stay [n_units, B].
+ * Everything else as cask_compress, which is this call with in_count = out_count = NULL and
+ * out_stride_rows = B.  in_count is not validated on the device: a count < 1 gives a
+ * meaningless out_count, nothing worse. */
+int cask_compress_step(const cask_params* params, const cask_batch* batch, const int32_t* in_count,
+                       void* K_out, void* V_out, int32_t out_stride_rows, int32_t* out_len,
+                       int32_t* out_src, float* out_mass, int32_t* out_count, int32_t* assign,
+                       float* scores, int32_t* status, void* ws, size_t ws_bytes,
+                       void* hip_stream);
+
 /* Representative-set mass diagnostics (Section 2.6), optional, after cask_compress:
  *   rho[2u]     = rho_core = mass(C) / mass(TopK)
  *   rho[2u + 1] = rho_rep  = mass(R) / mass(TopK)

@@ -25,7 +25,8 @@ ST_ACTIVE, ST_IDENTITY, ST_PREFIX_BUDGET_EXHAUSTED, ST_MERGE_INACTIVE = 0, 1, 2,
  ROLE_DECODE_EVICT) = range(7)
 
 EXPORTS = ["cask_plan", "cask_workspace_bytes", "cask_score", "cask_prefix_evict",
-           "cask_partition", "cask_consolidate", "cask_compress", "cask_mass_diagnostics", "cask_strerror",
+           "cask_partition", "cask_consolidate", "cask_compress", "cask_compress_step",
+           "cask_mass_diagnostics", "cask_strerror",
            "cask_timing_enable", "cask_timing_enable_stages", "cask_timing_read"]
 STAGES = ["score_rows", "score_cols", "select", "index_roles", "similarity", "gather", "emit"]
 
@@ -101,7 +102,8 @@ def load():
         lib.cask_timing_enable_stages.argtypes = [C.c_int, C.c_int]
         lib.cask_timing_read.argtypes = [vp, vp]
         for name in ("cask_plan", "cask_score", "cask_prefix_evict", "cask_partition",
-                     "cask_consolidate", "cask_compress", "cask_mass_diagnostics", "cask_timing_enable",
+                     "cask_consolidate", "cask_compress", "cask_compress_step", "cask_mass_diagnostics",
+                     "cask_timing_enable",
                      "cask_timing_read"):
             getattr(lib, name).restype = C.c_int
         _lib = lib
@@ -240,6 +242,25 @@ def consolidate(b: Batch, scores: torch.Tensor, role: torch.Tensor) -> torch.Ten
     if rc:
         raise CaskError("cask_consolidate", rc)
     return assign
+
+
+def compress_step(b: Batch, K_out: torch.Tensor, V_out: torch.Tensor, out: "Outputs",
+                  in_count: Optional[torch.Tensor] = None, out_count: Optional[torch.Tensor] = None,
+                  scores: Optional[torch.Tensor] = None) -> "Outputs":
+    """One event of a decode loop (cask_compress_step).  K_out, V_out: [n_units, stride, d] with
+    stride >= budget; out supplies out_len, out_src, out_mass, assign, scores, status."""
+    assert K_out.shape == V_out.shape and K_out.dim() == 3 and K_out.shape[0] == b.n_units
+    given = scores is not None
+    if given:
+        out.scores = scores
+    cp, cb, ws = b.params.c(1 if given else 0), b.c(), b.workspace()
+    rc = load().cask_compress_step(C.byref(cp), C.byref(cb), _dptr(in_count), _dptr(K_out), _dptr(V_out),
+                                   C.c_int32(K_out.shape[1]), _dptr(out.out_len), _dptr(out.out_src),
+                                   _dptr(out.out_mass), _dptr(out_count), _dptr(out.assign),
+                                   _dptr(out.scores), _dptr(out.status), _dptr(ws), ws.numel(), _stream())
+    if rc:
+        raise CaskError("cask_compress_step", rc)
+    return out
 
 
 def mass_diagnostics(b: Batch, scores: torch.Tensor, role: torch.Tensor, out_mass: torch.Tensor,

@@ -294,6 +294,16 @@ int cask_mass_diagnostics(const cask_params* params, const cask_batch* batch, co
 int cask_compress(const cask_params* params, const cask_batch* batch, void* K_out, void* V_out,
                   int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
                   float* scores, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream) {
+  return cask_compress_step(params, batch, nullptr, K_out, V_out, params ? params->budget : 0,
+                            out_len, out_src, out_mass, nullptr, assign, scores, status, ws, ws_bytes,
+                            hip_stream);
+}
+
+int cask_compress_step(const cask_params* params, const cask_batch* batch, const int32_t* in_count,
+                       void* K_out, void* V_out, int32_t out_stride_rows, int32_t* out_len,
+                       int32_t* out_src, float* out_mass, int32_t* out_count, int32_t* assign,
+                       float* scores, int32_t* status, void* ws, size_t ws_bytes,
+                       void* hip_stream) {
   KParams kp;
   Batch b;
   int rc = resolve_params(params, &kp, true);
@@ -306,6 +316,7 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
   if (((reinterpret_cast<uintptr_t>(K_out) | reinterpret_cast<uintptr_t>(V_out) | reinterpret_cast<uintptr_t>(ws)) & 15u) != 0)
     return CASK_EINVAL;
   if (given && !scores) return CASK_EINVAL;
+  if (out_stride_rows < kp.B) return CASK_EINVAL;
   const Workspace wl = layout_workspace(kp, b.n_units, b.total_rows, b.max_unit_len);
   if (ws_bytes < wl.total) return CASK_ENOMEM;
   char* w = static_cast<char*>(ws);
@@ -344,7 +355,7 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
   if (e != hipSuccess) return CASK_EDEVICE;
   rec.mark();
   e = launch_emit(kp, b, s, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out,
-                  V_out, out_mass, st);
+                  V_out, out_mass, in_count, out_count, out_stride_rows, st);
   rec.mark();
   return dev_rc(e);
 }

@@ -195,6 +195,7 @@ hipError_t launch_emit(const KParams& kp, const Batch& b, const float* scores,
                        const int32_t* out_src, const int32_t* out_len, const int32_t* ord_of_slot,
                        const int32_t* merged_row, const int32_t* merged_ord,
                        const int32_t* n_merged, void* K_out, void* V_out, float* out_mass,
+                       const int32_t* in_count, int32_t* out_count, int out_stride,
                        hipStream_t st);
 
 }  // namespace cask

@@ -397,7 +397,8 @@ __global__ __launch_bounds__(256) void emit_kernel(
     const int32_t* __restrict__ out_len, const int32_t* __restrict__ ord_of_slot,
     const int32_t* __restrict__ merged_row, const int32_t* __restrict__ merged_ord,
     const int32_t* __restrict__ n_merged, T* __restrict__ K_out, T* __restrict__ V_out,
-    float* __restrict__ out_mass) {
+    float* __restrict__ out_mass, const int32_t* __restrict__ in_count,
+    int32_t* __restrict__ out_count, int out_stride) {
   constexpr int EPL = D / 16;                    // elements per lane
   constexpr int WORDS = EPL * sizeof(T) / 4;     // 32-bit words per lane
   constexpr int kSlotsPerWave = 16;
@@ -416,7 +417,7 @@ __global__ __launch_bounds__(256) void emit_kernel(
   const int32_t* mr = merged_row + row0;
   const int32_t* mo = merged_ord + row0;
 
-  int slot[4], src[4], ord[4];
+  int slot[4], src[4], ord[4], c0[4];  // c0: original tokens the row stands for (1 unless counts are given)
   float a0[4];
   Raw kraw[4], vraw[4];
 #pragma unroll
@@ -432,15 +433,17 @@ __global__ __launch_bounds__(256) void emit_kernel(
       kraw[j] = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + src[j]) * D + gl * EPL);
       vraw[j] = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + src[j]) * D + gl * EPL);
       a0[j] = scores[row0 + src[j]];
+      c0[j] = in_count ? in_count[row0 + src[j]] : 1;
     } else {
       a0[j] = 0.f;
+      c0[j] = 0;
     }
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    int members = 1;
+    int members = 1, count = c0[j];
     float mass = a0[j];
-    float ka[EPL], va[EPL], ku[EPL], vu[EPL];  // weighted and unweighted sums
+    float ka[EPL], va[EPL], ku[EPL], vu[EPL];  // score-weighted and count-weighted sums
     const T* kself = reinterpret_cast<const T*>(&kraw[j]);
     const T* vself = reinterpret_cast<const T*>(&vraw[j]);
     if (nm > 0 && __any(ord[j] >= 0)) {
@@ -460,10 +463,12 @@ __global__ __launch_bounds__(256) void emit_kernel(
 #pragma unroll
               for (int e = 0; e < EPL; ++e) {
                 const float kf = Elem<T>::load(kself + e), vf = Elem<T>::load(vself + e);
-                ka[e] = a0[j] * kf; va[e] = a0[j] * vf; ku[e] = kf; vu[e] = vf;
+                ka[e] = a0[j] * kf; va[e] = a0[j] * vf; ku[e] = (float)c0[j] * kf; vu[e] = (float)c0[j] * vf;
               }
             }
             const float a = scores[row0 + drow];
+            const int dc = in_count ? in_count[row0 + drow] : 1;
+            const float dcf = (float)dc;
             const Raw dk = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + drow) * D + gl * EPL);
             const Raw dv = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + drow) * D + gl * EPL);
             const T* dkp = reinterpret_cast<const T*>(&dk);
@@ -473,24 +478,25 @@ __global__ __launch_bounds__(256) void emit_kernel(
               const float kf = Elem<T>::load(dkp + e), vf = Elem<T>::load(dvp + e);
               ka[e] = __builtin_fmaf(a, kf, ka[e]);
               va[e] = __builtin_fmaf(a, vf, va[e]);
-              ku[e] += kf;
-              vu[e] += vf;
+              ku[e] = __builtin_fmaf(dcf, kf, ku[e]);
+              vu[e] = __builtin_fmaf(dcf, vf, vu[e]);
             }
             mass += a;
+            count += dc;
             ++members;
           }
         }
       }
     }
     if (src[j] < 0) continue;
-    T* ko = K_out + ((size_t)u * B + slot[j]) * D + gl * EPL;
-    T* vo = V_out + ((size_t)u * B + slot[j]) * D + gl * EPL;
+    T* ko = K_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL;
+    T* vo = V_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL;
     if (members == 1) {
       *reinterpret_cast<Raw*>(ko) = kraw[j];
       *reinterpret_cast<Raw*>(vo) = vraw[j];
     } else {
-      const bool uniform = mass == 0.f;
-      const float denom = uniform ? (float)members : mass;
+      const bool uniform = mass == 0.f;  // no score mass: average over the original tokens
+      const float denom = uniform ? (float)count : mass;
       Raw ok_, ov_;
       T* okp = reinterpret_cast<T*>(&ok_);
       T* ovp = reinterpret_cast<T*>(&ov_);
@@ -503,6 +509,7 @@ __global__ __launch_bounds__(256) void emit_kernel(
       *reinterpret_cast<Raw*>(vo) = ov_;
     }
     if (out_mass && gl == 0) out_mass[(size_t)u * B + slot[j]] = mass;
+    if (out_count && gl == 0) out_count[(size_t)u * B + slot[j]] = count;
   }
 }
 
@@ -511,14 +518,15 @@ hipError_t launch_emit_t(const KParams& kp, const Batch& b, const float* scores,
                          const int32_t* out_src, const int32_t* out_len,
                          const int32_t* ord_of_slot, const int32_t* merged_row,
                          const int32_t* merged_ord, const int32_t* n_merged, void* K_out,
-                         void* V_out, float* out_mass, hipStream_t st) {
+                         void* V_out, float* out_mass, const int32_t* in_count,
+                         int32_t* out_count, int out_stride, hipStream_t st) {
   const long long waves = (long long)b.n_units * ((kp.B + 15) / 16);
   const long long blocks = (waves + 3) / 4;
   if (blocks == 0) return hipSuccess;
   emit_kernel<T, D><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(
       kp, b.n_units, b.row_off, static_cast<const T*>(b.K), static_cast<const T*>(b.V), scores,
       out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, static_cast<T*>(K_out),
-      static_cast<T*>(V_out), out_mass);
+      static_cast<T*>(V_out), out_mass, in_count, out_count, out_stride);
   return hipGetLastError();
 }
 
@@ -588,12 +596,14 @@ hipError_t launch_emit(const KParams& kp, const Batch& b, const float* scores,
                        const int32_t* out_src, const int32_t* out_len, const int32_t* ord_of_slot,
                        const int32_t* merged_row, const int32_t* merged_ord,
                        const int32_t* n_merged, void* K_out, void* V_out, float* out_mass,
+                       const int32_t* in_count, int32_t* out_count, int out_stride,
                        hipStream_t st) {
-  if (kp.dtype == CASK_F32)
-    return kp.d == 64 ? launch_emit_t<float, 64>(kp, b, scores, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out, V_out, out_mass, st)
-                      : launch_emit_t<float, 128>(kp, b, scores, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out, V_out, out_mass, st);
-  return kp.d == 64 ? launch_emit_t<uint16_t, 64>(kp, b, scores, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out, V_out, out_mass, st)
-                    : launch_emit_t<uint16_t, 128>(kp, b, scores, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out, V_out, out_mass, st);
+#define CASK_EMIT(T, D)                                                                          \
+  launch_emit_t<T, D>(kp, b, scores, out_src, out_len, ord_of_slot, merged_row, merged_ord,      \
+                      n_merged, K_out, V_out, out_mass, in_count, out_count, out_stride, st)
+  if (kp.dtype == CASK_F32) return kp.d == 64 ? CASK_EMIT(float, 64) : CASK_EMIT(float, 128);
+  return kp.d == 64 ? CASK_EMIT(uint16_t, 64) : CASK_EMIT(uint16_t, 128);
+#undef CASK_EMIT
 }
 
 }  // namespace cask

@@ -385,6 +385,114 @@ def test_mass_diagnostics_edge_cases(kind):
     _note((kind, want_rho.tolist(), "assign equal" if same else "assign differs at near-ties"))
 
 
+def test_decode_loop_events_with_count_carry():
+    """Three events of a decode loop: each compresses B + delta rows back to B, decoded tokens
+    are appended behind the output (row stride B + delta), and every cache row carries the
+    number of original tokens it stands for.  Each event is compared with the oracle on the
+    same state (the oracle's own output feeds the next event), so differences cannot pile up."""
+    B, delta, G, d = 256, 128, 7, 128
+    S = B + delta
+    n_units = 3
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=n_units, prefix=90, decode=S - 90, budget=B)
+    p = parity.params_of(w, sim_threshold=0.6)
+    rp = parity.ref_params(p)
+    first = caches.make(w, seed=21)
+    ro, pl, K, V, Q = parity.host_arrays(first)
+    K = K.reshape(n_units, S, d).copy()
+    V = V.reshape(n_units, S, d).copy()
+    cnt = np.ones((n_units, S), dtype=np.int32)
+    plen = pl.copy()
+    dev = torch.device("cuda:0")
+    tau = float(np.float32(p.sim_threshold))
+    folded_total = 0
+    for ev in range(3):
+        row_off = (np.arange(n_units + 1, dtype=np.int64) * S)
+        want = ref.compress_step(rp, row_off, plen, K.reshape(-1, d), V.reshape(-1, d), Q,
+                                 in_count=cnt.reshape(-1), out_stride_rows=S)
+        _, best, second = ref.consolidate(rp, row_off, plen, K.reshape(-1, d), want["scores"], want["role"],
+                                          want_sims=True)
+        # the library on the same state, the oracle's scores injected
+        dt = torch.bfloat16
+        Kd = torch.from_numpy(K.view(np.int16)).view(dt).reshape(-1, d).to(dev)
+        Vd = torch.from_numpy(V.view(np.int16)).view(dt).reshape(-1, d).to(dev)
+        Qd = torch.from_numpy(Q.view(np.int16)).view(dt).to(dev)
+        b = cask.Batch(p, torch.from_numpy(row_off), torch.from_numpy(plen), Kd, Vd, Qd)
+        out = cask.Outputs(b)
+        Ko = torch.zeros(n_units, S, d, dtype=dt, device=dev)
+        Vo = torch.zeros_like(Ko)
+        oc = torch.zeros(n_units, B, dtype=torch.int32, device=dev)
+        cd = torch.from_numpy(cnt.reshape(-1)).to(dev)
+        cask.compress_step(b, Ko, Vo, out, in_count=cd, out_count=oc,
+                           scores=torch.from_numpy(want["scores"]).to(dev))
+        torch.cuda.synchronize()
+        got = dict(K_out=caches.host_bits(Ko)[:, :B], V_out=caches.host_bits(Vo)[:, :B],
+                   out_len=out.out_len.cpu().numpy(), out_src=out.out_src.cpu().numpy(),
+                   out_mass=out.out_mass.cpu().numpy(), assign=out.assign.cpu().numpy(),
+                   status=out.status.cpu().numpy())
+        wv = dict(want)
+        wv["K_out"], wv["V_out"] = want["K_out"][:, :B], want["V_out"][:, :B]
+        assert np.array_equal(got["out_len"], want["out_len"]) and (got["out_len"] == B).all()
+        assert np.array_equal(got["out_src"], want["out_src"])
+        n_bad = 0
+        for u in range(n_units):
+            sl = slice(row_off[u], row_off[u + 1])
+            n_bad += parity.check_assign_excused(got["assign"][sl], want["assign"][sl], best[sl], second[sl],
+                                                 tau, f"event {ev} unit {u}")
+        if n_bad == 0:
+            assert np.array_equal(got["status"], want["status"])
+            assert np.array_equal(oc.cpu().numpy(), want["out_count"])
+        folded_total += parity.check_values(p, got, wv, K.reshape(-1, d), V.reshape(-1, d), row_off)
+        assert not caches.host_bits(Ko)[:, B:].any()            # rows behind the output stay untouched
+        # own scores once per event: within the score tolerance
+        s_own = cask.score(b)
+        torch.cuda.synchronize()
+        parity.check_scores(s_own.cpu().numpy(), want["scores"], row_off)
+        # next state: the oracle's output, then delta freshly decoded tokens with count 1
+        nxt = caches.make(w, seed=100 + ev)
+        _, _, Kn, Vn, Qn = parity.host_arrays(nxt)
+        Kn, Vn = Kn.reshape(n_units, S, d), Vn.reshape(n_units, S, d)
+        K = np.concatenate([want["K_out"][:, :B], Kn[:, S - delta:]], axis=1).copy()
+        V = np.concatenate([want["V_out"][:, :B], Vn[:, S - delta:]], axis=1).copy()
+        cnt = np.concatenate([want["out_count"], np.ones((n_units, delta), dtype=np.int32)], axis=1)
+        Q = Qn
+        plen = np.array([ref.plan(rp, int(plen[u]), S)["p_keep"] for u in range(n_units)], dtype=np.int32)
+    assert folded_total > 0
+    assert int(cnt.max()) > 1          # some representative stands for several tokens by now
+    _note(("decode loop", "folded rows", folded_total, "largest count", int(cnt.max()), "prefix", plen.tolist()))
+
+
+def test_step_zero_mass_groups_average_by_token_count():
+    """All scores zero: every fold is the count-weighted mean of its members."""
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=2, prefix=40, decode=1300, budget=200)
+    p = parity.params_of(w, sim_threshold=-1.0)        # every donor folds
+    rp = parity.ref_params(p)
+    c = caches.make(w, seed=23)
+    row_off, plen, K, V, Q = parity.host_arrays(c)
+    total = int(row_off[-1])
+    rng = np.random.default_rng(8)
+    cnt = rng.integers(1, 20, total).astype(np.int32)
+    s = np.zeros(total, dtype=np.float32)
+    want = ref.compress_step(rp, row_off, plen, K, V, Q, in_count=cnt, scores=s)
+    b = parity.to_device(c, p)
+    out = cask.Outputs(b)
+    Ko = torch.zeros(b.n_units, p.budget, p.head_dim, dtype=torch.bfloat16, device=b.device)
+    Vo = torch.zeros_like(Ko)
+    oc = torch.zeros(b.n_units, p.budget, dtype=torch.int32, device=b.device)
+    cask.compress_step(b, Ko, Vo, out, in_count=torch.from_numpy(cnt).to(b.device), out_count=oc,
+                       scores=torch.from_numpy(s).to(b.device))
+    torch.cuda.synchronize()
+    got = dict(K_out=caches.host_bits(Ko), V_out=caches.host_bits(Vo), out_len=out.out_len.cpu().numpy(),
+               out_src=out.out_src.cpu().numpy(), out_mass=out.out_mass.cpu().numpy(),
+               assign=out.assign.cpu().numpy())
+    assert np.array_equal(got["out_src"], want["out_src"])
+    d = p.head_dim
+    folded = parity.check_values(p, got, want, K.reshape(-1, d), V.reshape(-1, d), row_off)
+    assert folded >= 10
+    if np.array_equal(got["assign"], want["assign"]):
+        assert np.array_equal(oc.cpu().numpy(), want["out_count"])
+    _note(("zero-mass folds", folded))
+
+
 def test_compress_replays_from_a_hip_graph():
     """The whole event is plain kernel launches on the caller's stream (no allocation, no
     synchronisation, no memset): it can be captured once and replayed; every replay must equal
