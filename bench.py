@@ -42,7 +42,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20,
                     help="untimed events first; the clocks settle within about 20")
-    ap.add_argument("--workload", default="cfg2", help="cfg2 (default) | cfg3 | cfg4 | cfg4v | cfg5")
+    ap.add_argument("--workload", default="cfg2",
+                    help="cfg2 (default) | cfg3 | cfg4 | cfg4v | cfg5; cfg2ss / cfg3ss = the steady state of a "
+                         "decode loop on that shape: every event compresses budget + window rows back to the "
+                         "budget (cask_compress_step with token counts), also timed as a replayed HIP graph")
     ap.add_argument("--layers", type=int, default=0, help="use only the first L layers (0 = all)")
     ap.add_argument("--seqs", type=int, default=0, help="cfg5: use only the first S sequences")
     ap.add_argument("--copies", type=int, default=0,
@@ -80,7 +83,14 @@ def main():
         __graft_entry__.build()
     cask.load()
     dev = torch.device("cuda:0")
-    w = caches.WORKLOADS[args.workload]
+    steady = args.workload.endswith("ss")
+    w = caches.WORKLOADS[args.workload[:-2] if steady else args.workload]
+    if steady:
+        # B + delta rows per unit, delta = the window; the prefix has shrunk to its steady p_keep
+        p0 = cask.Params(dtype=cask.BF16, head_dim=w.head_dim, q_per_kv=w.q_per_kv, window=w.window,
+                         recent=w.recent, budget=w.budget, core=w.core)
+        keep = cask.plan(p0, w.prefix, w.prefix + w.decode)["p_keep"]
+        w = caches.scaled(w, prefix=keep, decode=w.budget + w.window - keep)
     layers = range(args.layers) if args.layers > 0 else None
     seqs = range(args.seqs) if args.seqs > 0 else None
     n_layers = args.layers if args.layers > 0 else w.n_layers
@@ -106,8 +116,19 @@ def main():
     kv_tokens = b0.total_rows
     n_units = b0.n_units
 
+    if steady:
+        stride = w.budget + w.window
+        dt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+        K_next = torch.zeros(n_units, stride, w.head_dim, dtype=dt, device=dev)
+        V_next = torch.zeros_like(K_next)
+        counts = torch.ones(kv_tokens, dtype=torch.int32, device=dev)
+        out_count = torch.zeros(n_units, w.budget, dtype=torch.int32, device=dev)
+
     def step(i):
-        cask.compress(batches[i % copies][1], outs)
+        if steady:
+            cask.compress_step(batches[i % copies][1], K_next, V_next, outs, in_count=counts, out_count=out_count)
+        else:
+            cask.compress(batches[i % copies][1], outs)
 
     if args.pmc_copy_mib > 0:
         src = torch.rand((args.pmc_copy_mib << 20) // 4, dtype=torch.float32, device=dev)
@@ -153,6 +174,28 @@ def main():
         spread = {"median": round(float(np.median(per)), 4), "p10": round(float(np.percentile(per, 10)), 4),
                   "p90": round(float(np.percentile(per, 90)), 4), "steps": args.breakdown_steps,
                   "note": "separate pass with an event after every kernel"}
+    graph_ms = None
+    if steady:
+        # the same event as one replayed HIP graph: the launch gaps of six small kernels go away
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step(0)
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - tg0) * 1e3 / args.steps
+        step(0)   # leave the outputs of an eager event behind for the checks below
+        torch.cuda.synchronize()
     status = outs.status.cpu().numpy()
     out_len = outs.out_len.cpu().numpy()
     lens = (b0.row_off_host[1:] - b0.row_off_host[:-1]).numpy()
@@ -237,7 +280,8 @@ def main():
                    "input_copies": copies, "saved_ratio": round(saved, 4),
                    "status_counts": {str(k): int(v) for k, v in zip(*np.unique(status, return_counts=True))},
                    "stage_ms": ({k: round(v, 4) for k, v in stage_ms.items()} if stage_ms else None),
-                   "event_ms_spread": spread},
+                   "event_ms_spread": spread,
+                   "graph_ms_per_step": (round(graph_ms, 4) if graph_ms is not None else None)},
         "roofline": roof,
         "cpu_baseline": cpu,
     }
