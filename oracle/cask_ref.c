@@ -70,6 +70,12 @@ static int check_shape(const cask_ref_params* p) {
 static int check_params(const cask_ref_params* p) {
   if (check_shape(p)) return -1;
   if (p->budget < resolved_recent(p) + 1) return -1;
+  if (p->merge_radius < 0 || p->merge_geometry < 0 || p->merge_geometry > 1) return -1;
+  if (p->merge_geometry == 1) {
+    if (!p->band_weight || !(p->dist_threshold >= 0.0f)) return -1;
+    for (int f = 0; f < p->head_dim / 2; ++f)
+      if (!(p->band_weight[f] >= 0.0f)) return -1;
+  }
   return 0;
 }
 
@@ -360,9 +366,25 @@ static void consolidate_unit(const cask_ref_params* p, int32_t N, const void* K,
     double best = -INFINITY, second = -INFINITY;
     int32_t best_r = -1;
     for (int32_t r = 0; r < n_seed; ++r) { /* ascending cache index */
-      double dot = 0.0;
-      for (int c = 0; c < d; ++c) dot += ki[c] * seed_k[(size_t)r * d + c];
-      double sim = (ni == 0.0 || seed_norm[r] == 0.0) ? 0.0 : dot / (ni * seed_norm[r]);
+      /* locality (Section 5.2): seeds further away than the radius are not candidates */
+      if (p->merge_radius > 0 && abs(seed_row[r] - i) > p->merge_radius) continue;
+      double sim;
+      if (p->merge_geometry == 1) {
+        /* kappa-weighted merge distance (Section 2.5): sum over rotary bands f = channels
+         * (f, f + d/2) of w_f times the Euclidean distance inside the band; kept as the
+         * NEGATED distance so that "larger is closer" like the cosine */
+        double dist = 0.0;
+        for (int f = 0; f < d / 2; ++f) {
+          const double a = ki[f] - seed_k[(size_t)r * d + f];
+          const double b = ki[f + d / 2] - seed_k[(size_t)r * d + f + d / 2];
+          dist += (double)p->band_weight[f] * sqrt(a * a + b * b);
+        }
+        sim = -dist;
+      } else {
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c) dot += ki[c] * seed_k[(size_t)r * d + c];
+        sim = (ni == 0.0 || seed_norm[r] == 0.0) ? 0.0 : dot / (ni * seed_norm[r]);
+      }
       if (sim > best) {
         second = best;
         best = sim;
@@ -373,7 +395,9 @@ static void consolidate_unit(const cask_ref_params* p, int32_t N, const void* K,
     }
     if (best_sim) best_sim[i] = best;
     if (second_sim) second_sim[i] = second;
-    assign[i] = (best_r >= 0 && best >= tau) ? seed_row[best_r] : -1;
+    /* geometry 1 compares the negated distance with -theta */
+    const double bar = p->merge_geometry == 1 ? -(double)p->dist_threshold : tau;
+    assign[i] = (best_r >= 0 && best >= bar) ? seed_row[best_r] : -1;
   }
   free(seed_row);
   free(seed_k);

@@ -66,6 +66,16 @@ typedef struct {
   float sim_threshold;   /* tau */
   float softmax_scale;   /* <= 0 means 1/sqrt(d) */
   int32_t causal;        /* 1: query at slot t sees keys j <= t */
+  /* Merge geometry (Sections 2.5 and 5.2).  All zero / NULL = raw cosine, no locality. */
+  int32_t merge_radius;  /* r > 0: a donor may fold only into a seed at most r cache rows away
+                            (merges stay inside temporal neighbourhoods); 0: anywhere */
+  int32_t merge_geometry; /* 0: key cosine >= sim_threshold; 1: kappa-weighted band distance
+                             d(k_i, k_j) = sum_f w_f |k_i,f - k_j,f|_2 <= dist_threshold, f the
+                             rotary band made of channels (f, f + d/2) */
+  float dist_threshold;  /* theta of geometry 1 */
+  const float* band_weight; /* geometry 1: w_f = |kappa(omega_f)| >= 0, d/2 values; the paper
+                               never fixes the horizon distribution behind kappa, so the caller
+                               supplies the weights */
 } cask_ref_params;
 
 typedef struct {

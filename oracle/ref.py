@@ -10,6 +10,7 @@ import ctypes as C
 import os
 import subprocess
 from dataclasses import dataclass
+from typing import Optional
 
 import numpy as np
 
@@ -39,7 +40,8 @@ class _Params(C.Structure):
                 ("window", C.c_int32), ("recent", C.c_int32), ("budget", C.c_int32),
                 ("core", C.c_int32), ("prefix_budget", C.c_int32),
                 ("sim_threshold", C.c_float), ("softmax_scale", C.c_float),
-                ("causal", C.c_int32)]
+                ("causal", C.c_int32), ("merge_radius", C.c_int32), ("merge_geometry", C.c_int32),
+                ("dist_threshold", C.c_float), ("band_weight", C.c_void_p)]
 
 
 class _Plan(C.Structure):
@@ -60,11 +62,21 @@ class Params:
     sim_threshold: float = 0.9
     softmax_scale: float = 0.0
     causal: int = 1
+    merge_radius: int = 0          # > 0: donors fold only into seeds at most this many rows away
+    merge_geometry: int = 0        # 0 cosine (sim_threshold), 1 kappa-weighted band distance
+    dist_threshold: float = 0.0    # geometry 1: fold iff distance <= this
+    band_weight: Optional[np.ndarray] = None   # geometry 1: float32 [head_dim / 2], >= 0
 
     def c(self) -> _Params:
+        bw = None
+        if self.band_weight is not None:
+            self._bw = np.ascontiguousarray(self.band_weight, dtype=np.float32)   # keep it alive
+            assert self._bw.size == self.head_dim // 2
+            bw = self._bw.ctypes.data
         return _Params(self.dtype, self.head_dim, self.q_per_kv, self.window, self.recent,
                        self.budget, self.core, self.prefix_budget, self.sim_threshold,
-                       self.softmax_scale, self.causal)
+                       self.softmax_scale, self.causal, self.merge_radius, self.merge_geometry,
+                       self.dist_threshold, bw)
 
 
 _lib = None

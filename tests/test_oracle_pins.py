@@ -746,3 +746,100 @@ def test_step_zero_mass_group_is_the_count_weighted_mean(oracle):
     np.testing.assert_array_equal(out["V_out"][0, 0], (1 * V[0] + 3 * V[1] + 4 * V[2]) / 8)
     np.testing.assert_array_equal(out["out_count"][0], [8, 2, 5])
     assert out["out_mass"][0, 0] == 0.0
+
+
+# ------------------------------------------------------------------ merge geometry (Sections 2.5, 5.2)
+
+def _roles_for(oracle, p, ro, pl, s):
+    role, _ = oracle.prefix_evict(p, ro, pl, s)
+    role, _ = oracle.partition(p, ro, pl, s, role)
+    return role
+
+
+def test_merge_radius_limits_candidates_to_neighbours(oracle):
+    rng = np.random.default_rng(51)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, P=10, D=300, B=120, tau=-1.0)
+    N = K.shape[0]
+    s = (rng.random(N) ** 3).astype(np.float32)
+    role = _roles_for(oracle, p, ro, pl, s)
+    base = oracle.consolidate(p, ro, pl, K, s, role)
+    for radius in (0, N, 10 * N):                      # no limit in effect
+        p.merge_radius = radius
+        np.testing.assert_array_equal(oracle.consolidate(p, ro, pl, K, s, role), base)
+    Kn = K.astype(np.float64)
+    Kn /= np.linalg.norm(Kn, axis=1, keepdims=True)
+    seeds = np.flatnonzero(role == oracle.SEED)
+    donors = np.flatnonzero(role == oracle.DONOR)
+    for radius in (3, 17, 60):
+        p.merge_radius = radius
+        got = oracle.consolidate(p, ro, pl, K, s, role)
+        cos = Kn[donors] @ Kn[seeds].T
+        near = np.abs(donors[:, None] - seeds[None, :]) <= radius
+        cos = np.where(near, cos, -np.inf)
+        want = np.where(near.any(1), seeds[cos.argmax(1)], -1)     # tau = -1: any neighbour will do
+        np.testing.assert_array_equal(got[donors], want)
+        assert (got[donors] >= 0).sum() < (base[donors] >= 0).sum() or radius == 60
+
+
+def test_kappa_distance_matches_numpy_and_closed_forms(oracle):
+    rng = np.random.default_rng(52)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, P=10, D=200, B=100)
+    d = p.head_dim
+    N = K.shape[0]
+    s = (rng.random(N) ** 3).astype(np.float32)
+    role = _roles_for(oracle, p, ro, pl, s)
+    seeds = np.flatnonzero(role == oracle.SEED)
+    donors = np.flatnonzero(role == oracle.DONOR)
+    w = rng.random(d // 2).astype(np.float32)
+    p.merge_geometry, p.band_weight = 1, w
+    # brute force: sum over bands (f, f + d/2) of w_f * 2-norm of the band difference
+    diff = K[donors, None, :].astype(np.float64) - K[None, seeds, :].astype(np.float64)
+    band = np.sqrt(diff[..., : d // 2] ** 2 + diff[..., d // 2:] ** 2)
+    dist = (band * w.astype(np.float64)).sum(-1)
+    for theta in (0.0, float(np.median(dist.min(1))), 1e9):
+        p.dist_threshold = theta
+        got, best, second = oracle.consolidate(p, ro, pl, K, s, role, want_sims=True)
+        want = np.where(dist.min(1) <= np.float64(np.float32(theta)), seeds[dist.argmin(1)], -1)
+        np.testing.assert_array_equal(got[donors], want)
+        np.testing.assert_allclose(-best[donors], dist.min(1), rtol=1e-12)
+    assert (got[donors] >= 0).all()                      # theta huge: every donor has a seed
+    # one live band, 3-4-5 triangles: the distance is exactly 5 w_f per step
+    Kc = np.zeros((N, d), dtype=np.float32)
+    f0 = 3
+    w1 = np.zeros(d // 2, dtype=np.float32)
+    w1[f0] = 0.5
+    Kc[:, 0] = rng.standard_normal(N)                    # other bands differ but weigh nothing
+    steps = rng.integers(0, 4, N)
+    Kc[:, f0], Kc[:, f0 + d // 2] = 3.0 * steps, 4.0 * steps
+    p.band_weight, p.dist_threshold = w1, 2.5            # one step = 2.5 is still allowed
+    got, best, _ = oracle.consolidate(p, ro, pl, Kc, s, role, want_sims=True)
+    gap = np.abs(steps[donors, None] - steps[None, seeds]).min(1)
+    np.testing.assert_array_equal(-best[donors], 2.5 * gap)
+    np.testing.assert_array_equal(got[donors] >= 0, gap <= 1)
+    # invalid weights are refused
+    p.band_weight = -w1
+    with pytest.raises(ValueError):
+        oracle.consolidate(p, ro, pl, Kc, s, role)
+    p.band_weight = None
+    with pytest.raises(ValueError):
+        oracle.consolidate(p, ro, pl, Kc, s, role)
+
+
+def test_kappa_geometry_end_to_end_folds_planted_duplicates(oracle):
+    rng = np.random.default_rng(53)
+    p, K, V, Q, ro, pl, pos = make_case(rng, oracle, tau=0.9)
+    d = p.head_dim
+    p.merge_geometry, p.band_weight = 1, np.ones(d // 2, dtype=np.float32)
+    p.dist_threshold = 1.0         # planted members differ by ~0.03 per channel: sum of 8 bands << 1
+    # near-duplicate keys get near-identical scores from the window and then share one role;
+    # independent scores spread each planted cluster over core, seeds and donors
+    s = (rng.random(K.shape[0]) ** 2).astype(np.float32)
+    out = oracle.compress(p, ro, pl, K, V, Q, scores=s)
+    a = out["assign"]
+    merged = np.flatnonzero((out["role"] == oracle.DONOR) & (a >= 0))
+    assert len(merged) > 0
+    src = out["out_src"][0]
+    for i in merged:                # a folded donor sits in the planted cluster of its seed
+        seed = src[a[i]]
+        ci = [c for c in range(pos.shape[0]) if i in pos[c]]
+        assert ci and seed in pos[ci[0]]
