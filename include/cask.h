@@ -80,6 +80,17 @@ typedef struct {
   float softmax_scale;   /* <= 0 => 1 / sqrt(d) */
   int32_t causal;        /* 1: the query at slot t sees keys j <= t; 0: all keys */
   int32_t scores_given;  /* cask_compress only: 1 => `scores` is an input, scoring skipped */
+  /* Merge geometry of the consolidation step; all zero / NULL = raw key cosine, no locality. */
+  int32_t merge_radius;  /* r > 0: a donor may fold only into a seed at most r cache rows away
+                            (merges stay inside temporal neighbourhoods, Section 5.2); 0: anywhere */
+  int32_t merge_geometry; /* 0: key cosine >= sim_threshold; 1: kappa-weighted band distance
+                             (Section 2.5) d(k_i, k_j) = sum_f w_f |k_i,f - k_j,f|_2 <= dist_threshold,
+                             f the rotary band of channels (f, f + d/2); nearest seed, ties to the
+                             lowest cache index */
+  float dist_threshold;  /* theta of geometry 1, >= 0 */
+  const float* band_weight; /* DEVICE [d/2], geometry 1: w_f = |kappa(omega_f)| >= 0 (the paper does
+                               not fix the horizon distribution behind kappa: the caller supplies
+                               the weights; not validated on the device) */
 } cask_params;
 
 typedef struct {

@@ -42,7 +42,8 @@ class _Params(C.Structure):
                 ("window", C.c_int32), ("recent", C.c_int32), ("budget", C.c_int32),
                 ("core", C.c_int32), ("prefix_budget", C.c_int32),
                 ("sim_threshold", C.c_float), ("softmax_scale", C.c_float),
-                ("causal", C.c_int32), ("scores_given", C.c_int32)]
+                ("causal", C.c_int32), ("scores_given", C.c_int32), ("merge_radius", C.c_int32),
+                ("merge_geometry", C.c_int32), ("dist_threshold", C.c_float), ("band_weight", C.c_void_p)]
 
 
 class _Batch(C.Structure):
@@ -69,11 +70,21 @@ class Params:
     sim_threshold: float = 0.9
     softmax_scale: float = 0.0
     causal: int = 1
+    merge_radius: int = 0          # > 0: donors fold only into seeds at most this many rows away
+    merge_geometry: int = 0        # 0 cosine (sim_threshold), 1 kappa-weighted band distance
+    dist_threshold: float = 0.0    # geometry 1: fold iff distance <= this
+    band_weight: Optional[torch.Tensor] = None   # geometry 1: device float32 [head_dim / 2], >= 0
 
     def c(self, scores_given: int = 0) -> _Params:
+        bw = None
+        if self.band_weight is not None:
+            t = self.band_weight
+            assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == self.head_dim // 2
+            bw = t.data_ptr()
         return _Params(self.dtype, self.head_dim, self.q_per_kv, self.window, self.recent,
                        self.budget, self.core, self.prefix_budget, self.sim_threshold,
-                       self.softmax_scale, self.causal, scores_given)
+                       self.softmax_scale, self.causal, scores_given, self.merge_radius,
+                       self.merge_geometry, self.dist_threshold, bw)
 
 
 _lib = None

@@ -80,6 +80,8 @@ static int resolve_params(const cask_params* p, KParams* kp, bool need_budget) {
   const int R = p->recent < 0 ? p->window : p->recent;
   if (need_budget && (p->budget < R + 1 || p->budget > (1 << 24))) return CASK_EINVAL;
   if (!(p->sim_threshold == p->sim_threshold)) return CASK_EINVAL;  // NaN
+  if (p->merge_radius < 0 || p->merge_geometry < 0 || p->merge_geometry > 1) return CASK_EINVAL;
+  if (p->merge_geometry == 1 && (!p->band_weight || !(p->dist_threshold >= 0.f))) return CASK_EINVAL;
   kp->dtype = p->dtype;
   kp->d = p->head_dim;
   kp->G = p->q_per_kv;
@@ -89,6 +91,10 @@ static int resolve_params(const cask_params* p, KParams* kp, bool need_budget) {
   kp->core = p->core;
   kp->prefix_budget = p->prefix_budget;
   kp->tau = p->sim_threshold;
+  kp->radius = p->merge_radius;
+  kp->geometry = p->merge_geometry;
+  kp->theta = p->dist_threshold;
+  kp->band_w = p->band_weight;
   const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
   kp->scale_log2 = (float)(scale * 1.4426950408889634);
   kp->causal = p->causal ? 1 : 0;

@@ -26,6 +26,10 @@ struct KParams {
   float scale_log2;  // softmax scale * log2(e): logits are handled in base-2 units
   int causal;
   int Mq;            // W * G window rows
+  int radius;        // merge radius in cache rows, 0 = unlimited
+  int geometry;      // 0 cosine, 1 kappa-weighted band distance
+  float theta;       // distance threshold of geometry 1
+  const float* band_w;  // device [d / 2] band weights of geometry 1
 };
 
 struct UnitPlan {

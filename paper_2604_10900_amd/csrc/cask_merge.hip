@@ -69,6 +69,7 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
   __shared__ __attribute__((aligned(16))) unsigned char seeds[(kSeedBlock / 4) * kGroupPitch];
   __shared__ __attribute__((aligned(16))) unsigned char turn[4][8 * kGroupPitch];
   __shared__ __attribute__((aligned(16))) float seed_inv[kSeedBlock];
+  __shared__ __attribute__((aligned(16))) int seed_pos[kSeedBlock];  // cache row of each staged seed
   const int bid = blockIdx.x;
   const int xcd = bid & 7, kk = bid >> 3;
   const int u = (kk / chunks_per_unit) * 8 + xcd;
@@ -140,10 +141,15 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
         float ss = sumsq_bf16x8(v[i]);
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-        if ((tid & 15) == 0) seed_inv[sr] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+        if ((tid & 15) == 0) {
+          seed_inv[sr] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+          seed_pos[sr] = idx[i];
+        }
       }
     }
   };
+  // merge radius (0 = none): seeds further than this many cache rows from the donor are skipped
+  const int radius = kp.radius > 0 ? kp.radius : 0x7fffffff;
 
 #pragma unroll
   for (int t = 0; t < kPrefetch; ++t) fetch_donors(t, dreg[t], rreg[t]);
@@ -195,12 +201,15 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
 #pragma unroll
         for (int g = 0; g < 4; ++g) {  // ascending seed ordinal within the lane
           const float4 si = *reinterpret_cast<const float4*>(&seed_inv[s0 + g * 8 + h * 4]);
+          const int4 sp = *reinterpret_cast<const int4*>(&seed_pos[s0 + g * 8 + h * 4]);
           const float sv[4] = {si.x, si.y, si.z, si.w};
+          const int pv[4] = {sp.x, sp.y, sp.z, sp.w};
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int sr = s0 + g * 8 + h * 4 + q;
             const float sim = (acc[g * 4 + q] * sv[q]) * dinv;
-            if (sr < m_blk && sim > best) {
+            const int gap = pv[q] > drow ? pv[q] - drow : drow - pv[q];
+            if (sr < m_blk && gap <= radius && sim > best) {
               best = sim;
               best_ord = sb + sr;
             }
@@ -275,6 +284,8 @@ __global__ __launch_bounds__(256) void similarity_fma_kernel(
     __syncthreads();
     const int lim = min(SEEDS, M - s0);
     for (int sr = 0; sr < lim; ++sr) {
+      const int gap = srow[s0 + sr] > i ? srow[s0 + sr] - i : i - srow[s0 + sr];
+      if (kp.radius > 0 && gap > kp.radius) continue;
       float dot = 0.f;
 #pragma unroll
       for (int c = 0; c < D; ++c) dot = __builtin_fmaf(k[c], sk[sr][c], dot);
@@ -289,6 +300,159 @@ __global__ __launch_bounds__(256) void similarity_fma_kernel(
     const bool donor = role[row0 + i] == CASK_ROLE_DONOR;
     assign_ord[row0 + i] = (donor && best_ord >= 0 && best >= kp.tau) ? best_ord : -1;
   }
+}
+
+// ------------------------------------------------------------------ similarity, kappa geometry
+
+// Kappa-weighted merge distance (Section 2.5): d(k_i, k_j) = sum over rotary bands f (channels
+// f and f + D/2) of w_f times the Euclidean distance inside the band.  A square root per band
+// keeps this off the matrix cores: one thread per donor with its key in registers, seeds staged
+// in LDS 32 at a time (every lane reads the same seed element: a broadcast), fp32 throughout.
+// Nearest seed wins (first minimum in ascending seed order) if its distance is <= theta.
+//
+// Every term is non-negative and fp32 addition of non-negative terms is monotone, so a partial
+// sum is a lower bound of the finished one.  Bands are summed in chunks of eight, heaviest
+// chunk (by summed weight) first, and a wave leaves a seed as soon as no lane's partial sum can
+// still win (<= theta and < its best so far).  Lanes that finish hold the full sum in the same
+// order as without the early exit, so the result does not depend on it.
+template <typename T>
+__device__ inline void load8(const T* p, float* out);
+template <>
+__device__ inline void load8<float>(const float* p, float* out) {
+  const float4 a = *reinterpret_cast<const float4*>(p);
+  const float4 b = *reinterpret_cast<const float4*>(p + 4);
+  out[0] = a.x, out[1] = a.y, out[2] = a.z, out[3] = a.w;
+  out[4] = b.x, out[5] = b.y, out[6] = b.z, out[7] = b.w;
+}
+template <>
+__device__ inline void load8<uint16_t>(const uint16_t* p, float* out) {
+  const uint4 r = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    out[2 * j] = __uint_as_float(w[j] << 16);
+    out[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+  }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void similarity_kappa_kernel(
+    KParams kp, int n_units, int tiles_per_unit, const int64_t* __restrict__ row_off,
+    const int32_t* __restrict__ prefix_len, const T* __restrict__ K,
+    const uint8_t* __restrict__ role, const int32_t* __restrict__ seed_rows,
+    const int32_t* __restrict__ n_seeds, int32_t* __restrict__ assign_ord) {
+  constexpr int SEEDS = 32;
+  constexpr int H = D / 2;
+  constexpr int NCH = H / 8;  // chunks of eight bands
+  __shared__ __attribute__((aligned(16))) float sk[SEEDS][D];
+  __shared__ __attribute__((aligned(16))) float wband[H];
+  __shared__ int spos[SEEDS];
+  __shared__ uint32_t chunk_order;  // four bits per position: which chunk is summed there
+  const int bid = blockIdx.x;
+  const int u = bid / tiles_per_unit, tile = bid % tiles_per_unit;
+  if (u >= n_units) return;
+  const int64_t row0 = row_off[u];
+  const int N = (int)(row_off[u + 1] - row0);
+  const int P = prefix_len[u];
+  const UnitPlan pl = make_plan(kp, P, N);
+  const int hi = N - pl.r_eff;
+  const int base = P + tile * 256;
+  if (base >= hi) return;
+  const int M = n_seeds[u];
+  const int tid = threadIdx.x;
+  const int i = base + tid;
+  const bool ok = i < hi;
+  const T* Ku = K + (size_t)row0 * D;
+  const int32_t* srow = seed_rows + (size_t)u * kp.B;
+  if (tid < H) wband[tid] = kp.band_w[tid];
+  __syncthreads();
+  if (tid == 0) {
+    float cw[NCH];
+    for (int c = 0; c < NCH; ++c) {
+      cw[c] = 0.f;
+      for (int f = 0; f < 8; ++f) cw[c] += wband[c * 8 + f];
+    }
+    uint32_t packed = 0;
+    for (int c = 0; c < NCH; ++c) {  // rank = chunks that come before c
+      int r = 0;
+      for (int e = 0; e < NCH; ++e) r += (cw[e] > cw[c]) || (cw[e] == cw[c] && e < c);
+      packed |= (uint32_t)c << (4 * r);
+    }
+    chunk_order = packed;
+  }
+  __syncthreads();
+  const uint32_t order = __builtin_amdgcn_readfirstlane(chunk_order);
+  const bool donor = ok && role[row0 + i] == CASK_ROLE_DONOR;
+  float k[D];
+#pragma unroll
+  for (int c = 0; c < D; c += 8) load8<T>(Ku + (size_t)(ok ? i : P) * D + c, k + c);
+  float best = __builtin_inff();
+  int best_ord = -1;
+  for (int s0 = 0; s0 < M; s0 += SEEDS) {
+    __syncthreads();
+    for (int q = tid; q < SEEDS * D / 8; q += 256) {
+      const int sr = q / (D / 8), c = (q % (D / 8)) * 8;
+      float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      if (s0 + sr < M) load8<T>(Ku + (size_t)srow[s0 + sr] * D + c, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sk[sr][c + e] = v[e];
+    }
+    if (tid < SEEDS) spos[tid] = (s0 + tid < M) ? srow[s0 + tid] : 0;
+    __syncthreads();
+    const int lim = min(SEEDS, M - s0);
+    for (int sr = 0; sr < lim; ++sr) {
+      const int gap = spos[sr] > i ? spos[sr] - i : i - spos[sr];
+      const bool in_reach = donor && (kp.radius <= 0 || gap <= kp.radius);
+      if (__builtin_amdgcn_ballot_w64(in_reach) == 0) continue;
+      float dist = 0.f;
+      bool finished = true;
+      for (int ci = 0; ci < NCH; ++ci) {
+        const int c = (int)((order >> (4 * ci)) & 15u);
+#pragma unroll
+        for (int cc = 0; cc < NCH; ++cc) {
+          if (c == cc) {
+            const float4 a0 = *reinterpret_cast<const float4*>(&sk[sr][cc * 8]);
+            const float4 a1 = *reinterpret_cast<const float4*>(&sk[sr][cc * 8 + 4]);
+            const float4 b0 = *reinterpret_cast<const float4*>(&sk[sr][H + cc * 8]);
+            const float4 b1 = *reinterpret_cast<const float4*>(&sk[sr][H + cc * 8 + 4]);
+            const float4 w0 = *reinterpret_cast<const float4*>(&wband[cc * 8]);
+            const float4 w1 = *reinterpret_cast<const float4*>(&wband[cc * 8 + 4]);
+            const float sa[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+            const float sb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+            const float ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+            for (int f = 0; f < 8; ++f) {
+              const float a = k[cc * 8 + f] - sa[f];
+              const float b = k[H + cc * 8 + f] - sb[f];
+              dist = __builtin_fmaf(ww[f], __builtin_amdgcn_sqrtf(__builtin_fmaf(a, a, b * b)), dist);
+            }
+          }
+        }
+        const bool alive = in_reach && dist <= kp.theta && dist < best;
+        if (ci + 1 < NCH && __builtin_amdgcn_ballot_w64(alive) == 0) {
+          finished = false;
+          break;
+        }
+      }
+      if (finished && in_reach && dist < best) {
+        best = dist;
+        best_ord = s0 + sr;
+      }
+    }
+  }
+  if (ok) assign_ord[row0 + i] = (donor && best_ord >= 0 && best <= kp.theta) ? best_ord : -1;
+}
+
+template <typename T, int D>
+hipError_t launch_similarity_kappa(const KParams& kp, const Batch& b, const uint8_t* role,
+                                   const int32_t* seed_rows, const int32_t* n_seeds,
+                                   int32_t* assign_ord, hipStream_t st) {
+  const int tiles = (b.max_decode_len + 255) / 256;
+  if (tiles == 0) return hipSuccess;
+  similarity_kappa_kernel<T, D><<<dim3(b.n_units * tiles), dim3(256), 0, st>>>(
+      kp, b.n_units, tiles, b.row_off, b.prefix_len, static_cast<const T*>(b.K), role, seed_rows,
+      n_seeds, assign_ord);
+  return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ gather merged donors
@@ -547,6 +711,13 @@ hipError_t launch_similarity_fma(const KParams& kp, const Batch& b, const uint8_
 hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* role,
                              const int32_t* seed_rows, const int32_t* n_seeds,
                              int32_t* assign_ord, bool roles_follow_plan, hipStream_t st) {
+  if (kp.geometry == 1) {
+    if (kp.dtype == CASK_F32)
+      return kp.d == 64 ? launch_similarity_kappa<float, 64>(kp, b, role, seed_rows, n_seeds, assign_ord, st)
+                        : launch_similarity_kappa<float, 128>(kp, b, role, seed_rows, n_seeds, assign_ord, st);
+    return kp.d == 64 ? launch_similarity_kappa<uint16_t, 64>(kp, b, role, seed_rows, n_seeds, assign_ord, st)
+                      : launch_similarity_kappa<uint16_t, 128>(kp, b, role, seed_rows, n_seeds, assign_ord, st);
+  }
   if (kp.dtype == CASK_BF16 && kp.d == 128) {
     // a few workgroups per unit, about two per compute unit in all, each walking its share of
     // the unit's donor tiles

@@ -26,7 +26,9 @@ def ref_params(p: cask.Params) -> ref.Params:
     return ref.Params(dtype=p.dtype, head_dim=p.head_dim, q_per_kv=p.q_per_kv, window=p.window,
                       recent=p.recent, budget=p.budget, core=p.core,
                       prefix_budget=p.prefix_budget, sim_threshold=p.sim_threshold,
-                      softmax_scale=p.softmax_scale, causal=p.causal)
+                      softmax_scale=p.softmax_scale, causal=p.causal, merge_radius=p.merge_radius,
+                      merge_geometry=p.merge_geometry, dist_threshold=p.dist_threshold,
+                      band_weight=None if p.band_weight is None else p.band_weight.cpu().numpy())
 
 
 def params_of(w: caches.Workload, **kw) -> cask.Params:
@@ -68,8 +70,11 @@ def check_assign_excused(got: np.ndarray, want: np.ndarray, best: np.ndarray, se
     """Mismatching donors must be near-ties in the oracle; returns the number excused."""
     bad = np.flatnonzero(got != want)
     for i in bad:
-        near_tau = abs(best[i] - tau) < SIM_EXCUSE
-        near_tie = np.isfinite(second[i]) and (best[i] - second[i]) < SIM_EXCUSE
+        # cosines live in [-1, 1]; negated band distances (kappa geometry) can be large: the
+        # margin is relative there
+        eps = SIM_EXCUSE * max(1.0, abs(best[i]))
+        near_tau = abs(best[i] - tau) < eps
+        near_tie = np.isfinite(second[i]) and (best[i] - second[i]) < eps
         assert near_tau or near_tie, (f"{label} row {i}: assign {got[i]} != {want[i]}, best cos "
                                       f"{best[i]:.6f}, second {second[i]:.6f}, tau {tau}")
     return len(bad)
@@ -165,8 +170,8 @@ def full_check(c: dict, p: cask.Params, expect_folds: bool = False, n_threads: i
                                              want_sims=True)
     a_gpu = cask.consolidate(b, s_inj, role)
     torch.cuda.synchronize()
-    stats["assign_excused"] = check_assign_excused(a_gpu.cpu().numpy(), want_src, best, second,
-                                                   float(np.float32(p.sim_threshold)), "consolidate")
+    bar = -float(np.float32(p.dist_threshold)) if p.merge_geometry == 1 else float(np.float32(p.sim_threshold))
+    stats["assign_excused"] = check_assign_excused(a_gpu.cpu().numpy(), want_src, best, second, bar, "consolidate")
 
     # ---- injected-score mode: whole event
     out = cask.compress(b, scores=s_inj)
@@ -178,7 +183,7 @@ def full_check(c: dict, p: cask.Params, expect_folds: bool = False, n_threads: i
     for u in range(n_units):
         sl = slice(row_off[u], row_off[u + 1])
         n_bad += check_assign_excused(got["assign"][sl], want["assign"][sl], best[sl], second[sl],
-                                      float(np.float32(p.sim_threshold)), f"compress unit {u}")
+                                      bar, f"compress unit {u}")
     if n_bad == 0:
         assert np.array_equal(got["status"], want["status"])
     stats["folded_rows"] = check_values(p, got, want, K2, V2, row_off)

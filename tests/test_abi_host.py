@@ -163,3 +163,26 @@ def test_mass_diagnostics_validates_on_the_host(cask):
     empty = cask.binding._Batch(0, None, None, None, None, None, None, None)
     assert lib.cask_mass_diagnostics(C.byref(ok), C.byref(empty), None, None, None, None, None, None) == cask.binding.OK
 
+
+
+def test_merge_geometry_fields_validate_on_the_host(cask):
+    """Negative radius, unknown geometry, and the kappa geometry without weights or with a
+    negative / NaN threshold are refused before any HIP call."""
+    lib = cask.load()
+    b = cask.binding._Batch(0, None, None, None, None, None, None, None)
+
+    def rc(**kw):
+        cp = cask.Params().c()
+        for k, v in kw.items():
+            setattr(cp, k, v)
+        return lib.cask_consolidate(C.byref(cp), C.byref(b), None, None, None, None, 0, None)
+
+    assert rc() == cask.binding.OK
+    assert rc(merge_radius=17) == cask.binding.OK
+    assert rc(merge_radius=-1) == cask.binding.EINVAL
+    assert rc(merge_geometry=2) == cask.binding.EINVAL
+    assert rc(merge_geometry=-1) == cask.binding.EINVAL
+    assert rc(merge_geometry=1) == cask.binding.EINVAL                       # no band weights
+    assert rc(merge_geometry=1, band_weight=256, dist_threshold=-1.0) == cask.binding.EINVAL
+    assert rc(merge_geometry=1, band_weight=256, dist_threshold=float("nan")) == cask.binding.EINVAL
+    assert rc(merge_geometry=1, band_weight=256, dist_threshold=3.0) == cask.binding.OK   # empty batch: no-op

@@ -174,6 +174,45 @@ def test_consolidate_with_caller_roles_naming_many_seeds():
     _note(("excused", n))
 
 
+@pytest.mark.parametrize("radius", [5, 40, 400])
+def test_merge_radius_bf16_mfma_and_fp32(radius):
+    """Donors fold only into seeds at most `radius` cache rows away (Section 5.2)."""
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=2, prefix=60, decode=2400, budget=700)
+    c = caches.make(w, seed=31)
+    st = parity.full_check(c, parity.params_of(w, core=150, sim_threshold=0.2, merge_radius=radius),
+                           expect_folds=radius >= 40)
+    _note((radius, st))
+    w32 = caches.scaled(W["cfg1"], decode=900, budget=300, core=60)
+    c32 = caches.make(w32, seed=32)
+    _note(parity.full_check(c32, parity.params_of(w32, sim_threshold=0.1, merge_radius=radius)))
+
+
+@pytest.mark.parametrize("dtype_case", ["bf16_d128", "bf16_d64", "f32_d64", "f32_d128"])
+def test_kappa_weighted_merge_distance(dtype_case):
+    """Geometry 1 (Section 2.5): nearest seed in the band-weighted distance, folded when within
+    dist_threshold; every entry point against the oracle, with and without a radius."""
+    dev = torch.device("cuda:0")
+    if dtype_case == "bf16_d128":
+        w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=2, prefix=60, decode=1500, budget=500)
+    elif dtype_case == "bf16_d64":
+        w = caches.scaled(W["cfg2"], head_dim=64, n_layers=1, n_kv_heads=2, q_per_kv=2, prefix=60, decode=900,
+                          window=48, budget=300)
+    elif dtype_case == "f32_d64":
+        w = caches.scaled(W["cfg1"], decode=700, budget=256, core=60)
+    else:
+        w = caches.scaled(W["cfg1"], head_dim=128, q_per_kv=2, decode=700, window=20, recent=16, budget=200,
+                          core=-1, fixed_clusters=None, cluster_lo=4, cluster_hi=9)
+    c = caches.make(w, seed=33)
+    d = w.head_dim
+    g = torch.Generator().manual_seed(7)
+    band = (torch.rand(d // 2, generator=g) ** 2).to(dev)            # a few bands dominate
+    for theta, radius in ((6.0, 0), (1e9, 0), (25.0, 64)):
+        p = parity.params_of(w, core=(60 if w.core < 0 else w.core), merge_geometry=1, band_weight=band,
+                             dist_threshold=theta, merge_radius=radius)
+        st = parity.full_check(c, p, expect_folds=theta > 1e6)
+        _note((dtype_case, theta, radius, st))
+
+
 def test_stage_timing_api():
     w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=2, decode=1200)
     c = caches.make(w)
