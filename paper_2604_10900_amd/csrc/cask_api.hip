@@ -63,6 +63,8 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
   w.assign_ord = take(rows * sizeof(int32_t));
   w.merged_row = take(rows * sizeof(int32_t));
   w.merged_ord = take(rows * sizeof(int32_t));
+  w.seg_row = take(rows * sizeof(int32_t));
+  w.seg_start = take(units * ((size_t)kp.B + 1) * sizeof(int32_t));
   w.seed_rows = take(units * kp.B * sizeof(int32_t));
   w.ord_of_slot = take(units * kp.B * sizeof(int32_t));
   w.n_merged = take(units * sizeof(int32_t));
@@ -278,7 +280,7 @@ int cask_consolidate(const cask_params* params, const cask_batch* batch, const f
   e = launch_gather_merged(kp, b, role, assign_ord, nullptr, seed_rows,
                            reinterpret_cast<int32_t*>(w + wl.merged_row),
                            reinterpret_cast<int32_t*>(w + wl.merged_ord), nullptr, assign, 2,
-                           nullptr, st);
+                           nullptr, n_seeds, nullptr, nullptr, st);
   return dev_rc(e);
 }
 
@@ -333,6 +335,8 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
   int32_t* assign_ord = reinterpret_cast<int32_t*>(w + wl.assign_ord);
   int32_t* merged_row = reinterpret_cast<int32_t*>(w + wl.merged_row);
   int32_t* merged_ord = reinterpret_cast<int32_t*>(w + wl.merged_ord);
+  int32_t* seg_row = reinterpret_cast<int32_t*>(w + wl.seg_row);
+  int32_t* seg_start = reinterpret_cast<int32_t*>(w + wl.seg_start);
   int32_t* seed_rows = reinterpret_cast<int32_t*>(w + wl.seed_rows);
   int32_t* ord_of_slot = reinterpret_cast<int32_t*>(w + wl.ord_of_slot);
   int32_t* n_merged = reinterpret_cast<int32_t*>(w + wl.n_merged);
@@ -357,10 +361,11 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
   if (e != hipSuccess) return CASK_EDEVICE;
   rec.mark();
   e = launch_gather_merged(kp, b, role, assign_ord, slot_of, seed_rows, merged_row, merged_ord,
-                           n_merged, assign, assign ? 1 : 0, status, st);
+                           n_merged, assign, assign ? 1 : 0, status, n_seeds, seg_row, seg_start, st);
   if (e != hipSuccess) return CASK_EDEVICE;
   rec.mark();
-  e = launch_emit(kp, b, s, out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, K_out,
+  e = launch_emit(kp, b, s, out_src, out_len, ord_of_slot, seed_rows, n_seeds, slot_of, seg_row,
+                  seg_start, n_merged, K_out,
                   V_out, out_mass, in_count, out_count, out_stride_rows, st);
   rec.mark();
   return dev_rc(e);

@@ -90,6 +90,14 @@ __host__ __device__ inline UnitPlan make_plan(const KParams& kp, int P, int N) {
   return make_plan(kp.R, kp.B, kp.core, kp.prefix_budget, P, N);
 }
 
+// Seeds a unit can have when its roles come from the plan: seeds = slots - core with
+// slots <= B, so at most B - core for an explicit core size and at most ceil(B / 5) for the
+// default four-fifths core share.
+inline int plan_seed_bound(const KParams& kp) {
+  const int sb = kp.core >= 0 ? (kp.B - kp.core > 0 ? kp.B - kp.core : 0) : (kp.B + 4) / 5;
+  return sb < kp.B ? sb : kp.B;
+}
+
 // ---------------------------------------------------------------- element helpers
 
 __device__ inline float bf16_bits_to_float(uint16_t h) {
@@ -142,6 +150,8 @@ struct Workspace {
   size_t assign_ord; // int32  [total_rows] seed ordinal a donor folds into, -1 otherwise
   size_t merged_row; // int32  [total_rows] per unit: rows of merged donors, ascending
   size_t merged_ord; // int32  [total_rows] their seed ordinals
+  size_t seg_row;    // int32  [total_rows] per unit: the same rows grouped by seed ordinal, ascending inside a group
+  size_t seg_start;  // int32  [n_units][B + 1] where each seed's group starts in seg_row
   size_t seed_rows;  // int32  [n_units][B] unit-local rows of the seeds, ascending
   size_t ord_of_slot;// int32  [n_units][B] seed ordinal of an output slot, -1 if not a seed
   size_t n_merged;   // int32  [n_units]
@@ -194,10 +204,12 @@ hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t
                                 const int32_t* assign_ord, const int32_t* slot_of,
                                 const int32_t* seed_rows, int32_t* merged_row, int32_t* merged_ord,
                                 int32_t* n_merged, int32_t* assign_out, int assign_mode,
-                                int32_t* status, hipStream_t st);
+                                int32_t* status, const int32_t* n_seeds, int32_t* seg_row,
+                                int32_t* seg_start, hipStream_t st);
 hipError_t launch_emit(const KParams& kp, const Batch& b, const float* scores,
                        const int32_t* out_src, const int32_t* out_len, const int32_t* ord_of_slot,
-                       const int32_t* merged_row, const int32_t* merged_ord,
+                       const int32_t* seed_rows, const int32_t* n_seeds, const int32_t* slot_of,
+                       const int32_t* seg_row, const int32_t* seg_start,
                        const int32_t* n_merged, void* K_out, void* V_out, float* out_mass,
                        const int32_t* in_count, int32_t* out_count, int out_stride,
                        hipStream_t st);

@@ -459,6 +459,7 @@ hipError_t launch_similarity_kappa(const KParams& kp, const Batch& b, const uint
 
 constexpr int kGatherThreads = 1024;
 constexpr int kGatherPer = 16;  // 64-row groups per wave and chunk
+constexpr int kSegLds = 8192;   // seed ordinals whose segment cursors fit in LDS at a time
 
 // assign_mode: 0 none, 1 output slot (whole event), 2 unit-local source row (consolidate API)
 __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
@@ -467,8 +468,10 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
     const int32_t* __restrict__ slot_of, const int32_t* __restrict__ seed_rows,
     int32_t* __restrict__ merged_row, int32_t* __restrict__ merged_ord,
     int32_t* __restrict__ n_merged, int32_t* __restrict__ assign_out, int assign_mode,
-    int32_t* __restrict__ status) {
+    int32_t* __restrict__ status, const int32_t* __restrict__ n_seeds,
+    int32_t* __restrict__ seg_row, int32_t* __restrict__ seg_start) {
   __shared__ int wsum[kGatherThreads / 64];
+  __shared__ int cursor[kSegLds];
   const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int64_t row0 = row_off[u];
   const int N = (int)(row_off[u + 1] - row0);
@@ -545,21 +548,106 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
     if (status && count == 0 && !(pl.status & (CASK_ST_IDENTITY | CASK_ST_PREFIX_BUDGET_EXHAUSTED)))
       status[u] = pl.status | CASK_ST_MERGE_INACTIVE;
   }
+  if (seg_row == nullptr || count == 0) return;  // count is the same in every thread
+
+  // Second pass: the same donors grouped by seed ordinal, rows still ascending inside a group
+  // (a stable split), so that a seed's fold reads one contiguous segment.  Histogram and scan
+  // give the segment starts; then wave w places the ordinals congruent to w modulo 16, walking
+  // the whole list in order, so no two waves ever touch the same cursor and the order inside a
+  // segment is the list's.  Ordinals are handled kSegLds at a time.
+  __syncthreads();  // the list written above is read by other threads below
+  const int M = n_seeds[u];
+  const int32_t* mrow = merged_row + row0;
+  const int32_t* mord = merged_ord + row0;
+  int32_t* sstart = seg_start + (size_t)u * (kp.B + 1);
+  int base = 0;
+  for (int o_lo = 0; o_lo < M; o_lo += kSegLds) {
+    const int range = min(kSegLds, M - o_lo);
+    for (int q = tid; q < range; q += kGatherThreads) cursor[q] = 0;
+    __syncthreads();
+    for (int idx = tid; idx < count; idx += kGatherThreads) {
+      const int o = mord[idx] - o_lo;
+      if (o >= 0 && o < range) atomicAdd(&cursor[o], 1);
+    }
+    __syncthreads();
+    constexpr int PER = kSegLds / kGatherThreads;
+    int loc[PER], sum = 0;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      const int q = tid * PER + e;
+      loc[e] = q < range ? cursor[q] : 0;
+      sum += loc[e];
+    }
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += y;
+    }
+    if (lane == 63) wsum[wv] = incl;
+    __syncthreads();
+    int before = 0, tot = 0;
+    for (int w = 0; w < kGatherThreads / 64; ++w) {
+      const int x = wsum[w];
+      if (w < wv) before += x;
+      tot += x;
+    }
+    int at = base + before + (incl - sum);
+#pragma unroll
+    for (int e = 0; e < PER; ++e) {
+      const int q = tid * PER + e;
+      if (q < range) {
+        cursor[q] = at;
+        sstart[o_lo + q] = at;
+        at += loc[e];
+      }
+    }
+    base += tot;
+    __syncthreads();
+    for (int i0 = 0; i0 < count; i0 += 64) {
+      const int idx = i0 + lane;
+      const int o = idx < count ? mord[idx] - o_lo : -1;
+      const bool mine = o >= 0 && o < range && (o & (kGatherThreads / 64 - 1)) == wv;
+      unsigned long long todo = __ballot(mine);
+      if (todo == 0ull) continue;
+      const int drow = idx < count ? mrow[idx] : 0;
+      while (todo != 0ull) {
+        const int l = __ffsll((long long)todo) - 1;
+        const int v = __shfl(o, l, 64);
+        const bool in = mine && o == v;
+        const unsigned long long m = __ballot(in);
+        const int c = cursor[v];
+        if (in) seg_row[row0 + c + __popcll(m & below)] = drow;
+        if (lane == l) cursor[v] = c + __popcll(m);
+        todo &= ~m;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) sstart[M] = count;
 }
 
 // ------------------------------------------------------------------ emit (copy + fold)
 
-// Sixteen lanes per output row (D / 16 elements each), so a wave moves four rows per load
-// instruction; it owns 16 consecutive slots of one unit and puts the loads of four rows of K
-// and V in flight before it touches any of them.  A seed slot then folds its donors: the
-// group walks the unit's merged list (ascending rows) and accumulates the matching ones in
-// fp32 in that order.
+// One launch, two kinds of workgroup.  Sixteen lanes hold one row (D / 16 elements each).
+//
+// Copy workgroups: a wave owns 16 consecutive output slots of one unit, puts the loads of four
+// rows of K and V in flight before it touches any of them, and writes every slot that is not
+// a representative (a seed whose group of donors is empty is copied like any kept row).
+//
+// Fold workgroups: a wave owns one seed of one unit.  Its four 16-lane groups take the seed's
+// donors (one contiguous segment of the grouped donor list, ascending rows) round-robin, four
+// donors' loads in flight per group, accumulate in fp32 in ascending order, and the four
+// partial sums are added in a fixed tree, so the result does not depend on timing.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void emit_kernel(
-    KParams kp, int n_units, const int64_t* __restrict__ row_off, const T* __restrict__ K,
-    const T* __restrict__ V, const float* __restrict__ scores, const int32_t* __restrict__ out_src,
-    const int32_t* __restrict__ out_len, const int32_t* __restrict__ ord_of_slot,
-    const int32_t* __restrict__ merged_row, const int32_t* __restrict__ merged_ord,
+    KParams kp, int n_units, int copy_blocks, int fold_per_unit,
+    const int64_t* __restrict__ row_off, const T* __restrict__ K, const T* __restrict__ V,
+    const float* __restrict__ scores,
+    const int32_t* __restrict__ out_src, const int32_t* __restrict__ out_len,
+    const int32_t* __restrict__ ord_of_slot, const int32_t* __restrict__ seed_rows,
+    const int32_t* __restrict__ n_seeds, const int32_t* __restrict__ slot_of,
+    const int32_t* __restrict__ seg_row, const int32_t* __restrict__ seg_start,
     const int32_t* __restrict__ n_merged, T* __restrict__ K_out, T* __restrict__ V_out,
     float* __restrict__ out_mass, const int32_t* __restrict__ in_count,
     int32_t* __restrict__ out_count, int out_stride) {
@@ -568,8 +656,124 @@ __global__ __launch_bounds__(256) void emit_kernel(
   constexpr int kSlotsPerWave = 16;
   struct alignas(WORDS * 4 > 16 ? 16 : WORDS * 4) Raw { uint32_t w[WORDS]; };
   const int lane = threadIdx.x & 63, grp = lane >> 4, gl = lane & 15;
-  const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int B = kp.B;
+
+  if ((int)blockIdx.x >= copy_blocks) {
+    // ---- fold role: work items are (unit, seed ordinal) pairs; each lane tests one item of
+    // a round (neighbouring ordinals go to different waves), then the wave folds the items
+    // that have donors one after the other.
+    const int NW = ((int)gridDim.x - copy_blocks) * 4;
+    const int w = ((int)blockIdx.x - copy_blocks) * 4 + (int)(threadIdx.x >> 6);
+    const long long items = (long long)n_units * fold_per_unit;
+    for (long long base = 0; base < items; base += 64LL * NW) {
+      const long long item = base + (long long)lane * NW + w;
+      int my_u = 0, my_ord = 0, my_s0 = 0, my_s1 = 0;
+      if (item < items) {
+        my_u = (int)(item / fold_per_unit);
+        my_ord = (int)(item % fold_per_unit);
+        if (my_ord < n_seeds[my_u] && n_merged[my_u] > 0) {
+          my_s0 = seg_start[(size_t)my_u * (B + 1) + my_ord];
+          my_s1 = seg_start[(size_t)my_u * (B + 1) + my_ord + 1];
+        }
+      }
+      unsigned long long todo = __ballot(my_s1 > my_s0);
+      while (todo != 0ull) {
+        const int src_lane = __ffsll((long long)todo) - 1;
+        todo &= todo - 1ull;
+        const int u = __shfl(my_u, src_lane, 64), ord = __shfl(my_ord, src_lane, 64);
+        const int s0 = __shfl(my_s0, src_lane, 64), s1 = __shfl(my_s1, src_lane, 64);
+        const int64_t row0 = row_off[u];
+        const int32_t* seg = seg_row + row0;
+        const int srow = seed_rows[(size_t)u * B + ord];
+        const int slot = slot_of[row0 + srow];
+        float ka[EPL], va[EPL], ku[EPL], vu[EPL];  // score-weighted and count-weighted sums
+        float mass = 0.f;
+        int count = 0;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) ka[e] = va[e] = ku[e] = vu[e] = 0.f;
+        if (grp == 0) {  // the seed's own row opens the first group's sum
+          const float a = scores[row0 + srow];
+          const int c = in_count ? in_count[row0 + srow] : 1;
+          const Raw sk = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + srow) * D + gl * EPL);
+          const Raw sv = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + srow) * D + gl * EPL);
+          const T* skp = reinterpret_cast<const T*>(&sk);
+          const T* svp = reinterpret_cast<const T*>(&sv);
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            const float kf = Elem<T>::load(skp + e), vf = Elem<T>::load(svp + e);
+            ka[e] = a * kf; va[e] = a * vf; ku[e] = (float)c * kf; vu[e] = (float)c * vf;
+          }
+          mass = a;
+          count = c;
+        }
+        for (int idx = s0 + grp; idx < s1; idx += 16) {
+          int drow[4], dc[4];
+          float a[4];
+          Raw dk[4], dv[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) drow[q] = seg[min(idx + 4 * q, s1 - 1)];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            a[q] = scores[row0 + drow[q]];
+            dc[q] = in_count ? in_count[row0 + drow[q]] : 1;
+            dk[q] = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + drow[q]) * D + gl * EPL);
+            dv[q] = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + drow[q]) * D + gl * EPL);
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (idx + 4 * q < s1) {
+              const float dcf = (float)dc[q];
+              const T* dkp = reinterpret_cast<const T*>(&dk[q]);
+              const T* dvp = reinterpret_cast<const T*>(&dv[q]);
+#pragma unroll
+              for (int e = 0; e < EPL; ++e) {
+                const float kf = Elem<T>::load(dkp + e), vf = Elem<T>::load(dvp + e);
+                ka[e] = __builtin_fmaf(a[q], kf, ka[e]);
+                va[e] = __builtin_fmaf(a[q], vf, va[e]);
+                ku[e] = __builtin_fmaf(dcf, kf, ku[e]);
+                vu[e] = __builtin_fmaf(dcf, vf, vu[e]);
+              }
+              mass += a[q];
+              count += dc[q];
+            }
+          }
+        }
+        // (g0 + g1) + (g2 + g3): addition commutes, so every lane ends with the same bits
+#pragma unroll
+        for (int o = 16; o <= 32; o <<= 1) {
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            ka[e] += __shfl_xor(ka[e], o, 64);
+            va[e] += __shfl_xor(va[e], o, 64);
+            ku[e] += __shfl_xor(ku[e], o, 64);
+            vu[e] += __shfl_xor(vu[e], o, 64);
+          }
+          mass += __shfl_xor(mass, o, 64);
+          count += __shfl_xor(count, o, 64);
+        }
+        if (grp == 0) {
+          const bool uniform = mass == 0.f;  // no score mass: average over the original tokens
+          const float denom = uniform ? (float)count : mass;
+          Raw ok_, ov_;
+          T* okp = reinterpret_cast<T*>(&ok_);
+          T* ovp = reinterpret_cast<T*>(&ov_);
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            Elem<T>::store(okp + e, (uniform ? ku[e] : ka[e]) / denom);
+            Elem<T>::store(ovp + e, (uniform ? vu[e] : va[e]) / denom);
+          }
+          *reinterpret_cast<Raw*>(K_out + ((size_t)u * out_stride + slot) * D + gl * EPL) = ok_;
+          *reinterpret_cast<Raw*>(V_out + ((size_t)u * out_stride + slot) * D + gl * EPL) = ov_;
+          if (out_mass && gl == 0) out_mass[(size_t)u * B + slot] = mass;
+          if (out_count && gl == 0) out_count[(size_t)u * B + slot] = count;
+        }
+      }
+    }
+    return;
+  }
+
+  // ---- copy role
+  const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int waves_per_unit = (B + kSlotsPerWave - 1) / kSlotsPerWave;
   const int u = (int)(wave / waves_per_unit);
   const int t_base = (int)(wave % waves_per_unit) * kSlotsPerWave;
@@ -578,119 +782,61 @@ __global__ __launch_bounds__(256) void emit_kernel(
   if (t_base >= len) return;
   const int64_t row0 = row_off[u];
   const int nm = n_merged[u];
-  const int32_t* mr = merged_row + row0;
-  const int32_t* mo = merged_ord + row0;
+  const int32_t* sstart = seg_start + (size_t)u * (B + 1);
 
-  int slot[4], src[4], ord[4], c0[4];  // c0: original tokens the row stands for (1 unless counts are given)
-  float a0[4];
+  int slot[4], src[4], ord[4];
   Raw kraw[4], vraw[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     slot[j] = t_base + j * 4 + grp;
     const bool ok = slot[j] < len;
     src[j] = ok ? out_src[(size_t)u * B + slot[j]] : -1;
-    ord[j] = ok ? ord_of_slot[(size_t)u * B + slot[j]] : -1;
+    ord[j] = (ok && nm > 0) ? ord_of_slot[(size_t)u * B + slot[j]] : -1;
   }
+  // the row loads do not wait for the test below: a representative's row is loaded in vain
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     if (src[j] >= 0) {
       kraw[j] = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + src[j]) * D + gl * EPL);
       vraw[j] = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + src[j]) * D + gl * EPL);
-      a0[j] = scores[row0 + src[j]];
-      c0[j] = in_count ? in_count[row0 + src[j]] : 1;
-    } else {
-      a0[j] = 0.f;
-      c0[j] = 0;
     }
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    int members = 1, count = c0[j];
-    float mass = a0[j];
-    float ka[EPL], va[EPL], ku[EPL], vu[EPL];  // score-weighted and count-weighted sums
-    const T* kself = reinterpret_cast<const T*>(&kraw[j]);
-    const T* vself = reinterpret_cast<const T*>(&vraw[j]);
-    if (nm > 0 && __any(ord[j] >= 0)) {
-      for (int b0 = 0; b0 < nm; b0 += 16) {
-        const int idx = b0 + gl;
-        const int my_ord = idx < nm ? mo[idx] : -1;
-        const int my_row = idx < nm ? mr[idx] : 0;
-        const unsigned long long bal = __ballot(ord[j] >= 0 && my_ord == ord[j]);
-        unsigned hit = (unsigned)(bal >> (grp * 16)) & 0xFFFFu;
-        while (__any(hit != 0u)) {  // every group steps through its own matches, together
-          const bool have = hit != 0u;
-          const int l = have ? __ffs((int)hit) - 1 : 0;
-          hit &= hit - 1u;
-          const int drow = __shfl(my_row, grp * 16 + l, 64);
-          if (have) {
-            if (members == 1) {
+    if (ord[j] >= 0 && sstart[ord[j] + 1] > sstart[ord[j]]) src[j] = -1;  // a fold wave writes it
+  }
 #pragma unroll
-              for (int e = 0; e < EPL; ++e) {
-                const float kf = Elem<T>::load(kself + e), vf = Elem<T>::load(vself + e);
-                ka[e] = a0[j] * kf; va[e] = a0[j] * vf; ku[e] = (float)c0[j] * kf; vu[e] = (float)c0[j] * vf;
-              }
-            }
-            const float a = scores[row0 + drow];
-            const int dc = in_count ? in_count[row0 + drow] : 1;
-            const float dcf = (float)dc;
-            const Raw dk = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + drow) * D + gl * EPL);
-            const Raw dv = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + drow) * D + gl * EPL);
-            const T* dkp = reinterpret_cast<const T*>(&dk);
-            const T* dvp = reinterpret_cast<const T*>(&dv);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-              const float kf = Elem<T>::load(dkp + e), vf = Elem<T>::load(dvp + e);
-              ka[e] = __builtin_fmaf(a, kf, ka[e]);
-              va[e] = __builtin_fmaf(a, vf, va[e]);
-              ku[e] = __builtin_fmaf(dcf, kf, ku[e]);
-              vu[e] = __builtin_fmaf(dcf, vf, vu[e]);
-            }
-            mass += a;
-            count += dc;
-            ++members;
-          }
-        }
-      }
-    }
+  for (int j = 0; j < 4; ++j) {
     if (src[j] < 0) continue;
-    T* ko = K_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL;
-    T* vo = V_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL;
-    if (members == 1) {
-      *reinterpret_cast<Raw*>(ko) = kraw[j];
-      *reinterpret_cast<Raw*>(vo) = vraw[j];
-    } else {
-      const bool uniform = mass == 0.f;  // no score mass: average over the original tokens
-      const float denom = uniform ? (float)count : mass;
-      Raw ok_, ov_;
-      T* okp = reinterpret_cast<T*>(&ok_);
-      T* ovp = reinterpret_cast<T*>(&ov_);
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) {
-        Elem<T>::store(okp + e, (uniform ? ku[e] : ka[e]) / denom);
-        Elem<T>::store(ovp + e, (uniform ? vu[e] : va[e]) / denom);
-      }
-      *reinterpret_cast<Raw*>(ko) = ok_;
-      *reinterpret_cast<Raw*>(vo) = ov_;
-    }
-    if (out_mass && gl == 0) out_mass[(size_t)u * B + slot[j]] = mass;
-    if (out_count && gl == 0) out_count[(size_t)u * B + slot[j]] = count;
+    *reinterpret_cast<Raw*>(K_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL) = kraw[j];
+    *reinterpret_cast<Raw*>(V_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL) = vraw[j];
+    if (out_mass && gl == 0) out_mass[(size_t)u * B + slot[j]] = scores[row0 + src[j]];
+    if (out_count && gl == 0) out_count[(size_t)u * B + slot[j]] = in_count ? in_count[row0 + src[j]] : 1;
   }
 }
 
 template <typename T, int D>
 hipError_t launch_emit_t(const KParams& kp, const Batch& b, const float* scores,
                          const int32_t* out_src, const int32_t* out_len,
-                         const int32_t* ord_of_slot, const int32_t* merged_row,
-                         const int32_t* merged_ord, const int32_t* n_merged, void* K_out,
+                         const int32_t* ord_of_slot, const int32_t* seed_rows,
+                         const int32_t* n_seeds, const int32_t* slot_of, const int32_t* seg_row,
+                         const int32_t* seg_start, const int32_t* n_merged, void* K_out,
                          void* V_out, float* out_mass, const int32_t* in_count,
                          int32_t* out_count, int out_stride, hipStream_t st) {
-  const long long waves = (long long)b.n_units * ((kp.B + 15) / 16);
-  const long long blocks = (waves + 3) / 4;
-  if (blocks == 0) return hipSuccess;
-  emit_kernel<T, D><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(
-      kp, b.n_units, b.row_off, static_cast<const T*>(b.K), static_cast<const T*>(b.V), scores,
-      out_src, out_len, ord_of_slot, merged_row, merged_ord, n_merged, static_cast<T*>(K_out),
-      static_cast<T*>(V_out), out_mass, in_count, out_count, out_stride);
+  const long long copy_waves = (long long)b.n_units * ((kp.B + 15) / 16);
+  const long long copy_blocks = (copy_waves + 3) / 4;
+  // (unit, seed ordinal) work items; a fold wave tests 64 of them per round
+  const int fold_per_unit = plan_seed_bound(kp);
+  const long long items = (long long)b.n_units * fold_per_unit;
+  long long fold_blocks = (items + 3) / 4;     // an item per wave ...
+  if (fold_blocks > 2048) fold_blocks = 2048;  // ... up to 8192 waves
+  if (copy_blocks + fold_blocks == 0) return hipSuccess;
+  if (copy_blocks + fold_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  emit_kernel<T, D><<<dim3((unsigned)(copy_blocks + fold_blocks)), dim3(256), 0, st>>>(
+      kp, b.n_units, (int)copy_blocks, fold_per_unit, b.row_off, static_cast<const T*>(b.K),
+      static_cast<const T*>(b.V), scores, out_src, out_len, ord_of_slot, seed_rows, n_seeds, slot_of,
+      seg_row, seg_start, n_merged, static_cast<T*>(K_out), static_cast<T*>(V_out), out_mass,
+      in_count, out_count, out_stride);
   return hipGetLastError();
 }
 
@@ -732,9 +878,7 @@ hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* r
     const int tiles_per_wg = (tiles + chunks - 1) / chunks;
     chunks = (tiles + tiles_per_wg - 1) / tiles_per_wg;
     const int units8 = (b.n_units + 7) / 8 * 8;
-    // seeds of a unit = slots - core with slots <= B: at most B - core for an explicit core
-    // size, at most ceil(B / 5) for the default four-fifths core share
-    const int seed_bound = kp.core >= 0 ? (kp.B - kp.core > 0 ? kp.B - kp.core : 0) : (kp.B + 4) / 5;
+    const int seed_bound = plan_seed_bound(kp);
     // (a caller-supplied role array may name any number of seeds: general kernel then)
     if (roles_follow_plan && seed_bound <= kSeedBlock)
       similarity_mfma_kernel<true><<<dim3(units8 * chunks), dim3(256), 0, st>>>(
@@ -756,22 +900,26 @@ hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t
                                 const int32_t* assign_ord, const int32_t* slot_of,
                                 const int32_t* seed_rows, int32_t* merged_row, int32_t* merged_ord,
                                 int32_t* n_merged, int32_t* assign_out, int assign_mode,
-                                int32_t* status, hipStream_t st) {
+                                int32_t* status, const int32_t* n_seeds, int32_t* seg_row,
+                                int32_t* seg_start, hipStream_t st) {
+  static_assert((kGatherThreads / 64 & (kGatherThreads / 64 - 1)) == 0, "waves per block: a power of two");
   gather_merged_kernel<<<dim3(b.n_units), dim3(kGatherThreads), 0, st>>>(
       kp, b.row_off, b.prefix_len, role, assign_ord, slot_of, seed_rows, merged_row, merged_ord,
-      n_merged, assign_out, assign_mode, status);
+      n_merged, assign_out, assign_mode, status, n_seeds, seg_row, seg_start);
   return hipGetLastError();
 }
 
 hipError_t launch_emit(const KParams& kp, const Batch& b, const float* scores,
                        const int32_t* out_src, const int32_t* out_len, const int32_t* ord_of_slot,
-                       const int32_t* merged_row, const int32_t* merged_ord,
+                       const int32_t* seed_rows, const int32_t* n_seeds, const int32_t* slot_of,
+                       const int32_t* seg_row, const int32_t* seg_start,
                        const int32_t* n_merged, void* K_out, void* V_out, float* out_mass,
                        const int32_t* in_count, int32_t* out_count, int out_stride,
                        hipStream_t st) {
 #define CASK_EMIT(T, D)                                                                          \
-  launch_emit_t<T, D>(kp, b, scores, out_src, out_len, ord_of_slot, merged_row, merged_ord,      \
-                      n_merged, K_out, V_out, out_mass, in_count, out_count, out_stride, st)
+  launch_emit_t<T, D>(kp, b, scores, out_src, out_len, ord_of_slot, seed_rows, n_seeds, slot_of, \
+                      seg_row, seg_start, n_merged, K_out, V_out, out_mass, in_count, out_count, \
+                      out_stride, st)
   if (kp.dtype == CASK_F32) return kp.d == 64 ? CASK_EMIT(float, 64) : CASK_EMIT(float, 128);
   return kp.d == 64 ? CASK_EMIT(uint16_t, 64) : CASK_EMIT(uint16_t, 128);
 #undef CASK_EMIT

@@ -187,6 +187,7 @@ def full_check(c: dict, p: cask.Params, expect_folds: bool = False, n_threads: i
     if n_bad == 0:
         assert np.array_equal(got["status"], want["status"])
     stats["folded_rows"] = check_values(p, got, want, K2, V2, row_off)
+    stats["folded_donors"] = int(np.count_nonzero((want["role"] == ref.DONOR) & (want["assign"] >= 0)))
     if expect_folds:
         assert stats["folded_rows"] > 0
 

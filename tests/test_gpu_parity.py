@@ -147,6 +147,37 @@ def test_many_seeds_take_several_lds_blocks():
     _note(st)
 
 
+@pytest.mark.parametrize("case", ["bf16_cosine", "f32_kappa"])
+def test_every_donor_folds(case):
+    """A threshold that every pair passes: each seed folds a long run of donors (hundreds), so
+    the grouped donor list and the segment fold carry the whole decode trace."""
+    if case == "bf16_cosine":
+        w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=3, prefix=60, decode=5000, budget=384)
+        p = parity.params_of(w, sim_threshold=-1.0)
+    else:
+        w = caches.scaled(W["cfg1"], decode=1500, budget=200, core=40)
+        band = torch.rand(w.head_dim // 2, generator=torch.Generator().manual_seed(2)).to("cuda:0")
+        p = parity.params_of(w, merge_geometry=1, band_weight=band, dist_threshold=1e30)
+    c = caches.make(w, seed=41)
+    st = parity.full_check(c, p, expect_folds=True)
+    assert st["folded_donors"] > 0.8 * w.decode * w.n_kv_heads
+    _note((case, st))
+
+
+def test_more_seeds_than_one_cursor_pass():
+    """More than 8192 seeds in a unit: the stable split of the donor list by seed takes two
+    passes over the ordinals."""
+    w = caches.scaled(W["cfg1"], n_seqs=1, n_layers=1, n_kv_heads=1, prefix=40, decode=15000, budget=9400,
+                      cluster_frac=0.6)
+    c = caches.make(w, seed=43)
+    p = parity.params_of(w, core=300, sim_threshold=0.1)
+    pl = cask.plan(p, 40, 15040)
+    assert pl["seeds"] > 8192 + 256
+    st = parity.full_check(c, p, expect_folds=True)
+    assert st["folded_donors"] > 300
+    _note(st)
+
+
 def test_consolidate_with_caller_roles_naming_many_seeds():
     """cask_consolidate takes any role array: here far more seeds than the plan would ever
     produce, so the seeds of a unit do not fit one LDS block."""
