@@ -605,3 +605,42 @@ int cask_ref_mass_diagnostics(const cask_ref_params* p, int32_t n_units, const i
   return 0;
 }
 
+int cask_ref_group_diagnostics(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                               const void* K, const float* scores, const int32_t* assign,
+                               const void* K_out, int32_t out_stride_rows, float* dispersion,
+                               float* lost_mass) {
+  if (!p || !row_off || !K || !scores || !assign || !K_out || !dispersion || !lost_mass || n_units < 0)
+    return -1;
+  if (check_shape(p) != 0 || out_stride_rows < p->budget) return -1;
+  const int d = p->head_dim;
+  if (p->band_weight)
+    for (int f = 0; f < d / 2; ++f)
+      if (!(p->band_weight[f] >= 0.0f)) return -1;
+  for (int32_t u = 0; u < n_units; ++u) {
+    const int64_t row0 = row_off[u];
+    const int32_t N = (int32_t)(row_off[u + 1] - row0);
+    double disp = 0.0, lost = 0.0;
+    for (int32_t i = 0; i < N; ++i) {
+      const double a = (double)scores[row0 + i];
+      const int32_t t = assign[row0 + i];
+      if (t < 0) {
+        lost += a;
+        continue;
+      }
+      if (t >= p->budget) return -1;
+      const int64_t rep = ((int64_t)u * out_stride_rows + t) * d;
+      double norm = 0.0;
+      for (int f = 0; f < d / 2; ++f) {
+        const double x = load_elem(K, p->dtype, (row0 + i) * d + f) - load_elem(K_out, p->dtype, rep + f);
+        const double y = load_elem(K, p->dtype, (row0 + i) * d + f + d / 2) -
+                         load_elem(K_out, p->dtype, rep + f + d / 2);
+        const double w = p->band_weight ? (double)p->band_weight[f] : 1.0;
+        norm += w * sqrt(x * x + y * y);
+      }
+      disp += a * norm;
+    }
+    dispersion[u] = (float)disp;
+    lost_mass[u] = (float)lost;
+  }
+  return 0;
+}

@@ -155,6 +155,24 @@ int cask_ref_mass_diagnostics(const cask_ref_params* p, int32_t n_units, const i
                               const float* scores, const uint8_t* role, const float* out_mass,
                               const int32_t* out_len, float* rho);
 
+/* Perturbation diagnostics of a finished event (Section 2.6, Appendix B): the bound on a
+ * representative's error splits into within-group kappa-dispersion and lost mass.
+ * Readings taken here:
+ *   - the weights a_i are the event's scores, not renormalised inside a group;
+ *   - ||x||_kappa is the band norm of Section 2.5, sum_f w_f * ||x_f||_2 over the rotary bands
+ *     (channels f and f + d/2), w = p->band_weight, all ones when that is NULL;
+ *   - k~_G is the representative as stored: row assign[i] of K_out (cache dtype);
+ *   - dispersion[u] = sum over rows with assign[i] >= 0 of s_i * ||k_i - k~||_kappa (rows
+ *     kept verbatim add exact zeros);
+ *   - a fold hands its group's whole mass to the representative, so the mass that is lost is
+ *     that of the rows that leave without one: lost_mass[u] = sum of s_i over assign[i] < 0.
+ * assign as written by cask_ref_compress(_step); K_out rows of unit u start at row
+ * u * out_stride_rows. */
+int cask_ref_group_diagnostics(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                               const void* K, const float* scores, const int32_t* assign,
+                               const void* K_out, int32_t out_stride_rows, float* dispersion,
+                               float* lost_mass);
+
 #ifdef __cplusplus
 }
 #endif

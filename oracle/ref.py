@@ -287,3 +287,24 @@ def mass_diagnostics(p: Params, row_off, scores, role, out_mass, out_len) -> np.
         raise ValueError(f"cask_ref_mass_diagnostics: {rc}")
     return rho
 
+
+def group_diagnostics(p: Params, row_off, K, scores, assign, K_out):
+    """(dispersion, lost_mass) per unit: within-group kappa-dispersion and lost mass of a finished
+    event (Section 2.6, Appendix B).  K_out [n_units, stride, d] with stride >= budget."""
+    row_off = np.ascontiguousarray(row_off, dtype=np.int64)
+    n_units = len(row_off) - 1
+    K = np.ascontiguousarray(K)
+    K_out = np.ascontiguousarray(K_out)
+    scores = np.ascontiguousarray(scores, dtype=np.float32)
+    assign = np.ascontiguousarray(assign, dtype=np.int32)
+    assert K.dtype == K_out.dtype and K_out.ndim == 3 and K_out.shape[0] == n_units
+    assert K_out.shape[2] == p.head_dim and scores.size == assign.size == int(row_off[-1])
+    disp = np.zeros(n_units, dtype=np.float32)
+    lost = np.zeros(n_units, dtype=np.float32)
+    cp = p.c()
+    rc = lib().cask_ref_group_diagnostics(C.byref(cp), C.c_int32(n_units), _ptr(row_off), _ptr(K),
+                                          _ptr(scores), _ptr(assign), _ptr(K_out),
+                                          C.c_int32(K_out.shape[1]), _ptr(disp), _ptr(lost))
+    if rc:
+        raise ValueError(f"cask_ref_group_diagnostics: {rc}")
+    return disp, lost

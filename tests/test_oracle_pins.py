@@ -843,3 +843,80 @@ def test_kappa_geometry_end_to_end_folds_planted_duplicates(oracle):
         seed = src[a[i]]
         ci = [c for c in range(pos.shape[0]) if i in pos[c]]
         assert ci and seed in pos[ci[0]]
+
+
+# ------------------------------------------------------------------ dispersion and lost mass (Section 2.6, Appendix B)
+
+def test_group_diagnostics_closed_forms(oracle):
+    """Hand-built event: one group of two keys a 3-4-5 triangle apart inside one band, one kept
+    row, one dropped row.  Equal scores put the representative at the midpoint, so each member
+    is 2.5 w_f away; the dropped row's score is the lost mass."""
+    d = 8
+    K = np.zeros((5, d), dtype=np.float32)
+    f = 1
+    K[1, f], K[1, f + d // 2] = 3.0, 4.0                  # rows 0 and 1: one band apart by 5
+    K[2, 0] = 7.0
+    K[3, 2] = 1.0
+    s = np.array([0.25, 0.25, 0.125, 0.0625, 0.5], dtype=np.float32)
+    assign = np.array([0, 0, 1, -1, 2], dtype=np.int32)
+    K_out = np.zeros((1, 4, d), dtype=np.float32)         # stride 4 > budget 3
+    K_out[0, 0] = 0.5 * (K[0] + K[1])
+    K_out[0, 1] = K[2]
+    K_out[0, 2] = K[4]
+    w = np.array([1.0, 0.5, 2.0, 1.0], dtype=np.float32)
+    p = oracle.Params(dtype=oracle.F32, head_dim=d, q_per_kv=1, window=1, recent=1, budget=3,
+                      band_weight=w)
+    disp, lost = oracle.group_diagnostics(p, np.array([0, 5]), K, s, assign, K_out)
+    assert disp[0] == np.float32(2 * 0.25 * 2.5 * 0.5) and lost[0] == np.float32(0.0625)
+    p.band_weight = None                                  # unit weights
+    disp, lost = oracle.group_diagnostics(p, np.array([0, 5]), K, s, assign, K_out)
+    assert disp[0] == np.float32(2 * 0.25 * 2.5) and lost[0] == np.float32(0.0625)
+    # unequal scores 3 : 1 -> the representative sits a quarter of the way: distances 1.25, 3.75
+    K_out[0, 0] = 0.75 * K[0] + 0.25 * K[1]
+    s2 = s.copy()
+    s2[0], s2[1] = 0.75, 0.25
+    disp, _ = oracle.group_diagnostics(p, np.array([0, 5]), K, s2, assign, K_out)
+    assert disp[0] == np.float32(0.75 * 1.25 + 0.25 * 3.75)
+    with pytest.raises(ValueError):
+        oracle.group_diagnostics(p, np.array([0, 5]), K, s, np.array([0, 0, 1, -1, 3], dtype=np.int32), K_out)
+
+
+def test_group_diagnostics_on_events_against_library_norms(oracle):
+    """On whole events: numpy's own norm over the bands; mass bookkeeping (what the output
+    carries plus what is lost is everything there was); no folds => no dispersion; identity =>
+    nothing at all; both outputs scale with the scores, the dispersion with the weights."""
+    rng = np.random.default_rng(61)
+    for tau, dtype in ((0.5, "f32"), (-1.0, "f32"), (0.5, "bf16"), (2.0, "f32")):
+        p, K, V, Q, ro, pl, _ = make_case(rng, oracle, P=30, D=300, d=16, B=90, tau=tau)
+        if dtype == "bf16":
+            p.dtype = oracle.BF16
+            K, V, Q = to_bf16_bits(K), to_bf16_bits(V), to_bf16_bits(Q)
+        out = oracle.compress(p, ro, pl, K, V, Q)
+        w = rng.random(p.head_dim // 2).astype(np.float32)
+        p.band_weight = w
+        disp, lost = oracle.group_diagnostics(p, ro, K, out["scores"], out["assign"], out["K_out"])
+        Kf = from_bf16_bits(K) if dtype == "bf16" else K
+        Ko = from_bf16_bits(out["K_out"]) if dtype == "bf16" else out["K_out"]
+        a, s = out["assign"], out["scores"].astype(np.float64)
+        kept = a >= 0
+        diff = (Kf[kept].astype(np.float64) - Ko[0, a[kept]].astype(np.float64)).reshape(-1, 2, p.head_dim // 2)
+        norms = np.linalg.norm(diff, axis=1) @ w.astype(np.float64)
+        assert disp[0] == pytest.approx(float((s[kept] * norms).sum()), rel=1e-6)
+        L = int(out["out_len"][0])
+        assert float(out["out_mass"][0, :L].astype(np.float64).sum()) + float(lost[0]) == \
+            pytest.approx(float(s.sum()), rel=1e-6)
+        folded = np.count_nonzero((out["role"] == oracle.DONOR) & kept)
+        if tau > 1.0:
+            assert folded == 0 and disp[0] == 0.0          # verbatim copies are exact zeros
+        else:
+            assert folded > 0 and disp[0] > 0.0
+        d2, l2 = oracle.group_diagnostics(p, ro, K, 2 * out["scores"], a, out["K_out"])
+        assert d2[0] == 2 * disp[0] and l2[0] == 2 * lost[0]
+        p.band_weight = 4 * w
+        d4, l4 = oracle.group_diagnostics(p, ro, K, out["scores"], a, out["K_out"])
+        assert d4[0] == 4 * disp[0] and l4[0] == lost[0]
+    # identity event: every row kept as it is
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, P=10, D=40, d=16, B=64)
+    out = oracle.compress(p, ro, pl, K, V, Q)
+    disp, lost = oracle.group_diagnostics(p, ro, K, out["scores"], out["assign"], out["K_out"])
+    assert disp[0] == 0.0 and lost[0] == 0.0
