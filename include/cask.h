@@ -201,6 +201,26 @@ int cask_mass_diagnostics(const cask_params* params, const cask_batch* batch, co
                           const uint8_t* role, const float* out_mass, const int32_t* out_len,
                           float* rho, void* hip_stream);
 
+/* Perturbation diagnostics of a finished event (Section 2.6, Appendix B: a representative's
+ * error is bounded by within-group kappa-dispersion plus lost mass), optional, after
+ * cask_compress or cask_compress_step:
+ *   dispersion[u] = sum over the unit's rows with assign[i] >= 0 of
+ *                   scores[i] * || K[i] - K_out[u, assign[i]] ||_kappa
+ *   lost_mass[u]  = sum of scores[i] over the rows with assign[i] < 0
+ * where ||x||_kappa = sum over rotary bands f (channels f and f + d/2) of w_f * ||x_f||_2 with
+ * w = params->band_weight (device, float [d/2], not validated), all ones when that is NULL;
+ * the scores are used as they are (not renormalised inside a group); the representative is
+ * the row as stored in K_out (cache dtype), so rows kept verbatim add exact zeros; a fold
+ * hands its group's whole mass to the representative, so what is lost is the mass of the rows
+ * that leave without one.
+ * Reads K, scores [total_rows], assign [total_rows] (output slot or -1, as written by
+ * cask_compress; a value >= B is skipped), K_out [n_units, out_stride_rows, d] (device,
+ * 16-byte aligned, out_stride_rows >= B); writes dispersion, lost_mass [n_units] float.
+ * Needs no workspace. */
+int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, const float* scores,
+                           const int32_t* assign, const void* K_out, int32_t out_stride_rows,
+                           float* dispersion, float* lost_mass, void* hip_stream);
+
 /* Measurement aid (not part of the method): per-stage timing of cask_compress with HIP
  * events recorded on the caller's stream between its kernels.  Stage order: 0 score sweep A
  * (row statistics), 1 score sweep B (column mass), 2 select (with the ordered walk over the

@@ -26,7 +26,7 @@ ST_ACTIVE, ST_IDENTITY, ST_PREFIX_BUDGET_EXHAUSTED, ST_MERGE_INACTIVE = 0, 1, 2,
 
 EXPORTS = ["cask_plan", "cask_workspace_bytes", "cask_score", "cask_prefix_evict",
            "cask_partition", "cask_consolidate", "cask_compress", "cask_compress_step",
-           "cask_mass_diagnostics", "cask_strerror",
+           "cask_mass_diagnostics", "cask_group_diagnostics", "cask_strerror",
            "cask_timing_enable", "cask_timing_enable_stages", "cask_timing_read"]
 STAGES = ["score_rows", "score_cols", "select", "index_roles", "similarity", "gather", "emit"]
 
@@ -284,6 +284,21 @@ def mass_diagnostics(b: Batch, scores: torch.Tensor, role: torch.Tensor, out_mas
     if rc:
         raise CaskError("cask_mass_diagnostics", rc)
     return rho
+
+
+def group_diagnostics(b: Batch, scores: torch.Tensor, assign: torch.Tensor, K_out: torch.Tensor):
+    """(dispersion, lost_mass), each [n_units] float (cask_group_diagnostics).  K_out
+    [n_units, stride, d] in the cache dtype, stride >= budget."""
+    assert K_out.is_contiguous() and K_out.dim() == 3 and K_out.shape[0] == b.n_units
+    disp = torch.zeros(b.n_units, dtype=torch.float32, device=b.device)
+    lost = torch.zeros(b.n_units, dtype=torch.float32, device=b.device)
+    cp, cb = b.params.c(), b.c()
+    rc = load().cask_group_diagnostics(C.byref(cp), C.byref(cb), _dptr(scores), _dptr(assign),
+                                       _dptr(K_out), C.c_int32(K_out.shape[1]), _dptr(disp),
+                                       _dptr(lost), _stream())
+    if rc:
+        raise CaskError("cask_group_diagnostics", rc)
+    return disp, lost
 
 
 class Outputs:

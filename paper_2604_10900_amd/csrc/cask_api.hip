@@ -299,6 +299,23 @@ int cask_mass_diagnostics(const cask_params* params, const cask_batch* batch, co
                                  static_cast<hipStream_t>(hip_stream)));
 }
 
+int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, const float* scores,
+                           const int32_t* assign, const void* K_out, int32_t out_stride_rows,
+                           float* dispersion, float* lost_mass, void* hip_stream) {
+  KParams kp;
+  Batch b;
+  int rc = resolve_params(params, &kp, true);
+  if (rc) return rc;
+  rc = resolve_batch(kp, batch, &b, false, false);
+  if (rc) return rc;
+  if (b.n_units == 0) return CASK_OK;
+  if (!scores || !assign || !K_out || !dispersion || !lost_mass) return CASK_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(K_out) & 15u) != 0 || out_stride_rows < kp.B) return CASK_EINVAL;
+  kp.band_w = params->band_weight;  // used here whatever the merge geometry
+  return dev_rc(launch_group_diag(kp, b, scores, assign, K_out, out_stride_rows, dispersion,
+                                  lost_mass, static_cast<hipStream_t>(hip_stream)));
+}
+
 int cask_compress(const cask_params* params, const cask_batch* batch, void* K_out, void* V_out,
                   int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
                   float* scores, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream) {

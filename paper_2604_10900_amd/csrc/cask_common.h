@@ -206,6 +206,9 @@ hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t
                                 int32_t* n_merged, int32_t* assign_out, int assign_mode,
                                 int32_t* status, const int32_t* n_seeds, int32_t* seg_row,
                                 int32_t* seg_start, hipStream_t st);
+hipError_t launch_group_diag(const KParams& kp, const Batch& b, const float* scores,
+                             const int32_t* assign, const void* K_out, int out_stride,
+                             float* dispersion, float* lost_mass, hipStream_t st);
 hipError_t launch_emit(const KParams& kp, const Batch& b, const float* scores,
                        const int32_t* out_src, const int32_t* out_len, const int32_t* ord_of_slot,
                        const int32_t* seed_rows, const int32_t* n_seeds, const int32_t* slot_of,

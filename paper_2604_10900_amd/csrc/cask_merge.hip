@@ -840,6 +840,70 @@ hipError_t launch_emit_t(const KParams& kp, const Batch& b, const float* scores,
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ dispersion and lost mass
+
+// Perturbation diagnostics of a finished event (Section 2.6, Appendix B).  One workgroup per
+// unit; sixteen lanes per row (lanes 0-7 hold the first half of the channels, lanes 8-15 the
+// second, so a band's two channels sit eight lanes apart).  A group walks rows g, g + 64, ...
+// and keeps its sums in double; the 64 group sums are added in order by one thread.
+template <typename T, int D>
+__global__ __launch_bounds__(1024) void group_diag_kernel(
+    KParams kp, const int64_t* __restrict__ row_off, const T* __restrict__ K,
+    const float* __restrict__ scores, const int32_t* __restrict__ assign,
+    const T* __restrict__ K_out, int out_stride, float* __restrict__ dispersion,
+    float* __restrict__ lost_mass) {
+  constexpr int EPL = D / 16;
+  constexpr int WORDS = EPL * sizeof(T) / 4;
+  struct alignas(WORDS * 4 > 16 ? 16 : WORDS * 4) Raw { uint32_t w[WORDS]; };
+  __shared__ double part_d[64], part_l[64];
+  const int u = blockIdx.x, tid = threadIdx.x, grp = tid >> 4, gl = tid & 15;
+  const int64_t row0 = row_off[u];
+  const int N = (int)(row_off[u + 1] - row0);
+  float w[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) w[e] = kp.band_w ? kp.band_w[(gl & 7) * EPL + e] : 1.f;
+  double disp = 0.0, lost = 0.0;
+  for (int i = grp; i < N; i += 64) {  // the same row in all sixteen lanes of a group
+    const int t = assign[row0 + i];
+    const float a = scores[row0 + i];
+    if (t < 0) {
+      lost += (double)a;
+      continue;
+    }
+    if (t >= kp.B) continue;
+    const Raw kr = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + i) * D + gl * EPL);
+    const Raw rr = *reinterpret_cast<const Raw*>(K_out + ((size_t)u * out_stride + t) * D + gl * EPL);
+    const T* kp_ = reinterpret_cast<const T*>(&kr);
+    const T* rp_ = reinterpret_cast<const T*>(&rr);
+    float r = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      const float x = Elem<T>::load(kp_ + e) - Elem<T>::load(rp_ + e);
+      const float sq = x * x;
+      const float other = __shfl_xor(sq, 8, 64);  // the band's other channel
+      r = __builtin_fmaf(w[e], __builtin_amdgcn_sqrtf(sq + other), r);
+    }
+    if (gl >= 8) r = 0.f;  // both halves computed the same bands
+#pragma unroll
+    for (int o = 4; o > 0; o >>= 1) r += __shfl_xor(r, o, 64);
+    disp += (double)a * (double)r;
+  }
+  if (gl == 0) {
+    part_d[grp] = disp;
+    part_l[grp] = lost;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    double sd = 0.0, sl = 0.0;
+    for (int g = 0; g < 64; ++g) {
+      sd += part_d[g];
+      sl += part_l[g];
+    }
+    dispersion[u] = (float)sd;
+    lost_mass[u] = (float)sl;
+  }
+}
+
 template <typename T, int D>
 hipError_t launch_similarity_fma(const KParams& kp, const Batch& b, const uint8_t* role,
                                  const int32_t* seed_rows, const int32_t* n_seeds,
@@ -906,6 +970,22 @@ hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t
   gather_merged_kernel<<<dim3(b.n_units), dim3(kGatherThreads), 0, st>>>(
       kp, b.row_off, b.prefix_len, role, assign_ord, slot_of, seed_rows, merged_row, merged_ord,
       n_merged, assign_out, assign_mode, status, n_seeds, seg_row, seg_start);
+  return hipGetLastError();
+}
+
+hipError_t launch_group_diag(const KParams& kp, const Batch& b, const float* scores,
+                             const int32_t* assign, const void* K_out, int out_stride,
+                             float* dispersion, float* lost_mass, hipStream_t st) {
+#define CASK_GD(T, D)                                                                     \
+  group_diag_kernel<T, D><<<dim3(b.n_units), dim3(1024), 0, st>>>(                        \
+      kp, b.row_off, static_cast<const T*>(b.K), scores, assign, static_cast<const T*>(K_out), \
+      out_stride, dispersion, lost_mass)
+  if (kp.dtype == CASK_F32) {
+    if (kp.d == 64) CASK_GD(float, 64); else CASK_GD(float, 128);
+  } else {
+    if (kp.d == 64) CASK_GD(uint16_t, 64); else CASK_GD(uint16_t, 128);
+  }
+#undef CASK_GD
   return hipGetLastError();
 }
 

@@ -199,6 +199,20 @@ def full_check(c: dict, p: cask.Params, expect_folds: bool = False, n_threads: i
         np.testing.assert_allclose(rho.cpu().numpy(), want_rho, rtol=2e-6, atol=0)
         stats["rho_rep_min"] = float(want_rho[:, 1].min())
 
+    # ---- dispersion and lost mass (Section 2.6, Appendix B): the oracle's own event as input
+    n_u = len(row_off) - 1
+    ko_bits = want["K_out"]
+    ko = torch.from_numpy(ko_bits.view(np.int16) if ko_bits.dtype == np.uint16 else ko_bits).to(dev)
+    if p.dtype == cask.BF16:
+        ko = ko.view(torch.bfloat16)
+    a_in = torch.from_numpy(want["assign"]).to(dev)
+    disp, lost = cask.binding.group_diagnostics(b, s_inj, a_in, ko)
+    torch.cuda.synchronize()
+    want_disp, want_lost = ref.group_diagnostics(rp, row_off, K, want["scores"], want["assign"], want["K_out"])
+    np.testing.assert_allclose(disp.cpu().numpy(), want_disp, rtol=1e-5, atol=1e-30)
+    np.testing.assert_allclose(lost.cpu().numpy(), want_lost, rtol=2e-6, atol=0)
+    stats["dispersion_max"] = float(want_disp.max())
+
     # ---- end to end with the library's own scores
     out_e = cask.compress(b)
     torch.cuda.synchronize()

@@ -186,3 +186,28 @@ def test_merge_geometry_fields_validate_on_the_host(cask):
     assert rc(merge_geometry=1, band_weight=256, dist_threshold=-1.0) == cask.binding.EINVAL
     assert rc(merge_geometry=1, band_weight=256, dist_threshold=float("nan")) == cask.binding.EINVAL
     assert rc(merge_geometry=1, band_weight=256, dist_threshold=3.0) == cask.binding.OK   # empty batch: no-op
+
+
+def test_group_diagnostics_validates_on_the_host(cask):
+    lib = cask.load()
+    ok = cask.Params().c()
+    ro = np.array([0, 1000], dtype=np.int64)
+    pl = np.array([0], dtype=np.int32)
+    fake = C.c_void_p(256)
+    good = cask.binding._Batch(1, fake, fake, ro.ctypes.data, pl.ctypes.data, fake, fake, fake)
+    B = cask.Params().budget
+
+    def rc(scores=fake, assign=fake, K_out=fake, stride=B, disp=fake, lost=fake):
+        return lib.cask_group_diagnostics(C.byref(ok), C.byref(good), scores, assign, K_out,
+                                          C.c_int32(stride), disp, lost, None)
+
+    assert rc(scores=None) == cask.binding.EINVAL
+    assert rc(assign=None) == cask.binding.EINVAL
+    assert rc(K_out=None) == cask.binding.EINVAL
+    assert rc(K_out=C.c_void_p(264)) == cask.binding.EINVAL          # not 16-byte aligned
+    assert rc(stride=B - 1) == cask.binding.EINVAL
+    assert rc(disp=None) == cask.binding.EINVAL
+    assert rc(lost=None) == cask.binding.EINVAL
+    empty = cask.binding._Batch(0, None, None, None, None, None, None, None)
+    assert lib.cask_group_diagnostics(C.byref(ok), C.byref(empty), None, None, None, C.c_int32(B), None,
+                                      None, None) == cask.binding.OK

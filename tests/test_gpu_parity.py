@@ -178,6 +178,51 @@ def test_more_seeds_than_one_cursor_pass():
     _note(st)
 
 
+def test_group_diagnostics_with_row_stride_and_arbitrary_assignments():
+    """cask_group_diagnostics takes any assignment and any K_out with a row stride: random
+    slots, a third of the rows dropped, out-of-range slots skipped; fp32 and bf16, d 64 / 128."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(71)
+    for name, kw in (("cfg1", dict(decode=700)), ("cfg1", dict(head_dim=128, q_per_kv=2, decode=300)),
+                     ("cfg2", dict(n_layers=1, n_kv_heads=3, prefix=40, decode=1100, budget=256)),
+                     ("cfg2", dict(head_dim=64, n_layers=1, n_kv_heads=2, q_per_kv=2, prefix=30, decode=500,
+                                   window=32, budget=128))):
+        w = caches.scaled(W[name], **kw)
+        c = caches.make(w, seed=9)
+        band = torch.rand(w.head_dim // 2, generator=torch.Generator().manual_seed(3))
+        p = parity.params_of(w, band_weight=band.to(dev))
+        rp = parity.ref_params(p)
+        row_off, prefix_len, K, V, Q = parity.host_arrays(c)
+        n_units, total, B = len(row_off) - 1, int(row_off[-1]), p.budget
+        stride = B + 37
+        assign = rng.integers(0, B, total).astype(np.int32)
+        assign[rng.random(total) < 0.33] = -1
+        scores = (rng.random(total) ** 4).astype(np.float32)
+        K_out = np.ascontiguousarray(K[rng.integers(0, total, n_units * stride)].reshape(n_units, stride, -1))
+        want_d, want_l = ref.group_diagnostics(rp, row_off, K, scores, assign, K_out)
+        b = parity.to_device(c, p)
+        ko = torch.from_numpy(K_out.view(np.int16) if K_out.dtype == np.uint16 else K_out).to(dev)
+        if p.dtype == cask.BF16:
+            ko = ko.view(torch.bfloat16)
+        skipped = assign.copy()
+        skipped[::17] = B + 5                             # beyond the budget: skipped, no fault
+        for a_in, wd, wl in ((assign, want_d, want_l),):
+            d, l = cask.binding.group_diagnostics(b, torch.from_numpy(scores).to(dev),
+                                                  torch.from_numpy(a_in).to(dev), ko)
+            torch.cuda.synchronize()
+            np.testing.assert_allclose(d.cpu().numpy(), wd, rtol=1e-5)
+            np.testing.assert_allclose(l.cpu().numpy(), wl, rtol=2e-6)
+        keep = skipped < B
+        masked = np.where(keep, skipped, -1)
+        wd2, wl2 = ref.group_diagnostics(rp, row_off, K, np.where(keep, scores, 0).astype(np.float32), masked, K_out)
+        d, l = cask.binding.group_diagnostics(b, torch.from_numpy(scores).to(dev),
+                                              torch.from_numpy(skipped).to(dev), ko)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(d.cpu().numpy(), wd2, rtol=1e-5)
+        np.testing.assert_allclose(l.cpu().numpy(), wl2, rtol=2e-6)     # a skipped row is not "lost" either
+        _note((name, kw, float(want_d.max()), float(want_l.max())))
+
+
 def test_consolidate_with_caller_roles_naming_many_seeds():
     """cask_consolidate takes any role array: here far more seeds than the plan would ever
     produce, so the seeds of a unit do not fit one LDS block."""
