@@ -148,7 +148,10 @@ int cask_consolidate(const cask_params* params, const cask_batch* batch, const f
                      const uint8_t* role, int32_t* assign, void* ws, size_t ws_bytes,
                      void* hip_stream);
 
-/* The whole event (Sections 2.1-2.4).
+/* The whole event (Sections 2.1-2.4).  (A batch whose units all have at most 1024 rows, with
+ * B <= 1024, bf16 and the cosine geometry, takes a one-launch path after scoring; results and
+ * tie rules are the same.  The environment variable CASK_FUSED_TAIL=0, read at every call,
+ * switches that path off.)
  *   K_out, V_out [n_units, B, d]  rows [0, out_len[u]) in ascending source order; a
  *                                 representative sits at its seed's position; kept tokens
  *                                 are bit-identical copies; rows >= out_len[u] untouched
@@ -225,7 +228,9 @@ int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, c
  * events recorded on the caller's stream between its kernels.  Stage order: 0 score sweep A
  * (row statistics), 1 score sweep B (column mass), 2 select (with the ordered walk over the
  * roles, which cask_compress runs in the same kernel), 3 index roles (zero in cask_compress),
- * 4 similarity, 5 gather merged donors, 6 emit.
+ * 4 similarity, 5 gather merged donors, 6 emit.  A batch of short units (every unit at most
+ * 1024 rows, B <= 1024, bf16, cosine geometry) runs stages 2-6 as one kernel: its time is
+ * reported as stage 2 and stages 3-6 read as the cost of an empty event pair.
  * cask_timing_enable(n > 0) creates events for the next n compress calls (n <= 4096) and
  * switches recording on; n <= 0 switches it off and destroys them.  Calls beyond n are not
  * recorded.  cask_timing_read waits for the recorded calls, writes the summed milliseconds

@@ -299,6 +299,13 @@ int cask_mass_diagnostics(const cask_params* params, const cask_batch* batch, co
                                  static_cast<hipStream_t>(hip_stream)));
 }
 
+// CASK_FUSED_TAIL=0 sends short units through the general kernels as well (read at every call:
+// tests and measurements compare the two paths inside one process)
+static bool fused_tail_disabled() {
+  const char* e = std::getenv("CASK_FUSED_TAIL");
+  return e && e[0] == '0';
+}
+
 int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, const float* scores,
                            const int32_t* assign, const void* K_out, int32_t out_stride_rows,
                            float* dispersion, float* lost_mass, void* hip_stream) {
@@ -369,6 +376,13 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
     rec.mark();
   }
   rec.mark();  // end of sweep B
+  if (tail_small_fits(kp, b) && !fused_tail_disabled()) {
+    // short units: the rest of the event is one launch (reported as the select stage)
+    e = launch_tail_small(kp, b, s, in_count, K_out, V_out, out_stride_rows, out_len, out_src,
+                          out_mass, out_count, assign, status, st);
+    for (int k = 0; k < 5; ++k) rec.mark();
+    return dev_rc(e);
+  }
   e = launch_select_index(kp, b, s, role, status, slot_of, out_src, out_len, seed_rows, ord_of_slot,
                           n_seeds, st);
   if (e != hipSuccess) return CASK_EDEVICE;

@@ -206,6 +206,14 @@ hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t
                                 int32_t* n_merged, int32_t* assign_out, int assign_mode,
                                 int32_t* status, const int32_t* n_seeds, int32_t* seg_row,
                                 int32_t* seg_start, hipStream_t st);
+// Everything after scoring in one launch, for batches whose units all fit a workgroup (a row per
+// thread), bf16, cosine geometry; `tail_small_fits` says whether a batch qualifies.
+bool tail_small_fits(const KParams& kp, const Batch& b);
+hipError_t launch_tail_small(const KParams& kp, const Batch& b, const float* scores,
+                             const int32_t* in_count, void* K_out, void* V_out, int out_stride,
+                             int32_t* out_len, int32_t* out_src, float* out_mass,
+                             int32_t* out_count, int32_t* assign, int32_t* status,
+                             hipStream_t st);
 hipError_t launch_group_diag(const KParams& kp, const Batch& b, const float* scores,
                              const int32_t* assign, const void* K_out, int out_stride,
                              float* dispersion, float* lost_mass, hipStream_t st);

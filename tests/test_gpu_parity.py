@@ -223,6 +223,39 @@ def test_group_diagnostics_with_row_stride_and_arbitrary_assignments():
         _note((name, kw, float(want_d.max()), float(want_l.max())))
 
 
+SHORT_CASES = {
+    # name: (workload overrides, parameter overrides, expect_folds)
+    "steady_state": (dict(n_layers=1, n_kv_heads=4, prefix=96, decode=416, budget=384), dict(sim_threshold=0.5), True),
+    "ragged_lengths": (dict(n_seqs=5, n_layers=1, n_kv_heads=2, prefix=70, decode=260, decode_hi=930, budget=300),
+                       dict(sim_threshold=0.4), True),
+    "every_donor_folds": (dict(n_layers=1, n_kv_heads=3, prefix=40, decode=900, budget=256), dict(sim_threshold=-1.0), True),
+    "seeds_in_several_blocks": (dict(n_layers=1, n_kv_heads=2, prefix=30, decode=990, budget=700),
+                                dict(core=20, sim_threshold=0.3), True),
+    "radius": (dict(n_layers=1, n_kv_heads=2, prefix=64, decode=800, budget=320), dict(sim_threshold=0.2, merge_radius=30), True),
+    "d64": (dict(head_dim=64, n_layers=1, n_kv_heads=3, q_per_kv=2, prefix=50, decode=600, window=48, budget=256),
+            dict(sim_threshold=0.3), True),
+    "prefix_evicted_too": (dict(n_layers=1, n_kv_heads=2, prefix=500, decode=400, budget=256), dict(sim_threshold=0.5), False),
+    "identity_and_short": (dict(n_seqs=4, n_layers=1, n_kv_heads=1, prefix=20, decode=140, decode_hi=420, budget=250),
+                           dict(sim_threshold=0.5), False),
+    "prefix_budget_exhausted": (dict(n_layers=1, n_kv_heads=2, prefix=600, decode=300, budget=200),
+                                dict(prefix_budget=72, recent=128, sim_threshold=0.5), False),
+}
+
+
+@pytest.mark.parametrize("tail", ["one_launch", "general_kernels"])
+@pytest.mark.parametrize("case", sorted(SHORT_CASES))
+def test_short_units_through_both_tails(case, tail, monkeypatch):
+    """Units of at most 1024 rows (bf16) finish the event in one launch; CASK_FUSED_TAIL=0 sends
+    them through the general kernels.  Both must match the oracle."""
+    monkeypatch.setenv("CASK_FUSED_TAIL", "1" if tail == "one_launch" else "0")
+    wkw, pkw, folds = SHORT_CASES[case]
+    w = caches.scaled(W["cfg2"], **wkw)
+    c = caches.make(w, seed=51)
+    assert int((c["row_off"][1:] - c["row_off"][:-1]).max()) <= 1024
+    st = parity.full_check(c, parity.params_of(w, **pkw), expect_folds=folds)
+    _note((case, tail, st))
+
+
 def test_consolidate_with_caller_roles_naming_many_seeds():
     """cask_consolidate takes any role array: here far more seeds than the plan would ever
     produce, so the seeds of a unit do not fit one LDS block."""
