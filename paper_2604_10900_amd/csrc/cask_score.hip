@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     KParams kp, int n_units, int tiles_per_unit, int n_splits, int split_len, int mq_pad,
     const int64_t* __restrict__ row_off, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ Q, float2* __restrict__ rowstat,
-    const float* __restrict__ bias, float* __restrict__ scores) {
+    const float* __restrict__ bias, float* __restrict__ bias_out, float* __restrict__ scores) {
   constexpr int NK = 8;  // k-steps per tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* ring = smem;
@@ -488,6 +488,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       ml_combine(m_ref[ct], l_run[ct], m2, l2);
       if (h == 0 && res_row[ct] < Mq)
         part[(size_t)split * mq_pad + res_row[ct]] = make_float2(m_ref[ct], l_run[ct]);
+      // a single split is the whole row: -L goes out here and no combining kernel runs
+      if (n_splits == 1 && h == 0 && res_row[ct] < mq_pad)
+        bias_out[(size_t)unit * mq_pad + res_row[ct]] =
+            res_row[ct] < Mq ? -(m_ref[ct] + log2f(l_run[ct])) : kPadNegL;
     }
   } else {
     const float inv = 1.0f / (float)Mq;
@@ -638,14 +642,15 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   const int qblocks = (kp.Mq + kResRows - 1) / kResRows;
   const int tilesA = qblocks * wl.n_splits;
   score_mfma_kernel<0><<<dim3(units8 * tilesA), dim3(kThreads), ldsA, st>>>(
-      kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off, K, Q, rowstat, bias,
-      scores);
-  score_bias_kernel<<<dim3(b.n_units), dim3(256), 0, st>>>(kp, wl.n_splits, wl.mq_pad, rowstat, bias);
+      kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off, K, Q, rowstat, nullptr,
+      bias, scores);
+  if (wl.n_splits > 1)  // with one split sweep A has written -L itself
+    score_bias_kernel<<<dim3(b.n_units), dim3(256), 0, st>>>(kp, wl.n_splits, wl.mq_pad, rowstat, bias);
   if (between) (void)hipEventRecord(between, st);
   const int tilesB = (b.max_unit_len + kResRows - 1) / kResRows;
   score_mfma_kernel<1><<<dim3(units8 * tilesB), dim3(kThreads), ldsB, st>>>(
       kp, b.n_units, tilesB, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off, K, Q, rowstat, bias,
-      scores);
+      nullptr, scores);
   return hipGetLastError();
 }
 
