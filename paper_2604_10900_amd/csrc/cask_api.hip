@@ -46,6 +46,19 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
   n_splits = (max_unit_len + split_len - 1) / split_len;
   if (n_splits < 1) n_splits = 1;
   w.n_splits = n_splits;
+  // Sweep B of a batch of short units has few workgroups (one per 256 keys), each paying its
+  // fixed cost for all W*G window rows: two workgroups then share a key tile, one half of the
+  // window rows each, and add their column sums (two addends onto zero: the order cannot
+  // change the result).
+  w.q_splits = 1;
+  {
+    const int64_t wgsB = (int64_t)((n_units + 7) / 8 * 8) * ((max_unit_len + 255) / 256);
+    if (wgsB * 2 <= 512 && kp.Mq >= 512) w.q_splits = 2;
+    if (const char* e = std::getenv("CASK_QSPLIT")) {
+      const int v = std::atoi(e);
+      if (v == 1 || v == 2) w.q_splits = v;
+    }
+  }
   w.split_len = split_len;
   w.mq_pad = (int)align_up((size_t)kp.Mq, 64);
   size_t off = 0;

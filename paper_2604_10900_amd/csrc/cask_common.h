@@ -159,6 +159,7 @@ struct Workspace {
   size_t total;
   int n_splits;
   int split_len;     // keys per split (multiple of the key tile)
+  int q_splits;      // sweep B: window-row halves taken by separate workgroups (1 or 2)
   int mq_pad;
 };
 

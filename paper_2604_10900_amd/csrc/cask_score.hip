@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
 // plain, unpipelined path with explicit masks.
 template <int MODE>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
-    KParams kp, int n_units, int tiles_per_unit, int n_splits, int split_len, int mq_pad,
+    KParams kp, int n_units, int tiles_per_unit, int n_splits, int split_len, int q_splits, int mq_pad,
     const int64_t* __restrict__ row_off, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ Q, float2* __restrict__ rowstat,
     const float* __restrict__ bias, float* __restrict__ bias_out, float* __restrict__ scores) {
@@ -178,16 +178,26 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
   } else {
     // a unit's last tile first: its waves run the masked path and take longest
-    res_base = (tiles_per_unit - 1 - tile) * kResRows;
+    const int key_tiles = tiles_per_unit / q_splits;
+    res_base = (key_tiles - 1 - tile / q_splits) * kResRows;
     if (res_base >= N) return;
     res_ptr = Ku;
     res_limit = N;
     str_ptr = Qu;
     s_begin = 0;
     s_end = Mq;
-    if (kp.causal && res_base > N - W) s_begin = (((res_base - (N - W)) * Gq) / kStageRows) * kStageRows;
+    if (q_splits == 2) {  // this workgroup's half of the window rows, whole stages
+      const int half = ((Mq + 2 * kStageRows - 1) / (2 * kStageRows)) * kStageRows;
+      if (tile & 1) s_begin = half; else s_end = min(Mq, half);
+    }
+    if (kp.causal && res_base > N - W)
+      s_begin = max(s_begin, (((res_base - (N - W)) * Gq) / kStageRows) * kStageRows);
   }
-  const int n_stages = (s_end - s_begin + kStageRows - 1) / kStageRows;
+  const int n_stages = s_end > s_begin ? (s_end - s_begin + kStageRows - 1) / kStageRows : 0;
+  if (MODE == 0 && q_splits == 2 && tile == 0) {
+    // sweep B will add two partial sums per key: clear the unit's scores here
+    for (int i = tid; i < N; i += kThreads) scores[row0 + i] = 0.f;
+  }
 
   // ---- ring loads: thread t, piece j covers 16-byte LDS slot t + kThreads * j of the stage:
   //      row = 4 * (slot / 64) + slot % 4, 16-byte piece = (slot % 64) / 4
@@ -498,7 +508,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct) {
       const float tot = colsum[ct] + __shfl_xor(colsum[ct], 32, 64);
-      if (h == 0 && res_row[ct] < N) scores[row0 + res_row[ct]] = tot * inv;
+      if (h == 0 && res_row[ct] < N) {
+        if (q_splits == 2) atomicAdd(&scores[row0 + res_row[ct]], tot * inv);
+        else scores[row0 + res_row[ct]] = tot * inv;
+      }
     }
   }
 }
@@ -642,15 +655,15 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   const int qblocks = (kp.Mq + kResRows - 1) / kResRows;
   const int tilesA = qblocks * wl.n_splits;
   score_mfma_kernel<0><<<dim3(units8 * tilesA), dim3(kThreads), ldsA, st>>>(
-      kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off, K, Q, rowstat, nullptr,
-      bias, scores);
+      kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
+      nullptr, bias, scores);
   if (wl.n_splits > 1)  // with one split sweep A has written -L itself
     score_bias_kernel<<<dim3(b.n_units), dim3(256), 0, st>>>(kp, wl.n_splits, wl.mq_pad, rowstat, bias);
   if (between) (void)hipEventRecord(between, st);
-  const int tilesB = (b.max_unit_len + kResRows - 1) / kResRows;
+  const int tilesB = (b.max_unit_len + kResRows - 1) / kResRows * wl.q_splits;
   score_mfma_kernel<1><<<dim3(units8 * tilesB), dim3(kThreads), ldsB, st>>>(
-      kp, b.n_units, tilesB, wl.n_splits, wl.split_len, wl.mq_pad, b.row_off, K, Q, rowstat, bias,
-      nullptr, scores);
+      kp, b.n_units, tilesB, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
+      bias, nullptr, scores);
   return hipGetLastError();
 }
 
