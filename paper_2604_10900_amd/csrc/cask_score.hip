@@ -291,17 +291,37 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
 
   // ---- epilogues
   float tsum = 0.f;  // sweep A: sum of the tile in flight
-  auto piece = [&](const f32x16& acc, const float (&nl)[16], int ct, int i) {  // two logits of the fast epilogue
+  // Masked variant (tag true): a logit is dropped by one comparison of its stream-row offset
+  // inside the tile (a constant) with `d`, the lane's limit relative to the tile:
+  //   sweep A: hidden iff offset > d, d = (last key the lane's row sees) - first row of the tile - 4 h
+  //   sweep B: hidden iff offset < d, d = (first row that sees the lane's key) - first row of the tile - 4 h
+  int lim_a[2];  // sweep A: last stream row (key) that counts for the lane's window row
+#pragma unroll
+  for (int ct = 0; ct < 2; ++ct) lim_a[ct] = min(s_end - 1, vis_limit[ct]);
+  auto mask_d = [&](int ct, int trow0) { return (MODE == 0 ? lim_a[ct] : first_row[ct]) - trow0 - h * 4; };
+  auto piece = [&](auto masked, const f32x16& acc, const float (&nl)[16], int ct, int i, int d) {  // two logits of the fast epilogue
+    constexpr bool kMasked = decltype(masked)::value;
+    const int o0 = ((2 * i) >> 2) * 8 + ((2 * i) & 3), o1 = o0 + 1;  // row offsets of logits 2i, 2i + 1
     if (MODE == 0) {
       const float nm = -m_ref[ct];
-      tsum += fast_exp2(__builtin_fmaf(acc[2 * i], c, nm));
-      tsum += fast_exp2(__builtin_fmaf(acc[2 * i + 1], c, nm));
+      float x0 = acc[2 * i], x1 = acc[2 * i + 1];
+      if (kMasked) {
+        x0 = o0 > d ? kNegInf : x0;
+        x1 = o1 > d ? kNegInf : x1;
+      }
+      tsum += fast_exp2(__builtin_fmaf(x0, c, nm));
+      tsum += fast_exp2(__builtin_fmaf(x1, c, nm));
       // pin the partial sum here: without it the optimiser is free to sink these pieces out
       // of the MFMA chain they are meant to overlap with
       asm volatile("" : "+v"(tsum));
     } else {
-      colsum[ct] += fast_exp2(__builtin_fmaf(acc[2 * i], c, nl[2 * i]));
-      colsum[ct] += fast_exp2(__builtin_fmaf(acc[2 * i + 1], c, nl[2 * i + 1]));
+      float y0 = __builtin_fmaf(acc[2 * i], c, nl[2 * i]), y1 = __builtin_fmaf(acc[2 * i + 1], c, nl[2 * i + 1]);
+      if (kMasked) {
+        y0 = o0 < d ? kNegInf : y0;
+        y1 = o1 < d ? kNegInf : y1;
+      }
+      colsum[ct] += fast_exp2(y0);
+      colsum[ct] += fast_exp2(y1);
       asm volatile("" : "+v"(colsum[ct]));
     }
   };
@@ -318,11 +338,22 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     l_run[ct] = l_run[ct] * fast_exp2(m_ref[ct] + nm) + sum;
     m_ref[ct] = m_new;
   };
-  auto finish_fast = [&](const f32x16& acc, int ct) {  // sweep A: bank the tile sum, guard the range
+  auto finish_fast = [&](auto masked, const f32x16& acc, int ct, int d) {  // sweep A: bank the tile sum, guard the range
+    constexpr bool kMasked = decltype(masked)::value;
     if (MODE == 0) {
       const bool bad = !(tsum < 0x1p100f);
       if (__builtin_amdgcn_ballot_w64(bad) != 0ull) {
-        if (bad) exact_update(acc, ct); else l_run[ct] += tsum;
+        if (bad) {
+          f32x16 am = acc;
+          if (kMasked) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              if ((r >> 2) * 8 + (r & 3) > d) am[r] = kNegInf;
+          }
+          exact_update(am, ct);
+        } else {
+          l_run[ct] += tsum;
+        }
       } else {
         l_run[ct] += tsum;
       }
@@ -357,22 +388,25 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct][ks], acc, 0, 0, 0);
   };
   // chain of the new tile interleaved with the fast epilogue of the old one
-  auto fused = [&](f32x16& acc_new, const bf16x8(&a)[NK], int ct_new, const f32x16& acc_old,
-                   const float (&nl_old)[16], int ct_old) {
+  // (`trow_old`: first stream row of the old tile; only the masked variant looks at it)
+  auto fused = [&](auto masked, f32x16& acc_new, const bf16x8(&a)[NK], int ct_new, const f32x16& acc_old,
+                   const float (&nl_old)[16], int ct_old, int trow_old) {
+    const int d = mask_d(ct_old, trow_old);
 #pragma unroll
     for (int ks = 0; ks < NK; ++ks) {
-      piece(acc_old, nl_old, ct_old, ks);
+      piece(masked, acc_old, nl_old, ct_old, ks, d);
       acc_new = (ks == 0)
                     ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], bres[ct_new][0], f32x16{0}, 0, 0, 0)
                     : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct_new][ks], acc_new, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
-    finish_fast(acc_old, ct_old);
+    finish_fast(masked, acc_old, ct_old, d);
   };
-  auto drain = [&](const f32x16& acc_old, const float (&nl_old)[16], int ct_old) {
+  auto drain = [&](auto masked, const f32x16& acc_old, const float (&nl_old)[16], int ct_old, int trow_old) {
+    const int d = mask_d(ct_old, trow_old);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) piece(acc_old, nl_old, ct_old, i);
-    finish_fast(acc_old, ct_old);
+    for (int i = 0; i < 8; ++i) piece(masked, acc_old, nl_old, ct_old, i, d);
+    finish_fast(masked, acc_old, ct_old, d);
   };
 
   // ---- main loop over ring stages
@@ -444,16 +478,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   f1 = max(min(f1, n_stages), f0);
   if (!wave_live) sk = f0 = f1 = n_stages;  // only loads and barriers: the first loop below
 
-  int it = 0;
-  for (; it < f0; ++it) {
-    stage_sync(it);
-    if (it >= sk) slow_stage(it);
-  }
-  if (f1 > f0) {
-    stage_sync(f0);
-    load_a(a0, slot_of(f0), 0);
-    load_nl(nl0, slot_of(f0), 0);
-    if (MODE == 0 && f0 == 0) {
+  // stages [from, to), to > from, software-pipelined; does the stage_sync of each of them
+  auto pipelined = [&](auto masked, int from, int to) {
+    constexpr bool kMasked = decltype(masked)::value;
+    stage_sync(from);
+    load_a(a0, slot_of(from), 0);
+    load_nl(nl0, slot_of(from), 0);
+    if (MODE == 0 && !kMasked && from == 0) {
       // Nothing seen yet: the first logit of the lane's own row is a safe reference.  Too low
       // is caught by the range guard of the fast epilogue; too high only means every other
       // term is negligible next to this one, which is itself part of the sum.
@@ -464,21 +495,43 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     } else {
       chain(acc0, a0, 0);
     }
-    for (it = f0;; ++it) {
+    for (int it = from;; ++it) {
       const unsigned char* cur = slot_of(it);
+      const int base = s_begin + it * kStageRows;
       load_a(a1, cur, 1);
       load_nl(nl1, cur, 1);
-      fused(acc1, a0, 1, acc0, nl0, 0);
+      fused(masked, acc1, a0, 1, acc0, nl0, 0, base);
       load_a(a0, slot_of(it + 1), 0);  // a0 is free: operands of the coming stage
-      fused(acc0, a1, 0, acc1, nl0, 1);
+      fused(masked, acc0, a1, 0, acc1, nl0, 1, base);
       load_nl(nl0, slot_of(it + 1), 0);  // the last tile of tile row 0 is through its epilogue
-      fused(acc1, a1, 1, acc0, nl1, 0);
-      if (it + 1 >= f1) break;
+      fused(masked, acc1, a1, 1, acc0, nl1, 0, base + 32);
+      if (it + 1 >= to) break;
       stage_sync(it + 1);
-      fused(acc0, a0, 0, acc1, nl1, 1);
+      fused(masked, acc0, a0, 0, acc1, nl1, 1, base + 32);
     }
-    drain(acc1, nl1, 1);
-    it = f1;
+    drain(masked, acc1, nl1, 1, s_begin + (to - 1) * kStageRows + 32);
+  };
+  const std::integral_constant<bool, false> clean_tag;
+  const std::integral_constant<bool, true> masked_tag;
+
+  int it = 0;
+  for (; it < sk; ++it) stage_sync(it);
+  if (MODE == 1) {
+    // the partly visible stages run pipelined as well, with the mask in the epilogue
+    if (f0 > sk) pipelined(masked_tag, sk, f0);
+  } else {
+    for (; it < f0; ++it) {
+      stage_sync(it);
+      slow_stage(it);
+    }
+  }
+  if (f1 > f0) pipelined(clean_tag, f0, f1);
+  it = f1;
+  if (MODE == 0 && f1 > 0 && n_stages > f1) {
+    // the tail (causal, ragged end) after at least one clean stage: the reference is set, so
+    // the masked epilogue can take it
+    pipelined(masked_tag, f1, n_stages);
+    it = n_stages;
   }
   for (; it < n_stages; ++it) {
     stage_sync(it);
