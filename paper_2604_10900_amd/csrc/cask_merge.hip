@@ -59,7 +59,8 @@ __device__ inline float sumsq_bf16x8(const uint4& v) {
 // cos = (dot * |seed|^-1) * |donor|^-1 in fp32, first maximum wins.
 // ONE_BLOCK: every unit has at most kSeedBlock seeds, so they are staged once per workgroup and
 // the tile loop contains nothing but the donor stream (the host knows the bound).
-template <bool ONE_BLOCK>
+// RADIUS: a merge radius is set (the epilogue then looks up every seed's cache row).
+template <bool ONE_BLOCK, bool RADIUS>
 __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
     KParams kp, int n_units, int chunks_per_unit, int tiles_per_wg,
     const int64_t* __restrict__ row_off, const int32_t* __restrict__ prefix_len,
@@ -201,15 +202,19 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
 #pragma unroll
         for (int g = 0; g < 4; ++g) {  // ascending seed ordinal within the lane
           const float4 si = *reinterpret_cast<const float4*>(&seed_inv[s0 + g * 8 + h * 4]);
-          const int4 sp = *reinterpret_cast<const int4*>(&seed_pos[s0 + g * 8 + h * 4]);
           const float sv[4] = {si.x, si.y, si.z, si.w};
-          const int pv[4] = {sp.x, sp.y, sp.z, sp.w};
+          int pv[4] = {0, 0, 0, 0};
+          if (RADIUS) {
+            const int4 sp = *reinterpret_cast<const int4*>(&seed_pos[s0 + g * 8 + h * 4]);
+            pv[0] = sp.x, pv[1] = sp.y, pv[2] = sp.z, pv[3] = sp.w;
+          }
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int sr = s0 + g * 8 + h * 4 + q;
             const float sim = (acc[g * 4 + q] * sv[q]) * dinv;
-            const int gap = pv[q] > drow ? pv[q] - drow : drow - pv[q];
-            if (sr < m_blk && gap <= radius && sim > best) {
+            bool near = true;
+            if (RADIUS) near = (pv[q] > drow ? pv[q] - drow : drow - pv[q]) <= radius;
+            if (sr < m_blk && near && sim > best) {
               best = sim;
               best_ord = sb + sr;
             }
@@ -784,7 +789,8 @@ __global__ __launch_bounds__(256) void emit_kernel(
   const int nm = n_merged[u];
   const int32_t* sstart = seg_start + (size_t)u * (B + 1);
 
-  int slot[4], src[4], ord[4];
+  int slot[4], src[4], ord[4], c0[4];
+  float a0[4];
   Raw kraw[4], vraw[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -799,6 +805,8 @@ __global__ __launch_bounds__(256) void emit_kernel(
     if (src[j] >= 0) {
       kraw[j] = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + src[j]) * D + gl * EPL);
       vraw[j] = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + src[j]) * D + gl * EPL);
+      a0[j] = scores[row0 + src[j]];
+      c0[j] = in_count ? in_count[row0 + src[j]] : 1;
     }
   }
 #pragma unroll
@@ -810,8 +818,8 @@ __global__ __launch_bounds__(256) void emit_kernel(
     if (src[j] < 0) continue;
     *reinterpret_cast<Raw*>(K_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL) = kraw[j];
     *reinterpret_cast<Raw*>(V_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL) = vraw[j];
-    if (out_mass && gl == 0) out_mass[(size_t)u * B + slot[j]] = scores[row0 + src[j]];
-    if (out_count && gl == 0) out_count[(size_t)u * B + slot[j]] = in_count ? in_count[row0 + src[j]] : 1;
+    if (out_mass && gl == 0) out_mass[(size_t)u * B + slot[j]] = a0[j];
+    if (out_count && gl == 0) out_count[(size_t)u * B + slot[j]] = c0[j];
   }
 }
 
@@ -944,14 +952,17 @@ hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* r
     const int units8 = (b.n_units + 7) / 8 * 8;
     const int seed_bound = plan_seed_bound(kp);
     // (a caller-supplied role array may name any number of seeds: general kernel then)
-    if (roles_follow_plan && seed_bound <= kSeedBlock)
-      similarity_mfma_kernel<true><<<dim3(units8 * chunks), dim3(256), 0, st>>>(
-          kp, b.n_units, chunks, tiles_per_wg, b.row_off, b.prefix_len,
-          static_cast<const uint16_t*>(b.K), role, seed_rows, n_seeds, assign_ord);
-    else
-      similarity_mfma_kernel<false><<<dim3(units8 * chunks), dim3(256), 0, st>>>(
-          kp, b.n_units, chunks, tiles_per_wg, b.row_off, b.prefix_len,
-          static_cast<const uint16_t*>(b.K), role, seed_rows, n_seeds, assign_ord);
+#define CASK_SIM(ONE, RAD)                                                             \
+  similarity_mfma_kernel<ONE, RAD><<<dim3(units8 * chunks), dim3(256), 0, st>>>(       \
+      kp, b.n_units, chunks, tiles_per_wg, b.row_off, b.prefix_len,                    \
+      static_cast<const uint16_t*>(b.K), role, seed_rows, n_seeds, assign_ord)
+    const bool one = roles_follow_plan && seed_bound <= kSeedBlock;
+    if (kp.radius > 0) {
+      if (one) CASK_SIM(true, true); else CASK_SIM(false, true);
+    } else {
+      if (one) CASK_SIM(true, false); else CASK_SIM(false, false);
+    }
+#undef CASK_SIM
     return hipGetLastError();
   }
   if (kp.dtype == CASK_F32)
