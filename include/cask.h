@@ -226,7 +226,8 @@ int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, c
 
 /* Measurement aid (not part of the method): per-stage timing of cask_compress with HIP
  * events recorded on the caller's stream between its kernels.  Stage order: 0 score sweep A
- * (row statistics), 1 score sweep B (column mass), 2 select (with the ordered walk over the
+ * (row statistics), 1 score sweep B (column mass; with the small kernel that combines the row
+ * statistics of several key splits in front of it), 2 select (with the ordered walk over the
  * roles, which cask_compress runs in the same kernel), 3 index roles (zero in cask_compress),
  * 4 similarity, 5 gather merged donors, 6 emit.  A batch of short units (every unit at most
  * 1024 rows, B <= 1024, bf16, cosine geometry) runs stages 2-6 as one kernel: its time is

@@ -710,9 +710,9 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   score_mfma_kernel<0><<<dim3(units8 * tilesA), dim3(kThreads), ldsA, st>>>(
       kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
       nullptr, bias, scores);
+  if (between) (void)hipEventRecord(between, st);  // right behind sweep A: the stage is that kernel alone
   if (wl.n_splits > 1)  // with one split sweep A has written -L itself
     score_bias_kernel<<<dim3(b.n_units), dim3(256), 0, st>>>(kp, wl.n_splits, wl.mq_pad, rowstat, bias);
-  if (between) (void)hipEventRecord(between, st);
   const int tilesB = (b.max_unit_len + kResRows - 1) / kResRows * wl.q_splits;
   score_mfma_kernel<1><<<dim3(units8 * tilesB), dim3(kThreads), ldsB, st>>>(
       kp, b.n_units, tilesB, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
