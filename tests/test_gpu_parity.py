@@ -409,6 +409,46 @@ def test_selection_with_tied_scores(quant):
     assert np.array_equal(st.cpu().numpy(), st_w)
 
 
+@pytest.mark.parametrize("tail", ["one_launch", "general_kernels"])
+@pytest.mark.parametrize("quant", [0, 3, 50])
+def test_whole_event_on_short_units_with_tied_scores(quant, tail, monkeypatch):
+    """The same ties through the whole event on units of at most 1024 rows, where the
+    one-launch tail ranks rows by counting: keep-sets, roles' consequences (assignments) and
+    values against the oracle on the same injected scores.  The keys are far apart (nothing
+    folds), so the comparison is exact."""
+    monkeypatch.setenv("CASK_FUSED_TAIL", "1" if tail == "one_launch" else "0")
+    rng = np.random.default_rng(100 + quant)
+    lens = [300, 700, 1024, 513]
+    pref = [100, 500, 30, 0]
+    row_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(row_off[-1])
+    s = np.full(total, 0.25, dtype=np.float32) if quant == 0 else \
+        (np.floor(rng.random(total) * quant) / quant).astype(np.float32)
+    p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=1, window=64, budget=200, sim_threshold=0.9)
+    rp = parity.ref_params(p)
+    Kf = rng.standard_normal((total, 128)).astype(np.float32)
+    Vf = rng.standard_normal((total, 128)).astype(np.float32)
+    dev = torch.device("cuda:0")
+    Kd = torch.from_numpy(Kf).to(dev).to(torch.bfloat16)
+    Vd = torch.from_numpy(Vf).to(dev).to(torch.bfloat16)
+    Qd = torch.zeros(len(lens), 64, 1, 128, dtype=torch.bfloat16, device=dev)
+    K, V, Q = caches.host_bits(Kd), caches.host_bits(Vd), caches.host_bits(Qd)
+    want = ref.compress(rp, row_off, np.array(pref, dtype=np.int32), K, V, Q, scores=s)
+    b = cask.Batch(p, torch.from_numpy(row_off), torch.tensor(pref, dtype=torch.int32), Kd, Vd, Qd)
+    out = cask.compress(b, scores=torch.from_numpy(s).to(dev))
+    torch.cuda.synchronize()
+    got = parity.gpu_outputs(out, p)
+    assert np.array_equal(got["out_len"], want["out_len"])
+    assert np.array_equal(got["out_src"], want["out_src"])
+    assert np.array_equal(got["assign"], want["assign"])
+    assert np.array_equal(got["status"], want["status"])
+    for u in range(len(lens)):
+        L = int(want["out_len"][u])
+        assert np.array_equal(got["K_out"][u, :L], want["K_out"][u, :L])
+        assert np.array_equal(got["V_out"][u, :L], want["V_out"][u, :L])
+        assert np.array_equal(got["out_mass"][u, :L], want["out_mass"][u, :L])
+
+
 def test_selection_handles_zero_and_tiny_scores():
     rng = np.random.default_rng(5)
     N, P = 3000, 500
