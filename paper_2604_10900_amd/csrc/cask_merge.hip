@@ -609,22 +609,32 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
     }
     base += tot;
     __syncthreads();
-    for (int i0 = 0; i0 < count; i0 += 64) {
-      const int idx = i0 + lane;
-      const int o = idx < count ? mord[idx] - o_lo : -1;
-      const bool mine = o >= 0 && o < range && (o & (kGatherThreads / 64 - 1)) == wv;
-      unsigned long long todo = __ballot(mine);
-      if (todo == 0ull) continue;
-      const int drow = idx < count ? mrow[idx] : 0;
-      while (todo != 0ull) {
-        const int l = __ffsll((long long)todo) - 1;
-        const int v = __shfl(o, l, 64);
-        const bool in = mine && o == v;
-        const unsigned long long m = __ballot(in);
-        const int c = cursor[v];
-        if (in) seg_row[row0 + c + __popcll(m & below)] = drow;
-        if (lane == l) cursor[v] = c + __popcll(m);
-        todo &= ~m;
+    constexpr int kAhead = 4;  // 64-entry steps whose loads are in flight together
+    for (int i0 = 0; i0 < count; i0 += 64 * kAhead) {
+      int os[kAhead], rs[kAhead];
+#pragma unroll
+      for (int e = 0; e < kAhead; ++e) {
+        const int idx = min(i0 + e * 64 + lane, count - 1);  // clamped: no branch around the loads
+        os[e] = mord[idx];
+        rs[e] = mrow[idx];
+      }
+#pragma unroll
+      for (int e = 0; e < kAhead; ++e) {
+        const int idx = i0 + e * 64 + lane;
+        const int o = idx < count ? os[e] - o_lo : -1;
+        const int drow = rs[e];
+        const bool mine = o >= 0 && o < range && (o & (kGatherThreads / 64 - 1)) == wv;
+        unsigned long long todo = __ballot(mine);
+        while (todo != 0ull) {
+          const int l = __ffsll((long long)todo) - 1;
+          const int v = __shfl(o, l, 64);
+          const bool in = mine && o == v;
+          const unsigned long long m = __ballot(in);
+          const int c = cursor[v];
+          if (in) seg_row[row0 + c + __popcll(m & below)] = drow;
+          if (lane == l) cursor[v] = c + __popcll(m);
+          todo &= ~m;
+        }
       }
     }
     __syncthreads();
