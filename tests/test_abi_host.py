@@ -69,6 +69,9 @@ def test_plan_agrees_with_oracle_on_random_sizes(cask, oracle):
         got = cask.plan(cask.Params(**kw), P, P + D)
         want = oracle.plan(oracle.Params(**kw), P, P + D)
         assert got == want, (kw, P, D)
+        # the kernels size LDS blocks and fold workgroups by this bound on the seeds of a unit
+        bound = (B + 4) // 5 if kw["core"] < 0 else max(0, B - kw["core"])
+        assert got["seeds"] <= min(B, bound), (kw, P, D, got)
         assert got["p_keep"] + min(D - got["r_eff"], got["slots"]) + got["r_eff"] == min(P + D, B)
 
 
