@@ -256,6 +256,38 @@ def test_short_units_through_both_tails(case, tail, monkeypatch):
     _note((case, tail, st))
 
 
+@pytest.mark.parametrize("tail", ["one_launch", "general_kernels"])
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_random_short_batches(seed, tail, monkeypatch):
+    """Seeded random shapes and parameters for batches of short ragged units (lengths, prefix,
+    budget, core size, recent tail, threshold, radius, head dimension, heads per group)."""
+    monkeypatch.setenv("CASK_FUSED_TAIL", "1" if tail == "one_launch" else "0")
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([64, 128]))
+    window = int(rng.choice([16, 32, 48, 64]))
+    G = int(rng.choice([1, 2, 4]))
+    prefix = int(rng.integers(0, 400))
+    lo = int(rng.integers(window + 8, 500))
+    hi = int(rng.integers(lo + 1, 1024 - prefix)) if 1024 - prefix > lo + 1 else lo + 1
+    if prefix + hi > 1024:
+        hi = 1024 - prefix
+    lo = min(lo, hi - 1) if hi - 1 >= window else window
+    recent = int(rng.integers(0, window + 1))
+    budget = int(rng.integers(recent + window + 8, 900))
+    core = int(rng.choice([-1, 0, 10, budget // 2]))
+    w = caches.scaled(W["cfg2"], head_dim=d, n_seqs=int(rng.integers(1, 4)), n_layers=1,
+                      n_kv_heads=int(rng.integers(1, 4)), q_per_kv=G, prefix=prefix, decode=lo, decode_hi=hi,
+                      window=window, budget=budget, recent=recent, core=core,
+                      cluster_frac=float(rng.choice([0.1, 0.4, 0.8])))
+    c = caches.make(w, seed=200 + seed)
+    assert int((c["row_off"][1:] - c["row_off"][:-1]).max()) <= 1024
+    p = parity.params_of(w, sim_threshold=float(rng.choice([-1.0, 0.2, 0.6, 0.95])),
+                         merge_radius=int(rng.choice([0, 0, 17, 200])),
+                         prefix_budget=int(rng.choice([-1, -1, 0, 40])))
+    st = parity.full_check(c, p)
+    _note((seed, tail, dict(d=d, W=window, G=G, P=prefix, dec=(lo, hi), B=budget, core=core, R=recent), st))
+
+
 def test_consolidate_with_caller_roles_naming_many_seeds():
     """cask_consolidate takes any role array: here far more seeds than the plan would ever
     produce, so the seeds of a unit do not fit one LDS block."""
