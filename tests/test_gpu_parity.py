@@ -288,6 +288,38 @@ def test_random_short_batches(seed, tail, monkeypatch):
     _note((seed, tail, dict(d=d, W=window, G=G, P=prefix, dec=(lo, hi), B=budget, core=core, R=recent), st))
 
 
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_random_longer_batches(seed):
+    """Seeded random shapes and parameters for ragged units of up to a few thousand rows: both
+    dtypes, both head dimensions, both merge geometries."""
+    rng = np.random.default_rng(3000 + seed)
+    f32 = bool(rng.integers(0, 2))
+    base = W["cfg1"] if f32 else W["cfg2"]
+    d = int(rng.choice([64, 128]))
+    window = int(rng.choice([16, 32, 64]))
+    G = int(rng.choice([1, 2, 7])) if not f32 else int(rng.choice([1, 2]))
+    prefix = int(rng.integers(0, 3000))
+    lo = int(rng.integers(1100, 2500))
+    hi = int(rng.integers(lo + 1, 4500))
+    recent = int(rng.integers(0, window + 1))
+    budget = int(rng.integers(recent + window + 8, 1500))
+    core = int(rng.choice([-1, 0, 25, budget // 2]))
+    w = caches.scaled(base, head_dim=d, n_seqs=int(rng.integers(1, 3)), n_layers=1, n_kv_heads=int(rng.integers(1, 3)),
+                      q_per_kv=G, prefix=prefix, decode=lo, decode_hi=hi, window=window, budget=budget, recent=recent,
+                      core=core, fixed_clusters=None, cluster_lo=3, cluster_hi=12,
+                      cluster_frac=float(rng.choice([0.1, 0.5])))
+    c = caches.make(w, seed=300 + seed)
+    kw = dict(merge_radius=int(rng.choice([0, 0, 64])), prefix_budget=int(rng.choice([-1, -1, 100])))
+    if rng.integers(0, 3) == 0:
+        band = torch.rand(d // 2, generator=torch.Generator().manual_seed(seed)).to("cuda:0")
+        kw.update(merge_geometry=1, band_weight=band, dist_threshold=float(rng.choice([4.0, 12.0, 1e9])))
+    else:
+        kw.update(sim_threshold=float(rng.choice([-1.0, 0.3, 0.7])))
+    st = parity.full_check(c, parity.params_of(w, **kw))
+    _note((seed, dict(f32=f32, d=d, W=window, G=G, P=prefix, dec=(lo, hi), B=budget, core=core, R=recent,
+                      **{k: v for k, v in kw.items() if k != "band_weight"}), st))
+
+
 def test_consolidate_with_caller_roles_naming_many_seeds():
     """cask_consolidate takes any role array: here far more seeds than the plan would ever
     produce, so the seeds of a unit do not fit one LDS block."""
