@@ -117,7 +117,11 @@ typedef struct {
 /* HOST: the split for prefix length P and cache length N.  Returns CASK_EINVAL on bad sizes. */
 int cask_plan(const cask_params* params, int32_t P, int32_t N, cask_plan_t* out);
 
-/* HOST: bytes of device workspace every entry point below needs for such a batch. */
+/* HOST: bytes of device workspace every entry point below needs for such a batch.
+ * (Measurement overrides, read from the environment when the workspace is laid out and at
+ * every scoring call, so they must not change between the two: CASK_SPLITS = 1..64 fixes the
+ * number of key splits of the first scoring sweep, CASK_QSPLIT = 1 | 2 the number of
+ * workgroups that share a key tile in the second.  Neither changes what is computed.) */
 size_t cask_workspace_bytes(const cask_params* params, int32_t n_units, int64_t total_rows,
                             int32_t max_unit_len);
 
