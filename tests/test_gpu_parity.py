@@ -91,6 +91,20 @@ def test_bf16_mfma_odd_window_noncausal_and_custom_scale():
         _note((causal, scale, st))
 
 
+@pytest.mark.parametrize("causal", [1, 0])
+def test_bf16_window_rows_shared_by_two_workgroups(causal):
+    """Few key tiles and at least 512 window rows: two workgroups of the second scoring sweep
+    share a key tile, half of the window rows each.  W * G = 525 is no multiple of the 64-row
+    stage or of the halves; units shorter than, equal to and longer than a key tile."""
+    lens = [75, 256, 300, 777, 1900]
+    pref = [0, 100, 0, 333, 40]
+    c = _ragged_bf16(lens, pref, G=7, Wn=75, seed=13)
+    p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=7, window=75, recent=20, budget=160,
+                    sim_threshold=0.5, causal=causal)
+    st = parity.full_check(c, p)
+    _note((causal, st))
+
+
 def test_bf16_single_query_head_small_window():
     c = _ragged_bf16([64, 700, 4100], [0, 10, 100], G=1, Wn=8, seed=9)
     p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=1, window=8, budget=96)
