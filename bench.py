@@ -57,6 +57,8 @@ def parse():
                          "FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="record no HIP events inside the timed region (no roofline object then)")
+    ap.add_argument("--graph-steps", type=int, default=50,
+                    help="replays of the extra HIP-graph measurement (0 = skip)")
     ap.add_argument("--overlap-steps", type=int, default=50,
                     help="events of the extra two-stream measurement (0 = skip)")
     ap.add_argument("--breakdown-steps", type=int, default=20,
@@ -197,8 +199,8 @@ def main():
         b1._ws = ws
         del outs1, lanes
     graph_ms = None
-    if steady:
-        # the same event as one replayed HIP graph: the launch gaps of six small kernels go away
+    if args.graph_steps > 0:
+        # the same event as one replayed HIP graph: the launch gaps between its kernels go away
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -212,10 +214,10 @@ def main():
             g.replay()
         torch.cuda.synchronize()
         tg0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(args.graph_steps):
             g.replay()
         torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - tg0) * 1e3 / args.steps
+        graph_ms = (time.perf_counter() - tg0) * 1e3 / args.graph_steps
         step(0)   # leave the outputs of an eager event behind for the checks below
         torch.cuda.synchronize()
     status = outs.status.cpu().numpy()
