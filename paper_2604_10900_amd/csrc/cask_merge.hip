@@ -644,9 +644,13 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
 
 // ------------------------------------------------------------------ emit (copy + fold)
 
+// row groups (of four rows) a copy wave handles one after the other; measured: two beat four
+// and one (a long prefix-heavy copy, B = 2048: 64 us against 76 and 74)
+constexpr int kCopyRounds = 2;
+
 // One launch, two kinds of workgroup.  Sixteen lanes hold one row (D / 16 elements each).
 //
-// Copy workgroups: a wave owns 16 consecutive output slots of one unit, puts the loads of four
+// Copy workgroups: a wave owns 8 consecutive output slots of one unit, puts the loads of its
 // rows of K and V in flight before it touches any of them, and writes every slot that is not
 // a representative (a seed whose group of donors is empty is copied like any kept row).
 //
@@ -668,7 +672,7 @@ __global__ __launch_bounds__(256) void emit_kernel(
     int32_t* __restrict__ out_count, int out_stride) {
   constexpr int EPL = D / 16;                    // elements per lane
   constexpr int WORDS = EPL * sizeof(T) / 4;     // 32-bit words per lane
-  constexpr int kSlotsPerWave = 16;
+  constexpr int kSlotsPerWave = 4 * kCopyRounds;
   struct alignas(WORDS * 4 > 16 ? 16 : WORDS * 4) Raw { uint32_t w[WORDS]; };
   const int lane = threadIdx.x & 63, grp = lane >> 4, gl = lane & 15;
   const int B = kp.B;
@@ -799,11 +803,11 @@ __global__ __launch_bounds__(256) void emit_kernel(
   const int nm = n_merged[u];
   const int32_t* sstart = seg_start + (size_t)u * (B + 1);
 
-  int slot[4], src[4], ord[4], c0[4];
-  float a0[4];
-  Raw kraw[4], vraw[4];
+  int slot[kCopyRounds], src[kCopyRounds], ord[kCopyRounds], c0[kCopyRounds];
+  float a0[kCopyRounds];
+  Raw kraw[kCopyRounds], vraw[kCopyRounds];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < kCopyRounds; ++j) {
     slot[j] = t_base + j * 4 + grp;
     const bool ok = slot[j] < len;
     src[j] = ok ? out_src[(size_t)u * B + slot[j]] : -1;
@@ -811,7 +815,7 @@ __global__ __launch_bounds__(256) void emit_kernel(
   }
   // the row loads do not wait for the test below: a representative's row is loaded in vain
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < kCopyRounds; ++j) {
     if (src[j] >= 0) {
       kraw[j] = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + src[j]) * D + gl * EPL);
       vraw[j] = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + src[j]) * D + gl * EPL);
@@ -820,11 +824,11 @@ __global__ __launch_bounds__(256) void emit_kernel(
     }
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < kCopyRounds; ++j) {
     if (ord[j] >= 0 && sstart[ord[j] + 1] > sstart[ord[j]]) src[j] = -1;  // a fold wave writes it
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < kCopyRounds; ++j) {
     if (src[j] < 0) continue;
     *reinterpret_cast<Raw*>(K_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL) = kraw[j];
     *reinterpret_cast<Raw*>(V_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL) = vraw[j];
@@ -841,7 +845,7 @@ hipError_t launch_emit_t(const KParams& kp, const Batch& b, const float* scores,
                          const int32_t* seg_start, const int32_t* n_merged, void* K_out,
                          void* V_out, float* out_mass, const int32_t* in_count,
                          int32_t* out_count, int out_stride, hipStream_t st) {
-  const long long copy_waves = (long long)b.n_units * ((kp.B + 15) / 16);
+  const long long copy_waves = (long long)b.n_units * ((kp.B + 4 * kCopyRounds - 1) / (4 * kCopyRounds));
   const long long copy_blocks = (copy_waves + 3) / 4;
   // (unit, seed ordinal) work items; a fold wave tests 64 of them per round
   const int fold_per_unit = plan_seed_bound(kp);
