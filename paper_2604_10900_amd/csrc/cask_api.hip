@@ -68,6 +68,9 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
     return at;
   };
   const size_t rows = (size_t)total_rows, units = (size_t)n_units;
+  // one-launch scoring of short units: partial column sums, one row per 64 window rows
+  w.parts_pitch = (max_unit_len <= 1024 && n_splits == 1) ? (int)align_up((size_t)(max_unit_len > 0 ? max_unit_len : 1), 64) : 0;
+  w.parts = take(units * (size_t)((kp.Mq + 63) / 64) * (size_t)w.parts_pitch * sizeof(float));
   w.rowstat = take(units * n_splits * w.mq_pad * sizeof(float2));
   w.bias = take(units * w.mq_pad * sizeof(float));
   w.scores = take(rows * sizeof(float));
@@ -319,6 +322,12 @@ static bool fused_tail_disabled() {
   return e && e[0] == '0';
 }
 
+// CASK_FUSED_SCORE=0: two scoring launches for short units as well (read at every call)
+static bool fused_score_disabled() {
+  const char* e = std::getenv("CASK_FUSED_SCORE");
+  return e && e[0] == '0';
+}
+
 int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, const float* scores,
                            const int32_t* assign, const void* K_out, int32_t out_stride_rows,
                            float* dispersion, float* lost_mass, void* hip_stream) {
@@ -381,7 +390,15 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
   hipError_t e;
   StageRecorder rec(st);
   rec.mark();  // start
-  if (!given) {
+  const bool fused_tail = tail_small_fits(kp, b) && !fused_tail_disabled();
+  // short units: both sweeps are one launch as well, handing partial sums to the tail kernel
+  // (reported as the first scoring stage; the second reads as an empty bracket)
+  const bool fused_score = fused_tail && !given && score_parts_fits(kp, b, wl) && !fused_score_disabled();
+  if (fused_score) {
+    e = launch_score_parts(kp, b, wl, w, st);
+    if (e != hipSuccess) return CASK_EDEVICE;
+    rec.mark();
+  } else if (!given) {
     e = launch_score(kp, b, wl, w, s, st, rec.peek());  // records the end of sweep A itself
     if (e != hipSuccess) return CASK_EDEVICE;
     rec.skip();
@@ -389,10 +406,11 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
     rec.mark();
   }
   rec.mark();  // end of sweep B
-  if (tail_small_fits(kp, b) && !fused_tail_disabled()) {
+  if (fused_tail) {
     // short units: the rest of the event is one launch (reported as the select stage)
-    e = launch_tail_small(kp, b, s, in_count, K_out, V_out, out_stride_rows, out_len, out_src,
-                          out_mass, out_count, assign, status, st);
+    e = launch_tail_small(kp, b, s, fused_score ? reinterpret_cast<const float*>(w + wl.parts) : nullptr,
+                          (kp.Mq + 63) / 64, wl.parts_pitch, in_count, K_out, V_out, out_stride_rows,
+                          out_len, out_src, out_mass, out_count, assign, status, st);
     for (int k = 0; k < 5; ++k) rec.mark();
     return dev_rc(e);
   }

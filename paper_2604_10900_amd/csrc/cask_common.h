@@ -160,6 +160,8 @@ struct Workspace {
   int n_splits;
   int split_len;     // keys per split (multiple of the key tile)
   int q_splits;      // sweep B: window-row halves taken by separate workgroups (1 or 2)
+  size_t parts;      // float  [n_units][ceil(Mq / 64)][parts_pitch]: partial column sums of the one-launch scoring
+  int parts_pitch;   // 0: not laid out (units too long for that path)
   int mq_pad;
 };
 
@@ -182,6 +184,11 @@ struct Batch {
 // `between`, when not null, is recorded on the stream between the two scoring sweeps.
 hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, char* ws,
                         float* scores, hipStream_t st, hipEvent_t between = nullptr);
+// Short units (at most Workspace::parts_pitch rows, one key split, bf16 d = 128): both scoring
+// sweeps in one launch, leaving partial column sums for the consumer to add.
+bool score_parts_fits(const KParams& kp, const Batch& b, const Workspace& wl);
+hipError_t launch_score_parts(const KParams& kp, const Batch& b, const Workspace& wl, char* ws,
+                              hipStream_t st);
 hipError_t launch_select(const KParams& kp, const Batch& b, const float* scores, uint8_t* role,
                          int32_t* status, bool do_prefix, bool do_decode, hipStream_t st);
 // both stages of the selection and the ordered walk in one launch (whole-event path)
@@ -210,8 +217,10 @@ hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t
 // Everything after scoring in one launch, for batches whose units all fit a workgroup (a row per
 // thread), bf16, cosine geometry; `tail_small_fits` says whether a batch qualifies.
 bool tail_small_fits(const KParams& kp, const Batch& b);
-hipError_t launch_tail_small(const KParams& kp, const Batch& b, const float* scores,
-                             const int32_t* in_count, void* K_out, void* V_out, int out_stride,
+// `parts` not null: the scores come as `n_parts` partial sums per key (row pitch
+// `parts_pitch`); the kernel adds them, writes the scores to `scores` and goes on from there.
+hipError_t launch_tail_small(const KParams& kp, const Batch& b, float* scores, const float* parts,
+                             int n_parts, int parts_pitch, const int32_t* in_count, void* K_out, void* V_out, int out_stride,
                              int32_t* out_len, int32_t* out_src, float* out_mass,
                              int32_t* out_count, int32_t* assign, int32_t* status,
                              hipStream_t st);

@@ -140,8 +140,12 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     KParams kp, int n_units, int tiles_per_unit, int n_splits, int split_len, int q_splits, int mq_pad,
     const int64_t* __restrict__ row_off, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ Q, float2* __restrict__ rowstat,
-    const float* __restrict__ bias, float* __restrict__ bias_out, float* __restrict__ scores) {
+    const float* __restrict__ bias, float* __restrict__ bias_out, float* __restrict__ scores,
+    float* __restrict__ parts, int part_pitch) {
   constexpr int NK = 8;  // k-steps per tile
+  // MODE 2 = both sweeps in one launch for short units (one key split): the first pass is
+  // MODE 0; the second keeps the same resident window rows and streams the keys again
+  constexpr bool kRowPass = MODE != 1;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* ring = smem;
 
@@ -162,7 +166,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   const uint16_t* str_ptr;
   int res_base, res_limit, s_begin, s_end;  // resident rows [res_base, ..), stream rows [s_begin, s_end)
   int split = 0;
-  if (MODE == 0) {
+  if (kRowPass) {
     const int qb = tile / n_splits;
     split = tile % n_splits;
     res_base = qb * kResRows;
@@ -172,7 +176,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     str_ptr = Ku;
     s_begin = split * split_len;
     s_end = min(N, s_begin + split_len);
-    if (kp.causal) {
+    if (kp.causal) {  // (MODE 2: the keys cut here get zeros as their partial sums at the end)
       const int last_row = min(Mq, res_base + kResRows) - 1;
       s_end = min(s_end, N - W + last_row / Gq + 1);
     }
@@ -216,7 +220,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       const_cast<float*>(bias + (size_t)unit * mq_pad), 0, mq_pad * 4, 0x00020000);
   auto issue_stage = [&](int stage) {  // rows past s_end read as zero through the descriptor
     unsigned char* slot = ring + (stage % kDepth) * kStageBytes;
-    const int soff = (s_begin + stage * kStageRows) * kRowBytes;
+    // MODE 2: the stages of the second pass follow those of the first and read the same keys
+    const int src_stage = (MODE == 2 && stage >= n_stages) ? stage - n_stages : stage;
+    const int soff = (s_begin + src_stage * kStageRows) * kRowBytes;
     if (MODE == 1 && (stage & (kWaves - 1)) == wv)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
           brsrc, (__attribute__((address_space(3))) void*)(slot + kDataBytes), 4, lane * 4,
@@ -282,7 +288,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   int vis_limit[2];  // sweep A: last key the lane's window row sees; sweep B: the lane's key
 #pragma unroll
   for (int ct = 0; ct < 2; ++ct)
-    vis_limit[ct] = (MODE == 0) ? (kp.causal ? N - W + res_row[ct] / Gq : N - 1) : res_row[ct];
+    vis_limit[ct] = (kRowPass) ? (kp.causal ? N - W + res_row[ct] / Gq : N - 1) : res_row[ct];
   const int tail_start = kp.causal ? N - W : N;  // keys > tail_start are hidden from some row
   int first_row[2];  // sweep B: first window row that sees the lane's key
 #pragma unroll
@@ -298,11 +304,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   int lim_a[2];  // sweep A: last stream row (key) that counts for the lane's window row
 #pragma unroll
   for (int ct = 0; ct < 2; ++ct) lim_a[ct] = min(s_end - 1, vis_limit[ct]);
-  auto mask_d = [&](int ct, int trow0) { return (MODE == 0 ? lim_a[ct] : first_row[ct]) - trow0 - h * 4; };
+  auto mask_d = [&](int ct, int trow0) { return (kRowPass ? lim_a[ct] : first_row[ct]) - trow0 - h * 4; };
   auto piece = [&](auto masked, const f32x16& acc, const float (&nl)[16], int ct, int i, int d) {  // two logits of the fast epilogue
     constexpr bool kMasked = decltype(masked)::value;
     const int o0 = ((2 * i) >> 2) * 8 + ((2 * i) & 3), o1 = o0 + 1;  // row offsets of logits 2i, 2i + 1
-    if (MODE == 0) {
+    if (kRowPass) {
       const float nm = -m_ref[ct];
       float x0 = acc[2 * i], x1 = acc[2 * i + 1];
       if (kMasked) {
@@ -340,7 +346,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   };
   auto finish_fast = [&](auto masked, const f32x16& acc, int ct, int d) {  // sweep A: bank the tile sum, guard the range
     constexpr bool kMasked = decltype(masked)::value;
-    if (MODE == 0) {
+    if (kRowPass) {
       const bool bad = !(tsum < 0x1p100f);
       if (__builtin_amdgcn_ballot_w64(bad) != 0ull) {
         if (bad) {
@@ -361,7 +367,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
   };
   auto slow_tile = [&](f32x16& acc, const float (&nl)[16], int ct, int trow0) {
-    if (MODE == 0) {
+    if (kRowPass) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = trow0 + (r >> 2) * 8 + h * 4 + (r & 3);
@@ -448,7 +454,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         slow_tile(acc0, nl0, ct, trow0);
       }
     }
-    if (MODE == 0) {
+    if (kRowPass) {
       // a lane that saw nothing yet takes 0 as its reference: (0, 0) is the empty sum
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct)
@@ -463,7 +469,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // nothing in the first stages (every row is older than its oldest key), is partly masked
   // until the rows pass its youngest key, and is clean from there on.
   int sk = 0, f0 = 0, f1;
-  if (MODE == 0) {
+  if (kRowPass) {
     const int clean_rows = min(tail_start + 1, s_end) - s_begin;  // keys every row sees
     f1 = clean_rows > 0 ? clean_rows / kStageRows : 0;
   } else {
@@ -484,7 +490,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     stage_sync(from);
     load_a(a0, slot_of(from), 0);
     load_nl(nl0, slot_of(from), 0);
-    if (MODE == 0 && !kMasked && from == 0) {
+    if (kRowPass && !kMasked && from == 0) {
       // Nothing seen yet: the first logit of the lane's own row is a safe reference.  Too low
       // is caught by the range guard of the fast epilogue; too high only means every other
       // term is negligible next to this one, which is itself part of the sum.
@@ -527,7 +533,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   }
   if (f1 > f0) pipelined(clean_tag, f0, f1);
   it = f1;
-  if (MODE == 0 && f1 > 0 && n_stages > f1) {
+  if (kRowPass && f1 > 0 && n_stages > f1) {
     // the tail (causal, ragged end) after at least one clean stage: the reference is set, so
     // the masked epilogue can take it
     pipelined(masked_tag, f1, n_stages);
@@ -539,10 +545,117 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   }
   // loads issued past the last stage may still be landing in LDS: let them finish before the
   // workgroup's LDS can be handed to another one
-  __builtin_amdgcn_s_waitcnt(0x0F70);
+  if (MODE != 2) __builtin_amdgcn_s_waitcnt(0x0F70);
 
   // ---- finish
-  if (MODE == 0) {
+  if (MODE == 2) {
+    // ---- second pass: the same resident window rows are now the A operand and the keys
+    // stream through the ring once more (their stages were requested while the first pass
+    // finished), so a lane owns one key column of a tile and 16 window rows.  exp2(c x - L_row)
+    // summed over the rows of this wave is one partial column sum per key; the waves write
+    // theirs side by side (`parts[unit][16-row-block wave][key]`) and whoever reads the scores
+    // adds them in wave order: no atomics, the same bits every run.
+    float* negl_s = reinterpret_cast<float*>(smem + kDepth * kStageBytes);  // -L of the workgroup's 256 rows
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) {
+      const float m2 = __shfl_xor(m_ref[ct], 32, 64);
+      const float l2 = __shfl_xor(l_run[ct], 32, 64);
+      ml_combine(m_ref[ct], l_run[ct], m2, l2);
+      if (h == 0)
+        negl_s[wv * 64 + ct * 32 + c32] = res_row[ct] < Mq ? -(m_ref[ct] + log2f(l_run[ct])) : kPadNegL;
+    }
+    // the wave reads back only what it wrote itself (LDS operations of a wave stay in order);
+    // the empty asm keeps the compiler from moving the differently typed reads above the writes
+    asm volatile("" ::: "memory");
+    float nlq[2][16];
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const bf16x8 raw = *reinterpret_cast<const bf16x8*>(
+            reinterpret_cast<const unsigned char*>(negl_s) + (wv * 64 + ct * 32 + g * 8 + h * 4) * 4);
+        const f32x4 v = __builtin_bit_cast(f32x4, raw);
+        nlq[ct][g * 4 + 0] = v[0]; nlq[ct][g * 4 + 1] = v[1]; nlq[ct][g * 4 + 2] = v[2]; nlq[ct][g * 4 + 3] = v[3];
+      }
+    float* part_out = parts + ((size_t)unit * ((Mq + 63) / 64) + (res_base >> 6) + wv) * part_pitch;
+    float ksum = 0.f;
+    auto chain2 = [&](f32x16& acc, const bf16x8(&a)[NK], int ct) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bres[ct][0], a[0], f32x16{0}, 0, 0, 0);
+#pragma unroll
+      for (int ks = 1; ks < NK; ++ks)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bres[ct][ks], a[ks], acc, 0, 0, 0);
+    };
+    // hidden iff the row's offset inside the resident tile is < d,
+    // d = (first window row that sees the lane's key) - first row of the tile - 4 h
+    auto mask_d2 = [&](int ct, int key) {
+      const int first = kp.causal ? max(0, (key - (N - W)) * Gq) : 0;
+      return first - (res_base + wv * 64 + ct * 32 + h * 4);
+    };
+    auto piece2 = [&](auto masked, const f32x16& acc, int ct, int i, int d) {
+      constexpr bool kMasked = decltype(masked)::value;
+      const int o0 = ((2 * i) >> 2) * 8 + ((2 * i) & 3), o1 = o0 + 1;
+      float y0 = __builtin_fmaf(acc[2 * i], c, nlq[ct][2 * i]), y1 = __builtin_fmaf(acc[2 * i + 1], c, nlq[ct][2 * i + 1]);
+      if (kMasked) {
+        y0 = o0 < d ? kNegInf : y0;
+        y1 = o1 < d ? kNegInf : y1;
+      }
+      ksum += fast_exp2(y0);
+      ksum += fast_exp2(y1);
+      asm volatile("" : "+v"(ksum));
+    };
+    auto fused2 = [&](auto masked, f32x16& acc_new, const bf16x8(&a)[NK], int ct_new, const f32x16& acc_old,
+                      int ct_old, int key_old) {
+      const int d = mask_d2(ct_old, key_old);
+#pragma unroll
+      for (int ks = 0; ks < NK; ++ks) {
+        piece2(masked, acc_old, ct_old, ks, d);
+        acc_new = (ks == 0)
+                      ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bres[ct_new][0], a[0], f32x16{0}, 0, 0, 0)
+                      : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bres[ct_new][ks], a[ks], acc_new, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    auto flush = [&](int key) {  // both resident tiles of this key tile are through their epilogue
+      const float tot = ksum + __shfl_xor(ksum, 32, 64);
+      if (h == 0 && key < N) part_out[key] = tot;
+      ksum = 0.f;
+    };
+    // stages [from, to) of the second pass (ring stages n_stages + from ...), software-pipelined
+    auto pipelined2 = [&](auto masked, int from, int to) {
+      stage_sync(n_stages + from);
+      load_a(a0, slot_of(n_stages + from), 0);
+      chain2(acc0, a0, 0);
+      for (int it = from;; ++it) {
+        const unsigned char* cur = slot_of(n_stages + it);
+        const int key0 = s_begin + it * kStageRows + c32;  // the lane's key in key tile 0 of the stage
+        load_a(a1, cur, 1);
+        fused2(masked, acc1, a0, 1, acc0, 0, key0);
+        load_a(a0, slot_of(n_stages + it + 1), 0);
+        fused2(masked, acc0, a1, 0, acc1, 1, key0);
+        flush(key0);
+        fused2(masked, acc1, a1, 1, acc0, 0, key0 + 32);
+        if (it + 1 >= to) break;
+        stage_sync(n_stages + it + 1);
+        fused2(masked, acc0, a0, 0, acc1, 1, key0 + 32);
+        flush(key0 + 32);
+      }
+      const int key1 = s_begin + (to - 1) * kStageRows + 32 + c32;
+      const int d = mask_d2(1, key1);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) piece2(masked, acc1, 1, i, d);
+      flush(key1);
+    };
+    if (wave_live) {
+      const int clean = min(f1, n_stages);  // stages whose keys every window row sees
+      if (clean > 0) pipelined2(clean_tag, 0, clean);
+      if (n_stages > clean) pipelined2(masked_tag, clean, n_stages);
+      // keys past the stages that ran are hidden from every row of this workgroup
+      for (int key = s_begin + n_stages * kStageRows + lane; key < N; key += 64) part_out[key] = 0.f;
+    } else {
+      for (int it2 = 0; it2 < n_stages; ++it2) stage_sync(n_stages + it2);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+  } else if (MODE == 0) {
     float2* part = rowstat + (size_t)unit * n_splits * mq_pad;
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct) {
@@ -556,7 +669,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         bias_out[(size_t)unit * mq_pad + res_row[ct]] =
             res_row[ct] < Mq ? -(m_ref[ct] + log2f(l_run[ct])) : kPadNegL;
     }
-  } else {
+  } else if (MODE == 1) {
     const float inv = 1.0f / (float)Mq;
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct) {
@@ -709,14 +822,41 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   const int tilesA = qblocks * wl.n_splits;
   score_mfma_kernel<0><<<dim3(units8 * tilesA), dim3(kThreads), ldsA, st>>>(
       kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
-      nullptr, bias, scores);
+      nullptr, bias, scores, nullptr, 0);
   if (between) (void)hipEventRecord(between, st);  // right behind sweep A: the stage is that kernel alone
   if (wl.n_splits > 1)  // with one split sweep A has written -L itself
     score_bias_kernel<<<dim3(b.n_units), dim3(256), 0, st>>>(kp, wl.n_splits, wl.mq_pad, rowstat, bias);
   const int tilesB = (b.max_unit_len + kResRows - 1) / kResRows * wl.q_splits;
   score_mfma_kernel<1><<<dim3(units8 * tilesB), dim3(kThreads), ldsB, st>>>(
       kp, b.n_units, tilesB, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
-      bias, nullptr, scores);
+      bias, nullptr, scores, nullptr, 0);
+  return hipGetLastError();
+}
+
+bool score_parts_fits(const KParams& kp, const Batch& b, const Workspace& wl) {
+  return score_uses_mfma(kp) && wl.n_splits == 1 && wl.parts_pitch > 0 && b.max_unit_len <= wl.parts_pitch;
+}
+
+// Both scoring sweeps in one launch (short units, one key split): writes, for every unit,
+// ceil(W*G / 64) partial column sums per key, `parts[unit][part][key]` with row pitch
+// wl.parts_pitch; score[key] = (sum of the parts in order) / (W*G).
+hipError_t launch_score_parts(const KParams& kp, const Batch& b, const Workspace& wl, char* ws,
+                              hipStream_t st) {
+  if (!score_parts_fits(kp, b, wl)) return hipErrorInvalidValue;
+  static bool attr_set = false;
+  const size_t lds = (size_t)kDepth * kStageBytes + kResRows * sizeof(float);
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<2>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int units8 = (b.n_units + 7) / 8 * 8;
+  const int qblocks = (kp.Mq + kResRows - 1) / kResRows;
+  score_mfma_kernel<2><<<dim3(units8 * qblocks), dim3(kThreads), lds, st>>>(
+      kp, b.n_units, qblocks, 1, wl.split_len, 1, wl.mq_pad, b.row_off,
+      static_cast<const uint16_t*>(b.K), static_cast<const uint16_t*>(b.Q), nullptr, nullptr, nullptr,
+      nullptr, reinterpret_cast<float*>(ws + wl.parts), wl.parts_pitch);
   return hipGetLastError();
 }
 

@@ -49,7 +49,8 @@ __device__ inline float sumsq8(const uint4& v) {
 template <int D>
 __global__ __launch_bounds__(kTailThreads) void tail_small_kernel(
     KParams kp, const int64_t* __restrict__ row_off, const int32_t* __restrict__ prefix_len,
-    const float* __restrict__ scores, const uint16_t* __restrict__ K,
+    float* scores, const float* __restrict__ parts, int n_parts, int parts_pitch,
+    const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ V, const int32_t* __restrict__ in_count,
     uint16_t* __restrict__ K_out, uint16_t* __restrict__ V_out, int out_stride,
     int32_t* __restrict__ out_len, int32_t* __restrict__ out_src, float* __restrict__ out_mass,
@@ -83,7 +84,27 @@ __global__ __launch_bounds__(kTailThreads) void tail_small_kernel(
   const int i = tid;
 
   // ---- 1. ranks
-  ckey[i] = i < N ? (((unsigned long long)score_key(s[i])) << 32) | (unsigned)(~i) : 0ull;
+  float my_s = 0.f;
+  if (i < N) {
+    if (parts) {
+      // the one-launch scoring left partial column sums: add them in order, scale, publish
+      const float* pp = parts + (size_t)u * n_parts * parts_pitch + i;
+      float tot = 0.f;
+      for (int q0 = 0; q0 < n_parts; q0 += 8) {  // eight loads in flight, added in order
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = pp[(size_t)min(q0 + e, n_parts - 1) * parts_pitch];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (q0 + e < n_parts) tot += v[e];
+      }
+      my_s = tot * (1.0f / (float)kp.Mq);
+      scores[row0 + i] = my_s;  // read again below by other threads, behind barriers
+    } else {
+      my_s = s[i];
+    }
+  }
+  ckey[i] = i < N ? (((unsigned long long)score_key(my_s)) << 32) | (unsigned)(~i) : 0ull;
   rank_s[i] = 0;
   __syncthreads();
   {
@@ -400,15 +421,16 @@ bool tail_small_fits(const KParams& kp, const Batch& b) {
   return kp.dtype == CASK_BF16 && kp.geometry == 0 && b.max_unit_len <= kTailRows && kp.B <= kTailRows;
 }
 
-hipError_t launch_tail_small(const KParams& kp, const Batch& b, const float* scores,
-                             const int32_t* in_count, void* K_out, void* V_out, int out_stride,
+hipError_t launch_tail_small(const KParams& kp, const Batch& b, float* scores, const float* parts,
+                             int n_parts, int parts_pitch, const int32_t* in_count, void* K_out, void* V_out, int out_stride,
                              int32_t* out_len, int32_t* out_src, float* out_mass,
                              int32_t* out_count, int32_t* assign, int32_t* status,
                              hipStream_t st) {
   if (!tail_small_fits(kp, b)) return hipErrorInvalidValue;
 #define CASK_TAIL(D)                                                                             \
   tail_small_kernel<D><<<dim3(b.n_units), dim3(kTailThreads), 0, st>>>(                          \
-      kp, b.row_off, b.prefix_len, scores, static_cast<const uint16_t*>(b.K),                    \
+      kp, b.row_off, b.prefix_len, scores, parts, n_parts, parts_pitch,                          \
+      static_cast<const uint16_t*>(b.K),                                                         \
       static_cast<const uint16_t*>(b.V), in_count, static_cast<uint16_t*>(K_out),                \
       static_cast<uint16_t*>(V_out), out_stride, out_len, out_src, out_mass, out_count, assign,  \
       status)

@@ -218,7 +218,12 @@ def full_check(c: dict, p: cask.Params, expect_folds: bool = False, n_threads: i
     torch.cuda.synchronize()
     got_e = gpu_outputs(out_e, p)
     check_scores(got_e["scores"], want["scores"], row_off)
-    assert np.array_equal(got_e["scores"], s_gpu.cpu().numpy()), "scoring is not deterministic"
+    # the same call again gives the same bits (short units score inside the event by another
+    # route than cask_score, so the two are compared to the tolerance only, above)
+    out_e2 = cask.compress(b)
+    torch.cuda.synchronize()
+    assert np.array_equal(got_e["scores"], out_e2.scores.cpu().numpy()), "scoring is not deterministic"
+    del out_e2
     assert np.array_equal(got_e["out_len"], want["out_len"])
     diff_units = 0
     for u in range(n_units):
