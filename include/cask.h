@@ -154,8 +154,9 @@ int cask_consolidate(const cask_params* params, const cask_batch* batch, const f
 
 /* The whole event (Sections 2.1-2.4).  (A batch whose units all have at most 1024 rows, with
  * B <= 1024, bf16 and the cosine geometry, takes a one-launch path after scoring; results and
- * tie rules are the same.  The environment variable CASK_FUSED_TAIL=0, read at every call,
- * switches that path off.)
+ * tie rules are the same; with d = 128 the two scoring sweeps of such a batch are one launch
+ * as well.  The environment variables CASK_FUSED_TAIL=0 and CASK_FUSED_SCORE=0, read at every
+ * call, switch these paths off.)
  *   K_out, V_out [n_units, B, d]  rows [0, out_len[u]) in ascending source order; a
  *                                 representative sits at its seed's position; kept tokens
  *                                 are bit-identical copies; rows >= out_len[u] untouched
@@ -235,7 +236,8 @@ int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, c
  * roles, which cask_compress runs in the same kernel), 3 index roles (zero in cask_compress),
  * 4 similarity, 5 gather merged donors, 6 emit.  A batch of short units (every unit at most
  * 1024 rows, B <= 1024, bf16, cosine geometry) runs stages 2-6 as one kernel: its time is
- * reported as stage 2 and stages 3-6 read as the cost of an empty event pair.
+ * reported as stage 2 and stages 3-6 read as the cost of an empty event pair; with d = 128
+ * stages 0 and 1 are one kernel too, reported as stage 0.
  * cask_timing_enable(n > 0) creates events for the next n compress calls (n <= 4096) and
  * switches recording on; n <= 0 switches it off and destroys them.  Calls beyond n are not
  * recorded.  cask_timing_read waits for the recorded calls, writes the summed milliseconds
