@@ -69,7 +69,12 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
   };
   const size_t rows = (size_t)total_rows, units = (size_t)n_units;
   // one-launch scoring of short units: partial column sums, one row per 64 window rows
-  w.parts_pitch = (max_unit_len <= 1024 && n_splits == 1) ? (int)align_up((size_t)(max_unit_len > 0 ? max_unit_len : 1), 64) : 0;
+  // (reserved whatever the unit length, capped at the longest unit that path takes, so that a
+  // workspace sized for longer units also serves a batch of shorter ones)
+  {
+    const size_t len64 = align_up((size_t)(max_unit_len > 0 ? max_unit_len : 1), 64);
+    w.parts_pitch = (int)(len64 < 1024 ? len64 : 1024);
+  }
   w.parts = take(units * (size_t)((kp.Mq + 63) / 64) * (size_t)w.parts_pitch * sizeof(float));
   w.rowstat = take(units * n_splits * w.mq_pad * sizeof(float2));
   w.bias = take(units * w.mq_pad * sizeof(float));

@@ -93,6 +93,20 @@ def test_workspace_size_is_sane(cask):
     assert cask.workspace_bytes(cask.Params(dtype=7), 1, 10, 10) == 0
 
 
+def test_workspace_size_grows_with_every_argument(cask):
+    """A workspace sized for longer units, more units or more rows also serves a smaller batch:
+    the entry points lay it out again from the batch they get and only compare sizes."""
+    for kw in (dict(q_per_kv=7, budget=384), dict(q_per_kv=1, window=16, budget=2048), dict(head_dim=64, budget=100)):
+        p = cask.Params(**kw)
+        prev = 0
+        for L in sorted({p.window, 64, 300, 512, 1000, 1024, 1025, 3000, 4608, 9000, 40000, 200000}):
+            n = cask.workspace_bytes(p, 64, 64 * 200000, L)
+            assert n >= prev > -1, (kw, L)
+            prev = n
+        assert cask.workspace_bytes(p, 65, 64 * 200000, 9000) >= cask.workspace_bytes(p, 64, 64 * 200000, 9000)
+        assert cask.workspace_bytes(p, 64, 65 * 200000, 9000) >= cask.workspace_bytes(p, 64, 64 * 200000, 9000)
+
+
 def test_host_validation_needs_no_gpu(cask):
     """Bad arguments are refused before any HIP call; an empty batch is a no-op."""
     lib = cask.load()
