@@ -724,6 +724,12 @@ def test_step_conserves_token_counts_and_places_units_by_stride(oracle):
                                    in_count=cnt[sl])
         np.testing.assert_array_equal(out["K_out"][u, :L], one["K_out"][0, :L])   # stride only moves rows
         assert not out["K_out"][u, L:].any()
+    # counts ride along: they weigh a fold only where the scores carry no mass, so other counts
+    # change out_count and nothing else
+    other = oracle.compress_step(p, ro, np.array(Ps), K, V, Q, in_count=3 * cnt + 1, out_stride_rows=B + W)
+    for key in ("K_out", "V_out", "out_src", "out_mass", "assign", "status", "scores"):
+        np.testing.assert_array_equal(out[key], other[key])
+    assert not np.array_equal(out["out_count"], other["out_count"])
     with pytest.raises(ValueError):
         oracle.compress_step(p, ro, np.array(Ps), K, V, Q, in_count=np.zeros(sum(lens), dtype=np.int32))
     with pytest.raises(ValueError):
