@@ -594,14 +594,17 @@ def test_zero_mass_group_and_exact_fold():
 
 # ------------------------------------------------------------------ determinism, errors, edges
 
-def test_two_runs_are_bitwise_identical():
-    w = caches.scaled(W["cfg2"], n_layers=1, decode=2500)
+@pytest.mark.parametrize("decode", [2500, 700])
+def test_two_runs_are_bitwise_identical(decode):
+    """Long units (general kernels) and short ones (one-launch scoring and tail, with many
+    folds): every output of the event has the same bits on every run."""
+    w = caches.scaled(W["cfg2"], n_layers=1, decode=decode)
     c = caches.make(w, seed=21)
     p = parity.params_of(w, sim_threshold=0.2)
     b = parity.to_device(c, p)
     a = parity.gpu_outputs(cask.compress(b), p)
     torch.cuda.synchronize()
-    for _ in range(2):
+    for _ in range(3):
         o = parity.gpu_outputs(cask.compress(b), p)
         for k in a:
             assert np.array_equal(a[k], o[k]), k
