@@ -103,6 +103,11 @@ def test_bf16_window_rows_shared_by_two_workgroups(causal):
                     sim_threshold=0.5, causal=causal)
     st = parity.full_check(c, p)
     _note((causal, st))
+    # the same window on short units only: both sweeps in one launch, nine 64-row parts of
+    # which the last is partly empty
+    c = _ragged_bf16([75, 256, 300, 777, 1000], [0, 100, 0, 333, 40], G=7, Wn=75, seed=14)
+    st = parity.full_check(c, p)
+    _note((causal, "short", st))
 
 
 def test_bf16_single_query_head_small_window():
