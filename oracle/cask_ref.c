@@ -644,3 +644,51 @@ int cask_ref_group_diagnostics(const cask_ref_params* p, int32_t n_units, const 
   }
   return 0;
 }
+
+int cask_ref_attend(const cask_ref_params* p, int32_t n_units, const void* Q, const void* K_c,
+                    const void* V_c, int32_t stride_rows, const int32_t* len, const int32_t* count,
+                    int32_t count_pitch, double* out) {
+  if (!p || !Q || !K_c || !V_c || !len || !out || n_units < 0) return -1;
+  if (check_shape(p) != 0) return -1;
+  const int d = p->head_dim, G = p->q_per_kv;
+  const double scale = p->softmax_scale != 0.0f ? (double)p->softmax_scale : 1.0 / sqrt((double)d);
+  for (int32_t u = 0; u < n_units; ++u) {
+    const int32_t L = len[u];
+    if (L < 1 || L > stride_rows || (count && L > count_pitch)) return -1;
+    double* logit = (double*)malloc(sizeof(double) * (size_t)L);
+    if (!logit) return -2;
+    for (int g = 0; g < G; ++g) {
+      const int64_t qrow = ((int64_t)u * G + g) * d;
+      double top = -INFINITY;
+      for (int32_t t = 0; t < L; ++t) {
+        const int64_t krow = ((int64_t)u * stride_rows + t) * d;
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c) dot += load_elem(Q, p->dtype, qrow + c) * load_elem(K_c, p->dtype, krow + c);
+        double x = scale * dot;
+        if (count) {
+          const int32_t n = count[(int64_t)u * count_pitch + t];
+          if (n < 1) {
+            free(logit);
+            return -1;
+          }
+          x += log((double)n);
+        }
+        logit[t] = x;
+        if (x > top) top = x;
+      }
+      double den = 0.0;
+      for (int32_t t = 0; t < L; ++t) {
+        logit[t] = exp(logit[t] - top);
+        den += logit[t];
+      }
+      for (int c = 0; c < d; ++c) {
+        double acc = 0.0;
+        for (int32_t t = 0; t < L; ++t)
+          acc += logit[t] * load_elem(V_c, p->dtype, ((int64_t)u * stride_rows + t) * d + c);
+        out[qrow + c] = acc / den;
+      }
+    }
+    free(logit);
+  }
+  return 0;
+}

@@ -308,3 +308,27 @@ def group_diagnostics(p: Params, row_off, K, scores, assign, K_out):
     if rc:
         raise ValueError(f"cask_ref_group_diagnostics: {rc}")
     return disp, lost
+
+
+def attend(p: Params, Q, K_c, V_c, length, count=None) -> np.ndarray:
+    """One decode step's attention over a compressed cache with the proportional (ln count)
+    bias; Q [n_units, G, d], K_c / V_c [n_units, stride, d], length [n_units], count
+    [n_units, pitch] or None.  Returns float64 [n_units, G, d]."""
+    Q, K_c, V_c = (np.ascontiguousarray(x) for x in (Q, K_c, V_c))
+    n_units = K_c.shape[0]
+    assert Q.shape == (n_units, p.q_per_kv, p.head_dim) and K_c.shape == V_c.shape and K_c.shape[2] == p.head_dim
+    assert Q.dtype == K_c.dtype == V_c.dtype == _np_elem(p.dtype)
+    length = np.ascontiguousarray(length, dtype=np.int32)
+    pitch = 0
+    if count is not None:
+        count = np.ascontiguousarray(count, dtype=np.int32)
+        assert count.ndim == 2 and count.shape[0] == n_units
+        pitch = count.shape[1]
+    out = np.zeros((n_units, p.q_per_kv, p.head_dim), dtype=np.float64)
+    cp = p.c()
+    rc = lib().cask_ref_attend(C.byref(cp), C.c_int32(n_units), _ptr(Q), _ptr(K_c), _ptr(V_c),
+                               C.c_int32(K_c.shape[1]), _ptr(length),
+                               _ptr(count) if count is not None else None, C.c_int32(pitch), _ptr(out))
+    if rc:
+        raise ValueError(f"cask_ref_attend: {rc}")
+    return out

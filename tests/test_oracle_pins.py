@@ -926,3 +926,85 @@ def test_group_diagnostics_on_events_against_library_norms(oracle):
     out = oracle.compress(p, ro, pl, K, V, Q)
     disp, lost = oracle.group_diagnostics(p, ro, K, out["scores"], out["assign"], out["K_out"])
     assert disp[0] == 0.0 and lost[0] == 0.0
+
+
+# ------------------------------------------------------------------ consumer side: proportional attention
+
+def test_attend_is_library_softmax_attention(oracle):
+    """Without counts (or with all ones): scipy's softmax and a numpy matmul; fp32 and bf16
+    inputs, a row stride, ragged lengths, a custom scale."""
+    rng = np.random.default_rng(81)
+    for dtype, scale in (("f32", 0.0), ("bf16", 0.0), ("f32", 0.21)):
+        d, G, stride = 16, 3, 40
+        lens = np.array([1, 17, 40], dtype=np.int32)
+        Q = rng.standard_normal((3, G, d)).astype(np.float32)
+        K = rng.standard_normal((3, stride, d)).astype(np.float32)
+        V = rng.standard_normal((3, stride, d)).astype(np.float32)
+        p = f32_params(oracle, head_dim=d, q_per_kv=G, window=1, budget=stride, softmax_scale=scale)
+        if dtype == "bf16":
+            p.dtype = oracle.BF16
+            Qb, Kb, Vb = to_bf16_bits(Q), to_bf16_bits(K), to_bf16_bits(V)
+            Q, K, V = from_bf16_bits(Qb), from_bf16_bits(Kb), from_bf16_bits(Vb)
+            got = oracle.attend(p, Qb, Kb, Vb, lens)
+            got1 = oracle.attend(p, Qb, Kb, Vb, lens, count=np.ones((3, stride), dtype=np.int32))
+        else:
+            got = oracle.attend(p, Q, K, V, lens)
+            got1 = oracle.attend(p, Q, K, V, lens, count=np.ones((3, stride), dtype=np.int32))
+        sc = float(np.float32(scale)) if scale else 1.0 / np.sqrt(d)     # the scale is an fp32 parameter
+        for u in range(3):
+            L = int(lens[u])
+            w = scipy_softmax(sc * Q[u].astype(np.float64) @ K[u, :L].astype(np.float64).T, axis=-1)
+            np.testing.assert_allclose(got[u], w @ V[u, :L].astype(np.float64), rtol=1e-12, atol=1e-14)
+        np.testing.assert_array_equal(got, got1)
+        np.testing.assert_allclose(got[0], np.broadcast_to(V[0, 0].astype(np.float64), (G, d)), rtol=1e-15)  # one row
+
+
+def test_attend_with_counts_equals_attention_over_repeated_rows(oracle):
+    """What fixes the ln(count) rule: a cache in which row t occurs n_t times gives the same
+    output as the cache with every row once and count n_t.  Also: invalid counts are refused."""
+    rng = np.random.default_rng(82)
+    d, G, L = 8, 2, 9
+    Q = rng.standard_normal((1, G, d)).astype(np.float32)
+    K = rng.standard_normal((1, L, d)).astype(np.float32)
+    V = rng.standard_normal((1, L, d)).astype(np.float32)
+    n = rng.integers(1, 6, L).astype(np.int32)
+    rep = np.repeat(np.arange(L), n)
+    rng.shuffle(rep)                                                    # order of the rows does not matter
+    p = f32_params(oracle, head_dim=d, q_per_kv=G, window=1, budget=64)
+    long = oracle.attend(p, Q, K[:, rep], V[:, rep], np.array([len(rep)]))
+    short = oracle.attend(p, Q, K, V, np.array([L]), count=n[None, :])
+    np.testing.assert_allclose(short, long, rtol=1e-13, atol=1e-15)
+    plain = oracle.attend(p, Q, K, V, np.array([L]))
+    assert np.abs(plain - long).max() > 1e-3                            # the counts do matter
+    with pytest.raises(ValueError):
+        oracle.attend(p, Q, K, V, np.array([L]), count=np.zeros((1, L), dtype=np.int32))
+    with pytest.raises(ValueError):
+        oracle.attend(p, Q, K, V, np.array([L + 1]))
+
+
+def test_attend_after_a_fold_of_exact_duplicates_is_lossless(oracle):
+    """End to end with the event: when the folded donors are exact copies of their seed, the
+    compressed cache with its counts attends exactly like the cache of kept and folded rows."""
+    rng = np.random.default_rng(83)
+    d, W, G, B = 16, 4, 2, 24
+    N, P = 60, 0
+    K = rng.standard_normal((N, d)).astype(np.float32)
+    V = rng.standard_normal((N, d)).astype(np.float32)
+    s = (rng.random(N).astype(np.float32) + 0.1)
+    p = f32_params(oracle, head_dim=d, window=W, q_per_kv=G, budget=B, core=4, sim_threshold=0.999999)
+    Qw = rng.standard_normal((1, W, G, d)).astype(np.float32)
+    ro, pl = np.array([0, N]), np.array([P])
+    # make every donor an exact copy of some seed (roles come from the scores alone)
+    role = _roles_for(oracle, p, ro, pl, s)
+    seeds, donors = np.flatnonzero(role == oracle.SEED), np.flatnonzero(role == oracle.DONOR)
+    assert len(seeds) > 2 and len(donors) > 10
+    src = rng.choice(seeds, size=len(donors))
+    K[donors], V[donors] = K[src], V[src]
+    out = oracle.compress_step(p, ro, pl, K, V, Qw, scores=s)
+    L = int(out["out_len"][0])
+    assert (out["assign"][donors] >= 0).all() and L == B
+    q = rng.standard_normal((1, G, d)).astype(np.float32)
+    comp = oracle.attend(p, q, out["K_out"], out["V_out"], out["out_len"], count=out["out_count"])
+    alive = out["assign"] >= 0                                           # kept rows and folded donors
+    full = oracle.attend(p, q, K[alive][None], V[alive][None], np.array([int(alive.sum())]))
+    np.testing.assert_allclose(comp, full, rtol=1e-5, atol=1e-6)        # K_out, V_out are fp32-rounded means
