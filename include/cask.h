@@ -229,6 +229,25 @@ int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, c
                            const int32_t* assign, const void* K_out, int32_t out_stride_rows,
                            float* dispersion, float* lost_mass, void* hip_stream);
 
+/* Consumer side: one decode step's attention over a compressed cache.  The folds preserve
+ * group mass (Section 2.4); how attention uses a representative is left open by the paper.
+ * The reading taken here is proportional attention: a row standing for n original tokens
+ * enters the softmax with n times its weight,
+ *     p_t = softmax_t( scale * <q, k_t> + ln(count_t) ),   out = sum_t p_t v_t,
+ * exact when the n tokens had the same key and value, plain attention for count == NULL.
+ *   Q     [n_units, G, d]               device, cache dtype: the step's queries of the G heads
+ *   K_c, V_c [n_units, stride_rows, d]  device, cache dtype: rows [0, len[u]) are used
+ *   len   [n_units] device (cask_compress's out_len); clamped to [0, stride_rows], 0 gives zeros
+ *   count [n_units, count_pitch] device or NULL (cask_compress_step's out_count; values < 1
+ *         are not validated and count as 1)
+ *   out   [n_units, G, d]               device, cache dtype (fp32 accumulation, rounded once)
+ * All data pointers 16-byte aligned.  scale = softmax_scale, 1/sqrt(d) when that is 0.  Needs
+ * no workspace.  Decoded tokens appended behind the compressed rows attend the same way (their
+ * count is 1): pass the buffer with its row stride and the enlarged len. */
+int cask_attend(const cask_params* params, int32_t n_units, const void* Q, const void* K_c,
+                const void* V_c, int32_t stride_rows, const int32_t* len, const int32_t* count,
+                int32_t count_pitch, void* out, void* hip_stream);
+
 /* Measurement aid (not part of the method): per-stage timing of cask_compress with HIP
  * events recorded on the caller's stream between its kernels.  Stage order: 0 score sweep A
  * (row statistics), 1 score sweep B (column mass; with the small kernel that combines the row

@@ -26,7 +26,7 @@ ST_ACTIVE, ST_IDENTITY, ST_PREFIX_BUDGET_EXHAUSTED, ST_MERGE_INACTIVE = 0, 1, 2,
 
 EXPORTS = ["cask_plan", "cask_workspace_bytes", "cask_score", "cask_prefix_evict",
            "cask_partition", "cask_consolidate", "cask_compress", "cask_compress_step",
-           "cask_mass_diagnostics", "cask_group_diagnostics", "cask_strerror",
+           "cask_mass_diagnostics", "cask_group_diagnostics", "cask_attend", "cask_strerror",
            "cask_timing_enable", "cask_timing_enable_stages", "cask_timing_read"]
 STAGES = ["score_rows", "score_cols", "select", "index_roles", "similarity", "gather", "emit"]
 
@@ -299,6 +299,27 @@ def group_diagnostics(b: Batch, scores: torch.Tensor, assign: torch.Tensor, K_ou
     if rc:
         raise CaskError("cask_group_diagnostics", rc)
     return disp, lost
+
+
+def attend(p: Params, Q: torch.Tensor, K_c: torch.Tensor, V_c: torch.Tensor, length: torch.Tensor,
+           count: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One decode step's attention over a compressed cache (cask_attend): Q [n_units, G, d],
+    K_c / V_c [n_units, stride, d], length [n_units] int32, count [n_units, pitch] int32 or None."""
+    n_units = K_c.shape[0]
+    assert Q.is_contiguous() and K_c.is_contiguous() and V_c.is_contiguous() and K_c.shape == V_c.shape
+    assert Q.shape == (n_units, p.q_per_kv, p.head_dim) and K_c.shape[2] == p.head_dim
+    assert length.dtype == torch.int32 and length.numel() == n_units
+    if count is not None:
+        assert count.dtype == torch.int32 and count.dim() == 2 and count.shape[0] == n_units and count.is_contiguous()
+    if out is None:
+        out = torch.empty_like(Q)
+    cp = p.c()
+    rc = load().cask_attend(C.byref(cp), C.c_int32(n_units), _dptr(Q), _dptr(K_c), _dptr(V_c),
+                            C.c_int32(K_c.shape[1]), _dptr(length), _dptr(count) if count is not None else None,
+                            C.c_int32(count.shape[1] if count is not None else 0), _dptr(out), _stream())
+    if rc:
+        raise CaskError("cask_attend", rc)
+    return out
 
 
 class Outputs:

@@ -350,6 +350,23 @@ int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, c
                                   lost_mass, static_cast<hipStream_t>(hip_stream)));
 }
 
+int cask_attend(const cask_params* params, int32_t n_units, const void* Q, const void* K_c,
+                const void* V_c, int32_t stride_rows, const int32_t* len, const int32_t* count,
+                int32_t count_pitch, void* out, void* hip_stream) {
+  KParams kp;
+  int rc = resolve_params(params, &kp, false);
+  if (rc) return rc;
+  if (n_units < 0) return CASK_EINVAL;
+  if (n_units == 0) return CASK_OK;
+  if (!Q || !K_c || !V_c || !len || !out || stride_rows < 1) return CASK_EINVAL;
+  if (count && count_pitch < 1) return CASK_EINVAL;
+  if (((reinterpret_cast<uintptr_t>(Q) | reinterpret_cast<uintptr_t>(K_c) | reinterpret_cast<uintptr_t>(V_c) |
+        reinterpret_cast<uintptr_t>(out)) & 15u) != 0)
+    return CASK_EINVAL;
+  return dev_rc(launch_attend(kp, n_units, Q, K_c, V_c, stride_rows, len, count, count_pitch, out,
+                              static_cast<hipStream_t>(hip_stream)));
+}
+
 int cask_compress(const cask_params* params, const cask_batch* batch, void* K_out, void* V_out,
                   int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
                   float* scores, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream) {

@@ -224,6 +224,9 @@ hipError_t launch_tail_small(const KParams& kp, const Batch& b, float* scores, c
                              int32_t* out_len, int32_t* out_src, float* out_mass,
                              int32_t* out_count, int32_t* assign, int32_t* status,
                              hipStream_t st);
+hipError_t launch_attend(const KParams& kp, int n_units, const void* Q, const void* Kc, const void* Vc,
+                         int stride, const int32_t* len, const int32_t* count, int count_pitch,
+                         void* out, hipStream_t st);
 hipError_t launch_group_diag(const KParams& kp, const Batch& b, const float* scores,
                              const int32_t* assign, const void* K_out, int out_stride,
                              float* dispersion, float* lost_mass, hipStream_t st);

@@ -228,3 +228,26 @@ def test_group_diagnostics_validates_on_the_host(cask):
     empty = cask.binding._Batch(0, None, None, None, None, None, None, None)
     assert lib.cask_group_diagnostics(C.byref(ok), C.byref(empty), None, None, None, C.c_int32(B), None,
                                       None, None) == cask.binding.OK
+
+
+def test_attend_validates_on_the_host(cask):
+    lib = cask.load()
+    ok = cask.Params().c()
+    fake = C.c_void_p(256)
+
+    def rc(n=3, Q=fake, K=fake, V=fake, stride=100, length=fake, count=None, pitch=0, out=fake, params=ok):
+        return lib.cask_attend(C.byref(params) if params is not None else None, C.c_int32(n), Q, K, V,
+                               C.c_int32(stride), length, count, C.c_int32(pitch), out, None)
+
+    assert rc(n=0) == cask.binding.OK                       # empty batch: nothing is touched
+    assert rc(n=-1) == cask.binding.EINVAL
+    assert rc(Q=None) == cask.binding.EINVAL
+    assert rc(K=None) == cask.binding.EINVAL
+    assert rc(V=None) == cask.binding.EINVAL
+    assert rc(out=None) == cask.binding.EINVAL
+    assert rc(length=None) == cask.binding.EINVAL
+    assert rc(stride=0) == cask.binding.EINVAL
+    assert rc(K=C.c_void_p(264)) == cask.binding.EINVAL     # not 16-byte aligned
+    assert rc(count=fake, pitch=0) == cask.binding.EINVAL
+    assert rc(params=None) == cask.binding.EINVAL
+    assert rc(params=cask.Params(head_dim=100).c()) == cask.binding.EINVAL

@@ -339,6 +339,73 @@ def test_random_longer_batches(seed):
                       **{k: v for k, v in kw.items() if k != "band_weight"}), st))
 
 
+def _attend_tol(p):
+    return (2e-5, 2e-6) if p.dtype == cask.F32 else (1.5e-2, 2e-3)
+
+
+@pytest.mark.parametrize("case", ["bf16_d128_g7", "bf16_d64_g2", "f32_d128_g5", "f32_d64_g1"])
+def test_attend_over_a_compressed_cache(case):
+    """cask_attend against the oracle: ragged lengths inside a row stride (one row, fewer rows
+    than groups, thousands), with and without counts, more query heads than one pass takes."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(91)
+    f32 = case.startswith("f32")
+    d = 128 if "d128" in case else 64
+    G = int(case.split("_g")[1])
+    stride = 2300
+    lens = np.array([1, 7, 16, 17, 300, 2300, 1111], dtype=np.int32)
+    n = len(lens)
+    dt = torch.float32 if f32 else torch.bfloat16
+    Q = (1.5 * torch.randn(n, G, d, generator=torch.Generator().manual_seed(1))).to(dt).to(dev)
+    Kc = torch.randn(n, stride, d, generator=torch.Generator().manual_seed(2)).to(dt).to(dev)
+    Vc = torch.randn(n, stride, d, generator=torch.Generator().manual_seed(3)).to(dt).to(dev)
+    count = rng.integers(1, 40, (n, stride + 5)).astype(np.int32)
+    count[rng.random(count.shape) < 0.7] = 1
+    p = cask.Params(dtype=cask.F32 if f32 else cask.BF16, head_dim=d, q_per_kv=G, window=1, budget=stride)
+    rp = parity.ref_params(p)
+    Qh, Kh, Vh = caches.host_bits(Q), caches.host_bits(Kc), caches.host_bits(Vc)
+    rtol, atol = _attend_tol(p)
+    for cnt in (None, count):
+        want = ref.attend(rp, Qh, Kh, Vh, lens, count=cnt)
+        got = cask.attend(p, Q, Kc, Vc, torch.from_numpy(lens).to(dev),
+                          count=None if cnt is None else torch.from_numpy(cnt).to(dev))
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(got.float().cpu().numpy().astype(np.float64), want, rtol=rtol, atol=atol)
+    again = cask.attend(p, Q, Kc, Vc, torch.from_numpy(lens).to(dev), count=torch.from_numpy(count).to(dev))
+    torch.cuda.synchronize()
+    assert torch.equal(got, again)                                       # same bits every run
+
+
+def test_attend_on_the_output_of_an_event():
+    """The event's own outputs as the cache: K_out, V_out with their row stride, out_len and
+    out_count from cask_compress_step, then one decode step's attention with and without the
+    count bias, against the oracle on the oracle's event."""
+    dev = torch.device("cuda:0")
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=4, prefix=96, decode=416, budget=384)
+    c = caches.make(w, seed=61)
+    p = parity.params_of(w, sim_threshold=0.3)
+    rp = parity.ref_params(p)
+    row_off, prefix_len, K, V, Q = parity.host_arrays(c)
+    n_units, S = len(row_off) - 1, 512
+    want = ref.compress_step(rp, row_off, prefix_len, K, V, Q, out_stride_rows=S)
+    b = parity.to_device(c, p)
+    out = cask.Outputs(b)
+    Ko = torch.zeros(n_units, S, w.head_dim, dtype=torch.bfloat16, device=dev)
+    Vo = torch.zeros_like(Ko)
+    oc = torch.zeros(n_units, p.budget, dtype=torch.int32, device=dev)
+    cask.compress_step(b, Ko, Vo, out, out_count=oc, scores=torch.from_numpy(want["scores"]).to(dev))
+    torch.cuda.synchronize()
+    assert np.array_equal(oc.cpu().numpy(), want["out_count"]) and int(want["out_count"].max()) > 1
+    q = (2.0 * torch.randn(n_units, w.q_per_kv, w.head_dim, generator=torch.Generator().manual_seed(4))).to(torch.bfloat16).to(dev)
+    rtol, atol = _attend_tol(p)
+    for cnt_g, cnt_w in ((oc, want["out_count"]), (None, None)):
+        ref_o = ref.attend(rp, caches.host_bits(q), want["K_out"], want["V_out"], want["out_len"], count=cnt_w)
+        got = cask.attend(p, q, Ko, Vo, out.out_len, count=cnt_g)
+        torch.cuda.synchronize()
+        # (the library's K_out / V_out differ from the oracle's by bf16 rounding of the folds)
+        np.testing.assert_allclose(got.float().cpu().numpy().astype(np.float64), ref_o, rtol=3e-2, atol=4e-3)
+
+
 def test_consolidate_with_caller_roles_naming_many_seeds():
     """cask_consolidate takes any role array: here far more seeds than the plan would ever
     produce, so the seeds of a unit do not fit one LDS block."""
