@@ -239,7 +239,7 @@ int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, c
  *   K_c, V_c [n_units, stride_rows, d]  device, cache dtype: rows [0, len[u]) are used
  *   len   [n_units] device (cask_compress's out_len); clamped to [0, stride_rows], 0 gives zeros
  *   count [n_units, count_pitch] device or NULL (cask_compress_step's out_count; values < 1
- *         are not validated and count as 1)
+ *         are not validated and count as 1, and so do rows at or behind count_pitch)
  *   out   [n_units, G, d]               device, cache dtype (fp32 accumulation, rounded once)
  * All data pointers 16-byte aligned.  scale = softmax_scale, 1/sqrt(d) when that is 0.  Needs
  * no workspace.  Decoded tokens appended behind the compressed rows attend the same way (their

@@ -4,6 +4,8 @@
 // which a fold of identical tokens is lossless).
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "cask.h"
 #include "cask_common.h"
 
@@ -72,7 +74,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
         const int t = min(t0 + a * kAttGroups, L - 1);
         kr[a] = *reinterpret_cast<const Raw*>(Ku + (size_t)t * D + gl * EPL);
         vr[a] = *reinterpret_cast<const Raw*>(Vu + (size_t)t * D + gl * EPL);
-        cn[a] = cu ? cu[t] : 1;
+        cn[a] = cu ? cu[min(t, count_pitch - 1)] : 1;
+        if (t >= count_pitch) cn[a] = 1;
       }
 #pragma unroll
       for (int a = 0; a < kAttAhead; ++a) {
@@ -151,7 +154,213 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
   }
 }
 
+
+// ------------------------------------------------------------------ bf16 path: logits on MFMA
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kAttWaves = 8;  // waves of the MFMA workgroup, two per SIMD
+
+// One workgroup per unit, one tile of 32 cache rows per wave and step, tiles dealt to the waves
+// round robin.  Per tile: the logits of up to HP query heads against the 32 keys are one
+// 32x32 MFMA product (keys as rows, heads as columns, zero columns beyond HP; the two lane
+// halves hold the two halves of the head dimension, in the same order for keys and queries),
+// the lane of a head column holds its 32 logits in registers and takes the block step of the
+// online softmax (running maximum, correction factor, weights) there, the weights go through
+// LDS to the lanes that hold the value rows (D / 8 lanes per row), and those lanes add the
+// weighted rows in fp32.  Everything inside the tile loop is wave-local: no workgroup barrier.
+// The key rows of the next tile are requested as soon as the product has consumed this tile's,
+// the value rows as soon as the weighted sum has, so a wave always has a tile of loads in
+// flight.  At the end the lane groups of a wave add up, and the waves' states are merged in
+// wave order: the same bits every run.
+template <int D, int HP, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void attend_mfma_kernel(
+    KParams kp, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kc,
+    const uint16_t* __restrict__ Vc, int stride, const int32_t* __restrict__ len,
+    const int32_t* __restrict__ count, int count_pitch, uint16_t* __restrict__ out) {
+  constexpr int KS = D / 16;     // k-steps of the product
+  constexpr int LPR = D / 8;     // lanes per value row
+  constexpr int GPW = 64 / LPR;  // value rows one load instruction of a wave covers
+  constexpr int RPG = 32 / GPW;  // value rows per lane group and tile
+  __shared__ __align__(16) float bias_s[WAVES][32];
+  __shared__ __align__(16) float p_s[WAVES][32][HP];
+  __shared__ __align__(16) float corr_s[WAVES][HP < 4 ? 4 : HP];
+  __shared__ float st_m[WAVES][HP], st_l[WAVES][HP];
+  __shared__ __align__(16) float st_acc[WAVES][HP][D];
+  const int u = blockIdx.x, tid = threadIdx.x, wv = tid >> 6, lane = tid & 63;
+  const int c32 = lane & 31, hh = lane >> 5;
+  const int g = lane / LPR, gl = lane % LPR;
+  int L = len[u];
+  L = L < 0 ? 0 : (L > stride ? stride : L);
+  const int n_tiles = (L + 31) >> 5;
+  const int G = kp.G;
+  const uint16_t* Ku = Kc + (size_t)u * stride * D;
+  const uint16_t* Vu = Vc + (size_t)u * stride * D;
+  const int32_t* cu = count ? count + (size_t)u * count_pitch : nullptr;
+  const float c = kp.scale_log2;  // softmax scale * log2(e)
+  const int last = L > 0 ? L - 1 : 0;
+
+  for (int g0 = 0; g0 < G; g0 += HP) {
+    u32x4 qb[KS];
+    {
+      const bool head = c32 < HP && g0 + c32 < G;
+      const uint16_t* qp = Q + ((size_t)u * G + (head ? g0 + c32 : 0)) * D + hh * (D / 2);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        qb[ks] = *reinterpret_cast<const u32x4*>(qp + ks * 8);
+        if (!head) qb[ks] = u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+    float m_run = kNegInf, l_run = 0.f;  // of head c32, over the keys this lane has seen
+    float acc[HP][8];
+#pragma unroll
+    for (int h = 0; h < HP; ++h)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
+
+    u32x4 ka[KS], va[RPG];
+    int cn;
+    // Rows past the end are clamped to the last row (never branched over: every load is in
+    // flight at once); past the last tile all lanes read that one row.
+    auto load_keys = [&](int t) {
+      const int r = min(t * 32 + c32, last);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        ka[ks] = *reinterpret_cast<const u32x4*>(Ku + (size_t)r * D + hh * (D / 2) + ks * 8);
+      cn = cu ? cu[min(r, count_pitch - 1)] : 1;
+      if (r >= count_pitch) cn = 1;  // rows behind the counted ones stand for themselves
+    };
+    auto load_values = [&](int t) {
+#pragma unroll
+      for (int j = 0; j < RPG; ++j) {
+        const int r = min(t * 32 + j * GPW + g, last);
+        va[j] = *reinterpret_cast<const u32x4*>(Vu + (size_t)r * D + gl * 8);
+      }
+    };
+    if (L > 0) {
+      load_keys(wv);
+      load_values(wv);
+    }
+    for (int t = wv; t < n_tiles; t += WAVES) {
+      {  // bias of key c32 of the tile: log2(count), or -inf past the end of the unit
+        const float b = t * 32 + c32 < L ? (cn > 1 ? __log2f((float)cn) : 0.f) : kNegInf;
+        if (hh == 0) bias_s[wv][c32] = b;
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      f32x16 s = {0};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[ks]),
+                                                    __builtin_bit_cast(bf16x8, qb[ks]), s, 0, 0, 0);
+      // s[r] = <key (r / 4) * 8 + hh * 4 + r % 4, head c32>
+      float x[16], mx = kNegInf;
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const float4 b4 = *reinterpret_cast<const float4*>(&bias_s[wv][r4 * 8 + hh * 4]);
+        x[r4 * 4 + 0] = __builtin_fmaf(s[r4 * 4 + 0], c, b4.x);
+        x[r4 * 4 + 1] = __builtin_fmaf(s[r4 * 4 + 1], c, b4.y);
+        x[r4 * 4 + 2] = __builtin_fmaf(s[r4 * 4 + 2], c, b4.z);
+        x[r4 * 4 + 3] = __builtin_fmaf(s[r4 * 4 + 3], c, b4.w);
+      }
+      load_keys(t + WAVES);  // the product is done with this tile's key rows
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, x[r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mn = fmaxf(m_run, mx);  // finite: key 0 of a tile in range is in range
+      const float corr = __builtin_amdgcn_exp2f(m_run - mn);  // exp2(-inf) = 0 on the first tile
+      float ps = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        x[r] = __builtin_amdgcn_exp2f(x[r] - mn);
+        ps += x[r];
+      }
+      l_run = __builtin_fmaf(l_run, corr, ps);
+      m_run = mn;
+      if (c32 < HP) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) p_s[wv][(r >> 2) * 8 + hh * 4 + (r & 3)][c32] = x[r];
+        if (hh == 0) corr_s[wv][c32] = corr;
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      float cr[HP];
+#pragma unroll
+      for (int h = 0; h < HP; ++h) cr[h] = corr_s[wv][h];
+#pragma unroll
+      for (int h = 0; h < HP; ++h)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] *= cr[h];
+#pragma unroll
+      for (int j = 0; j < RPG; ++j) {
+        float pj[HP], vf[8];
+#pragma unroll
+        for (int h = 0; h < HP; ++h) pj[h] = p_s[wv][j * GPW + g][h];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          vf[2 * w] = __uint_as_float(va[j][w] << 16);
+          vf[2 * w + 1] = __uint_as_float(va[j][w] & 0xffff0000u);
+        }
+#pragma unroll
+        for (int h = 0; h < HP; ++h)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[h][e] = __builtin_fmaf(pj[h], vf[e], acc[h][e]);
+      }
+      asm volatile("" ::: "memory");  // the next tile's LDS writes stay behind these reads
+      load_values(t + WAVES);
+    }
+    // The lane groups of a wave share the wave's running maximum: their sums simply add.
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1)
+#pragma unroll
+      for (int h = 0; h < HP; ++h)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] += __shfl_xor(acc[h][e], o, 64);
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (lane < HP) {
+      st_m[wv][lane] = m_run;
+      st_l[wv][lane] = l_tot;
+    }
+    if (g == 0) {
+#pragma unroll
+      for (int h = 0; h < HP; ++h)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st_acc[wv][h][gl * 8 + e] = acc[h][e];
+    }
+    __syncthreads();
+    for (int o = tid; o < HP * D; o += WAVES * 64) {
+      const int h = o / D, ch = o % D;
+      if (g0 + h >= G) continue;
+      float top = kNegInf;
+      for (int w = 0; w < WAVES; ++w) top = fmaxf(top, st_m[w][h]);
+      float num = 0.f, den = 0.f;
+      for (int w = 0; w < WAVES; ++w) {  // wave order: the same bits every run
+        const float f = st_m[w][h] == kNegInf ? 0.f : __builtin_amdgcn_exp2f(st_m[w][h] - top);
+        den = __builtin_fmaf(st_l[w][h], f, den);
+        num = __builtin_fmaf(st_acc[w][h][ch], f, num);
+      }
+      out[((size_t)u * G + g0 + h) * D + ch] = float_to_bf16_bits(den > 0.f ? num / den : 0.f);
+    }
+    __syncthreads();
+  }
+}
+
+template <int D, int HP>
+void launch_attend_mfma(const KParams& kp, int n_units, const void* Q, const void* Kc, const void* Vc,
+                        int stride, const int32_t* len, const int32_t* count, int count_pitch,
+                        void* out, hipStream_t st) {
+  attend_mfma_kernel<D, HP, kAttWaves><<<dim3(n_units), dim3(kAttWaves * 64), 0, st>>>(
+      kp, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(Kc),
+      static_cast<const uint16_t*>(Vc), stride, len, count, count_pitch, static_cast<uint16_t*>(out));
+}
+
 }  // namespace
+
+// CASK_ATTEND_VECTOR=1 sends bf16 through the vector-ALU kernel too (for comparisons).
+static bool attend_vector_forced() {
+  const char* e = getenv("CASK_ATTEND_VECTOR");
+  return e && e[0] == '1';
+}
 
 hipError_t launch_attend(const KParams& kp, int n_units, const void* Q, const void* Kc, const void* Vc,
                          int stride, const int32_t* len, const int32_t* count, int count_pitch,
@@ -161,11 +370,23 @@ hipError_t launch_attend(const KParams& kp, int n_units, const void* Q, const vo
   attend_kernel<T, D><<<dim3(n_units), dim3(kAttThreads), 0, st>>>(                          \
       kp, static_cast<const T*>(Q), static_cast<const T*>(Kc), static_cast<const T*>(Vc),    \
       stride, len, count, count_pitch, static_cast<T*>(out))
+#define CASK_ATT_MFMA(D, HP) \
+  launch_attend_mfma<D, HP>(kp, n_units, Q, Kc, Vc, stride, len, count, count_pitch, out, st)
   if (kp.dtype == CASK_F32) {
     if (kp.d == 64) CASK_ATT(float, 64); else CASK_ATT(float, 128);
-  } else {
+  } else if (attend_vector_forced()) {
     if (kp.d == 64) CASK_ATT(uint16_t, 64); else CASK_ATT(uint16_t, 128);
+  } else {
+    const int hp = kp.G >= 5 ? 8 : kp.G >= 3 ? 4 : kp.G;  // query heads per pass over the cache
+    if (kp.d == 64) {
+      if (hp == 8) CASK_ATT_MFMA(64, 8); else if (hp == 4) CASK_ATT_MFMA(64, 4);
+      else if (hp == 2) CASK_ATT_MFMA(64, 2); else CASK_ATT_MFMA(64, 1);
+    } else {
+      if (hp == 8) CASK_ATT_MFMA(128, 8); else if (hp == 4) CASK_ATT_MFMA(128, 4);
+      else if (hp == 2) CASK_ATT_MFMA(128, 2); else CASK_ATT_MFMA(128, 1);
+    }
   }
+#undef CASK_ATT_MFMA
 #undef CASK_ATT
   return hipGetLastError();
 }

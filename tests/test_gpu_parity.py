@@ -343,17 +343,19 @@ def _attend_tol(p):
     return (2e-5, 2e-6) if p.dtype == cask.F32 else (1.5e-2, 2e-3)
 
 
-@pytest.mark.parametrize("case", ["bf16_d128_g7", "bf16_d64_g2", "f32_d128_g5", "f32_d64_g1"])
+@pytest.mark.parametrize("case", ["bf16_d128_g7", "bf16_d128_g1", "bf16_d128_g4", "bf16_d128_g12",
+                                  "bf16_d64_g2", "bf16_d64_g8", "f32_d128_g5", "f32_d64_g1"])
 def test_attend_over_a_compressed_cache(case):
-    """cask_attend against the oracle: ragged lengths inside a row stride (one row, fewer rows
-    than groups, thousands), with and without counts, more query heads than one pass takes."""
+    """cask_attend against the oracle: ragged lengths inside a row stride (none, one row, fewer
+    rows than a tile, tile and workgroup boundaries, thousands), with and without counts, more
+    query heads than one pass takes."""
     dev = torch.device("cuda:0")
     rng = np.random.default_rng(91)
     f32 = case.startswith("f32")
     d = 128 if "d128" in case else 64
     G = int(case.split("_g")[1])
     stride = 2300
-    lens = np.array([1, 7, 16, 17, 300, 2300, 1111], dtype=np.int32)
+    lens = np.array([1, 7, 16, 17, 300, 2300, 1111, 0, 32, 33, 256, 257, 511], dtype=np.int32)
     n = len(lens)
     dt = torch.float32 if f32 else torch.bfloat16
     Q = (1.5 * torch.randn(n, G, d, generator=torch.Generator().manual_seed(1))).to(dt).to(dev)
@@ -366,7 +368,8 @@ def test_attend_over_a_compressed_cache(case):
     Qh, Kh, Vh = caches.host_bits(Q), caches.host_bits(Kc), caches.host_bits(Vc)
     rtol, atol = _attend_tol(p)
     for cnt in (None, count):
-        want = ref.attend(rp, Qh, Kh, Vh, lens, count=cnt)
+        want = ref.attend(rp, Qh, Kh, Vh, np.maximum(lens, 1), count=cnt)
+        want[lens == 0] = 0.0                       # the library's convention for an empty unit
         got = cask.attend(p, Q, Kc, Vc, torch.from_numpy(lens).to(dev),
                           count=None if cnt is None else torch.from_numpy(cnt).to(dev))
         torch.cuda.synchronize()
@@ -374,6 +377,28 @@ def test_attend_over_a_compressed_cache(case):
     again = cask.attend(p, Q, Kc, Vc, torch.from_numpy(lens).to(dev), count=torch.from_numpy(count).to(dev))
     torch.cuda.synchronize()
     assert torch.equal(got, again)                                       # same bits every run
+
+
+def test_attend_rows_behind_the_counted_ones():
+    """A count array narrower than the row stride: the rows behind it (tokens decoded since the
+    last event) enter with count 1."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(5)
+    n, G, d, stride, pitch = 6, 7, 128, 520, 384
+    lens = np.array([520, 384, 385, 100, 450, 519], dtype=np.int32)
+    Q = (1.5 * torch.randn(n, G, d, generator=torch.Generator().manual_seed(11))).to(torch.bfloat16).to(dev)
+    Kc = torch.randn(n, stride, d, generator=torch.Generator().manual_seed(12)).to(torch.bfloat16).to(dev)
+    Vc = torch.randn(n, stride, d, generator=torch.Generator().manual_seed(13)).to(torch.bfloat16).to(dev)
+    count = rng.integers(1, 30, (n, pitch)).astype(np.int32)
+    padded = np.ones((n, stride), dtype=np.int32)
+    padded[:, :pitch] = count
+    p = cask.Params(dtype=cask.BF16, head_dim=d, q_per_kv=G, window=1, budget=pitch)
+    want = ref.attend(parity.ref_params(p), caches.host_bits(Q), caches.host_bits(Kc), caches.host_bits(Vc),
+                      lens, count=padded)
+    got = cask.attend(p, Q, Kc, Vc, torch.from_numpy(lens).to(dev), count=torch.from_numpy(count).to(dev))
+    torch.cuda.synchronize()
+    rtol, atol = _attend_tol(p)
+    np.testing.assert_allclose(got.float().cpu().numpy().astype(np.float64), want, rtol=rtol, atol=atol)
 
 
 def test_attend_on_the_output_of_an_event():
