@@ -161,37 +161,48 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kAttWaves = 8;  // waves of the MFMA workgroup, two per SIMD
-
 // One workgroup per unit, one tile of 32 cache rows per wave and step, tiles dealt to the waves
-// round robin.  Per tile: the logits of up to HP query heads against the 32 keys are one
-// 32x32 MFMA product (keys as rows, heads as columns, zero columns beyond HP; the two lane
-// halves hold the two halves of the head dimension, in the same order for keys and queries),
-// the lane of a head column holds its 32 logits in registers and takes the block step of the
-// online softmax (running maximum, correction factor, weights) there, the weights go through
-// LDS to the lanes that hold the value rows (D / 8 lanes per row), and those lanes add the
-// weighted rows in fp32.  Everything inside the tile loop is wave-local: no workgroup barrier.
-// The key rows of the next tile are requested as soon as the product has consumed this tile's,
-// the value rows as soon as the weighted sum has, so a wave always has a tile of loads in
-// flight.  At the end the lane groups of a wave add up, and the waves' states are merged in
-// wave order: the same bits every run.
+// round robin.  Per tile, two MFMA products with the head dimension, then the keys, contracted:
+//   logits   S[key][head]  = K_tile (32 x D) . Q^T (D x up to HP heads, zero columns beyond);
+//            the two lane halves hold the two halves of the head dimension, in the same order
+//            for keys and queries,
+//   values   O[dim][head] += V_tile^T (D x 32) . P (32 x heads), 32 dims per product.
+// The lane pair of a head column holds that head's 32 logits in registers and takes the block
+// step of the online softmax there (running maximum, correction factor, weights); the weights,
+// rounded to bf16, are the second product's operand as they stand, because the order in which
+// a lane holds its keys is a permutation the value operand simply repeats.  The value rows
+// reach their operand layout (a lane: 8 keys of one dim) through a wave-private LDS area,
+// written transposed 2 bytes at a time and read back 16 bytes at a time.  The result columns of
+// a head live in the same lanes as its softmax state, so nothing but the value rows crosses
+// lanes inside the tile loop, and nothing there is a workgroup barrier.  The key rows of the
+// next tile are requested as soon as the first product has consumed this tile's, the value rows
+// as soon as they are in LDS, so a wave always has a tile of loads in flight.  At the end the
+// waves' states are merged in wave order: the same bits every run.
+template <int D>
+constexpr int att_vt_bytes() { return D * 64 + (D / 4) * 16; }  // [dim][32 keys] bf16, 16 B pad per 4 dims
 template <int D, int HP, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void attend_mfma_kernel(
+constexpr int att_lds_bytes() { return WAVES * att_vt_bytes<D>() + WAVES * 32 * 4 + 2 * WAVES * HP * 4; }
+
+template <int D, int HP, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void attend_mfma_kernel(
     KParams kp, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ Kc,
     const uint16_t* __restrict__ Vc, int stride, const int32_t* __restrict__ len,
     const int32_t* __restrict__ count, int count_pitch, uint16_t* __restrict__ out) {
-  constexpr int KS = D / 16;     // k-steps of the product
+  constexpr int KS = D / 16;     // k-steps of the logit product
+  constexpr int NB = D / 32;     // 32-dim blocks of the value product
   constexpr int LPR = D / 8;     // lanes per value row
   constexpr int GPW = 64 / LPR;  // value rows one load instruction of a wave covers
   constexpr int RPG = 32 / GPW;  // value rows per lane group and tile
-  __shared__ __align__(16) float bias_s[WAVES][32];
-  __shared__ __align__(16) float p_s[WAVES][32][HP];
-  __shared__ __align__(16) float corr_s[WAVES][HP < 4 ? 4 : HP];
-  __shared__ float st_m[WAVES][HP], st_l[WAVES][HP];
-  __shared__ __align__(16) float st_acc[WAVES][HP][D];
+  constexpr int kVt = att_vt_bytes<D>();
+  static_assert(HP * D * 4 <= kVt, "a wave's final state reuses its value area");
+  extern __shared__ __align__(16) unsigned char att_lds[];
   const int u = blockIdx.x, tid = threadIdx.x, wv = tid >> 6, lane = tid & 63;
   const int c32 = lane & 31, hh = lane >> 5;
   const int g = lane / LPR, gl = lane % LPR;
+  unsigned char* vt = att_lds + wv * kVt;
+  float* bias_s = reinterpret_cast<float*>(att_lds + WAVES * kVt) + wv * 32;
+  float* st_m = reinterpret_cast<float*>(att_lds + WAVES * kVt) + WAVES * 32;  // [WAVES][HP]
+  float* st_l = st_m + WAVES * HP;
   int L = len[u];
   L = L < 0 ? 0 : (L > stride ? stride : L);
   const int n_tiles = (L + 31) >> 5;
@@ -201,6 +212,9 @@ __global__ __launch_bounds__(WAVES * 64) void attend_mfma_kernel(
   const int32_t* cu = count ? count + (size_t)u * count_pitch : nullptr;
   const float c = kp.scale_log2;  // softmax scale * log2(e)
   const int last = L > 0 ? L - 1 : 0;
+  // Value area: dim x at byte x * 64 + (x / 4) * 16, key slots of 2 bytes inside.
+  const uint32_t vt_wr = gl * (8 * 64 + 2 * 16);
+  const uint32_t vt_rd = c32 * 64 + (c32 >> 2) * 16 + hh * 16;
 
   for (int g0 = 0; g0 < G; g0 += HP) {
     u32x4 qb[KS];
@@ -214,11 +228,9 @@ __global__ __launch_bounds__(WAVES * 64) void attend_mfma_kernel(
       }
     }
     float m_run = kNegInf, l_run = 0.f;  // of head c32, over the keys this lane has seen
-    float acc[HP][8];
+    f32x16 acc[NB];                      // acc[b][r] = O[dim b*32 + (r/4)*8 + hh*4 + r%4][head c32]
 #pragma unroll
-    for (int h = 0; h < HP; ++h)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
+    for (int b = 0; b < NB; ++b) acc[b] = f32x16{0};
 
     u32x4 ka[KS], va[RPG];
     int cn;
@@ -246,7 +258,7 @@ __global__ __launch_bounds__(WAVES * 64) void attend_mfma_kernel(
     for (int t = wv; t < n_tiles; t += WAVES) {
       {  // bias of key c32 of the tile: log2(count), or -inf past the end of the unit
         const float b = t * 32 + c32 < L ? (cn > 1 ? __log2f((float)cn) : 0.f) : kNegInf;
-        if (hh == 0) bias_s[wv][c32] = b;
+        if (hh == 0) bias_s[c32] = b;
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
       f32x16 s = {0};
@@ -258,100 +270,122 @@ __global__ __launch_bounds__(WAVES * 64) void attend_mfma_kernel(
       float x[16], mx = kNegInf;
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const float4 b4 = *reinterpret_cast<const float4*>(&bias_s[wv][r4 * 8 + hh * 4]);
+        const float4 b4 = *reinterpret_cast<const float4*>(&bias_s[r4 * 8 + hh * 4]);
         x[r4 * 4 + 0] = __builtin_fmaf(s[r4 * 4 + 0], c, b4.x);
         x[r4 * 4 + 1] = __builtin_fmaf(s[r4 * 4 + 1], c, b4.y);
         x[r4 * 4 + 2] = __builtin_fmaf(s[r4 * 4 + 2], c, b4.z);
         x[r4 * 4 + 3] = __builtin_fmaf(s[r4 * 4 + 3], c, b4.w);
       }
       load_keys(t + WAVES);  // the product is done with this tile's key rows
+      // Value rows into the wave's LDS area, transposed: key k sits in slot
+      // (k / 16) * 16 + (k / 4 % 2) * 8 + (k / 8 % 2) * 4 + k % 4, the order in which a lane's
+      // logit registers enumerate the keys of its half.
+#pragma unroll
+      for (int j = 0; j < RPG; ++j) {
+        const int k = j * GPW + g;
+        const int slot = ((k >> 4) & 1) * 16 + ((k >> 2) & 1) * 8 + ((k >> 3) & 1) * 4 + (k & 3);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t w = va[j][e >> 1];
+          *reinterpret_cast<uint16_t*>(vt + vt_wr + e * 64 + (e >> 2) * 16 + slot * 2) =
+              (e & 1) ? (uint16_t)(w >> 16) : (uint16_t)w;
+        }
+      }
+      load_values(t + WAVES);  // this tile's value rows are in LDS
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, x[r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float mn = fmaxf(m_run, mx);  // finite: key 0 of a tile in range is in range
       const float corr = __builtin_amdgcn_exp2f(m_run - mn);  // exp2(-inf) = 0 on the first tile
+      bf16x8 pb[2];
       float ps = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        x[r] = __builtin_amdgcn_exp2f(x[r] - mn);
-        ps += x[r];
+        const __bf16 pr = (__bf16)__builtin_amdgcn_exp2f(x[r] - mn);  // the weight the product uses
+        pb[r >> 3][r & 7] = pr;
+        ps += (float)pr;
       }
       l_run = __builtin_fmaf(l_run, corr, ps);
       m_run = mn;
-      if (c32 < HP) {
+      if (__any(corr != 1.f)) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) p_s[wv][(r >> 2) * 8 + hh * 4 + (r & 3)][c32] = x[r];
-        if (hh == 0) corr_s[wv][c32] = corr;
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[b][r] *= corr;
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      float cr[HP];
 #pragma unroll
-      for (int h = 0; h < HP; ++h) cr[h] = corr_s[wv][h];
+      for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int h = 0; h < HP; ++h)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[h][e] *= cr[h];
-#pragma unroll
-      for (int j = 0; j < RPG; ++j) {
-        float pj[HP], vf[8];
-#pragma unroll
-        for (int h = 0; h < HP; ++h) pj[h] = p_s[wv][j * GPW + g][h];
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          vf[2 * w] = __uint_as_float(va[j][w] << 16);
-          vf[2 * w + 1] = __uint_as_float(va[j][w] & 0xffff0000u);
+        for (int ks = 0; ks < 2; ++ks) {
+          const u32x4 vop = *reinterpret_cast<const u32x4*>(vt + vt_rd + b * (32 * 64 + 8 * 16) + ks * 32);
+          acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop), pb[ks], acc[b], 0, 0, 0);
         }
-#pragma unroll
-        for (int h = 0; h < HP; ++h)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[h][e] = __builtin_fmaf(pj[h], vf[e], acc[h][e]);
-      }
       asm volatile("" ::: "memory");  // the next tile's LDS writes stay behind these reads
-      load_values(t + WAVES);
     }
-    // The lane groups of a wave share the wave's running maximum: their sums simply add.
-#pragma unroll
-    for (int o = LPR; o < 64; o <<= 1)
-#pragma unroll
-      for (int h = 0; h < HP; ++h)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[h][e] += __shfl_xor(acc[h][e], o, 64);
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    if (lane < HP) {
-      st_m[wv][lane] = m_run;
-      st_l[wv][lane] = l_tot;
-    }
-    if (g == 0) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    float* st_acc = reinterpret_cast<float*>(vt);  // [HP][D]: the wave's value area is free now
+    if (c32 < HP) {
+      if (hh == 0) {
+        st_m[wv * HP + c32] = m_run;
+        st_l[wv * HP + c32] = l_tot;
+      }
 #pragma unroll
-      for (int h = 0; h < HP; ++h)
+      for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) st_acc[wv][h][gl * 8 + e] = acc[h][e];
+        for (int r4 = 0; r4 < 4; ++r4)
+          *reinterpret_cast<float4*>(&st_acc[c32 * D + b * 32 + r4 * 8 + hh * 4]) =
+              float4{acc[b][r4 * 4], acc[b][r4 * 4 + 1], acc[b][r4 * 4 + 2], acc[b][r4 * 4 + 3]};
     }
+    asm volatile("" ::: "memory");
     __syncthreads();
     for (int o = tid; o < HP * D; o += WAVES * 64) {
       const int h = o / D, ch = o % D;
       if (g0 + h >= G) continue;
       float top = kNegInf;
-      for (int w = 0; w < WAVES; ++w) top = fmaxf(top, st_m[w][h]);
+      for (int w = 0; w < WAVES; ++w) top = fmaxf(top, st_m[w * HP + h]);
       float num = 0.f, den = 0.f;
       for (int w = 0; w < WAVES; ++w) {  // wave order: the same bits every run
-        const float f = st_m[w][h] == kNegInf ? 0.f : __builtin_amdgcn_exp2f(st_m[w][h] - top);
-        den = __builtin_fmaf(st_l[w][h], f, den);
-        num = __builtin_fmaf(st_acc[w][h][ch], f, num);
+        const float mw = st_m[w * HP + h];
+        const float f = mw == kNegInf ? 0.f : __builtin_amdgcn_exp2f(mw - top);
+        den = __builtin_fmaf(st_l[w * HP + h], f, den);
+        num = __builtin_fmaf(reinterpret_cast<const float*>(att_lds + w * kVt)[h * D + ch], f, num);
       }
       out[((size_t)u * G + g0 + h) * D + ch] = float_to_bf16_bits(den > 0.f ? num / den : 0.f);
     }
+    asm volatile("" ::: "memory");
     __syncthreads();
   }
 }
 
-template <int D, int HP>
-void launch_attend_mfma(const KParams& kp, int n_units, const void* Q, const void* Kc, const void* Vc,
-                        int stride, const int32_t* len, const int32_t* count, int count_pitch,
-                        void* out, hipStream_t st) {
-  attend_mfma_kernel<D, HP, kAttWaves><<<dim3(n_units), dim3(kAttWaves * 64), 0, st>>>(
+template <int D, int HP, int WAVES>
+hipError_t launch_attend_mfma_w(const KParams& kp, int n_units, const void* Q, const void* Kc,
+                                const void* Vc, int stride, const int32_t* len, const int32_t* count,
+                                int count_pitch, void* out, hipStream_t st) {
+  constexpr int lds = att_lds_bytes<D, HP, WAVES>();
+  static bool raised = false;  // (benign if two threads both set it)
+  if (lds > 48 * 1024 && !raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_mfma_kernel<D, HP, WAVES>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  attend_mfma_kernel<D, HP, WAVES><<<dim3(n_units), dim3(WAVES * 64), lds, st>>>(
       kp, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(Kc),
       static_cast<const uint16_t*>(Vc), stride, len, count, count_pitch, static_cast<uint16_t*>(out));
+  return hipSuccess;
+}
+
+// Few units: eight waves per workgroup (more rows of a unit in flight); many: four, so that
+// two workgroups share a compute unit and one's merge overlaps the other's loads.
+template <int D, int HP>
+hipError_t launch_attend_mfma(const KParams& kp, int n_units, const void* Q, const void* Kc, const void* Vc,
+                              int stride, const int32_t* len, const int32_t* count, int count_pitch,
+                              void* out, hipStream_t st) {
+  if (n_units >= 512)
+    return launch_attend_mfma_w<D, HP, 4>(kp, n_units, Q, Kc, Vc, stride, len, count, count_pitch, out, st);
+  return launch_attend_mfma_w<D, HP, 8>(kp, n_units, Q, Kc, Vc, stride, len, count, count_pitch, out, st);
 }
 
 }  // namespace
@@ -366,12 +400,13 @@ hipError_t launch_attend(const KParams& kp, int n_units, const void* Q, const vo
                          int stride, const int32_t* len, const int32_t* count, int count_pitch,
                          void* out, hipStream_t st) {
   if (n_units == 0) return hipSuccess;
+  hipError_t e = hipSuccess;
 #define CASK_ATT(T, D)                                                                       \
   attend_kernel<T, D><<<dim3(n_units), dim3(kAttThreads), 0, st>>>(                          \
       kp, static_cast<const T*>(Q), static_cast<const T*>(Kc), static_cast<const T*>(Vc),    \
       stride, len, count, count_pitch, static_cast<T*>(out))
 #define CASK_ATT_MFMA(D, HP) \
-  launch_attend_mfma<D, HP>(kp, n_units, Q, Kc, Vc, stride, len, count, count_pitch, out, st)
+  e = launch_attend_mfma<D, HP>(kp, n_units, Q, Kc, Vc, stride, len, count, count_pitch, out, st)
   if (kp.dtype == CASK_F32) {
     if (kp.d == 64) CASK_ATT(float, 64); else CASK_ATT(float, 128);
   } else if (attend_vector_forced()) {
@@ -388,6 +423,7 @@ hipError_t launch_attend(const KParams& kp, int n_units, const void* Q, const vo
   }
 #undef CASK_ATT_MFMA
 #undef CASK_ATT
+  if (e != hipSuccess) return e;
   return hipGetLastError();
 }
 
