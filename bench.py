@@ -61,6 +61,9 @@ def parse():
                     help="replays of the extra HIP-graph measurement (0 = skip)")
     ap.add_argument("--overlap-steps", type=int, default=50,
                     help="events of the extra two-stream measurement (0 = skip)")
+    ap.add_argument("--attend-steps", type=int, default=50,
+                    help="after the timed region: time the consumer side, one decode step's attention "
+                         "(cask_attend) over the compressed caches the event wrote (0 = skip)")
     ap.add_argument("--breakdown-steps", type=int, default=20,
                     help="extra untimed steps with an event after every kernel for config.stage_ms (0 = skip)")
     return ap.parse_args()
@@ -222,6 +225,29 @@ def main():
         torch.cuda.synchronize()
     status = outs.status.cpu().numpy()
     out_len = outs.out_len.cpu().numpy()
+
+    # ---- consumer side (not part of the event, reported beside it): one decode step's attention
+    # of the G query heads of every unit over the cache the event wrote; HBM-bound, its bytes are
+    # the kept key and value rows
+    consumer = None
+    if args.attend_steps > 0:
+        gen = torch.Generator(device=dev).manual_seed(7)
+        qd = torch.randn(n_units, p.q_per_kv, p.head_dim, device=dev, generator=gen).to(outs.K_out.dtype)
+        od = torch.empty_like(qd)
+        cnt = torch.ones(n_units, p.budget, dtype=torch.int32, device=dev)
+        for _ in range(5):
+            cask.attend(p, qd, outs.K_out, outs.V_out, outs.out_len, count=cnt, out=od)
+        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ea.record()
+        for _ in range(args.attend_steps):
+            cask.attend(p, qd, outs.K_out, outs.V_out, outs.out_len, count=cnt, out=od)
+        eb.record()
+        torch.cuda.synchronize()
+        att_us = ea.elapsed_time(eb) * 1e3 / args.attend_steps
+        att_bytes = float(out_len.sum()) * p.head_dim * outs.K_out.element_size() * 2
+        consumer = {"kernel": "cask_attend", "us": round(att_us, 2), "row_bytes": att_bytes,
+                    "GB/s": round(att_bytes / att_us * 1e-3, 1),
+                    "frac_of_hbm_peak": round(att_bytes / att_us * 1e-3 / PEAK_HBM_GBS, 4)}
     lens = (b0.row_off_host[1:] - b0.row_off_host[:-1]).numpy()
     saved = 1.0 - float(out_len.sum()) / float(lens.sum())
 
@@ -315,7 +341,8 @@ def main():
                    "stage_ms": ({k: round(v, 4) for k, v in stage_ms.items()} if stage_ms else None),
                    "event_ms_spread": spread,
                    "graph_ms_per_step": (round(graph_ms, 4) if graph_ms is not None else None),
-                   "two_stream_ms_per_step": (round(overlap_ms, 4) if overlap_ms is not None else None)},
+                   "two_stream_ms_per_step": (round(overlap_ms, 4) if overlap_ms is not None else None),
+                   "consumer_attend": consumer},
         "roofline": roof,
         "cpu_baseline": cpu,
     }
