@@ -181,7 +181,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <int D>
 constexpr int att_vt_bytes() { return D * 64 + (D / 4) * 16; }  // [dim][32 keys] bf16, 16 B pad per 4 dims
 template <int D, int HP, int WAVES>
-constexpr int att_lds_bytes() { return WAVES * att_vt_bytes<D>() + WAVES * 32 * 4 + 2 * WAVES * HP * 4; }
+constexpr int att_lds_bytes() {
+  return WAVES * att_vt_bytes<D>() + WAVES * 32 * 4 + 2 * WAVES * HP * 4 + (D / 16) * 64 * 16;
+}
 
 template <int D, int HP, int WAVES>
 __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void attend_mfma_kernel(
@@ -203,6 +205,7 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void attend_mfma_kernel(
   float* bias_s = reinterpret_cast<float*>(att_lds + WAVES * kVt) + wv * 32;
   float* st_m = reinterpret_cast<float*>(att_lds + WAVES * kVt) + WAVES * 32;  // [WAVES][HP]
   float* st_l = st_m + WAVES * HP;
+  u32x4* q_s = reinterpret_cast<u32x4*>(st_l + WAVES * HP);  // [KS][64]: the query operand, lane by lane
   int L = len[u];
   L = L < 0 ? 0 : (L > stride ? stride : L);
   const int n_tiles = (L + 31) >> 5;
@@ -217,16 +220,18 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void attend_mfma_kernel(
   const uint32_t vt_rd = c32 * 64 + (c32 >> 2) * 16 + hh * 16;
 
   for (int g0 = 0; g0 < G; g0 += HP) {
-    u32x4 qb[KS];
-    {
+    if (wv == 0) {  // the query operand is the same for every wave and tile: it waits in LDS
       const bool head = c32 < HP && g0 + c32 < G;
       const uint16_t* qp = Q + ((size_t)u * G + (head ? g0 + c32 : 0)) * D + hh * (D / 2);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        qb[ks] = *reinterpret_cast<const u32x4*>(qp + ks * 8);
-        if (!head) qb[ks] = u32x4{0u, 0u, 0u, 0u};
+        u32x4 qv = *reinterpret_cast<const u32x4*>(qp + ks * 8);
+        if (!head) qv = u32x4{0u, 0u, 0u, 0u};
+        q_s[ks * 64 + lane] = qv;
       }
     }
+    asm volatile("" ::: "memory");
+    __syncthreads();
     float m_run = kNegInf, l_run = 0.f;  // of head c32, over the keys this lane has seen
     f32x16 acc[NB];                      // acc[b][r] = O[dim b*32 + (r/4)*8 + hh*4 + r%4][head c32]
 #pragma unroll
@@ -265,7 +270,7 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void attend_mfma_kernel(
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[ks]),
-                                                    __builtin_bit_cast(bf16x8, qb[ks]), s, 0, 0, 0);
+                                                    __builtin_bit_cast(bf16x8, q_s[ks * 64 + lane]), s, 0, 0, 0);
       // s[r] = <key (r / 4) * 8 + hh * 4 + r % 4, head c32>
       float x[16], mx = kNegInf;
 #pragma unroll
@@ -297,13 +302,17 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void attend_mfma_kernel(
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float mn = fmaxf(m_run, mx);  // finite: key 0 of a tile in range is in range
       const float corr = __builtin_amdgcn_exp2f(m_run - mn);  // exp2(-inf) = 0 on the first tile
-      bf16x8 pb[2];
+      // A weight enters the value product as two bf16 terms, p = hi + lo (lo the rounded
+      // remainder: 16 mantissa bits in all), so that the product sees it to 2^-17.
+      bf16x8 pb[2], pl[2];
       float ps = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const __bf16 pr = (__bf16)__builtin_amdgcn_exp2f(x[r] - mn);  // the weight the product uses
-        pb[r >> 3][r & 7] = pr;
-        ps += (float)pr;
+        const float pr = __builtin_amdgcn_exp2f(x[r] - mn);
+        const __bf16 hi = (__bf16)pr;
+        pb[r >> 3][r & 7] = hi;
+        pl[r >> 3][r & 7] = (__bf16)(pr - (float)hi);
+        ps += pr;
       }
       l_run = __builtin_fmaf(l_run, corr, ps);
       m_run = mn;
@@ -320,6 +329,7 @@ __global__ __launch_bounds__(WAVES * 64, 8 / WAVES) void attend_mfma_kernel(
         for (int ks = 0; ks < 2; ++ks) {
           const u32x4 vop = *reinterpret_cast<const u32x4*>(vt + vt_rd + b * (32 * 64 + 8 * 16) + ks * 32);
           acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop), pb[ks], acc[b], 0, 0, 0);
+          acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop), pl[ks], acc[b], 0, 0, 0);
         }
       asm volatile("" ::: "memory");  // the next tile's LDS writes stay behind these reads
     }
