@@ -243,7 +243,9 @@ int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, c
  *   out   [n_units, G, d]               device, cache dtype (fp32 accumulation, rounded once)
  * All data pointers 16-byte aligned.  scale = softmax_scale, 1/sqrt(d) when that is 0.  Needs
  * no workspace.  Decoded tokens appended behind the compressed rows attend the same way (their
- * count is 1): pass the buffer with its row stride and the enlarged len. */
+ * count is 1): pass the buffer with its row stride and the enlarged len.  bf16 caches run on
+ * the matrix cores; the environment variable CASK_ATTEND_VECTOR=1, read at every call, sends
+ * them through the vector kernel that serves fp32 caches (for comparisons). */
 int cask_attend(const cask_params* params, int32_t n_units, const void* Q, const void* K_c,
                 const void* V_c, int32_t stride_rows, const int32_t* len, const int32_t* count,
                 int32_t count_pitch, void* out, void* hip_stream);

@@ -344,8 +344,9 @@ def _attend_tol(p):
 
 
 @pytest.mark.parametrize("case", ["bf16_d128_g7", "bf16_d128_g1", "bf16_d128_g4", "bf16_d128_g12",
-                                  "bf16_d64_g2", "bf16_d64_g8", "f32_d128_g5", "f32_d64_g1"])
-def test_attend_over_a_compressed_cache(case):
+                                  "bf16_d64_g2", "bf16_d64_g8", "f32_d128_g5", "f32_d64_g1",
+                                  "bf16_d128_g7_vector", "bf16_d64_g6_vector"])
+def test_attend_over_a_compressed_cache(case, monkeypatch):
     """cask_attend against the oracle: ragged lengths inside a row stride (none, one row, fewer
     rows than a tile, tile and workgroup boundaries, thousands), with and without counts, more
     query heads than one pass takes."""
@@ -353,7 +354,9 @@ def test_attend_over_a_compressed_cache(case):
     rng = np.random.default_rng(91)
     f32 = case.startswith("f32")
     d = 128 if "d128" in case else 64
-    G = int(case.split("_g")[1])
+    G = int(case.split("_g")[1].split("_")[0])
+    # bf16 caches take the MFMA kernel; "_vector" sends them through the kernel fp32 caches use
+    monkeypatch.setenv("CASK_ATTEND_VECTOR", "1" if case.endswith("_vector") else "0")
     stride = 2300
     lens = np.array([1, 7, 16, 17, 300, 2300, 1111, 0, 32, 33, 256, 257, 511], dtype=np.int32)
     n = len(lens)
