@@ -340,6 +340,8 @@ def main():
                    "status_counts": {str(k): int(v) for k, v in zip(*np.unique(status, return_counts=True))},
                    "stage_ms": ({k: round(v, 4) for k, v in stage_ms.items()} if stage_ms else None),
                    "event_ms_spread": spread,
+                   # an event fires once per `window` decoded tokens of a sequence
+                   "ms_per_decode_step_amortised": round(ms_per_step / w.window, 6),
                    "graph_ms_per_step": (round(graph_ms, 4) if graph_ms is not None else None),
                    "two_stream_ms_per_step": (round(overlap_ms, 4) if overlap_ms is not None else None),
                    "consumer_attend": consumer},
