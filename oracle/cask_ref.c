@@ -71,6 +71,7 @@ static int check_params(const cask_ref_params* p) {
   if (check_shape(p)) return -1;
   if (p->budget < resolved_recent(p) + 1) return -1;
   if (p->merge_radius < 0 || p->merge_geometry < 0 || p->merge_geometry > 1) return -1;
+  if (p->seed_dedup < 0 || (p->seed_dedup > 0 && p->merge_geometry != 0)) return -1;
   if (p->merge_geometry == 1) {
     if (!p->band_weight || !(p->dist_threshold >= 0.0f)) return -1;
     for (int f = 0; f < p->head_dim / 2; ++f)
@@ -277,6 +278,57 @@ static void partition_unit(const cask_ref_plan_t* pl, int32_t P, int32_t N, cons
   free(r);
 }
 
+/* De-duplicated seeding (an option; the paper does not say how representatives are seeded,
+ * and with the default rule two copies of one token can both become seeds and split their
+ * group).  The scratch rows are the decode rows outside the recent tail that are not core,
+ * in the total order.  Walk the first min(#scratch, h*M) of them: a row becomes a seed unless
+ * its key cosine with some seed chosen earlier is >= tau (then it is a donor, and the
+ * consolidation will fold it into a seed it resembles); stop when M seeds are chosen.
+ * Everything else in the scratch is a donor. */
+static void dedup_seeds_unit(const cask_ref_params* p, const cask_ref_plan_t* pl, int32_t P, int32_t N,
+                             const void* K, int64_t row0, const float* s, uint8_t* role,
+                             double* min_gap) {
+  if (min_gap) *min_gap = INFINITY;
+  if (pl->status & CASK_REF_ST_PREFIX_BUDGET_EXHAUSTED) return;
+  const int32_t hi = N - pl->r_eff, n = hi - P, d = p->head_dim;
+  if (pl->seeds <= 0 || n <= pl->core + pl->seeds) return; /* no donors: nothing to de-duplicate for */
+  const double tau = (double)p->sim_threshold;
+  ranked_t* r = rank_range(s, P, hi);
+  int64_t horizon = (int64_t)p->seed_dedup * pl->seeds;
+  if (horizon > n - pl->core) horizon = n - pl->core;
+  for (int32_t t = pl->core; t < n; ++t) role[r[t].i] = CASK_REF_DONOR;
+  double* seed_k = (double*)malloc(sizeof(double) * (size_t)pl->seeds * d);
+  double* seed_norm = (double*)malloc(sizeof(double) * (size_t)pl->seeds);
+  double* ki = (double*)malloc(sizeof(double) * d);
+  int32_t chosen = 0;
+  for (int64_t t = pl->core; t < pl->core + horizon && chosen < pl->seeds; ++t) {
+    const int32_t i = r[t].i;
+    double nn = 0.0;
+    for (int c = 0; c < d; ++c) {
+      ki[c] = load_elem(K, p->dtype, (row0 + i) * d + c);
+      nn += ki[c] * ki[c];
+    }
+    const double ni = sqrt(nn);
+    int blocked = 0;
+    for (int32_t q = 0; q < chosen; ++q) {
+      double dot = 0.0;
+      for (int c = 0; c < d; ++c) dot += ki[c] * seed_k[(size_t)q * d + c];
+      const double sim = (ni == 0.0 || seed_norm[q] == 0.0) ? 0.0 : dot / (ni * seed_norm[q]);
+      if (min_gap && fabs(sim - tau) < *min_gap) *min_gap = fabs(sim - tau);
+      if (sim >= tau) blocked = 1;
+    }
+    if (blocked) continue;
+    memcpy(seed_k + (size_t)chosen * d, ki, sizeof(double) * d);
+    seed_norm[chosen] = ni;
+    ++chosen;
+    role[i] = CASK_REF_SEED;
+  }
+  free(seed_k);
+  free(seed_norm);
+  free(ki);
+  free(r);
+}
+
 int cask_ref_prefix_evict(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
                           const int32_t* prefix_len, const float* scores, uint8_t* role,
                           int32_t* status) {
@@ -304,6 +356,26 @@ int cask_ref_partition(const cask_ref_params* p, int32_t n_units, const int64_t*
     cask_ref_plan_t pl;
     cask_ref_plan(p, prefix_len[u], N, &pl);
     partition_unit(&pl, prefix_len[u], N, scores + row_off[u], role + row_off[u]);
+    if (status) status[u] = pl.status;
+  }
+  return 0;
+}
+
+int cask_ref_partition_keys(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                            const int32_t* prefix_len, const void* K, const float* scores,
+                            uint8_t* role, int32_t* status, double* min_gap) {
+  if (check_params(p) || n_units < 0 || !K) return -1;
+  for (int32_t u = 0; u < n_units; ++u)
+    if (check_unit(p, row_off[u + 1] - row_off[u], prefix_len[u])) return -1;
+  for (int32_t u = 0; u < n_units; ++u) {
+    int32_t N = (int32_t)(row_off[u + 1] - row_off[u]);
+    cask_ref_plan_t pl;
+    cask_ref_plan(p, prefix_len[u], N, &pl);
+    partition_unit(&pl, prefix_len[u], N, scores + row_off[u], role + row_off[u]);
+    if (min_gap) min_gap[u] = INFINITY;
+    if (p->seed_dedup > 0)
+      dedup_seeds_unit(p, &pl, prefix_len[u], N, K, row_off[u], scores + row_off[u], role + row_off[u],
+                       min_gap ? &min_gap[u] : NULL);
     if (status) status[u] = pl.status;
   }
   return 0;
@@ -541,6 +613,7 @@ int cask_ref_compress_step(const cask_ref_params* p, int32_t n_units, const int6
     int32_t* asrc = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
     prefix_evict_unit(&pl, P, s, role);
     partition_unit(&pl, P, N, s, role);
+    if (p->seed_dedup > 0) dedup_seeds_unit(p, &pl, P, N, K, row0, s, role, NULL);
     consolidate_unit(p, N, K, row0, role, asrc, NULL, NULL);
     int32_t merged = 0;
     emit_unit(p, N, K, V, row0, s, role, asrc, K_out, V_out, (int64_t)u * out_stride_rows,

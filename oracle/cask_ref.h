@@ -76,6 +76,12 @@ typedef struct {
   const float* band_weight; /* geometry 1: w_f = |kappa(omega_f)| >= 0, d/2 values; the paper
                                never fixes the horizon distribution behind kappa, so the caller
                                supplies the weights */
+  /* De-duplicated seeding.  0: the seeds are the M best-scored scratch rows.  h > 0: walk the
+     best h*M scratch rows in the order (score descending, index ascending); a row becomes a
+     seed unless its key cosine with a seed chosen before it is >= sim_threshold; stop at M
+     seeds.  Rows passed over, and everything behind the walk, are donors.  Fewer than M seeds
+     may result.  Needs merge_geometry 0. */
+  int32_t seed_dedup;
 } cask_ref_params;
 
 typedef struct {
@@ -107,6 +113,14 @@ int cask_ref_prefix_evict(const cask_ref_params* p, int32_t n_units, const int64
 int cask_ref_partition(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
                        const int32_t* prefix_len, const float* scores, uint8_t* role,
                        int32_t* status);
+
+/* cask_ref_partition followed by de-duplicated seeding when p->seed_dedup > 0 (needs the keys).
+ * min_gap[u] (optional) = the smallest |cosine - sim_threshold| over the (row, earlier seed)
+ * pairs the walk compared, +inf when it compared none: how close the unit came to another
+ * seed set. */
+int cask_ref_partition_keys(const cask_ref_params* p, int32_t n_units, const int64_t* row_off,
+                            const int32_t* prefix_len, const void* K, const float* scores,
+                            uint8_t* role, int32_t* status, double* min_gap);
 
 /* assign[row] = unit-local row of the seed a donor folds into, own row if kept, -1 if evicted.
  * best_sim / second_sim (either may be NULL): per row, the largest and second largest cosine

@@ -41,7 +41,8 @@ class _Params(C.Structure):
                 ("core", C.c_int32), ("prefix_budget", C.c_int32),
                 ("sim_threshold", C.c_float), ("softmax_scale", C.c_float),
                 ("causal", C.c_int32), ("merge_radius", C.c_int32), ("merge_geometry", C.c_int32),
-                ("dist_threshold", C.c_float), ("band_weight", C.c_void_p)]
+                ("dist_threshold", C.c_float), ("band_weight", C.c_void_p),
+                ("seed_dedup", C.c_int32)]
 
 
 class _Plan(C.Structure):
@@ -66,6 +67,7 @@ class Params:
     merge_geometry: int = 0        # 0 cosine (sim_threshold), 1 kappa-weighted band distance
     dist_threshold: float = 0.0    # geometry 1: fold iff distance <= this
     band_weight: Optional[np.ndarray] = None   # geometry 1: float32 [head_dim / 2], >= 0
+    seed_dedup: int = 0            # h > 0: seeds chosen greedily among the best h*M scratch rows
 
     def c(self) -> _Params:
         bw = None
@@ -76,7 +78,7 @@ class Params:
         return _Params(self.dtype, self.head_dim, self.q_per_kv, self.window, self.recent,
                        self.budget, self.core, self.prefix_budget, self.sim_threshold,
                        self.softmax_scale, self.causal, self.merge_radius, self.merge_geometry,
-                       self.dist_threshold, bw)
+                       self.dist_threshold, bw, self.seed_dedup)
 
 
 _lib = None
@@ -176,6 +178,23 @@ def partition(p: Params, row_off, prefix_len, scores, role=None):
     if rc:
         raise ValueError(f"cask_ref_partition: {rc}")
     return role, status
+
+
+def partition_keys(p: Params, row_off, prefix_len, K, scores, role=None):
+    """partition, then de-duplicated seeding when p.seed_dedup > 0; returns role, status, min_gap."""
+    row_off, prefix_len, n_units = _units(row_off, prefix_len)
+    _check_data(p, K)
+    scores = np.ascontiguousarray(scores, dtype=np.float32)
+    if role is None:
+        role = np.full(int(row_off[-1]), 255, dtype=np.uint8)
+    status = np.zeros(n_units, dtype=np.int32)
+    gap = np.zeros(n_units, dtype=np.float64)
+    cp = p.c()
+    rc = lib().cask_ref_partition_keys(C.byref(cp), C.c_int32(n_units), _ptr(row_off), _ptr(prefix_len),
+                                       _ptr(K), _ptr(scores), _ptr(role), _ptr(status), _ptr(gap))
+    if rc:
+        raise ValueError(f"cask_ref_partition_keys: {rc}")
+    return role, status, gap
 
 
 def consolidate(p: Params, row_off, prefix_len, K, scores, role, want_sims: bool = False):

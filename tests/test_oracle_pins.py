@@ -1008,3 +1008,106 @@ def test_attend_after_a_fold_of_exact_duplicates_is_lossless(oracle):
     alive = out["assign"] >= 0                                           # kept rows and folded donors
     full = oracle.attend(p, q, K[alive][None], V[alive][None], np.array([int(alive.sum())]))
     np.testing.assert_allclose(comp, full, rtol=1e-5, atol=1e-6)        # K_out, V_out are fp32-rounded means
+
+
+# ------------------------------------------------------------------ de-duplicated seeding
+
+def _dedup_roles(oracle, p, ro, pl, K, s):
+    role, _ = oracle.prefix_evict(p, ro, pl, s)
+    role, _, gap = oracle.partition_keys(p, ro, pl, K, s, role)
+    return role, gap
+
+
+def test_dedup_seeding_is_the_greedy_walk_by_its_defining_properties(oracle):
+    """The walk is pinned by what characterises it, checked with numpy: seeds are pairwise
+    below tau; a row passed over inside the walk resembles a seed ranked before it; the walk
+    stops at M seeds or at its horizon; core, prefix and recent roles are those of the default
+    rule."""
+    for seed, tau, h in ((61, 0.9, 4), (62, 0.5, 2), (63, 0.97, 8), (64, 0.9, 1)):
+        rng = np.random.default_rng(seed)
+        p, K, V, Q, ro, pl, _ = make_case(rng, oracle, P=12, D=400, B=90, tau=tau, clusters=30)
+        N, P = K.shape[0], int(pl[0])
+        s = (rng.random(N) ** 3).astype(np.float32)
+        base = _roles_for(oracle, p, ro, pl, s)
+        p.seed_dedup = h
+        role, gap = _dedup_roles(oracle, p, ro, pl, K, s)
+        plan = oracle.plan(p, P, N)
+        C, M, hi = plan["core"], plan["seeds"], N - plan["r_eff"]
+        fixed = (base != oracle.SEED) & (base != oracle.DONOR)
+        np.testing.assert_array_equal(role[fixed], base[fixed])
+        scratch = np.flatnonzero(~fixed)
+        assert set(np.unique(role[scratch])) <= {oracle.SEED, oracle.DONOR}
+        order = scratch[np.lexsort((scratch, -s[scratch].astype(np.float64)))]   # score desc, index asc
+        walk = order[: min(len(order), h * M)]
+        seeds = [i for i in order if role[i] == oracle.SEED]
+        assert 0 < len(seeds) <= M and set(seeds) <= set(walk)
+        Kn = K.astype(np.float64)
+        Kn /= np.linalg.norm(Kn, axis=1, keepdims=True)
+        tau64 = float(np.float32(tau))
+        cos_ss = Kn[seeds] @ Kn[seeds].T
+        assert (cos_ss[np.triu_indices(len(seeds), 1)] < tau64).all()
+        last = order.tolist().index(seeds[-1])
+        stop = last if len(seeds) == M else len(walk) - 1          # rows examined: up to here
+        rank_of = {i: t for t, i in enumerate(order)}
+        passed_over = 0
+        for t in range(stop + 1):
+            i = order[t]
+            if role[i] == oracle.SEED:
+                continue
+            earlier = [q for q in seeds if rank_of[q] < t]
+            assert earlier and (Kn[earlier] @ Kn[i]).max() >= tau64, (seed, t)
+            passed_over += 1
+        assert passed_over > 0 or h == 1
+        assert gap[0] > 1e-6          # no decision of these cases sits on the threshold
+
+
+def test_dedup_seeding_reduces_to_the_default_rule_and_to_one_seed(oracle):
+    rng = np.random.default_rng(65)
+    p, K, V, Q, ro, pl, _ = make_case(rng, oracle, P=10, D=300, B=80, tau=2.0)
+    N = K.shape[0]
+    s = (rng.random(N) ** 2).astype(np.float32)
+    base = _roles_for(oracle, p, ro, pl, s)
+    for h in (1, 3):                      # nothing resembles anything at tau > 1: the M best rows
+        p.seed_dedup = h
+        np.testing.assert_array_equal(_dedup_roles(oracle, p, ro, pl, K, s)[0], base)
+    # tau <= -1: every later row resembles the first seed, which stays alone; the event then
+    # folds the whole scratch into it and conserves the decode mass outside the recent tail
+    p.sim_threshold, p.seed_dedup = -1.0, 4
+    role, _ = _dedup_roles(oracle, p, ro, pl, K, s)
+    plan = oracle.plan(p, int(pl[0]), N)
+    scratch = np.flatnonzero((base == oracle.SEED) | (base == oracle.DONOR))
+    best = scratch[np.lexsort((scratch, -s[scratch].astype(np.float64)))][0]
+    assert list(np.flatnonzero(role == oracle.SEED)) == [best]
+    out = oracle.compress(p, ro, pl, K, V, Q, scores=s)
+    assert out["out_len"][0] == plan["p_keep"] + plan["core"] + 1 + plan["r_eff"]
+    slot = int(np.flatnonzero(out["out_src"][0] == best)[0])
+    assert np.isclose(out["out_mass"][0, slot], s[scratch].astype(np.float64).sum(), rtol=1e-6)
+
+
+def test_dedup_seeding_keeps_one_copy_of_every_repeated_key(oracle):
+    """Each of 40 distinct keys appears 6 times in the scratch: the seeds are the best-scored
+    copy of each of the M best keys, where the default rule spends several seeds on one key."""
+    rng = np.random.default_rng(66)
+    d, P, W, reps, kinds = 16, 0, 4, 6, 40
+    D = reps * kinds + W
+    base_k = rng.standard_normal((kinds, d)).astype(np.float32)
+    kind = np.concatenate([rng.permutation(np.repeat(np.arange(kinds), reps)), np.full(W, -1)])
+    K = np.where(kind[:, None] >= 0, base_k[np.maximum(kind, 0)], rng.standard_normal((D, d))).astype(np.float32)
+    V = rng.standard_normal((D, d)).astype(np.float32)
+    Q = rng.standard_normal((1, W, 1, d)).astype(np.float32)
+    ro, pl = np.array([0, D], dtype=np.int64), np.array([P], dtype=np.int32)
+    # copies of a key score alike (as near-duplicates do), every score distinct
+    s = (10.0 * rng.permutation(kinds + 1)[kind] + rng.permutation(D) / D).astype(np.float32)
+    p = f32_params(oracle, head_dim=d, window=W, q_per_kv=1, recent=W, budget=W + 12, core=0,
+                   prefix_budget=0, sim_threshold=0.99, seed_dedup=reps * kinds)
+    plan = oracle.plan(p, P, D)
+    M = plan["seeds"]
+    assert plan["core"] == 0 and M == 12
+    role, _ = _dedup_roles(oracle, p, ro, pl, K, s)
+    seeds = np.flatnonzero(role == oracle.SEED)
+    best_of_kind = np.array([np.flatnonzero(kind == k)[np.argmax(s[kind == k])] for k in range(kinds)])
+    want = np.sort(best_of_kind[np.argsort(-s[best_of_kind])[:M]])
+    np.testing.assert_array_equal(seeds, want)
+    p.seed_dedup = 0
+    default_seeds = np.flatnonzero(_roles_for(oracle, p, ro, pl, s) == oracle.SEED)
+    assert len(np.unique(kind[default_seeds])) < M
