@@ -91,6 +91,14 @@ typedef struct {
   const float* band_weight; /* DEVICE [d/2], geometry 1: w_f = |kappa(omega_f)| >= 0 (the paper does
                                not fix the horizon distribution behind kappa: the caller supplies
                                the weights; not validated on the device) */
+  /* De-duplicated seeding (the paper does not say how representatives are seeded).  0: the
+     seeds are the M best-scored scratch rows.  h > 0: walk the best h * M scratch rows in the
+     order (score descending, index ascending); a row becomes a seed unless its key cosine
+     with a seed chosen before it is >= sim_threshold, until M seeds are chosen; rows passed
+     over, and all rows behind the walk, are donors; fewer than M seeds (out_len < B) may
+     result.  Needs merge_geometry 0 and h * (largest M of the plan) <= 2048, else
+     CASK_EINVAL.  Applies to cask_partition, cask_compress and cask_compress_step. */
+  int32_t seed_dedup;
 } cask_params;
 
 typedef struct {

@@ -43,7 +43,8 @@ class _Params(C.Structure):
                 ("core", C.c_int32), ("prefix_budget", C.c_int32),
                 ("sim_threshold", C.c_float), ("softmax_scale", C.c_float),
                 ("causal", C.c_int32), ("scores_given", C.c_int32), ("merge_radius", C.c_int32),
-                ("merge_geometry", C.c_int32), ("dist_threshold", C.c_float), ("band_weight", C.c_void_p)]
+                ("merge_geometry", C.c_int32), ("dist_threshold", C.c_float), ("band_weight", C.c_void_p),
+                ("seed_dedup", C.c_int32)]
 
 
 class _Batch(C.Structure):
@@ -74,6 +75,7 @@ class Params:
     merge_geometry: int = 0        # 0 cosine (sim_threshold), 1 kappa-weighted band distance
     dist_threshold: float = 0.0    # geometry 1: fold iff distance <= this
     band_weight: Optional[torch.Tensor] = None   # geometry 1: device float32 [head_dim / 2], >= 0
+    seed_dedup: int = 0            # h > 0: seeds chosen greedily among the best h * M scratch rows
 
     def c(self, scores_given: int = 0) -> _Params:
         bw = None
@@ -84,7 +86,7 @@ class Params:
         return _Params(self.dtype, self.head_dim, self.q_per_kv, self.window, self.recent,
                        self.budget, self.core, self.prefix_budget, self.sim_threshold,
                        self.softmax_scale, self.causal, scores_given, self.merge_radius,
-                       self.merge_geometry, self.dist_threshold, bw)
+                       self.merge_geometry, self.dist_threshold, bw, self.seed_dedup)
 
 
 _lib = None

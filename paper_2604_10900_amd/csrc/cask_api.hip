@@ -105,6 +105,7 @@ static int resolve_params(const cask_params* p, KParams* kp, bool need_budget) {
   if (!(p->sim_threshold == p->sim_threshold)) return CASK_EINVAL;  // NaN
   if (p->merge_radius < 0 || p->merge_geometry < 0 || p->merge_geometry > 1) return CASK_EINVAL;
   if (p->merge_geometry == 1 && (!p->band_weight || !(p->dist_threshold >= 0.f))) return CASK_EINVAL;
+  if (p->seed_dedup < 0 || (p->seed_dedup > 0 && p->merge_geometry != 0)) return CASK_EINVAL;
   kp->dtype = p->dtype;
   kp->d = p->head_dim;
   kp->G = p->q_per_kv;
@@ -118,10 +119,13 @@ static int resolve_params(const cask_params* p, KParams* kp, bool need_budget) {
   kp->geometry = p->merge_geometry;
   kp->theta = p->dist_threshold;
   kp->band_w = p->band_weight;
+  kp->dedup = p->seed_dedup;
   const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
   kp->scale_log2 = (float)(scale * 1.4426950408889634);
   kp->causal = p->causal ? 1 : 0;
   kp->Mq = p->q_per_kv * p->window;
+  // the de-duplicating walk of a unit covers at most h * M rows and holds them in LDS
+  if (need_budget && kp->dedup > 0 && (int64_t)kp->dedup * plan_seed_bound(*kp) > kSeedWalkMax) return CASK_EINVAL;
   return CASK_OK;
 }
 
@@ -271,7 +275,9 @@ int cask_partition(const cask_params* params, const cask_batch* batch, const flo
   if (rc) return rc;
   if (b.n_units == 0) return CASK_OK;
   if (!scores || !role) return CASK_EINVAL;
-  return dev_rc(launch_select(kp, b, scores, role, status, false, true, static_cast<hipStream_t>(hip_stream)));
+  hipError_t e = launch_select(kp, b, scores, role, status, false, true, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return CASK_EDEVICE;
+  return dev_rc(launch_dedup_seeds(kp, b, scores, role, static_cast<hipStream_t>(hip_stream)));
 }
 
 int cask_consolidate(const cask_params* params, const cask_batch* batch, const float* scores,
@@ -412,7 +418,7 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
   hipError_t e;
   StageRecorder rec(st);
   rec.mark();  // start
-  const bool fused_tail = tail_small_fits(kp, b) && !fused_tail_disabled();
+  const bool fused_tail = tail_small_fits(kp, b) && kp.dedup == 0 && !fused_tail_disabled();
   // short units: both sweeps are one launch as well, handing partial sums to the tail kernel
   // (reported as the first scoring stage; the second reads as an empty bracket)
   const bool fused_score = fused_tail && !given && score_parts_fits(kp, b, wl) && !fused_score_disabled();
@@ -436,11 +442,22 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
     for (int k = 0; k < 5; ++k) rec.mark();
     return dev_rc(e);
   }
-  e = launch_select_index(kp, b, s, role, status, slot_of, out_src, out_len, seed_rows, ord_of_slot,
-                          n_seeds, st);
-  if (e != hipSuccess) return CASK_EDEVICE;
-  rec.mark();
-  rec.mark();  // the ordered walk runs inside the select kernel here: its own stage reads as zero
+  if (kp.dedup > 0) {
+    // de-duplicated seeding sits between the selection and the ordered walk: three launches
+    e = launch_select(kp, b, s, role, status, true, true, st);
+    if (e == hipSuccess) e = launch_dedup_seeds(kp, b, s, role, st);
+    if (e != hipSuccess) return CASK_EDEVICE;
+    rec.mark();
+    e = launch_index_roles(kp, b, role, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds, st);
+    if (e != hipSuccess) return CASK_EDEVICE;
+    rec.mark();
+  } else {
+    e = launch_select_index(kp, b, s, role, status, slot_of, out_src, out_len, seed_rows, ord_of_slot,
+                            n_seeds, st);
+    if (e != hipSuccess) return CASK_EDEVICE;
+    rec.mark();
+    rec.mark();  // the ordered walk runs inside the select kernel here: its own stage reads as zero
+  }
   e = launch_similarity(kp, b, role, seed_rows, n_seeds, assign_ord, true, st);
   if (e != hipSuccess) return CASK_EDEVICE;
   rec.mark();

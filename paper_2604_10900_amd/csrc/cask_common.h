@@ -30,7 +30,10 @@ struct KParams {
   int geometry;      // 0 cosine, 1 kappa-weighted band distance
   float theta;       // distance threshold of geometry 1
   const float* band_w;  // device [d / 2] band weights of geometry 1
+  int dedup;         // h > 0: de-duplicated seeding over the best h * M scratch rows
 };
+
+constexpr int kSeedWalkMax = 2048;  // rows the de-duplicating walk of a unit can cover
 
 struct UnitPlan {
   int r_eff, p_keep, slots, core, seeds, status;
@@ -93,6 +96,15 @@ __host__ __device__ inline UnitPlan make_plan(const KParams& kp, int P, int N) {
 // Seeds a unit can have when its roles come from the plan: seeds = slots - core with
 // slots <= B, so at most B - core for an explicit core size and at most ceil(B / 5) for the
 // default four-fifths core share.
+// Rows of the scratch (n of them outside the recent tail, C of them core) that the selection
+// marks as seeds: the M best, or with de-duplicated seeding the best h * M (the walk's range),
+// when the unit has donors at all.
+__host__ __device__ inline int seed_range(const KParams& kp, const UnitPlan& pl, int n) {
+  if (kp.dedup <= 0 || pl.seeds <= 0 || n <= pl.core + pl.seeds) return pl.seeds;
+  const long long want = (long long)kp.dedup * pl.seeds;
+  return (int)(want < n - pl.core ? want : n - pl.core);
+}
+
 inline int plan_seed_bound(const KParams& kp) {
   const int sb = kp.core >= 0 ? (kp.B - kp.core > 0 ? kp.B - kp.core : 0) : (kp.B + 4) / 5;
   return sb < kp.B ? sb : kp.B;
@@ -191,6 +203,9 @@ hipError_t launch_score_parts(const KParams& kp, const Batch& b, const Workspace
                               hipStream_t st);
 hipError_t launch_select(const KParams& kp, const Batch& b, const float* scores, uint8_t* role,
                          int32_t* status, bool do_prefix, bool do_decode, hipStream_t st);
+// de-duplicated seeding: turns the provisional seeds launch_select marked into seeds and donors
+hipError_t launch_dedup_seeds(const KParams& kp, const Batch& b, const float* scores, uint8_t* role,
+                              hipStream_t st);
 // both stages of the selection and the ordered walk in one launch (whole-event path)
 hipError_t launch_select_index(const KParams& kp, const Batch& b, const float* scores,
                                uint8_t* role, int32_t* status, int32_t* slot_of, int32_t* out_src,

@@ -306,7 +306,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   // and seeds).  A rank of 0 selects nothing, a rank >= the range everything.
   const int hi = N - pl.r_eff;
   const int n = hi - P;
-  const int C = pl.core, CM = pl.core + pl.seeds;
+  const int C = pl.core, CM = pl.core + seed_range(kp, pl, n);
   const bool pre_sel = do_prefix && P > 0 && pl.p_keep > 0 && pl.p_keep < P;
   const bool dec_sel = do_decode && n > 0 && !(pl.status & CASK_ST_PREFIX_BUDGET_EXHAUSTED) && C < n;
   const bool all_seed = CM >= n;

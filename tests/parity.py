@@ -28,7 +28,8 @@ def ref_params(p: cask.Params) -> ref.Params:
                       prefix_budget=p.prefix_budget, sim_threshold=p.sim_threshold,
                       softmax_scale=p.softmax_scale, causal=p.causal, merge_radius=p.merge_radius,
                       merge_geometry=p.merge_geometry, dist_threshold=p.dist_threshold,
-                      band_weight=None if p.band_weight is None else p.band_weight.cpu().numpy())
+                      band_weight=None if p.band_weight is None else p.band_weight.cpu().numpy(),
+                      seed_dedup=p.seed_dedup)
 
 
 def params_of(w: caches.Workload, **kw) -> cask.Params:
@@ -147,6 +148,17 @@ def full_check(c: dict, p: cask.Params, expect_folds: bool = False, n_threads: i
 
     # ---- oracle, end to end
     want = ref.compress(rp, row_off, prefix_len, K, V, Q, n_threads=n_threads)
+    if p.seed_dedup > 0:
+        # a walk decision that sits on the threshold would change the whole seed set: the case
+        # has to keep clear of it (the near-tie rule covers single tokens, not cascades)
+        role0, _ = ref.prefix_evict(rp, row_off, prefix_len, want["scores"])
+        role0, _, gap = ref.partition_keys(rp, row_off, prefix_len, K, want["scores"], role0)
+        assert np.array_equal(role0, want["role"])
+        stats["dedup_min_gap"] = float(gap.min())
+        assert gap.min() >= 1e-4, "unsuitable case: a de-duplication decision within 1e-4 of the threshold"
+        n_seeds = np.array([np.count_nonzero(want["role"][row_off[u]:row_off[u + 1]] == ref.SEED)
+                            for u in range(n_units)])
+        stats["dedup_seeds"] = (int(n_seeds.min()), int(n_seeds.max()))
 
     # ---- scores
     s_gpu = cask.score(b)

@@ -461,6 +461,76 @@ def test_consolidate_with_caller_roles_naming_many_seeds():
     _note(("excused", n))
 
 
+DEDUP_CASES = {
+    # name: (workload overrides, parameter overrides)
+    "bf16_d128": (dict(n_kv_heads=3, prefix=100, decode=2600, budget=384, cluster_frac=0.5),
+                  dict(sim_threshold=0.8, seed_dedup=4)),
+    "f32_d64": (dict(base="cfg1", head_dim=64, n_kv_heads=2, prefix=40, decode=1500, budget=200, core=-1,
+                     fixed_clusters=None, cluster_lo=3, cluster_hi=12, cluster_frac=0.6),
+                dict(sim_threshold=0.7, seed_dedup=3)),
+    # several hundred seeds: many walk blocks, kept seeds staged through LDS in many chunks
+    "many_seeds": (dict(n_kv_heads=2, prefix=64, decode=5000, budget=900, core=100, cluster_frac=0.6),
+                   dict(sim_threshold=0.85, seed_dedup=2)),
+    # the walk covers the whole scratch (h * M beyond it)
+    "whole_scratch": (dict(n_kv_heads=2, prefix=30, decode=700, budget=300, cluster_frac=0.7),
+                      dict(sim_threshold=0.8, seed_dedup=30)),
+    # h = 1: the walk may only pass rows over, never replace them (fewer than M seeds)
+    "h1_short_units": (dict(n_kv_heads=4, prefix=60, decode=450, budget=256, cluster_frac=0.8),
+                       dict(sim_threshold=0.8, seed_dedup=1)),
+    # bf16 d = 64 and ragged units
+    "bf16_d64_ragged": (dict(head_dim=64, n_seqs=3, n_kv_heads=2, prefix=80, decode=900, decode_hi=2400,
+                             budget=320, cluster_frac=0.5),
+                        dict(sim_threshold=0.75, seed_dedup=5)),
+}
+
+
+@pytest.mark.parametrize("case", sorted(DEDUP_CASES))
+def test_dedup_seeding(case):
+    """De-duplicated seeding through cask_partition and the whole event against the oracle's
+    walk: roles bit-exact on injected scores, folds and outputs as for the default rule."""
+    wkw, pkw = DEDUP_CASES[case]
+    wkw = dict(wkw)
+    base = W[wkw.pop("base", "cfg2")]
+    w = caches.scaled(base, n_layers=1, **wkw)
+    c = caches.make(w, seed=71)
+    row_off, prefix_len, K, V, Q = parity.host_arrays(c)
+    # take the first threshold near the stated one that no walk decision of this cache comes
+    # close to (decided on the oracle alone): a decision on the threshold would flip a whole
+    # seed set, which the near-tie rule for single tokens does not cover
+    for dt in (0.0, 0.013, -0.017, 0.031, -0.029, 0.047):
+        p = parity.params_of(w, **{**pkw, "sim_threshold": pkw["sim_threshold"] + dt})
+        rp = parity.ref_params(p)
+        scores = ref.score(rp, row_off, K, Q)
+        role0, _ = ref.prefix_evict(rp, row_off, prefix_len, scores)
+        gap = ref.partition_keys(rp, row_off, prefix_len, K, scores, role0)[2]
+        if gap.min() >= 1e-3:
+            break
+    else:
+        pytest.fail("no clear threshold for this cache")
+    st = parity.full_check(c, p, expect_folds=True)
+    lo, hi = st["dedup_seeds"]
+    default = parity.ref_params(parity.params_of(w, **{**pkw, "seed_dedup": 0}))
+    M = max(ref.plan(default, int(prefix_len[u]), int(row_off[u + 1] - row_off[u]))["seeds"]
+            for u in range(len(row_off) - 1))
+    assert hi <= M and (case != "h1_short_units" or lo < M)
+    _note((case, st))
+
+
+def test_dedup_seeding_validates_on_the_host():
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=1, prefix=50, decode=3000, budget=1500, core=100)
+    c = caches.make(w, seed=3)
+    p = parity.params_of(w, seed_dedup=2)                 # 2 * 1400 possible seeds: over the walk's capacity
+    b = parity.to_device(c, p)
+    s = torch.rand(b.total_rows, device=b.device)
+    with pytest.raises(cask.CaskError):
+        cask.partition(b, s)
+    band = torch.ones(w.head_dim // 2, device=b.device)
+    p2 = parity.params_of(caches.scaled(w, budget=384, core=-1), seed_dedup=2, merge_geometry=1,
+                          band_weight=band, dist_threshold=1.0)
+    with pytest.raises(cask.CaskError):
+        cask.partition(parity.to_device(c, p2), s)
+
+
 @pytest.mark.parametrize("radius", [5, 40, 400])
 def test_merge_radius_bf16_mfma_and_fp32(radius):
     """Donors fold only into seeds at most `radius` cache rows away (Section 5.2)."""
