@@ -205,6 +205,28 @@ def test_merge_geometry_fields_validate_on_the_host(cask):
     assert rc(merge_geometry=1, band_weight=256, dist_threshold=3.0) == cask.binding.OK   # empty batch: no-op
 
 
+def test_seed_dedup_validates_on_the_host(cask):
+    """Negative multiples, the kappa geometry, and walks longer than the kernel's LDS list
+    (multiple x largest possible seed count > 2048) are refused before any HIP call."""
+    lib = cask.load()
+    b = cask.binding._Batch(0, None, None, None, None, None, None, None)
+
+    def rc(**kw):
+        cp = cask.Params().c()
+        for k, v in kw.items():
+            setattr(cp, k, v)
+        return lib.cask_partition(C.byref(cp), C.byref(b), None, None, None, None, 0, None)
+
+    assert rc(seed_dedup=0) == cask.binding.OK
+    assert rc(seed_dedup=4) == cask.binding.OK                 # budget 384: at most 77 seeds, 308 rows
+    assert rc(seed_dedup=-1) == cask.binding.EINVAL
+    assert rc(seed_dedup=2, merge_geometry=1, band_weight=256, dist_threshold=1.0) == cask.binding.EINVAL
+    assert rc(seed_dedup=26) == cask.binding.OK                # 26 * 77 = 2002
+    assert rc(seed_dedup=27) == cask.binding.EINVAL            # 27 * 77 = 2079
+    assert rc(seed_dedup=8, core=100) == cask.binding.EINVAL   # up to 284 seeds: 2272 rows
+    assert rc(seed_dedup=7, core=100) == cask.binding.OK
+
+
 def test_group_diagnostics_validates_on_the_host(cask):
     lib = cask.load()
     ok = cask.Params().c()

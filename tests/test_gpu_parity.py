@@ -484,10 +484,13 @@ DEDUP_CASES = {
 }
 
 
-@pytest.mark.parametrize("case", sorted(DEDUP_CASES))
-def test_dedup_seeding(case):
+@pytest.mark.parametrize("case", sorted(DEDUP_CASES) + ["bf16_d128_vector", "many_seeds_vector"])
+def test_dedup_seeding(case, monkeypatch):
     """De-duplicated seeding through cask_partition and the whole event against the oracle's
-    walk: roles bit-exact on injected scores, folds and outputs as for the default rule."""
+    walk: roles bit-exact on injected scores, folds and outputs as for the default rule.
+    bf16 caches take the MFMA kernel; "_vector" sends them through the one fp32 caches use."""
+    monkeypatch.setenv("CASK_DEDUP_VECTOR", "1" if case.endswith("_vector") else "0")
+    case = case[:-len("_vector")] if case.endswith("_vector") else case
     wkw, pkw = DEDUP_CASES[case]
     wkw = dict(wkw)
     base = W[wkw.pop("base", "cfg2")]
