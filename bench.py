@@ -61,6 +61,9 @@ def parse():
                     help="replays of the extra HIP-graph measurement (0 = skip)")
     ap.add_argument("--overlap-steps", type=int, default=50,
                     help="events of the extra two-stream measurement (0 = skip)")
+    ap.add_argument("--seed-dedup", type=int, default=0,
+                    help="cask_params.seed_dedup for the event (0 = the default seeding rule; the headline "
+                         "figure is quoted with 0)")
     ap.add_argument("--attend-steps", type=int, default=50,
                     help="after the timed region: time the consumer side, one decode step's attention "
                          "(cask_attend) over the compressed caches the event wrote (0 = skip)")
@@ -103,7 +106,7 @@ def main():
     n_layers = args.layers if args.layers > 0 else w.n_layers
     p = cask.Params(dtype=cask.F32 if w.dtype == "f32" else cask.BF16, head_dim=w.head_dim,
                     q_per_kv=w.q_per_kv, window=w.window, recent=w.recent, budget=w.budget,
-                    core=w.core)
+                    core=w.core, seed_dedup=args.seed_dedup)
 
     # ---- inputs, resident in HBM; alternate copies so the 256 MB last-level cache cannot
     # stand in for HBM between steps
@@ -302,7 +305,7 @@ def main():
         sub_ro = np.concatenate([[0], np.cumsum(sub_lens)]).astype(np.int64)
         sub_pl = b0.prefix_len_host.numpy()[pick]
         rp = ref.Params(dtype=p.dtype, head_dim=p.head_dim, q_per_kv=p.q_per_kv, window=p.window,
-                        recent=p.recent, budget=p.budget, core=p.core)
+                        recent=p.recent, budget=p.budget, core=p.core, seed_dedup=p.seed_dedup)
         threads = min(int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), os.cpu_count() or 1, take)
         tc0 = time.perf_counter()
         want = ref.compress(rp, sub_ro, sub_pl, Kh, Vh, Qh, n_threads=threads)
@@ -336,7 +339,7 @@ def main():
                       (str(w.decode) if w.decode_hi is None else "%d..%d" % (w.decode, w.decode_hi)), w.window, w.budget),
                    "units": n_units, "kv_tokens_per_event": kv_tokens,
                    "seq_tokens_per_s": round(value / (n_layers * w.n_kv_heads), 1),
-                   "input_copies": copies, "saved_ratio": round(saved, 4),
+                   "input_copies": copies, "saved_ratio": round(saved, 4), "seed_dedup": args.seed_dedup,
                    "status_counts": {str(k): int(v) for k, v in zip(*np.unique(status, return_counts=True))},
                    "stage_ms": ({k: round(v, 4) for k, v in stage_ms.items()} if stage_ms else None),
                    "event_ms_spread": spread,

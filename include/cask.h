@@ -97,7 +97,10 @@ typedef struct {
      with a seed chosen before it is >= sim_threshold, until M seeds are chosen; rows passed
      over, and all rows behind the walk, are donors; fewer than M seeds (out_len < B) may
      result.  Needs merge_geometry 0 and h * (largest M of the plan) <= 2048, else
-     CASK_EINVAL.  Applies to cask_partition, cask_compress and cask_compress_step. */
+     CASK_EINVAL.  Applies to cask_partition, cask_compress and cask_compress_step.  bf16
+     caches run the walk's cosines on the matrix cores; the environment variable
+     CASK_DEDUP_VECTOR=1, read at every call, sends them through the vector kernel that
+     serves fp32 caches (for comparisons). */
   int32_t seed_dedup;
 } cask_params;
 
