@@ -273,3 +273,15 @@ def test_attend_validates_on_the_host(cask):
     assert rc(count=fake, pitch=0) == cask.binding.EINVAL
     assert rc(params=None) == cask.binding.EINVAL
     assert rc(params=cask.Params(head_dim=100).c()) == cask.binding.EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU is what this build measures: `bench.py --gpus 2` says so and exits before it
+    touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
