@@ -20,7 +20,12 @@
  * implements it.  The constants of those readings (tau = 0.9, the quarter share
  * and 1/64 floor of the prefix budget, the 4/5 core share, softmax-mean scoring)
  * have no external anchor: "parity unpinned" for those constants -- they are
- * parameters with defaults, pinned only by self-consistency tests.
+ * parameters with defaults, pinned only by self-consistency tests.  The same holds for
+ * the choice of two later rules the paper leaves open altogether -- how attention weighs a
+ * representative (cask_ref_attend: count-proportional) and how seeds avoid duplicates
+ * (seed_dedup: the greedy walk): what each function computes is pinned (library softmax and
+ * the repeated-row identity; the properties that characterise the walk), that the paper
+ * would choose these rules is not.
  *
  * All pointers are HOST pointers owned by the caller.
  */
