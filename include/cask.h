@@ -256,7 +256,9 @@ int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, c
  * no workspace.  Decoded tokens appended behind the compressed rows attend the same way (their
  * count is 1): pass the buffer with its row stride and the enlarged len.  bf16 caches run on
  * the matrix cores; the environment variable CASK_ATTEND_VECTOR=1, read at every call, sends
- * them through the vector kernel that serves fp32 caches (for comparisons). */
+ * them through the vector kernel that serves fp32 caches (for comparisons).  The first call of
+ * a kernel variant in a process raises that kernel's LDS limit (a function attribute, not a
+ * stream operation): make one call before capturing the stream into a HIP graph. */
 int cask_attend(const cask_params* params, int32_t n_units, const void* Q, const void* K_c,
                 const void* V_c, int32_t stride_rows, const int32_t* len, const int32_t* count,
                 int32_t count_pitch, void* out, void* hip_stream);

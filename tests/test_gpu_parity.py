@@ -978,6 +978,61 @@ def test_compress_replays_from_a_hip_graph():
     _note("graph replays equal the eager event")
 
 
+def test_step_with_dedup_and_attention_replay_from_a_hip_graph():
+    """A decode-loop step with de-duplicated seeding (three selection launches) followed by the
+    consumer's attention over its output, captured as one graph: every replay equals eager."""
+    dev = torch.device("cuda:0")
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=3, prefix=80, decode=1900, budget=384, cluster_frac=0.5)
+    c = caches.make(w, seed=19)
+    p = parity.params_of(w, sim_threshold=0.8, seed_dedup=4)
+    b = parity.to_device(c, p)
+    S = 512
+    q = torch.randn(b.n_units, w.q_per_kv, w.head_dim, generator=torch.Generator().manual_seed(2)).to(torch.bfloat16).to(dev)
+
+    def run(out, Ko, Vo, oc, att):
+        cask.compress_step(b, Ko, Vo, out, out_count=oc)
+        cask.attend(p, q, Ko, Vo, out.out_len, count=oc, out=att)
+
+    def fresh():
+        Ko = torch.zeros(b.n_units, S, w.head_dim, dtype=torch.bfloat16, device=dev)
+        return (cask.Outputs(b), Ko, torch.zeros_like(Ko),
+                torch.zeros(b.n_units, p.budget, dtype=torch.int32, device=dev), torch.empty_like(q))
+
+    eager = fresh()
+    run(*eager)
+    torch.cuda.synchronize()
+    assert int(eager[3].max()) > 1                      # something folded
+    cap = fresh()
+    b.workspace()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(*cap)                                       # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run(*cap)
+    for rep in range(3):
+        for t in (cap[1], cap[2], cap[4]):
+            t.zero_()
+        cap[3].zero_()
+        cap[0].out_src.fill_(-7)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(cap[0].out_len, eager[0].out_len) and torch.equal(cap[0].status, eager[0].status)
+        assert torch.equal(cap[0].assign, eager[0].assign)
+        for u in range(b.n_units):
+            n = int(eager[0].out_len[u])
+            assert torch.equal(cap[0].out_src[u, :n], eager[0].out_src[u, :n])
+            assert torch.equal(cap[1][u, :n], eager[1][u, :n]) and torch.equal(cap[2][u, :n], eager[2][u, :n])
+            assert torch.equal(cap[3][u, :n], eager[3][u, :n])
+        assert torch.equal(cap[4], eager[4])
+        cask.score(b)                                   # eager work between the replays
+        torch.cuda.synchronize()
+
+
 def test_argument_errors_and_empty_batch():
     dev = torch.device("cuda:0")
     p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=2, window=16, budget=64)
