@@ -169,8 +169,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 //   values   O[dim][head] += V_tile^T (D x 32) . P (32 x heads), 32 dims per product.
 // The lane pair of a head column holds that head's 32 logits in registers and takes the block
 // step of the online softmax there (running maximum, correction factor, weights); the weights,
-// rounded to bf16, are the second product's operand as they stand, because the order in which
-// a lane holds its keys is a permutation the value operand simply repeats.  The value rows
+// each split into two bf16 terms, are the second product's operand as they stand, because the
+// order in which a lane holds its keys is a permutation the value operand simply repeats.  The
+// query operand, the same for every wave and tile, waits in LDS.  The value rows
 // reach their operand layout (a lane: 8 keys of one dim) through a wave-private LDS area,
 // written transposed 2 bytes at a time and read back 16 bytes at a time.  The result columns of
 // a head live in the same lanes as its softmax state, so nothing but the value rows crosses
