@@ -267,6 +267,7 @@ def main():
         t_dom = sweep_ms[dom] * 1e-3
         # short units: both sweeps are one launch (score_mfma_kernel<2>), bracketed as the first stage
         one_launch = (w.dtype != "f32" and p.head_dim == 128 and int(lens.max()) <= 1024 and p.budget <= 1024
+                      and args.seed_dedup == 0
                       and os.environ.get("CASK_FUSED_TAIL", "1")[0] != "0"
                       and os.environ.get("CASK_FUSED_SCORE", "1")[0] != "0")
         passes = 2.0 if one_launch else 1.0
