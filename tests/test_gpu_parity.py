@@ -1072,13 +1072,13 @@ def test_argument_errors_and_empty_batch():
 
 # ------------------------------------------------------------------ full benchmark sizes
 
-def _full_size(name, sample_units, seed=caches.BASE_SEED):
+def _full_size(name, sample_units, seed=caches.BASE_SEED, layers=None):
     """Whole workload on the GPU in the benchmark's launch configuration; the oracle runs on a
     sample of units (each regenerated bit-identically on the host is not needed: the sampled
     rows are copied back)."""
     w = W[name]
     dev = torch.device("cuda:0")
-    c = caches.make(w, seed=seed, device=dev)
+    c = caches.make(w, seed=seed, device=dev, layers=layers)
     p = parity.params_of(w)
     b = cask.Batch(p, c["row_off"], c["prefix_len"], c["K"], c["V"], c["Q"])
     out = cask.compress(b)
@@ -1086,6 +1086,8 @@ def _full_size(name, sample_units, seed=caches.BASE_SEED):
     got = parity.gpu_outputs(out, p)
     ro = b.row_off_host.numpy()
     n_units = b.n_units
+    if callable(sample_units):
+        sample_units = sample_units(ro)
     # properties that hold at any size
     sums = np.add.reduceat(got["scores"].astype(np.float64), ro[:-1])
     np.testing.assert_allclose(sums, 1.0, atol=2e-5)
@@ -1128,6 +1130,17 @@ def test_cfg3_full_size_sampled_units():
 
 def test_cfg4_full_size_sampled_units():
     _full_size("cfg4", [1, 60])
+
+
+def test_cfg5_ragged_many_units_sampled():
+    """Two of cfg5's 32 layers (1024 ragged units of 4.6k - 33k rows, G = 4): the many-units
+    launch configuration (one key split, thousands of workgroups per sweep); the oracle runs
+    on the shortest unit and on one of median length."""
+    def pick(ro):
+        lens = ro[1:] - ro[:-1]
+        order = np.argsort(lens, kind="stable")
+        return [int(order[0]), int(order[len(order) // 2])]
+    _full_size("cfg5", pick, layers=range(2))
 
 
 def test_cfg4v_full_size_exhausted():
