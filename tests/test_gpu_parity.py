@@ -935,6 +935,47 @@ def test_step_zero_mass_groups_average_by_token_count():
     _note(("zero-mass folds", folded))
 
 
+def test_step_with_dedup_seeding_counts_and_row_stride():
+    """A decode-loop step (token counts in, counts out, output row stride beyond the budget)
+    with de-duplicated seeding, on injected scores: source rows, folded values and counts
+    against the oracle's step."""
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=3, prefix=70, decode=1700, budget=320, cluster_frac=0.6)
+    c = caches.make(w, seed=29)
+    row_off, plen, K, V, Q = parity.host_arrays(c)
+    total, S = int(row_off[-1]), 448
+    rng = np.random.default_rng(12)
+    cnt = rng.integers(1, 6, total).astype(np.int32)
+    for dt in (0.0, 0.013, -0.017, 0.031, -0.029, 0.047):
+        p = parity.params_of(w, sim_threshold=0.8 + dt, seed_dedup=4)
+        rp = parity.ref_params(p)
+        s = ref.score(rp, row_off, K, Q)
+        role0, _ = ref.prefix_evict(rp, row_off, plen, s)
+        if ref.partition_keys(rp, row_off, plen, K, s, role0)[2].min() >= 1e-3:
+            break
+    else:
+        pytest.fail("no clear threshold for this cache")
+    want = ref.compress_step(rp, row_off, plen, K, V, Q, in_count=cnt, scores=s, out_stride_rows=S)
+    b = parity.to_device(c, p)
+    out = cask.Outputs(b)
+    Ko = torch.zeros(b.n_units, S, p.head_dim, dtype=torch.bfloat16, device=b.device)
+    Vo = torch.zeros_like(Ko)
+    oc = torch.zeros(b.n_units, p.budget, dtype=torch.int32, device=b.device)
+    cask.compress_step(b, Ko, Vo, out, in_count=torch.from_numpy(cnt).to(b.device), out_count=oc,
+                       scores=torch.from_numpy(s).to(b.device))
+    torch.cuda.synchronize()
+    got = dict(K_out=caches.host_bits(Ko), V_out=caches.host_bits(Vo), out_len=out.out_len.cpu().numpy(),
+               out_src=out.out_src.cpu().numpy(), out_mass=out.out_mass.cpu().numpy(),
+               assign=out.assign.cpu().numpy())
+    assert np.array_equal(got["out_len"], want["out_len"]) and np.array_equal(got["out_src"], want["out_src"])
+    d = p.head_dim
+    folded = parity.check_values(p, got, want, K.reshape(-1, d), V.reshape(-1, d), row_off)
+    assert folded >= 5
+    if np.array_equal(got["assign"], want["assign"]):
+        assert np.array_equal(oc.cpu().numpy(), want["out_count"])
+        assert int(want["out_count"].max()) > int(cnt.max())      # counts of folded rows add up
+    _note(("dedup step", "folded rows", folded, "largest count", int(want["out_count"].max())))
+
+
 def test_compress_replays_from_a_hip_graph():
     """The whole event is plain kernel launches on the caller's stream (no allocation, no
     synchronisation, no memset): it can be captured once and replayed; every replay must equal
