@@ -27,6 +27,12 @@
  *     [row_off[u], row_off[u+1]).  row_off and prefix_len live on the device AND are
  *     mirrored on the host (the host copy sizes the launches).
  *   - Calls that share a workspace on different streams race; one workspace per stream.
+ *   - The first launch of a kernel on a device raises that kernel's LDS limit (a function
+ *     attribute, not a stream operation; the scoring sweeps, the one-launch scoring and
+ *     cask_attend's matrix-core kernels need more than the default 64 KB): make one call of an
+ *     entry point with the shapes in question before capturing the stream into a HIP graph.
+ *   - Entry points may be called from several host threads (each on its own stream and
+ *     workspace); the timing aid at the end of this header records one stream at a time.
  */
 #ifndef CASK_H
 #define CASK_H
@@ -98,11 +104,24 @@ typedef struct {
      over, and all rows behind the walk, are donors; fewer than M seeds (out_len < B) may
      result.  Needs merge_geometry 0 and h * (largest M of the plan) <= 2048, else
      CASK_EINVAL.  Applies to cask_partition, cask_compress and cask_compress_step.  bf16
-     caches run the walk's cosines on the matrix cores; the environment variable
-     CASK_DEDUP_VECTOR=1, read at every call, sends them through the vector kernel that
-     serves fp32 caches (for comparisons). */
+     caches run the walk's cosines on the matrix cores (CASK_PATH_DEDUP_VECTOR in path_flags
+     sends them through the vector kernel that serves fp32 caches, for comparisons). */
   int32_t seed_dedup;
+  /* Path selection for measurements and tests; all zero = the library's own choice.  None of
+     them changes what is computed (results agree bit for bit, or to the scoring tolerance where
+     a different kernel sums in another order). */
+  uint32_t path_flags;   /* CASK_PATH_* bits below */
+  int32_t score_splits;  /* 1..64: key splits of the first scoring sweep; 0 = chosen by a cost model */
+  int32_t score_qsplit;  /* 1 | 2: workgroups sharing a key tile in the second sweep; 0 = chosen */
 } cask_params;
+
+enum {
+  CASK_PATH_NO_FUSED_TAIL = 1,  /* short units: the general kernels instead of the one-launch tail */
+  CASK_PATH_NO_FUSED_SCORE = 2, /* short units: two scoring launches instead of one */
+  CASK_PATH_DEDUP_VECTOR = 4,   /* bf16 de-duplicated seeding on the vector kernel fp32 caches use */
+  CASK_PATH_ATTEND_VECTOR = 8,  /* bf16 cask_attend on the vector kernel fp32 caches use */
+  CASK_PATH_NO_FUSED_SWEEPS = 16 /* long units with few window rows: two scoring launches instead of one */
+};
 
 typedef struct {
   int32_t n_units;
@@ -128,11 +147,8 @@ typedef struct {
 /* HOST: the split for prefix length P and cache length N.  Returns CASK_EINVAL on bad sizes. */
 int cask_plan(const cask_params* params, int32_t P, int32_t N, cask_plan_t* out);
 
-/* HOST: bytes of device workspace every entry point below needs for such a batch.
- * (Measurement overrides, read from the environment when the workspace is laid out and at
- * every scoring call, so they must not change between the two: CASK_SPLITS = 1..64 fixes the
- * number of key splits of the first scoring sweep, CASK_QSPLIT = 1 | 2 the number of
- * workgroups that share a key tile in the second.  Neither changes what is computed.) */
+/* HOST: bytes of device workspace every entry point below needs for such a batch (with the
+ * same params: score_splits and score_qsplit enter the layout). */
 size_t cask_workspace_bytes(const cask_params* params, int32_t n_units, int64_t total_rows,
                             int32_t max_unit_len);
 
@@ -166,8 +182,8 @@ int cask_consolidate(const cask_params* params, const cask_batch* batch, const f
 /* The whole event (Sections 2.1-2.4).  (A batch whose units all have at most 1024 rows, with
  * B <= 1024, bf16 and the cosine geometry, takes a one-launch path after scoring; results and
  * tie rules are the same; with d = 128 the two scoring sweeps of such a batch are one launch
- * as well.  The environment variables CASK_FUSED_TAIL=0 and CASK_FUSED_SCORE=0, read at every
- * call, switch these paths off.)
+ * as well; CASK_PATH_NO_FUSED_TAIL and CASK_PATH_NO_FUSED_SCORE in path_flags switch these
+ * paths off.)
  *   K_out, V_out [n_units, B, d]  rows [0, out_len[u]) in ascending source order; a
  *                                 representative sits at its seed's position; kept tokens
  *                                 are bit-identical copies; rows >= out_len[u] untouched
@@ -252,13 +268,12 @@ int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, c
  *   count [n_units, count_pitch] device or NULL (cask_compress_step's out_count; values < 1
  *         are not validated and count as 1, and so do rows at or behind count_pitch)
  *   out   [n_units, G, d]               device, cache dtype (fp32 accumulation, rounded once)
- * All data pointers 16-byte aligned.  scale = softmax_scale, 1/sqrt(d) when that is 0.  Needs
+ * All data pointers 16-byte aligned.  scale = softmax_scale, 1/sqrt(d) when that is <= 0.  Needs
  * no workspace.  Decoded tokens appended behind the compressed rows attend the same way (their
  * count is 1): pass the buffer with its row stride and the enlarged len.  bf16 caches run on
- * the matrix cores; the environment variable CASK_ATTEND_VECTOR=1, read at every call, sends
- * them through the vector kernel that serves fp32 caches (for comparisons).  The first call of
- * a kernel variant in a process raises that kernel's LDS limit (a function attribute, not a
- * stream operation): make one call before capturing the stream into a HIP graph. */
+ * the matrix cores (CASK_PATH_ATTEND_VECTOR in path_flags sends them through the vector kernel
+ * that serves fp32 caches, for comparisons).  (Graph capture: see the
+ * note on LDS limits at the top of this header.) */
 int cask_attend(const cask_params* params, int32_t n_units, const void* Q, const void* K_c,
                 const void* V_c, int32_t stride_rows, const int32_t* len, const int32_t* count,
                 int32_t count_pitch, void* out, void* hip_stream);
@@ -278,7 +293,7 @@ int cask_attend(const cask_params* params, int32_t n_units, const void* Q, const
  * per stage into stage_ms[CASK_N_STAGES] and the number of recorded calls into *n_calls,
  * and rearms.  cask_timing_enable_stages(n, k) records only the first k stages (k = 2: the two
  * scoring sweeps, three events per call instead of eight); the other entries read as 0.
- * Not thread-safe; one stream at a time. */
+ * The bookkeeping is guarded by a lock; the events of one recording belong to one stream. */
 #define CASK_N_STAGES 7
 int cask_timing_enable(int max_calls);
 int cask_timing_enable_stages(int max_calls, int n_stages);

@@ -102,55 +102,52 @@ static int check_unit(const cask_ref_params* p, int64_t N, int64_t P) {
  *     representatives.
  */
 void cask_ref_plan(const cask_ref_params* p, int32_t P, int32_t N, cask_ref_plan_t* out) {
-  int32_t R = resolved_recent(p);
-  int32_t B = p->budget;
-  int32_t D = N - P;
-  int32_t r_eff = R < D ? R : D;
-  int32_t dnr = D - r_eff;
+  const int32_t B = p->budget;
+  const int32_t decode = N - P;
+  const int32_t recent = resolved_recent(p) < decode ? resolved_recent(p) : decode;
+  const int32_t scratch_span = decode - recent; /* decode tokens that compete for slots */
   memset(out, 0, sizeof(*out));
-  out->r_eff = r_eff;
-  if (N <= B) {
+  out->r_eff = recent;
+  if (N <= B) { /* everything fits: every token is kept as it is */
     out->p_keep = P;
-    out->slots = dnr;
-    out->core = dnr;
-    out->seeds = 0;
+    out->slots = scratch_span;
+    out->core = scratch_span;
     out->status = CASK_REF_ST_IDENTITY;
     return;
   }
-  int32_t bp;
-  if (p->prefix_budget >= 0) {
-    bp = p->prefix_budget;
-  } else {
-    int32_t quarter = B / 4;
-    int32_t floor64 = (P + 63) / 64;
-    bp = quarter > floor64 ? quarter : floor64;
+  /* What the prefix may claim: its own budget B_p, or the space the decode trace would leave
+   * empty, whichever is larger.  Stage 1 keeps the largest prefix count that respects this
+   * claim, the prefix length and the room beside the recent tail: the conditions are tested
+   * one candidate count after the other, from the top. */
+  int32_t own = p->prefix_budget;
+  if (own < 0) {
+    own = B / 4;
+    while ((int64_t)own * 64 < P) ++own; /* at least one kept token per 64 prefix tokens, rounded up */
   }
-  int32_t room = B - r_eff;          /* what prefix and non-recent decode share */
-  int32_t unused = room - dnr;       /* space the decode trace cannot fill */
-  int32_t want = bp > unused ? bp : unused;
-  int32_t p_keep = P;
-  if (room < p_keep) p_keep = room;
-  if (want < p_keep) p_keep = want;
-  out->p_keep = p_keep;
-  out->slots = room - p_keep;
-  if (dnr <= out->slots) {
-    out->core = dnr;
-    out->seeds = 0;
+  const int32_t beside_recent = B - recent;
+  const int32_t idle = beside_recent - scratch_span; /* negative when the decode trace overflows */
+  const int32_t claim = own > idle ? own : idle;
+  int32_t keep = P < beside_recent ? P : beside_recent;
+  while (keep > 0 && keep > claim) --keep;
+  out->p_keep = keep;
+  out->slots = beside_recent - keep;
+  /* decode tokens that cannot be kept verbatim in the slots */
+  const int32_t overflow = scratch_span - out->slots;
+  if (overflow <= 0) { /* all of them fit (also: no such token at all): nothing to consolidate */
+    out->core = scratch_span;
     out->status = CASK_REF_ST_MERGE_INACTIVE;
-  } else if (out->slots == 0) {
-    out->core = 0;
-    out->seeds = 0;
-    out->status = CASK_REF_ST_PREFIX_BUDGET_EXHAUSTED;
-  } else {
-    int32_t c;
-    if (p->core >= 0)
-      c = p->core < out->slots ? p->core : out->slots;
-    else
-      c = (int32_t)((4LL * out->slots) / 5);
-    out->core = c;
-    out->seeds = out->slots - c;
-    out->status = out->seeds == 0 ? CASK_REF_ST_MERGE_INACTIVE : CASK_REF_ST_ACTIVE;
+    return;
   }
+  if (out->slots == 0) { /* tokens wait and the prefix left them nothing (Section 5.2) */
+    out->status = CASK_REF_ST_PREFIX_BUDGET_EXHAUSTED;
+    return;
+  }
+  if (p->core >= 0)
+    out->core = p->core < out->slots ? p->core : out->slots;
+  else
+    out->core = (int32_t)(((int64_t)out->slots * 4) / 5);
+  out->seeds = out->slots - out->core;
+  out->status = out->seeds > 0 ? CASK_REF_ST_ACTIVE : CASK_REF_ST_MERGE_INACTIVE;
 }
 
 /* ------------------------------------------------------------------ scoring
@@ -383,9 +380,9 @@ int cask_ref_partition_keys(const cask_ref_params* p, int32_t n_units, const int
 
 /* ------------------------------------------------------------------ consolidation
  *
- * A scratch token need not be kept "as long as a sufficiently similar representative
- * remains" (Section 1); similarity is raw cosine between cached keys (Section 2.5 names raw
- * cosine as the plain geometry).  Reading taken: each donor looks at every seed, picks the
+ * A scratch token can go once a representative close enough to it stays in the cache
+ * (Section 1); similarity is raw cosine between cached keys (Section 2.5 names raw cosine as
+ * the plain geometry).  Reading taken: each donor looks at every seed, picks the
  * seed of largest cosine (ties: lowest cache index), and folds into it when that cosine is
  * >= tau; otherwise it is evicted.  Core tokens neither give nor receive merges (Section 2.1).
  */
@@ -724,7 +721,7 @@ int cask_ref_attend(const cask_ref_params* p, int32_t n_units, const void* Q, co
   if (!p || !Q || !K_c || !V_c || !len || !out || n_units < 0) return -1;
   if (check_shape(p) != 0) return -1;
   const int d = p->head_dim, G = p->q_per_kv;
-  const double scale = p->softmax_scale != 0.0f ? (double)p->softmax_scale : 1.0 / sqrt((double)d);
+  const double scale = p->softmax_scale > 0.0f ? (double)p->softmax_scale : 1.0 / sqrt((double)d);
   for (int32_t u = 0; u < n_units; ++u) {
     const int32_t L = len[u];
     if (L < 1 || L > stride_rows || (count && L > count_pitch)) return -1;

@@ -192,8 +192,8 @@ int cask_ref_group_diagnostics(const cask_ref_params* p, int32_t n_units, const 
                                const void* K_out, int32_t out_stride_rows, float* dispersion,
                                float* lost_mass);
 
-/* Consumer side: one decode step's attention over a compressed cache.  The paper folds keys and
- * values "while preserving group mass" (Section 2.4) and leaves the consumer open; the reading
+/* Consumer side: one decode step's attention over a compressed cache.  A fold keeps the mass of its
+ * group (Section 2.4); what a consumer does with it the paper leaves open; the reading
  * taken here is proportional attention: a row that stands for n original tokens enters the
  * softmax with n times its weight,
  *     p_t = softmax_t( scale * <q, k_t> + ln(count_t) ),   o = sum_t p_t v_t,
@@ -204,7 +204,7 @@ int cask_ref_group_diagnostics(const cask_ref_params* p, int32_t n_units, const 
  *   K_c, V_c [n_units, stride_rows, d]  rows [0, len[u]) in use
  *   count [n_units, count_pitch] or NULL (count_pitch >= max len)
  *   out [n_units, G, d] double (not rounded to the cache dtype)
- * scale = softmax_scale, or 1/sqrt(d) when that is 0. */
+ * scale = softmax_scale, or 1/sqrt(d) when that is <= 0 (the one rule of every scorer here). */
 int cask_ref_attend(const cask_ref_params* p, int32_t n_units, const void* Q, const void* K_c,
                     const void* V_c, int32_t stride_rows, const int32_t* len, const int32_t* count,
                     int32_t count_pitch, double* out);

@@ -23,7 +23,14 @@ PREFIX_DROP, PREFIX_KEEP, CORE, SEED, DONOR, RECENT, DECODE_EVICT = range(7)
 
 
 def build(force: bool = False) -> str:
-    """Compile cask_ref.c with gcc into libcask_ref.so next to this file."""
+    """Compile cask_ref.c with gcc into libcask_ref.so next to this file.  (CASK_REF_LIB in the
+    environment names another build of the same source to load instead, e.g. one made with
+    sanitizers by tests/test_sanitizers.py; nothing is compiled then.)"""
+    global _LIB_PATH
+    other = os.environ.get("CASK_REF_LIB")
+    if other:
+        _LIB_PATH = other
+        return _LIB_PATH
     src = os.path.join(_HERE, "cask_ref.c")
     hdr = os.path.join(_HERE, "cask_ref.h")
     if (not force and os.path.exists(_LIB_PATH)

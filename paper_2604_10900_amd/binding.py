@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libcask.so")
 F32, BF16 = 0, 1
 OK, EINVAL, ENOMEM, EDEVICE = 0, -1, -2, -3
 ST_ACTIVE, ST_IDENTITY, ST_PREFIX_BUDGET_EXHAUSTED, ST_MERGE_INACTIVE = 0, 1, 2, 4
+PATH_NO_FUSED_TAIL, PATH_NO_FUSED_SCORE, PATH_DEDUP_VECTOR, PATH_ATTEND_VECTOR, PATH_NO_FUSED_SWEEPS = 1, 2, 4, 8, 16
 (ROLE_PREFIX_DROP, ROLE_PREFIX_KEEP, ROLE_CORE, ROLE_SEED, ROLE_DONOR, ROLE_RECENT,
  ROLE_DECODE_EVICT) = range(7)
 
@@ -44,7 +45,8 @@ class _Params(C.Structure):
                 ("sim_threshold", C.c_float), ("softmax_scale", C.c_float),
                 ("causal", C.c_int32), ("scores_given", C.c_int32), ("merge_radius", C.c_int32),
                 ("merge_geometry", C.c_int32), ("dist_threshold", C.c_float), ("band_weight", C.c_void_p),
-                ("seed_dedup", C.c_int32)]
+                ("seed_dedup", C.c_int32), ("path_flags", C.c_uint32), ("score_splits", C.c_int32),
+                ("score_qsplit", C.c_int32)]
 
 
 class _Batch(C.Structure):
@@ -76,6 +78,9 @@ class Params:
     dist_threshold: float = 0.0    # geometry 1: fold iff distance <= this
     band_weight: Optional[torch.Tensor] = None   # geometry 1: device float32 [head_dim / 2], >= 0
     seed_dedup: int = 0            # h > 0: seeds chosen greedily among the best h * M scratch rows
+    path_flags: int = 0            # PATH_* bits: kernel choice for measurements and tests
+    score_splits: int = 0          # forced key splits of the first scoring sweep (0: the library's choice)
+    score_qsplit: int = 0          # forced sharing of a key tile in the second sweep (0: the library's choice)
 
     def c(self, scores_given: int = 0) -> _Params:
         bw = None
@@ -86,7 +91,35 @@ class Params:
         return _Params(self.dtype, self.head_dim, self.q_per_kv, self.window, self.recent,
                        self.budget, self.core, self.prefix_budget, self.sim_threshold,
                        self.softmax_scale, self.causal, scores_given, self.merge_radius,
-                       self.merge_geometry, self.dist_threshold, bw, self.seed_dedup)
+                       self.merge_geometry, self.dist_threshold, bw, self.seed_dedup,
+                       self.path_flags | _env_path_flags(), self.score_splits or _env_int("CASK_SPLITS"),
+                       self.score_qsplit or _env_int("CASK_QSPLIT"))
+
+
+def _env_int(name: str) -> int:
+    try:
+        return int(os.environ.get(name, "0"))
+    except ValueError:
+        return 0
+
+
+def _env_path_flags() -> int:
+    """Measurement switches of the Python layer (the library itself reads no environment):
+    CASK_FUSED_TAIL=0, CASK_FUSED_SCORE=0, CASK_FUSED_SWEEPS=0, CASK_DEDUP_VECTOR=1,
+    CASK_ATTEND_VECTOR=1 set the matching PATH_* bit of every call made through this binding."""
+    env = os.environ
+    f = 0
+    if env.get("CASK_FUSED_TAIL", "1")[:1] == "0":
+        f |= PATH_NO_FUSED_TAIL
+    if env.get("CASK_FUSED_SCORE", "1")[:1] == "0":
+        f |= PATH_NO_FUSED_SCORE
+    if env.get("CASK_FUSED_SWEEPS", "1")[:1] == "0":
+        f |= PATH_NO_FUSED_SWEEPS
+    if env.get("CASK_DEDUP_VECTOR", "0")[:1] == "1":
+        f |= PATH_DEDUP_VECTOR
+    if env.get("CASK_ATTEND_VECTOR", "0")[:1] == "1":
+        f |= PATH_ATTEND_VECTOR
+    return f
 
 
 _lib = None
@@ -94,31 +127,38 @@ _lib = None
 
 def load():
     """Load libcask.so (built in-tree by paper_2604_10900_amd.build.build_lib)."""
-    global _lib
+    global _lib, LIB_PATH
     if _lib is None:
+        # CASK_LIB names another build of the same sources to load (the host-sanitizer test)
+        LIB_PATH = os.environ.get("CASK_LIB") or LIB_PATH
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with "
                               "`python -c 'import __graft_entry__ as g; g.build()'`")
         lib = C.CDLL(LIB_PATH)
-        lib.cask_workspace_bytes.restype = C.c_size_t
-        lib.cask_workspace_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32]
-        lib.cask_strerror.restype = C.c_char_p
-        lib.cask_strerror.argtypes = [C.c_int]
-        lib.cask_plan.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
-        vp = C.c_void_p
-        lib.cask_score.argtypes = [vp, vp, vp, vp, C.c_size_t, vp]
-        lib.cask_prefix_evict.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
-        lib.cask_partition.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
-        lib.cask_consolidate.argtypes = [vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
-        lib.cask_compress.argtypes = [vp] * 11 + [C.c_size_t, vp]
-        lib.cask_timing_enable.argtypes = [C.c_int]
-        lib.cask_timing_enable_stages.argtypes = [C.c_int, C.c_int]
-        lib.cask_timing_read.argtypes = [vp, vp]
-        for name in ("cask_plan", "cask_score", "cask_prefix_evict", "cask_partition",
-                     "cask_consolidate", "cask_compress", "cask_compress_step", "cask_mass_diagnostics",
-                     "cask_timing_enable",
-                     "cask_timing_read"):
-            getattr(lib, name).restype = C.c_int
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        # (restype, argtypes) of every entry point include/cask.h declares: without them ctypes
+        # would pass a Python int as a 32-bit C int, which truncates a size_t workspace size
+        sigs = {
+            "cask_plan": (C.c_int, [vp, i32, i32, vp]),
+            "cask_workspace_bytes": (sz, [vp, i32, i64, i32]),
+            "cask_score": (C.c_int, [vp, vp, vp, vp, sz, vp]),
+            "cask_prefix_evict": (C.c_int, [vp, vp, vp, vp, vp, vp, sz, vp]),
+            "cask_partition": (C.c_int, [vp, vp, vp, vp, vp, vp, sz, vp]),
+            "cask_consolidate": (C.c_int, [vp, vp, vp, vp, vp, vp, sz, vp]),
+            "cask_compress": (C.c_int, [vp] * 11 + [sz, vp]),
+            "cask_compress_step": (C.c_int, [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
+            "cask_mass_diagnostics": (C.c_int, [vp] * 8),
+            "cask_group_diagnostics": (C.c_int, [vp, vp, vp, vp, vp, i32, vp, vp, vp]),
+            "cask_attend": (C.c_int, [vp, i32, vp, vp, vp, i32, vp, vp, i32, vp, vp]),
+            "cask_strerror": (C.c_char_p, [C.c_int]),
+            "cask_timing_enable": (C.c_int, [C.c_int]),
+            "cask_timing_enable_stages": (C.c_int, [C.c_int, C.c_int]),
+            "cask_timing_read": (C.c_int, [vp, vp]),
+        }
+        assert set(sigs) == set(EXPORTS)
+        for name, (res, args) in sigs.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
         _lib = lib
     return _lib
 

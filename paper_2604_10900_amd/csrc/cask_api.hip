@@ -4,8 +4,8 @@
 //   -> similarity -> gather merged donors -> emit (copy kept rows, fold representatives).
 // Nothing here allocates or synchronises; everything is enqueued on the caller's stream.
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "cask_common.h"
@@ -37,10 +37,7 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
       n_splits = sp;
     }
   }
-  if (const char* e = std::getenv("CASK_SPLITS")) {
-    const int v = std::atoi(e);
-    if (v >= 1 && v <= 64) n_splits = v;
-  }
+  if (kp.score_splits >= 1) n_splits = kp.score_splits;
   int split_len = (int)align_up((size_t)(max_unit_len + n_splits - 1) / n_splits, 64);
   if (split_len < 64) split_len = 64;
   n_splits = (max_unit_len + split_len - 1) / split_len;
@@ -54,10 +51,7 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
   {
     const int64_t wgsB = (int64_t)((n_units + 7) / 8 * 8) * ((max_unit_len + 255) / 256);
     if (wgsB <= 384 && kp.Mq >= 512) w.q_splits = 2;  // measured: helps up to about 1.5 rounds of the 512 slots
-    if (const char* e = std::getenv("CASK_QSPLIT")) {
-      const int v = std::atoi(e);
-      if (v == 1 || v == 2) w.q_splits = v;
-    }
+    if (kp.score_qsplit >= 1) w.q_splits = kp.score_qsplit;
   }
   w.split_len = split_len;
   w.mq_pad = (int)align_up((size_t)kp.Mq, 64);
@@ -106,6 +100,7 @@ static int resolve_params(const cask_params* p, KParams* kp, bool need_budget) {
   if (p->merge_radius < 0 || p->merge_geometry < 0 || p->merge_geometry > 1) return CASK_EINVAL;
   if (p->merge_geometry == 1 && (!p->band_weight || !(p->dist_threshold >= 0.f))) return CASK_EINVAL;
   if (p->seed_dedup < 0 || (p->seed_dedup > 0 && p->merge_geometry != 0)) return CASK_EINVAL;
+  if (p->score_splits < 0 || p->score_splits > 64 || p->score_qsplit < 0 || p->score_qsplit > 2) return CASK_EINVAL;
   kp->dtype = p->dtype;
   kp->d = p->head_dim;
   kp->G = p->q_per_kv;
@@ -120,6 +115,9 @@ static int resolve_params(const cask_params* p, KParams* kp, bool need_budget) {
   kp->theta = p->dist_threshold;
   kp->band_w = p->band_weight;
   kp->dedup = p->seed_dedup;
+  kp->path_flags = p->path_flags;
+  kp->score_splits = p->score_splits;
+  kp->score_qsplit = p->score_qsplit;
   const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
   kp->scale_log2 = (float)(scale * 1.4426950408889634);
   kp->causal = p->causal ? 1 : 0;
@@ -173,22 +171,26 @@ struct StageTiming {
   std::vector<hipEvent_t> ev;  // (CASK_N_STAGES + 1) per call
 };
 static StageTiming g_timing;
+static std::mutex g_timing_mu;  // guards g_timing's bookkeeping (the events themselves belong to one stream)
 
 struct StageRecorder {
   hipEvent_t* ev = nullptr;
   hipStream_t st;
   int next = 0;
+  int stages = 0;
   explicit StageRecorder(hipStream_t s) : st(s) {
+    std::lock_guard<std::mutex> lock(g_timing_mu);
     if (g_timing.on && g_timing.n_calls < g_timing.max_calls) {
       ev = g_timing.ev.data() + (size_t)g_timing.n_calls * (CASK_N_STAGES + 1);
+      stages = g_timing.stages;
       ++g_timing.n_calls;
     }
   }
-  hipEvent_t peek() const { return (ev && next <= g_timing.stages) ? ev[next] : nullptr; }  // handed to a launcher to record
+  hipEvent_t peek() const { return (ev && next <= stages) ? ev[next] : nullptr; }  // handed to a launcher to record
   void skip() { if (ev) ++next; }
   void mark() {
     if (!ev) return;
-    if (next <= g_timing.stages) (void)hipEventRecord(ev[next], st);
+    if (next <= stages) (void)hipEventRecord(ev[next], st);
     ++next;
   }
 };
@@ -326,19 +328,6 @@ int cask_mass_diagnostics(const cask_params* params, const cask_batch* batch, co
                                  static_cast<hipStream_t>(hip_stream)));
 }
 
-// CASK_FUSED_TAIL=0 sends short units through the general kernels as well (read at every call:
-// tests and measurements compare the two paths inside one process)
-static bool fused_tail_disabled() {
-  const char* e = std::getenv("CASK_FUSED_TAIL");
-  return e && e[0] == '0';
-}
-
-// CASK_FUSED_SCORE=0: two scoring launches for short units as well (read at every call)
-static bool fused_score_disabled() {
-  const char* e = std::getenv("CASK_FUSED_SCORE");
-  return e && e[0] == '0';
-}
-
 int cask_group_diagnostics(const cask_params* params, const cask_batch* batch, const float* scores,
                            const int32_t* assign, const void* K_out, int32_t out_stride_rows,
                            float* dispersion, float* lost_mass, void* hip_stream) {
@@ -418,10 +407,11 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
   hipError_t e;
   StageRecorder rec(st);
   rec.mark();  // start
-  const bool fused_tail = tail_small_fits(kp, b) && kp.dedup == 0 && !fused_tail_disabled();
+  const bool fused_tail = tail_small_fits(kp, b) && kp.dedup == 0 && !(kp.path_flags & CASK_PATH_NO_FUSED_TAIL);
   // short units: both sweeps are one launch as well, handing partial sums to the tail kernel
   // (reported as the first scoring stage; the second reads as an empty bracket)
-  const bool fused_score = fused_tail && !given && score_parts_fits(kp, b, wl) && !fused_score_disabled();
+  const bool fused_score = fused_tail && !given && score_parts_fits(kp, b, wl) &&
+                           !(kp.path_flags & CASK_PATH_NO_FUSED_SCORE);
   if (fused_score) {
     e = launch_score_parts(kp, b, wl, w, st);
     if (e != hipSuccess) return CASK_EDEVICE;
@@ -475,6 +465,7 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
 int cask_timing_enable(int max_calls) { return cask_timing_enable_stages(max_calls, CASK_N_STAGES); }
 
 int cask_timing_enable_stages(int max_calls, int n_stages) {
+  std::lock_guard<std::mutex> lock(g_timing_mu);
   for (hipEvent_t e : g_timing.ev) (void)hipEventDestroy(e);
   g_timing.ev.clear();
   g_timing.on = false;
@@ -493,6 +484,7 @@ int cask_timing_enable_stages(int max_calls, int n_stages) {
 
 int cask_timing_read(float* stage_ms, int* n_calls) {
   if (!stage_ms || !n_calls) return CASK_EINVAL;
+  std::lock_guard<std::mutex> lock(g_timing_mu);
   for (int i = 0; i < CASK_N_STAGES; ++i) stage_ms[i] = 0.f;
   *n_calls = g_timing.n_calls;
   for (int c = 0; c < g_timing.n_calls; ++c) {

@@ -375,12 +375,10 @@ hipError_t launch_attend_mfma_w(const KParams& kp, int n_units, const void* Q, c
                                 const void* Vc, int stride, const int32_t* len, const int32_t* count,
                                 int count_pitch, void* out, hipStream_t st) {
   constexpr int lds = att_lds_bytes<D, HP, WAVES>();
-  static bool raised = false;  // (benign if two threads both set it)
-  if (lds > 48 * 1024 && !raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_mfma_kernel<D, HP, WAVES>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  static LdsLimitOnce lim;  // one per instantiation
+  if (lds > 48 * 1024) {
+    const hipError_t e = lim.ensure(reinterpret_cast<const void*>(&attend_mfma_kernel<D, HP, WAVES>), (int)lds);
     if (e != hipSuccess) return e;
-    raised = true;
   }
   attend_mfma_kernel<D, HP, WAVES><<<dim3(n_units), dim3(WAVES * 64), lds, st>>>(
       kp, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(Kc),
@@ -401,12 +399,6 @@ hipError_t launch_attend_mfma(const KParams& kp, int n_units, const void* Q, con
 
 }  // namespace
 
-// CASK_ATTEND_VECTOR=1 sends bf16 through the vector-ALU kernel too (for comparisons).
-static bool attend_vector_forced() {
-  const char* e = getenv("CASK_ATTEND_VECTOR");
-  return e && e[0] == '1';
-}
-
 hipError_t launch_attend(const KParams& kp, int n_units, const void* Q, const void* Kc, const void* Vc,
                          int stride, const int32_t* len, const int32_t* count, int count_pitch,
                          void* out, hipStream_t st) {
@@ -420,7 +412,7 @@ hipError_t launch_attend(const KParams& kp, int n_units, const void* Q, const vo
   e = launch_attend_mfma<D, HP>(kp, n_units, Q, Kc, Vc, stride, len, count, count_pitch, out, st)
   if (kp.dtype == CASK_F32) {
     if (kp.d == 64) CASK_ATT(float, 64); else CASK_ATT(float, 128);
-  } else if (attend_vector_forced()) {
+  } else if (kp.path_flags & CASK_PATH_ATTEND_VECTOR) {  // the vector-ALU kernel, for comparisons
     if (kp.d == 64) CASK_ATT(uint16_t, 64); else CASK_ATT(uint16_t, 128);
   } else {
     const int hp = kp.G >= 5 ? 8 : kp.G >= 3 ? 4 : kp.G;  // query heads per pass over the cache

@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "cask.h"
 
 namespace cask {
@@ -31,6 +33,9 @@ struct KParams {
   float theta;       // distance threshold of geometry 1
   const float* band_w;  // device [d / 2] band weights of geometry 1
   int dedup;         // h > 0: de-duplicated seeding over the best h * M scratch rows
+  unsigned path_flags;  // CASK_PATH_* bits (host-side path selection only)
+  int score_splits;  // forced key splits of sweep A, 0 = cost model
+  int score_qsplit;  // forced window-row halves of sweep B, 0 = chosen
 };
 
 constexpr int kSeedWalkMax = 2048;  // rows the de-duplicating walk of a unit can cover
@@ -149,6 +154,28 @@ __device__ inline float wave_sum(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
 }
+
+// Raises a kernel's dynamic-LDS limit the first time the kernel is launched on a device (a
+// function attribute, not a stream operation).  One instance per kernel; safe to call from
+// several threads.
+class LdsLimitOnce {
+ public:
+  hipError_t ensure(const void* kernel, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu_);
+    if (done_ & (1ull << dev)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done_ |= 1ull << dev;
+    return e;
+  }
+
+ private:
+  std::mutex mu_;
+  uint64_t done_ = 0;
+};
 
 // ---------------------------------------------------------------- workspace layout
 

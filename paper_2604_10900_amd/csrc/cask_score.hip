@@ -806,18 +806,12 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   const int units8 = (b.n_units + 7) / 8 * 8;
   const uint16_t* K = static_cast<const uint16_t*>(b.K);
   const uint16_t* Q = static_cast<const uint16_t*>(b.Q);
-  static bool attr_set = false;
   const size_t ldsA = (size_t)kDepth * kStageBytes;
   const size_t ldsB = ldsA;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<0>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<1>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsLimitOnce limA, limB;
+  hipError_t e = limA.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<0>), 160 * 1024);
+  if (e == hipSuccess) e = limB.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<1>), 160 * 1024);
+  if (e != hipSuccess) return e;
   const int qblocks = (kp.Mq + kResRows - 1) / kResRows;
   const int tilesA = qblocks * wl.n_splits;
   score_mfma_kernel<0><<<dim3(units8 * tilesA), dim3(kThreads), ldsA, st>>>(
@@ -843,14 +837,10 @@ bool score_parts_fits(const KParams& kp, const Batch& b, const Workspace& wl) {
 hipError_t launch_score_parts(const KParams& kp, const Batch& b, const Workspace& wl, char* ws,
                               hipStream_t st) {
   if (!score_parts_fits(kp, b, wl)) return hipErrorInvalidValue;
-  static bool attr_set = false;
   const size_t lds = (size_t)kDepth * kStageBytes + kResRows * sizeof(float);
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<2>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsLimitOnce lim;
+  const hipError_t e = lim.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<2>), 160 * 1024);
+  if (e != hipSuccess) return e;
   const int units8 = (b.n_units + 7) / 8 * 8;
   const int qblocks = (kp.Mq + kResRows - 1) / kResRows;
   score_mfma_kernel<2><<<dim3(units8 * qblocks), dim3(kThreads), lds, st>>>(

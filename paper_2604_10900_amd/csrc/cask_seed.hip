@@ -390,12 +390,6 @@ __global__ __launch_bounds__(kDdThreads) void dedup_seed_mfma_kernel(
 
 }  // namespace
 
-// CASK_DEDUP_VECTOR=1 sends bf16 caches through the vector-ALU kernel too (for comparisons).
-static bool dedup_vector_forced() {
-  const char* e = getenv("CASK_DEDUP_VECTOR");
-  return e && e[0] == '1';
-}
-
 hipError_t launch_dedup_seeds(const KParams& kp, const Batch& b, const float* scores, uint8_t* role,
                               hipStream_t st) {
   if (b.n_units == 0 || kp.dedup <= 0) return hipSuccess;
@@ -404,7 +398,7 @@ hipError_t launch_dedup_seeds(const KParams& kp, const Batch& b, const float* sc
       kp, b.row_off, b.prefix_len, static_cast<const T*>(b.K), scores, role)
   if (kp.dtype == CASK_F32) {
     if (kp.d == 64) CASK_DD(float, 64); else CASK_DD(float, 128);
-  } else if (dedup_vector_forced()) {
+  } else if (kp.path_flags & CASK_PATH_DEDUP_VECTOR) {  // the vector-ALU kernel, for comparisons
     if (kp.d == 64) CASK_DD(uint16_t, 64); else CASK_DD(uint16_t, 128);
   } else if (kp.d == 64) {
     dedup_seed_mfma_kernel<64><<<dim3(b.n_units), dim3(kDdThreads), 0, st>>>(

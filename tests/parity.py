@@ -81,6 +81,85 @@ def check_assign_excused(got: np.ndarray, want: np.ndarray, best: np.ndarray, se
     return len(bad)
 
 
+TIE_REL = 1e-4
+
+
+def check_keepset_near_ties(rp, P: int, s: np.ndarray, got_src: np.ndarray, want_src: np.ndarray,
+                            label: str = "") -> int:
+    """End-to-end keep-sets (own scores on the GPU side) may differ from the oracle's only at a
+    rank boundary whose tie the oracle itself nearly has.  `s`: the oracle's fp32 scores of the
+    unit; got_src / want_src: the kept source rows.  Inside each range that is cut by rank (the
+    prefix at rank P_keep, the decode trace outside the recent tail at rank C + M) the rows only
+    one side keeps must pair up, a row only the oracle keeps must score within 1e-4 (relative)
+    of the oracle's best dropped row of that range, and a row only the library keeps within 1e-4
+    of the oracle's worst kept row.  With de-duplicated seeding the seeds are not a rank cut: a
+    differing row must then be near-tied with its neighbour in the oracle's order.  Returns the
+    number of rows that differ."""
+    N = len(s)
+    pl = ref.plan(rp, P, N)
+    only_want = np.setdiff1d(want_src, got_src)
+    only_got = np.setdiff1d(got_src, want_src)
+    if len(only_want) + len(only_got) == 0:
+        return 0
+    s64 = s.astype(np.float64)
+    ranges = [(0, P, pl["p_keep"]), (P, N - pl["r_eff"], pl["core"] + pl["seeds"])]
+    covered = 0
+    for lo, hi, k in ranges:
+        w_ = only_want[(only_want >= lo) & (only_want < hi)]
+        g_ = only_got[(only_got >= lo) & (only_got < hi)]
+        covered += len(w_) + len(g_)
+        if len(w_) + len(g_) == 0:
+            continue
+        idx = np.arange(lo, hi)
+        order = idx[np.lexsort((idx, -s64[lo:hi]))]         # score descending, index ascending
+        if rp.seed_dedup > 0 and lo == P:
+            rank = np.empty(hi - lo, dtype=np.int64)
+            rank[order - lo] = np.arange(hi - lo)
+            for j in np.concatenate([w_, g_]):
+                r = rank[j - lo]
+                near = [order[q] for q in (r - 1, r + 1) if 0 <= q < hi - lo]
+                gap = min(abs(s64[j] - s64[q]) for q in near)
+                assert gap <= TIE_REL * max(s64[j], 1e-300), \
+                    f"{label}: keep-set differs at row {j} without a near-tie in the walk order"
+            continue
+        assert len(w_) == len(g_), f"{label}: rows {w_} / {g_} do not pair up inside [{lo}, {hi})"
+        assert 0 < k < hi - lo, f"{label}: rows differ in a range that is not cut by rank"
+        worst_kept, best_dropped = s64[order[k - 1]], s64[order[k]]
+        for j in w_:
+            assert s64[j] - best_dropped <= TIE_REL * max(s64[j], 1e-300), \
+                f"{label}: the library dropped row {j} (score {s64[j]:.9e}) though the cut at rank {k} " \
+                f"is at {best_dropped:.9e}"
+        for j in g_:
+            assert worst_kept - s64[j] <= TIE_REL * max(worst_kept, 1e-300), \
+                f"{label}: the library kept row {j} (score {s64[j]:.9e}) though the cut at rank {k} " \
+                f"is at {worst_kept:.9e}"
+    assert covered == len(only_want) + len(only_got), f"{label}: always-kept rows differ"
+    return len(only_want) + len(only_got)
+
+
+def check_assign_near_ties(rp, row_off, prefix_len, K, want: dict, got_assign: np.ndarray, label="") -> int:
+    """End-to-end merge assignment of a one-unit batch (own scores on the GPU side, identical
+    keep-set) against the oracle's: a differing donor must be a near-tie of cosines in the oracle
+    (best against runner-up, or best against the threshold).  The core / seed cut at rank C does
+    not show in the keep-set; when the oracle's scores nearly tie there the seed sets may differ,
+    and the comparison is skipped (returns -1).  Returns the number of excused donors."""
+    if np.array_equal(got_assign, want["assign"]):
+        return 0
+    assert len(row_off) == 2
+    P, N = int(prefix_len[0]), int(row_off[1])
+    pl = ref.plan(rp, P, N)
+    lo, hi, C_ = P, N - pl["r_eff"], pl["core"]
+    if 0 < C_ < hi - lo:
+        s64 = want["scores"].astype(np.float64)
+        idx = np.arange(lo, hi)
+        order = idx[np.lexsort((idx, -s64[lo:hi]))]
+        if s64[order[C_ - 1]] - s64[order[C_]] <= TIE_REL * max(s64[order[C_ - 1]], 1e-300):
+            return -1
+    _, best, second = ref.consolidate(rp, row_off, prefix_len, K, want["scores"], want["role"], want_sims=True)
+    bar = -float(np.float32(rp.dist_threshold)) if rp.merge_geometry == 1 else float(np.float32(rp.sim_threshold))
+    return check_assign_excused(got_assign, want["assign"], best, second, bar, label)
+
+
 def check_values(p: cask.Params, got: dict, want: dict, K: np.ndarray, V: np.ndarray,
                  row_off: np.ndarray, units=None, own_scores: bool = False):
     """Output rows: bit-exact copies for single-member rows, tolerance for folds.  Rows are
@@ -240,18 +319,12 @@ def full_check(c: dict, p: cask.Params, expect_folds: bool = False, n_threads: i
     diff_units = 0
     for u in range(n_units):
         L = int(want["out_len"][u])
-        a, w_ = got_e["out_src"][u, :L], want["out_src"][u, :L]
-        if np.array_equal(a, w_):
-            continue
-        diff_units += 1
-        # every token in the symmetric difference must sit at a near-tied rank boundary
-        s = want["scores"][row_off[u]:row_off[u + 1]].astype(np.float64)
-        extra = np.setxor1d(a, w_)
-        for j in extra:
-            # some token on the other side of the boundary has an almost equal score
-            others = np.setdiff1d(np.arange(len(s)), [j])
-            gap = np.min(np.abs(s[others] - s[j]))
-            assert gap <= 1e-4 * max(s[j], 1e-30), f"unit {u}: keep-set differs at row {j} without a near-tie"
+        flips = check_keepset_near_ties(rp, int(prefix_len[u]), want["scores"][row_off[u]:row_off[u + 1]],
+                                        got_e["out_src"][u, :L], want["out_src"][u, :L], f"unit {u}")
+        diff_units += flips > 0
     stats["e2e_units_with_tie_flips"] = diff_units
+    # a near-tie exactly at a rank cut is rare (a cut falls on a relative gap below 1e-4 in a
+    # few units of a hundred, and the score error is a hundredth of that gap)
+    assert diff_units <= max(1, n_units // 20), f"{diff_units} of {n_units} units differ at near-ties"
     check_values(p, got_e, want, K2, V2, row_off, own_scores=True)
     return stats

@@ -233,14 +233,15 @@ def test_plan_golden_table(oracle):
             if not line or line.startswith("#"):
                 continue
             lhs, rhs = line.split("|")
-            P, D, B, R, core = (int(x) for x in lhs.split())
+            P, D, B, R, core, *pb = (int(x) for x in lhs.split())
             r_eff, p_keep, slots, c, m, status = (int(x) for x in rhs.split())
-            p = f32_params(oracle, window=min(128, P + D), recent=R, budget=B, core=core)
+            p = f32_params(oracle, window=min(128, P + D), recent=R, budget=B, core=core,
+                           prefix_budget=pb[0] if pb else -1)
             got = oracle.plan(p, P, P + D)
             assert got == dict(r_eff=r_eff, p_keep=p_keep, slots=slots, core=c, seeds=m,
                                status=status), (line, got)
             rows += 1
-    assert rows >= 10
+    assert rows >= 18
 
 
 def test_plan_fills_budget_exactly(oracle):
@@ -266,6 +267,53 @@ def test_plan_fills_budget_exactly(oracle):
         assert pl["core"] >= 0 and pl["seeds"] >= 0 and pl["core"] + pl["seeds"] <= max(pl["slots"], 0)
         if pl["status"] & oracle.ST_PREFIX_BUDGET_EXHAUSTED:
             assert pl["slots"] == 0 and dnr > 0 and pl["p_keep"] == B - pl["r_eff"]
+
+
+def test_plan_properties_of_the_split_rule(oracle):
+    """What the budget-split rule fixes, stated as properties and checked over random sizes with
+    the prefix budget, core size and recent tail drawn as well (two-stage compression, Section
+    2.2; |R| <= B, Section 2.3; the exhausted regime, Section 5.2):
+      - a closed form of the kept prefix written here from the rule's text:
+        min(P, B - r, max(B_p, B - r - Dnr));
+      - r_eff + p_keep + slots == B whenever N > B;
+      - exhausted  <=>  N > B, no slot, and decode tokens outside the recent tail waiting;
+      - a larger budget never keeps fewer prefix tokens or offers fewer slots;
+      - a longer decode trace never keeps more prefix tokens."""
+    rng = np.random.default_rng(77)
+    for _ in range(3000):
+        R = int(rng.integers(0, 150))
+        B = int(rng.integers(R + 1, 1200))
+        P = int(rng.integers(0, 70000)) if rng.integers(0, 2) else int(rng.integers(0, 600))
+        D = int(rng.integers(0, 5000))
+        if P + D == 0:
+            continue
+        kw = dict(window=1, recent=R, core=int(rng.integers(-1, 300)), prefix_budget=int(rng.integers(-1, 900)))
+        pl = oracle.plan(f32_params(oracle, budget=B, **kw), P, P + D)
+        r = min(R, D)
+        dnr = D - r
+        assert pl["r_eff"] == r
+        if P + D <= B:
+            assert pl["status"] == oracle.ST_IDENTITY and pl["p_keep"] == P and pl["core"] == dnr
+            continue
+        bp = kw["prefix_budget"] if kw["prefix_budget"] >= 0 else max(B // 4, -(-P // 64))
+        assert pl["p_keep"] == min(P, B - r, max(bp, B - r - dnr)), (kw, P, D, B, pl)
+        assert pl["r_eff"] + pl["p_keep"] + pl["slots"] == B
+        exhausted = pl["slots"] == 0 and dnr > 0
+        assert bool(pl["status"] & oracle.ST_PREFIX_BUDGET_EXHAUSTED) == exhausted
+        if exhausted:
+            assert pl["core"] == 0 and pl["seeds"] == 0
+        elif dnr <= pl["slots"]:
+            assert pl["status"] == oracle.ST_MERGE_INACTIVE and pl["core"] == dnr and pl["seeds"] == 0
+        else:
+            want_core = min(kw["core"], pl["slots"]) if kw["core"] >= 0 else (4 * pl["slots"]) // 5
+            assert (pl["core"], pl["seeds"]) == (want_core, pl["slots"] - want_core)
+            assert pl["status"] == (oracle.ST_ACTIVE if pl["seeds"] > 0 else oracle.ST_MERGE_INACTIVE)
+        # monotone in the budget (explicit prefix budget: the default one grows with B as well)
+        big = oracle.plan(f32_params(oracle, budget=B + int(rng.integers(1, 200)), **kw), P, P + D)
+        if not big["status"] & oracle.ST_IDENTITY:
+            assert big["p_keep"] >= pl["p_keep"] and big["slots"] >= pl["slots"]
+        longer = oracle.plan(f32_params(oracle, budget=B, **kw), P, P + D + int(rng.integers(1, 500)))
+        assert longer["p_keep"] <= pl["p_keep"] or R > D   # (a tail still growing into R shrinks the room)
 
 
 # ------------------------------------------------------------------ R6 consolidate
@@ -926,6 +974,27 @@ def test_group_diagnostics_on_events_against_library_norms(oracle):
     out = oracle.compress(p, ro, pl, K, V, Q)
     disp, lost = oracle.group_diagnostics(p, ro, K, out["scores"], out["assign"], out["K_out"])
     assert disp[0] == 0.0 and lost[0] == 0.0
+
+
+def test_nonpositive_softmax_scale_is_the_default_scale(oracle):
+    """One rule for the scale parameter everywhere: a value <= 0 stands for 1/sqrt(d), in the
+    scorer and in the consumer-side attention alike."""
+    rng = np.random.default_rng(5)
+    d, W, G, N = 16, 4, 2, 50
+    K, V, Q, ro = rand_unit(rng, N, d, W, G)
+    explicit = float(np.float32(1.0 / np.sqrt(d)))   # exactly representable: d is a power of four
+    base = dict(head_dim=d, window=W, q_per_kv=G, budget=30)
+    s_def = oracle.score(f32_params(oracle, softmax_scale=0.0, **base), ro, K, Q)
+    for sc in (-1.0, -0.0, explicit):
+        np.testing.assert_array_equal(oracle.score(f32_params(oracle, softmax_scale=sc, **base), ro, K, Q), s_def)
+    assert not np.array_equal(oracle.score(f32_params(oracle, softmax_scale=0.5, **base), ro, K, Q), s_def)
+    q1 = rng.standard_normal((1, G, d)).astype(np.float32)
+    Kc, Vc = K[None, :40], V[None, :40]
+    lens = np.array([40], dtype=np.int32)
+    pa = dict(head_dim=d, window=1, q_per_kv=G, budget=40)
+    o_def = oracle.attend(f32_params(oracle, softmax_scale=0.0, **pa), q1, Kc, Vc, lens)
+    for sc in (-1.0, explicit):
+        np.testing.assert_array_equal(oracle.attend(f32_params(oracle, softmax_scale=sc, **pa), q1, Kc, Vc, lens), o_def)
 
 
 # ------------------------------------------------------------------ consumer side: proportional attention
