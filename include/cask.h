@@ -199,6 +199,24 @@ int cask_compress(const cask_params* params, const cask_batch* batch, void* K_ou
                   int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
                   float* scores, int32_t* status, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* cask_compress for callers that cannot allocate device memory: a stream under HIP graph
+ * capture, a tight serving loop, a harness that forbids allocation.  Same arguments and results
+ * as cask_compress without `ws`: the workspace is a fixed array of CASK_STATIC_WORKSPACE_BYTES
+ * in device memory that the library owns (each device the library is used on holds its copy
+ * until the process ends).  Calls no allocating routine.
+ *   - CASK_ENOMEM when cask_workspace_bytes() for the batch exceeds CASK_STATIC_WORKSPACE_BYTES
+ *     (48 MiB: about 1.3 million cached rows, e.g. 112 units of 8448 rows with 896 window rows);
+ *     nothing is enqueued then.
+ *   - Every call on a device shares that device's array: calls that overlap on one device (two
+ *     streams, two threads) race.  Calls in sequence on one stream are fine; nothing has to be
+ *     cleared between them.
+ *   - The first call on a device looks up the array's address (no stream operation): make one
+ *     call before capturing the stream into a HIP graph. */
+#define CASK_STATIC_WORKSPACE_BYTES (48u << 20)
+int cask_compress_static(const cask_params* params, const cask_batch* batch, void* K_out, void* V_out,
+                         int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
+                         float* scores, int32_t* status, void* hip_stream);
+
 /* One event of a decode loop: cask_compress with per-row token counts carried in and out and
  * an output row stride.  The paper's runs compress a trace several times (its result tables
  * count the events) without stating a trigger or carry rule; the readings taken:

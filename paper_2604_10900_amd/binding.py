@@ -26,7 +26,7 @@ PATH_NO_FUSED_TAIL, PATH_NO_FUSED_SCORE, PATH_DEDUP_VECTOR, PATH_ATTEND_VECTOR, 
  ROLE_DECODE_EVICT) = range(7)
 
 EXPORTS = ["cask_plan", "cask_workspace_bytes", "cask_score", "cask_prefix_evict",
-           "cask_partition", "cask_consolidate", "cask_compress", "cask_compress_step",
+           "cask_partition", "cask_consolidate", "cask_compress", "cask_compress_static", "cask_compress_step",
            "cask_mass_diagnostics", "cask_group_diagnostics", "cask_attend", "cask_strerror",
            "cask_timing_enable", "cask_timing_enable_stages", "cask_timing_read"]
 STAGES = ["score_rows", "score_cols", "select", "index_roles", "similarity", "gather", "emit"]
@@ -146,6 +146,7 @@ def load():
             "cask_partition": (C.c_int, [vp, vp, vp, vp, vp, vp, sz, vp]),
             "cask_consolidate": (C.c_int, [vp, vp, vp, vp, vp, vp, sz, vp]),
             "cask_compress": (C.c_int, [vp] * 11 + [sz, vp]),
+            "cask_compress_static": (C.c_int, [vp] * 11),
             "cask_compress_step": (C.c_int, [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
             "cask_mass_diagnostics": (C.c_int, [vp] * 8),
             "cask_group_diagnostics": (C.c_int, [vp, vp, vp, vp, vp, i32, vp, vp, vp]),
@@ -395,4 +396,22 @@ def compress(b: Batch, out: Optional[Outputs] = None, scores: Optional[torch.Ten
                               ws.numel(), _stream())
     if rc:
         raise CaskError("cask_compress", rc)
+    return out
+
+
+STATIC_WORKSPACE_BYTES = 48 << 20
+
+
+def compress_static(b: Batch, out: Outputs, scores: Optional[torch.Tensor] = None) -> Outputs:
+    """cask_compress_static: the event with the library's own fixed workspace (no workspace
+    argument, nothing allocated by the call; `out` is allocated by the caller beforehand)."""
+    given = scores is not None
+    if given:
+        out.scores = scores
+    cp, cb = b.params.c(1 if given else 0), b.c()
+    rc = load().cask_compress_static(C.byref(cp), C.byref(cb), _dptr(out.K_out), _dptr(out.V_out),
+                                     _dptr(out.out_len), _dptr(out.out_src), _dptr(out.out_mass),
+                                     _dptr(out.assign), _dptr(out.scores), _dptr(out.status), _stream())
+    if rc:
+        raise CaskError("cask_compress_static", rc)
     return out

@@ -462,6 +462,59 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
   return dev_rc(e);
 }
 
+// ---------------------------------------------------------------- allocation-free variant
+//
+// cask_compress for callers that cannot allocate device memory (a stream under graph capture, a
+// tight serving loop, a harness that forbids allocation): the workspace is a fixed array in
+// device memory that belongs to the library.  Every device the library runs on holds its own
+// copy of the array, at its own address, until the process ends.  In host code the array's
+// name only stands for the symbol: its device address is looked up once per device and every
+// use below goes through that address.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[CASK_STATIC_WORKSPACE_BYTES];
+
+namespace {
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[64] = {};  // per device: address of that device's copy of `scratch`
+
+// Address of the current device's copy; looked up on the first call on that device.
+int static_workspace(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CASK_EDEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return CASK_EDEVICE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CASK_OK;
+}
+}  // namespace
+
+int cask_compress_static(const cask_params* params, const cask_batch* batch, void* K_out, void* V_out,
+                         int32_t* out_len, int32_t* out_src, float* out_mass, int32_t* assign,
+                         float* scores, int32_t* status, void* hip_stream) {
+  // sizes first, on the host mirrors: a batch whose workspace would not fit is refused before
+  // anything touches the device
+  KParams kp;
+  Batch b;
+  int rc = resolve_params(params, &kp, true);
+  if (rc) return rc;
+  rc = resolve_batch(kp, batch, &b, params->scores_given == 0, true);
+  if (rc) return rc;
+  if (b.n_units == 0) return CASK_OK;
+  if (layout_workspace(kp, b.n_units, b.total_rows, b.max_unit_len).total > (size_t)CASK_STATIC_WORKSPACE_BYTES)
+    return CASK_ENOMEM;
+  void* ws = nullptr;
+  rc = static_workspace(&ws);
+  if (rc) return rc;
+  // Nothing in the workspace has to start at zero: every kernel of the event writes what it or a
+  // later kernel reads (the same holds for a caller's uninitialised workspace), so the contents
+  // the previous call left behind are harmless.
+  return cask_compress(params, batch, K_out, V_out, out_len, out_src, out_mass, assign, scores, status,
+                       ws, (size_t)CASK_STATIC_WORKSPACE_BYTES, hip_stream);
+}
+
 int cask_timing_enable(int max_calls) { return cask_timing_enable_stages(max_calls, CASK_N_STAGES); }
 
 int cask_timing_enable_stages(int max_calls, int n_stages) {
