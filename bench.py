@@ -27,12 +27,12 @@ METRIC = "KV tokens compressed/s per layer x head at budget 384; % HBM/MFMA roof
 PEAK_MFMA_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the two scoring sweeps from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this file, each counter scaled by what it reads for a conversion kernel of known
-# traffic (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0; profiles/cfg2_hbm_traffic.md).  None where
-# not measured.
-MEASURED_TRAFFIC = {
-    "cfg2": {"score_rows": (131012.6 * 2.0 + 3136.0) * 1024, "score_cols": (131116.7 * 2.0 + 3696.0) * 1024},
+# HBM bytes per launch of the dominant kernel (the first scoring sweep) as read by
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in separate runs of this file, each counter scaled by
+# what it reads for the copy probe of known size in the same run.  These are constants taken
+# from the named summaries under profiles/, not measured by the run that prints them; a workload
+# without a summary, or a cut-down run (--layers / --seqs), reports null.
+PROFILED_TRAFFIC = {
 }
 
 
@@ -52,9 +52,14 @@ def parse():
                     help="input copies alternated between steps (0 = 2 when they fit in 2 GB)")
     ap.add_argument("--cpu-units", type=int, default=48, help="units the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--pmc-copy-mib", type=int, default=0,
-                    help="also run one fp32 -> bf16 conversion of a buffer of this many MiB (a kernel of "
-                         "known traffic, N MiB read and N/2 MiB written, for scaling rocprofv3 "
-                         "FETCH_SIZE / WRITE_SIZE readings)")
+                    help="also run the copy probe once on a buffer of this many MiB (a kernel of known "
+                         "traffic, N MiB read and N MiB written, for scaling rocprofv3 FETCH_SIZE / "
+                         "WRITE_SIZE readings)")
+    ap.add_argument("--sim-threshold", type=float, default=0.9,
+                    help="cask_params.sim_threshold; the headline is quoted at the default 0.9, -1 makes "
+                         "every donor fold (the merge-heavy variant that loads the fold path)")
+    ap.add_argument("--no-pinned-peaks", action="store_true",
+                    help="skip the two probe loops (MFMA chain, streaming copy) that pin this box's ceilings")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="record no HIP events inside the timed region (no roofline object then)")
     ap.add_argument("--graph-steps", type=int, default=50,
@@ -106,7 +111,7 @@ def main():
     n_layers = args.layers if args.layers > 0 else w.n_layers
     p = cask.Params(dtype=cask.F32 if w.dtype == "f32" else cask.BF16, head_dim=w.head_dim,
                     q_per_kv=w.q_per_kv, window=w.window, recent=w.recent, budget=w.budget,
-                    core=w.core, seed_dedup=args.seed_dedup)
+                    core=w.core, seed_dedup=args.seed_dedup, sim_threshold=args.sim_threshold)
 
     # ---- inputs, resident in HBM; alternate copies so the 256 MB last-level cache cannot
     # stand in for HBM between steps
@@ -141,11 +146,28 @@ def main():
             cask.compress(batches[i % copies][1], outs)
 
     if args.pmc_copy_mib > 0:
-        src = torch.rand((args.pmc_copy_mib << 20) // 4, dtype=torch.float32, device=dev)
+        src = torch.empty(args.pmc_copy_mib << 20, dtype=torch.uint8, device=dev).random_(0, 256)
+        dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        dst = src.to(torch.bfloat16)
+        rc = cask.load().cask_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel(),
+                                         torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
         torch.cuda.synchronize()
         del src, dst
+    # ---- this box's ceilings, pinned by two plain loops of the library (a chain of bf16 MFMA on
+    # random register operands, two waves per SIMD on every compute unit; a 1 GiB streaming copy)
+    pinned = None
+    if not args.no_pinned_peaks:
+        pm = binding.probe_issue(0, waves_per_simd=2, blocks=256, iters=20000)
+        pv = binding.probe_issue(1, waves_per_simd=2, blocks=256, iters=20000)
+        pc = binding.probe_copy(1 << 30)
+        pinned = {"mfma_bf16_TFLOP/s": round(pm["tflops"], 1), "mfma_loop_clock_GHz": round(pm["ghz"], 3),
+                  "mfma_loop_cycles_per_mfma": round(pm["cycles_per_unit"], 2),
+                  "mfma_with_softmax_epilogue_TFLOP/s": round(pv["tflops"], 1),
+                  "mfma_with_softmax_epilogue_clock_GHz": round(pv["ghz"], 3),
+                  "mfma_with_softmax_epilogue_cycles_per_mfma": round(pv["cycles_per_unit"], 2),
+                  "copy_GB/s": round(pc["gbs"], 1),
+                  "note": "cask_probe_issue kinds 0 and 1 (256 workgroups x 8 waves: two waves per SIMD on every compute unit), cask_probe_copy (1 GiB, read + write)"}
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -253,6 +275,18 @@ def main():
                     "frac_of_hbm_peak": round(att_bytes / att_us * 1e-3 / PEAK_HBM_GBS, 4)}
     lens = (b0.row_off_host[1:] - b0.row_off_host[:-1]).numpy()
     saved = 1.0 - float(out_len.sum()) / float(lens.sum())
+    # how much the fold path had to do: donors folded into representatives by the last event
+    n_assigned = int((outs.assign >= 0).sum().item())
+    folded_donors = n_assigned - int(out_len.sum())
+    fold_path = {"folded_donors_per_event": folded_donors, "sim_threshold": args.sim_threshold}
+    if stage_ms:
+        esz = outs.K_out.element_size()
+        # emit reads K and V of every kept row and folded donor and writes K and V of the kept rows
+        emit_bytes = 2.0 * p.head_dim * esz * (n_assigned + float(out_len.sum()))
+        fold_path.update({"gather_ms": round(stage_ms["gather"], 4), "emit_ms": round(stage_ms["emit"], 4),
+                          "emit_row_bytes": emit_bytes,
+                          "emit_GB/s": (round(emit_bytes / (stage_ms["emit"] * 1e-3) / 1e9, 1)
+                                        if stage_ms["emit"] > 0 else None)})
 
     # ---- roofline of the dominant kernel: one scoring sweep is one Q.K^T pass of
     # 2 * (W*G) * N * d flops per unit on the matrix cores
@@ -276,8 +310,10 @@ def main():
                                             else "score_mfma_kernel<0> (score_rows)"),
                 "achieved": round(achieved, 2), "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),
-                "traffic": (MEASURED_TRAFFIC.get(args.workload, {}).get(dom)
-                            if args.layers == 0 and args.seqs == 0 else None),
+                "traffic": (PROFILED_TRAFFIC.get(args.workload, {}).get("bytes")
+                            if args.layers == 0 and args.seqs == 0 and args.seed_dedup == 0 else None),
+                "traffic_source": (PROFILED_TRAFFIC.get(args.workload, {}).get("source")
+                                   if args.layers == 0 and args.seqs == 0 and args.seed_dedup == 0 else None),
                 "kernel_ms": round(sweep_ms[dom], 4),
                 "flops_per_launch": passes * flops_pass,
                 "both_sweeps_frac": round(2 * flops_pass / ((sweep_ms["score_rows"] + sweep_ms["score_cols"]) * 1e-3)
@@ -285,6 +321,10 @@ def main():
                 # whole event against its own bound: one algorithmic Q.K^T pass at MFMA peak
                 "event_frac_of_one_pass_at_peak": round(flops_pass / (ms_per_step * 1e-3) / 1e12
                                                         / PEAK_MFMA_BF16_TFLOPS, 4)}
+        if pinned is not None:
+            roof["pinned_peaks"] = pinned
+            roof["frac_of_pinned_mfma"] = round(achieved / pinned["mfma_bf16_TFLOP/s"], 4)
+            roof["frac_of_pinned_mfma_with_epilogue"] = round(achieved / pinned["mfma_with_softmax_epilogue_TFLOP/s"], 4)
 
     # ---- CPU oracle on a bounded sample of the same units (rank 0, N = 1 only)
     cpu = None
@@ -306,7 +346,8 @@ def main():
         sub_ro = np.concatenate([[0], np.cumsum(sub_lens)]).astype(np.int64)
         sub_pl = b0.prefix_len_host.numpy()[pick]
         rp = ref.Params(dtype=p.dtype, head_dim=p.head_dim, q_per_kv=p.q_per_kv, window=p.window,
-                        recent=p.recent, budget=p.budget, core=p.core, seed_dedup=p.seed_dedup)
+                        recent=p.recent, budget=p.budget, core=p.core, seed_dedup=p.seed_dedup,
+                        sim_threshold=p.sim_threshold)
         threads = min(int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), os.cpu_count() or 1, take)
         tc0 = time.perf_counter()
         want = ref.compress(rp, sub_ro, sub_pl, Kh, Vh, Qh, n_threads=threads)
@@ -348,6 +389,7 @@ def main():
                    "ms_per_decode_step_amortised": round(ms_per_step / w.window, 6),
                    "graph_ms_per_step": (round(graph_ms, 4) if graph_ms is not None else None),
                    "two_stream_ms_per_step": (round(overlap_ms, 4) if overlap_ms is not None else None),
+                   "fold_path": fold_path,
                    "consumer_attend": consumer},
         "roofline": roof,
         "cpu_baseline": cpu,

@@ -317,6 +317,25 @@ int cask_timing_enable(int max_calls);
 int cask_timing_enable_stages(int max_calls, int n_stages);
 int cask_timing_read(float* stage_ms, int* n_calls);
 
+/* Measurement aids (not part of the method): plain loops that pin what the device delivers, so
+ * that a report can print measured ceilings beside the published ones.  Both only launch a kernel
+ * on `hip_stream`; the caller times it with events.
+ *
+ * cask_probe_issue: register-only loops of the scoring sweeps' instruction mix.  One unit = one
+ * v_mfma_f32_32x32x16_bf16 (32 768 flop, 32 matrix-pipe cycles), kind 0; the same followed by the
+ * vector epilogue of two logits (fma, exp2, add each), kind 1; the vector part alone, kind 2.
+ * `blocks` workgroups of 4 * waves_per_simd waves (one compute unit's SIMDs each get
+ * waves_per_simd of them) run iters * 8 units per wave.
+ *   operands  DEVICE, 32 KB of random bf16 values, 16-byte aligned (operand bits set the power)
+ *   cycles    DEVICE uint64 [2 * blocks]: per workgroup, shader-clock cycles and 100 MHz ticks
+ *   sink      DEVICE float [blocks * 256 * waves_per_simd] (keeps the loops alive)
+ * cask_probe_copy: dst[0, bytes) = src[0, bytes), 16 bytes per thread and step; bytes a multiple
+ * of 16, both pointers 16-byte aligned.  (Also the kernel of known size that scales the
+ * profiler's HBM byte counters.) */
+int cask_probe_issue(int kind, int waves_per_simd, int blocks, int iters, const void* operands,
+                     uint64_t* cycles, float* sink, void* hip_stream);
+int cask_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
+
 /* HOST: short name of a return code. */
 const char* cask_strerror(int code);
 

@@ -28,7 +28,8 @@ PATH_NO_FUSED_TAIL, PATH_NO_FUSED_SCORE, PATH_DEDUP_VECTOR, PATH_ATTEND_VECTOR, 
 EXPORTS = ["cask_plan", "cask_workspace_bytes", "cask_score", "cask_prefix_evict",
            "cask_partition", "cask_consolidate", "cask_compress", "cask_compress_static", "cask_compress_step",
            "cask_mass_diagnostics", "cask_group_diagnostics", "cask_attend", "cask_strerror",
-           "cask_timing_enable", "cask_timing_enable_stages", "cask_timing_read"]
+           "cask_timing_enable", "cask_timing_enable_stages", "cask_timing_read",
+           "cask_probe_issue", "cask_probe_copy"]
 STAGES = ["score_rows", "score_cols", "select", "index_roles", "similarity", "gather", "emit"]
 
 
@@ -155,6 +156,8 @@ def load():
             "cask_timing_enable": (C.c_int, [C.c_int]),
             "cask_timing_enable_stages": (C.c_int, [C.c_int, C.c_int]),
             "cask_timing_read": (C.c_int, [vp, vp]),
+            "cask_probe_issue": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]),
+            "cask_probe_copy": (C.c_int, [vp, vp, sz, vp]),
         }
         assert set(sigs) == set(EXPORTS)
         for name, (res, args) in sigs.items():
@@ -415,3 +418,59 @@ def compress_static(b: Batch, out: Outputs, scores: Optional[torch.Tensor] = Non
     if rc:
         raise CaskError("cask_compress_static", rc)
     return out
+
+
+def probe_issue(kind: int, waves_per_simd: int = 2, blocks: int = 256, iters: int = 20000) -> dict:
+    """cask_probe_issue timed with events: {ms, ghz (shader clock read in the kernel), cycles_per_unit
+    (per SIMD), tflops (kinds 0, 1)}."""
+    dev = torch.device("cuda", torch.cuda.current_device())
+    g = torch.Generator().manual_seed(1)
+    ops = (torch.rand(16384, generator=g) * 2 - 1).to(torch.bfloat16).to(dev)
+    cyc = torch.zeros(2 * blocks, dtype=torch.int64, device=dev)
+    sink = torch.empty(blocks * 256 * waves_per_simd, dtype=torch.float32, device=dev)
+    lib = load()
+
+    def run(n):
+        rc = lib.cask_probe_issue(kind, waves_per_simd, blocks, n, _dptr(ops), _dptr(cyc), _dptr(sink), _stream())
+        if rc:
+            raise CaskError("cask_probe_issue", rc)
+    run(max(iters // 4, 1))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    run(iters)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    c = cyc.cpu().numpy().reshape(-1, 2).astype(np.float64)
+    ghz = float(c[:, 0].sum() / c[:, 1].sum() * 0.1)
+    units = iters * 8.0
+    # cycles per unit and SIMD from the wall time and the clock: the waves of a SIMD do not finish
+    # together (the oldest ready wave is served first), so one wave's own cycle count says little
+    rounds = -(-blocks // 256)          # workgroups beyond one per compute unit queue up
+    res = dict(ms=ms, ghz=ghz, cycles_per_unit=ms * 1e6 * ghz / (units * waves_per_simd * rounds))
+    if kind != 2:
+        res["tflops"] = blocks * 4 * waves_per_simd * units * 32768.0 / (ms * 1e-3) / 1e12
+    return res
+
+
+def probe_copy(n_bytes: int = 1 << 30, reps: int = 5) -> dict:
+    """cask_probe_copy timed with events: GB/s counting the bytes read plus the bytes written."""
+    dev = torch.device("cuda", torch.cuda.current_device())
+    src = torch.empty(n_bytes, dtype=torch.uint8, device=dev).random_(0, 256)
+    dst = torch.empty_like(src)
+    lib = load()
+
+    def run():
+        rc = lib.cask_probe_copy(_dptr(src), _dptr(dst), n_bytes, _stream())
+        if rc:
+            raise CaskError("cask_probe_copy", rc)
+    run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    ok = bool(torch.equal(src[:4096], dst[:4096]) and torch.equal(src[-4096:], dst[-4096:]))
+    return dict(ms=ms, gbs=2.0 * n_bytes / (ms * 1e-3) / 1e9, bytes=n_bytes, verified=ok)

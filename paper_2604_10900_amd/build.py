@@ -8,7 +8,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libcask.so")
-SOURCES = ["cask_api.hip", "cask_score.hip", "cask_select.hip", "cask_merge.hip", "cask_tail.hip", "cask_attend.hip", "cask_seed.hip"]
+SOURCES = ["cask_api.hip", "cask_score.hip", "cask_select.hip", "cask_merge.hip", "cask_tail.hip", "cask_attend.hip", "cask_seed.hip",
+           "cask_probe.hip"]
 
 
 def hipcc() -> str:
