@@ -299,15 +299,15 @@ def main():
         # so A is the one reported; `both_sweeps_frac` covers the pair.
         dom = "score_rows"
         t_dom = sweep_ms[dom] * 1e-3
-        # short units: both sweeps are one launch (score_mfma_kernel<2>), bracketed as the first stage
-        one_launch = (w.dtype != "f32" and p.head_dim == 128 and int(lens.max()) <= 1024 and p.budget <= 1024
-                      and args.seed_dedup == 0
-                      and os.environ.get("CASK_FUSED_TAIL", "1")[0] != "0"
-                      and os.environ.get("CASK_FUSED_SCORE", "1")[0] != "0")
+        # Both sweeps as ONE launch, bracketed as the first stage (the second bracket is then
+        # empty): short units (score_mfma_kernel<2>, with the one-launch tail), and many long units
+        # with W*G <= 512 (score_mfma_kernel<3>).  Told from the brackets themselves.
+        one_launch = w.dtype != "f32" and p.head_dim == 128 and sweep_ms["score_cols"] < 0.05 * sweep_ms["score_rows"]
+        fused_name = ("score_mfma_kernel<2> (both sweeps in one launch, short units)" if int(lens.max()) <= 1024
+                      else "score_mfma_kernel<3> (both sweeps in one launch)")
         passes = 2.0 if one_launch else 1.0
         achieved = passes * flops_pass / t_dom / 1e12
-        roof = {"bound": "mfma", "kernel": ("score_mfma_kernel<2> (both sweeps in one launch)" if one_launch
-                                            else "score_mfma_kernel<0> (score_rows)"),
+        roof = {"bound": "mfma", "kernel": (fused_name if one_launch else "score_mfma_kernel<0> (score_rows)"),
                 "achieved": round(achieved, 2), "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),
                 "traffic": (PROFILED_TRAFFIC.get(args.workload, {}).get("bytes")

@@ -120,7 +120,8 @@ enum {
   CASK_PATH_NO_FUSED_SCORE = 2, /* short units: two scoring launches instead of one */
   CASK_PATH_DEDUP_VECTOR = 4,   /* bf16 de-duplicated seeding on the vector kernel fp32 caches use */
   CASK_PATH_ATTEND_VECTOR = 8,  /* bf16 cask_attend on the vector kernel fp32 caches use */
-  CASK_PATH_NO_FUSED_SWEEPS = 16 /* long units with few window rows: two scoring launches instead of one */
+  CASK_PATH_NO_FUSED_SWEEPS = 16, /* many long units with W*G <= 512: two scoring launches instead of one */
+  CASK_PATH_FORCE_FUSED_SWEEPS = 32 /* W*G <= 512: one scoring launch whatever the number of units */
 };
 
 typedef struct {
@@ -323,7 +324,8 @@ int cask_timing_read(float* stage_ms, int* n_calls);
  *
  * cask_probe_issue: register-only loops of the scoring sweeps' instruction mix.  One unit = one
  * v_mfma_f32_32x32x16_bf16 (32 768 flop, 32 matrix-pipe cycles), kind 0; the same followed by the
- * vector epilogue of two logits (fma, exp2, add each), kind 1; the vector part alone, kind 2.
+ * vector epilogue of two logits (fma, exp2, add each), kind 1; the vector part alone, kind 2;
+ * kind 1 with the MFMA's first operand read from LDS as the sweeps read theirs, kind 3.
  * `blocks` workgroups of 4 * waves_per_simd waves (one compute unit's SIMDs each get
  * waves_per_simd of them) run iters * 8 units per wave.
  *   operands  DEVICE, 32 KB of random bf16 values, 16-byte aligned (operand bits set the power)

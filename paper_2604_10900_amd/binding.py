@@ -22,6 +22,7 @@ F32, BF16 = 0, 1
 OK, EINVAL, ENOMEM, EDEVICE = 0, -1, -2, -3
 ST_ACTIVE, ST_IDENTITY, ST_PREFIX_BUDGET_EXHAUSTED, ST_MERGE_INACTIVE = 0, 1, 2, 4
 PATH_NO_FUSED_TAIL, PATH_NO_FUSED_SCORE, PATH_DEDUP_VECTOR, PATH_ATTEND_VECTOR, PATH_NO_FUSED_SWEEPS = 1, 2, 4, 8, 16
+PATH_FORCE_FUSED_SWEEPS = 32
 (ROLE_PREFIX_DROP, ROLE_PREFIX_KEEP, ROLE_CORE, ROLE_SEED, ROLE_DONOR, ROLE_RECENT,
  ROLE_DECODE_EVICT) = range(7)
 

@@ -246,6 +246,8 @@ int cask_score(const cask_params* params, const cask_batch* batch, float* scores
   if ((reinterpret_cast<uintptr_t>(ws) & 15u) != 0) return CASK_EINVAL;
   const Workspace wl = layout_workspace(kp, b.n_units, b.total_rows, b.max_unit_len);
   if (ws_bytes < wl.total) return CASK_ENOMEM;
+  if (score_fused_fits(kp, b) && (reinterpret_cast<uintptr_t>(scores) & 15u) == 0)
+    return dev_rc(launch_score_fused(kp, b, wl, scores, static_cast<hipStream_t>(hip_stream)));
   return dev_rc(launch_score(kp, b, wl, static_cast<char*>(ws), scores, static_cast<hipStream_t>(hip_stream)));
 }
 
@@ -414,6 +416,12 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
                            !(kp.path_flags & CASK_PATH_NO_FUSED_SCORE);
   if (fused_score) {
     e = launch_score_parts(kp, b, wl, w, st);
+    if (e != hipSuccess) return CASK_EDEVICE;
+    rec.mark();
+  } else if (!given && score_fused_fits(kp, b) && (reinterpret_cast<uintptr_t>(s) & 15u) == 0) {
+    // many long units with few window rows: both sweeps in one launch (reported as the first
+    // scoring stage; the second reads as an empty bracket)
+    e = launch_score_fused(kp, b, wl, s, st);
     if (e != hipSuccess) return CASK_EDEVICE;
     rec.mark();
   } else if (!given) {

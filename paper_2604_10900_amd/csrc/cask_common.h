@@ -223,6 +223,11 @@ struct Batch {
 // `between`, when not null, is recorded on the stream between the two scoring sweeps.
 hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, char* ws,
                         float* scores, hipStream_t st, hipEvent_t between = nullptr);
+// Both sweeps in one launch for long units with W*G <= 512 (bf16, d = 128), results in `scores`
+// (must be 16-byte aligned when W*G > 256).
+bool score_fused_fits(const KParams& kp, const Batch& b);
+hipError_t launch_score_fused(const KParams& kp, const Batch& b, const Workspace& wl, float* scores,
+                              hipStream_t st);
 // Short units (at most Workspace::parts_pitch rows, one key split, bf16 d = 128): both scoring
 // sweeps in one launch, leaving partial column sums for the consumer to add.
 bool score_parts_fits(const KParams& kp, const Batch& b, const Workspace& wl);

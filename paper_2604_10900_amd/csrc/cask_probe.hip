@@ -14,7 +14,9 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-// KIND 0: MFMA alone; 1: MFMA + vector epilogue of two logits; 2: vector epilogue alone.
+// KIND 0: MFMA alone; 1: MFMA + vector epilogue of two logits; 2: vector epilogue alone;
+// 3: as 1, with the MFMA's first operand read from LDS at the sweeps' rate (one 16-byte read per
+// lane for every two MFMA, conflict-free), to see what the operand traffic costs.
 // One "unit" = one MFMA (32 matrix-pipe cycles) and/or six vector instructions.
 template <int KIND>
 __global__ __launch_bounds__(1024) void issue_probe_kernel(const uint4* __restrict__ operands, int iters,
@@ -31,12 +33,23 @@ __global__ __launch_bounds__(1024) void issue_probe_kernel(const uint4* __restri
   const float c = 0.127f, nm = -3.0f;
   f32x16 acc = {0};
   float s0 = 0.f, s1 = 0.f;
+  __shared__ uint4 tile[KIND == 3 ? 4096 : 1];  // 64 KB: a ring's worth of operand data
+  if (KIND == 3) {
+    for (int i = tid; i < 4096; i += blockDim.x) tile[i] = operands[i & 2047];
+  }
+  bf16x8 a_lds[4] = {a, a, a, a};
   __syncthreads();
   const uint64_t t0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      if (KIND != 2) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+      if (KIND == 3) {
+        // operands for four units ahead, read two units apart
+        if ((i & 1) == 0) a_lds[(i >> 1) & 3] = __builtin_bit_cast(bf16x8, tile[(((it * 4 + (i >> 1)) * 64) + (tid & 63) + (tid >> 6) * 512) & 4095]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lds[((i >> 1) + 2) & 3], b, acc, 0, 0, 0);
+      } else if (KIND != 2) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+      }
       if (KIND != 0) {
         // the sweeps' epilogue for two logits, written as the six instructions themselves so
         // that the optimiser cannot hoist or merge any of them: fma, fma, exp2, exp2, add, add
@@ -86,7 +99,7 @@ extern "C" {
 
 int cask_probe_issue(int kind, int waves_per_simd, int blocks, int iters, const void* operands,
                      uint64_t* cycles, float* sink, void* hip_stream) {
-  if (kind < 0 || kind > 2 || waves_per_simd < 1 || waves_per_simd > 4 || blocks < 1 || blocks > 65536 ||
+  if (kind < 0 || kind > 3 || waves_per_simd < 1 || waves_per_simd > 4 || blocks < 1 || blocks > 65536 ||
       iters < 1 || iters > (1 << 24) || !operands || !cycles || !sink)
     return CASK_EINVAL;
   if ((reinterpret_cast<uintptr_t>(operands) & 15u) != 0) return CASK_EINVAL;
@@ -95,7 +108,8 @@ int cask_probe_issue(int kind, int waves_per_simd, int blocks, int iters, const 
   const uint4* ops = static_cast<const uint4*>(operands);
   if (kind == 0) issue_probe_kernel<0><<<grid, block, 0, st>>>(ops, iters, cycles, sink);
   else if (kind == 1) issue_probe_kernel<1><<<grid, block, 0, st>>>(ops, iters, cycles, sink);
-  else issue_probe_kernel<2><<<grid, block, 0, st>>>(ops, iters, cycles, sink);
+  else if (kind == 2) issue_probe_kernel<2><<<grid, block, 0, st>>>(ops, iters, cycles, sink);
+  else issue_probe_kernel<3><<<grid, block, 0, st>>>(ops, iters, cycles, sink);
   return hipGetLastError() == hipSuccess ? CASK_OK : CASK_EDEVICE;
 }
 

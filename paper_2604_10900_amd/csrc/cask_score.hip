@@ -144,8 +144,15 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     float* __restrict__ parts, int part_pitch) {
   constexpr int NK = 8;  // k-steps per tile
   // MODE 2 = both sweeps in one launch for short units (one key split): the first pass is
-  // MODE 0; the second keeps the same resident window rows and streams the keys again
+  // MODE 0; the second keeps the same resident window rows and streams the keys again, leaving
+  // one partial column sum per wave.  MODE 3 = the same for units of any length when W*G <= 512
+  // (at most two row blocks per unit): the four waves' column sums are added in LDS in wave
+  // order and leave the workgroup as one addend per key -- stored when the unit has one row
+  // block, added atomically onto scores cleared beforehand when it has two (two addends onto
+  // zero: the order cannot change the bits).
   constexpr bool kRowPass = MODE != 1;
+  constexpr bool kTwoPass = MODE >= 2;
+  constexpr bool kWgReduce = MODE == 3;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   unsigned char* ring = smem;
 
@@ -166,11 +173,18 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   const uint16_t* str_ptr;
   int res_base, res_limit, s_begin, s_end;  // resident rows [res_base, ..), stream rows [s_begin, s_end)
   int split = 0;
+  bool half_block = false;
   if (kRowPass) {
     const int qb = tile / n_splits;
     split = tile % n_splits;
     res_base = qb * kResRows;
     if (res_base >= Mq) return;
+    // A last row block of at most 128 window rows (W*G = 896: three and a half blocks) would
+    // leave two of the four waves without rows.  Such a block is shared out differently: waves
+    // w and w + 2 hold the same 64 rows and take the first and the second 32 keys of every
+    // stage, so all four waves work, a stage costs the workgroup half the time, and the two
+    // partial statistics of a row are combined through LDS at the end.
+    half_block = MODE == 0 && Mq - res_base <= kResRows / 2;
     res_ptr = Qu;
     res_limit = Mq;
     str_ptr = Ku;
@@ -221,7 +235,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   auto issue_stage = [&](int stage) {  // rows past s_end read as zero through the descriptor
     unsigned char* slot = ring + (stage % kDepth) * kStageBytes;
     // MODE 2: the stages of the second pass follow those of the first and read the same keys
-    const int src_stage = (MODE == 2 && stage >= n_stages) ? stage - n_stages : stage;
+    const int src_stage = (kTwoPass && stage >= n_stages) ? stage - n_stages : stage;
     const int soff = (s_begin + src_stage * kStageRows) * kRowBytes;
     if (MODE == 1 && (stage & (kWaves - 1)) == wv)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
@@ -246,11 +260,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // ring's first loads are on their way so that the two latencies overlap.
   const __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(res_ptr), 0, res_limit * kRowBytes, 0x00020000);
+  const int wrow = half_block ? (wv & 1) : wv;  // the wave's 64-row group of the resident block
+  const int rt_own = wv >> 1;                    // half block: the 32-row tile of every stage this wave takes
   bf16x8 bres[2][NK];
   int res_row[2];
 #pragma unroll
   for (int ct = 0; ct < 2; ++ct) {
-    const int r = res_base + wv * 64 + ct * 32 + c32;
+    const int r = res_base + wrow * 64 + ct * 32 + c32;
     res_row[ct] = r;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
@@ -259,7 +275,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
   }
   // a wave whose resident rows are all past the end only helps with loads and barriers
-  const bool wave_live = res_base + wv * 64 < res_limit;
+  const bool wave_live = res_base + wrow * 64 < res_limit;
 
   // A-operand rows of this lane inside a stage: row rt * 32 + c32 -> group, row-in-group
   const int a_off = (c32 >> 2) * kGroupPitch + (c32 & 3) * 16 + h * 64;
@@ -445,7 +461,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) {
       const int trow0 = stage_base + rt * 32;
-      if (trow0 >= s_end) continue;
+      if (trow0 >= s_end || (half_block && rt != rt_own)) continue;
       load_a(a0, cur, rt);
       load_nl(nl0, cur, rt);
 #pragma unroll
@@ -517,6 +533,41 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
     drain(masked, acc1, nl1, 1, s_begin + (to - 1) * kStageRows + 32);
   };
+  // The same for a half block: two tiles per stage (the wave's own tile row, both resident
+  // column tiles), two stages per trip so that the operand registers alternate statically.
+  auto pipelined_half = [&](auto masked, int from, int to) {
+    constexpr bool kMasked = decltype(masked)::value;
+    const int ro = rt_own * 32;
+    stage_sync(from);
+    load_a(a0, slot_of(from), rt_own);
+    if (!kMasked && from == 0) {
+      chain(acc1, a0, 1);
+      m_ref[1] = acc1[0] * c;
+      chain(acc0, a0, 0);
+      m_ref[0] = acc0[0] * c;
+    } else {
+      chain(acc0, a0, 0);
+    }
+    for (int it = from;; it += 2) {
+      const int base = s_begin + it * kStageRows + ro;
+      load_a(a1, slot_of(it + 1), rt_own);  // stage it + 1 has landed with stage it
+      fused(masked, acc1, a0, 1, acc0, nl0, 0, base);
+      if (it + 1 >= to) {
+        drain(masked, acc1, nl0, 1, base);
+        break;
+      }
+      stage_sync(it + 1);
+      fused(masked, acc0, a1, 0, acc1, nl0, 1, base);
+      load_a(a0, slot_of(it + 2), rt_own);
+      fused(masked, acc1, a1, 1, acc0, nl0, 0, base + kStageRows);
+      if (it + 2 >= to) {
+        drain(masked, acc1, nl0, 1, base + kStageRows);
+        break;
+      }
+      stage_sync(it + 2);
+      fused(masked, acc0, a0, 0, acc1, nl0, 1, base + kStageRows);
+    }
+  };
   const std::integral_constant<bool, false> clean_tag;
   const std::integral_constant<bool, true> masked_tag;
 
@@ -531,13 +582,22 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       slow_stage(it);
     }
   }
-  if (f1 > f0) pipelined(clean_tag, f0, f1);
-  it = f1;
-  if (kRowPass && f1 > 0 && n_stages > f1) {
-    // the tail (causal, ragged end) after at least one clean stage: the reference is set, so
-    // the masked epilogue can take it
-    pipelined(masked_tag, f1, n_stages);
-    it = n_stages;
+  if (MODE == 0 && half_block) {
+    if (f1 > f0) pipelined_half(clean_tag, f0, f1);
+    it = f1;
+    if (f1 > 0 && n_stages > f1) {
+      pipelined_half(masked_tag, f1, n_stages);
+      it = n_stages;
+    }
+  } else {
+    if (f1 > f0) pipelined(clean_tag, f0, f1);
+    it = f1;
+    if (kRowPass && f1 > 0 && n_stages > f1) {
+      // the tail (causal, ragged end) after at least one clean stage: the reference is set, so
+      // the masked epilogue can take it
+      pipelined(masked_tag, f1, n_stages);
+      it = n_stages;
+    }
   }
   for (; it < n_stages; ++it) {
     stage_sync(it);
@@ -545,10 +605,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   }
   // loads issued past the last stage may still be landing in LDS: let them finish before the
   // workgroup's LDS can be handed to another one
-  if (MODE != 2) __builtin_amdgcn_s_waitcnt(0x0F70);
+  if (!kTwoPass) __builtin_amdgcn_s_waitcnt(0x0F70);
 
   // ---- finish
-  if (MODE == 2) {
+  if (kTwoPass) {
     // ---- second pass: the same resident window rows are now the A operand and the keys
     // stream through the ring once more (their stages were requested while the first pass
     // finished), so a lane owns one key column of a tile and 16 window rows.  exp2(c x - L_row)
@@ -615,14 +675,54 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);
       }
     };
-    auto flush = [&](int key) {  // both resident tiles of this key tile are through their epilogue
+    // MODE 3: per stage and wave 64 partial column sums go to LDS (a ring of four stages behind
+    // the -L table), and two barriers later the wave whose turn it is adds the four waves' sums
+    // in wave order.  The LDS traffic is written out as instructions: accesses the compiler
+    // generates here would be taken to alias the ring's loads in flight and wait for all of them.
+    const unsigned xs_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)(
+        smem + kDepth * kStageBytes + kResRows * sizeof(float));
+    const int two_blocks = Mq > kResRows;
+    const float inv_mq = 1.0f / (float)Mq;
+    auto reduce_stage = [&](int st) {  // all four waves' sums of pass-2 stage `st` are in LDS
+      float v0, v1, v2, v3;
+      const unsigned addr = xs_base + (unsigned)(((st & 3) * kWaves * 64 + lane) * 4);
+      asm volatile(
+          "ds_read_b32 %0, %4\n\tds_read_b32 %1, %4 offset:256\n\tds_read_b32 %2, %4 offset:512\n\t"
+          "ds_read_b32 %3, %4 offset:768\n\ts_waitcnt lgkmcnt(0)"
+          : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+          : "v"(addr));
+      float v = v0;  // wave 0 always has rows
+      if (res_base + 64 < res_limit) v += v1;
+      if (res_base + 128 < res_limit) v += v2;
+      if (res_base + 192 < res_limit) v += v3;
+      const int key = s_begin + st * kStageRows + lane;
+      if (key < N) {
+        if (two_blocks) atomicAdd(&scores[row0 + key], v * inv_mq);
+        else scores[row0 + key] = v * inv_mq;
+      }
+    };
+    auto flush = [&](int key, int st, int kt) {  // both resident tiles of this key tile are through their epilogue
       const float tot = ksum + __shfl_xor(ksum, 32, 64);
-      if (h == 0 && key < N) part_out[key] = tot;
+      if (kWgReduce) {
+        if (h == 0) {
+          const unsigned addr = xs_base + (unsigned)((((st & 3) * kWaves + wv) * 64 + kt * 32 + c32) * 4);
+          asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(tot));
+        }
+      } else {
+        if (h == 0 && key < N) part_out[key] = tot;
+      }
       ksum = 0.f;
+    };
+    // barrier of pass-2 stage it2; MODE 3: the waves' LDS writes are complete before it, and the
+    // sums of stage it2 - 2 (complete since the barrier before this one) are added by one wave
+    auto sync2 = [&](int it2) {
+      if (kWgReduce) __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) alone; vmcnt is stage_sync's business
+      stage_sync(n_stages + it2);
+      if (kWgReduce && it2 >= 2 && ((it2 - 2) & 3) == wv) reduce_stage(it2 - 2);
     };
     // stages [from, to) of the second pass (ring stages n_stages + from ...), software-pipelined
     auto pipelined2 = [&](auto masked, int from, int to) {
-      stage_sync(n_stages + from);
+      sync2(from);
       load_a(a0, slot_of(n_stages + from), 0);
       chain2(acc0, a0, 0);
       for (int it = from;; ++it) {
@@ -632,31 +732,59 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         fused2(masked, acc1, a0, 1, acc0, 0, key0);
         load_a(a0, slot_of(n_stages + it + 1), 0);
         fused2(masked, acc0, a1, 0, acc1, 1, key0);
-        flush(key0);
+        flush(key0, it, 0);
         fused2(masked, acc1, a1, 1, acc0, 0, key0 + 32);
         if (it + 1 >= to) break;
-        stage_sync(n_stages + it + 1);
+        sync2(it + 1);
         fused2(masked, acc0, a0, 0, acc1, 1, key0 + 32);
-        flush(key0 + 32);
+        flush(key0 + 32, it, 1);
       }
       const int key1 = s_begin + (to - 1) * kStageRows + 32 + c32;
       const int d = mask_d2(1, key1);
 #pragma unroll
       for (int i = 0; i < 8; ++i) piece2(masked, acc1, 1, i, d);
-      flush(key1);
+      flush(key1, to - 1, 1);
     };
     if (wave_live) {
       const int clean = min(f1, n_stages);  // stages whose keys every window row sees
       if (clean > 0) pipelined2(clean_tag, 0, clean);
       if (n_stages > clean) pipelined2(masked_tag, clean, n_stages);
       // keys past the stages that ran are hidden from every row of this workgroup
-      for (int key = s_begin + n_stages * kStageRows + lane; key < N; key += 64) part_out[key] = 0.f;
+      if (!kWgReduce)
+        for (int key = s_begin + n_stages * kStageRows + lane; key < N; key += 64) part_out[key] = 0.f;
     } else {
-      for (int it2 = 0; it2 < n_stages; ++it2) stage_sync(n_stages + it2);
+      for (int it2 = 0; it2 < n_stages; ++it2) sync2(it2);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (kWgReduce) {
+      // the last two stages' sums: complete once every wave is here
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+      __builtin_amdgcn_s_barrier();
+      if (n_stages >= 2 && ((n_stages - 2) & 3) == wv) reduce_stage(n_stages - 2);
+      if (n_stages >= 1 && ((n_stages - 1) & 3) == wv) reduce_stage(n_stages - 1);
+      // a single row block stores its scores: keys past its stages are hidden from every row
+      if (!two_blocks && wv == 0)
+        for (int key = s_begin + n_stages * kStageRows + lane; key < N; key += 64) scores[row0 + key] = 0.f;
+    }
   } else if (MODE == 0) {
     float2* part = rowstat + (size_t)unit * n_splits * mq_pad;
+    if (half_block) {
+      // waves 2 and 3 hand the statistics of their key halves to waves 0 and 1 (same rows, same
+      // lanes) through an LDS area behind the ring (the ring itself may still receive the zero
+      // fill of other waves' loads past the last stage)
+      float2* xch = reinterpret_cast<float2*>(smem + kDepth * kStageBytes);
+      if (wv >= 2) {
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) xch[((wv - 2) * 2 + ct) * 64 + lane] = make_float2(m_ref[ct], l_run[ct]);
+      }
+      __syncthreads();
+      if (wv >= 2) return;
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) {
+        const float2 o = xch[(wv * 2 + ct) * 64 + lane];
+        ml_combine(m_ref[ct], l_run[ct], o.x, o.y);
+      }
+    }
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct) {
       const float m2 = __shfl_xor(m_ref[ct], 32, 64);
@@ -806,8 +934,8 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   const int units8 = (b.n_units + 7) / 8 * 8;
   const uint16_t* K = static_cast<const uint16_t*>(b.K);
   const uint16_t* Q = static_cast<const uint16_t*>(b.Q);
-  const size_t ldsA = (size_t)kDepth * kStageBytes;
-  const size_t ldsB = ldsA;
+  const size_t ldsB = (size_t)kDepth * kStageBytes;
+  const size_t ldsA = ldsB + 4 * 64 * sizeof(float2);  // + the exchange area of a half row block
   static LdsLimitOnce limA, limB;
   hipError_t e = limA.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<0>), 160 * 1024);
   if (e == hipSuccess) e = limB.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<1>), 160 * 1024);
@@ -824,6 +952,55 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   score_mfma_kernel<1><<<dim3(units8 * tilesB), dim3(kThreads), ldsB, st>>>(
       kp, b.n_units, tilesB, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
       bias, nullptr, scores, nullptr, 0);
+  return hipGetLastError();
+}
+
+namespace {
+__global__ __launch_bounds__(256) void clear_scores_kernel(float* __restrict__ scores, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * 256 * 4;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += stride) {
+    if (i + 3 < n) {
+      *reinterpret_cast<float4*>(scores + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    } else {
+      for (int64_t j = i; j < n; ++j) scores[j] = 0.f;
+    }
+  }
+}
+}  // namespace
+
+// Both sweeps in one launch for units of any length: pays when a workgroup of the second sweep
+// would stream few window rows (W*G <= 512: at most eight stages behind a full prologue) and
+// there are enough (unit, row block) pairs to fill the chip several times over.
+bool score_fused_fits(const KParams& kp, const Batch& b) {
+  const int row_blocks = (kp.Mq + kResRows - 1) / kResRows;
+  if (!score_uses_mfma(kp) || kp.Mq > 2 * kResRows || (kp.path_flags & CASK_PATH_NO_FUSED_SWEEPS)) return false;
+  return (int64_t)b.n_units * row_blocks >= 1024 || (kp.path_flags & CASK_PATH_FORCE_FUSED_SWEEPS);
+}
+
+hipError_t launch_score_fused(const KParams& kp, const Batch& b, const Workspace& wl, float* scores,
+                              hipStream_t st) {
+  if (!score_fused_fits(kp, b)) return hipErrorInvalidValue;
+  const size_t lds = (size_t)kDepth * kStageBytes + kResRows * sizeof(float) + 4 * kWaves * 64 * sizeof(float);
+  static LdsLimitOnce lim;
+  const hipError_t e = lim.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<3>), 160 * 1024);
+  if (e != hipSuccess) return e;
+  const int units8 = (b.n_units + 7) / 8 * 8;
+  const int qblocks = (kp.Mq + kResRows - 1) / kResRows;
+  if (qblocks == 2) {
+    // two workgroups add onto each key's score; scores is 4-byte aligned only: float4 stores need 16
+    const bool al16 = (reinterpret_cast<uintptr_t>(scores) & 15u) == 0;
+    if (al16) {
+      const int64_t n = b.total_rows;
+      const int blocks = (int)((n / 4 + 255) / 256 < 8192 ? (n / 4 + 255) / 256 + 1 : 8192);
+      clear_scores_kernel<<<dim3(blocks), dim3(256), 0, st>>>(scores, n);
+    } else {
+      return hipErrorInvalidValue;
+    }
+  }
+  const int whole = (b.max_unit_len + kStageRows - 1) / kStageRows * kStageRows;
+  score_mfma_kernel<3><<<dim3(units8 * qblocks), dim3(kThreads), lds, st>>>(
+      kp, b.n_units, qblocks, 1, whole, 1, wl.mq_pad, b.row_off, static_cast<const uint16_t*>(b.K),
+      static_cast<const uint16_t*>(b.Q), nullptr, nullptr, nullptr, scores, nullptr, 0);
   return hipGetLastError();
 }
 

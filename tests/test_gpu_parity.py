@@ -91,6 +91,36 @@ def test_bf16_mfma_odd_window_noncausal_and_custom_scale():
         _note((causal, scale, st))
 
 
+@pytest.mark.parametrize("G,Wn,causal", [(4, 128, 1), (2, 128, 1), (4, 128, 0), (3, 100, 1), (1, 64, 1), (4, 72, 1)])
+def test_both_sweeps_in_one_launch_for_long_units(G, Wn, causal):
+    """W*G <= 512: the two scoring sweeps of long units as one launch, the four waves' column sums
+    added in LDS (one row block: stored; two: added onto cleared scores).  Forced here on a small
+    batch (the library takes the path by itself from about a thousand (unit, row block) pairs);
+    ragged units shorter than, equal to and far longer than a stage, keys inside the window,
+    against the oracle, against the two-launch path, and bit-identical when run again."""
+    lens = [Wn, Wn + 1, 300, 777, 1900, 4097, 2048]
+    pref = [0, 0, 100, 333, 40, 1000, 0]
+    c = _ragged_bf16(lens, pref, G=G, Wn=Wn, seed=11)
+    kw = dict(dtype=cask.BF16, head_dim=128, q_per_kv=G, window=Wn, recent=min(Wn, 40), budget=Wn + 60,
+              sim_threshold=0.8, causal=causal)
+    row_off, prefix_len, K, V, Q = parity.host_arrays(c)
+    p1 = cask.Params(path_flags=cask.binding.PATH_FORCE_FUSED_SWEEPS, **kw)
+    p2 = cask.Params(path_flags=cask.binding.PATH_NO_FUSED_SWEEPS, **kw)
+    want = ref.score(parity.ref_params(p1), row_off, K, Q)
+    b1, b2 = parity.to_device(c, p1), parity.to_device(c, p2)
+    s1 = cask.score(b1)
+    s1b = cask.score(b1, torch.full_like(s1, 7.0))          # whatever the buffer held before
+    s2 = cask.score(b2)
+    torch.cuda.synchronize()
+    e1 = parity.check_scores(s1.cpu().numpy(), want, row_off)
+    e2 = parity.check_scores(s2.cpu().numpy(), want, row_off)
+    assert torch.equal(s1, s1b), "one-launch scoring is not deterministic"
+    np.testing.assert_allclose(np.add.reduceat(s1.cpu().numpy().astype(np.float64), row_off[:-1]), 1.0, atol=2e-5)
+    _note((G, Wn, causal, "score error / max: one launch", e1, "two launches", e2))
+    st = parity.full_check(c, p1)          # the whole event through the one-launch scoring
+    _note(st)
+
+
 def test_nonpositive_softmax_scale_is_the_default_scale():
     """softmax_scale <= 0 means 1/sqrt(d) in cask_score and in cask_attend, as in the oracle."""
     dev = torch.device("cuda:0")
