@@ -161,13 +161,15 @@ def main():
         pm = binding.probe_issue(0, waves_per_simd=2, blocks=256, iters=20000)
         pv = binding.probe_issue(1, waves_per_simd=2, blocks=256, iters=20000)
         pc = binding.probe_copy(1 << 30)
+        pr = binding.probe_read(1 << 30)
         pinned = {"mfma_bf16_TFLOP/s": round(pm["tflops"], 1), "mfma_loop_clock_GHz": round(pm["ghz"], 3),
                   "mfma_loop_cycles_per_mfma": round(pm["cycles_per_unit"], 2),
                   "mfma_with_softmax_epilogue_TFLOP/s": round(pv["tflops"], 1),
                   "mfma_with_softmax_epilogue_clock_GHz": round(pv["ghz"], 3),
                   "mfma_with_softmax_epilogue_cycles_per_mfma": round(pv["cycles_per_unit"], 2),
-                  "copy_GB/s": round(pc["gbs"], 1),
-                  "note": "cask_probe_issue kinds 0 and 1 (256 workgroups x 8 waves: two waves per SIMD on every compute unit), cask_probe_copy (1 GiB, read + write)"}
+                  "copy_GB/s": round(pc["gbs"], 1), "read_GB/s": round(pr["gbs"], 1),
+                  "note": "cask_probe_issue kinds 0 and 1 (256 workgroups x 8 waves: two waves per SIMD on every "
+                          "compute unit), cask_probe_copy (1 GiB, bytes read + written), cask_probe_read (1 GiB)"}
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -302,7 +304,7 @@ def main():
         # Both sweeps as ONE launch, bracketed as the first stage (the second bracket is then
         # empty): short units (score_mfma_kernel<2>, with the one-launch tail), and many long units
         # with W*G <= 512 (score_mfma_kernel<3>).  Told from the brackets themselves.
-        one_launch = w.dtype != "f32" and p.head_dim == 128 and sweep_ms["score_cols"] < 0.05 * sweep_ms["score_rows"]
+        one_launch = w.dtype != "f32" and p.head_dim == 128 and sweep_ms["score_cols"] < 0.25 * sweep_ms["score_rows"]
         fused_name = ("score_mfma_kernel<2> (both sweeps in one launch, short units)" if int(lens.max()) <= 1024
                       else "score_mfma_kernel<3> (both sweeps in one launch)")
         passes = 2.0 if one_launch else 1.0

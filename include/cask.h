@@ -337,6 +337,10 @@ int cask_timing_read(float* stage_ms, int* n_calls);
 int cask_probe_issue(int kind, int waves_per_simd, int blocks, int iters, const void* operands,
                      uint64_t* cycles, float* sink, void* hip_stream);
 int cask_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
+/* cask_probe_read: a read-only stream over src[0, bytes) (what the HBM-bound kernels of the event
+ * do: they read far more than they write); `blocks` workgroups of 256 threads, eight 16-byte
+ * loads in flight per thread; sink DEVICE uint32 [blocks * 256]. */
+int cask_probe_read(const void* src, size_t bytes, uint32_t* sink, int blocks, void* hip_stream);
 
 /* HOST: short name of a return code. */
 const char* cask_strerror(int code);

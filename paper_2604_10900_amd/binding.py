@@ -30,7 +30,7 @@ EXPORTS = ["cask_plan", "cask_workspace_bytes", "cask_score", "cask_prefix_evict
            "cask_partition", "cask_consolidate", "cask_compress", "cask_compress_static", "cask_compress_step",
            "cask_mass_diagnostics", "cask_group_diagnostics", "cask_attend", "cask_strerror",
            "cask_timing_enable", "cask_timing_enable_stages", "cask_timing_read",
-           "cask_probe_issue", "cask_probe_copy"]
+           "cask_probe_issue", "cask_probe_copy", "cask_probe_read"]
 STAGES = ["score_rows", "score_cols", "select", "index_roles", "similarity", "gather", "emit"]
 
 
@@ -159,6 +159,7 @@ def load():
             "cask_timing_read": (C.c_int, [vp, vp]),
             "cask_probe_issue": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]),
             "cask_probe_copy": (C.c_int, [vp, vp, sz, vp]),
+            "cask_probe_read": (C.c_int, [vp, sz, vp, C.c_int, vp]),
         }
         assert set(sigs) == set(EXPORTS)
         for name, (res, args) in sigs.items():
@@ -475,3 +476,25 @@ def probe_copy(n_bytes: int = 1 << 30, reps: int = 5) -> dict:
     ms = e0.elapsed_time(e1) / reps
     ok = bool(torch.equal(src[:4096], dst[:4096]) and torch.equal(src[-4096:], dst[-4096:]))
     return dict(ms=ms, gbs=2.0 * n_bytes / (ms * 1e-3) / 1e9, bytes=n_bytes, verified=ok)
+
+
+def probe_read(n_bytes: int = 1 << 30, blocks: int = 512, reps: int = 5) -> dict:
+    """cask_probe_read timed with events: GB/s of a read-only stream."""
+    dev = torch.device("cuda", torch.cuda.current_device())
+    src = torch.empty(n_bytes, dtype=torch.uint8, device=dev).random_(0, 256)
+    sink = torch.empty(blocks * 256, dtype=torch.int32, device=dev)
+    lib = load()
+
+    def run():
+        rc = lib.cask_probe_read(_dptr(src), n_bytes, _dptr(sink), blocks, _stream())
+        if rc:
+            raise CaskError("cask_probe_read", rc)
+    run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    return dict(ms=ms, gbs=n_bytes / (ms * 1e-3) / 1e9, bytes=n_bytes, blocks=blocks)

@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(
-          krsrc, lane * 16, (int)((unsigned)(r0 + 4 * j) * (unsigned)kRowBytes), 0);
+          krsrc, lane * 16, (int)((unsigned)(r0 + 4 * j) * (unsigned)kRowBytes), 2);  // nt: a stream read once
       d[j] = make_uint4(v[0], v[1], v[2], v[3]);
     }
   };

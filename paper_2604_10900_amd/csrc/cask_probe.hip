@@ -13,6 +13,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // KIND 0: MFMA alone; 1: MFMA + vector epilogue of two logits; 2: vector epilogue alone;
 // 3: as 1, with the MFMA's first operand read from LDS at the sweeps' rate (one 16-byte read per
@@ -90,6 +91,27 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict
   for (; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Read-only stream: every thread keeps eight 16-byte loads in flight and folds what it reads
+// into one word (written once at the end so that the loads cannot be dropped).
+__global__ __launch_bounds__(256) void read_probe_kernel(const u32x4* __restrict__ src, size_t n16,
+                                                         uint32_t* __restrict__ sink) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  uint32_t acc = 0;
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    u32x4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(src + i + j * stride);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+  }
+  for (; i < n16; i += stride) {
+    const u32x4 v = src[i];
+    acc ^= v.x ^ v.y ^ v.z ^ v.w;
+  }
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = acc;
+}
+
 }  // namespace
 }  // namespace cask
 
@@ -118,6 +140,14 @@ int cask_probe_copy(const void* src, void* dst, size_t bytes, void* hip_stream) 
   if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) != 0) return CASK_EINVAL;
   copy_probe_kernel<<<dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(
       static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16);
+  return hipGetLastError() == hipSuccess ? CASK_OK : CASK_EDEVICE;
+}
+
+int cask_probe_read(const void* src, size_t bytes, uint32_t* sink, int blocks, void* hip_stream) {
+  if (!src || !sink || bytes == 0 || (bytes & 15u) != 0 || blocks < 1 || blocks > 65536) return CASK_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(src) & 15u) != 0) return CASK_EINVAL;
+  read_probe_kernel<<<dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(
+      static_cast<const u32x4*>(src), bytes / 16, sink);
   return hipGetLastError() == hipSuccess ? CASK_OK : CASK_EDEVICE;
 }
 

@@ -128,9 +128,12 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
 // the exp2 epilogue of the tile before it, so the matrix cores and the vector ALU of a wave
 // run at the same time; the epilogue of a stage's last tile rides on the next stage's first
 // chain.  The epilogue is exactly three vector instructions per logit:
-//   sweep A  fma, exp2, add: the running maximum is lazy -- exp2 is taken against a per-lane
-//            reference that is only raised when a tile's sum threatens fp32 range (one test
-//            per tile); exact, because (reference, sum) pairs combine exactly;
+//   sweep A  fma, exp2, add: no running maximum in the loop -- exp2 is taken against a per-lane
+//            reference (the first logit of the lane's row), which is exact as long as the sum
+//            stays finite, because (reference, sum) pairs combine exactly.  A sum that left the
+//            fp32 range (a logit more than ~128 binary orders above the reference) shows as
+//            inf at the end; the wave then recomputes its share with a true running maximum,
+//            operands straight from memory (rare, slow, exact);
 //   sweep B  fma, exp2, add: the fma adds -L_row, read from LDS next to the stage's rows (a lane's
 //            16 rows of a tile are four float4 reads).
 // Stages that touch masked entries (causal tail, ragged end, keys inside the window) take a
@@ -312,7 +315,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     first_row[ct] = (MODE == 1 && kp.causal) ? max(0, (res_row[ct] - (N - W)) * Gq) : 0;
 
   // ---- epilogues
-  float tsum = 0.f;  // sweep A: sum of the tile in flight
   // Masked variant (tag true): a logit is dropped by one comparison of its stream-row offset
   // inside the tile (a constant) with `d`, the lane's limit relative to the tile:
   //   sweep A: hidden iff offset > d, d = (last key the lane's row sees) - first row of the tile - 4 h
@@ -331,11 +333,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         x0 = o0 > d ? kNegInf : x0;
         x1 = o1 > d ? kNegInf : x1;
       }
-      tsum += fast_exp2(__builtin_fmaf(x0, c, nm));
-      tsum += fast_exp2(__builtin_fmaf(x1, c, nm));
+      l_run[ct] += fast_exp2(__builtin_fmaf(x0, c, nm));
+      l_run[ct] += fast_exp2(__builtin_fmaf(x1, c, nm));
       // pin the partial sum here: without it the optimiser is free to sink these pieces out
       // of the MFMA chain they are meant to overlap with
-      asm volatile("" : "+v"(tsum));
+      asm volatile("" : "+v"(l_run[ct]));
     } else {
       float y0 = __builtin_fmaf(acc[2 * i], c, nl[2 * i]), y1 = __builtin_fmaf(acc[2 * i + 1], c, nl[2 * i + 1]);
       if (kMasked) {
@@ -359,28 +361,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     for (int r = 0; r < 16; ++r) sum += fast_exp2(__builtin_fmaf(acc[r], c, nm));
     l_run[ct] = l_run[ct] * fast_exp2(m_ref[ct] + nm) + sum;
     m_ref[ct] = m_new;
-  };
-  auto finish_fast = [&](auto masked, const f32x16& acc, int ct, int d) {  // sweep A: bank the tile sum, guard the range
-    constexpr bool kMasked = decltype(masked)::value;
-    if (kRowPass) {
-      const bool bad = !(tsum < 0x1p100f);
-      if (__builtin_amdgcn_ballot_w64(bad) != 0ull) {
-        if (bad) {
-          f32x16 am = acc;
-          if (kMasked) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-              if ((r >> 2) * 8 + (r & 3) > d) am[r] = kNegInf;
-          }
-          exact_update(am, ct);
-        } else {
-          l_run[ct] += tsum;
-        }
-      } else {
-        l_run[ct] += tsum;
-      }
-      tsum = 0.f;
-    }
   };
   auto slow_tile = [&](f32x16& acc, const float (&nl)[16], int ct, int trow0) {
     if (kRowPass) {
@@ -422,13 +402,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
                     : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct_new][ks], acc_new, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
-    finish_fast(masked, acc_old, ct_old, d);
   };
   auto drain = [&](auto masked, const f32x16& acc_old, const float (&nl_old)[16], int ct_old, int trow_old) {
     const int d = mask_d(ct_old, trow_old);
 #pragma unroll
     for (int i = 0; i < 8; ++i) piece(masked, acc_old, nl_old, ct_old, i, d);
-    finish_fast(masked, acc_old, ct_old, d);
   };
 
   // ---- main loop over ring stages
@@ -507,9 +485,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     load_a(a0, slot_of(from), 0);
     load_nl(nl0, slot_of(from), 0);
     if (kRowPass && !kMasked && from == 0) {
-      // Nothing seen yet: the first logit of the lane's own row is a safe reference.  Too low
-      // is caught by the range guard of the fast epilogue; too high only means every other
-      // term is negligible next to this one, which is itself part of the sum.
+      // Nothing seen yet: the first logit of the lane's own row is the reference.  Too low shows
+      // as an infinite sum at the end and sends the wave through the exact recomputation; too
+      // high only means every other term is negligible next to this one, which is itself part
+      // of the sum.
       chain(acc1, a0, 1);
       m_ref[1] = acc1[0] * c;
       chain(acc0, a0, 0);
@@ -602,6 +581,39 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   for (; it < n_stages; ++it) {
     stage_sync(it);
     slow_stage(it);
+  }
+  if (kRowPass && wave_live) {
+    // Range check of the fast epilogue, once per wave: a finite sum is exact.
+    const bool bad = !(l_run[0] < __builtin_inff()) || !(l_run[1] < __builtin_inff());
+    if (__builtin_amdgcn_ballot_w64(bad) != 0ull) {
+      // Recompute this wave's statistics with a true running maximum.  The ring belongs to the
+      // whole workgroup, so the stream rows come straight from memory (same bounds-checked
+      // descriptor: rows past the end read as zero and are masked).
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) {
+        m_ref[ct] = kNegInf;
+        l_run[ct] = 0.f;
+      }
+      for (int stg = 0; stg < n_stages; ++stg) {
+        for (int rt = 0; rt < 2; ++rt) {
+          const int trow0 = s_begin + stg * kStageRows + rt * 32;
+          if (trow0 >= s_end || (half_block && rt != rt_own)) continue;
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (trow0 + c32) * kRowBytes + h * 16, ks * 32, 0);
+            a0[ks] = __builtin_bit_cast(bf16x8, v);
+          }
+#pragma unroll
+          for (int ct = 0; ct < 2; ++ct) {
+            chain(acc0, a0, ct);
+            slow_tile(acc0, nl0, ct, trow0);
+          }
+        }
+      }
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct)
+        if (m_ref[ct] == kNegInf) m_ref[ct] = 0.f;
+    }
   }
   // loads issued past the last stage may still be landing in LDS: let them finish before the
   // workgroup's LDS can be handed to another one

@@ -699,14 +699,20 @@ def test_ragged_batch_llama_shape():
     _note(parity.full_check(c, parity.params_of(w)))
 
 
-def test_score_with_steep_logit_ramps():
-    """Logits that climb (or fall) by hundreds of octaves along the cache: the running
-    reference of the row statistics has to be raised many times without losing mass."""
-    d, Wn, G = 128, 16, 3
+@pytest.mark.parametrize("Wn,G,N,path", [(16, 3, 6000, "two_launches"), (64, 7, 6000, "two_launches"),
+                                         (128, 7, 3000, "two_launches"), (128, 4, 5000, "one_launch_long"),
+                                         (64, 2, 5000, "one_launch_long"), (32, 7, 900, "one_launch_short")])
+def test_score_with_steep_logit_ramps(Wn, G, N, path):
+    """Logits that climb (or fall) by hundreds of octaves along the cache.  Climbing, the sums
+    of the row statistics leave the fp32 range against their first-logit reference and the
+    waves recompute their share with a running maximum (full row blocks, a half block, both
+    one-launch forms of the scoring); falling, every later term underflows next to the first."""
+    d = 128
     rng = np.random.default_rng(4)
-    N = 6000
     q = rng.standard_normal(d).astype(np.float32)
     q /= np.linalg.norm(q)
+    flags = {"two_launches": cask.binding.PATH_NO_FUSED_SWEEPS | cask.binding.PATH_NO_FUSED_SCORE,
+             "one_launch_long": cask.binding.PATH_FORCE_FUSED_SWEEPS, "one_launch_short": 0}[path]
     for direction in (+1, -1):
         ramp = np.linspace(0.0, 1.0, N, dtype=np.float32)
         if direction < 0:
@@ -717,14 +723,16 @@ def test_score_with_steep_logit_ramps():
         c = dict(K=torch.from_numpy(K).to(torch.bfloat16), V=torch.from_numpy(K).to(torch.bfloat16),
                  Q=torch.from_numpy(Qm).to(torch.bfloat16).reshape(1, Wn, G, d),
                  row_off=torch.tensor([0, N], dtype=torch.int64), prefix_len=torch.tensor([0], dtype=torch.int32))
-        p = cask.Params(dtype=cask.BF16, head_dim=d, q_per_kv=G, window=Wn, budget=64)
+        p = cask.Params(dtype=cask.BF16, head_dim=d, q_per_kv=G, window=Wn, budget=Wn + 100, path_flags=flags)
         row_off, prefix_len, Kb, Vb, Qb = parity.host_arrays(c)
         want = ref.score(parity.ref_params(p), row_off, Kb, Qb)
-        got = cask.score(parity.to_device(c, p))
+        b = parity.to_device(c, p)
+        # (short units score inside the event: the whole event is run and its scores taken)
+        got = cask.compress(b).scores if path == "one_launch_short" else cask.score(b)
         torch.cuda.synchronize()
         assert np.isfinite(got.cpu().numpy()).all()
         err = parity.check_scores(got.cpu().numpy(), want, row_off)
-        _note((direction, "max score", float(want.max()), "rel err", err))
+        _note((path, Wn, G, direction, "max score", float(want.max()), "rel err", err))
 
 
 # ------------------------------------------------------------------ selection under ties
