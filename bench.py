@@ -58,6 +58,9 @@ def parse():
     ap.add_argument("--sim-threshold", type=float, default=0.9,
                     help="cask_params.sim_threshold; the headline is quoted at the default 0.9, -1 makes "
                          "every donor fold (the merge-heavy variant that loads the fold path)")
+    ap.add_argument("--probe-only", action="store_true",
+                    help="run only the library's probe loops (every instruction mix at 1-3 waves per SIMD, the "
+                         "copy and the read stream), print them as one JSON object and exit")
     ap.add_argument("--no-pinned-peaks", action="store_true",
                     help="skip the two probe loops (MFMA chain, streaming copy) that pin this box's ceilings")
     ap.add_argument("--no-stage-events", action="store_true",
@@ -98,6 +101,22 @@ def main():
         __graft_entry__.build()
     cask.load()
     dev = torch.device("cuda:0")
+    if args.probe_only:
+        names = {0: "mfma alone", 1: "mfma + softmax epilogue of two logits (fma, fma, exp2, exp2, add, add)",
+                 2: "the six vector instructions alone", 3: "as 1, first operand read from LDS at the sweeps' rate",
+                 4: "as 1, epilogue in dependent order with one running sum"}
+        rows = []
+        for kind in (0, 1, 2, 3, 4):
+            for wps in (1, 2, 3):
+                r = binding.probe_issue(kind, waves_per_simd=wps, blocks=256, iters=24000 // wps)
+                rows.append({"kind": kind, "what": names[kind], "waves_per_simd": wps,
+                             **{k: round(v, 3) for k, v in r.items()}})
+        mem = {"copy_1GiB": binding.probe_copy(1 << 30), "copy_4GiB": binding.probe_copy(4 << 30),
+               "read_1GiB": binding.probe_read(1 << 30), "read_4GiB": binding.probe_read(4 << 30)}
+        print(json.dumps({"probe_issue": rows, "probe_memory": mem,
+                          "note": "256 workgroups (one per compute unit); TFLOP/s counts the MFMA flop; cycles per unit "
+                                  "and SIMD = time x shader clock / units; copy GB/s counts bytes read plus written"}))
+        return
     steady = args.workload.endswith("ss")
     w = caches.WORKLOADS[args.workload[:-2] if steady else args.workload]
     if steady:

@@ -325,7 +325,8 @@ int cask_timing_read(float* stage_ms, int* n_calls);
  * cask_probe_issue: register-only loops of the scoring sweeps' instruction mix.  One unit = one
  * v_mfma_f32_32x32x16_bf16 (32 768 flop, 32 matrix-pipe cycles), kind 0; the same followed by the
  * vector epilogue of two logits (fma, exp2, add each), kind 1; the vector part alone, kind 2;
- * kind 1 with the MFMA's first operand read from LDS as the sweeps read theirs, kind 3.
+ * kind 1 with the MFMA's first operand read from LDS as the sweeps read theirs, kind 3; kind 1
+ * with the six vector instructions in dependent order on one running sum, kind 4.
  * `blocks` workgroups of 4 * waves_per_simd waves (one compute unit's SIMDs each get
  * waves_per_simd of them) run iters * 8 units per wave.
  *   operands  DEVICE, 32 KB of random bf16 values, 16-byte aligned (operand bits set the power)

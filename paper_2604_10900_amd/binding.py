@@ -436,7 +436,7 @@ def probe_issue(kind: int, waves_per_simd: int = 2, blocks: int = 256, iters: in
         rc = lib.cask_probe_issue(kind, waves_per_simd, blocks, n, _dptr(ops), _dptr(cyc), _dptr(sink), _stream())
         if rc:
             raise CaskError("cask_probe_issue", rc)
-    run(max(iters // 4, 1))
+    run(iters)      # warm-up of the same length: the clock settles while it runs
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     run(iters)

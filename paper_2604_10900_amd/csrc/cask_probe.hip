@@ -55,6 +55,17 @@ __global__ __launch_bounds__(1024) void issue_probe_kernel(const uint4* __restri
         // the sweeps' epilogue for two logits, written as the six instructions themselves so
         // that the optimiser cannot hoist or merge any of them: fma, fma, exp2, exp2, add, add
         float t, u;
+        if (KIND == 4) {
+          // the same six instructions in dependent order with one running sum
+          asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(t) : "v"(x[2 * i]), "v"(c), "v"(nm));
+          asm volatile("v_exp_f32 %0, %0" : "+v"(t));
+          asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u) : "v"(x[2 * i + 1]), "v"(c), "v"(nm));
+          asm volatile("v_exp_f32 %0, %0" : "+v"(u));
+          asm volatile("v_add_f32 %0, %0, %1" : "+v"(s0) : "v"(t));
+          asm volatile("v_add_f32 %0, %0, %1" : "+v"(s0) : "v"(u));
+          __builtin_amdgcn_sched_barrier(0);
+          continue;
+        }
         asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(t) : "v"(x[2 * i]), "v"(c), "v"(nm));
         asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(u) : "v"(x[2 * i + 1]), "v"(c), "v"(nm));
         asm volatile("v_exp_f32 %0, %0" : "+v"(t));
@@ -121,7 +132,7 @@ extern "C" {
 
 int cask_probe_issue(int kind, int waves_per_simd, int blocks, int iters, const void* operands,
                      uint64_t* cycles, float* sink, void* hip_stream) {
-  if (kind < 0 || kind > 3 || waves_per_simd < 1 || waves_per_simd > 4 || blocks < 1 || blocks > 65536 ||
+  if (kind < 0 || kind > 4 || waves_per_simd < 1 || waves_per_simd > 4 || blocks < 1 || blocks > 65536 ||
       iters < 1 || iters > (1 << 24) || !operands || !cycles || !sink)
     return CASK_EINVAL;
   if ((reinterpret_cast<uintptr_t>(operands) & 15u) != 0) return CASK_EINVAL;
@@ -131,7 +142,8 @@ int cask_probe_issue(int kind, int waves_per_simd, int blocks, int iters, const 
   if (kind == 0) issue_probe_kernel<0><<<grid, block, 0, st>>>(ops, iters, cycles, sink);
   else if (kind == 1) issue_probe_kernel<1><<<grid, block, 0, st>>>(ops, iters, cycles, sink);
   else if (kind == 2) issue_probe_kernel<2><<<grid, block, 0, st>>>(ops, iters, cycles, sink);
-  else issue_probe_kernel<3><<<grid, block, 0, st>>>(ops, iters, cycles, sink);
+  else if (kind == 3) issue_probe_kernel<3><<<grid, block, 0, st>>>(ops, iters, cycles, sink);
+  else issue_probe_kernel<4><<<grid, block, 0, st>>>(ops, iters, cycles, sink);
   return hipGetLastError() == hipSuccess ? CASK_OK : CASK_EDEVICE;
 }
 

@@ -176,18 +176,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   const uint16_t* str_ptr;
   int res_base, res_limit, s_begin, s_end;  // resident rows [res_base, ..), stream rows [s_begin, s_end)
   int split = 0;
-  bool half_block = false;
   if (kRowPass) {
     const int qb = tile / n_splits;
     split = tile % n_splits;
     res_base = qb * kResRows;
     if (res_base >= Mq) return;
-    // A last row block of at most 128 window rows (W*G = 896: three and a half blocks) would
-    // leave two of the four waves without rows.  Such a block is shared out differently: waves
-    // w and w + 2 hold the same 64 rows and take the first and the second 32 keys of every
-    // stage, so all four waves work, a stage costs the workgroup half the time, and the two
-    // partial statistics of a row are combined through LDS at the end.
-    half_block = MODE == 0 && Mq - res_base <= kResRows / 2;
     res_ptr = Qu;
     res_limit = Mq;
     str_ptr = Ku;
@@ -263,13 +256,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // ring's first loads are on their way so that the two latencies overlap.
   const __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(res_ptr), 0, res_limit * kRowBytes, 0x00020000);
-  const int wrow = half_block ? (wv & 1) : wv;  // the wave's 64-row group of the resident block
-  const int rt_own = wv >> 1;                    // half block: the 32-row tile of every stage this wave takes
   bf16x8 bres[2][NK];
   int res_row[2];
 #pragma unroll
   for (int ct = 0; ct < 2; ++ct) {
-    const int r = res_base + wrow * 64 + ct * 32 + c32;
+    const int r = res_base + wv * 64 + ct * 32 + c32;
     res_row[ct] = r;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
@@ -278,7 +269,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
   }
   // a wave whose resident rows are all past the end only helps with loads and barriers
-  const bool wave_live = res_base + wrow * 64 < res_limit;
+  const bool wave_live = res_base + wv * 64 < res_limit;
 
   // A-operand rows of this lane inside a stage: row rt * 32 + c32 -> group, row-in-group
   const int a_off = (c32 >> 2) * kGroupPitch + (c32 & 3) * 16 + h * 64;
@@ -439,7 +430,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) {
       const int trow0 = stage_base + rt * 32;
-      if (trow0 >= s_end || (half_block && rt != rt_own)) continue;
+      if (trow0 >= s_end) continue;
       load_a(a0, cur, rt);
       load_nl(nl0, cur, rt);
 #pragma unroll
@@ -512,41 +503,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
     drain(masked, acc1, nl1, 1, s_begin + (to - 1) * kStageRows + 32);
   };
-  // The same for a half block: two tiles per stage (the wave's own tile row, both resident
-  // column tiles), two stages per trip so that the operand registers alternate statically.
-  auto pipelined_half = [&](auto masked, int from, int to) {
-    constexpr bool kMasked = decltype(masked)::value;
-    const int ro = rt_own * 32;
-    stage_sync(from);
-    load_a(a0, slot_of(from), rt_own);
-    if (!kMasked && from == 0) {
-      chain(acc1, a0, 1);
-      m_ref[1] = acc1[0] * c;
-      chain(acc0, a0, 0);
-      m_ref[0] = acc0[0] * c;
-    } else {
-      chain(acc0, a0, 0);
-    }
-    for (int it = from;; it += 2) {
-      const int base = s_begin + it * kStageRows + ro;
-      load_a(a1, slot_of(it + 1), rt_own);  // stage it + 1 has landed with stage it
-      fused(masked, acc1, a0, 1, acc0, nl0, 0, base);
-      if (it + 1 >= to) {
-        drain(masked, acc1, nl0, 1, base);
-        break;
-      }
-      stage_sync(it + 1);
-      fused(masked, acc0, a1, 0, acc1, nl0, 1, base);
-      load_a(a0, slot_of(it + 2), rt_own);
-      fused(masked, acc1, a1, 1, acc0, nl0, 0, base + kStageRows);
-      if (it + 2 >= to) {
-        drain(masked, acc1, nl0, 1, base + kStageRows);
-        break;
-      }
-      stage_sync(it + 2);
-      fused(masked, acc0, a0, 0, acc1, nl0, 1, base + kStageRows);
-    }
-  };
   const std::integral_constant<bool, false> clean_tag;
   const std::integral_constant<bool, true> masked_tag;
 
@@ -561,22 +517,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       slow_stage(it);
     }
   }
-  if (MODE == 0 && half_block) {
-    if (f1 > f0) pipelined_half(clean_tag, f0, f1);
-    it = f1;
-    if (f1 > 0 && n_stages > f1) {
-      pipelined_half(masked_tag, f1, n_stages);
-      it = n_stages;
-    }
-  } else {
-    if (f1 > f0) pipelined(clean_tag, f0, f1);
-    it = f1;
-    if (kRowPass && f1 > 0 && n_stages > f1) {
-      // the tail (causal, ragged end) after at least one clean stage: the reference is set, so
-      // the masked epilogue can take it
-      pipelined(masked_tag, f1, n_stages);
-      it = n_stages;
-    }
+  if (f1 > f0) pipelined(clean_tag, f0, f1);
+  it = f1;
+  if (kRowPass && f1 > 0 && n_stages > f1) {
+    // the tail (causal, ragged end) after at least one clean stage: the reference is set, so
+    // the masked epilogue can take it
+    pipelined(masked_tag, f1, n_stages);
+    it = n_stages;
   }
   for (; it < n_stages; ++it) {
     stage_sync(it);
@@ -597,7 +544,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       for (int stg = 0; stg < n_stages; ++stg) {
         for (int rt = 0; rt < 2; ++rt) {
           const int trow0 = s_begin + stg * kStageRows + rt * 32;
-          if (trow0 >= s_end || (half_block && rt != rt_own)) continue;
+          if (trow0 >= s_end) continue;
 #pragma unroll
           for (int ks = 0; ks < 8; ++ks) {
             const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (trow0 + c32) * kRowBytes + h * 16, ks * 32, 0);
@@ -780,23 +727,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
   } else if (MODE == 0) {
     float2* part = rowstat + (size_t)unit * n_splits * mq_pad;
-    if (half_block) {
-      // waves 2 and 3 hand the statistics of their key halves to waves 0 and 1 (same rows, same
-      // lanes) through an LDS area behind the ring (the ring itself may still receive the zero
-      // fill of other waves' loads past the last stage)
-      float2* xch = reinterpret_cast<float2*>(smem + kDepth * kStageBytes);
-      if (wv >= 2) {
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct) xch[((wv - 2) * 2 + ct) * 64 + lane] = make_float2(m_ref[ct], l_run[ct]);
-      }
-      __syncthreads();
-      if (wv >= 2) return;
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        const float2 o = xch[(wv * 2 + ct) * 64 + lane];
-        ml_combine(m_ref[ct], l_run[ct], o.x, o.y);
-      }
-    }
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct) {
       const float m2 = __shfl_xor(m_ref[ct], 32, 64);
@@ -946,8 +876,8 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   const int units8 = (b.n_units + 7) / 8 * 8;
   const uint16_t* K = static_cast<const uint16_t*>(b.K);
   const uint16_t* Q = static_cast<const uint16_t*>(b.Q);
-  const size_t ldsB = (size_t)kDepth * kStageBytes;
-  const size_t ldsA = ldsB + 4 * 64 * sizeof(float2);  // + the exchange area of a half row block
+  const size_t ldsA = (size_t)kDepth * kStageBytes;
+  const size_t ldsB = ldsA;
   static LdsLimitOnce limA, limB;
   hipError_t e = limA.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<0>), 160 * 1024);
   if (e == hipSuccess) e = limB.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<1>), 160 * 1024);
