@@ -306,6 +306,16 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     first_row[ct] = (MODE == 1 && kp.causal) ? max(0, (res_row[ct] - (N - W)) * Gq) : 0;
 
   // ---- epilogues
+  // sweep A: a tile's 16 terms are summed on their own and banked into the lane's running sum
+  // once per tile, so the long sum over a unit's keys has N / 32 addends, not N / 2 (the rounding
+  // error of a single fp32 running sum would grow with the unit's length)
+  float tsum = 0.f;
+  auto bank_tile = [&](int ct) {
+    if (kRowPass) {
+      l_run[ct] += tsum;
+      tsum = 0.f;
+    }
+  };
   // Masked variant (tag true): a logit is dropped by one comparison of its stream-row offset
   // inside the tile (a constant) with `d`, the lane's limit relative to the tile:
   //   sweep A: hidden iff offset > d, d = (last key the lane's row sees) - first row of the tile - 4 h
@@ -324,11 +334,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         x0 = o0 > d ? kNegInf : x0;
         x1 = o1 > d ? kNegInf : x1;
       }
-      l_run[ct] += fast_exp2(__builtin_fmaf(x0, c, nm));
-      l_run[ct] += fast_exp2(__builtin_fmaf(x1, c, nm));
+      tsum += fast_exp2(__builtin_fmaf(x0, c, nm));
+      tsum += fast_exp2(__builtin_fmaf(x1, c, nm));
       // pin the partial sum here: without it the optimiser is free to sink these pieces out
       // of the MFMA chain they are meant to overlap with
-      asm volatile("" : "+v"(l_run[ct]));
+      asm volatile("" : "+v"(tsum));
     } else {
       float y0 = __builtin_fmaf(acc[2 * i], c, nl[2 * i]), y1 = __builtin_fmaf(acc[2 * i + 1], c, nl[2 * i + 1]);
       if (kMasked) {
@@ -393,11 +403,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
                     : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct_new][ks], acc_new, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
+    bank_tile(ct_old);
   };
   auto drain = [&](auto masked, const f32x16& acc_old, const float (&nl_old)[16], int ct_old, int trow_old) {
     const int d = mask_d(ct_old, trow_old);
 #pragma unroll
     for (int i = 0; i < 8; ++i) piece(masked, acc_old, nl_old, ct_old, i, d);
+    bank_tile(ct_old);
   };
 
   // ---- main loop over ring stages

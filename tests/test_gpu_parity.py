@@ -121,6 +121,22 @@ def test_both_sweeps_in_one_launch_for_long_units(G, Wn, causal):
     _note(st)
 
 
+def test_score_error_does_not_grow_with_unit_length():
+    """A 48k-row unit: the row statistics sum tens of thousands of terms per window row.  Summed
+    tile by tile the error stays at a few 1e-6 of the largest score (a single fp32 running sum
+    per lane would be ten times off that and keep growing with the length); the bar itself is 1e-4."""
+    w = caches.scaled(W["cfg2"], n_layers=1, n_kv_heads=1, prefix=512, decode=48000 - 512)
+    c = caches.make(w, seed=23)
+    p = parity.params_of(w)
+    row_off, prefix_len, K, V, Q = parity.host_arrays(c)
+    want = ref.score(parity.ref_params(p), row_off, K, Q, n_threads=8)
+    got = cask.score(parity.to_device(c, p))
+    torch.cuda.synchronize()
+    err = parity.check_scores(got.cpu().numpy(), want, row_off)
+    _note(("48k rows: score error / max", err))
+    assert err <= 5e-6
+
+
 def test_nonpositive_softmax_scale_is_the_default_scale():
     """softmax_scale <= 0 means 1/sqrt(d) in cask_score and in cask_attend, as in the oracle."""
     dev = torch.device("cuda:0")
