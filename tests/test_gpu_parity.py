@@ -1230,6 +1230,30 @@ def test_argument_errors_and_empty_batch():
     assert out.out_len.numel() == 0
 
 
+def test_probe_loops_run_and_report_sane_figures():
+    """The measurement aids: the copy probe copies (whole buffer, odd multiple of 16 bytes), the
+    read probe and the issue probes run, and their figures are in a sane range for the part."""
+    dev = torch.device("cuda:0")
+    lib = cask.load()
+    n = (1 << 20) * 16 + 48
+    src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 256)
+    dst = torch.zeros_like(src)
+    st = torch.cuda.current_stream().cuda_stream
+    assert lib.cask_probe_copy(src.data_ptr(), dst.data_ptr(), n, st) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    assert lib.cask_probe_copy(src.data_ptr(), dst.data_ptr(), n - 8, st) == cask.binding.EINVAL   # not a multiple of 16
+    assert lib.cask_probe_copy(None, dst.data_ptr(), n, st) == cask.binding.EINVAL
+    r = cask.binding.probe_read(1 << 28, blocks=512, reps=2)
+    assert 500.0 < r["gbs"] < 8000.0, r
+    for kind in (0, 1, 2, 3, 4):
+        p = cask.binding.probe_issue(kind, waves_per_simd=2, blocks=256, iters=500)
+        assert 0.8 < p["ghz"] < 2.6 and 25.0 < p["cycles_per_unit"] < 120.0, (kind, p)
+        if kind != 2:
+            assert 200.0 < p["tflops"] < 2500.0, (kind, p)
+    assert lib.cask_probe_issue(7, 2, 256, 10, src.data_ptr(), dst.data_ptr(), dst.data_ptr(), st) == cask.binding.EINVAL
+
+
 # ------------------------------------------------------------------ full benchmark sizes
 
 def _full_size(name, sample_units, seed=caches.BASE_SEED, layers=None):
