@@ -11,6 +11,8 @@
 // index_roles then walks the roles in index order to give every kept row its output slot
 // (ascending source order, representatives at their seed's position: |R| <= B with C subset
 // of R, Section 2.3) and every seed its ordinal.
+#include <type_traits>
+
 #include "cask_common.h"
 
 namespace cask {
@@ -40,26 +42,32 @@ struct Query3 {
   int lo[3], hi[3], k[3];
 };
 
-constexpr int kSelPer = 16;                       // keys a thread holds at a time
-constexpr int kSelChunk = kSelThreads * kSelPer;  // rows per chunk
+// The number of keys a thread holds at a time is the template parameter PER of the selection (a
+// chunk is PER * 1024 rows).  The straight-line code over a thread's keys costs what PER says
+// whatever the unit's length, and a unit that fits one chunk keeps its keys in registers across
+// the four passes, so the launcher takes the smallest instance that covers the longest unit.
+constexpr int kSelPerDefault = 16;
 
-// keys of rows base + e * kSelThreads + tid, e < kSelPer (0 past `end`): all loads of the
+// keys of rows base + e * kSelThreads + tid, e < PER (0 past `end`): all loads of the
 // chunk are in flight together
-__device__ inline void load_keys(const float* __restrict__ s, int base, int end, uint32_t (&key)[kSelPer]) {
-  float v[kSelPer];
+template <int PER>
+__device__ inline void load_keys(const float* __restrict__ s, int base, int end, uint32_t (&key)[PER]) {
+  float v[PER];
 #pragma unroll
-  for (int e = 0; e < kSelPer; ++e) {
+  for (int e = 0; e < PER; ++e) {
     const int i = base + e * kSelThreads + (int)threadIdx.x;
     v[e] = i < end ? s[i] : 0.f;
   }
 #pragma unroll
-  for (int e = 0; e < kSelPer; ++e) key[e] = score_key(v[e]);
+  for (int e = 0; e < PER; ++e) key[e] = score_key(v[e]);
 }
 
 // `key` holds the chunk starting at lo_all on return when the ranges fit one chunk
 // (hi_all - lo_all <= kSelChunk), so the caller can mark the rows without reading them again.
+template <int PER>
 __device__ void radix_select3(const float* __restrict__ s, const Query3& q, int lo_all, int hi_all,
-                              Kth (&out)[3], uint32_t (&key)[kSelPer], int* hist, int* bcast) {
+                              Kth (&out)[3], uint32_t (&key)[PER], int* hist, int* bcast) {
+  constexpr int kSelChunk = kSelThreads * PER;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   uint32_t prefix[3] = {0, 0, 0};
   uint32_t mask = 0;
@@ -69,11 +77,11 @@ __device__ void radix_select3(const float* __restrict__ s, const Query3& q, int 
   // single chunk: bit j of live[e] says that row e of this thread still competes in query j
   // (inside its range, all digits so far equal to the chosen ones), so later passes skip most
   // rows with one test
-  uint32_t live[kSelPer];
+  uint32_t live[PER];
   if (single) {
-    load_keys(s, lo_all, hi_all, key);
+    load_keys<PER>(s, lo_all, hi_all, key);
 #pragma unroll
-    for (int e = 0; e < kSelPer; ++e) {
+    for (int e = 0; e < PER; ++e) {
       const int i = lo_all + e * kSelThreads + tid;
       live[e] = 0;
 #pragma unroll
@@ -97,7 +105,7 @@ __device__ void radix_select3(const float* __restrict__ s, const Query3& q, int 
     const bool share = same12 && pass == 0;
     if (single) {
 #pragma unroll
-      for (int e = 0; e < kSelPer; ++e) {
+      for (int e = 0; e < PER; ++e) {
         uint32_t lv = live[e];
         if (share) lv &= ~4u;
         if (lv != 0u) {
@@ -110,9 +118,9 @@ __device__ void radix_select3(const float* __restrict__ s, const Query3& q, int 
       }
     } else {
       for (int base = lo_all; base < hi_all; base += kSelChunk) {
-        load_keys(s, base, hi_all, key);
+        load_keys<PER>(s, base, hi_all, key);
 #pragma unroll
-        for (int e = 0; e < kSelPer; ++e) {
+        for (int e = 0; e < PER; ++e) {
           const int i = base + e * kSelThreads + tid;
           const uint32_t digit = (key[e] >> shift) & 255u;
 #pragma unroll
@@ -171,7 +179,7 @@ __device__ void radix_select3(const float* __restrict__ s, const Query3& q, int 
     mask |= 0xFFu << shift;
     if (single) {
 #pragma unroll
-      for (int e = 0; e < kSelPer; ++e) {
+      for (int e = 0; e < PER; ++e) {
         if (live[e] != 0u) {
 #pragma unroll
           for (int j = 0; j < 3; ++j)
@@ -284,6 +292,7 @@ __device__ void index_walk(const KParams& kp, int u, int64_t row0, int N, const 
 }
 
 
+template <int PER>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     KParams kp, const int64_t* __restrict__ row_off, const int32_t* __restrict__ prefix_len,
     const float* __restrict__ scores, uint8_t* __restrict__ role, int32_t* __restrict__ status,
@@ -314,8 +323,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   q.lo[0] = 0; q.hi[0] = P; q.k[0] = pre_sel ? pl.p_keep : 0;
   q.lo[1] = P; q.hi[1] = hi; q.k[1] = (dec_sel && C > 0) ? C : 0;
   q.lo[2] = P; q.hi[2] = hi; q.k[2] = (dec_sel && !all_seed && CM > C) ? CM : 0;
+  constexpr int kSelChunk = kSelThreads * PER;
   Kth kth[3];
-  uint32_t key[kSelPer];
+  uint32_t key[PER];
   bool have_keys = false;  // `key` holds rows lo_all + e * kSelThreads + tid
   int lo_all = N, hi_all = 0;
 #pragma unroll
@@ -325,7 +335,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
       hi_all = max(hi_all, q.hi[j]);
     }
   if (hi_all > lo_all) {
-    radix_select3(s, q, lo_all, hi_all, kth, key, hist, bcast);
+    radix_select3<PER>(s, q, lo_all, hi_all, kth, key, hist, bcast);
     have_keys = hi_all - lo_all <= kSelChunk;
   }
   const bool keys_cover_prefix = have_keys && lo_all == 0 && hi_all >= P;
@@ -340,7 +350,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
       if (kt.take_eq == kt.total_eq) {
         if (keys_cover_prefix) {
 #pragma unroll
-          for (int e = 0; e < kSelPer; ++e) {
+          for (int e = 0; e < PER; ++e) {
             const int i = lo_all + e * kSelThreads + tid;
             if (i < P) ro[i] = key[e] >= kt.key ? CASK_ROLE_PREFIX_KEEP : CASK_ROLE_PREFIX_DROP;
           }
@@ -398,7 +408,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
       };
       if (keys_cover_decode) {
 #pragma unroll
-        for (int e = 0; e < kSelPer; ++e) {
+        for (int e = 0; e < PER; ++e) {
           const int i = lo_all + e * kSelThreads + tid;
           if (i >= P && i < hi) mark(i, key[e]);
         }
@@ -486,8 +496,8 @@ __global__ __launch_bounds__(kSelThreads) void mass_diag_kernel(
     q.lo[1] = q.hi[1] = q.k[1] = 0;
     q.lo[2] = q.hi[2] = q.k[2] = 0;
     Kth kth[3];
-    uint32_t key[kSelPer];
-    radix_select3(s, q, 0, N, kth, key, hist, bcast);
+    uint32_t key[kSelPerDefault];
+    radix_select3<kSelPerDefault>(s, q, 0, N, kth, key, hist, bcast);
     kt = kth[0];
   }
   for (int i = tid; i < N; i += kSelThreads) {
@@ -513,11 +523,27 @@ __global__ __launch_bounds__(kSelThreads) void mass_diag_kernel(
 
 }  // namespace
 
+namespace {
+// calls f with the smallest instance whose single chunk covers the longest unit; units beyond
+// the largest instance take the default one and read their keys again in every pass
+template <typename F>
+void with_select_instance(int max_unit_len, F&& f) {
+  const int need = (max_unit_len + kSelThreads - 1) / kSelThreads;
+  if (need <= 4) f(std::integral_constant<int, 4>());
+  else if (need <= 6) f(std::integral_constant<int, 6>());
+  else if (need <= 9) f(std::integral_constant<int, 9>());
+  else if (need <= 12) f(std::integral_constant<int, 12>());
+  else f(std::integral_constant<int, kSelPerDefault>());  // more keys per thread would spill
+}
+}  // namespace
+
 hipError_t launch_select(const KParams& kp, const Batch& b, const float* scores, uint8_t* role,
                          int32_t* status, bool do_prefix, bool do_decode, hipStream_t st) {
-  select_kernel<<<dim3(b.n_units), dim3(kSelThreads), 0, st>>>(
-      kp, b.row_off, b.prefix_len, scores, role, status, do_prefix ? 1 : 0, do_decode ? 1 : 0, 0,
-      nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+  with_select_instance(b.max_unit_len, [&](auto per) {
+    select_kernel<decltype(per)::value><<<dim3(b.n_units), dim3(kSelThreads), 0, st>>>(
+        kp, b.row_off, b.prefix_len, scores, role, status, do_prefix ? 1 : 0, do_decode ? 1 : 0, 0,
+        nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+  });
   return hipGetLastError();
 }
 
@@ -525,9 +551,11 @@ hipError_t launch_select_index(const KParams& kp, const Batch& b, const float* s
                                uint8_t* role, int32_t* status, int32_t* slot_of, int32_t* out_src,
                                int32_t* out_len, int32_t* seed_rows, int32_t* ord_of_slot,
                                int32_t* n_seeds, hipStream_t st) {
-  select_kernel<<<dim3(b.n_units), dim3(kSelThreads), 0, st>>>(
-      kp, b.row_off, b.prefix_len, scores, role, status, 1, 1, 1, slot_of, out_src, out_len,
-      seed_rows, ord_of_slot, n_seeds);
+  with_select_instance(b.max_unit_len, [&](auto per) {
+    select_kernel<decltype(per)::value><<<dim3(b.n_units), dim3(kSelThreads), 0, st>>>(
+        kp, b.row_off, b.prefix_len, scores, role, status, 1, 1, 1, slot_of, out_src, out_len,
+        seed_rows, ord_of_slot, n_seeds);
+  });
   return hipGetLastError();
 }
 
