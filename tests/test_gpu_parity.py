@@ -753,12 +753,15 @@ def test_score_with_steep_logit_ramps(Wn, G, N, path):
 
 # ------------------------------------------------------------------ selection under ties
 
+@pytest.mark.parametrize("longest", [4000, 4097, 9000, 12000, 16384, 20000])
 @pytest.mark.parametrize("quant", [0, 3, 50])
-def test_selection_with_tied_scores(quant):
+def test_selection_with_tied_scores(quant, longest):
     """quant == 0: all scores equal; else scores rounded to `quant` levels so that every
-    rank boundary falls inside a run of equal values."""
+    rank boundary falls inside a run of equal values.  The batch's longest unit picks the
+    selection kernel's instance (4, 6, 9, 12 or 16 keys per thread; beyond 16 384 rows the keys
+    are read again in every pass)."""
     rng = np.random.default_rng(quant)
-    lens = [1500, 2600, 4097]
+    lens = [1500, 2600, longest]
     pref = [300, 1200, 100]
     row_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
     total = int(row_off[-1])
