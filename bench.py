@@ -273,8 +273,8 @@ def main():
             g.replay()
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - tg0) * 1e3 / args.graph_steps
-        step(0)   # leave the outputs of an eager event behind for the checks below
-        torch.cuda.synchronize()
+    step(0)   # leave the outputs of an eager event on the first input copy behind for the checks below
+    torch.cuda.synchronize()
     status = outs.status.cpu().numpy()
     out_len = outs.out_len.cpu().numpy()
 

@@ -3,7 +3,8 @@
 //
 // The softmax normaliser of a row needs all keys before any column can be summed, so the
 // score takes two sweeps of Q.K^T:
-//   sweep A (row statistics)  per window row: running max and sum of exp2 over key splits;
+//   sweep A (row statistics)  per window row and key split: a reference logit and the sum of
+//                             exp2 against it (pairs of splits combine exactly);
 //   sweep B (column mass)     per key: sum over window rows of exp2(logit - L_row).
 // Logits are never stored: recomputing the contraction on the matrix cores is cheaper than
 // writing and re-reading a W*G x N fp32 matrix through HBM.
@@ -136,8 +137,10 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
 //            operands straight from memory (rare, slow, exact);
 //   sweep B  fma, exp2, add: the fma adds -L_row, read from LDS next to the stage's rows (a lane's
 //            16 rows of a tile are four float4 reads).
-// Stages that touch masked entries (causal tail, ragged end, keys inside the window) take a
-// plain, unpipelined path with explicit masks.
+// Stages that touch masked entries (causal tail, ragged end, keys inside the window) run the same
+// pipeline with two more instructions per logit (a compare of the logit's constant row offset
+// with a per-lane limit, a select); only a sweep-A workgroup without a single clean stage, which
+// has no reference logit yet, takes a plain unpipelined path with a true running maximum.
 template <int MODE>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     KParams kp, int n_units, int tiles_per_unit, int n_splits, int split_len, int q_splits, int mq_pad,
