@@ -135,7 +135,8 @@ __device__ void radix_select3(const float* __restrict__ s, const Query3& q, int 
     // wave j: lane l owns digits 255-4l .. 252-4l (descending) of query j (query 2 reads query
     // 1's counts while they are shared); find the digit where the running count from the top
     // reaches `remaining`
-    if (wv < 3 && q.k[wv] > 0) {
+    const int qk_w = wv == 0 ? q.k[0] : (wv == 1 ? q.k[1] : q.k[2]);  // (no indexing by wave: that would put q in memory)
+    if (wv < 3 && qk_w > 0) {
       const int rem = wv == 0 ? remaining[0] : (wv == 1 ? remaining[1] : remaining[2]);
       const int* hq = cur + ((share && wv == 2) ? 1 : wv) * 256 * kHistCopies;
       int h4[4];
@@ -222,64 +223,74 @@ __device__ inline int block_excl_scan(int v, int* wsum, int* total) {
 
 // Ordered walk over the roles of a unit: output slot of every kept row, ordinal of every seed.
 // A wave owns kIdxPer * 64 consecutive rows, read and written 64 consecutive rows at a time
-// (coalesced); positions inside the wave come from ballots with a running carry, and one
-// exchange of the wave totals per chunk of kSelThreads * kIdxPer rows orders the waves.
+// (coalesced); positions inside the wave come from ballots with a running carry (kept rows in
+// the low half of a word, seeds in the high half: a wave sees at most 1024 rows per chunk), and
+// one exchange of the wave totals per chunk of kSelThreads * kIdxPer rows orders the waves.
+// Inlined on purpose: as a called function its pointers lose their address space and the
+// ballots' scalar registers are spilled lane by lane, which made the walk issue-bound.
 constexpr int kIdxPer = 16;
 
-__device__ void index_walk(const KParams& kp, int u, int64_t row0, int N, const uint8_t* __restrict__ ro,
-                           int32_t* __restrict__ slot_of, int32_t* __restrict__ out_src,
-                           int32_t* __restrict__ out_len, int32_t* __restrict__ seed_rows,
-                           int32_t* __restrict__ ord_of_slot, int32_t* __restrict__ n_seeds,
-                           int* wsum) {
+__device__ __forceinline__ bool role_is_kept(int r) {
+  // prefix survivor, core, seed, recent
+  return r <= CASK_ROLE_RECENT && ((0x2E >> r) & 1);
+}
+
+__device__ __forceinline__ void index_walk(const KParams& kp, int u, int64_t row0, int N,
+                                           const uint8_t* __restrict__ ro, int32_t* __restrict__ slot_of,
+                                           int32_t* __restrict__ out_src, int32_t* __restrict__ out_len,
+                                           int32_t* __restrict__ seed_rows, int32_t* __restrict__ ord_of_slot,
+                                           int32_t* __restrict__ n_seeds, int* wsum) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int B = kp.B;
-  const unsigned long long below = (1ull << lane) - 1ull;
-  int kept_before = 0, seeds_before = 0;
+  int32_t* const slot_u = slot_of ? slot_of + row0 : nullptr;
+  int32_t* const src_u = out_src ? out_src + (size_t)u * B : nullptr;
+  int32_t* const ord_u = ord_of_slot ? ord_of_slot + (size_t)u * B : nullptr;
+  int32_t* const seed_u = seed_rows + (size_t)u * B;
+  int kept_before = 0, seeds_before = 0;  // of the chunks walked so far
   for (int cb = 0; cb < N; cb += kSelThreads * kIdxPer) {
     const int i0 = cb + wv * (64 * kIdxPer) + lane;
-    uint8_t r[kIdxPer];
+    int r[kIdxPer];
 #pragma unroll
-    for (int e = 0; e < kIdxPer; ++e) r[e] = (i0 + e * 64 < N) ? ro[i0 + e * 64] : (uint8_t)CASK_ROLE_PREFIX_DROP;
-    int kpos[kIdxPer], spos[kIdxPer];  // kept rows / seeds before this row inside the wave
-    int run_k = 0, run_s = 0;
+    for (int e = 0; e < kIdxPer; ++e) r[e] = (i0 + e * 64 < N) ? (int)ro[i0 + e * 64] : (int)CASK_ROLE_PREFIX_DROP;
+    int pos[kIdxPer];  // kept rows | seeds << 16 before this row inside the wave
+    int run = 0;
 #pragma unroll
     for (int e = 0; e < kIdxPer; ++e) {
-      const bool is_seed = r[e] == CASK_ROLE_SEED;
-      const bool kept = r[e] == CASK_ROLE_PREFIX_KEEP || r[e] == CASK_ROLE_CORE ||
-                        r[e] == CASK_ROLE_RECENT || is_seed;
-      const unsigned long long bk = __ballot(kept), bs = __ballot(is_seed);
-      kpos[e] = run_k + __popcll(bk & below);
-      spos[e] = run_s + __popcll(bs & below);
-      run_k += __popcll(bk);
-      run_s += __popcll(bs);
+      const unsigned long long bk = __ballot(role_is_kept(r[e])), bs = __ballot(r[e] == CASK_ROLE_SEED);
+      const int nk = __builtin_amdgcn_mbcnt_hi((unsigned)(bk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bk, 0));
+      const int ns = __builtin_amdgcn_mbcnt_hi((unsigned)(bs >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bs, 0));
+      pos[e] = run + nk + (ns << 16);
+      run += __popcll(bk) + (__popcll(bs) << 16);
+      // the positions are final here: keep them from being recomputed behind the barrier out
+      // of ballots that would have to be kept alive in scalar registers
+      asm volatile("" : "+v"(pos[e]));
     }
-    if (lane == 0) wsum[wv] = run_k | (run_s << 16);
+    int* ws = wsum + ((cb / (kSelThreads * kIdxPer)) & 1) * kSelWaves;  // two buffers: one barrier per chunk
+    if (lane == 0) ws[wv] = run;
     __syncthreads();
     int base = 0, tot = 0;
+#pragma unroll
     for (int w = 0; w < kSelWaves; ++w) {
-      const int x = wsum[w];
-      if (w < wv) base += x;
+      const int x = ws[w];
+      base += w < wv ? x : 0;
       tot += x;
     }
-    __syncthreads();
-    const int k0 = kept_before + (base & 0xFFFF), s0 = seeds_before + (base >> 16);
 #pragma unroll
     for (int e = 0; e < kIdxPer; ++e) {
       const int i = i0 + e * 64;
+      const int at = base + pos[e];  // inside the chunk: at most 16 384 in either half
+      const int slot = kept_before + (at & 0xFFFF), ord = seeds_before + (at >> 16);
+      const bool is_seed = r[e] == CASK_ROLE_SEED;
+      // a caller-supplied role array could keep more rows than the budget: never write past
+      // the unit's B output slots
+      const bool fits = role_is_kept(r[e]) && slot < B;
       if (i < N) {
-        const bool is_seed = r[e] == CASK_ROLE_SEED;
-        const bool kept = r[e] == CASK_ROLE_PREFIX_KEEP || r[e] == CASK_ROLE_CORE ||
-                          r[e] == CASK_ROLE_RECENT || is_seed;
-        const int slot = k0 + kpos[e], ord = s0 + spos[e];
-        // a caller-supplied role array could keep more rows than the budget: never write
-        // past the unit's B output slots
-        const bool fits = kept && slot < B;
-        if (slot_of) slot_of[row0 + i] = fits ? slot : -1;
+        if (slot_u) slot_u[i] = fits ? slot : -1;
         if (fits) {
-          if (out_src) out_src[(size_t)u * B + slot] = i;
-          if (ord_of_slot) ord_of_slot[(size_t)u * B + slot] = is_seed ? ord : -1;
+          if (src_u) src_u[slot] = i;
+          if (ord_u) ord_u[slot] = is_seed ? ord : -1;
         }
-        if (is_seed && ord < B) seed_rows[(size_t)u * B + ord] = i;
+        if (is_seed && ord < B) seed_u[ord] = i;
       }
     }
     kept_before += tot & 0xFFFF;
@@ -301,7 +312,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     int32_t* __restrict__ ord_of_slot, int32_t* __restrict__ n_seeds) {
   __shared__ int hist[2 * 3 * 256 * kHistCopies];
   __shared__ int bcast[3 * 4];
-  __shared__ int wsum[kSelWaves];
+  __shared__ int wsum[2 * kSelWaves];
   const int u = blockIdx.x, tid = threadIdx.x;
   const int64_t row0 = row_off[u];
   const int N = (int)(row_off[u + 1] - row0);
@@ -449,7 +460,7 @@ __global__ __launch_bounds__(kSelThreads) void index_roles_kernel(
     int32_t* __restrict__ slot_of, int32_t* __restrict__ out_src, int32_t* __restrict__ out_len,
     int32_t* __restrict__ seed_rows, int32_t* __restrict__ ord_of_slot,
     int32_t* __restrict__ n_seeds) {
-  __shared__ int wsum[kSelWaves];
+  __shared__ int wsum[2 * kSelWaves];
   const int u = blockIdx.x;
   const int64_t row0 = row_off[u];
   const int N = (int)(row_off[u + 1] - row0);
