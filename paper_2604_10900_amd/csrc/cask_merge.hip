@@ -465,6 +465,7 @@ hipError_t launch_similarity_kappa(const KParams& kp, const Batch& b, const uint
 constexpr int kGatherThreads = 1024;
 constexpr int kGatherPer = 16;  // 64-row groups per wave and chunk
 constexpr int kSegLds = 8192;   // seed ordinals whose segment cursors fit in LDS at a time
+constexpr int kSmallList = 64;  // donor lists up to this length are split by a single wave
 
 // assign_mode: 0 none, 1 output slot (whole event), 2 unit-local source row (consolidate API)
 __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
@@ -528,22 +529,35 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
 #pragma unroll
     for (int e = 0; e < kGatherPer; ++e) {
       const int i = i0 + e * 64;
-      if (i < hi) {
-        if (ord[e] >= 0) {
-          const int at = count + before + pos[e];
-          merged_row[row0 + at] = i;
-          merged_ord[row0 + at] = ord[e];
+      if (i < hi && ord[e] >= 0) {
+        const int at = count + before + pos[e];
+        merged_row[row0 + at] = i;
+        merged_ord[row0 + at] = ord[e];
+        if (at < kSmallList) {  // the head of the list also waits in LDS for the short-list split below
+          cursor[at] = ord[e];
+          cursor[kSmallList + at] = i;
         }
-        if (assign_mode != 0) {
-          int v;
-          if (r[e] == CASK_ROLE_DONOR) {
-            v = ord[e] < 0 ? -1 : (assign_mode == 1 ? slot_of[row0 + srow[ord[e]]] : srow[ord[e]]);
-          } else {
-            const bool kept = r[e] == CASK_ROLE_CORE || r[e] == CASK_ROLE_SEED;
-            v = !kept ? -1 : (assign_mode == 1 ? slot_of[row0 + i] : i);
-          }
-          assign_out[row0 + i] = v;
-        }
+      }
+    }
+    if (assign_mode != 0) {
+      // What a row maps to: a folding donor to its seed, a kept row to itself, anything else to
+      // nothing.  The two dependent lookups (seed's row, then its slot) are taken for all of the
+      // thread's rows at a time: one after the other, every row would wait for its own round trip.
+      int tgt[kGatherPer];
+#pragma unroll
+      for (int e = 0; e < kGatherPer; ++e) {
+        const int i = i0 + e * 64;
+        const bool kept = r[e] == CASK_ROLE_CORE || r[e] == CASK_ROLE_SEED;
+        tgt[e] = (i < hi && ord[e] >= 0) ? srow[ord[e]] : ((i < hi && kept) ? i : -1);  // (ord >= 0 only for donors)
+      }
+      if (assign_mode == 1) {
+#pragma unroll
+        for (int e = 0; e < kGatherPer; ++e) tgt[e] = tgt[e] >= 0 ? slot_of[row0 + tgt[e]] : -1;
+      }
+#pragma unroll
+      for (int e = 0; e < kGatherPer; ++e) {
+        const int i = i0 + e * 64;
+        if (i < hi) assign_out[row0 + i] = tgt[e];
       }
     }
     count += tot;
@@ -565,6 +579,28 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
   const int32_t* mrow = merged_row + row0;
   const int32_t* mord = merged_ord + row0;
   int32_t* sstart = seg_start + (size_t)u * (kp.B + 1);
+  if (count <= kSmallList) {
+    // A list of at most 64 donors (the usual case: few donors reach the threshold) is split by
+    // one wave from its copy in LDS: an entry's place is the number of entries with a smaller
+    // ordinal plus the earlier ones with the same ordinal; a segment starts at the number of
+    // entries with a smaller ordinal.
+    if (wv == 0) {
+      const int o_l = lane < count ? cursor[lane] : 0x7fffffff;
+      const int r_l = cursor[kSmallList + lane];
+      int place = 0;
+      for (int j = 0; j < count; ++j) {
+        const int oj = __shfl(o_l, j, 64);
+        place += (oj < o_l || (oj == o_l && j < lane)) ? 1 : 0;
+      }
+      if (lane < count) seg_row[row0 + place] = r_l;
+    }
+    for (int q = tid; q <= M; q += kGatherThreads) {
+      int smaller = 0;
+      for (int j = 0; j < count; ++j) smaller += cursor[j] < q ? 1 : 0;
+      sstart[q] = smaller;
+    }
+    return;
+  }
   int base = 0;
   for (int o_lo = 0; o_lo < M; o_lo += kSegLds) {
     const int range = min(kSegLds, M - o_lo);
