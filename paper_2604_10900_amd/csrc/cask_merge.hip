@@ -726,9 +726,13 @@ __global__ __launch_bounds__(256) void emit_kernel(
       if (item < items) {
         my_u = (int)(item / fold_per_unit);
         my_ord = (int)(item % fold_per_unit);
+        // the segment bounds are read along with the counts that say whether they mean anything
+        // (the slots exist for every ordinal below B; one round trip instead of two)
+        const int s0 = seg_start[(size_t)my_u * (B + 1) + my_ord];
+        const int s1 = seg_start[(size_t)my_u * (B + 1) + my_ord + 1];
         if (my_ord < n_seeds[my_u] && n_merged[my_u] > 0) {
-          my_s0 = seg_start[(size_t)my_u * (B + 1) + my_ord];
-          my_s1 = seg_start[(size_t)my_u * (B + 1) + my_ord + 1];
+          my_s0 = s0;
+          my_s1 = s1;
         }
       }
       unsigned long long todo = __ballot(my_s1 > my_s0);
@@ -833,21 +837,28 @@ __global__ __launch_bounds__(256) void emit_kernel(
   const int u = (int)(wave / waves_per_unit);
   const int t_base = (int)(wave % waves_per_unit) * kSlotsPerWave;
   if (u >= n_units) return;
+  int slot[kCopyRounds], src[kCopyRounds], ord[kCopyRounds], c0[kCopyRounds];
+  float a0[kCopyRounds];
+  Raw kraw[kCopyRounds], vraw[kCopyRounds];
+  // the slots' sources are read along with the unit's length, which says how many of them mean
+  // anything (every unit owns B slots of these arrays: one round trip instead of two)
+#pragma unroll
+  for (int j = 0; j < kCopyRounds; ++j) {
+    slot[j] = t_base + j * 4 + grp;
+    const bool in = slot[j] < B;
+    src[j] = in ? out_src[(size_t)u * B + slot[j]] : -1;
+    ord[j] = in ? ord_of_slot[(size_t)u * B + slot[j]] : -1;
+  }
   const int len = out_len[u];
   if (t_base >= len) return;
   const int64_t row0 = row_off[u];
   const int nm = n_merged[u];
   const int32_t* sstart = seg_start + (size_t)u * (B + 1);
-
-  int slot[kCopyRounds], src[kCopyRounds], ord[kCopyRounds], c0[kCopyRounds];
-  float a0[kCopyRounds];
-  Raw kraw[kCopyRounds], vraw[kCopyRounds];
 #pragma unroll
   for (int j = 0; j < kCopyRounds; ++j) {
-    slot[j] = t_base + j * 4 + grp;
     const bool ok = slot[j] < len;
-    src[j] = ok ? out_src[(size_t)u * B + slot[j]] : -1;
-    ord[j] = (ok && nm > 0) ? ord_of_slot[(size_t)u * B + slot[j]] : -1;
+    src[j] = ok ? src[j] : -1;
+    ord[j] = (ok && nm > 0) ? ord[j] : -1;
   }
   // the row loads do not wait for the test below: a representative's row is loaded in vain
 #pragma unroll
