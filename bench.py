@@ -33,12 +33,12 @@ PEAK_HBM_GBS = 8000.0
 # from the named summaries under profiles/, not measured by the run that prints them; a workload
 # without a summary, or a cut-down run (--layers / --seqs), reports null.
 PROFILED_TRAFFIC = {
-    "cfg2": {"bytes": (131008.0 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg2_kernels_and_hbm_traffic.md (score_mfma_kernel<0>)"},
-    "cfg3": {"bytes": (488876.3 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg3_kernels_and_hbm_traffic.md (score_mfma_kernel<0>)"},
-    "cfg4": {"bytes": (273504.7 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg4_kernels_and_hbm_traffic.md (score_mfma_kernel<0>)"},
-    "cfg4v": {"bytes": (1032144.0 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg4v_kernels_and_hbm_traffic.md (score_mfma_kernel<0>)"},
-    "cfg5": {"bytes": (120931155.1 * 2.0 + 2779132.2) * 1024, "source": "profiles/cfg5_kernels_and_hbm_traffic.md (score_mfma_kernel<3>)"},
-    "cfg2ss": {"bytes": (22096.2 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg2ss_kernels_and_hbm_traffic.md (score_mfma_kernel<2>)"},
+    "cfg2": {"bytes": (131008.9 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg2_kernels_and_hbm_traffic.md (score_mfma_kernel<0>)"},
+    "cfg3": {"bytes": (484807.1 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg3_kernels_and_hbm_traffic.md (score_mfma_kernel<0>)"},
+    "cfg4": {"bytes": (272298.3 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg4_kernels_and_hbm_traffic.md (score_mfma_kernel<0>)"},
+    "cfg4v": {"bytes": (1014431.4 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg4v_kernels_and_hbm_traffic.md (score_mfma_kernel<0>)"},
+    "cfg5": {"bytes": (119059307.1 * 2.0 + 2779132.2) * 1024, "source": "profiles/cfg5_kernels_and_hbm_traffic.md (score_mfma_kernel<3>)"},
+    "cfg2ss": {"bytes": (21696.9 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg2ss_kernels_and_hbm_traffic.md (score_mfma_kernel<2>)"},
 }
 
 
