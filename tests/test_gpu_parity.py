@@ -887,6 +887,47 @@ def test_zero_mass_group_and_exact_fold():
     np.testing.assert_allclose(parity.rows_as_float(got["K_out"][0, t0], cask.BF16), K[0] * 7 / 3, rtol=1e-2)
 
 
+@pytest.mark.parametrize("n_fold", [1, 63, 64, 65, 300])
+def test_donor_list_lengths_around_the_short_list_split(n_fold):
+    """Exactly n_fold donors of the first unit fold (copies of a seed's key, scaled), 300 of the
+    second: lists of at most 64 entries are grouped by seed by a single wave, longer ones by the
+    histogram path; both sit in one launch.  Scores injected, so roles are exact."""
+    d, N, Wn, n_core, M = 128, 3000, 64, 20, 16
+    rng = np.random.default_rng(700 + n_fold)
+    Ks, Vs, ss = [], [], []
+    for unit_fold in (n_fold, 300):
+        K = rng.integers(-4, 5, (N, d)).astype(np.float32)
+        V = rng.integers(-4, 5, (N, d)).astype(np.float32)
+        s = (1e-3 * (1.0 + rng.permutation(N))).astype(np.float32) / N   # distinct, small
+        free = rng.permutation(N - Wn)
+        core, seeds, donors = free[:n_core], free[n_core:n_core + M], free[n_core + M:n_core + M + unit_fold]
+        s[core] = 0.5 + 1e-3 * np.arange(n_core, dtype=np.float32)
+        s[seeds] = 0.25 + 1e-3 * np.arange(M, dtype=np.float32)
+        for j, r in enumerate(donors):
+            K[r] = K[seeds[j % M]] * (2.0 if j % 2 else 1.0)           # cosine 1 with that seed
+        Ks.append(K); Vs.append(V); ss.append(s)
+    p = cask.Params(dtype=cask.BF16, head_dim=d, q_per_kv=1, window=Wn, budget=Wn + n_core + M,
+                    core=n_core, prefix_budget=0, sim_threshold=0.999)
+    rp = parity.ref_params(p)
+    tb = lambda x: torch.from_numpy(x).to(torch.bfloat16)
+    Kc, Vc, sc = np.concatenate(Ks), np.concatenate(Vs), np.concatenate(ss)
+    c = dict(K=tb(Kc), V=tb(Vc), Q=torch.zeros(2, Wn, 1, d, dtype=torch.bfloat16),
+             row_off=torch.tensor([0, N, 2 * N], dtype=torch.int64), prefix_len=torch.tensor([0, 0], dtype=torch.int32))
+    row_off, prefix_len, Kb, Vb, Qb = parity.host_arrays(c)
+    want = ref.compress(rp, row_off, prefix_len, Kb, Vb, Qb, scores=sc)
+    folded = [(want["assign"][u * N:(u + 1) * N] >= 0).sum() - want["out_len"][u] for u in range(2)]
+    assert folded == [n_fold, 300], folded
+    b = parity.to_device(c, p)
+    out = cask.compress(b, scores=torch.from_numpy(sc).cuda())
+    torch.cuda.synchronize()
+    got = parity.gpu_outputs(out, p)
+    assert np.array_equal(got["out_len"], want["out_len"])
+    assert np.array_equal(got["out_src"], want["out_src"])
+    assert np.array_equal(got["assign"], want["assign"])
+    assert np.array_equal(got["status"], want["status"])
+    assert parity.check_values(p, got, want, Kb.reshape(2 * N, d), Vb.reshape(2 * N, d), row_off) >= min(n_fold, M)
+
+
 # ------------------------------------------------------------------ determinism, errors, edges
 
 @pytest.mark.parametrize("decode", [2500, 700])
