@@ -42,6 +42,44 @@ PROFILED_TRAFFIC = {
 }
 
 
+def sample_sclk(fn, seconds=4.0):
+    """Median and range of the shader clock `rocm-smi --showclocks --json` reports (MHz) while fn is
+    called in a loop for `seconds`; None where rocm-smi is missing or prints no clock."""
+    import re
+    import subprocess
+    import threading
+
+    import torch
+    vals, stop = [], threading.Event()
+
+    def sampler():
+        while not stop.is_set():
+            try:
+                out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True,
+                                     timeout=10).stdout
+                card = json.loads(out)
+                for k, v in card[sorted(card)[0]].items():
+                    m = re.search(r"(\d+)\s*mhz", str(v).lower())
+                    if k.lower().startswith("sclk clock speed") and m:
+                        vals.append(int(m.group(1)))
+            except Exception:
+                return
+
+    th = threading.Thread(target=sampler)
+    th.start()
+    t0 = time.time()
+    while time.time() - t0 < seconds:
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+    stop.set()
+    th.join()
+    vals = vals[1:]  # the first sample may predate the load
+    if not vals:
+        return None
+    return {"median": int(sorted(vals)[len(vals) // 2]), "min": int(min(vals)), "max": int(max(vals)), "samples": len(vals)}
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,6 +90,9 @@ def parse():
                     help="cfg2 (default) | cfg3 | cfg4 | cfg4v | cfg5; cfg2ss / cfg3ss = the steady state of a "
                          "decode loop on that shape: every event compresses budget + window rows back to the "
                          "budget (cask_compress_step with token counts), also timed as a replayed HIP graph")
+    ap.add_argument("--sample-clocks", action="store_true",
+                    help="with --probe-only: also report the shader clock rocm-smi shows while cask_score and "
+                         "the probe loops run (is the part at its power limit?)")
     ap.add_argument("--layers", type=int, default=0, help="use only the first L layers (0 = all)")
     ap.add_argument("--seqs", type=int, default=0, help="cfg5: use only the first S sequences")
     ap.add_argument("--copies", type=int, default=0,
@@ -119,7 +160,23 @@ def main():
                              **{k: round(v, 3) for k, v in r.items()}})
         mem = {"copy_1GiB": binding.probe_copy(1 << 30), "copy_4GiB": binding.probe_copy(4 << 30),
                "read_1GiB": binding.probe_read(1 << 30), "read_4GiB": binding.probe_read(4 << 30)}
-        print(json.dumps({"probe_issue": rows, "probe_memory": mem,
+        clocks = None
+        if args.sample_clocks:
+            # the shader clock rocm-smi reports while one kernel loops: the sweeps and the MFMA loops
+            # hold the part at its power limit, the vector-only loop does not
+            w3 = caches.WORKLOADS["cfg3"]
+            c3 = caches.make(w3, device=dev)
+            p3 = cask.Params(dtype=cask.BF16, head_dim=w3.head_dim, q_per_kv=w3.q_per_kv, window=w3.window,
+                             budget=w3.budget)
+            b3 = cask.Batch(p3, c3["row_off"], c3["prefix_len"], c3["K"], c3["V"], c3["Q"])
+            clocks = {"idle": sample_sclk(lambda: None, 2.0),
+                      "cask_score cfg3": sample_sclk(lambda: cask.score(b3)),
+                      "probe kind 0, two waves": sample_sclk(lambda: binding.probe_issue(0, 2, 256, 20000)),
+                      "probe kind 1, two waves": sample_sclk(lambda: binding.probe_issue(1, 2, 256, 20000)),
+                      "probe kind 3, two waves": sample_sclk(lambda: binding.probe_issue(3, 2, 256, 20000)),
+                      "probe kind 3, three waves": sample_sclk(lambda: binding.probe_issue(3, 3, 256, 20000)),
+                      "probe kind 2, two waves": sample_sclk(lambda: binding.probe_issue(2, 2, 256, 20000))}
+        print(json.dumps({"probe_issue": rows, "probe_memory": mem, "sclk_MHz_under_load": clocks,
                           "note": "256 workgroups (one per compute unit); TFLOP/s counts the MFMA flop; cycles per unit "
                                   "and SIMD = time x shader clock / units; copy GB/s counts bytes read plus written"}))
         return
