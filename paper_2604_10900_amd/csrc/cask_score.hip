@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
 // pipeline with two more instructions per logit (a compare of the logit's constant row offset
 // with a per-lane limit, a select); only a sweep-A workgroup without a single clean stage, which
 // has no reference logit yet, takes a plain unpipelined path with a true running maximum.
-template <int MODE>
+template <int MODE, int CT = 2>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     KParams kp, int n_units, int tiles_per_unit, int n_splits, int split_len, int q_splits, int mq_pad,
     const int64_t* __restrict__ row_off, const uint16_t* __restrict__ K,
@@ -156,6 +156,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // order and leave the workgroup as one addend per key -- stored when the unit has one row
   // block, added atomically onto scores cleared beforehand when it has two (two addends onto
   // zero: the order cannot change the bits).
+  // CT = resident 32-row tiles per wave: 2 (64 rows a wave, 256 a workgroup) or 4 (128 / 512:
+  // every stream operand read from LDS then serves four products instead of two)
+  constexpr int kWaveRows = CT * 32;
+  constexpr int kResRowsT = kWaves * kWaveRows;
   constexpr bool kRowPass = MODE != 1;
   constexpr bool kTwoPass = MODE >= 2;
   constexpr bool kWgReduce = MODE == 3;
@@ -182,7 +186,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   if (kRowPass) {
     const int qb = tile / n_splits;
     split = tile % n_splits;
-    res_base = qb * kResRows;
+    res_base = qb * kResRowsT;
     if (res_base >= Mq) return;
     res_ptr = Qu;
     res_limit = Mq;
@@ -190,13 +194,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     s_begin = split * split_len;
     s_end = min(N, s_begin + split_len);
     if (kp.causal) {  // (MODE 2: the keys cut here get zeros as their partial sums at the end)
-      const int last_row = min(Mq, res_base + kResRows) - 1;
+      const int last_row = min(Mq, res_base + kResRowsT) - 1;
       s_end = min(s_end, N - W + last_row / Gq + 1);
     }
   } else {
     // a unit's last tile first: its waves run the masked path and take longest
     const int key_tiles = tiles_per_unit / q_splits;
-    res_base = (key_tiles - 1 - tile / q_splits) * kResRows;
+    res_base = (key_tiles - 1 - tile / q_splits) * kResRowsT;
     if (res_base >= N) return;
     res_ptr = Ku;
     res_limit = N;
@@ -221,12 +225,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   const __amdgpu_buffer_rsrc_t rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(str_ptr), 0,
                                         max(s_end, 0) * kRowBytes, 0x00020000);
-  int ld_voff[kLoadsPerThread];
-#pragma unroll
-  for (int j = 0; j < kLoadsPerThread; ++j) {
-    const int grp = wv + kWaves * j;  // 4-row group of the stage this wave's load j fills
-    ld_voff[j] = (grp * 4 + (lane & 3)) * kRowBytes + (lane >> 2) * 16;
-  }
+  // (load j of a wave fills 4-row group wv + kWaves * j: the same lane offset, 4 * kWaves rows on)
+  const int ld_voff = (wv * 4 + (lane & 3)) * kRowBytes + (lane >> 2) * 16;
   // sweep B: the -L_row of a stage's 64 rows is one more 256-byte load, taken in turn by the
   // waves (stage % kWaves), so every wave has at most one extra load in flight
   const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       const int grp = wv + kWaves * j;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
           rsrc, (__attribute__((address_space(3))) void*)(slot + grp * kGroupPitch),
-          16, ld_voff[j], soff, 0, 0);
+          16, ld_voff, soff + j * (4 * kWaves * kRowBytes), 0, 0);
     }
   };
 
@@ -259,12 +259,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // ring's first loads are on their way so that the two latencies overlap.
   const __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(res_ptr), 0, res_limit * kRowBytes, 0x00020000);
-  bf16x8 bres[2][NK];
-  int res_row[2];
+  bf16x8 bres[CT][NK];
+  auto res_row_of = [&](int ct) { return res_base + wv * kWaveRows + ct * 32 + c32; };
 #pragma unroll
-  for (int ct = 0; ct < 2; ++ct) {
-    const int r = res_base + wv * 64 + ct * 32 + c32;
-    res_row[ct] = r;
+  for (int ct = 0; ct < CT; ++ct) {
+    const int r = res_row_of(ct);
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(res_rsrc, r * kRowBytes + h * 16, ks * 32, 0);
@@ -272,7 +271,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
   }
   // a wave whose resident rows are all past the end only helps with loads and barriers
-  const bool wave_live = res_base + wv * 64 < res_limit;
+  const bool wave_live = res_base + wv * kWaveRows < res_limit;
 
   // A-operand rows of this lane inside a stage: row rt * 32 + c32 -> group, row-in-group
   const int a_off = (c32 >> 2) * kGroupPitch + (c32 & 3) * 16 + h * 64;
@@ -296,17 +295,25 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   };
 
   // per-lane reduction state
-  float m_ref[2] = {kNegInf, kNegInf}, l_run[2] = {0.f, 0.f};  // sweep A
-  float colsum[2] = {0.f, 0.f};                                  // sweep B
-  int vis_limit[2];  // sweep A: last key the lane's window row sees; sweep B: the lane's key
+  // (vector values, not arrays: an array the optimiser cannot split ends up in scratch memory)
+  typedef float fxCT __attribute__((ext_vector_type(CT)));
+  fxCT m_ref, l_run;  // sweep A
+  float colsum[CT];            // sweep B
 #pragma unroll
-  for (int ct = 0; ct < 2; ++ct)
-    vis_limit[ct] = (kRowPass) ? (kp.causal ? N - W + res_row[ct] / Gq : N - 1) : res_row[ct];
+  for (int ct = 0; ct < CT; ++ct) {
+    m_ref[ct] = kNegInf;
+    l_run[ct] = 0.f;
+    colsum[ct] = 0.f;
+  }
+  // sweep A: last key the lane's window row sees; sweep B: the lane's key
+  auto vis_limit_of = [&](int ct) {
+    return (kRowPass) ? (kp.causal ? N - W + res_row_of(ct) / Gq : N - 1) : res_row_of(ct);
+  };
   const int tail_start = kp.causal ? N - W : N;  // keys > tail_start are hidden from some row
-  int first_row[2];  // sweep B: first window row that sees the lane's key
+  int first_row[CT];  // sweep B: first window row that sees the lane's key
 #pragma unroll
-  for (int ct = 0; ct < 2; ++ct)
-    first_row[ct] = (MODE == 1 && kp.causal) ? max(0, (res_row[ct] - (N - W)) * Gq) : 0;
+  for (int ct = 0; ct < CT; ++ct)
+    first_row[ct] = (MODE == 1 && kp.causal) ? max(0, (res_row_of(ct) - (N - W)) * Gq) : 0;
 
   // ---- epilogues
   // sweep A: a tile's 16 terms are summed on their own and banked into the lane's running sum
@@ -315,7 +322,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   float tsum = 0.f;
   auto bank_tile = [&](int ct) {
     if (kRowPass) {
-      l_run[ct] += tsum;
+      // (static indices only: an index the optimiser does not see through would move the
+      // array into scratch memory)
+#pragma unroll
+      for (int k = 0; k < CT; ++k)
+        if (k == ct) l_run[k] += tsum;
       tsum = 0.f;
     }
   };
@@ -323,9 +334,13 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // inside the tile (a constant) with `d`, the lane's limit relative to the tile:
   //   sweep A: hidden iff offset > d, d = (last key the lane's row sees) - first row of the tile - 4 h
   //   sweep B: hidden iff offset < d, d = (first row that sees the lane's key) - first row of the tile - 4 h
-  int lim_a[2];  // sweep A: last stream row (key) that counts for the lane's window row
+  // sweep A: last stream row (key) that counts for the lane's window row.  Only masked stages
+  // look at it: set_limits() runs in front of them, so the clean stages do not carry the values.
+  int lim_a[CT];
+  auto set_limits = [&]() {
 #pragma unroll
-  for (int ct = 0; ct < 2; ++ct) lim_a[ct] = min(s_end - 1, vis_limit[ct]);
+    for (int ct = 0; ct < CT; ++ct) lim_a[ct] = min(s_end - 1, vis_limit_of(ct));
+  };
   auto mask_d = [&](int ct, int trow0) { return (kRowPass ? lim_a[ct] : first_row[ct]) - trow0 - h * 4; };
   auto piece = [&](auto masked, const f32x16& acc, const float (&nl)[16], int ct, int i, int d) {  // two logits of the fast epilogue
     constexpr bool kMasked = decltype(masked)::value;
@@ -371,7 +386,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = trow0 + (r >> 2) * 8 + h * 4 + (r & 3);
-        if (!(key < s_end && key <= vis_limit[ct])) acc[r] = kNegInf;
+        if (!(key <= lim_a[ct])) acc[r] = kNegInf;  // (the limit is already cut at the end of the stream)
       }
       exact_update(acc, ct);
     } else {
@@ -420,7 +435,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // left to the compiler it lands inside the loop prologue as a wait for every load in flight,
   // the ring's newest stage included.
 #pragma unroll
-  for (int ct = 0; ct < 2; ++ct)
+  for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(bres[ct][ks]));
   // Once per stage: this thread's pieces of stages `it` and `it + 1` have landed when at most
@@ -449,7 +464,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       load_a(a0, cur, rt);
       load_nl(nl0, cur, rt);
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
+      for (int ct = 0; ct < CT; ++ct) {
         chain(acc0, a0, ct);
         slow_tile(acc0, nl0, ct, trow0);
       }
@@ -457,7 +472,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     if (kRowPass) {
       // a lane that saw nothing yet takes 0 as its reference: (0, 0) is the empty sum
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
+      for (int ct = 0; ct < CT; ++ct)
         if (m_ref[ct] == kNegInf) m_ref[ct] = 0.f;
     }
   };
@@ -474,8 +489,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     f1 = clean_rows > 0 ? clean_rows / kStageRows : 0;
   } else {
     if (kp.causal) {
-      const int k0 = res_base + wv * 64 - (N - W);  // the wave's oldest key, relative to the window
-      const int fr_min = max(0, k0 * Gq), fr_max = max(0, (k0 + 63) * Gq);
+      const int k0 = res_base + wv * kWaveRows - (N - W);  // the wave's oldest key, relative to the window
+      const int fr_min = max(0, k0 * Gq), fr_max = max(0, (k0 + kWaveRows - 1) * Gq);
       sk = max(0, min(n_stages, (fr_min - s_begin) / kStageRows));
       f0 = max(sk, min(n_stages, (fr_max - s_begin + kStageRows - 1) / kStageRows));
     }
@@ -518,10 +533,72 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
     drain(masked, acc1, nl1, 1, s_begin + (to - 1) * kStageRows + 32);
   };
+  // Four resident tiles per wave (sweep A): a wave keeps ONE tile row's stream operands; while
+  // the last of the tile row's four chains consumes them k-step by k-step, each is replaced in
+  // place by the next tile row's (the 32 registers that saves, with the 64 the two more resident
+  // tiles cost, still fit two waves per SIMD).  Tiles of a stage in the order (tile row, resident
+  // tile) = (0,0) (0,1) (0,2) (0,3) (1,0) ... (1,3), accumulators alternating.
+  auto fused_refill = [&](auto masked, f32x16& acc_new, bf16x8(&a)[NK], int ct_new, const f32x16& acc_old,
+                          int ct_old, int trow_old, const unsigned char* next_rows) {
+    const int d = mask_d(ct_old, trow_old);
+#pragma unroll
+    for (int ks = 0; ks < NK; ++ks) {
+      piece(masked, acc_old, nl0, ct_old, ks, d);
+      acc_new = (ks == 0)
+                    ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], bres[ct_new][0], f32x16{0}, 0, 0, 0)
+                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct_new][ks], acc_new, 0, 0, 0);
+      a[ks] = *reinterpret_cast<const bf16x8*>(next_rows + ks * 128);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    bank_tile(ct_old);
+  };
+  auto pipelined_wide = [&](auto masked, int from, int to) {
+    constexpr bool kMasked = decltype(masked)::value;
+    constexpr int L = CT - 1;  // the last resident tile
+    stage_sync(from);
+    load_a(a0, slot_of(from), 0);
+    if (kRowPass && !kMasked && from == 0) {
+      // references: the first logit of every resident row of the lane
+#pragma unroll
+      for (int ct = L; ct >= 1; --ct) {
+        chain(acc1, a0, ct);
+        m_ref[ct] = acc1[0] * c;
+      }
+      chain(acc0, a0, 0);
+      m_ref[0] = acc0[0] * c;
+    } else {
+      chain(acc0, a0, 0);
+    }
+    for (int it = from;; ++it) {
+      const unsigned char* cur = slot_of(it);
+      const int base = s_begin + it * kStageRows;
+      fused(masked, acc1, a0, 1, acc0, nl0, 0, base);
+      fused(masked, acc0, a0, 2, acc1, nl0, 1, base);
+      fused_refill(masked, acc1, a0, 3, acc0, 2, base, cur + 8 * kGroupPitch + a_off);  // a0 <- tile row 1
+      fused(masked, acc0, a0, 0, acc1, nl0, 3, base);
+      fused(masked, acc1, a0, 1, acc0, nl0, 0, base + 32);
+      fused(masked, acc0, a0, 2, acc1, nl0, 1, base + 32);
+      if (it + 1 >= to) {
+        fused(masked, acc1, a0, 3, acc0, nl0, 2, base + 32);
+        break;
+      }
+      fused_refill(masked, acc1, a0, 3, acc0, 2, base + 32, slot_of(it + 1) + a_off);  // a0 <- next stage
+      stage_sync(it + 1);
+      fused(masked, acc0, a0, 0, acc1, nl0, 3, base + 32);
+    }
+    drain(masked, acc1, nl0, L, s_begin + (to - 1) * kStageRows + 32);
+  };
   const std::integral_constant<bool, false> clean_tag;
   const std::integral_constant<bool, true> masked_tag;
 
   int it = 0;
+  if (kRowPass && f0 < f1) {
+    // (placeholder values while the clean stages run: nothing reads them there)
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) lim_a[ct] = 0;
+  } else if (kRowPass) {
+    set_limits();
+  }
   for (; it < sk; ++it) stage_sync(it);
   if (MODE == 1) {
     // the partly visible stages run pipelined as well, with the mask in the epilogue
@@ -532,12 +609,17 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       slow_stage(it);
     }
   }
-  if (f1 > f0) pipelined(clean_tag, f0, f1);
+  if (f1 > f0) {
+    if (CT == 4) pipelined_wide(clean_tag, f0, f1);
+    else pipelined(clean_tag, f0, f1);
+  }
   it = f1;
+  if (kRowPass) set_limits();
   if (kRowPass && f1 > 0 && n_stages > f1) {
     // the tail (causal, ragged end) after at least one clean stage: the reference is set, so
     // the masked epilogue can take it
-    pipelined(masked_tag, f1, n_stages);
+    if (CT == 4) pipelined_wide(masked_tag, f1, n_stages);
+    else pipelined(masked_tag, f1, n_stages);
     it = n_stages;
   }
   for (; it < n_stages; ++it) {
@@ -546,13 +628,15 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   }
   if (kRowPass && wave_live) {
     // Range check of the fast epilogue, once per wave: a finite sum is exact.
-    const bool bad = !(l_run[0] < __builtin_inff()) || !(l_run[1] < __builtin_inff());
+    bool bad = false;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) bad = bad || !(l_run[ct] < __builtin_inff());
     if (__builtin_amdgcn_ballot_w64(bad) != 0ull) {
       // Recompute this wave's statistics with a true running maximum.  The ring belongs to the
       // whole workgroup, so the stream rows come straight from memory (same bounds-checked
       // descriptor: rows past the end read as zero and are masked).
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
+      for (int ct = 0; ct < CT; ++ct) {
         m_ref[ct] = kNegInf;
         l_run[ct] = 0.f;
       }
@@ -566,14 +650,14 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
             a0[ks] = __builtin_bit_cast(bf16x8, v);
           }
 #pragma unroll
-          for (int ct = 0; ct < 2; ++ct) {
+          for (int ct = 0; ct < CT; ++ct) {
             chain(acc0, a0, ct);
             slow_tile(acc0, nl0, ct, trow0);
           }
         }
       }
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct)
+      for (int ct = 0; ct < CT; ++ct)
         if (m_ref[ct] == kNegInf) m_ref[ct] = 0.f;
     }
   }
@@ -594,9 +678,12 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     for (int ct = 0; ct < 2; ++ct) {
       const float m2 = __shfl_xor(m_ref[ct], 32, 64);
       const float l2 = __shfl_xor(l_run[ct], 32, 64);
-      ml_combine(m_ref[ct], l_run[ct], m2, l2);
+      float mc = m_ref[ct], lc = l_run[ct];
+      ml_combine(mc, lc, m2, l2);
+      m_ref[ct] = mc;
+      l_run[ct] = lc;
       if (h == 0)
-        negl_s[wv * 64 + ct * 32 + c32] = res_row[ct] < Mq ? -(m_ref[ct] + log2f(l_run[ct])) : kPadNegL;
+        negl_s[wv * 64 + ct * 32 + c32] = res_row_of(ct) < Mq ? -(m_ref[ct] + log2f(l_run[ct])) : kPadNegL;
     }
     // the wave reads back only what it wrote itself (LDS operations of a wave stay in order);
     // the empty asm keeps the compiler from moving the differently typed reads above the writes
@@ -743,25 +830,28 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   } else if (MODE == 0) {
     float2* part = rowstat + (size_t)unit * n_splits * mq_pad;
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
+    for (int ct = 0; ct < CT; ++ct) {
       const float m2 = __shfl_xor(m_ref[ct], 32, 64);
       const float l2 = __shfl_xor(l_run[ct], 32, 64);
-      ml_combine(m_ref[ct], l_run[ct], m2, l2);
-      if (h == 0 && res_row[ct] < Mq)
-        part[(size_t)split * mq_pad + res_row[ct]] = make_float2(m_ref[ct], l_run[ct]);
+      float mc = m_ref[ct], lc = l_run[ct];
+      ml_combine(mc, lc, m2, l2);
+      m_ref[ct] = mc;
+      l_run[ct] = lc;
+      if (h == 0 && res_row_of(ct) < Mq)
+        part[(size_t)split * mq_pad + res_row_of(ct)] = make_float2(m_ref[ct], l_run[ct]);
       // a single split is the whole row: -L goes out here and no combining kernel runs
-      if (n_splits == 1 && h == 0 && res_row[ct] < mq_pad)
-        bias_out[(size_t)unit * mq_pad + res_row[ct]] =
-            res_row[ct] < Mq ? -(m_ref[ct] + log2f(l_run[ct])) : kPadNegL;
+      if (n_splits == 1 && h == 0 && res_row_of(ct) < mq_pad)
+        bias_out[(size_t)unit * mq_pad + res_row_of(ct)] =
+            res_row_of(ct) < Mq ? -(m_ref[ct] + log2f(l_run[ct])) : kPadNegL;
     }
   } else if (MODE == 1) {
     const float inv = 1.0f / (float)Mq;
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
+    for (int ct = 0; ct < CT; ++ct) {
       const float tot = colsum[ct] + __shfl_xor(colsum[ct], 32, 64);
-      if (h == 0 && res_row[ct] < N) {
-        if (q_splits == 2) atomicAdd(&scores[row0 + res_row[ct]], tot * inv);
-        else scores[row0 + res_row[ct]] = tot * inv;
+      if (h == 0 && res_row_of(ct) < N) {
+        if (q_splits == 2) atomicAdd(&scores[row0 + res_row_of(ct)], tot * inv);
+        else scores[row0 + res_row_of(ct)] = tot * inv;
       }
     }
   }
@@ -898,10 +988,20 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   if (e == hipSuccess) e = limB.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<1>), 160 * 1024);
   if (e != hipSuccess) return e;
   const int qblocks = (kp.Mq + kResRows - 1) / kResRows;
-  const int tilesA = qblocks * wl.n_splits;
-  score_mfma_kernel<0><<<dim3(units8 * tilesA), dim3(kThreads), ldsA, st>>>(
-      kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
-      nullptr, bias, scores, nullptr, 0);
+  if (wl.wide_rows) {
+    static LdsLimitOnce limAw;
+    e = limAw.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<0, 4>), 160 * 1024);
+    if (e != hipSuccess) return e;
+    const int tilesAw = (kp.Mq + 2 * kResRows - 1) / (2 * kResRows) * wl.n_splits;
+    score_mfma_kernel<0, 4><<<dim3(units8 * tilesAw), dim3(kThreads), ldsA, st>>>(
+        kp, b.n_units, tilesAw, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
+        nullptr, bias, scores, nullptr, 0);
+  } else {
+    const int tilesA = qblocks * wl.n_splits;
+    score_mfma_kernel<0><<<dim3(units8 * tilesA), dim3(kThreads), ldsA, st>>>(
+        kp, b.n_units, tilesA, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
+        nullptr, bias, scores, nullptr, 0);
+  }
   if (between) (void)hipEventRecord(between, st);  // right behind sweep A: the stage is that kernel alone
   if (wl.n_splits > 1)  // with one split sweep A has written -L itself
     score_bias_kernel<<<dim3(b.n_units), dim3(256), 0, st>>>(kp, wl.n_splits, wl.mq_pad, rowstat, bias);
