@@ -97,9 +97,13 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
     float nl = kPadNegL;
     if (r < kp.Mq) {
       float m = kNegInf, l = 0.f;
-      for (int sp = 0; sp < n_splits; ++sp) {
-        const float2 pr = part[(size_t)sp * mq_pad + r];
-        ml_combine(m, l, pr.x, pr.y);
+      for (int s0 = 0; s0 < n_splits; s0 += 8) {  // eight partials in flight, combined in order
+        float2 pr[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pr[e] = part[(size_t)min(s0 + e, n_splits - 1) * mq_pad + r];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (s0 + e < n_splits) ml_combine(m, l, pr[e].x, pr[e].y);
       }
       nl = -(m + log2f(l));
     }
