@@ -65,6 +65,12 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
     if (wgsB <= 384 && kp.Mq >= 512) w.q_splits = 2;  // measured: helps up to about 1.5 rounds of the 512 slots
     if (kp.score_qsplit >= 1) w.q_splits = kp.score_qsplit;
   }
+  // Sweep B with 128 resident keys per wave (512 per workgroup) when that still leaves at least
+  // two rounds of workgroups
+  {
+    const int64_t wgs_wide = (int64_t)((n_units + 7) / 8 * 8) * ((max_unit_len + 511) / 512);
+    w.wide_cols = (w.q_splits == 1 && wgs_wide >= 1024 && !(kp.path_flags & CASK_PATH_NARROW_ROWS)) ? 1 : 0;
+  }
   w.split_len = split_len;
   w.mq_pad = (int)align_up((size_t)kp.Mq, 64);
   size_t off = 0;

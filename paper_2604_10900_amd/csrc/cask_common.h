@@ -200,6 +200,7 @@ struct Workspace {
   int split_len;     // keys per split (multiple of the key tile)
   int q_splits;      // sweep B: window-row halves taken by separate workgroups (1 or 2)
   int wide_rows;     // sweep A: 1 = 128 resident window rows per wave (512 per workgroup), 0 = 64 (256)
+  int wide_cols;     // sweep B: 1 = 128 resident keys per wave (512 per workgroup), 0 = 64 (256)
   size_t parts;      // float  [n_units][ceil(Mq / 64)][parts_pitch]: partial column sums of the one-launch scoring
   int parts_pitch;   // 0: not laid out (units too long for that path)
   int mq_pad;

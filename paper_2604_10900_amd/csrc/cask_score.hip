@@ -302,7 +302,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // (vector values, not arrays: an array the optimiser cannot split ends up in scratch memory)
   typedef float fxCT __attribute__((ext_vector_type(CT)));
   fxCT m_ref, l_run;  // sweep A
-  float colsum[CT];            // sweep B
+  fxCT colsum;                 // sweep B
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) {
     m_ref[ct] = kNegInf;
@@ -314,7 +314,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     return (kRowPass) ? (kp.causal ? N - W + res_row_of(ct) / Gq : N - 1) : res_row_of(ct);
   };
   const int tail_start = kp.causal ? N - W : N;  // keys > tail_start are hidden from some row
-  int first_row[CT];  // sweep B: first window row that sees the lane's key
+  typedef int ixCT __attribute__((ext_vector_type(CT)));
+  ixCT first_row;  // sweep B: first window row that sees the lane's key
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct)
     first_row[ct] = (MODE == 1 && kp.causal) ? max(0, (res_row_of(ct) - (N - W)) * Gq) : 0;
@@ -542,16 +543,26 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // place by the next tile row's (the 32 registers that saves, with the 64 the two more resident
   // tiles cost, still fit two waves per SIMD).  Tiles of a stage in the order (tile row, resident
   // tile) = (0,0) (0,1) (0,2) (0,3) (1,0) ... (1,3), accumulators alternating.
-  auto fused_refill = [&](auto masked, f32x16& acc_new, bf16x8(&a)[NK], int ct_new, const f32x16& acc_old,
-                          int ct_old, int trow_old, const unsigned char* next_rows) {
+  // `next_rows` (not null): the stream operands are replaced by the rows there; `next_nl` (not
+  // null, sweep B): the -L values, four at a time behind the two pieces that used them
+  auto fused_refill = [&](auto masked, auto refill_a, auto refill_nl, f32x16& acc_new, bf16x8(&a)[NK],
+                          int ct_new, const f32x16& acc_old, float (&nl)[16], int ct_old, int trow_old,
+                          const unsigned char* next_rows, const unsigned char* next_nl) {
+    constexpr bool kA = decltype(refill_a)::value, kNl = decltype(refill_nl)::value && MODE == 1;
     const int d = mask_d(ct_old, trow_old);
 #pragma unroll
     for (int ks = 0; ks < NK; ++ks) {
-      piece(masked, acc_old, nl0, ct_old, ks, d);
+      piece(masked, acc_old, nl, ct_old, ks, d);
       acc_new = (ks == 0)
                     ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], bres[ct_new][0], f32x16{0}, 0, 0, 0)
                     : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ct_new][ks], acc_new, 0, 0, 0);
-      a[ks] = *reinterpret_cast<const bf16x8*>(next_rows + ks * 128);
+      if (kA) a[ks] = *reinterpret_cast<const bf16x8*>(next_rows + ks * 128);
+      if (kNl && (ks & 1)) {
+        const int g = ks >> 1;
+        const bf16x8 raw = *reinterpret_cast<const bf16x8*>(next_nl + (g * 8 + h * 4) * 4);
+        const f32x4 v = __builtin_bit_cast(f32x4, raw);
+        nl[g * 4 + 0] = v[0]; nl[g * 4 + 1] = v[1]; nl[g * 4 + 2] = v[2]; nl[g * 4 + 3] = v[3];
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
     bank_tile(ct_old);
@@ -559,8 +570,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   auto pipelined_wide = [&](auto masked, int from, int to) {
     constexpr bool kMasked = decltype(masked)::value;
     constexpr int L = CT - 1;  // the last resident tile
+    const std::integral_constant<bool, true> yes;
+    const std::integral_constant<bool, false> no;
     stage_sync(from);
     load_a(a0, slot_of(from), 0);
+    load_nl(nl0, slot_of(from), 0);
     if (kRowPass && !kMasked && from == 0) {
       // references: the first logit of every resident row of the lane
 #pragma unroll
@@ -578,17 +592,20 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       const int base = s_begin + it * kStageRows;
       fused(masked, acc1, a0, 1, acc0, nl0, 0, base);
       fused(masked, acc0, a0, 2, acc1, nl0, 1, base);
-      fused_refill(masked, acc1, a0, 3, acc0, 2, base, cur + 8 * kGroupPitch + a_off);  // a0 <- tile row 1
-      fused(masked, acc0, a0, 0, acc1, nl0, 3, base);
+      // a0 <- tile row 1 behind the last chain of tile row 0
+      fused_refill(masked, yes, no, acc1, a0, 3, acc0, nl0, 2, base, cur + 8 * kGroupPitch + a_off, nullptr);
+      // the last epilogue of tile row 0 hands its -L registers over to tile row 1
+      fused_refill(masked, no, yes, acc0, a0, 0, acc1, nl0, 3, base, nullptr, cur + kDataBytes + 32 * 4);
       fused(masked, acc1, a0, 1, acc0, nl0, 0, base + 32);
       fused(masked, acc0, a0, 2, acc1, nl0, 1, base + 32);
       if (it + 1 >= to) {
         fused(masked, acc1, a0, 3, acc0, nl0, 2, base + 32);
         break;
       }
-      fused_refill(masked, acc1, a0, 3, acc0, 2, base + 32, slot_of(it + 1) + a_off);  // a0 <- next stage
+      const unsigned char* nxt = slot_of(it + 1);
+      fused_refill(masked, yes, no, acc1, a0, 3, acc0, nl0, 2, base + 32, nxt + a_off, nullptr);  // a0 <- next stage
       stage_sync(it + 1);
-      fused(masked, acc0, a0, 0, acc1, nl0, 3, base + 32);
+      fused_refill(masked, no, yes, acc0, a0, 0, acc1, nl0, 3, base + 32, nullptr, nxt + kDataBytes);
     }
     drain(masked, acc1, nl0, L, s_begin + (to - 1) * kStageRows + 32);
   };
@@ -606,7 +623,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   for (; it < sk; ++it) stage_sync(it);
   if (MODE == 1) {
     // the partly visible stages run pipelined as well, with the mask in the epilogue
-    if (f0 > sk) pipelined(masked_tag, sk, f0);
+    if (f0 > sk) {
+      if (CT == 4) pipelined_wide(masked_tag, sk, f0);
+      else pipelined(masked_tag, sk, f0);
+    }
   } else {
     for (; it < f0; ++it) {
       stage_sync(it);
@@ -1009,10 +1029,20 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   if (between) (void)hipEventRecord(between, st);  // right behind sweep A: the stage is that kernel alone
   if (wl.n_splits > 1)  // with one split sweep A has written -L itself
     score_bias_kernel<<<dim3(b.n_units), dim3(256), 0, st>>>(kp, wl.n_splits, wl.mq_pad, rowstat, bias);
-  const int tilesB = (b.max_unit_len + kResRows - 1) / kResRows * wl.q_splits;
-  score_mfma_kernel<1><<<dim3(units8 * tilesB), dim3(kThreads), ldsB, st>>>(
-      kp, b.n_units, tilesB, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
-      bias, nullptr, scores, nullptr, 0);
+  if (wl.wide_cols) {
+    static LdsLimitOnce limBw;
+    e = limBw.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<1, 4>), 160 * 1024);
+    if (e != hipSuccess) return e;
+    const int tilesBw = (b.max_unit_len + 2 * kResRows - 1) / (2 * kResRows) * wl.q_splits;
+    score_mfma_kernel<1, 4><<<dim3(units8 * tilesBw), dim3(kThreads), ldsB, st>>>(
+        kp, b.n_units, tilesBw, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
+        bias, nullptr, scores, nullptr, 0);
+  } else {
+    const int tilesB = (b.max_unit_len + kResRows - 1) / kResRows * wl.q_splits;
+    score_mfma_kernel<1><<<dim3(units8 * tilesB), dim3(kThreads), ldsB, st>>>(
+        kp, b.n_units, tilesB, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
+        bias, nullptr, scores, nullptr, 0);
+  }
   return hipGetLastError();
 }
 
