@@ -122,7 +122,8 @@ enum {
   CASK_PATH_ATTEND_VECTOR = 8,  /* bf16 cask_attend on the vector kernel fp32 caches use */
   CASK_PATH_NO_FUSED_SWEEPS = 16, /* many long units with W*G <= 512: two scoring launches instead of one */
   CASK_PATH_FORCE_FUSED_SWEEPS = 32, /* W*G <= 512: one scoring launch whatever the number of units */
-  CASK_PATH_NARROW_ROWS = 64 /* first scoring sweep: 64 resident window rows per wave whatever W*G is */
+  CASK_PATH_NARROW_ROWS = 64, /* both scoring sweeps: 64 resident rows per wave (256 per workgroup) whatever the shape */
+  CASK_PATH_WIDE_ROWS = 128   /* both scoring sweeps: 128 resident rows per wave (512 per workgroup) whatever the shape */
 };
 
 typedef struct {

@@ -24,6 +24,7 @@ ST_ACTIVE, ST_IDENTITY, ST_PREFIX_BUDGET_EXHAUSTED, ST_MERGE_INACTIVE = 0, 1, 2,
 PATH_NO_FUSED_TAIL, PATH_NO_FUSED_SCORE, PATH_DEDUP_VECTOR, PATH_ATTEND_VECTOR, PATH_NO_FUSED_SWEEPS = 1, 2, 4, 8, 16
 PATH_FORCE_FUSED_SWEEPS = 32
 PATH_NARROW_ROWS = 64
+PATH_WIDE_ROWS = 128
 (ROLE_PREFIX_DROP, ROLE_PREFIX_KEEP, ROLE_CORE, ROLE_SEED, ROLE_DONOR, ROLE_RECENT,
  ROLE_DECODE_EVICT) = range(7)
 
@@ -109,7 +110,7 @@ def _env_int(name: str) -> int:
 def _env_path_flags() -> int:
     """Measurement switches of the Python layer (the library itself reads no environment):
     CASK_FUSED_TAIL=0, CASK_FUSED_SCORE=0, CASK_FUSED_SWEEPS=0, CASK_DEDUP_VECTOR=1,
-    CASK_ATTEND_VECTOR=1, CASK_NARROW_ROWS=1 set the matching PATH_* bit of every call made through this binding."""
+    CASK_ATTEND_VECTOR=1, CASK_NARROW_ROWS=1, CASK_WIDE_ROWS=1 set the matching PATH_* bit of every call made through this binding."""
     env = os.environ
     f = 0
     if env.get("CASK_FUSED_TAIL", "1")[:1] == "0":
@@ -124,6 +125,8 @@ def _env_path_flags() -> int:
         f |= PATH_ATTEND_VECTOR
     if env.get("CASK_NARROW_ROWS", "0")[:1] == "1":
         f |= PATH_NARROW_ROWS
+    if env.get("CASK_WIDE_ROWS", "0")[:1] == "1":
+        f |= PATH_WIDE_ROWS
     return f
 
 

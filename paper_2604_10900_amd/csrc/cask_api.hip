@@ -25,6 +25,7 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
     const int live_w = (kp.Mq + 127) / 128, all_w = (kp.Mq + 511) / 512 * 4;
     const int live_n = (kp.Mq + 63) / 64, all_n = (kp.Mq + 255) / 256 * 4;
     w.wide_rows = (kp.Mq > 256 && (int64_t)live_w * all_n >= (int64_t)live_n * all_w) ? 1 : 0;
+    if (kp.path_flags & CASK_PATH_WIDE_ROWS) w.wide_rows = 1;
     if (kp.path_flags & CASK_PATH_NARROW_ROWS) w.wide_rows = 0;
   }
   // Key splits of the row-statistics sweep: more splits mean more, shorter workgroups (better
@@ -69,7 +70,12 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
   // two rounds of workgroups
   {
     const int64_t wgs_wide = (int64_t)((n_units + 7) / 8 * 8) * ((max_unit_len + 511) / 512);
-    w.wide_cols = (w.q_splits == 1 && wgs_wide >= 1024 && !(kp.path_flags & CASK_PATH_NARROW_ROWS)) ? 1 : 0;
+    w.wide_cols = (w.q_splits == 1 && wgs_wide >= 1024) ? 1 : 0;
+    if (kp.path_flags & CASK_PATH_WIDE_ROWS) {
+      w.wide_cols = 1;
+      w.q_splits = 1;
+    }
+    if (kp.path_flags & CASK_PATH_NARROW_ROWS) w.wide_cols = 0;
   }
   w.split_len = split_len;
   w.mq_pad = (int)align_up((size_t)kp.Mq, 64);

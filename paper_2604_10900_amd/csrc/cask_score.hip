@@ -1060,12 +1060,17 @@ __global__ __launch_bounds__(256) void clear_scores_kernel(float* __restrict__ s
 }  // namespace
 
 // Both sweeps in one launch for units of any length: pays when a workgroup of the second sweep
-// would stream few window rows (W*G <= 512: at most eight stages behind a full prologue) and
-// there are enough (unit, row block) pairs to fill the chip several times over.
+// would stream few window rows (at most eight stages behind a full prologue) and there are
+// enough (unit, row block) pairs to fill the chip several times over.  Its waves hold 64 window
+// rows each; with 256 < W*G <= 512 the two separate sweeps in their wide form (128 resident rows
+// per wave) are faster (a Llama-shaped ragged batch: 10.7 against 11.4 ms), so the one launch is
+// left to W*G <= 256 unless the caller asks for it.
 bool score_fused_fits(const KParams& kp, const Batch& b) {
   const int row_blocks = (kp.Mq + kResRows - 1) / kResRows;
   if (!score_uses_mfma(kp) || kp.Mq > 2 * kResRows || (kp.path_flags & CASK_PATH_NO_FUSED_SWEEPS)) return false;
-  return (int64_t)b.n_units * row_blocks >= 1024 || (kp.path_flags & CASK_PATH_FORCE_FUSED_SWEEPS);
+  if (kp.path_flags & CASK_PATH_FORCE_FUSED_SWEEPS) return true;
+  if (kp.Mq > kResRows && !(kp.path_flags & CASK_PATH_NARROW_ROWS)) return false;
+  return (int64_t)b.n_units * row_blocks >= 1024;
 }
 
 hipError_t launch_score_fused(const KParams& kp, const Batch& b, const Workspace& wl, float* scores,

@@ -67,12 +67,14 @@ def _ragged_bf16(lens, prefixes, G=7, Wn=128, seed=3):
     return dict(K=K, V=V, Q=Q, row_off=row_off, prefix_len=torch.tensor(prefixes, dtype=torch.int32))
 
 
-@pytest.mark.parametrize("rows", ["wide_rows", "narrow_rows"])
+@pytest.mark.parametrize("rows", ["chosen", "narrow_rows", "wide_rows"])
 def test_bf16_mfma_ragged_units_all_regimes(rows, monkeypatch):
     """N == W, N just above W, identity (N <= B), merge-inactive, active, several key tiles with
     ragged tails, and prefix lengths from 0 to almost N.  W*G = 896 takes the first sweep's
-    wide form (128 resident window rows per wave) unless told otherwise: both forms."""
+    wide form (128 resident window rows per wave) by itself, the second sweep only in large
+    batches: the library's choice, both sweeps narrow, both sweeps wide."""
     monkeypatch.setenv("CASK_NARROW_ROWS", "1" if rows == "narrow_rows" else "0")
+    monkeypatch.setenv("CASK_WIDE_ROWS", "1" if rows == "wide_rows" else "0")
     lens = [128, 129, 200, 257, 300, 1000, 2177, 5000, 2304, 640]
     pref = [0, 1, 0, 100, 290, 0, 50, 300, 2048, 512]
     c = _ragged_bf16(lens, pref)
@@ -82,7 +84,9 @@ def test_bf16_mfma_ragged_units_all_regimes(rows, monkeypatch):
     _note(st)
 
 
-def test_bf16_mfma_odd_window_noncausal_and_custom_scale():
+@pytest.mark.parametrize("rows", ["chosen", "wide_rows"])
+def test_bf16_mfma_odd_window_noncausal_and_custom_scale(rows, monkeypatch):
+    monkeypatch.setenv("CASK_WIDE_ROWS", "1" if rows == "wide_rows" else "0")
     lens = [100, 333, 1500, 3001]
     pref = [0, 33, 200, 0]
     c = _ragged_bf16(lens, pref, G=4, Wn=100, seed=5)
@@ -198,9 +202,10 @@ def test_bf16_single_query_head_small_window():
     _note(parity.full_check(c, p))
 
 
-@pytest.mark.parametrize("rows", ["wide_rows", "narrow_rows"])
+@pytest.mark.parametrize("rows", ["chosen", "narrow_rows", "wide_rows"])
 def test_cfg2_two_layers_full_length(rows, monkeypatch):
     monkeypatch.setenv("CASK_NARROW_ROWS", "1" if rows == "narrow_rows" else "0")
+    monkeypatch.setenv("CASK_WIDE_ROWS", "1" if rows == "wide_rows" else "0")
     w = caches.scaled(W["cfg2"], n_layers=2)
     c = caches.make(w)
     st = parity.full_check(c, parity.params_of(w))
@@ -722,6 +727,7 @@ def test_ragged_batch_llama_shape():
 
 @pytest.mark.parametrize("Wn,G,N,path", [(16, 3, 6000, "two_launches"), (64, 7, 6000, "two_launches"),
                                          (128, 7, 3000, "two_launches"), (128, 7, 3000, "two_launches_narrow"),
+                                         (128, 7, 3000, "two_launches_wide"), (16, 3, 6000, "two_launches_wide"),
                                          (128, 8, 3000, "two_launches"), (100, 3, 3000, "two_launches"),
                                          (128, 4, 5000, "one_launch_long"),
                                          (64, 2, 5000, "one_launch_long"), (32, 7, 900, "one_launch_short")])
@@ -736,6 +742,7 @@ def test_score_with_steep_logit_ramps(Wn, G, N, path):
     q /= np.linalg.norm(q)
     two = cask.binding.PATH_NO_FUSED_SWEEPS | cask.binding.PATH_NO_FUSED_SCORE
     flags = {"two_launches": two, "two_launches_narrow": two | cask.binding.PATH_NARROW_ROWS,
+             "two_launches_wide": two | cask.binding.PATH_WIDE_ROWS,
              "one_launch_long": cask.binding.PATH_FORCE_FUSED_SWEEPS, "one_launch_short": 0}[path]
     for direction in (+1, -1):
         ramp = np.linspace(0.0, 1.0, N, dtype=np.float32)
