@@ -396,10 +396,13 @@ def test_random_short_batches(seed, tail, monkeypatch):
     _note((seed, tail, dict(d=d, W=window, G=G, P=prefix, dec=(lo, hi), B=budget, core=core, R=recent), st))
 
 
+@pytest.mark.parametrize("rows", ["chosen", "wide_rows"])
 @pytest.mark.parametrize("seed", list(range(8)))
-def test_random_longer_batches(seed):
+def test_random_longer_batches(seed, rows, monkeypatch):
     """Seeded random shapes and parameters for ragged units of up to a few thousand rows: both
-    dtypes, both head dimensions, both merge geometries."""
+    dtypes, both head dimensions, both merge geometries; the scoring sweeps in the form the
+    library picks and forced into their wide form (it only exists for bf16, d = 128)."""
+    monkeypatch.setenv("CASK_WIDE_ROWS", "1" if rows == "wide_rows" else "0")
     rng = np.random.default_rng(3000 + seed)
     f32 = bool(rng.integers(0, 2))
     base = W["cfg1"] if f32 else W["cfg2"]
