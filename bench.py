@@ -402,8 +402,10 @@ def main():
                       else "score_mfma_kernel<3> (both sweeps in one launch)")
         passes = 2.0 if one_launch else 1.0
         achieved = passes * flops_pass / t_dom / 1e12
-        two_name = ("score_mfma_kernel<0> (score_rows)" if dom == "score_rows" else
-                    "score_mfma_kernel<1> (score_cols; its bracket also holds the kernel that combines the key splits)")
+        # (second template argument: resident 32-row tiles per wave, 4 in the wide form the library
+        # takes for these shapes, 2 in the narrow one)
+        two_name = ("score_mfma_kernel<0, CT> (score_rows)" if dom == "score_rows" else
+                    "score_mfma_kernel<1, CT> (score_cols; its bracket also holds the kernel that combines the key splits)")
         roof = {"bound": "mfma", "kernel": (fused_name if one_launch else two_name),
                 "achieved": round(achieved, 2), "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_MFMA_BF16_TFLOPS, 4),
