@@ -116,8 +116,11 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
 //
 // Workgroup: 4 waves, one per SIMD, and two workgroups per compute unit, so a SIMD always has a
 // second wave from an independent workgroup to run while the first sits in its prologue or at
-// a barrier.  Wave w keeps resident rows [64 w, 64 w + 64) of the workgroup's 256 as MFMA
-// B-operands in registers.  Stream rows arrive 64 at a time in a ring of LDS slots,
+// a barrier.  Wave w keeps CT resident tiles of 32 rows (rows [32 CT w, 32 CT (w + 1)) of the
+// workgroup's 128 CT) as MFMA B-operands in registers: CT = 2 in the narrow form, CT = 4 in the
+// wide form that the two separate sweeps take where the shape fills such blocks (every stream
+// operand read from LDS then serves four products instead of two; see pipelined_wide below).
+// Stream rows arrive 64 at a time in a ring of LDS slots,
 // written by direct global->LDS loads (no register staging, no LDS stores) that run
 // kDepth - 1 stages ahead of the stage being consumed; one barrier per stage both publishes a
 // slot and frees the one consumed before it.
@@ -128,7 +131,7 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
 // 16 consecutive bytes per row and groups 1088 bytes apart: conflict-free, and the eight
 // k-steps are plain immediate offsets (128 bytes apart).
 //
-// Per stage a wave runs four 32x32 tiles (rt0,ct0) (rt0,ct1) (rt1,ct0) (rt1,ct1),
+// Per stage a wave runs 2 CT tiles of 32x32, (rt0,ct0) ... (rt0,ct CT-1) (rt1,ct0) ...,
 // software-pipelined: the MFMA chain of a tile is issued interleaved, two logits per MFMA, with
 // the exp2 epilogue of the tile before it, so the matrix cores and the vector ALU of a wave
 // run at the same time; the epilogue of a stage's last tile rides on the next stage's first
