@@ -17,39 +17,45 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, int max_unit_len) {
   Workspace w;
   std::memset(&w, 0, sizeof(w));
-  // Resident window rows of the row-statistics sweep: 128 per wave (512 per workgroup: every
-  // stream operand read from LDS serves four products) when that leaves no more waves idle than
-  // 64 per wave (256 per workgroup) does; W*G = 896, 1024, 512, 384 take the wide form, 640 and
-  // 768 the narrow one.
-  {
-    const int live_w = (kp.Mq + 127) / 128, all_w = (kp.Mq + 511) / 512 * 4;
-    const int live_n = (kp.Mq + 63) / 64, all_n = (kp.Mq + 255) / 256 * 4;
-    w.wide_rows = (kp.Mq > 256 && (int64_t)live_w * all_n >= (int64_t)live_n * all_w) ? 1 : 0;
-    if (kp.path_flags & CASK_PATH_WIDE_ROWS) w.wide_rows = 1;
-    if (kp.path_flags & CASK_PATH_NARROW_ROWS) w.wide_rows = 0;
-  }
   // Key splits of the row-statistics sweep: more splits mean more, shorter workgroups (better
   // balance over the 512 workgroup slots, two per compute unit) but a fixed cost per workgroup.
   // Measured on this kernel, a launch takes about (rounds of 512 workgroups, rounded up to a
-  // half) x (stages per workgroup, twice that in the wide form, + 4); take the split count that
-  // minimises it (cfg2: 4 splits narrow, 8 wide).
-  const int block_rows = w.wide_rows ? 512 : 256;
-  const int row_blocks = (kp.Mq + block_rows - 1) / block_rows;
-  const int64_t pairs = (int64_t)n_units * row_blocks;
-  int n_splits = 1;
-  double best_cost = 0.0;
-  for (int sp = 1; sp <= 64; ++sp) {
-    const int len = (int)align_up((size_t)(max_unit_len + sp - 1) / sp, 64);
-    if (sp > 1 && len < 1024) break;
-    const int eff = len > 0 ? (max_unit_len + len - 1) / len : 1;
-    const int64_t wgs = pairs * eff;
-    const double rounds = 0.5 * (double)((wgs + 255) / 256);
-    const double cost = rounds * ((len / 64) * (w.wide_rows ? 2 : 1) + 4);
-    if (sp == 1 || cost < best_cost) {
-      best_cost = cost;
-      n_splits = sp;
+  // half) x (stages per workgroup + 4), a stage of the wide form counting 1.85 narrow ones (twice
+  // the products, less LDS traffic per product); take the split count that minimises it.
+  auto best_splits = [&](bool wide, double* cost_out) {
+    const int block_rows = wide ? 512 : 256;
+    const int64_t pairs = (int64_t)n_units * ((kp.Mq + block_rows - 1) / block_rows);
+    int best = 1;
+    double best_cost = 0.0;
+    for (int sp = 1; sp <= 64; ++sp) {
+      const int len = (int)align_up((size_t)(max_unit_len + sp - 1) / sp, 64);
+      if (sp > 1 && len < 1024) break;
+      const int eff = len > 0 ? (max_unit_len + len - 1) / len : 1;
+      const int64_t wgs = pairs * eff;
+      const double rounds = 0.5 * (double)((wgs + 255) / 256);
+      const double cost = rounds * ((len / 64) * (wide ? 1.85 : 1.0) + 4);
+      if (sp == 1 || cost < best_cost) {
+        best_cost = cost;
+        best = sp;
+      }
     }
+    *cost_out = best_cost;
+    return best;
+  };
+  // Resident window rows of that sweep: 128 per wave (512 per workgroup: every stream operand
+  // read from LDS serves four products) when that leaves no more waves idle than 64 per wave
+  // (256 per workgroup) does (W*G = 896, 1024, 512, 384: yes; 640, 768: no) and the model above
+  // does not prefer the narrow form (small batches: twice as many workgroups fill more of the chip).
+  double cost_n = 0.0, cost_w = 0.0;
+  const int splits_n = best_splits(false, &cost_n), splits_w = best_splits(true, &cost_w);
+  {
+    const int live_w = (kp.Mq + 127) / 128, all_w = (kp.Mq + 511) / 512 * 4;
+    const int live_n = (kp.Mq + 63) / 64, all_n = (kp.Mq + 255) / 256 * 4;
+    w.wide_rows = (kp.Mq > 256 && (int64_t)live_w * all_n >= (int64_t)live_n * all_w && cost_w <= cost_n) ? 1 : 0;
+    if (kp.path_flags & CASK_PATH_WIDE_ROWS) w.wide_rows = 1;
+    if (kp.path_flags & CASK_PATH_NARROW_ROWS) w.wide_rows = 0;
   }
+  int n_splits = w.wide_rows ? splits_w : splits_n;
   if (kp.score_splits >= 1) n_splits = kp.score_splits;
   int split_len = (int)align_up((size_t)(max_unit_len + n_splits - 1) / n_splits, 64);
   if (split_len < 64) split_len = 64;
