@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_split
 // pipeline with two more instructions per logit (a compare of the logit's constant row offset
 // with a per-lane limit, a select); only a sweep-A workgroup without a single clean stage, which
 // has no reference logit yet, takes a plain unpipelined path with a true running maximum.
-template <int MODE, int CT = 2>
+template <int MODE, int CT = 2, bool RING_RES = false>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     KParams kp, int n_units, int tiles_per_unit, int n_splits, int split_len, int q_splits, int mq_pad,
     const int64_t* __restrict__ row_off, const uint16_t* __restrict__ K,
@@ -167,6 +167,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // every stream operand read from LDS then serves four products instead of two)
   constexpr int kWaveRows = CT * 32;
   constexpr int kResRowsT = kWaves * kWaveRows;
+  // RING_RES: the resident rows come through the ring as well, in kResStages ring stages ahead
+  // of the stream (else they are loaded straight into registers and the ring starts with the stream)
+  constexpr int kResStages = RING_RES ? kResRowsT / kStageRows : 0;
   constexpr bool kRowPass = MODE != 1;
   constexpr bool kTwoPass = MODE >= 2;
   constexpr bool kWgReduce = MODE == 3;
@@ -238,15 +241,37 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // waves (stage % kWaves), so every wave has at most one extra load in flight
   const __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<float*>(bias + (size_t)unit * mq_pad), 0, mq_pad * 4, 0x00020000);
-  auto issue_stage = [&](int stage) {  // rows past s_end read as zero through the descriptor
+  // RING_RES: ring stages [0, kResStages) hold resident rows [res_base + 64 s, ...), each read out
+  // of LDS by the wave that owns those rows; ring stage kResStages + s is stream stage s.  Loaded
+  // straight into registers, a lane per row, every load instruction touches 32 rows at 32 bytes
+  // each: a workgroup of the wide sweep B spends 8 us on its resident keys.  Through the ring the
+  // loads are whole rows, but the stream waits behind them: it pays where workgroups are short
+  // (W*G <= 512: eight stream stages in sweep B) and costs elsewhere (measured both ways).
+  const __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(res_ptr), 0, res_limit * kRowBytes, 0x00020000);
+  // (two functions, and the resident phase below unrolled: where one call site could take
+  // either descriptor the compiler kept both in scratch memory and fetched one per call)
+  auto issue_resident = [&](int stage) {  // rows past the end read as zero through the descriptor
     unsigned char* slot = ring + (stage % kDepth) * kStageBytes;
+    const int roff = (res_base + stage * kStageRows) * kRowBytes;
+#pragma unroll
+    for (int j = 0; j < kLoadsPerThread; ++j) {
+      const int grp = wv + kWaves * j;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          res_rsrc, (__attribute__((address_space(3))) void*)(slot + grp * kGroupPitch),
+          16, ld_voff, roff + j * (4 * kWaves * kRowBytes), 0, 0);
+    }
+  };
+  auto issue_stage = [&](int stage) {  // ring stage >= kResStages; rows past s_end read as zero
+    unsigned char* slot = ring + (stage % kDepth) * kStageBytes;
+    const int sstage = stage - kResStages;
     // MODE 2: the stages of the second pass follow those of the first and read the same keys
-    const int src_stage = (kTwoPass && stage >= n_stages) ? stage - n_stages : stage;
+    const int src_stage = (kTwoPass && sstage >= n_stages) ? sstage - n_stages : sstage;
     const int soff = (s_begin + src_stage * kStageRows) * kRowBytes;
     if (MODE == 1 && (stage & (kWaves - 1)) == wv)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(
           brsrc, (__attribute__((address_space(3))) void*)(slot + kDataBytes), 4, lane * 4,
-          (s_begin + stage * kStageRows) * 4, 0, 0);
+          (s_begin + sstage * kStageRows) * 4, 0, 0);
 #pragma unroll
     for (int j = 0; j < kLoadsPerThread; ++j) {
       const int grp = wv + kWaves * j;
@@ -255,38 +280,78 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
           16, ld_voff, soff + j * (4 * kWaves * kRowBytes), 0, 0);
     }
   };
+  // Once per ring stage g: this thread's pieces of stages g and g + 1 have landed when at most
+  // (kDepth - 3) later stages of its loads are still in flight; the barrier extends that to
+  // every thread's pieces and tells everyone that the slot consumed before is free, so the next
+  // load can go there.  The barrier is bare: a fence here would drain the whole ring.
+  auto ring_wait = [&]() {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (((kDepth - 3) * kLoadsPerThread) & 0xF) |
+                               ((((kDepth - 3) * kLoadsPerThread) >> 4) << 14));
+    __builtin_amdgcn_s_barrier();
+  };
+  auto ring_sync = [&](int g) {  // g + kDepth - 1 >= kResStages
+    ring_wait();
+    issue_stage(g + kDepth - 1);
+  };
 
+  static_assert(!RING_RES || kResStages >= kDepth - 1, "the ring's first loads are resident rows");
   if (n_stages > 0) {
 #pragma unroll
-    for (int s = 0; s < kDepth - 1; ++s) issue_stage(s);
-  }
-
-  // ---- resident fragments: lane (c32, h) holds row c32 of each 32-row tile, k-chunk h.
-  // Loaded through a bounds-checked descriptor (rows past the end read as zero), after the
-  // ring's first loads are on their way so that the two latencies overlap.
-  const __amdgpu_buffer_rsrc_t res_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint16_t*>(res_ptr), 0, res_limit * kRowBytes, 0x00020000);
-  bf16x8 bres[CT][NK];
-  auto res_row_of = [&](int ct) { return res_base + wv * kWaveRows + ct * 32 + c32; };
-#pragma unroll
-  for (int ct = 0; ct < CT; ++ct) {
-    const int r = res_row_of(ct);
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(res_rsrc, r * kRowBytes + h * 16, ks * 32, 0);
-      bres[ct][ks] = __builtin_bit_cast(bf16x8, v);
+    for (int s = 0; s < kDepth - 1; ++s) {
+      if (RING_RES) issue_resident(s);
+      else issue_stage(s);
     }
   }
-  // a wave whose resident rows are all past the end only helps with loads and barriers
-  const bool wave_live = res_base + wv * kWaveRows < res_limit;
 
-  // A-operand rows of this lane inside a stage: row rt * 32 + c32 -> group, row-in-group
+  // Operand rows of this lane inside a stage: row rt * 32 + c32 -> group, row-in-group
+  // (lane (c32, h) holds row c32 of a 32-row tile, k-chunk h: the same layout for both operands)
   const int a_off = (c32 >> 2) * kGroupPitch + (c32 & 3) * 16 + h * 64;
   auto load_a = [&](bf16x8(&a)[NK], const unsigned char* slot, int rt) {
     const unsigned char* p = slot + rt * 8 * kGroupPitch + a_off;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(p + ks * 128);
   };
+
+  // ---- resident fragments: wave w owns ring stages [w CT / 2, (w + 1) CT / 2) of the resident
+  // phase, two 32-row tiles each
+  bf16x8 bres[CT][NK];
+  auto res_row_of = [&](int ct) { return res_base + wv * kWaveRows + ct * 32 + c32; };
+  if (!RING_RES) {
+    // straight into registers through a bounds-checked descriptor (rows past the end read as
+    // zero), after the ring's first loads are on their way so that the two latencies overlap
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+      const int r = res_row_of(ct);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(res_rsrc, r * kRowBytes + h * 16, ks * 32, 0);
+        bres[ct][ks] = __builtin_bit_cast(bf16x8, v);
+      }
+    }
+  } else if (n_stages > 0) {
+#pragma unroll
+    for (int g = 0; g < kResStages; ++g) {
+      ring_wait();
+      if (g + kDepth - 1 < kResStages) issue_resident(g + kDepth - 1);
+      else issue_stage(g + kDepth - 1);
+      const unsigned char* slot = ring + (g % kDepth) * kStageBytes;
+#pragma unroll
+      for (int q = 0; q < CT / 2; ++q)
+        if (g == wv * (CT / 2) + q) {
+          load_a(bres[2 * q], slot, 0);
+          load_a(bres[2 * q + 1], slot, 1);
+          // the rows are in registers before the wave lets the slot go at the next barrier
+          __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) alone
+        }
+    }
+  } else {
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+      for (int ks = 0; ks < NK; ++ks) bres[ct][ks] = bf16x8{0};
+  }
+  // a wave whose resident rows are all past the end only helps with loads and barriers
+  const bool wave_live = res_base + wv * kWaveRows < res_limit;
   // sweep B: -L of the lane's 16 rows of tile row rt (accumulator order)
   auto load_nl = [&](float (&nl)[16], const unsigned char* slot, int rt) {
     if (MODE == 1) {
@@ -446,19 +511,12 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(bres[ct][ks]));
-  // Once per stage: this thread's pieces of stages `it` and `it + 1` have landed when at most
-  // (kDepth - 3) later stages of its loads are still in flight; the barrier extends that to
-  // every thread's pieces and tells everyone that the slot consumed in the previous iteration
-  // is free, so the next load can go there.  Being one stage ahead lets a wave fetch the next
-  // stage's first operands from LDS while it is still busy with this one.  The barrier is
-  // bare: a fence here would drain the whole ring.
-  auto stage_sync = [&](int it) {
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (((kDepth - 3) * kLoadsPerThread) & 0xF) |
-                               ((((kDepth - 3) * kLoadsPerThread) >> 4) << 14));
-    __builtin_amdgcn_s_barrier();
-    issue_stage(it + kDepth - 1);
+  // Stream stage `it` is ring stage kResStages + it.  Being one stage ahead (see ring_sync) lets
+  // a wave fetch the next stage's first operands from LDS while it is still busy with this one.
+  auto stage_sync = [&](int it) { ring_sync(kResStages + it); };
+  auto slot_of = [&](int it) -> const unsigned char* {
+    return ring + ((kResStages + it) % kDepth) * kStageBytes;
   };
-  auto slot_of = [&](int it) -> const unsigned char* { return ring + (it % kDepth) * kStageBytes; };
   f32x16 acc0, acc1;
   bf16x8 a0[NK], a1[NK];
   float nl0[16], nl1[16];  // sweep B: -L of the rows of tile rows 0 and 1 of the stage in flight
@@ -1015,12 +1073,18 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   if (e == hipSuccess) e = limB.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<1>), 160 * 1024);
   if (e != hipSuccess) return e;
   const int qblocks = (kp.Mq + kResRows - 1) / kResRows;
+  // W*G <= 512 (one wide row block per unit, eight stream stages per workgroup of sweep B): the
+  // resident rows come through the ring (measured: both sweeps 3 - 4 % faster on the Llama-shaped
+  // batch, up to 4 % slower at W*G = 896)
+  const bool ring_res = kp.Mq <= 2 * kResRows;
   if (wl.wide_rows) {
-    static LdsLimitOnce limAw;
-    e = limAw.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<0, 4>), 160 * 1024);
+    static LdsLimitOnce limAw, limAr;
+    e = ring_res ? limAr.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<0, 4, true>), 160 * 1024)
+                 : limAw.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<0, 4>), 160 * 1024);
     if (e != hipSuccess) return e;
     const int tilesAw = (kp.Mq + 2 * kResRows - 1) / (2 * kResRows) * wl.n_splits;
-    score_mfma_kernel<0, 4><<<dim3(units8 * tilesAw), dim3(kThreads), ldsA, st>>>(
+    auto kern = ring_res ? &score_mfma_kernel<0, 4, true> : &score_mfma_kernel<0, 4>;
+    kern<<<dim3(units8 * tilesAw), dim3(kThreads), ldsA, st>>>(
         kp, b.n_units, tilesAw, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
         nullptr, bias, scores, nullptr, 0);
   } else {
@@ -1033,11 +1097,13 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   if (wl.n_splits > 1)  // with one split sweep A has written -L itself
     score_bias_kernel<<<dim3(b.n_units), dim3(256), 0, st>>>(kp, wl.n_splits, wl.mq_pad, rowstat, bias);
   if (wl.wide_cols) {
-    static LdsLimitOnce limBw;
-    e = limBw.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<1, 4>), 160 * 1024);
+    static LdsLimitOnce limBw, limBr;
+    e = ring_res ? limBr.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<1, 4, true>), 160 * 1024)
+                 : limBw.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<1, 4>), 160 * 1024);
     if (e != hipSuccess) return e;
     const int tilesBw = (b.max_unit_len + 2 * kResRows - 1) / (2 * kResRows) * wl.q_splits;
-    score_mfma_kernel<1, 4><<<dim3(units8 * tilesBw), dim3(kThreads), ldsB, st>>>(
+    auto kern = ring_res ? &score_mfma_kernel<1, 4, true> : &score_mfma_kernel<1, 4>;
+    kern<<<dim3(units8 * tilesBw), dim3(kThreads), ldsB, st>>>(
         kp, b.n_units, tilesBw, wl.n_splits, wl.split_len, wl.q_splits, wl.mq_pad, b.row_off, K, Q, rowstat,
         bias, nullptr, scores, nullptr, 0);
   } else {
