@@ -599,13 +599,16 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     }
     drain(masked, acc1, nl1, 1, s_begin + (to - 1) * kStageRows + 32);
   };
-  // Four resident tiles per wave (sweep A): a wave keeps ONE tile row's stream operands; while
-  // the last of the tile row's four chains consumes them k-step by k-step, each is replaced in
-  // place by the next tile row's (the 32 registers that saves, with the 64 the two more resident
-  // tiles cost, still fit two waves per SIMD).  Tiles of a stage in the order (tile row, resident
-  // tile) = (0,0) (0,1) (0,2) (0,3) (1,0) ... (1,3), accumulators alternating.
-  // `next_rows` (not null): the stream operands are replaced by the rows there; `next_nl` (not
-  // null, sweep B): the -L values, four at a time behind the two pieces that used them
+  // Wide form, four resident tiles per wave (both sweeps): a wave keeps ONE tile row's stream
+  // operands; while the last of the tile row's four chains consumes them k-step by k-step, each
+  // is replaced in place by the next tile row's (the 32 registers that saves, with the 64 the two
+  // more resident tiles cost, still fit two waves per SIMD).  Sweep B's 16 -L values of a tile
+  // row change hands the same way during the chain that carries the tile row's last epilogue.
+  // Tiles of a stage in the order (tile row, resident tile) = (0,0) (0,1) (0,2) (0,3) (1,0) ...
+  // (1,3), accumulators alternating.
+  // fused_refill: `refill_a`: the stream operands are replaced by the rows at `next_rows`;
+  // `refill_nl` (sweep B): the -L values by those at `next_nl`, four at a time behind the two
+  // pieces that used them.
   auto fused_refill = [&](auto masked, auto refill_a, auto refill_nl, f32x16& acc_new, bf16x8(&a)[NK],
                           int ct_new, const f32x16& acc_old, float (&nl)[16], int ct_old, int trow_old,
                           const unsigned char* next_rows, const unsigned char* next_nl) {
