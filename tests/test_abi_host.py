@@ -133,6 +133,27 @@ def test_workspace_size_is_sane(cask):
     assert cask.workspace_bytes(cask.Params(dtype=7), 1, 10, 10) == 0
 
 
+def test_split_choice_of_the_first_sweep_shows_in_the_workspace_size(cask):
+    """The per-split row statistics are the only part of the layout that depends on the number
+    of key splits, so the size tells which count the cost model took: on the headline shape 8
+    splits in the wide form of the sweep, 4 in the narrow one; a small batch stays narrow."""
+    from paper_2604_10900_amd import binding
+    kw = dict(q_per_kv=7, budget=384)
+    shape = (112, 112 * 8448, 8448)
+    auto = cask.workspace_bytes(cask.Params(**kw), *shape)
+    narrow = cask.workspace_bytes(cask.Params(path_flags=binding.PATH_NARROW_ROWS, **kw), *shape)
+    by_splits = {sp: cask.workspace_bytes(cask.Params(score_splits=sp, **kw), *shape) for sp in (2, 4, 8)}
+    assert by_splits[2] < by_splits[4] < by_splits[8]
+    assert auto == by_splits[8]
+    assert narrow == by_splits[4]
+    # one more split costs units x padded window rows x 8 bytes (up to the 256-byte rounding)
+    per_split = (by_splits[8] - by_splits[4]) / 4
+    assert abs(per_split - 112 * 896 * 8) <= 256
+    small = (8, 8 * 8448, 8448)
+    assert cask.workspace_bytes(cask.Params(**kw), *small) == \
+        cask.workspace_bytes(cask.Params(path_flags=binding.PATH_NARROW_ROWS, **kw), *small)
+
+
 def test_workspace_size_grows_with_every_argument(cask):
     """A workspace sized for longer units, more units or more rows also serves a smaller batch:
     the entry points lay it out again from the batch they get and only compare sizes."""
