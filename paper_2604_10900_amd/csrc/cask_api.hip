@@ -111,7 +111,6 @@ Workspace layout_workspace(const KParams& kp, int n_units, int64_t total_rows, i
   w.seg_row = take(rows * sizeof(int32_t));
   w.seg_start = take(units * ((size_t)kp.B + 1) * sizeof(int32_t));
   w.seed_rows = take(units * kp.B * sizeof(int32_t));
-  w.ord_of_slot = take(units * kp.B * sizeof(int32_t));
   w.n_merged = take(units * sizeof(int32_t));
   w.n_seeds = take(units * sizeof(int32_t));
   w.total = off;
@@ -334,14 +333,14 @@ int cask_consolidate(const cask_params* params, const cask_batch* batch, const f
   int32_t* seed_rows = reinterpret_cast<int32_t*>(w + wl.seed_rows);
   int32_t* n_seeds = reinterpret_cast<int32_t*>(w + wl.n_seeds);
   int32_t* assign_ord = reinterpret_cast<int32_t*>(w + wl.assign_ord);
-  hipError_t e = launch_index_roles(kp, b, role, nullptr, nullptr, nullptr, seed_rows, nullptr, n_seeds, st);
+  hipError_t e = launch_index_roles(kp, b, role, nullptr, nullptr, nullptr, seed_rows, n_seeds, st);
   if (e != hipSuccess) return CASK_EDEVICE;
   e = launch_similarity(kp, b, role, seed_rows, n_seeds, assign_ord, false, st);
   if (e != hipSuccess) return CASK_EDEVICE;
   e = launch_gather_merged(kp, b, role, assign_ord, nullptr, seed_rows,
                            reinterpret_cast<int32_t*>(w + wl.merged_row),
                            reinterpret_cast<int32_t*>(w + wl.merged_ord), nullptr, assign, 2,
-                           nullptr, n_seeds, nullptr, nullptr, st);
+                           nullptr, n_seeds, nullptr, nullptr, nullptr, st);
   return dev_rc(e);
 }
 
@@ -433,7 +432,6 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
   int32_t* seg_row = reinterpret_cast<int32_t*>(w + wl.seg_row);
   int32_t* seg_start = reinterpret_cast<int32_t*>(w + wl.seg_start);
   int32_t* seed_rows = reinterpret_cast<int32_t*>(w + wl.seed_rows);
-  int32_t* ord_of_slot = reinterpret_cast<int32_t*>(w + wl.ord_of_slot);
   int32_t* n_merged = reinterpret_cast<int32_t*>(w + wl.n_merged);
   int32_t* n_seeds = reinterpret_cast<int32_t*>(w + wl.n_seeds);
   hipError_t e;
@@ -476,12 +474,12 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
     if (e == hipSuccess) e = launch_dedup_seeds(kp, b, s, role, st);
     if (e != hipSuccess) return CASK_EDEVICE;
     rec.mark();
-    e = launch_index_roles(kp, b, role, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds, st);
+    e = launch_index_roles(kp, b, role, slot_of, out_src, out_len, seed_rows, n_seeds, st);
     if (e != hipSuccess) return CASK_EDEVICE;
     rec.mark();
   } else {
-    e = launch_select_index(kp, b, s, role, status, slot_of, out_src, out_len, seed_rows, ord_of_slot,
-                            n_seeds, st);
+    e = launch_select_index(kp, b, s, role, status, slot_of, out_src, out_len, seed_rows, n_seeds,
+                            st);
     if (e != hipSuccess) return CASK_EDEVICE;
     rec.mark();
     rec.mark();  // the ordered walk runs inside the select kernel here: its own stage reads as zero
@@ -489,12 +487,25 @@ int cask_compress_step(const cask_params* params, const cask_batch* batch, const
   e = launch_similarity(kp, b, role, seed_rows, n_seeds, assign_ord, true, st);
   if (e != hipSuccess) return CASK_EDEVICE;
   rec.mark();
+  // the rows that pass through unchanged are copied by spare workgroups of the grouping launch
+  CopyJob cj{};
+  cj.K = static_cast<const unsigned char*>(b.K);
+  cj.V = static_cast<const unsigned char*>(b.V);
+  cj.K_out = static_cast<unsigned char*>(K_out);
+  cj.V_out = static_cast<unsigned char*>(V_out);
+  cj.scores = s;
+  cj.in_count = in_count;
+  cj.out_src = out_src;
+  cj.out_len = out_len;
+  cj.out_mass = out_mass;
+  cj.out_count = out_count;
+  cj.out_stride = out_stride_rows;
   e = launch_gather_merged(kp, b, role, assign_ord, slot_of, seed_rows, merged_row, merged_ord,
-                           n_merged, assign, assign ? 1 : 0, status, n_seeds, seg_row, seg_start, st);
+                           n_merged, assign, assign ? 1 : 0, status, n_seeds, seg_row, seg_start,
+                           &cj, st);
   if (e != hipSuccess) return CASK_EDEVICE;
   rec.mark();
-  e = launch_emit(kp, b, s, out_src, out_len, ord_of_slot, seed_rows, n_seeds, slot_of, seg_row,
-                  seg_start, n_merged, K_out,
+  e = launch_emit(kp, b, s, seed_rows, n_seeds, slot_of, seg_row, seg_start, n_merged, K_out,
                   V_out, out_mass, in_count, out_count, out_stride_rows, st);
   rec.mark();
   return dev_rc(e);

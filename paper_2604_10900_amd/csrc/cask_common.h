@@ -192,7 +192,6 @@ struct Workspace {
   size_t seg_row;    // int32  [total_rows] per unit: the same rows grouped by seed ordinal, ascending inside a group
   size_t seg_start;  // int32  [n_units][B + 1] where each seed's group starts in seg_row
   size_t seed_rows;  // int32  [n_units][B] unit-local rows of the seeds, ascending
-  size_t ord_of_slot;// int32  [n_units][B] seed ordinal of an output slot, -1 if not a seed
   size_t n_merged;   // int32  [n_units]
   size_t n_seeds;    // int32  [n_units]
   size_t total;
@@ -243,12 +242,11 @@ hipError_t launch_dedup_seeds(const KParams& kp, const Batch& b, const float* sc
 // both stages of the selection and the ordered walk in one launch (whole-event path)
 hipError_t launch_select_index(const KParams& kp, const Batch& b, const float* scores,
                                uint8_t* role, int32_t* status, int32_t* slot_of, int32_t* out_src,
-                               int32_t* out_len, int32_t* seed_rows, int32_t* ord_of_slot,
-                               int32_t* n_seeds, hipStream_t st);
+                               int32_t* out_len, int32_t* seed_rows, int32_t* n_seeds,
+                               hipStream_t st);
 hipError_t launch_index_roles(const KParams& kp, const Batch& b, const uint8_t* role,
                               int32_t* slot_of, int32_t* out_src, int32_t* out_len,
-                              int32_t* seed_rows, int32_t* ord_of_slot, int32_t* n_seeds,
-                              hipStream_t st);
+                              int32_t* seed_rows, int32_t* n_seeds, hipStream_t st);
 hipError_t launch_mass_diag(const KParams& kp, const Batch& b, const float* scores,
                             const uint8_t* role, const float* out_mass, const int32_t* out_len,
                             float* rho, hipStream_t st);
@@ -257,12 +255,29 @@ hipError_t launch_mass_diag(const KParams& kp, const Batch& b, const float* scor
 hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* role,
                              const int32_t* seed_rows, const int32_t* n_seeds,
                              int32_t* assign_ord, bool roles_follow_plan, hipStream_t st);
+// Copy of the kept rows that rides in the launch that groups the donors (`n_units` and
+// `lane_bytes` are filled in by the launcher).
+struct CopyJob {
+  const unsigned char* K;
+  const unsigned char* V;
+  unsigned char* K_out;
+  unsigned char* V_out;
+  const float* scores;
+  const int32_t* in_count;
+  const int32_t* out_src;
+  const int32_t* out_len;
+  float* out_mass;
+  int32_t* out_count;
+  int out_stride;
+  int n_units;
+  int lane_bytes;
+};
 hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t* role,
                                 const int32_t* assign_ord, const int32_t* slot_of,
                                 const int32_t* seed_rows, int32_t* merged_row, int32_t* merged_ord,
                                 int32_t* n_merged, int32_t* assign_out, int assign_mode,
                                 int32_t* status, const int32_t* n_seeds, int32_t* seg_row,
-                                int32_t* seg_start, hipStream_t st);
+                                int32_t* seg_start, const CopyJob* copy, hipStream_t st);
 // Everything after scoring in one launch, for batches whose units all fit a workgroup (a row per
 // thread), bf16, cosine geometry; `tail_small_fits` says whether a batch qualifies.
 bool tail_small_fits(const KParams& kp, const Batch& b);
@@ -279,8 +294,9 @@ hipError_t launch_attend(const KParams& kp, int n_units, const void* Q, const vo
 hipError_t launch_group_diag(const KParams& kp, const Batch& b, const float* scores,
                              const int32_t* assign, const void* K_out, int out_stride,
                              float* dispersion, float* lost_mass, hipStream_t st);
+// Folds every seed that has donors into its output slot; the kept rows (the seeds' own among
+// them) were copied by the launch that grouped the donors (`launch_gather_merged` with a copy).
 hipError_t launch_emit(const KParams& kp, const Batch& b, const float* scores,
-                       const int32_t* out_src, const int32_t* out_len, const int32_t* ord_of_slot,
                        const int32_t* seed_rows, const int32_t* n_seeds, const int32_t* slot_of,
                        const int32_t* seg_row, const int32_t* seg_start,
                        const int32_t* n_merged, void* K_out, void* V_out, float* out_mass,

@@ -467,9 +467,81 @@ constexpr int kGatherPer = 16;  // 64-row groups per wave and chunk
 constexpr int kSegLds = 8192;   // seed ordinals whose segment cursors fit in LDS at a time
 constexpr int kSmallList = 64;  // donor lists up to this length are split by a single wave
 
+// row groups (of four rows) a copy wave handles one after the other; measured: two beat four
+// and one (a long prefix-heavy copy, B = 2048: 64 us against 76 and 74)
+constexpr int kCopyRounds = 2;
+
+// Copy of the rows an event keeps as they are (Sections 2.1, 2.4: protected tokens and the kept
+// part of the scratch stay untouched; only a seed with donors becomes a folded representative).
+// A wave owns 8 consecutive output slots of one unit, sixteen lanes a row (a sixteenth of the
+// row each); it puts the loads of its rows of K and V in flight before it touches any of them
+// and writes every slot, the seeds' too: the fold that follows in the stream overwrites the
+// seeds whose group has donors.  The copy needs nothing but the ordered walk's output, so it
+// shares a launch with the grouping of the donors, whose workgroups leave most of the chip
+// idle.  The row pieces are native vectors: with HIP's vector classes the staging arrays end up
+// in scratch memory.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <typename Vec, int PIECES>
+__device__ __forceinline__ void copy_kept_rows(const CopyJob& cj, int B,
+                                               const int64_t* __restrict__ row_off,
+                                               long long wave, int lane) {
+  constexpr int kSlotsPerWave = 4 * kCopyRounds;
+  constexpr int BPL = (int)sizeof(Vec) * PIECES;  // a lane's share of a row: a sixteenth of it
+  const int grp = lane >> 4, gl = lane & 15;
+  const int waves_per_unit = (B + kSlotsPerWave - 1) / kSlotsPerWave;
+  const int u = (int)(wave / waves_per_unit);
+  const int t_base = (int)(wave % waves_per_unit) * kSlotsPerWave;
+  if (u >= cj.n_units) return;
+  int slot[kCopyRounds], src[kCopyRounds], c0[kCopyRounds];
+  float a0[kCopyRounds];
+  Vec kraw[kCopyRounds][PIECES], vraw[kCopyRounds][PIECES];
+  // the slots' sources are read along with the unit's length, which says how many of them mean
+  // anything (every unit owns B slots of the array: one round trip instead of two)
+#pragma unroll
+  for (int j = 0; j < kCopyRounds; ++j) {
+    slot[j] = t_base + j * 4 + grp;
+    src[j] = slot[j] < B ? cj.out_src[(size_t)u * B + slot[j]] : -1;
+  }
+  const int len = cj.out_len[u];
+  if (t_base >= len) return;
+  const int64_t row0 = row_off[u];
+  const size_t pitch = (size_t)16 * BPL;
+#pragma unroll
+  for (int j = 0; j < kCopyRounds; ++j) {
+    if (slot[j] >= len) src[j] = -1;
+    // a slot past the unit's length reads the unit's first row and writes nothing
+    const int64_t row = row0 + max(src[j], 0);
+    const size_t at = (size_t)row * pitch + (size_t)gl * BPL;
+#pragma unroll
+    for (int q = 0; q < PIECES; ++q) {
+      kraw[j][q] = *reinterpret_cast<const Vec*>(cj.K + at + q * sizeof(Vec));
+      vraw[j][q] = *reinterpret_cast<const Vec*>(cj.V + at + q * sizeof(Vec));
+    }
+    a0[j] = cj.scores[row];
+    c0[j] = cj.in_count ? cj.in_count[row] : 1;
+  }
+#pragma unroll
+  for (int j = 0; j < kCopyRounds; ++j) {
+    if (src[j] < 0) continue;
+    const size_t at = ((size_t)u * cj.out_stride + slot[j]) * pitch + (size_t)gl * BPL;
+#pragma unroll
+    for (int q = 0; q < PIECES; ++q) {
+      *reinterpret_cast<Vec*>(cj.K_out + at + q * sizeof(Vec)) = kraw[j][q];
+      *reinterpret_cast<Vec*>(cj.V_out + at + q * sizeof(Vec)) = vraw[j][q];
+    }
+    if (cj.out_mass && gl == 0) cj.out_mass[(size_t)u * B + slot[j]] = a0[j];
+    if (cj.out_count && gl == 0) cj.out_count[(size_t)u * B + slot[j]] = c0[j];
+  }
+}
+
+// Workgroups below `n_gather` group the donors of one unit each; the ones above copy kept rows
+// (`cj.K_out` null: there are none).
 // assign_mode: 0 none, 1 output slot (whole event), 2 unit-local source row (consolidate API)
 __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
-    KParams kp, const int64_t* __restrict__ row_off, const int32_t* __restrict__ prefix_len,
+    KParams kp, int n_gather, CopyJob cj,
+    const int64_t* __restrict__ row_off, const int32_t* __restrict__ prefix_len,
     const uint8_t* __restrict__ role, const int32_t* __restrict__ assign_ord,
     const int32_t* __restrict__ slot_of, const int32_t* __restrict__ seed_rows,
     int32_t* __restrict__ merged_row, int32_t* __restrict__ merged_ord,
@@ -479,6 +551,13 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
   __shared__ int wsum[kGatherThreads / 64];
   __shared__ int cursor[kSegLds];
   const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (u >= n_gather) {
+    const long long wave = (long long)(u - n_gather) * (kGatherThreads / 64) + wv;
+    if (cj.lane_bytes == 16) copy_kept_rows<u32x4, 1>(cj, kp.B, row_off, wave, lane);
+    else if (cj.lane_bytes == 32) copy_kept_rows<u32x4, 2>(cj, kp.B, row_off, wave, lane);
+    else copy_kept_rows<u32x2, 1>(cj, kp.B, row_off, wave, lane);
+    return;
+  }
   const int64_t row0 = row_off[u];
   const int N = (int)(row_off[u + 1] - row0);
   const int P = prefix_len[u];
@@ -678,29 +757,19 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
   if (tid == 0) sstart[M] = count;
 }
 
-// ------------------------------------------------------------------ emit (copy + fold)
+// ------------------------------------------------------------------ emit (fold)
 
-// row groups (of four rows) a copy wave handles one after the other; measured: two beat four
-// and one (a long prefix-heavy copy, B = 2048: 64 us against 76 and 74)
-constexpr int kCopyRounds = 2;
-
-// One launch, two kinds of workgroup.  Sixteen lanes hold one row (D / 16 elements each).
-//
-// Copy workgroups: a wave owns 8 consecutive output slots of one unit, puts the loads of its
-// rows of K and V in flight before it touches any of them, and writes every slot that is not
-// a representative (a seed whose group of donors is empty is copied like any kept row).
-//
-// Fold workgroups: a wave owns one seed of one unit.  Its four 16-lane groups take the seed's
-// donors (one contiguous segment of the grouped donor list, ascending rows) round-robin, four
-// donors' loads in flight per group, accumulate in fp32 in ascending order, and the four
-// partial sums are added in a fixed tree, so the result does not depend on timing.
+// Sixteen lanes hold one row (D / 16 elements each).  A wave owns one seed of one unit.  Its
+// four 16-lane groups take the seed's donors (one contiguous segment of the grouped donor
+// list, ascending rows) round-robin, four donors' loads in flight per group, accumulate in
+// fp32 in ascending order, and the four partial sums are added in a fixed tree, so the result
+// does not depend on timing.  Runs after the launch that copied every kept row, the seeds'
+// own rows included, and overwrites the slots of the seeds that have donors.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void emit_kernel(
-    KParams kp, int n_units, int copy_blocks, int fold_per_unit,
+    KParams kp, int n_units, int fold_per_unit,
     const int64_t* __restrict__ row_off, const T* __restrict__ K, const T* __restrict__ V,
-    const float* __restrict__ scores,
-    const int32_t* __restrict__ out_src, const int32_t* __restrict__ out_len,
-    const int32_t* __restrict__ ord_of_slot, const int32_t* __restrict__ seed_rows,
+    const float* __restrict__ scores, const int32_t* __restrict__ seed_rows,
     const int32_t* __restrict__ n_seeds, const int32_t* __restrict__ slot_of,
     const int32_t* __restrict__ seg_row, const int32_t* __restrict__ seg_start,
     const int32_t* __restrict__ n_merged, T* __restrict__ K_out, T* __restrict__ V_out,
@@ -708,204 +777,143 @@ __global__ __launch_bounds__(256) void emit_kernel(
     int32_t* __restrict__ out_count, int out_stride) {
   constexpr int EPL = D / 16;                    // elements per lane
   constexpr int WORDS = EPL * sizeof(T) / 4;     // 32-bit words per lane
-  constexpr int kSlotsPerWave = 4 * kCopyRounds;
   struct alignas(WORDS * 4 > 16 ? 16 : WORDS * 4) Raw { uint32_t w[WORDS]; };
   const int lane = threadIdx.x & 63, grp = lane >> 4, gl = lane & 15;
   const int B = kp.B;
-
-  if ((int)blockIdx.x >= copy_blocks) {
-    // ---- fold role: work items are (unit, seed ordinal) pairs; each lane tests one item of
-    // a round (neighbouring ordinals go to different waves), then the wave folds the items
-    // that have donors one after the other.
-    const int NW = ((int)gridDim.x - copy_blocks) * 4;
-    const int w = ((int)blockIdx.x - copy_blocks) * 4 + (int)(threadIdx.x >> 6);
-    const long long items = (long long)n_units * fold_per_unit;
-    for (long long base = 0; base < items; base += 64LL * NW) {
-      const long long item = base + (long long)lane * NW + w;
-      int my_u = 0, my_ord = 0, my_s0 = 0, my_s1 = 0;
-      if (item < items) {
-        my_u = (int)(item / fold_per_unit);
-        my_ord = (int)(item % fold_per_unit);
-        // the segment bounds are read along with the counts that say whether they mean anything
-        // (the slots exist for every ordinal below B; one round trip instead of two)
-        const int s0 = seg_start[(size_t)my_u * (B + 1) + my_ord];
-        const int s1 = seg_start[(size_t)my_u * (B + 1) + my_ord + 1];
-        if (my_ord < n_seeds[my_u] && n_merged[my_u] > 0) {
-          my_s0 = s0;
-          my_s1 = s1;
-        }
+  // Work items are (unit, seed ordinal) pairs; each lane tests one item of a round
+  // (neighbouring ordinals go to different waves), then the wave folds the items that have
+  // donors one after the other.
+  const int NW = (int)gridDim.x * 4;
+  const int w = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
+  const long long items = (long long)n_units * fold_per_unit;
+  for (long long base = 0; base < items; base += 64LL * NW) {
+    const long long item = base + (long long)lane * NW + w;
+    int my_u = 0, my_ord = 0, my_s0 = 0, my_s1 = 0;
+    if (item < items) {
+      my_u = (int)(item / fold_per_unit);
+      my_ord = (int)(item % fold_per_unit);
+      // the segment bounds are read along with the counts that say whether they mean anything
+      // (the slots exist for every ordinal below B; one round trip instead of two)
+      const int s0 = seg_start[(size_t)my_u * (B + 1) + my_ord];
+      const int s1 = seg_start[(size_t)my_u * (B + 1) + my_ord + 1];
+      if (my_ord < n_seeds[my_u] && n_merged[my_u] > 0) {
+        my_s0 = s0;
+        my_s1 = s1;
       }
-      unsigned long long todo = __ballot(my_s1 > my_s0);
-      while (todo != 0ull) {
-        const int src_lane = __ffsll((long long)todo) - 1;
-        todo &= todo - 1ull;
-        const int u = __shfl(my_u, src_lane, 64), ord = __shfl(my_ord, src_lane, 64);
-        const int s0 = __shfl(my_s0, src_lane, 64), s1 = __shfl(my_s1, src_lane, 64);
-        const int64_t row0 = row_off[u];
-        const int32_t* seg = seg_row + row0;
-        const int srow = seed_rows[(size_t)u * B + ord];
-        const int slot = slot_of[row0 + srow];
-        float ka[EPL], va[EPL], ku[EPL], vu[EPL];  // score-weighted and count-weighted sums
-        float mass = 0.f;
-        int count = 0;
+    }
+    unsigned long long todo = __ballot(my_s1 > my_s0);
+    while (todo != 0ull) {
+      const int src_lane = __ffsll((long long)todo) - 1;
+      todo &= todo - 1ull;
+      const int u = __shfl(my_u, src_lane, 64), ord = __shfl(my_ord, src_lane, 64);
+      const int s0 = __shfl(my_s0, src_lane, 64), s1 = __shfl(my_s1, src_lane, 64);
+      const int64_t row0 = row_off[u];
+      const int32_t* seg = seg_row + row0;
+      const int srow = seed_rows[(size_t)u * B + ord];
+      const int slot = slot_of[row0 + srow];
+      float ka[EPL], va[EPL], ku[EPL], vu[EPL];  // score-weighted and count-weighted sums
+      float mass = 0.f;
+      int count = 0;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) ka[e] = va[e] = ku[e] = vu[e] = 0.f;
-        if (grp == 0) {  // the seed's own row opens the first group's sum
-          const float a = scores[row0 + srow];
-          const int c = in_count ? in_count[row0 + srow] : 1;
-          const Raw sk = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + srow) * D + gl * EPL);
-          const Raw sv = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + srow) * D + gl * EPL);
-          const T* skp = reinterpret_cast<const T*>(&sk);
-          const T* svp = reinterpret_cast<const T*>(&sv);
+      for (int e = 0; e < EPL; ++e) ka[e] = va[e] = ku[e] = vu[e] = 0.f;
+      if (grp == 0) {  // the seed's own row opens the first group's sum
+        const float a = scores[row0 + srow];
+        const int c = in_count ? in_count[row0 + srow] : 1;
+        const Raw sk = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + srow) * D + gl * EPL);
+        const Raw sv = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + srow) * D + gl * EPL);
+        const T* skp = reinterpret_cast<const T*>(&sk);
+        const T* svp = reinterpret_cast<const T*>(&sv);
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) {
-            const float kf = Elem<T>::load(skp + e), vf = Elem<T>::load(svp + e);
-            ka[e] = a * kf; va[e] = a * vf; ku[e] = (float)c * kf; vu[e] = (float)c * vf;
-          }
-          mass = a;
-          count = c;
+        for (int e = 0; e < EPL; ++e) {
+          const float kf = Elem<T>::load(skp + e), vf = Elem<T>::load(svp + e);
+          ka[e] = a * kf; va[e] = a * vf; ku[e] = (float)c * kf; vu[e] = (float)c * vf;
         }
-        for (int idx = s0 + grp; idx < s1; idx += 16) {
-          int drow[4], dc[4];
-          float a[4];
-          Raw dk[4], dv[4];
+        mass = a;
+        count = c;
+      }
+      for (int idx = s0 + grp; idx < s1; idx += 16) {
+        int drow[4], dc[4];
+        float a[4];
+        Raw dk[4], dv[4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) drow[q] = seg[min(idx + 4 * q, s1 - 1)];
+        for (int q = 0; q < 4; ++q) drow[q] = seg[min(idx + 4 * q, s1 - 1)];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            a[q] = scores[row0 + drow[q]];
-            dc[q] = in_count ? in_count[row0 + drow[q]] : 1;
-            dk[q] = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + drow[q]) * D + gl * EPL);
-            dv[q] = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + drow[q]) * D + gl * EPL);
-          }
+        for (int q = 0; q < 4; ++q) {
+          a[q] = scores[row0 + drow[q]];
+          dc[q] = in_count ? in_count[row0 + drow[q]] : 1;
+          dk[q] = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + drow[q]) * D + gl * EPL);
+          dv[q] = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + drow[q]) * D + gl * EPL);
+        }
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            if (idx + 4 * q < s1) {
-              const float dcf = (float)dc[q];
-              const T* dkp = reinterpret_cast<const T*>(&dk[q]);
-              const T* dvp = reinterpret_cast<const T*>(&dv[q]);
+        for (int q = 0; q < 4; ++q) {
+          if (idx + 4 * q < s1) {
+            const float dcf = (float)dc[q];
+            const T* dkp = reinterpret_cast<const T*>(&dk[q]);
+            const T* dvp = reinterpret_cast<const T*>(&dv[q]);
 #pragma unroll
-              for (int e = 0; e < EPL; ++e) {
-                const float kf = Elem<T>::load(dkp + e), vf = Elem<T>::load(dvp + e);
-                ka[e] = __builtin_fmaf(a[q], kf, ka[e]);
-                va[e] = __builtin_fmaf(a[q], vf, va[e]);
-                ku[e] = __builtin_fmaf(dcf, kf, ku[e]);
-                vu[e] = __builtin_fmaf(dcf, vf, vu[e]);
-              }
-              mass += a[q];
-              count += dc[q];
+            for (int e = 0; e < EPL; ++e) {
+              const float kf = Elem<T>::load(dkp + e), vf = Elem<T>::load(dvp + e);
+              ka[e] = __builtin_fmaf(a[q], kf, ka[e]);
+              va[e] = __builtin_fmaf(a[q], vf, va[e]);
+              ku[e] = __builtin_fmaf(dcf, kf, ku[e]);
+              vu[e] = __builtin_fmaf(dcf, vf, vu[e]);
             }
+            mass += a[q];
+            count += dc[q];
           }
-        }
-        // (g0 + g1) + (g2 + g3): addition commutes, so every lane ends with the same bits
-#pragma unroll
-        for (int o = 16; o <= 32; o <<= 1) {
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) {
-            ka[e] += __shfl_xor(ka[e], o, 64);
-            va[e] += __shfl_xor(va[e], o, 64);
-            ku[e] += __shfl_xor(ku[e], o, 64);
-            vu[e] += __shfl_xor(vu[e], o, 64);
-          }
-          mass += __shfl_xor(mass, o, 64);
-          count += __shfl_xor(count, o, 64);
-        }
-        if (grp == 0) {
-          const bool uniform = mass == 0.f;  // no score mass: average over the original tokens
-          const float denom = uniform ? (float)count : mass;
-          Raw ok_, ov_;
-          T* okp = reinterpret_cast<T*>(&ok_);
-          T* ovp = reinterpret_cast<T*>(&ov_);
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) {
-            Elem<T>::store(okp + e, (uniform ? ku[e] : ka[e]) / denom);
-            Elem<T>::store(ovp + e, (uniform ? vu[e] : va[e]) / denom);
-          }
-          *reinterpret_cast<Raw*>(K_out + ((size_t)u * out_stride + slot) * D + gl * EPL) = ok_;
-          *reinterpret_cast<Raw*>(V_out + ((size_t)u * out_stride + slot) * D + gl * EPL) = ov_;
-          if (out_mass && gl == 0) out_mass[(size_t)u * B + slot] = mass;
-          if (out_count && gl == 0) out_count[(size_t)u * B + slot] = count;
         }
       }
+      // (g0 + g1) + (g2 + g3): addition commutes, so every lane ends with the same bits
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          ka[e] += __shfl_xor(ka[e], o, 64);
+          va[e] += __shfl_xor(va[e], o, 64);
+          ku[e] += __shfl_xor(ku[e], o, 64);
+          vu[e] += __shfl_xor(vu[e], o, 64);
+        }
+        mass += __shfl_xor(mass, o, 64);
+        count += __shfl_xor(count, o, 64);
+      }
+      if (grp == 0) {
+        const bool uniform = mass == 0.f;  // no score mass: average over the original tokens
+        const float denom = uniform ? (float)count : mass;
+        Raw ok_, ov_;
+        T* okp = reinterpret_cast<T*>(&ok_);
+        T* ovp = reinterpret_cast<T*>(&ov_);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          Elem<T>::store(okp + e, (uniform ? ku[e] : ka[e]) / denom);
+          Elem<T>::store(ovp + e, (uniform ? vu[e] : va[e]) / denom);
+        }
+        *reinterpret_cast<Raw*>(K_out + ((size_t)u * out_stride + slot) * D + gl * EPL) = ok_;
+        *reinterpret_cast<Raw*>(V_out + ((size_t)u * out_stride + slot) * D + gl * EPL) = ov_;
+        if (out_mass && gl == 0) out_mass[(size_t)u * B + slot] = mass;
+        if (out_count && gl == 0) out_count[(size_t)u * B + slot] = count;
+      }
     }
-    return;
-  }
-
-  // ---- copy role
-  const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int waves_per_unit = (B + kSlotsPerWave - 1) / kSlotsPerWave;
-  const int u = (int)(wave / waves_per_unit);
-  const int t_base = (int)(wave % waves_per_unit) * kSlotsPerWave;
-  if (u >= n_units) return;
-  int slot[kCopyRounds], src[kCopyRounds], ord[kCopyRounds], c0[kCopyRounds];
-  float a0[kCopyRounds];
-  Raw kraw[kCopyRounds], vraw[kCopyRounds];
-  // the slots' sources are read along with the unit's length, which says how many of them mean
-  // anything (every unit owns B slots of these arrays: one round trip instead of two)
-#pragma unroll
-  for (int j = 0; j < kCopyRounds; ++j) {
-    slot[j] = t_base + j * 4 + grp;
-    const bool in = slot[j] < B;
-    src[j] = in ? out_src[(size_t)u * B + slot[j]] : -1;
-    ord[j] = in ? ord_of_slot[(size_t)u * B + slot[j]] : -1;
-  }
-  const int len = out_len[u];
-  if (t_base >= len) return;
-  const int64_t row0 = row_off[u];
-  const int nm = n_merged[u];
-  const int32_t* sstart = seg_start + (size_t)u * (B + 1);
-#pragma unroll
-  for (int j = 0; j < kCopyRounds; ++j) {
-    const bool ok = slot[j] < len;
-    src[j] = ok ? src[j] : -1;
-    ord[j] = (ok && nm > 0) ? ord[j] : -1;
-  }
-  // the row loads do not wait for the test below: a representative's row is loaded in vain
-#pragma unroll
-  for (int j = 0; j < kCopyRounds; ++j) {
-    if (src[j] >= 0) {
-      kraw[j] = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + src[j]) * D + gl * EPL);
-      vraw[j] = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + src[j]) * D + gl * EPL);
-      a0[j] = scores[row0 + src[j]];
-      c0[j] = in_count ? in_count[row0 + src[j]] : 1;
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < kCopyRounds; ++j) {
-    if (ord[j] >= 0 && sstart[ord[j] + 1] > sstart[ord[j]]) src[j] = -1;  // a fold wave writes it
-  }
-#pragma unroll
-  for (int j = 0; j < kCopyRounds; ++j) {
-    if (src[j] < 0) continue;
-    *reinterpret_cast<Raw*>(K_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL) = kraw[j];
-    *reinterpret_cast<Raw*>(V_out + ((size_t)u * out_stride + slot[j]) * D + gl * EPL) = vraw[j];
-    if (out_mass && gl == 0) out_mass[(size_t)u * B + slot[j]] = a0[j];
-    if (out_count && gl == 0) out_count[(size_t)u * B + slot[j]] = c0[j];
   }
 }
 
 template <typename T, int D>
 hipError_t launch_emit_t(const KParams& kp, const Batch& b, const float* scores,
-                         const int32_t* out_src, const int32_t* out_len,
-                         const int32_t* ord_of_slot, const int32_t* seed_rows,
-                         const int32_t* n_seeds, const int32_t* slot_of, const int32_t* seg_row,
+                         const int32_t* seed_rows, const int32_t* n_seeds,
+                         const int32_t* slot_of, const int32_t* seg_row,
                          const int32_t* seg_start, const int32_t* n_merged, void* K_out,
                          void* V_out, float* out_mass, const int32_t* in_count,
                          int32_t* out_count, int out_stride, hipStream_t st) {
-  const long long copy_waves = (long long)b.n_units * ((kp.B + 4 * kCopyRounds - 1) / (4 * kCopyRounds));
-  const long long copy_blocks = (copy_waves + 3) / 4;
   // (unit, seed ordinal) work items; a fold wave tests 64 of them per round
   const int fold_per_unit = plan_seed_bound(kp);
   const long long items = (long long)b.n_units * fold_per_unit;
   long long fold_blocks = (items + 3) / 4;     // an item per wave ...
   if (fold_blocks > 2048) fold_blocks = 2048;  // ... up to 8192 waves
-  if (copy_blocks + fold_blocks == 0) return hipSuccess;
-  if (copy_blocks + fold_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  emit_kernel<T, D><<<dim3((unsigned)(copy_blocks + fold_blocks)), dim3(256), 0, st>>>(
-      kp, b.n_units, (int)copy_blocks, fold_per_unit, b.row_off, static_cast<const T*>(b.K),
-      static_cast<const T*>(b.V), scores, out_src, out_len, ord_of_slot, seed_rows, n_seeds, slot_of,
-      seg_row, seg_start, n_merged, static_cast<T*>(K_out), static_cast<T*>(V_out), out_mass,
-      in_count, out_count, out_stride);
+  if (fold_blocks == 0) return hipSuccess;
+  emit_kernel<T, D><<<dim3((unsigned)fold_blocks), dim3(256), 0, st>>>(
+      kp, b.n_units, fold_per_unit, b.row_off, static_cast<const T*>(b.K),
+      static_cast<const T*>(b.V), scores, seed_rows, n_seeds, slot_of, seg_row, seg_start,
+      n_merged, static_cast<T*>(K_out), static_cast<T*>(V_out), out_mass, in_count, out_count,
+      out_stride);
   return hipGetLastError();
 }
 
@@ -1037,10 +1045,20 @@ hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t
                                 const int32_t* seed_rows, int32_t* merged_row, int32_t* merged_ord,
                                 int32_t* n_merged, int32_t* assign_out, int assign_mode,
                                 int32_t* status, const int32_t* n_seeds, int32_t* seg_row,
-                                int32_t* seg_start, hipStream_t st) {
+                                int32_t* seg_start, const CopyJob* copy, hipStream_t st) {
   static_assert((kGatherThreads / 64 & (kGatherThreads / 64 - 1)) == 0, "waves per block: a power of two");
-  gather_merged_kernel<<<dim3(b.n_units), dim3(kGatherThreads), 0, st>>>(
-      kp, b.row_off, b.prefix_len, role, assign_ord, slot_of, seed_rows, merged_row, merged_ord,
+  CopyJob cj{};
+  long long copy_blocks = 0;
+  if (copy && copy->K_out) {
+    cj = *copy;
+    cj.n_units = b.n_units;
+    cj.lane_bytes = kp.d * (kp.dtype == CASK_F32 ? 4 : 2) / 16;
+    const long long waves = (long long)b.n_units * ((kp.B + 4 * kCopyRounds - 1) / (4 * kCopyRounds));
+    copy_blocks = (waves + kGatherThreads / 64 - 1) / (kGatherThreads / 64);
+    if (b.n_units + copy_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  }
+  gather_merged_kernel<<<dim3((unsigned)(b.n_units + copy_blocks)), dim3(kGatherThreads), 0, st>>>(
+      kp, b.n_units, cj, b.row_off, b.prefix_len, role, assign_ord, slot_of, seed_rows, merged_row, merged_ord,
       n_merged, assign_out, assign_mode, status, n_seeds, seg_row, seg_start);
   return hipGetLastError();
 }
@@ -1062,16 +1080,14 @@ hipError_t launch_group_diag(const KParams& kp, const Batch& b, const float* sco
 }
 
 hipError_t launch_emit(const KParams& kp, const Batch& b, const float* scores,
-                       const int32_t* out_src, const int32_t* out_len, const int32_t* ord_of_slot,
                        const int32_t* seed_rows, const int32_t* n_seeds, const int32_t* slot_of,
                        const int32_t* seg_row, const int32_t* seg_start,
                        const int32_t* n_merged, void* K_out, void* V_out, float* out_mass,
                        const int32_t* in_count, int32_t* out_count, int out_stride,
                        hipStream_t st) {
-#define CASK_EMIT(T, D)                                                                          \
-  launch_emit_t<T, D>(kp, b, scores, out_src, out_len, ord_of_slot, seed_rows, n_seeds, slot_of, \
-                      seg_row, seg_start, n_merged, K_out, V_out, out_mass, in_count, out_count, \
-                      out_stride, st)
+#define CASK_EMIT(T, D)                                                                     \
+  launch_emit_t<T, D>(kp, b, scores, seed_rows, n_seeds, slot_of, seg_row, seg_start, n_merged, \
+                      K_out, V_out, out_mass, in_count, out_count, out_stride, st)
   if (kp.dtype == CASK_F32) return kp.d == 64 ? CASK_EMIT(float, 64) : CASK_EMIT(float, 128);
   return kp.d == 64 ? CASK_EMIT(uint16_t, 64) : CASK_EMIT(uint16_t, 128);
 #undef CASK_EMIT

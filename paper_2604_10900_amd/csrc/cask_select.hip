@@ -238,13 +238,12 @@ __device__ __forceinline__ bool role_is_kept(int r) {
 __device__ __forceinline__ void index_walk(const KParams& kp, int u, int64_t row0, int N,
                                            const uint8_t* __restrict__ ro, int32_t* __restrict__ slot_of,
                                            int32_t* __restrict__ out_src, int32_t* __restrict__ out_len,
-                                           int32_t* __restrict__ seed_rows, int32_t* __restrict__ ord_of_slot,
-                                           int32_t* __restrict__ n_seeds, int* wsum) {
+                                           int32_t* __restrict__ seed_rows, int32_t* __restrict__ n_seeds,
+                                           int* wsum) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int B = kp.B;
   int32_t* const slot_u = slot_of ? slot_of + row0 : nullptr;
   int32_t* const src_u = out_src ? out_src + (size_t)u * B : nullptr;
-  int32_t* const ord_u = ord_of_slot ? ord_of_slot + (size_t)u * B : nullptr;
   int32_t* const seed_u = seed_rows + (size_t)u * B;
   int kept_before = 0, seeds_before = 0;  // of the chunks walked so far
   for (int cb = 0; cb < N; cb += kSelThreads * kIdxPer) {
@@ -286,10 +285,7 @@ __device__ __forceinline__ void index_walk(const KParams& kp, int u, int64_t row
       const bool fits = role_is_kept(r[e]) && slot < B;
       if (i < N) {
         if (slot_u) slot_u[i] = fits ? slot : -1;
-        if (fits) {
-          if (src_u) src_u[slot] = i;
-          if (ord_u) ord_u[slot] = is_seed ? ord : -1;
-        }
+        if (fits && src_u) src_u[slot] = i;
         if (is_seed && ord < B) seed_u[ord] = i;
       }
     }
@@ -309,7 +305,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const float* __restrict__ scores, uint8_t* __restrict__ role, int32_t* __restrict__ status,
     int do_prefix, int do_decode, int do_index, int32_t* __restrict__ slot_of,
     int32_t* __restrict__ out_src, int32_t* __restrict__ out_len, int32_t* __restrict__ seed_rows,
-    int32_t* __restrict__ ord_of_slot, int32_t* __restrict__ n_seeds) {
+    int32_t* __restrict__ n_seeds) {
   __shared__ int hist[2 * 3 * 256 * kHistCopies];
   __shared__ int bcast[3 * 4];
   __shared__ int wsum[2 * kSelWaves];
@@ -451,20 +447,19 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     // the roles this workgroup just wrote are read back in index order: the barrier makes
     // them visible to all of its threads
     __syncthreads();
-    index_walk(kp, u, row0, N, ro, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds, wsum);
+    index_walk(kp, u, row0, N, ro, slot_of, out_src, out_len, seed_rows, n_seeds, wsum);
   }
 }
 
 __global__ __launch_bounds__(kSelThreads) void index_roles_kernel(
     KParams kp, const int64_t* __restrict__ row_off, const uint8_t* __restrict__ role,
     int32_t* __restrict__ slot_of, int32_t* __restrict__ out_src, int32_t* __restrict__ out_len,
-    int32_t* __restrict__ seed_rows, int32_t* __restrict__ ord_of_slot,
-    int32_t* __restrict__ n_seeds) {
+    int32_t* __restrict__ seed_rows, int32_t* __restrict__ n_seeds) {
   __shared__ int wsum[2 * kSelWaves];
   const int u = blockIdx.x;
   const int64_t row0 = row_off[u];
   const int N = (int)(row_off[u + 1] - row0);
-  index_walk(kp, u, row0, N, role + row0, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds, wsum);
+  index_walk(kp, u, row0, N, role + row0, slot_of, out_src, out_len, seed_rows, n_seeds, wsum);
 }
 
 // Representative-set mass diagnostics (Section 2.6): per unit
@@ -553,29 +548,28 @@ hipError_t launch_select(const KParams& kp, const Batch& b, const float* scores,
   with_select_instance(b.max_unit_len, [&](auto per) {
     select_kernel<decltype(per)::value><<<dim3(b.n_units), dim3(kSelThreads), 0, st>>>(
         kp, b.row_off, b.prefix_len, scores, role, status, do_prefix ? 1 : 0, do_decode ? 1 : 0, 0,
-        nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+        nullptr, nullptr, nullptr, nullptr, nullptr);
   });
   return hipGetLastError();
 }
 
 hipError_t launch_select_index(const KParams& kp, const Batch& b, const float* scores,
                                uint8_t* role, int32_t* status, int32_t* slot_of, int32_t* out_src,
-                               int32_t* out_len, int32_t* seed_rows, int32_t* ord_of_slot,
-                               int32_t* n_seeds, hipStream_t st) {
+                               int32_t* out_len, int32_t* seed_rows, int32_t* n_seeds,
+                               hipStream_t st) {
   with_select_instance(b.max_unit_len, [&](auto per) {
     select_kernel<decltype(per)::value><<<dim3(b.n_units), dim3(kSelThreads), 0, st>>>(
         kp, b.row_off, b.prefix_len, scores, role, status, 1, 1, 1, slot_of, out_src, out_len,
-        seed_rows, ord_of_slot, n_seeds);
+        seed_rows, n_seeds);
   });
   return hipGetLastError();
 }
 
 hipError_t launch_index_roles(const KParams& kp, const Batch& b, const uint8_t* role,
                               int32_t* slot_of, int32_t* out_src, int32_t* out_len,
-                              int32_t* seed_rows, int32_t* ord_of_slot, int32_t* n_seeds,
-                              hipStream_t st) {
+                              int32_t* seed_rows, int32_t* n_seeds, hipStream_t st) {
   index_roles_kernel<<<dim3(b.n_units), dim3(kSelThreads), 0, st>>>(
-      kp, b.row_off, role, slot_of, out_src, out_len, seed_rows, ord_of_slot, n_seeds);
+      kp, b.row_off, role, slot_of, out_src, out_len, seed_rows, n_seeds);
   return hipGetLastError();
 }
 
