@@ -33,13 +33,13 @@ PEAK_HBM_GBS = 8000.0
 # from the named summaries under profiles/, not measured by the run that prints them; a workload
 # without a summary, or a cut-down run (--layers / --seqs), reports null.
 PROFILED_TRAFFIC = {
-    "cfg2": {"bytes": (130986.2 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg2_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4>)"},
-    "cfg3": {"bytes": (475916.2 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg3_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4>)"},
-    "cfg4": {"bytes": (270760.3 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg4_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4>)"},
-    "cfg4v": {"bytes": (959110.1 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg4v_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4>)"},
+    "cfg2": {"bytes": (130980.6 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg2_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
+    "cfg3": {"bytes": (475827.7 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg3_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
+    "cfg4": {"bytes": (270773.6 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg4_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
+    "cfg4v": {"bytes": (959133.2 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg4v_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
     # (the slower of the two sweeps on this workload is the second one)
-    "cfg5": {"bytes": (42022986.2 * 2.0 + 1282968.0) * 1024, "source": "profiles/cfg5_kernels_and_hbm_traffic.md (score_mfma_kernel<1, 4, true>)"},
-    "cfg2ss": {"bytes": (22047.3 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg2ss_kernels_and_hbm_traffic.md (score_mfma_kernel<2, 2>)"},
+    "cfg5": {"bytes": (42022820.4 * 2.0 + 1282974.6) * 1024, "source": "profiles/cfg5_kernels_and_hbm_traffic.md (score_mfma_kernel<1, 4, true>)"},
+    "cfg2ss": {"bytes": (22078.1 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg2ss_kernels_and_hbm_traffic.md (score_mfma_kernel<2, 2, false>)"},
 }
 
 
@@ -375,12 +375,14 @@ def main():
     fold_path = {"folded_donors_per_event": folded_donors, "sim_threshold": args.sim_threshold}
     if stage_ms:
         esz = outs.K_out.element_size()
-        # emit reads K and V of every kept row and folded donor and writes K and V of the kept rows
-        emit_bytes = 2.0 * p.head_dim * esz * (n_assigned + float(out_len.sum()))
+        # The grouping launch also copies K and V of every kept row; emit reads K and V of the
+        # seeds that fold and of their donors and writes the folded rows: together every kept row
+        # and folded donor is read and every kept row is written, over the two stages.
+        moved = 2.0 * p.head_dim * esz * (n_assigned + float(out_len.sum()))
+        both = stage_ms["gather"] + stage_ms["emit"]
         fold_path.update({"gather_ms": round(stage_ms["gather"], 4), "emit_ms": round(stage_ms["emit"], 4),
-                          "emit_row_bytes": emit_bytes,
-                          "emit_GB/s": (round(emit_bytes / (stage_ms["emit"] * 1e-3) / 1e9, 1)
-                                        if stage_ms["emit"] > 0 else None)})
+                          "copy_fold_row_bytes": moved,
+                          "copy_fold_GB/s": round(moved / (both * 1e-3) / 1e9, 1) if both > 0 else None})
 
     # ---- roofline of the dominant kernel: one scoring sweep is one Q.K^T pass of
     # 2 * (W*G) * N * d flops per unit on the matrix cores
@@ -396,7 +398,7 @@ def main():
         t_dom = sweep_ms[dom] * 1e-3
         # Both sweeps as ONE launch, bracketed as the first stage (the second bracket is then
         # empty): short units (score_mfma_kernel<2>, with the one-launch tail), and many long units
-        # with W*G <= 512 (score_mfma_kernel<3>).  Told from the brackets themselves.
+        # with W*G <= 256 (score_mfma_kernel<3>).  Told from the brackets themselves.
         one_launch = w.dtype != "f32" and p.head_dim == 128 and sweep_ms["score_cols"] < 0.25 * sweep_ms["score_rows"]
         fused_name = ("score_mfma_kernel<2> (both sweeps in one launch, short units)" if int(lens.max()) <= 1024
                       else "score_mfma_kernel<3> (both sweeps in one launch)")
