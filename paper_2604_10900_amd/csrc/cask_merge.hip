@@ -8,6 +8,7 @@
 //                v~ = sum a_i v_i / m with a_i the token's score, accumulated in fp32 in
 //                ascending row order (fixed order: reruns are bitwise identical).
 #include "cask_common.h"
+#include <type_traits>
 
 namespace cask {
 
@@ -759,12 +760,16 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
 
 // ------------------------------------------------------------------ emit (fold)
 
-// Sixteen lanes hold one row (D / 16 elements each).  A wave owns one seed of one unit.  Its
-// four 16-lane groups take the seed's donors (one contiguous segment of the grouped donor
-// list, ascending rows) round-robin, four donors' loads in flight per group, accumulate in
-// fp32 in ascending order, and the four partial sums are added in a fixed tree, so the result
-// does not depend on timing.  Runs after the launch that copied every kept row, the seeds'
-// own rows included, and overwrites the slots of the seeds that have donors.
+// Sixteen lanes hold one row (D / 16 elements each).  A seed with up to kWaveFoldMax donors is
+// folded by one wave: its four 16-lane groups take the seed's donors (one contiguous segment of
+// the grouped donor list, ascending rows) round-robin, four donors' loads in flight per group,
+// accumulate in fp32 in ascending order, and the four partial sums are added in a fixed tree.
+// A longer group is folded by the four waves of a workgroup together (sixteen groups, the
+// waves' sums added in a fixed tree through LDS).  Either way the result depends on the group
+// alone, not on timing.  Runs after the launch that copied every kept row, the seeds' own rows
+// included, and overwrites the slots of the seeds that have donors.
+constexpr int kWaveFoldMax = 64;  // donors of one seed that a single wave folds (four rounds of its four groups)
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void emit_kernel(
     KParams kp, int n_units, int fold_per_unit,
@@ -778,15 +783,156 @@ __global__ __launch_bounds__(256) void emit_kernel(
   constexpr int EPL = D / 16;                    // elements per lane
   constexpr int WORDS = EPL * sizeof(T) / 4;     // 32-bit words per lane
   struct alignas(WORDS * 4 > 16 ? 16 : WORDS * 4) Raw { uint32_t w[WORDS]; };
-  const int lane = threadIdx.x & 63, grp = lane >> 4, gl = lane & 15;
+  __shared__ int long_item[256][4];              // (unit, ordinal, segment bounds) of the long groups of a round
+  __shared__ int n_long;
+  __shared__ float part[4][4 * EPL][16];         // the waves' sums of a group folded by all four
+  __shared__ float part_mass[4];
+  __shared__ int part_count[4];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, grp = lane >> 4, gl = lane & 15;
   const int B = kp.B;
+
+  // Folds the donors [s0, s1) of one seed.  `ng` 16-lane groups share them round-robin and this
+  // one is number `g`; with `all_waves` the groups are the workgroup's sixteen and the waves'
+  // sums are added through LDS as (w0 + w1) + (w2 + w3), else they are the wave's four.
+  auto fold_group = [&](int u, int ord, int s0, int s1, int g, auto ng_c, auto all_c) {
+    constexpr int ng = decltype(ng_c)::value;
+    constexpr bool all_waves = decltype(all_c)::value;
+    const int64_t row0 = row_off[u];
+    const int32_t* seg = seg_row + row0;
+    const int srow = seed_rows[(size_t)u * B + ord];
+    const int slot = slot_of[row0 + srow];
+    float ka[EPL], va[EPL], ku[EPL], vu[EPL];  // score-weighted and count-weighted sums
+    float mass = 0.f;
+    int count = 0;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) ka[e] = va[e] = ku[e] = vu[e] = 0.f;
+    if (g == 0) {  // the seed's own row opens the first group's sum
+      const float a = scores[row0 + srow];
+      const int c = in_count ? in_count[row0 + srow] : 1;
+      const Raw sk = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + srow) * D + gl * EPL);
+      const Raw sv = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + srow) * D + gl * EPL);
+      const T* skp = reinterpret_cast<const T*>(&sk);
+      const T* svp = reinterpret_cast<const T*>(&sv);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const float kf = Elem<T>::load(skp + e), vf = Elem<T>::load(svp + e);
+        ka[e] = a * kf; va[e] = a * vf; ku[e] = (float)c * kf; vu[e] = (float)c * vf;
+      }
+      mass = a;
+      count = c;
+    }
+    for (int idx = s0 + g; idx < s1; idx += 4 * ng) {
+      int drow[4], dc[4];
+      float a[4];
+      Raw dk[4], dv[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) drow[q] = seg[min(idx + ng * q, s1 - 1)];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        a[q] = scores[row0 + drow[q]];
+        dc[q] = in_count ? in_count[row0 + drow[q]] : 1;
+        dk[q] = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + drow[q]) * D + gl * EPL);
+        dv[q] = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + drow[q]) * D + gl * EPL);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (idx + ng * q < s1) {
+          const float dcf = (float)dc[q];
+          const T* dkp = reinterpret_cast<const T*>(&dk[q]);
+          const T* dvp = reinterpret_cast<const T*>(&dv[q]);
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            const float kf = Elem<T>::load(dkp + e), vf = Elem<T>::load(dvp + e);
+            ka[e] = __builtin_fmaf(a[q], kf, ka[e]);
+            va[e] = __builtin_fmaf(a[q], vf, va[e]);
+            ku[e] = __builtin_fmaf(dcf, kf, ku[e]);
+            vu[e] = __builtin_fmaf(dcf, vf, vu[e]);
+          }
+          mass += a[q];
+          count += dc[q];
+        }
+      }
+    }
+    // (g0 + g1) + (g2 + g3): addition commutes, so every lane ends with the same bits
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        ka[e] += __shfl_xor(ka[e], o, 64);
+        va[e] += __shfl_xor(va[e], o, 64);
+        ku[e] += __shfl_xor(ku[e], o, 64);
+        vu[e] += __shfl_xor(vu[e], o, 64);
+      }
+      mass += __shfl_xor(mass, o, 64);
+      count += __shfl_xor(count, o, 64);
+    }
+    if constexpr (all_waves) {
+      // The waves' sums meet in LDS.  Wave 0 adds them as (w0 + w1) + (w2 + w3), its 16-lane group
+      // q taking one of the four sums (score-weighted K, V, count-weighted K, V), and the two
+      // groups whose sums the result is made of write it.
+      if (grp == 0) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          part[wv][e][gl] = ka[e];
+          part[wv][EPL + e][gl] = va[e];
+          part[wv][2 * EPL + e][gl] = ku[e];
+          part[wv][3 * EPL + e][gl] = vu[e];
+        }
+        if (gl == 0) {
+          part_mass[wv] = mass;
+          part_count[wv] = count;
+        }
+      }
+      __syncthreads();
+      if (wv == 0) {
+        const float m = (part_mass[0] + part_mass[1]) + (part_mass[2] + part_mass[3]);
+        const int c = (part_count[0] + part_count[1]) + (part_count[2] + part_count[3]);
+        const bool uniform = m == 0.f;  // no score mass: average over the original tokens
+        const float denom = uniform ? (float)c : m;
+        if ((grp >= 2) == uniform) {
+          Raw o_;
+          T* op = reinterpret_cast<T*>(&o_);
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            const int k = grp * EPL + e;
+            Elem<T>::store(op + e, ((part[0][k][gl] + part[1][k][gl]) + (part[2][k][gl] + part[3][k][gl])) / denom);
+          }
+          T* dst = (grp & 1) ? V_out : K_out;
+          *reinterpret_cast<Raw*>(dst + ((size_t)u * out_stride + slot) * D + gl * EPL) = o_;
+        }
+        if (out_mass && lane == 0) out_mass[(size_t)u * B + slot] = m;
+        if (out_count && lane == 0) out_count[(size_t)u * B + slot] = c;
+      }
+      __syncthreads();  // the next group's sums go to the same place
+    } else if (grp == 0) {
+      const bool uniform = mass == 0.f;  // no score mass: average over the original tokens
+      const float denom = uniform ? (float)count : mass;
+      Raw ok_, ov_;
+      T* okp = reinterpret_cast<T*>(&ok_);
+      T* ovp = reinterpret_cast<T*>(&ov_);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        Elem<T>::store(okp + e, (uniform ? ku[e] : ka[e]) / denom);
+        Elem<T>::store(ovp + e, (uniform ? vu[e] : va[e]) / denom);
+      }
+      *reinterpret_cast<Raw*>(K_out + ((size_t)u * out_stride + slot) * D + gl * EPL) = ok_;
+      *reinterpret_cast<Raw*>(V_out + ((size_t)u * out_stride + slot) * D + gl * EPL) = ov_;
+      if (out_mass && gl == 0) out_mass[(size_t)u * B + slot] = mass;
+      if (out_count && gl == 0) out_count[(size_t)u * B + slot] = count;
+    }
+  };
+
   // Work items are (unit, seed ordinal) pairs; each lane tests one item of a round
-  // (neighbouring ordinals go to different waves), then the wave folds the items that have
-  // donors one after the other.
+  // (neighbouring ordinals go to different waves).  A wave folds its items that have up to
+  // kWaveFoldMax donors one after the other; the longer ones are put on a list and folded by
+  // the whole workgroup, one after the other: a seed that gathered a thousand donors is
+  // otherwise a chain of sixty dependent round trips in one wave while the chip idles.
   const int NW = (int)gridDim.x * 4;
-  const int w = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
+  const int w = (int)blockIdx.x * 4 + wv;
   const long long items = (long long)n_units * fold_per_unit;
-  for (long long base = 0; base < items; base += 64LL * NW) {
+  for (long long base = 0; base < items; base += 64LL * NW) {  // (the same trips in every wave)
+    if (threadIdx.x == 0) n_long = 0;
+    __syncthreads();
     const long long item = base + (long long)lane * NW + w;
     int my_u = 0, my_ord = 0, my_s0 = 0, my_s1 = 0;
     if (item < items) {
@@ -801,98 +947,26 @@ __global__ __launch_bounds__(256) void emit_kernel(
         my_s1 = s1;
       }
     }
-    unsigned long long todo = __ballot(my_s1 > my_s0);
+    if (my_s1 - my_s0 > kWaveFoldMax) {
+      const int at = atomicAdd(&n_long, 1);  // (the order on the list does not reach the results)
+      long_item[at][0] = my_u;
+      long_item[at][1] = my_ord;
+      long_item[at][2] = my_s0;
+      long_item[at][3] = my_s1;
+    }
+    unsigned long long todo = __ballot(my_s1 > my_s0 && my_s1 - my_s0 <= kWaveFoldMax);
     while (todo != 0ull) {
       const int src_lane = __ffsll((long long)todo) - 1;
       todo &= todo - 1ull;
-      const int u = __shfl(my_u, src_lane, 64), ord = __shfl(my_ord, src_lane, 64);
-      const int s0 = __shfl(my_s0, src_lane, 64), s1 = __shfl(my_s1, src_lane, 64);
-      const int64_t row0 = row_off[u];
-      const int32_t* seg = seg_row + row0;
-      const int srow = seed_rows[(size_t)u * B + ord];
-      const int slot = slot_of[row0 + srow];
-      float ka[EPL], va[EPL], ku[EPL], vu[EPL];  // score-weighted and count-weighted sums
-      float mass = 0.f;
-      int count = 0;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) ka[e] = va[e] = ku[e] = vu[e] = 0.f;
-      if (grp == 0) {  // the seed's own row opens the first group's sum
-        const float a = scores[row0 + srow];
-        const int c = in_count ? in_count[row0 + srow] : 1;
-        const Raw sk = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + srow) * D + gl * EPL);
-        const Raw sv = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + srow) * D + gl * EPL);
-        const T* skp = reinterpret_cast<const T*>(&sk);
-        const T* svp = reinterpret_cast<const T*>(&sv);
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-          const float kf = Elem<T>::load(skp + e), vf = Elem<T>::load(svp + e);
-          ka[e] = a * kf; va[e] = a * vf; ku[e] = (float)c * kf; vu[e] = (float)c * vf;
-        }
-        mass = a;
-        count = c;
-      }
-      for (int idx = s0 + grp; idx < s1; idx += 16) {
-        int drow[4], dc[4];
-        float a[4];
-        Raw dk[4], dv[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) drow[q] = seg[min(idx + 4 * q, s1 - 1)];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          a[q] = scores[row0 + drow[q]];
-          dc[q] = in_count ? in_count[row0 + drow[q]] : 1;
-          dk[q] = *reinterpret_cast<const Raw*>(K + (size_t)(row0 + drow[q]) * D + gl * EPL);
-          dv[q] = *reinterpret_cast<const Raw*>(V + (size_t)(row0 + drow[q]) * D + gl * EPL);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if (idx + 4 * q < s1) {
-            const float dcf = (float)dc[q];
-            const T* dkp = reinterpret_cast<const T*>(&dk[q]);
-            const T* dvp = reinterpret_cast<const T*>(&dv[q]);
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) {
-              const float kf = Elem<T>::load(dkp + e), vf = Elem<T>::load(dvp + e);
-              ka[e] = __builtin_fmaf(a[q], kf, ka[e]);
-              va[e] = __builtin_fmaf(a[q], vf, va[e]);
-              ku[e] = __builtin_fmaf(dcf, kf, ku[e]);
-              vu[e] = __builtin_fmaf(dcf, vf, vu[e]);
-            }
-            mass += a[q];
-            count += dc[q];
-          }
-        }
-      }
-      // (g0 + g1) + (g2 + g3): addition commutes, so every lane ends with the same bits
-#pragma unroll
-      for (int o = 16; o <= 32; o <<= 1) {
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-          ka[e] += __shfl_xor(ka[e], o, 64);
-          va[e] += __shfl_xor(va[e], o, 64);
-          ku[e] += __shfl_xor(ku[e], o, 64);
-          vu[e] += __shfl_xor(vu[e], o, 64);
-        }
-        mass += __shfl_xor(mass, o, 64);
-        count += __shfl_xor(count, o, 64);
-      }
-      if (grp == 0) {
-        const bool uniform = mass == 0.f;  // no score mass: average over the original tokens
-        const float denom = uniform ? (float)count : mass;
-        Raw ok_, ov_;
-        T* okp = reinterpret_cast<T*>(&ok_);
-        T* ovp = reinterpret_cast<T*>(&ov_);
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) {
-          Elem<T>::store(okp + e, (uniform ? ku[e] : ka[e]) / denom);
-          Elem<T>::store(ovp + e, (uniform ? vu[e] : va[e]) / denom);
-        }
-        *reinterpret_cast<Raw*>(K_out + ((size_t)u * out_stride + slot) * D + gl * EPL) = ok_;
-        *reinterpret_cast<Raw*>(V_out + ((size_t)u * out_stride + slot) * D + gl * EPL) = ov_;
-        if (out_mass && gl == 0) out_mass[(size_t)u * B + slot] = mass;
-        if (out_count && gl == 0) out_count[(size_t)u * B + slot] = count;
-      }
+      fold_group(__shfl(my_u, src_lane, 64), __shfl(my_ord, src_lane, 64), __shfl(my_s0, src_lane, 64),
+                 __shfl(my_s1, src_lane, 64), grp, std::integral_constant<int, 4>{}, std::false_type{});
     }
+    __syncthreads();
+    const int nl = n_long;
+    for (int i = 0; i < nl; ++i)
+      fold_group(long_item[i][0], long_item[i][1], long_item[i][2], long_item[i][3], wv * 4 + grp,
+                 std::integral_constant<int, 16>{}, std::true_type{});
+    __syncthreads();  // everyone has read the list's length before it is cleared
   }
 }
 

@@ -946,6 +946,54 @@ def test_donor_list_lengths_around_the_short_list_split(n_fold):
     assert parity.check_values(p, got, want, Kb.reshape(2 * N, d), Vb.reshape(2 * N, d), row_off) >= min(n_fold, M)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_group_sizes_around_the_single_wave_fold_limit(dtype):
+    """One seed each with 1, 63, 64, 65, 200 and 1500 donors (copies of the seed's key, scaled)
+    in a unit, and a second unit with one group of 700: a seed with up to 64 donors is folded
+    by one wave, a longer group by the four waves of a workgroup whose sums meet in LDS.
+    Scores injected, so roles are exact; V random, so every donor's weight shows."""
+    d, N, Wn, n_core, M = 128, 3000, 64, 20, 16
+    dt = cask.BF16 if dtype == "bf16" else cask.F32
+    rng = np.random.default_rng(911)
+    Ks, Vs, ss, expect = [], [], [], []
+    for sizes in ([1, 63, 64, 65, 200, 1500], [700]):
+        K = rng.integers(-4, 5, (N, d)).astype(np.float32)
+        V = rng.integers(-4, 5, (N, d)).astype(np.float32)
+        s = (1e-3 * (1.0 + rng.permutation(N))).astype(np.float32) / N   # distinct, small
+        free = rng.permutation(N - Wn)
+        core, seeds, rest = free[:n_core], free[n_core:n_core + M], free[n_core + M:]
+        s[core] = 0.5 + 1e-3 * np.arange(n_core, dtype=np.float32)
+        s[seeds] = 0.25 + 1e-3 * np.arange(M, dtype=np.float32)
+        at = 0
+        for j, n in enumerate(sizes):
+            for i, r in enumerate(rest[at:at + n]):
+                K[r] = K[seeds[j]] * (2.0 if i % 2 else 1.0)              # cosine 1 with that seed
+            at += n
+        Ks.append(K); Vs.append(V); ss.append(s); expect.append(sum(sizes))
+    p = cask.Params(dtype=dt, head_dim=d, q_per_kv=1, window=Wn, budget=Wn + n_core + M,
+                    core=n_core, prefix_budget=0, sim_threshold=0.999)
+    rp = parity.ref_params(p)
+    tt = (lambda x: torch.from_numpy(x).to(torch.bfloat16)) if dtype == "bf16" else torch.from_numpy
+    Kc, Vc, sc = np.concatenate(Ks), np.concatenate(Vs), np.concatenate(ss)
+    c = dict(K=tt(Kc), V=tt(Vc), Q=tt(np.zeros((2, Wn, 1, d), np.float32)),
+             row_off=torch.tensor([0, N, 2 * N], dtype=torch.int64), prefix_len=torch.tensor([0, 0], dtype=torch.int32))
+    row_off, prefix_len, Kb, Vb, Qb = parity.host_arrays(c)
+    want = ref.compress(rp, row_off, prefix_len, Kb, Vb, Qb, scores=sc)
+    folded = [int((want["assign"][u * N:(u + 1) * N] >= 0).sum() - want["out_len"][u]) for u in range(2)]
+    assert folded == expect, folded
+    b = parity.to_device(c, p)
+    outs = [parity.gpu_outputs(cask.compress(b, scores=torch.from_numpy(sc).cuda()), p) for _ in range(2)]
+    torch.cuda.synchronize()
+    got = outs[0]
+    for k in got:
+        assert np.array_equal(got[k], outs[1][k]), k          # the same bits on a second run
+    assert np.array_equal(got["out_len"], want["out_len"])
+    assert np.array_equal(got["out_src"], want["out_src"])
+    assert np.array_equal(got["assign"], want["assign"])
+    assert np.array_equal(got["status"], want["status"])
+    assert parity.check_values(p, got, want, Kb.reshape(2 * N, d), Vb.reshape(2 * N, d), row_off) == 7
+
+
 # ------------------------------------------------------------------ determinism, errors, edges
 
 @pytest.mark.parametrize("decode", [2500, 700])
