@@ -650,10 +650,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
   if (seg_row == nullptr || count == 0) return;  // count is the same in every thread
 
   // Second pass: the same donors grouped by seed ordinal, rows still ascending inside a group
-  // (a stable split), so that a seed's fold reads one contiguous segment.  Histogram and scan
-  // give the segment starts; then wave w places the ordinals congruent to w modulo 16, walking
-  // the whole list in order, so no two waves ever touch the same cursor and the order inside a
-  // segment is the list's.  Ordinals are handled kSegLds at a time.
+  // (a stable split), so that a seed's fold reads one contiguous segment.
   __syncthreads();  // the list written above is read by other threads below
   const int M = n_seeds[u];
   const int32_t* mrow = merged_row + row0;
@@ -681,25 +678,42 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
     }
     return;
   }
+  // Longer lists: every wave owns a contiguous run of the list.  Per range of kWaveOrds
+  // ordinals: a histogram per wave in LDS, from which every (wave, ordinal) pair gets the place
+  // of its first entry (the segment's start plus what the earlier waves hold of that ordinal).
+  // Then a wave walks its run 64 entries at a time: an entry's place is its pair's cursor plus
+  // the number of earlier lanes with the same ordinal (the lanes that agree in every bit of the
+  // ordinal: one ballot per bit), so rows stay ascending inside a segment and no two waves
+  // touch the same cursor.
+  constexpr int NWV = kGatherThreads / 64;
+  constexpr int kWaveOrds = kSegLds / NWV;  // ordinals per range: a cursor per wave and ordinal
+  static_assert(kWaveOrds <= kGatherThreads, "a thread per ordinal of a range");
+  const int run = (count + NWV * 64 - 1) / (NWV * 64) * 64;
+  const int c0 = min(count, wv * run), c1 = min(count, c0 + run);
+  int* const my_cursor = cursor + wv * kWaveOrds;
   int base = 0;
-  for (int o_lo = 0; o_lo < M; o_lo += kSegLds) {
-    const int range = min(kSegLds, M - o_lo);
-    for (int q = tid; q < range; q += kGatherThreads) cursor[q] = 0;
+  for (int o_lo = 0; o_lo < M; o_lo += kWaveOrds) {
+    const int range = min(kWaveOrds, M - o_lo);
+    int nbits = 1;
+    while ((1 << nbits) < range) ++nbits;
+    for (int q = tid; q < kSegLds; q += kGatherThreads) cursor[q] = 0;
     __syncthreads();
-    for (int idx = tid; idx < count; idx += kGatherThreads) {
+    for (int idx = c0 + lane; idx < c1; idx += 64) {
       const int o = mord[idx] - o_lo;
-      if (o >= 0 && o < range) atomicAdd(&cursor[o], 1);
+      if (o >= 0 && o < range) atomicAdd(&my_cursor[o], 1);
     }
     __syncthreads();
-    constexpr int PER = kSegLds / kGatherThreads;
-    int loc[PER], sum = 0;
-#pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      const int q = tid * PER + e;
-      loc[e] = q < range ? cursor[q] : 0;
-      sum += loc[e];
+    // thread q: ordinal o_lo + q.  Its entries per wave become the waves' offsets inside the
+    // segment; the segment starts come from a scan of the totals.
+    int total = 0;
+    if (tid < range) {
+      for (int w = 0; w < NWV; ++w) {
+        const int t = cursor[w * kWaveOrds + tid];
+        cursor[w * kWaveOrds + tid] = total;
+        total += t;
+      }
     }
-    int incl = sum;
+    int incl = total;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
       const int y = __shfl_up(incl, o, 64);
@@ -708,52 +722,47 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
     if (lane == 63) wsum[wv] = incl;
     __syncthreads();
     int before = 0, tot = 0;
-    for (int w = 0; w < kGatherThreads / 64; ++w) {
+    for (int w = 0; w < NWV; ++w) {
       const int x = wsum[w];
       if (w < wv) before += x;
       tot += x;
     }
-    int at = base + before + (incl - sum);
-#pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      const int q = tid * PER + e;
-      if (q < range) {
-        cursor[q] = at;
-        sstart[o_lo + q] = at;
-        at += loc[e];
-      }
+    if (tid < range) {
+      const int start = base + before + (incl - total);
+      sstart[o_lo + tid] = start;
+      for (int w = 0; w < NWV; ++w) cursor[w * kWaveOrds + tid] += start;
     }
     base += tot;
     __syncthreads();
     constexpr int kAhead = 4;  // 64-entry steps whose loads are in flight together
-    for (int i0 = 0; i0 < count; i0 += 64 * kAhead) {
+    for (int i0 = c0; i0 < c1; i0 += 64 * kAhead) {
       int os[kAhead], rs[kAhead];
 #pragma unroll
       for (int e = 0; e < kAhead; ++e) {
-        const int idx = min(i0 + e * 64 + lane, count - 1);  // clamped: no branch around the loads
+        const int idx = min(i0 + e * 64 + lane, c1 - 1);  // clamped: no branch around the loads
         os[e] = mord[idx];
         rs[e] = mrow[idx];
       }
 #pragma unroll
       for (int e = 0; e < kAhead; ++e) {
         const int idx = i0 + e * 64 + lane;
-        const int o = idx < count ? os[e] - o_lo : -1;
-        const int drow = rs[e];
-        const bool mine = o >= 0 && o < range && (o & (kGatherThreads / 64 - 1)) == wv;
-        unsigned long long todo = __ballot(mine);
-        while (todo != 0ull) {
-          const int l = __ffsll((long long)todo) - 1;
-          const int v = __shfl(o, l, 64);
-          const bool in = mine && o == v;
-          const unsigned long long m = __ballot(in);
-          const int c = cursor[v];
-          if (in) seg_row[row0 + c + __popcll(m & below)] = drow;
-          if (lane == l) cursor[v] = c + __popcll(m);
-          todo &= ~m;
+        const int o = os[e] - o_lo;
+        const bool valid = idx < c1 && o >= 0 && o < range;
+        unsigned long long same = __ballot(valid);
+        for (int bit = 0; bit < nbits; ++bit) {
+          const bool one = ((o >> bit) & 1) != 0;
+          const unsigned long long ones = __ballot(valid && one);
+          same &= one ? ones : ~ones;
+        }
+        if (valid) {  // `same`: the valid lanes with this lane's ordinal
+          const int rank = __popcll(same & below);
+          const int cur = my_cursor[o];
+          seg_row[row0 + cur + rank] = rs[e];
+          if (rank == __popcll(same) - 1) my_cursor[o] = cur + rank + 1;  // (after every lane's read)
         }
       }
     }
-    __syncthreads();
+    __syncthreads();  // the cursors are cleared for the next range
   }
   if (tid == 0) sstart[M] = count;
 }

@@ -273,8 +273,8 @@ def test_every_donor_folds(case):
 
 
 def test_more_seeds_than_one_cursor_pass():
-    """More than 8192 seeds in a unit: the stable split of the donor list by seed takes two
-    passes over the ordinals."""
+    """More than 8192 seeds in a unit: the stable split of the donor list by seed takes the
+    ordinals a range at a time (seventeen ranges here)."""
     w = caches.scaled(W["cfg1"], n_seqs=1, n_layers=1, n_kv_heads=1, prefix=40, decode=15000, budget=9400,
                       cluster_frac=0.6)
     c = caches.make(w, seed=43)
