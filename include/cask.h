@@ -304,7 +304,8 @@ int cask_attend(const cask_params* params, int32_t n_units, const void* Q, const
  * (row statistics), 1 score sweep B (column mass; with the small kernel that combines the row
  * statistics of several key splits in front of it), 2 select (with the ordered walk over the
  * roles, which cask_compress runs in the same kernel), 3 index roles (zero in cask_compress),
- * 4 similarity, 5 gather merged donors, 6 emit.  A batch of short units (every unit at most
+ * 4 similarity, 5 gather merged donors (grouping by seed; the same launch copies the kept rows
+ * to the output), 6 emit (folds the seeds that have donors).  A batch of short units (every unit at most
  * 1024 rows, B <= 1024, bf16, cosine geometry) runs stages 2-6 as one kernel: its time is
  * reported as stage 2 and stages 3-6 read as the cost of an empty event pair; with d = 128
  * stages 0 and 1 are one kernel too, reported as stage 0.
