@@ -2,11 +2,12 @@
 //   similarity   every donor against every seed of its unit by key cosine; best seed kept
 //                when the cosine reaches tau (bf16 d=128: MFMA contraction seeds x donors^T,
 //                each lane owns one donor and scans its seeds in ascending order);
-//   gather       ordered list of the donors that merge (ascending row), per unit;
-//   emit         sixteen lanes per output row: kept tokens are copied bit for bit, a seed
-//                with donors becomes the weighted fold m = sum a_i, k~ = sum a_i k_i / m,
-//                v~ = sum a_i v_i / m with a_i the token's score, accumulated in fp32 in
-//                ascending row order (fixed order: reruns are bitwise identical).
+//   gather       ordered list of the donors that merge (ascending row), per unit, then the
+//                same list grouped by seed; spare workgroups of the launch copy the kept
+//                tokens to the output bit for bit, sixteen lanes per row;
+//   emit         a seed with donors becomes the weighted fold m = sum a_i,
+//                k~ = sum a_i k_i / m, v~ = sum a_i v_i / m with a_i the token's score,
+//                accumulated in fp32 in a fixed order (reruns are bitwise identical).
 #include "cask_common.h"
 #include <type_traits>
 
@@ -482,7 +483,6 @@ constexpr int kCopyRounds = 2;
 // idle.  The row pieces are native vectors: with HIP's vector classes the staging arrays end up
 // in scratch memory.
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <typename Vec, int PIECES>
 __device__ __forceinline__ void copy_kept_rows(const CopyJob& cj, int B,
