@@ -286,6 +286,20 @@ def test_more_seeds_than_one_cursor_pass():
     _note(st)
 
 
+def test_every_donor_folds_into_more_seeds_than_one_range():
+    """About 830 seeds and 14 000 folding donors in a unit: the grouping of the donor list takes
+    the seed ordinals in two ranges of 512, every wave splitting its own run of a long list."""
+    w = caches.scaled(W["cfg1"], n_seqs=1, n_layers=1, n_kv_heads=2, prefix=40, decode=15000, budget=1000,
+                      cluster_frac=0.6)
+    c = caches.make(w, seed=47)
+    p = parity.params_of(w, core=100, sim_threshold=-1.0)
+    pl = cask.plan(p, 40, 15040)
+    assert 512 < pl["seeds"] <= 1024
+    st = parity.full_check(c, p, expect_folds=True)
+    assert st["folded_donors"] > 2 * 13000
+    _note(st)
+
+
 def test_group_diagnostics_with_row_stride_and_arbitrary_assignments():
     """cask_group_diagnostics takes any assignment and any K_out with a row stride: random
     slots, a third of the rows dropped, out-of-range slots skipped; fp32 and bf16, d 64 / 128."""
