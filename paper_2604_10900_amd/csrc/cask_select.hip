@@ -333,21 +333,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   constexpr int kSelChunk = kSelThreads * PER;
   Kth kth[3];
   uint32_t key[PER];
-  bool have_keys = false;  // `key` holds rows lo_all + e * kSelThreads + tid
-  int lo_all = N, hi_all = 0;
-#pragma unroll
-  for (int j = 0; j < 3; ++j)
-    if (q.k[j] > 0) {
-      lo_all = min(lo_all, q.lo[j]);
-      hi_all = max(hi_all, q.hi[j]);
-    }
-  if (hi_all > lo_all) {
-    radix_select3<PER>(s, q, lo_all, hi_all, kth, key, hist, bcast);
-    have_keys = hi_all - lo_all <= kSelChunk;
-  }
-  const bool keys_cover_prefix = have_keys && lo_all == 0 && hi_all >= P;
-  const bool keys_cover_decode = have_keys && lo_all <= P && hi_all >= hi;
-  if (do_prefix && P > 0) {
+  // `key` holds rows key_lo + e * kSelThreads + tid of [key_lo, key_hi) when `have_keys`
+  bool have_keys = false;
+  int key_lo = 0, key_hi = 0;
+
+  auto prefix_roles = [&]() {
+    const bool keys_cover_prefix = have_keys && key_lo == 0 && key_hi >= P;
     if (pl.p_keep >= P) {
       for (int i = tid; i < P; i += kSelThreads) ro[i] = CASK_ROLE_PREFIX_KEEP;
     } else if (pl.p_keep == 0) {
@@ -358,7 +349,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         if (keys_cover_prefix) {
 #pragma unroll
           for (int e = 0; e < PER; ++e) {
-            const int i = lo_all + e * kSelThreads + tid;
+            const int i = key_lo + e * kSelThreads + tid;
             if (i < P) ro[i] = key[e] >= kt.key ? CASK_ROLE_PREFIX_KEEP : CASK_ROLE_PREFIX_DROP;
           }
         } else {
@@ -381,7 +372,49 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         }
       }
     }
+  };
+
+  // The ranks are found together in one walk over [first row of an active range, last), unless
+  // the prefix and the decode trace each take fewer chunks of kSelChunk rows on their own than
+  // the span of both does (a 16 384-row prefix with a 2048-row trace behind it: one chunk each,
+  // keys in registers across the passes, against two chunks read again in every pass): then
+  // the prefix rank is found first, its roles are written, and the decode ranks follow.
+  const bool pre_q = q.k[0] > 0, dec_q = q.k[1] > 0 || q.k[2] > 0;
+  auto chunks = [&](int rows) { return (rows + kSelChunk - 1) / kSelChunk; };
+  // (only the largest instance meets units beyond one chunk)
+  const bool two_walks = PER == kSelPerDefault && pre_q && dec_q && chunks(P) + chunks(n) <= chunks(hi);
+  auto find_ranks = [&](const Query3& qw) {  // the ranks of the active queries of qw -> kth, keys -> key
+    int lo_all = N, hi_all = 0;
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+      if (qw.k[j] > 0) {
+        lo_all = min(lo_all, qw.lo[j]);
+        hi_all = max(hi_all, qw.hi[j]);
+      }
+    if (hi_all > lo_all) {
+      Kth found[3];
+      radix_select3<PER>(s, qw, lo_all, hi_all, found, key, hist, bcast);
+#pragma unroll
+      for (int j = 0; j < 3; ++j)
+        if (qw.k[j] > 0) kth[j] = found[j];
+      have_keys = hi_all - lo_all <= kSelChunk;
+      key_lo = lo_all;
+      key_hi = hi_all;
+    }
+  };
+  if (PER == kSelPerDefault && two_walks) {
+    Query3 qa = q;
+    qa.k[1] = qa.k[2] = 0;
+    find_ranks(qa);
+    prefix_roles();  // (the prefix rank is only asked for with do_prefix and P > 0)
+    Query3 qb = q;
+    qb.k[0] = 0;
+    find_ranks(qb);
+  } else {
+    find_ranks(q);
+    if (do_prefix && P > 0) prefix_roles();
   }
+  const bool keys_cover_decode = have_keys && key_lo <= P && key_hi >= hi;
 
   auto decode_roles = [&]() {
     for (int i = hi + tid; i < N; i += kSelThreads) ro[i] = CASK_ROLE_RECENT;
@@ -416,7 +449,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
       if (keys_cover_decode) {
 #pragma unroll
         for (int e = 0; e < PER; ++e) {
-          const int i = lo_all + e * kSelThreads + tid;
+          const int i = key_lo + e * kSelThreads + tid;
           if (i >= P && i < hi) mark(i, key[e]);
         }
       } else {

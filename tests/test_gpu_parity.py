@@ -1008,6 +1008,44 @@ def test_group_sizes_around_the_single_wave_fold_limit(dtype):
     assert parity.check_values(p, got, want, Kb.reshape(2 * N, d), Vb.reshape(2 * N, d), row_off) == 7
 
 
+@pytest.mark.parametrize("quant", [0, 40, None])
+@pytest.mark.parametrize("N,P", [(18432, 16384), (33024, 256), (34000, 17000), (20000, 3000), (17000, 600)])
+def test_event_selection_on_units_beyond_one_chunk_of_keys(N, P, quant):
+    """Whole events on injected scores with units longer than the selection's 16 384 keys per
+    walk: where the prefix and the decode trace take fewer chunks on their own than their span,
+    the prefix rank is found in a walk of its own before the decode ranks (the first three
+    shapes), else all three ranks in one walk.  quant: all scores equal / 40 levels (every rank
+    boundary inside a run of equal values) / all distinct.  A short second unit rides along."""
+    d, Wn = 128, 64
+    rng = np.random.default_rng(N + (quant or 7))
+    lens = [N, 2500]
+    pref = [P, 300]
+    row_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(row_off[-1])
+    if quant is None:
+        sc = ((1.0 + rng.permutation(total)) / total).astype(np.float32)
+    elif quant == 0:
+        sc = np.full(total, 0.25, dtype=np.float32)
+    else:
+        sc = (np.floor(rng.random(total) * quant) / quant).astype(np.float32)
+    K = rng.integers(-4, 5, (total, d)).astype(np.float32)
+    V = rng.integers(-4, 5, (total, d)).astype(np.float32)
+    # (no donor reaches a threshold above 1: the roles alone decide every output)
+    p = cask.Params(dtype=cask.BF16, head_dim=d, q_per_kv=1, window=Wn, budget=2048, sim_threshold=2.0)
+    tb = lambda x: torch.from_numpy(x).to(torch.bfloat16)
+    c = dict(K=tb(K), V=tb(V), Q=torch.zeros(2, Wn, 1, d, dtype=torch.bfloat16),
+             row_off=torch.from_numpy(row_off), prefix_len=torch.tensor(pref, dtype=torch.int32))
+    ro, plen, Kb, Vb, Qb = parity.host_arrays(c)
+    want = ref.compress(parity.ref_params(p), ro, plen, Kb, Vb, Qb, scores=sc)
+    out = cask.compress(parity.to_device(c, p), scores=torch.from_numpy(sc).cuda())
+    torch.cuda.synchronize()
+    got = parity.gpu_outputs(out, p)
+    assert np.array_equal(got["status"], want["status"])
+    assert np.array_equal(got["out_len"], want["out_len"])
+    assert np.array_equal(got["out_src"], want["out_src"])
+    assert np.array_equal(got["assign"], want["assign"])
+
+
 # ------------------------------------------------------------------ determinism, errors, edges
 
 @pytest.mark.parametrize("decode", [2500, 700])
