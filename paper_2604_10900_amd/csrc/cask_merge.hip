@@ -32,6 +32,7 @@ constexpr int kGroupPitch = 1024 + 64;  // LDS pitch of a 4-row group, piece-maj
 constexpr int kSeedBlock = 128;         // seeds held in LDS at a time
 constexpr int kDonorTile = 128;         // donor rows per tile: 4 waves x 32
 constexpr int kPrefetch = 2;            // donor tiles in flight ahead of the one being contracted
+constexpr int kMultiTiles = 4;          // tiles per workgroup where a unit's seeds take several blocks
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 __device__ inline float sumsq_bf16x8(const uint4& v) {
@@ -154,24 +155,16 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
   // merge radius (0 = none): seeds further than this many cache rows from the donor are skipped
   const int radius = kp.radius > 0 ? kp.radius : 0x7fffffff;
 
-#pragma unroll
-  for (int t = 0; t < kPrefetch; ++t) fetch_donors(t, dreg[t], rreg[t]);
-  constexpr bool one_block = ONE_BLOCK;
-  if (one_block) {
-    stage_seeds(0);
-    __syncthreads();
-  }
   unsigned char* my_turn = turn[wv];
   const int op_off = (c32 >> 2) * kGroupPitch + (c32 & 3) * 16 + h * 64;  // operand rows of this lane
 
-  auto tile_body = [&](int t, uint4 (&d)[8], int& rl) {
-    // registers -> private LDS region -> B operand of this lane's donor
+  // registers -> private LDS region -> B operand of this lane's donor; refills the registers
+  // with tile t + kPrefetch; returns the donor's inverse norm
+  auto turn_donors = [&](int t, uint4 (&d)[8], int& rl, bf16x8 (&bres)[8]) -> float {
 #pragma unroll
     for (int j = 0; j < 8; ++j)
       *reinterpret_cast<uint4*>(my_turn + j * kGroupPitch + (lane & 15) * 64 + (lane >> 4) * 16) = d[j];
-    const bool donor = rl == CASK_ROLE_DONOR;
     fetch_donors(t + kPrefetch, d, rl);  // refill the registers just freed
-    bf16x8 bres[8];
     float ss = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
@@ -180,50 +173,45 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
       bres[ks] = __builtin_bit_cast(bf16x8, v);
     }
     ss += __shfl_xor(ss, 32, 64);
-    const float dinv = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
-    const int drow = first + t * kDonorTile + wv * 32 + c32;
-
-    float best = kNegInf;
-    int best_ord = -1;
-    for (int sb = 0; sb < M; sb += kSeedBlock) {
-      if (!one_block) {
-        __syncthreads();  // previous block fully consumed
-        stage_seeds(sb);
-        __syncthreads();
-      }
-      const int m_blk = min(kSeedBlock, M - sb);
-      for (int s0 = 0; s0 < m_blk; s0 += 32) {
-        bf16x8 a[8];
-        const unsigned char* ap = seeds + (s0 >> 2) * kGroupPitch + op_off;
+    return ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+  };
+  // the lane's donor against the staged seeds [sb, sb + m_blk), ascending ordinal: first maximum wins
+  auto against_block = [&](int sb, int m_blk, const bf16x8 (&bres)[8], float dinv, int drow, float& best,
+                           int& best_ord) {
+    for (int s0 = 0; s0 < m_blk; s0 += 32) {
+      bf16x8 a[8];
+      const unsigned char* ap = seeds + (s0 >> 2) * kGroupPitch + op_off;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 128);
-        f32x16 acc = {0};
+      for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 128);
+      f32x16 acc = {0};
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ks], acc, 0, 0, 0);
+      for (int ks = 0; ks < 8; ++ks)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ks], acc, 0, 0, 0);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {  // ascending seed ordinal within the lane
-          const float4 si = *reinterpret_cast<const float4*>(&seed_inv[s0 + g * 8 + h * 4]);
-          const float sv[4] = {si.x, si.y, si.z, si.w};
-          int pv[4] = {0, 0, 0, 0};
-          if (RADIUS) {
-            const int4 sp = *reinterpret_cast<const int4*>(&seed_pos[s0 + g * 8 + h * 4]);
-            pv[0] = sp.x, pv[1] = sp.y, pv[2] = sp.z, pv[3] = sp.w;
-          }
+      for (int g = 0; g < 4; ++g) {  // ascending seed ordinal within the lane
+        const float4 si = *reinterpret_cast<const float4*>(&seed_inv[s0 + g * 8 + h * 4]);
+        const float sv[4] = {si.x, si.y, si.z, si.w};
+        int pv[4] = {0, 0, 0, 0};
+        if (RADIUS) {
+          const int4 sp = *reinterpret_cast<const int4*>(&seed_pos[s0 + g * 8 + h * 4]);
+          pv[0] = sp.x, pv[1] = sp.y, pv[2] = sp.z, pv[3] = sp.w;
+        }
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int sr = s0 + g * 8 + h * 4 + q;
-            const float sim = (acc[g * 4 + q] * sv[q]) * dinv;
-            bool near = true;
-            if (RADIUS) near = (pv[q] > drow ? pv[q] - drow : drow - pv[q]) <= radius;
-            if (sr < m_blk && near && sim > best) {
-              best = sim;
-              best_ord = sb + sr;
-            }
+        for (int q = 0; q < 4; ++q) {
+          const int sr = s0 + g * 8 + h * 4 + q;
+          const float sim = (acc[g * 4 + q] * sv[q]) * dinv;
+          bool near = true;
+          if (RADIUS) near = (pv[q] > drow ? pv[q] - drow : drow - pv[q]) <= radius;
+          if (sr < m_blk && near && sim > best) {
+            best = sim;
+            best_ord = sb + sr;
           }
         }
       }
     }
+  };
+  // the two half-waves hold the even and the odd groups of four seeds: lowest ordinal wins a tie
+  auto settle = [&](float best, int best_ord, bool donor, int drow) {
     const float ob = __shfl_xor(best, 32, 64);
     const int oo = __shfl_xor(best_ord, 32, 64);
     if (oo >= 0 && (best_ord < 0 || better(ob, oo, best, best_ord))) {
@@ -233,9 +221,61 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
     if (h == 0 && drow < last)  // rows past the workgroup's share belong to another one
       assign_ord[row0 + drow] = (donor && best_ord >= 0 && best >= kp.tau) ? best_ord : -1;
   };
-  for (int t = 0; t < n_tiles; t += kPrefetch) {
+
+  if constexpr (ONE_BLOCK) {
 #pragma unroll
-    for (int b = 0; b < kPrefetch; ++b) tile_body(t + b, dreg[b], rreg[b]);
+    for (int t = 0; t < kPrefetch; ++t) fetch_donors(t, dreg[t], rreg[t]);
+    stage_seeds(0);
+    __syncthreads();
+    auto tile_body = [&](int t, uint4 (&d)[8], int& rl) {
+      const bool donor = rl == CASK_ROLE_DONOR;
+      bf16x8 bres[8];
+      const float dinv = turn_donors(t, d, rl, bres);
+      const int drow = first + t * kDonorTile + wv * 32 + c32;
+      float best = kNegInf;
+      int best_ord = -1;
+      against_block(0, M, bres, dinv, drow, best, best_ord);
+      settle(best, best_ord, donor, drow);
+    };
+    for (int t = 0; t < n_tiles; t += kPrefetch) {
+#pragma unroll
+      for (int b = 0; b < kPrefetch; ++b) tile_body(t + b, dreg[b], rreg[b]);
+    }
+  } else {
+    // More seeds than LDS holds at a time: a block of seeds is staged once and meets every tile
+    // of the workgroup (at most kMultiTiles; the donors stream again per block, from L2) while
+    // each tile's best seed so far waits in registers.  Staging per tile instead made a unit
+    // with 282 seeds and four tiles a chain of twelve stagings and twenty-four barriers.
+    float best[kMultiTiles];
+    int best_ord[kMultiTiles];
+    bool donor[kMultiTiles];
+#pragma unroll
+    for (int t = 0; t < kMultiTiles; ++t) {
+      best[t] = kNegInf;
+      best_ord[t] = -1;
+      donor[t] = false;
+    }
+    for (int sb = 0; sb < M; sb += kSeedBlock) {
+      if (sb > 0) __syncthreads();  // previous block fully consumed
+#pragma unroll
+      for (int t = 0; t < kPrefetch; ++t) fetch_donors(t, dreg[t], rreg[t]);
+      stage_seeds(sb);
+      __syncthreads();
+      const int m_blk = min(kSeedBlock, M - sb);
+      static_assert(kMultiTiles % kPrefetch == 0, "whole rounds of the register ring");
+#pragma unroll
+      for (int t = 0; t < kMultiTiles; ++t) {
+        if (t < n_tiles) {  // (the same for the whole workgroup)
+          donor[t] = rreg[t % kPrefetch] == CASK_ROLE_DONOR;
+          bf16x8 bres[8];
+          const float dinv = turn_donors(t, dreg[t % kPrefetch], rreg[t % kPrefetch], bres);
+          against_block(sb, m_blk, bres, dinv, first + t * kDonorTile + wv * 32 + c32, best[t], best_ord[t]);
+        }
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < kMultiTiles; ++t)
+      if (t < n_tiles) settle(best[t], best_ord[t], donor[t], first + t * kDonorTile + wv * 32 + c32);
   }
 }
 
@@ -1099,16 +1139,17 @@ hipError_t launch_similarity(const KParams& kp, const Batch& b, const uint8_t* r
     if (chunks < 1) chunks = (tiles + 31) / 32;
     if (chunks < 1) chunks = 1;
     if (chunks > tiles) chunks = tiles;
-    const int tiles_per_wg = (tiles + chunks - 1) / chunks;
-    chunks = (tiles + tiles_per_wg - 1) / tiles_per_wg;
-    const int units8 = (b.n_units + 7) / 8 * 8;
     const int seed_bound = plan_seed_bound(kp);
     // (a caller-supplied role array may name any number of seeds: general kernel then)
+    const bool one = roles_follow_plan && seed_bound <= kSeedBlock;
+    int tiles_per_wg = (tiles + chunks - 1) / chunks;
+    if (!one && tiles_per_wg > kMultiTiles) tiles_per_wg = kMultiTiles;  // its tiles' results wait in registers
+    chunks = (tiles + tiles_per_wg - 1) / tiles_per_wg;
+    const int units8 = (b.n_units + 7) / 8 * 8;
 #define CASK_SIM(ONE, RAD)                                                             \
   similarity_mfma_kernel<ONE, RAD><<<dim3(units8 * chunks), dim3(256), 0, st>>>(       \
       kp, b.n_units, chunks, tiles_per_wg, b.row_off, b.prefix_len,                    \
       static_cast<const uint16_t*>(b.K), role, seed_rows, n_seeds, assign_ord)
-    const bool one = roles_follow_plan && seed_bound <= kSeedBlock;
     if (kp.radius > 0) {
       if (one) CASK_SIM(true, true); else CASK_SIM(false, true);
     } else {
