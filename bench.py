@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0
 PROFILED_TRAFFIC = {
     "cfg2": {"bytes": (130980.6 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg2_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
     "cfg3": {"bytes": (475896.5 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg3_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
-    "cfg4": {"bytes": (270766.4 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg4_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
+    "cfg4": {"bytes": (270760.2 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg4_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
     "cfg4v": {"bytes": (959133.2 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg4v_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
     # (the slower of the two sweeps on this workload is the second one)
     "cfg5": {"bytes": (42022908.0 * 2.0 + 1282976.2) * 1024, "source": "profiles/cfg5_kernels_and_hbm_traffic.md (score_mfma_kernel<1, 4, true>)"},
