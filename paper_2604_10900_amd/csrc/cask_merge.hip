@@ -175,9 +175,10 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
     ss += __shfl_xor(ss, 32, 64);
     return ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
   };
-  // the lane's donor against the staged seeds [sb, sb + m_blk), ascending ordinal: first maximum wins
-  auto against_block = [&](int sb, int m_blk, const bf16x8 (&bres)[8], float dinv, int drow, float& best,
-                           int& best_ord) {
+  // The lane's donor against the staged seeds [sb, sb + m_blk), ascending ordinal: first maximum
+  // wins.  `best` is the cosine without the donor's own inverse norm: a positive factor common
+  // to all of a donor's seeds, applied once when the winner is settled.
+  auto against_block = [&](int sb, int m_blk, const bf16x8 (&bres)[8], int drow, float& best, int& best_ord) {
     for (int s0 = 0; s0 < m_blk; s0 += 32) {
       bf16x8 a[8];
       const unsigned char* ap = seeds + (s0 >> 2) * kGroupPitch + op_off;
@@ -187,31 +188,36 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks)
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], bres[ks], acc, 0, 0, 0);
+      auto pick = [&](auto whole_tag) {  // whole: all 32 seeds of this step exist
+        constexpr bool kWhole = decltype(whole_tag)::value;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {  // ascending seed ordinal within the lane
-        const float4 si = *reinterpret_cast<const float4*>(&seed_inv[s0 + g * 8 + h * 4]);
-        const float sv[4] = {si.x, si.y, si.z, si.w};
-        int pv[4] = {0, 0, 0, 0};
-        if (RADIUS) {
-          const int4 sp = *reinterpret_cast<const int4*>(&seed_pos[s0 + g * 8 + h * 4]);
-          pv[0] = sp.x, pv[1] = sp.y, pv[2] = sp.z, pv[3] = sp.w;
-        }
+        for (int g = 0; g < 4; ++g) {  // ascending seed ordinal within the lane
+          const float4 si = *reinterpret_cast<const float4*>(&seed_inv[s0 + g * 8 + h * 4]);
+          const float sv[4] = {si.x, si.y, si.z, si.w};
+          int pv[4] = {0, 0, 0, 0};
+          if (RADIUS) {
+            const int4 sp = *reinterpret_cast<const int4*>(&seed_pos[s0 + g * 8 + h * 4]);
+            pv[0] = sp.x, pv[1] = sp.y, pv[2] = sp.z, pv[3] = sp.w;
+          }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int sr = s0 + g * 8 + h * 4 + q;
-          const float sim = (acc[g * 4 + q] * sv[q]) * dinv;
-          bool near = true;
-          if (RADIUS) near = (pv[q] > drow ? pv[q] - drow : drow - pv[q]) <= radius;
-          if (sr < m_blk && near && sim > best) {
-            best = sim;
-            best_ord = sb + sr;
+          for (int q = 0; q < 4; ++q) {
+            const int sr = s0 + g * 8 + h * 4 + q;
+            const float sim = acc[g * 4 + q] * sv[q];
+            bool near = true;
+            if (RADIUS) near = (pv[q] > drow ? pv[q] - drow : drow - pv[q]) <= radius;
+            if ((kWhole || sr < m_blk) && near && sim > best) {
+              best = sim;
+              best_ord = sb + sr;
+            }
           }
         }
-      }
+      };
+      if (s0 + 32 <= m_blk) pick(std::true_type{});
+      else pick(std::false_type{});
     }
   };
   // the two half-waves hold the even and the odd groups of four seeds: lowest ordinal wins a tie
-  auto settle = [&](float best, int best_ord, bool donor, int drow) {
+  auto settle = [&](float best, int best_ord, float dinv, bool donor, int drow) {
     const float ob = __shfl_xor(best, 32, 64);
     const int oo = __shfl_xor(best_ord, 32, 64);
     if (oo >= 0 && (best_ord < 0 || better(ob, oo, best, best_ord))) {
@@ -219,7 +225,7 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
       best_ord = oo;
     }
     if (h == 0 && drow < last)  // rows past the workgroup's share belong to another one
-      assign_ord[row0 + drow] = (donor && best_ord >= 0 && best >= kp.tau) ? best_ord : -1;
+      assign_ord[row0 + drow] = (donor && best_ord >= 0 && best * dinv >= kp.tau) ? best_ord : -1;
   };
 
   if constexpr (ONE_BLOCK) {
@@ -234,8 +240,8 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
       const int drow = first + t * kDonorTile + wv * 32 + c32;
       float best = kNegInf;
       int best_ord = -1;
-      against_block(0, M, bres, dinv, drow, best, best_ord);
-      settle(best, best_ord, donor, drow);
+      against_block(0, M, bres, drow, best, best_ord);
+      settle(best, best_ord, dinv, donor, drow);
     };
     for (int t = 0; t < n_tiles; t += kPrefetch) {
 #pragma unroll
@@ -246,12 +252,13 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
     // of the workgroup (at most kMultiTiles; the donors stream again per block, from L2) while
     // each tile's best seed so far waits in registers.  Staging per tile instead made a unit
     // with 282 seeds and four tiles a chain of twelve stagings and twenty-four barriers.
-    float best[kMultiTiles];
+    float best[kMultiTiles], dinv[kMultiTiles];
     int best_ord[kMultiTiles];
     bool donor[kMultiTiles];
 #pragma unroll
     for (int t = 0; t < kMultiTiles; ++t) {
       best[t] = kNegInf;
+      dinv[t] = 0.f;
       best_ord[t] = -1;
       donor[t] = false;
     }
@@ -268,14 +275,14 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
         if (t < n_tiles) {  // (the same for the whole workgroup)
           donor[t] = rreg[t % kPrefetch] == CASK_ROLE_DONOR;
           bf16x8 bres[8];
-          const float dinv = turn_donors(t, dreg[t % kPrefetch], rreg[t % kPrefetch], bres);
-          against_block(sb, m_blk, bres, dinv, first + t * kDonorTile + wv * 32 + c32, best[t], best_ord[t]);
+          dinv[t] = turn_donors(t, dreg[t % kPrefetch], rreg[t % kPrefetch], bres);
+          against_block(sb, m_blk, bres, first + t * kDonorTile + wv * 32 + c32, best[t], best_ord[t]);
         }
       }
     }
 #pragma unroll
     for (int t = 0; t < kMultiTiles; ++t)
-      if (t < n_tiles) settle(best[t], best_ord[t], donor[t], first + t * kDonorTile + wv * 32 + c32);
+      if (t < n_tiles) settle(best[t], best_ord[t], dinv[t], donor[t], first + t * kDonorTile + wv * 32 + c32);
   }
 }
 
