@@ -156,6 +156,15 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
   const int radius = kp.radius > 0 ? kp.radius : 0x7fffffff;
 
   unsigned char* my_turn = turn[wv];
+  // The wave's turning region holds a 4-row group row by row, the 16-byte piece g of row r at
+  // slot g ^ r of the row: the store of a load's 64 pieces (lane = row l / 16, piece l % 16) and
+  // the operand reads (lane = row c32, pieces h, h + 2, ...) then both spread any eight
+  // consecutive lanes over all banks.  (Piece-major, as the seeds are kept, the stores ran
+  // four lanes to a bank: 44 % of the kernel's LDS cycles were bank conflicts.)
+  const int turn_st = (lane >> 4) * 256 + (((lane & 15) ^ (lane >> 4)) * 16);
+  const int turn_row = (c32 >> 2) * kGroupPitch + (c32 & 3) * 256;
+  const int turn_ld0 = turn_row + ((h ^ (c32 & 3)) * 16);        // k-steps 0, 2, ...: piece 2 ks + h
+  const int turn_ld1 = turn_row + (((2 + h) ^ (c32 & 3)) * 16);  // k-steps 1, 3, ...
   const int op_off = (c32 >> 2) * kGroupPitch + (c32 & 3) * 16 + h * 64;  // operand rows of this lane
 
   // registers -> private LDS region -> B operand of this lane's donor; refills the registers
@@ -163,12 +172,12 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
   auto turn_donors = [&](int t, uint4 (&d)[8], int& rl, bf16x8 (&bres)[8]) -> float {
 #pragma unroll
     for (int j = 0; j < 8; ++j)
-      *reinterpret_cast<uint4*>(my_turn + j * kGroupPitch + (lane & 15) * 64 + (lane >> 4) * 16) = d[j];
+      *reinterpret_cast<uint4*>(my_turn + j * kGroupPitch + turn_st) = d[j];
     fetch_donors(t + kPrefetch, d, rl);  // refill the registers just freed
     float ss = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      const uint4 v = *reinterpret_cast<const uint4*>(my_turn + op_off + ks * 128);
+      const uint4 v = *reinterpret_cast<const uint4*>(my_turn + ((ks & 1) ? turn_ld1 : turn_ld0) + (ks >> 1) * 64);
       ss += sumsq_bf16x8(v);
       bres[ks] = __builtin_bit_cast(bf16x8, v);
     }
