@@ -88,12 +88,13 @@ constexpr float kPadNegL = -1.0e30f;
 
 // Per window row of a unit: -L_row, L_row the base-2 log-sum-exp combined over the key splits
 // of sweep A.  Sweep B adds it to every logit of the row inside the exponent's fma.
-__global__ __launch_bounds__(256) void score_bias_kernel(KParams kp, int n_splits, int mq_pad,
+constexpr int kBiasThreads = 1024;  // a thread per window row at W*G <= 1024: every partial of the unit in flight at once
+__global__ __launch_bounds__(kBiasThreads) void score_bias_kernel(KParams kp, int n_splits, int mq_pad,
                                                          const float2* __restrict__ rowstat,
                                                          float* __restrict__ bias) {
   const int unit = blockIdx.x;
   const float2* part = rowstat + (size_t)unit * n_splits * mq_pad;
-  for (int r = threadIdx.x; r < mq_pad; r += 256) {
+  for (int r = threadIdx.x; r < mq_pad; r += kBiasThreads) {
     float nl = kPadNegL;
     if (r < kp.Mq) {
       float m = kNegInf, l = 0.f;
@@ -1098,7 +1099,7 @@ hipError_t launch_score(const KParams& kp, const Batch& b, const Workspace& wl, 
   }
   if (between) (void)hipEventRecord(between, st);  // right behind sweep A: the stage is that kernel alone
   if (wl.n_splits > 1)  // with one split sweep A has written -L itself
-    score_bias_kernel<<<dim3(b.n_units), dim3(256), 0, st>>>(kp, wl.n_splits, wl.mq_pad, rowstat, bias);
+    score_bias_kernel<<<dim3(b.n_units), dim3(kBiasThreads), 0, st>>>(kp, wl.n_splits, wl.mq_pad, rowstat, bias);
   if (wl.wide_cols) {
     static LdsLimitOnce limBw, limBr;
     e = ring_res ? limBr.ensure(reinterpret_cast<const void*>(&score_mfma_kernel<1, 4, true>), 160 * 1024)
