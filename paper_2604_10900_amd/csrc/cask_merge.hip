@@ -28,7 +28,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kD = 128;
 constexpr int kRowBytes = kD * 2;
-constexpr int kGroupPitch = 1024 + 64;  // LDS pitch of a 4-row group, piece-major (see below)
+constexpr int kGroupPitch = 1024 + 64;  // LDS pitch of a 4-row group (layout: see below)
 constexpr int kSeedBlock = 128;         // seeds held in LDS at a time
 constexpr int kDonorTile = 128;         // donor rows per tile: 4 waves x 32
 constexpr int kPrefetch = 2;            // donor tiles in flight ahead of the one being contracted
@@ -52,10 +52,11 @@ __device__ inline float sumsq_bf16x8(const uint4& v) {
 // Memory side: a wave reads its 32 rows with 8 fully coalesced loads (4 whole 256-byte rows
 // per instruction: lane l takes 16-byte piece l % 16 of row l / 16), kPrefetch tiles ahead, so
 // K streams at memory speed.  The registers then hold rows across lanes, not MFMA operands;
-// the wave turns them round through a private LDS region: piece g of row r of a 4-row group
-// goes to g * 64 + r * 16 (a 1 KB store per instruction, conflict-free), and lane (c32, h)
-// reads back row c32's pieces h, h + 2, ... as the B operand of the eight k-steps
-// (conflict-free as well, 1088-byte group pitch).  No barrier: the region is the wave's own.
+// the wave turns them round through a private LDS region: a 4-row group is kept row by row,
+// the 16-byte piece g of row r at slot g ^ r of the row (a 1 KB store per instruction), and lane
+// (c32, h) reads back row c32's pieces h, h + 2, ... as the B operand of the eight k-steps; with
+// the 1088-byte group pitch both spread any eight consecutive lanes over all banks.  No
+// barrier: the region is the wave's own.  The staged seeds use the same layout.
 //
 // Compute side: the unit's seeds (kSeedBlock at a time, same layout, with inverse norms) are
 // the A operand, so a lane owns one donor and sees its seeds in ascending order:
@@ -141,7 +142,8 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int sr = s0 + i * 16 + (tid >> 4);
-        *reinterpret_cast<uint4*>(seeds + (sr >> 2) * kGroupPitch + (tid & 15) * 64 + (sr & 3) * 16) = v[i];
+        // (row by row with piece g of row r at slot g ^ r, like the waves' turning regions)
+        *reinterpret_cast<uint4*>(seeds + (sr >> 2) * kGroupPitch + (sr & 3) * 256 + (((tid & 15) ^ (sr & 3)) * 16)) = v[i];
         float ss = sumsq_bf16x8(v[i]);
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
@@ -159,13 +161,12 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
   // The wave's turning region holds a 4-row group row by row, the 16-byte piece g of row r at
   // slot g ^ r of the row: the store of a load's 64 pieces (lane = row l / 16, piece l % 16) and
   // the operand reads (lane = row c32, pieces h, h + 2, ...) then both spread any eight
-  // consecutive lanes over all banks.  (Piece-major, as the seeds are kept, the stores ran
-  // four lanes to a bank: 44 % of the kernel's LDS cycles were bank conflicts.)
+  // consecutive lanes over all banks.  (Piece-major -- piece g of row r at g * 64 + r * 16 -- the
+  // stores ran four lanes to a bank: 44 % of the kernel's LDS cycles were bank conflicts.)
   const int turn_st = (lane >> 4) * 256 + (((lane & 15) ^ (lane >> 4)) * 16);
   const int turn_row = (c32 >> 2) * kGroupPitch + (c32 & 3) * 256;
   const int turn_ld0 = turn_row + ((h ^ (c32 & 3)) * 16);        // k-steps 0, 2, ...: piece 2 ks + h
   const int turn_ld1 = turn_row + (((2 + h) ^ (c32 & 3)) * 16);  // k-steps 1, 3, ...
-  const int op_off = (c32 >> 2) * kGroupPitch + (c32 & 3) * 16 + h * 64;  // operand rows of this lane
 
   // registers -> private LDS region -> B operand of this lane's donor; refills the registers
   // with tile t + kPrefetch; returns the donor's inverse norm
@@ -190,9 +191,10 @@ __global__ __launch_bounds__(256, 2) void similarity_mfma_kernel(
   auto against_block = [&](int sb, int m_blk, const bf16x8 (&bres)[8], int drow, float& best, int& best_ord) {
     for (int s0 = 0; s0 < m_blk; s0 += 32) {
       bf16x8 a[8];
-      const unsigned char* ap = seeds + (s0 >> 2) * kGroupPitch + op_off;
+      const unsigned char* ap = seeds + (s0 >> 2) * kGroupPitch;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(ap + ks * 128);
+      for (int ks = 0; ks < 8; ++ks)
+        a[ks] = *reinterpret_cast<const bf16x8*>(ap + ((ks & 1) ? turn_ld1 : turn_ld0) + (ks >> 1) * 64);
       f32x16 acc = {0};
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks)
