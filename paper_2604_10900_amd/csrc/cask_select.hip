@@ -222,10 +222,10 @@ __device__ inline int block_excl_scan(int v, int* wsum, int* total) {
 }
 
 // Ordered walk over the roles of a unit: output slot of every kept row, ordinal of every seed.
-// A wave owns kIdxPer * 64 consecutive rows, read and written 64 consecutive rows at a time
+// A wave owns IDX * 64 consecutive rows, read and written 64 consecutive rows at a time
 // (coalesced); positions inside the wave come from ballots with a running carry (kept rows in
 // the low half of a word, seeds in the high half: a wave sees at most 1024 rows per chunk), and
-// one exchange of the wave totals per chunk of kSelThreads * kIdxPer rows orders the waves.
+// one exchange of the wave totals per chunk of kSelThreads * IDX rows orders the waves.
 // Inlined on purpose: as a called function its pointers lose their address space and the
 // ballots' scalar registers are spilled lane by lane, which made the walk issue-bound.
 constexpr int kIdxPer = 16;
@@ -235,6 +235,7 @@ __device__ __forceinline__ bool role_is_kept(int r) {
   return r <= CASK_ROLE_RECENT && ((0x2E >> r) & 1);
 }
 
+template <int IDX>
 __device__ __forceinline__ void index_walk(const KParams& kp, int u, int64_t row0, int N,
                                            const uint8_t* __restrict__ ro, int32_t* __restrict__ slot_of,
                                            int32_t* __restrict__ out_src, int32_t* __restrict__ out_len,
@@ -246,15 +247,15 @@ __device__ __forceinline__ void index_walk(const KParams& kp, int u, int64_t row
   int32_t* const src_u = out_src ? out_src + (size_t)u * B : nullptr;
   int32_t* const seed_u = seed_rows + (size_t)u * B;
   int kept_before = 0, seeds_before = 0;  // of the chunks walked so far
-  for (int cb = 0; cb < N; cb += kSelThreads * kIdxPer) {
-    const int i0 = cb + wv * (64 * kIdxPer) + lane;
-    int r[kIdxPer];
+  for (int cb = 0; cb < N; cb += kSelThreads * IDX) {
+    const int i0 = cb + wv * (64 * IDX) + lane;
+    int r[IDX];
 #pragma unroll
-    for (int e = 0; e < kIdxPer; ++e) r[e] = (i0 + e * 64 < N) ? (int)ro[i0 + e * 64] : (int)CASK_ROLE_PREFIX_DROP;
-    int pos[kIdxPer];  // kept rows | seeds << 16 before this row inside the wave
+    for (int e = 0; e < IDX; ++e) r[e] = (i0 + e * 64 < N) ? (int)ro[i0 + e * 64] : (int)CASK_ROLE_PREFIX_DROP;
+    int pos[IDX];  // kept rows | seeds << 16 before this row inside the wave
     int run = 0;
 #pragma unroll
-    for (int e = 0; e < kIdxPer; ++e) {
+    for (int e = 0; e < IDX; ++e) {
       const unsigned long long bk = __ballot(role_is_kept(r[e])), bs = __ballot(r[e] == CASK_ROLE_SEED);
       const int nk = __builtin_amdgcn_mbcnt_hi((unsigned)(bk >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bk, 0));
       const int ns = __builtin_amdgcn_mbcnt_hi((unsigned)(bs >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bs, 0));
@@ -264,7 +265,7 @@ __device__ __forceinline__ void index_walk(const KParams& kp, int u, int64_t row
       // of ballots that would have to be kept alive in scalar registers
       asm volatile("" : "+v"(pos[e]));
     }
-    int* ws = wsum + ((cb / (kSelThreads * kIdxPer)) & 1) * kSelWaves;  // two buffers: one barrier per chunk
+    int* ws = wsum + ((cb / (kSelThreads * IDX)) & 1) * kSelWaves;  // two buffers: one barrier per chunk
     if (lane == 0) ws[wv] = run;
     __syncthreads();
     int base = 0, tot = 0;
@@ -275,7 +276,7 @@ __device__ __forceinline__ void index_walk(const KParams& kp, int u, int64_t row
       tot += x;
     }
 #pragma unroll
-    for (int e = 0; e < kIdxPer; ++e) {
+    for (int e = 0; e < IDX; ++e) {
       const int i = i0 + e * 64;
       const int at = base + pos[e];  // inside the chunk: at most 16 384 in either half
       const int slot = kept_before + (at & 0xFFFF), ord = seeds_before + (at >> 16);
@@ -480,7 +481,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     // the roles this workgroup just wrote are read back in index order: the barrier makes
     // them visible to all of its threads
     __syncthreads();
-    index_walk(kp, u, row0, N, ro, slot_of, out_src, out_len, seed_rows, n_seeds, wsum);
+    // (as many rows per thread and chunk as the selection holds keys: a unit that fits one chunk
+    // of the selection is walked by all sixteen waves, not by the first N / 1024 of them)
+    index_walk<PER>(kp, u, row0, N, ro, slot_of, out_src, out_len, seed_rows, n_seeds, wsum);
   }
 }
 
@@ -492,7 +495,7 @@ __global__ __launch_bounds__(kSelThreads) void index_roles_kernel(
   const int u = blockIdx.x;
   const int64_t row0 = row_off[u];
   const int N = (int)(row_off[u + 1] - row0);
-  index_walk(kp, u, row0, N, role + row0, slot_of, out_src, out_len, seed_rows, n_seeds, wsum);
+  index_walk<kIdxPer>(kp, u, row0, N, role + row0, slot_of, out_src, out_len, seed_rows, n_seeds, wsum);
 }
 
 // Representative-set mass diagnostics (Section 2.6): per unit
