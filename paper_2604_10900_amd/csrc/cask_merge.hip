@@ -523,7 +523,7 @@ hipError_t launch_similarity_kappa(const KParams& kp, const Batch& b, const uint
 // ------------------------------------------------------------------ gather merged donors
 
 constexpr int kGatherThreads = 1024;
-constexpr int kGatherPer = 16;  // 64-row groups per wave and chunk
+constexpr int kGatherPer = 16;  // 64-row groups per wave and chunk, at most (the kernel's instances: 4, 8, 16)
 constexpr int kSegLds = 8192;   // seed ordinals whose segment cursors fit in LDS at a time
 constexpr int kSmallList = 64;  // donor lists up to this length are split by a single wave
 
@@ -598,6 +598,7 @@ __device__ __forceinline__ void copy_kept_rows(const CopyJob& cj, int B,
 // Workgroups below `n_gather` group the donors of one unit each; the ones above copy kept rows
 // (`cj.K_out` null: there are none).
 // assign_mode: 0 none, 1 output slot (whole event), 2 unit-local source row (consolidate API)
+template <int PER>
 __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
     KParams kp, int n_gather, CopyJob cj,
     const int64_t* __restrict__ row_off, const int32_t* __restrict__ prefix_len,
@@ -633,23 +634,23 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
       assign_out[row0 + i] = !kept ? -1 : (assign_mode == 1 ? slot_of[row0 + i] : i);
     }
   }
-  // A wave owns kGatherPer * 64 consecutive rows, touched 64 consecutive rows at a time
+  // A wave owns PER * 64 consecutive rows of a chunk, touched 64 consecutive rows at a time
   // (coalesced); positions inside the wave come from ballots with a running carry, and one
   // exchange of the wave totals per chunk orders the waves.
   const unsigned long long below = (1ull << lane) - 1ull;
   int count = 0;
-  for (int cb = P; cb < hi; cb += kGatherThreads * kGatherPer) {
-    const int i0 = cb + wv * (64 * kGatherPer) + lane;
-    int r[kGatherPer], ord[kGatherPer], pos[kGatherPer];
+  for (int cb = P; cb < hi; cb += kGatherThreads * PER) {
+    const int i0 = cb + wv * (64 * PER) + lane;
+    int r[PER], ord[PER], pos[PER];
 #pragma unroll
-    for (int e = 0; e < kGatherPer; ++e) {
+    for (int e = 0; e < PER; ++e) {
       const bool in = i0 + e * 64 < hi;
       r[e] = in ? (int)role[row0 + i0 + e * 64] : (int)CASK_ROLE_PREFIX_DROP;
       ord[e] = in ? assign_ord[row0 + i0 + e * 64] : -1;
     }
     int run = 0;
 #pragma unroll
-    for (int e = 0; e < kGatherPer; ++e) {
+    for (int e = 0; e < PER; ++e) {
       if (r[e] != CASK_ROLE_DONOR) ord[e] = -1;
       const unsigned long long b = __ballot(ord[e] >= 0);
       pos[e] = run + __popcll(b & below);
@@ -665,7 +666,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
     }
     __syncthreads();
 #pragma unroll
-    for (int e = 0; e < kGatherPer; ++e) {
+    for (int e = 0; e < PER; ++e) {
       const int i = i0 + e * 64;
       if (i < hi && ord[e] >= 0) {
         const int at = count + before + pos[e];
@@ -681,19 +682,19 @@ __global__ __launch_bounds__(kGatherThreads) void gather_merged_kernel(
       // What a row maps to: a folding donor to its seed, a kept row to itself, anything else to
       // nothing.  The two dependent lookups (seed's row, then its slot) are taken for all of the
       // thread's rows at a time: one after the other, every row would wait for its own round trip.
-      int tgt[kGatherPer];
+      int tgt[PER];
 #pragma unroll
-      for (int e = 0; e < kGatherPer; ++e) {
+      for (int e = 0; e < PER; ++e) {
         const int i = i0 + e * 64;
         const bool kept = r[e] == CASK_ROLE_CORE || r[e] == CASK_ROLE_SEED;
         tgt[e] = (i < hi && ord[e] >= 0) ? srow[ord[e]] : ((i < hi && kept) ? i : -1);  // (ord >= 0 only for donors)
       }
       if (assign_mode == 1) {
 #pragma unroll
-        for (int e = 0; e < kGatherPer; ++e) tgt[e] = tgt[e] >= 0 ? slot_of[row0 + tgt[e]] : -1;
+        for (int e = 0; e < PER; ++e) tgt[e] = tgt[e] >= 0 ? slot_of[row0 + tgt[e]] : -1;
       }
 #pragma unroll
-      for (int e = 0; e < kGatherPer; ++e) {
+      for (int e = 0; e < PER; ++e) {
         const int i = i0 + e * 64;
         if (i < hi) assign_out[row0 + i] = tgt[e];
       }
@@ -1199,7 +1200,12 @@ hipError_t launch_gather_merged(const KParams& kp, const Batch& b, const uint8_t
     copy_blocks = (waves + kGatherThreads / 64 - 1) / (kGatherThreads / 64);
     if (b.n_units + copy_blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   }
-  gather_merged_kernel<<<dim3((unsigned)(b.n_units + copy_blocks)), dim3(kGatherThreads), 0, st>>>(
+  // the smallest instance whose chunk covers the longest decode trace: a unit that fits one chunk
+  // is then shared by all of the workgroup's waves, not by the first few
+  const int per_need = (b.max_decode_len + kGatherThreads - 1) / kGatherThreads;
+  auto kern = per_need <= 4 ? &gather_merged_kernel<4>
+                            : (per_need <= 8 ? &gather_merged_kernel<8> : &gather_merged_kernel<kGatherPer>);
+  kern<<<dim3((unsigned)(b.n_units + copy_blocks)), dim3(kGatherThreads), 0, st>>>(
       kp, b.n_units, cj, b.row_off, b.prefix_len, role, assign_ord, slot_of, seed_rows, merged_row, merged_ord,
       n_merged, assign_out, assign_mode, status, n_seeds, seg_row, seg_start);
   return hipGetLastError();
