@@ -64,9 +64,13 @@ __device__ inline void load_keys(const float* __restrict__ s, int base, int end,
 
 // `key` holds the chunk starting at lo_all on return when the ranges fit one chunk
 // (hi_all - lo_all <= kSelChunk), so the caller can mark the rows without reading them again.
+// `early`: the caller only compares keys against the result when a query's k-th value is not
+// shared beyond the rank (take_eq == total_eq), so the passes may stop as soon as every query's
+// boundary bucket is taken whole; the key then has its remaining low digits zero (a lower
+// bound of the bucket: "key >= result" still separates the top k).
 template <int PER>
 __device__ void radix_select3(const float* __restrict__ s, const Query3& q, int lo_all, int hi_all,
-                              Kth (&out)[3], uint32_t (&key)[PER], int* hist, int* bcast) {
+                              Kth (&out)[3], uint32_t (&key)[PER], int* hist, int* bcast, bool early) {
   constexpr int kSelChunk = kSelThreads * PER;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   uint32_t prefix[3] = {0, 0, 0};
@@ -178,6 +182,14 @@ __device__ void radix_select3(const float* __restrict__ s, const Query3& q, int 
         eq_total[j] = bcast[j * 4 + 2];
       }
     mask |= 0xFFu << shift;
+    if (early && pass < 3) {
+      // (the same values in every thread: they come from the broadcast words)
+      bool whole = true;
+#pragma unroll
+      for (int j = 0; j < 3; ++j)
+        if (q.k[j] > 0 && remaining[j] != eq_total[j]) whole = false;
+      if (whole) break;
+    }
     if (single) {
 #pragma unroll
       for (int e = 0; e < PER; ++e) {
@@ -394,7 +406,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
       }
     if (hi_all > lo_all) {
       Kth found[3];
-      radix_select3<PER>(s, qw, lo_all, hi_all, found, key, hist, bcast);
+      radix_select3<PER>(s, qw, lo_all, hi_all, found, key, hist, bcast, true);
 #pragma unroll
       for (int j = 0; j < 3; ++j)
         if (qw.k[j] > 0) kth[j] = found[j];
@@ -539,7 +551,7 @@ __global__ __launch_bounds__(kSelThreads) void mass_diag_kernel(
     q.lo[2] = q.hi[2] = q.k[2] = 0;
     Kth kth[3];
     uint32_t key[kSelPerDefault];
-    radix_select3<kSelPerDefault>(s, q, 0, N, kth, key, hist, bcast);
+    radix_select3<kSelPerDefault>(s, q, 0, N, kth, key, hist, bcast, false);  // (the key itself is used below)
     kt = kth[0];
   }
   for (int i = tid; i < N; i += kSelThreads) {
