@@ -33,13 +33,13 @@ PEAK_HBM_GBS = 8000.0
 # from the named summaries under profiles/, not measured by the run that prints them; a workload
 # without a summary, or a cut-down run (--layers / --seqs), reports null.
 PROFILED_TRAFFIC = {
-    "cfg2": {"bytes": (130988.3 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg2_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
-    "cfg3": {"bytes": (475885.2 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg3_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
-    "cfg4": {"bytes": (270758.9 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg4_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
-    "cfg4v": {"bytes": (959115.4 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg4v_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
+    "cfg2": {"bytes": (130983.6 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg2_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
+    "cfg3": {"bytes": (475940.1 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg3_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
+    "cfg4": {"bytes": (270769.8 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg4_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
+    "cfg4v": {"bytes": (959114.4 * 2.0 + 6272.0) * 1024, "source": "profiles/cfg4v_kernels_and_hbm_traffic.md (score_mfma_kernel<0, 4, false>)"},
     # (the slower of the two sweeps on this workload is the second one)
-    "cfg5": {"bytes": (42022591.9 * 2.0 + 1282986.0) * 1024, "source": "profiles/cfg5_kernels_and_hbm_traffic.md (score_mfma_kernel<1, 4, true>)"},
-    "cfg2ss": {"bytes": (22043.6 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg2ss_kernels_and_hbm_traffic.md (score_mfma_kernel<2, 2, false>)"},
+    "cfg5": {"bytes": (42022467.9 * 2.0 + 1282985.8) * 1024, "source": "profiles/cfg5_kernels_and_hbm_traffic.md (score_mfma_kernel<1, 4, true>)"},
+    "cfg2ss": {"bytes": (22075.3 * 2.0 + 3136.0) * 1024, "source": "profiles/cfg2ss_kernels_and_hbm_traffic.md (score_mfma_kernel<2, 2, false>)"},
 }
 
 
