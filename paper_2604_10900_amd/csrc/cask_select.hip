@@ -2,9 +2,11 @@
 // decode trace into protected core, representative seeds and donor scratch (Section 2.1).
 //
 // "Top k" is exact and order-defined: higher float score first, equal scores by ascending
-// cache index.  One workgroup per unit runs an LDS radix select (4 passes of 8 bits over an
-// order-preserving key image of the scores; the three ranks a unit needs -- prefix keep, core,
-// core + seeds -- are found in the same passes) to find the k-th keys, then marks the elements;
+// cache index.  One workgroup per unit runs an LDS radix select (up to 4 passes of 8 bits over
+// an order-preserving key image of the scores, ending early once every rank's boundary bucket
+// is taken whole; the three ranks a unit needs -- prefix keep, core, core + seeds -- are found
+// in the same passes, or the prefix rank in a walk of its own where that reads fewer keys) to
+// find the k-th keys, then marks the elements;
 // when the k-th value is shared by more elements than there are places left, an ordered block
 // scan hands the places to the lowest indices -- no atomics decide membership.
 //
