@@ -1008,6 +1008,37 @@ def test_group_sizes_around_the_single_wave_fold_limit(dtype):
     assert parity.check_values(p, got, want, Kb.reshape(2 * N, d), Vb.reshape(2 * N, d), row_off) == 7
 
 
+@pytest.mark.parametrize("step", [1, 3, 256, 32768])
+def test_selection_with_scores_a_few_ulps_apart(step):
+    """All scores of a unit are `step` fp32 ulps apart (a shuffled arithmetic progression of bit
+    patterns), so every radix digit but the lowest ones is shared by long runs and the rank
+    boundaries fall in the middle of a bucket of the last pass, at its edge, or (large steps) are
+    decided passes earlier, where the select stops.  Roles against the oracle, three units."""
+    rng = np.random.default_rng(step)
+    lens = [3000, 9000, 20000]
+    pref = [500, 2000, 300]
+    row_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    parts = []
+    for n in lens:
+        bits = (np.uint32(0x30000000) + np.uint32(step) * rng.permutation(n).astype(np.uint32)).astype(np.uint32)
+        parts.append(bits.view(np.float32))
+        assert np.isfinite(parts[-1]).all() and len(np.unique(parts[-1])) == n
+    s = np.concatenate(parts)
+    p = cask.Params(dtype=cask.BF16, head_dim=128, q_per_kv=1, window=64, budget=400)
+    rp = parity.ref_params(p)
+    role_w, _ = ref.prefix_evict(rp, row_off, np.array(pref), s)
+    role_w, st_w = ref.partition(rp, row_off, np.array(pref), s, role_w)
+    dev = torch.device("cuda:0")
+    K = torch.zeros(int(row_off[-1]), 128, dtype=torch.bfloat16, device=dev)
+    b = cask.Batch(p, torch.from_numpy(row_off), torch.tensor(pref, dtype=torch.int32), K, K, None)
+    sd = torch.from_numpy(s).to(dev)
+    role, st = cask.prefix_evict(b, sd)
+    role, st = cask.partition(b, sd, role)
+    torch.cuda.synchronize()
+    assert np.array_equal(role.cpu().numpy(), role_w)
+    assert np.array_equal(st.cpu().numpy(), st_w)
+
+
 @pytest.mark.parametrize("quant", [0, 40, None])
 @pytest.mark.parametrize("N,P", [(18432, 16384), (33024, 256), (34000, 17000), (20000, 3000), (17000, 600)])
 def test_event_selection_on_units_beyond_one_chunk_of_keys(N, P, quant):
